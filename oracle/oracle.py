@@ -1,0 +1,593 @@
+"""CPU oracle for one worker's synchronous-SGD iteration of an elastic job.
+
+TEST INFRASTRUCTURE ONLY: tests, the smoke check and the bench's cpu_baseline
+leg may import this; the product path never does.  It shares no code with the
+HIP path.  Everything is float64 unless a function says otherwise.
+
+What it computes, in the paper's terms:
+
+* section 2.1, the mini-batch SGD equation: the model moves by minus the
+  learning rate times the mean of the per-sample gradients of the mini-batch;
+* section 2.1, synchronous data parallelism: each of the p workers computes
+  the gradient of its own samples, the local gradients are aggregated, and
+  the aggregate is applied before the next mini-batch;
+* section 3.1: the aggregate batch size B is constant, a worker's batch is
+  B/p, and an epoch visits every sample exactly once whatever p does;
+* section 4.3: the leader holds a random permutation and hands out the next
+  unassigned piece on request (here: one-sample pieces, requests served in
+  worker-rank order);
+* section 4.2: a joining worker receives the model of ONE existing worker
+  (here: parameters, momentum, running statistics of worker 0, progress).
+
+Readings the paper leaves open (optimizer = momentum SGD with weight decay,
+mean aggregation, per-worker batch-norm statistics, generator constants) are
+listed in the design notes of this repository.
+
+Parity pins: tests/test_oracle_*.py (finite differences, library routines on
+special cases, closed forms of the update, brute-force shard invariants).
+Unpinned: the specific permutation constants (any permutation satisfies the
+paper) and the bf16 rounding points of emulate_bf16 mode.
+"""
+import ctypes
+import math
+import struct
+
+import numpy as np
+
+from . import build as _build
+
+_lib = ctypes.CDLL(_build.build())
+_dp = ctypes.POINTER(ctypes.c_double)
+_ip = ctypes.POINTER(ctypes.c_int32)
+
+
+def _d(a):
+    return None if a is None else a.ctypes.data_as(_dp)
+
+
+MASK64 = (1 << 64) - 1
+GOLDEN = 0x9E3779B97F4A7C15
+INIT_KEY = 0xD1B54A32D192ED03
+
+
+# ----------------------------------------------------------------------------
+# counter-based generator (SplitMix64 finaliser applied to key + (j+1)*GOLDEN)
+# ----------------------------------------------------------------------------
+def splitmix64_at(key: int, j: int) -> int:
+    z = (key + (j + 1) * GOLDEN) & MASK64
+    z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & MASK64
+    z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & MASK64
+    return z ^ (z >> 31)
+
+
+def _splitmix64_vec(key: int, j: np.ndarray) -> np.ndarray:
+    with np.errstate(over="ignore"):
+        z = np.uint64(key) + (j.astype(np.uint64) + np.uint64(1)) * np.uint64(GOLDEN)
+        z = (z ^ (z >> np.uint64(30))) * np.uint64(0xBF58476D1CE4E5B9)
+        z = (z ^ (z >> np.uint64(27))) * np.uint64(0x94D049BB133111EB)
+        return z ^ (z >> np.uint64(31))
+
+
+# ----------------------------------------------------------------------------
+# shard assignment (sections 3.1 and 4.3)
+# ----------------------------------------------------------------------------
+def epoch_permutation(seed: int, epoch: int, N: int) -> list:
+    """Leader's random permutation for one epoch: Fisher-Yates from the top
+    with j = floor(r * (i+1) / 2^64), r the next 64-bit draw."""
+    key = (seed ^ ((GOLDEN * (epoch + 1)) & MASK64)) & MASK64
+    perm = list(range(N))
+    draw = 0
+    for i in range(N - 1, 0, -1):
+        r = splitmix64_at(key, draw)
+        draw += 1
+        j = (r * (i + 1)) >> 64
+        perm[i], perm[j] = perm[j], perm[i]
+    return perm
+
+
+def shard(seed: int, N: int, B: int, p: int, epoch: int, step_in_epoch: int):
+    """Global batch `step_in_epoch` of `epoch`, cut into p consecutive pieces
+    of B/p samples (worker k gets piece k).  Returns (idx[B], off[p+1])."""
+    if p <= 0 or B <= 0 or B % p or N % B or not 0 <= step_in_epoch < N // B:
+        raise ValueError("bad shard request")
+    perm = epoch_permutation(seed, epoch, N)
+    idx = perm[step_in_epoch * B:(step_in_epoch + 1) * B]
+    n = B // p
+    return np.array(idx, dtype=np.int64), np.arange(p + 1, dtype=np.int64) * n
+
+
+# ----------------------------------------------------------------------------
+# bf16 rounding used by emulate_bf16 mode only (round to nearest even)
+# ----------------------------------------------------------------------------
+def round_bf16(a: np.ndarray) -> np.ndarray:
+    f = np.ascontiguousarray(a, dtype=np.float32)
+    u = f.view(np.uint32).astype(np.uint64)
+    r = ((u + np.uint64(0x7FFF) + ((u >> np.uint64(16)) & np.uint64(1))) >> np.uint64(16)) << np.uint64(16)
+    out = r.astype(np.uint32).view(np.float32).astype(np.float64)
+    nan = np.isnan(f)
+    if nan.any():
+        out[nan] = np.nan
+    return out.reshape(a.shape)
+
+
+# ----------------------------------------------------------------------------
+# layer primitives
+# ----------------------------------------------------------------------------
+def conv_out(n, k, stride, pad):
+    return (n + 2 * pad - k) // stride + 1
+
+
+def conv2d_forward(x, w, b, stride, pad):
+    N, H, W, C = x.shape
+    K, R, S, C2 = w.shape
+    assert C == C2
+    y = np.empty((N, conv_out(H, R, stride, pad), conv_out(W, S, stride, pad), K))
+    _lib.oracle_conv2d_forward(_d(x), _d(w), _d(b), _d(y), N, H, W, C, K, R, S, stride, pad)
+    return y
+
+
+def conv2d_backward_input(dy, w, xshape, stride, pad):
+    N, H, W, C = xshape
+    K, R, S, _ = w.shape
+    dx = np.empty(xshape)
+    _lib.oracle_conv2d_backward_input(_d(dy), _d(w), _d(dx), N, H, W, C, K, R, S, stride, pad)
+    return dx
+
+
+def conv2d_backward_weight(x, dy, wshape, stride, pad, want_bias):
+    N, H, W, C = x.shape
+    K, R, S, _ = wshape
+    dw = np.empty(wshape)
+    db = np.empty(K) if want_bias else None
+    _lib.oracle_conv2d_backward_weight(_d(x), _d(dy), _d(dw), _d(db), N, H, W, C, K, R, S, stride, pad)
+    return dw, db
+
+
+def maxpool_forward(x, k, stride, pad):
+    N, H, W, C = x.shape
+    Ho, Wo = conv_out(H, k, stride, pad), conv_out(W, k, stride, pad)
+    y = np.empty((N, Ho, Wo, C))
+    arg = np.empty((N, Ho, Wo, C), dtype=np.int32)
+    _lib.oracle_maxpool_forward(_d(x), _d(y), arg.ctypes.data_as(_ip), N, H, W, C, k, stride, pad)
+    return y, arg
+
+
+def maxpool_backward(dy, arg, xshape):
+    N, H, W, C = xshape
+    dx = np.empty(xshape)
+    _lib.oracle_maxpool_backward(_d(dy), arg.ctypes.data_as(_ip), _d(dx), N, H, W, C,
+                                 dy.shape[1], dy.shape[2])
+    return dx
+
+
+BN_EPS = 1e-5
+BN_RUNNING_MOMENTUM = 0.1
+
+
+def batchnorm_forward(x, gamma, beta):
+    """Training-mode batch norm over all rows of x[..., C]; returns
+    (y, xhat, mean, biased variance)."""
+    x2 = x.reshape(-1, x.shape[-1])
+    mean = x2.mean(axis=0)
+    var = ((x2 - mean) ** 2).mean(axis=0)
+    xhat = (x - mean) / np.sqrt(var + BN_EPS)
+    return gamma * xhat + beta, xhat, mean, var
+
+
+def batchnorm_backward(dy, xhat, gamma, var):
+    M = dy.size // dy.shape[-1]
+    dy2 = dy.reshape(M, -1)
+    xh2 = xhat.reshape(M, -1)
+    dbeta = dy2.sum(axis=0)
+    dgamma = (dy2 * xh2).sum(axis=0)
+    dx = (gamma / np.sqrt(var + BN_EPS)) * (dy - dbeta / M - xhat * (dgamma / M))
+    return dx, dgamma, dbeta
+
+
+def softmax_ce_forward(z, labels):
+    """Mean over rows of -log softmax(z)[label], with max subtraction."""
+    zs = z - z.max(axis=1, keepdims=True)
+    e = np.exp(zs)
+    prob = e / e.sum(axis=1, keepdims=True)
+    n = z.shape[0]
+    loss = -np.log(prob[np.arange(n), labels]).mean()
+    return loss, prob
+
+
+def softmax_ce_backward(prob, labels):
+    n = prob.shape[0]
+    dz = prob.copy()
+    dz[np.arange(n), labels] -= 1.0
+    return dz / n
+
+
+def sgd_momentum_update(w, v, grads, lr, momentum, wd):
+    """Aggregate the p local gradients by their mean (in rank order), then
+    g = mean + wd*w ; v = momentum*v + g ; w = w - lr*v.  With momentum = wd = 0
+    this is the paper's SGD equation for equal shards."""
+    acc = np.zeros_like(w)
+    for g in grads:
+        acc = acc + g
+    gbar = acc / len(grads)
+    g = gbar + wd * w
+    v_new = momentum * v + g
+    w_new = w - lr * v_new
+    return w_new, v_new
+
+
+# ----------------------------------------------------------------------------
+# model tables.  An op list over named tensors; parameters live in one flat
+# vector in op order: conv -> weight[K,R,S,C] then bias[K] (if any);
+# bn -> gamma[C] then beta[C].  Running statistics: per bn op mean[C], var[C].
+# ----------------------------------------------------------------------------
+class Graph:
+    def __init__(self, H, W, C):
+        self.ops = []
+        self.shape = {"x": (H, W, C)}
+        self.P = 0
+        self.R = 0
+        self.tensors = []     # (name, offset, shape, fan_in or 0)
+        self._n = 0
+
+    def _name(self):
+        self._n += 1
+        return "t%d" % self._n
+
+    def conv(self, x, K, R, stride, pad, bias, relu, name):
+        H, W, C = self.shape[x]
+        y = self._name()
+        op = dict(kind="conv", x=x, y=y, K=K, R=R, S=R, stride=stride, pad=pad, relu=relu,
+                  w_off=self.P, b_off=None, name=name)
+        self.tensors.append((name + ".w", self.P, (K, R, R, C), C * R * R))
+        self.P += K * R * R * C
+        if bias:
+            op["b_off"] = self.P
+            self.tensors.append((name + ".b", self.P, (K,), 0))
+            self.P += K
+        self.shape[y] = (conv_out(H, R, stride, pad), conv_out(W, R, stride, pad), K)
+        self.ops.append(op)
+        return y
+
+    def bn(self, x, relu, res, name):
+        H, W, C = self.shape[x]
+        y = self._name()
+        op = dict(kind="bn", x=x, y=y, C=C, relu=relu, res=res, g_off=self.P, b_off=self.P + C,
+                  run_off=self.R, name=name)
+        self.tensors.append((name + ".g", self.P, (C,), 0))
+        self.tensors.append((name + ".b", self.P + C, (C,), 0))
+        self.P += 2 * C
+        self.R += 2 * C
+        self.shape[y] = (H, W, C)
+        self.ops.append(op)
+        return y
+
+    def maxpool(self, x, k, stride, pad):
+        H, W, C = self.shape[x]
+        y = self._name()
+        self.ops.append(dict(kind="maxpool", x=x, y=y, k=k, stride=stride, pad=pad))
+        self.shape[y] = (conv_out(H, k, stride, pad), conv_out(W, k, stride, pad), C)
+        return y
+
+    def gavgpool(self, x):
+        H, W, C = self.shape[x]
+        y = self._name()
+        self.ops.append(dict(kind="gavgpool", x=x, y=y))
+        self.shape[y] = (1, 1, C)
+        return y
+
+    def flatten(self, x):
+        H, W, C = self.shape[x]
+        y = self._name()
+        self.ops.append(dict(kind="flatten", x=x, y=y))
+        self.shape[y] = (1, 1, H * W * C)
+        return y
+
+    def loss(self, x):
+        self.ops.append(dict(kind="loss", x=x))
+        self.logits = x
+
+
+def build_mlp(H=1, W=1, C=784, hidden=(256, 256), classes=10):
+    g = Graph(H, W, C)
+    t = g.flatten("x")
+    for i, h in enumerate(hidden):
+        t = g.conv(t, h, 1, 1, 0, True, True, "fc%d" % (i + 1))
+    t = g.conv(t, classes, 1, 1, 0, True, False, "fc%d" % (len(hidden) + 1))
+    g.loss(t)
+    return g
+
+
+def build_resnet20(H=32, W=32, C=3, classes=10, widths=(16, 32, 64), blocks=3):
+    g = Graph(H, W, C)
+    t = g.conv("x", widths[0], 3, 1, 1, False, False, "stem.conv")
+    t = g.bn(t, True, None, "stem.bn")
+    cin = widths[0]
+    for si, wd in enumerate(widths):
+        for bi in range(blocks):
+            stride = 2 if (si > 0 and bi == 0) else 1
+            nm = "s%d.b%d" % (si + 1, bi + 1)
+            u = g.conv(t, wd, 3, stride, 1, False, False, nm + ".conv1")
+            u = g.bn(u, True, None, nm + ".bn1")
+            u = g.conv(u, wd, 3, 1, 1, False, False, nm + ".conv2")
+            sc = t
+            if stride != 1 or cin != wd:
+                sc = g.conv(t, wd, 1, stride, 0, False, False, nm + ".proj")
+                sc = g.bn(sc, False, None, nm + ".projbn")
+            t = g.bn(u, True, sc, nm + ".bn2")
+            cin = wd
+    t = g.gavgpool(t)
+    t = g.conv(t, classes, 1, 1, 0, True, False, "fc")
+    g.loss(t)
+    return g
+
+
+def build_resnet50(H=224, W=224, C=3, classes=1000, base=64, blocks=(3, 4, 6, 3)):
+    g = Graph(H, W, C)
+    t = g.conv("x", base, 7, 2, 3, False, False, "stem.conv")
+    t = g.bn(t, True, None, "stem.bn")
+    t = g.maxpool(t, 3, 2, 1)
+    cin = base
+    for si, nb in enumerate(blocks):
+        width = base * (2 ** si)
+        for bi in range(nb):
+            stride = 2 if (si > 0 and bi == 0) else 1
+            nm = "s%d.b%d" % (si + 1, bi + 1)
+            u = g.conv(t, width, 1, 1, 0, False, False, nm + ".conv1")
+            u = g.bn(u, True, None, nm + ".bn1")
+            u = g.conv(u, width, 3, stride, 1, False, False, nm + ".conv2")
+            u = g.bn(u, True, None, nm + ".bn2")
+            u = g.conv(u, 4 * width, 1, 1, 0, False, False, nm + ".conv3")
+            sc = t
+            if bi == 0:
+                sc = g.conv(t, 4 * width, 1, stride, 0, False, False, nm + ".proj")
+                sc = g.bn(sc, False, None, nm + ".projbn")
+            t = g.bn(u, True, sc, nm + ".bn3")
+            cin = 4 * width
+    t = g.gavgpool(t)
+    t = g.conv(t, classes, 1, 1, 0, True, False, "fc")
+    g.loss(t)
+    return g
+
+
+def build_vgg16(H=224, W=224, C=3, classes=1000, base=64, fc=4096):
+    g = Graph(H, W, C)
+    t = "x"
+    plan = [(base, 2), (2 * base, 2), (4 * base, 3), (8 * base, 3), (8 * base, 3)]
+    i = 0
+    for width, reps in plan:
+        for _ in range(reps):
+            i += 1
+            t = g.conv(t, width, 3, 1, 1, True, True, "conv%d" % i)
+        t = g.maxpool(t, 2, 2, 0)
+    t = g.flatten(t)
+    t = g.conv(t, fc, 1, 1, 0, True, True, "fc1")
+    t = g.conv(t, fc, 1, 1, 0, True, True, "fc2")
+    t = g.conv(t, classes, 1, 1, 0, True, False, "fc3")
+    g.loss(t)
+    return g
+
+
+MODEL_IDS = {"mlp": 0, "resnet20": 1, "resnet50": 2, "vgg16": 3}
+BUILDERS = {"mlp": build_mlp, "resnet20": build_resnet20, "resnet50": build_resnet50,
+            "vgg16": build_vgg16}
+
+
+# ----------------------------------------------------------------------------
+# He initialisation from the seed
+# ----------------------------------------------------------------------------
+def he_init(graph: Graph, seed: int) -> np.ndarray:
+    """Weights ~ N(0, 2/fan_in) by Box-Muller on counter-based draws, one
+    stream per parameter tensor; biases 0, gamma 1, beta 0.  Values are
+    rounded to float32 (the storage type of the master weights)."""
+    w = np.zeros(graph.P, dtype=np.float64)
+    for t, (name, off, shape, fan_in) in enumerate(graph.tensors):
+        n = int(np.prod(shape))
+        if name.endswith(".g"):
+            w[off:off + n] = 1.0
+        if fan_in == 0:
+            continue
+        key = (seed ^ ((INIT_KEY * (t + 1)) & MASK64)) & MASK64
+        npair = (n + 1) // 2
+        q = np.arange(npair, dtype=np.uint64)
+        r1 = _splitmix64_vec(key, q * np.uint64(2))
+        r2 = _splitmix64_vec(key, q * np.uint64(2) + np.uint64(1))
+        u1 = ((r1 >> np.uint64(11)).astype(np.float64) + 1.0) * 2.0 ** -53
+        u2 = (r2 >> np.uint64(11)).astype(np.float64) * 2.0 ** -53
+        rad = np.sqrt(-2.0 * np.log(u1))
+        ang = 2.0 * math.pi * u2
+        z = np.empty(2 * npair)
+        z[0::2] = rad * np.cos(ang)
+        z[1::2] = rad * np.sin(ang)
+        std = math.sqrt(2.0 / fan_in)
+        w[off:off + n] = (z[:n] * std).astype(np.float32).astype(np.float64)
+    return w
+
+
+# ----------------------------------------------------------------------------
+# the worker state and its iteration
+# ----------------------------------------------------------------------------
+SNAPSHOT_MAGIC = 0x314C4445      # "EDL1"
+SNAPSHOT_HEADER_BYTES = 256
+
+
+class Oracle:
+    def __init__(self, model: str, seed: int, N: int, B: int, lr=0.1, momentum=0.9, wd=5e-4,
+                 emulate_bf16=False, graph_kwargs=None, dtype_code=0):
+        self.model = model
+        self.graph = BUILDERS[model](**(graph_kwargs or {}))
+        self.seed, self.N, self.B = seed, N, B
+        self.lr, self.momentum, self.wd = lr, momentum, wd
+        self.emulate_bf16 = emulate_bf16
+        self.dtype_code = dtype_code
+        self.w = he_init(self.graph, seed)
+        self.v = np.zeros_like(self.w)
+        self.running = np.zeros(self.graph.R)
+        for op in self.graph.ops:
+            if op["kind"] == "bn":
+                C = op["C"]
+                self.running[op["run_off"] + C:op["run_off"] + 2 * C] = 1.0
+        self.step_count = 0
+        self.epoch = 0
+        self.step_in_epoch = 0
+        self.last_grads = None
+        self.last_losses = None
+
+    # -- helpers ---------------------------------------------------------
+    def _q(self, a):
+        return round_bf16(a) if self.emulate_bf16 else a
+
+    def _param(self, off, shape):
+        n = int(np.prod(shape))
+        return self.w[off:off + n].reshape(shape)
+
+    # -- forward + backward on one worker's samples ------------------------
+    def forward_backward(self, x, labels, update_running=False):
+        """x: [n,H,W,C] float64, labels: [n] ints.  Returns (mean loss over
+        the n samples, flat gradient of that mean loss w.r.t. all parameters)."""
+        g = self.graph
+        q = self._q
+        act = {"x": q(np.ascontiguousarray(x, dtype=np.float64))}
+        saved = {}
+        for i, op in enumerate(g.ops):
+            kind = op["kind"]
+            if kind == "conv":
+                xin = act[op["x"]]
+                C = xin.shape[-1]
+                w = q(self._param(op["w_off"], (op["K"], op["R"], op["S"], C)))
+                b = self._param(op["b_off"], (op["K"],)) if op["b_off"] is not None else None
+                y = conv2d_forward(xin, np.ascontiguousarray(w), b, op["stride"], op["pad"])
+                if op["relu"]:
+                    y = np.maximum(y, 0.0)
+                act[op["y"]] = q(y) if op["y"] != g.logits else y
+                saved[i] = w
+            elif kind == "bn":
+                xin = act[op["x"]]
+                C = op["C"]
+                gamma = self._param(op["g_off"], (C,))
+                beta = self._param(op["b_off"], (C,))
+                y, xhat, mean, var = batchnorm_forward(xin, gamma, beta)
+                if op["res"] is not None:
+                    y = y + act[op["res"]]
+                if op["relu"]:
+                    y = np.maximum(y, 0.0)
+                act[op["y"]] = q(y)
+                saved[i] = (xhat, var)
+                if update_running:
+                    M = xin.size // C
+                    ro = op["run_off"]
+                    m = BN_RUNNING_MOMENTUM
+                    self.running[ro:ro + C] = (1 - m) * self.running[ro:ro + C] + m * mean
+                    self.running[ro + C:ro + 2 * C] = ((1 - m) * self.running[ro + C:ro + 2 * C]
+                                                       + m * var * M / (M - 1))
+            elif kind == "maxpool":
+                y, arg = maxpool_forward(act[op["x"]], op["k"], op["stride"], op["pad"])
+                act[op["y"]] = y
+                saved[i] = arg
+            elif kind == "gavgpool":
+                act[op["y"]] = q(act[op["x"]].mean(axis=(1, 2), keepdims=True))
+            elif kind == "flatten":
+                a = act[op["x"]]
+                act[op["y"]] = a.reshape(a.shape[0], 1, 1, -1)
+            elif kind == "loss":
+                z = act[op["x"]].reshape(x.shape[0], -1)
+                loss, prob = softmax_ce_forward(z, labels)
+                saved[i] = prob
+        # backward
+        G = np.zeros(g.P)
+        grad = {}
+
+        def add(name, val):
+            if name == "x":
+                return
+            grad[name] = q(grad[name] + val) if name in grad else q(val)
+
+        for i in range(len(g.ops) - 1, -1, -1):
+            op = g.ops[i]
+            kind = op["kind"]
+            if kind == "loss":
+                dz = softmax_ce_backward(saved[i], labels)
+                grad[op["x"]] = q(dz.reshape(act[op["x"]].shape))
+            elif kind == "conv":
+                dy = grad.pop(op["y"])
+                if op["relu"]:
+                    dy = dy * (act[op["y"]] > 0)
+                xin = act[op["x"]]
+                w = saved[i]
+                dw, db = conv2d_backward_weight(xin, np.ascontiguousarray(dy), w.shape, op["stride"],
+                                                op["pad"], op["b_off"] is not None)
+                G[op["w_off"]:op["w_off"] + dw.size] = dw.ravel()
+                if db is not None:
+                    G[op["b_off"]:op["b_off"] + db.size] = db
+                if op["x"] != "x":
+                    add(op["x"], conv2d_backward_input(np.ascontiguousarray(dy), np.ascontiguousarray(w),
+                                                       xin.shape, op["stride"], op["pad"]))
+            elif kind == "bn":
+                dy = grad.pop(op["y"])
+                if op["relu"]:
+                    dy = dy * (act[op["y"]] > 0)
+                if op["res"] is not None:
+                    add(op["res"], dy)
+                xhat, var = saved[i]
+                C = op["C"]
+                gamma = self._param(op["g_off"], (C,))
+                dx, dgamma, dbeta = batchnorm_backward(dy, xhat, gamma, var)
+                G[op["g_off"]:op["g_off"] + C] = dgamma
+                G[op["b_off"]:op["b_off"] + C] = dbeta
+                add(op["x"], dx)
+            elif kind == "maxpool":
+                dy = grad.pop(op["y"])
+                add(op["x"], maxpool_backward(np.ascontiguousarray(dy), saved[i], act[op["x"]].shape))
+            elif kind == "gavgpool":
+                dy = grad.pop(op["y"])
+                a = act[op["x"]]
+                add(op["x"], np.broadcast_to(dy / (a.shape[1] * a.shape[2]), a.shape).copy())
+            elif kind == "flatten":
+                dy = grad.pop(op["y"])
+                add(op["x"], dy.reshape(act[op["x"]].shape))
+        return loss, G
+
+    # -- one synchronous iteration at parallelism p ----------------------
+    def step(self, p, data_x, data_y, idx=None, off=None):
+        """One mini-batch: every worker k computes the gradient on its shard,
+        the p gradients are averaged and applied.  Returns the mean of the
+        workers' losses.  Worker 0 (the one that would broadcast its model to
+        a joiner) is the one whose batch-norm running statistics are kept."""
+        if idx is None:
+            idx, off = shard(self.seed, self.N, self.B, p, self.epoch, self.step_in_epoch)
+        grads, losses = [], []
+        for k in range(p):
+            sel = idx[off[k]:off[k + 1]]
+            x = np.asarray(data_x[sel], dtype=np.float64)
+            loss, G = self.forward_backward(x, np.asarray(data_y[sel]), update_running=(k == 0))
+            grads.append(G)
+            losses.append(loss)
+        self.w, self.v = sgd_momentum_update(self.w, self.v, grads, self.lr, self.momentum, self.wd)
+        self.last_grads, self.last_losses = grads, losses
+        self.step_count += 1
+        self.step_in_epoch += 1
+        if self.step_in_epoch == self.N // self.B:
+            self.step_in_epoch = 0
+            self.epoch += 1
+        return float(np.mean(losses))
+
+    # -- what a joining worker receives ------------------------------------
+    def snapshot(self) -> bytes:
+        """Header (job meta-data and progress), then parameters, momentum and
+        running statistics as float32.  Little endian."""
+        hdr = struct.pack("<IIIIQqqqqqfffIqq", SNAPSHOT_MAGIC, 1, MODEL_IDS[self.model], self.dtype_code,
+                          self.seed, self.N, self.B, self.step_count, self.epoch, self.step_in_epoch,
+                          self.lr, self.momentum, self.wd, 0, self.graph.P, self.graph.R)
+        hdr = hdr + b"\0" * (SNAPSHOT_HEADER_BYTES - len(hdr))
+        return (hdr + self.w.astype(np.float32).tobytes() + self.v.astype(np.float32).tobytes()
+                + self.running.astype(np.float32).tobytes())
+
+    def restore(self, blob: bytes):
+        P, R = self.graph.P, self.graph.R
+        f = struct.unpack_from("<IIIIQqqqqqfffIqq", blob, 0)
+        assert f[0] == SNAPSHOT_MAGIC and f[14] == P and f[15] == R
+        self.seed, self.N, self.B = f[4], f[5], f[6]      # job meta-data travels with the model
+        self.step_count, self.epoch, self.step_in_epoch = f[7], f[8], f[9]
+        o = SNAPSHOT_HEADER_BYTES
+        self.w = np.frombuffer(blob, np.float32, P, o).astype(np.float64)
+        self.v = np.frombuffer(blob, np.float32, P, o + 4 * P).astype(np.float64)
+        self.running = np.frombuffer(blob, np.float32, R, o + 8 * P).astype(np.float64)
