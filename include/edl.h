@@ -1,0 +1,185 @@
+/*
+ * edl.h - C boundary of the data-parallel training step of an elastic
+ * deep-learning job, native on MI355X (gfx950).
+ *
+ * One handle is one job on one GPU.  The p workers of the job are simulated
+ * as p shards of the aggregate mini-batch, processed one after the other on
+ * the handle's stream.  What the calls mean, in the paper's terms:
+ *
+ *   edl_init      init() of the framework API (section 3.2, Table 1)
+ *   edl_shard     elastic_shard_generator().next() (sections 3.2, 4.3)
+ *   edl_step      one mini-batch: session.run(obj) + all_reduce() +
+ *                 notify_batch_end() (section 3.2); a p that differs from the
+ *                 previous call's is a scale_in / scale_out that takes effect
+ *                 at this mini-batch boundary (sections 3.1, 4.2)
+ *   edl_snapshot  the model a joining worker receives from one existing
+ *                 worker (section 4.2), with the job meta-data a new leader
+ *                 receives (section 4.2, scale in) and the data-loading
+ *                 progress kept in checkpoints (section 4.3)
+ *   edl_shutdown  shutdown() (section 3.2)
+ *
+ * Conventions
+ *   - every call returns 0 on success or a negative EDL_E* code;
+ *     edl_last_error() gives a thread-local message for the last failure.
+ *   - "dev" pointers are device memory owned by the caller; "host" pointers
+ *     are ordinary host memory owned by the caller.  The library owns only
+ *     the handle (freed by edl_shutdown) and allocates no device memory.
+ *   - all device work is queued on the hipStream_t given to edl_init (NULL =
+ *     the default stream).  Calls on one handle are not thread-safe.
+ *   - tensors are channels-last: images [N][H][W][C], convolution weights
+ *     [K][R][S][C]; parameters, momentum and gradients are float32 in one
+ *     flat vector whose order is the model's layer order (see
+ *     edl_tensor_info).
+ */
+#ifndef EDL_H
+#define EDL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { EDL_OK = 0, EDL_EINVAL = -1, EDL_EINDIVISIBLE = -2, EDL_ENOMEM = -3, EDL_ERANGE = -4, EDL_EHIP = -5 };
+
+enum { EDL_MODEL_MLP = 0, EDL_MODEL_RESNET20 = 1, EDL_MODEL_RESNET50 = 2, EDL_MODEL_VGG16 = 3 };
+
+/* arithmetic type of activations and of the weight copies the matrix cores
+ * read; master weights, momentum and gradients are float32 in both cases */
+enum { EDL_DTYPE_F32 = 0, EDL_DTYPE_BF16 = 1 };
+
+#define EDL_SNAPSHOT_MAGIC 0x314C4445u /* "EDL1" */
+#define EDL_SNAPSHOT_HEADER_BYTES 256
+
+typedef struct edl_handle edl_handle;
+
+typedef struct edl_config {
+    int32_t model;      /* EDL_MODEL_* */
+    int32_t dtype;      /* EDL_DTYPE_* */
+    int64_t N;          /* samples in the data set; a multiple of B */
+    int64_t B;          /* aggregate mini-batch size, constant under scaling (section 3.1) */
+    int32_t p_max;      /* largest parallelism the job will see (number of gradient buffers) */
+    int32_t max_shard;  /* largest per-worker batch, B / (smallest p) */
+    float lr, momentum, wd;
+    /* geometry; 0 selects the model's default.  H, W, C: input image; classes: labels.
+     * arch[] per model -
+     *   MLP      {hidden1, hidden2}                     default {256, 256}; input is H*W*C features
+     *   RESNET20 {width of stage 1, stages, blocks}     default {16, 3, 3}
+     *   RESNET50 {base width, blocks of stages 1..4}    default {64, 3, 4, 6, 3}; 0 blocks ends the net
+     *   VGG16    {base width, fc width}                 default {64, 4096} */
+    int32_t H, W, C, classes;
+    int32_t arch[6];
+} edl_config;
+
+/* byte sizes and offsets inside the caller's arena (all offsets 256-byte aligned) */
+typedef struct edl_sizes {
+    int64_t P;              /* parameters */
+    int64_t R;              /* running-statistics floats (per batch-norm layer: mean[C], var[C]) */
+    int64_t params_off;     /* float32 w[P] */
+    int64_t momentum_off;   /* float32 v[P] */
+    int64_t running_off;    /* float32 [R]   (params, momentum, running are contiguous) */
+    int64_t grads_off;      /* float32 G[p_max][P_padded] */
+    int64_t grad_stride;    /* floats between consecutive workers' gradient buffers */
+    int64_t arena_bytes;    /* total the caller must provide to edl_init */
+    int64_t snapshot_bytes; /* EDL_SNAPSHOT_HEADER_BYTES + 4*(2P + R) */
+    double flops_per_sample; /* multiply-add flops of forward + both backward contractions */
+} edl_sizes;
+
+/* progress of the job: what notify_batch_end() counts */
+typedef struct edl_progress {
+    int64_t step, epoch, step_in_epoch;
+} edl_progress;
+
+const char* edl_last_error(void);
+
+/* Sizes for a configuration.  Host only; no GPU needed. */
+int32_t edl_query(const edl_config* cfg, edl_sizes* out);
+
+/* Number of parameter tensors and their place in the flat vector.  Host only.
+ * name_buf receives a NUL-terminated name such as "s2.b1.conv2.w". */
+int32_t edl_tensor_count(const edl_config* cfg, int32_t* out_count);
+int32_t edl_tensor_info(const edl_config* cfg, int32_t i, char* name_buf, size_t name_cap,
+                        int64_t* out_offset, int64_t* out_size, int64_t* out_fan_in);
+
+/* He initialisation from the seed, as edl_init produces it.  Host only:
+ * out_params is host float32[P].  Weights ~ N(0, 2/fan_in), biases 0,
+ * batch-norm scale 1 and shift 0. */
+int32_t edl_init_params_host(const edl_config* cfg, uint64_t seed, float* out_params);
+
+/* Shard assignment (sections 3.1, 4.3).  Pure function of its arguments, host
+ * only.  The epoch's permutation of 0..N-1 depends on (seed, epoch) only;
+ * mini-batch `step_in_epoch` is its B consecutive entries from
+ * step_in_epoch*B; worker k gets out_idx[out_off[k] .. out_off[k+1]).
+ * out_idx: host int64[B]; out_off: host int64[p+1].
+ * EDL_EINDIVISIBLE if B % p or N % B; EDL_ERANGE if step_in_epoch >= N/B. */
+int32_t edl_shard_host(uint64_t seed, int64_t N, int64_t B, int32_t p, int64_t epoch,
+                       int64_t step_in_epoch, int64_t* out_idx, int64_t* out_off);
+
+/* Create a job.  dev_arena: device memory of at least edl_query().arena_bytes,
+ * 256-byte aligned, owned by the caller and alive until edl_shutdown.
+ * Initialises parameters from the seed (He), zeroes momentum, sets running
+ * statistics to mean 0 / variance 1, progress to 0. */
+int32_t edl_init(edl_handle** out, const edl_config* cfg, uint64_t seed, void* dev_arena,
+                 size_t arena_bytes, void* hip_stream);
+
+/* The data set the shards index into: dev_x float32 [N][H][W][C], dev_y int32 [N]
+ * (device memory, caller-owned, must stay alive). */
+int32_t edl_bind_dataset(edl_handle* h, const float* dev_x, const int32_t* dev_y, int64_t N);
+
+/* edl_shard_host with the job's seed and N. */
+int32_t edl_shard(const edl_handle* h, int64_t B, int32_t p, int64_t epoch, int64_t step_in_epoch,
+                  int64_t* out_idx, int64_t* out_off);
+
+/* One synchronous mini-batch at parallelism p (sections 2.1, 3.1): for each
+ * worker k, forward and backward on its shard into gradient buffer k; then the
+ * p buffers are averaged and the fused momentum-SGD update
+ *   g = mean_k G_k + wd*w ;  v = momentum*v + g ;  w = w - lr*v
+ * is applied.  idx/off (host, as produced by edl_shard) may be NULL: then the
+ * library takes the shards of its own progress cursor.  out_loss (host, may be
+ * NULL) receives the mean of the workers' mean losses; asking for it
+ * synchronises the stream, otherwise the call only queues work.
+ * EDL_EINVAL p<=0 or p>p_max; EDL_EINDIVISIBLE B%p; EDL_ENOMEM B/p>max_shard;
+ * EDL_ERANGE index outside [0,N) or offsets not those of equal shards. */
+int32_t edl_step(edl_handle* h, int32_t p, const int64_t* idx, const int64_t* off, float* out_loss);
+
+/* Only the first half of edl_step (gradients of the p shards, no update).  For
+ * parity tests and profiling. */
+int32_t edl_gradients(edl_handle* h, int32_t p, const int64_t* idx, const int64_t* off, float* out_loss);
+
+/* Only the second half: average the p gradient buffers and update. */
+int32_t edl_apply(edl_handle* h, int32_t p);
+
+/* State image for a joining worker: header, w[P], v[P], running[R] (float32,
+ * little endian), written to device memory dev_dst of capacity cap. */
+int32_t edl_snapshot(edl_handle* h, void* dev_dst, size_t cap, size_t* out_written);
+int32_t edl_restore(edl_handle* h, const void* dev_src, size_t len);
+
+int32_t edl_get_progress(const edl_handle* h, edl_progress* out);
+
+/* Test hooks: copy state to host float32 buffers (synchronise the stream). */
+int32_t edl_get_params(edl_handle* h, float* host_dst /* [P] */);
+int32_t edl_get_momentum(edl_handle* h, float* host_dst /* [P] */);
+int32_t edl_get_running(edl_handle* h, float* host_dst /* [R] */);
+int32_t edl_get_grad(edl_handle* h, int32_t k, float* host_dst /* [P] */);
+int32_t edl_get_losses(edl_handle* h, int32_t p, float* host_dst /* [p] */);
+int32_t edl_set_params(edl_handle* h, const float* host_src /* [P] */);
+
+int32_t edl_shutdown(edl_handle* h);
+
+/* Stand-alone aggregation + update on caller buffers (the aggregation step without a
+ * model): dev_grads is a HOST array of p device pointers to float32[P];
+ * dev_w, dev_v float32[P]; dev_w16 (may be NULL) receives the bf16 copy of the
+ * updated weights, rounded to nearest even.  P need not be a multiple of
+ * anything; pointers must be 16-byte aligned. */
+int32_t edl_average_update(int32_t p, const float* const* dev_grads, float* dev_w, float* dev_v,
+                           uint16_t* dev_w16, int64_t P, float lr, float momentum, float wd,
+                           void* hip_stream);
+
+/* Stand-alone vectorised device-to-device copy used by edl_snapshot. */
+int32_t edl_copy(void* dev_dst, const void* dev_src, size_t bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EDL_H */

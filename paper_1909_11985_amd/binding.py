@@ -1,0 +1,254 @@
+"""ctypes binding of libedl.so: argument marshalling only.
+
+Names follow include/edl.h.  The library is loaded from this directory and is
+never replaced by a fallback: if it is missing, build it with
+`python -m paper_1909_11985_amd.build` (needs hipcc); if that is impossible the
+import fails.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libedl.so")
+
+MODELS = {"mlp": 0, "resnet20": 1, "resnet50": 2, "vgg16": 3}
+DTYPES = {"f32": 0, "bf16": 1}
+
+
+class EdlError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("edl error %d: %s" % (code, msg))
+        self.code = code
+
+
+class Config(C.Structure):
+    _fields_ = [("model", C.c_int32), ("dtype", C.c_int32), ("N", C.c_int64), ("B", C.c_int64),
+                ("p_max", C.c_int32), ("max_shard", C.c_int32),
+                ("lr", C.c_float), ("momentum", C.c_float), ("wd", C.c_float),
+                ("H", C.c_int32), ("W", C.c_int32), ("C", C.c_int32), ("classes", C.c_int32),
+                ("arch", C.c_int32 * 6)]
+
+
+class Sizes(C.Structure):
+    _fields_ = [("P", C.c_int64), ("R", C.c_int64), ("params_off", C.c_int64), ("momentum_off", C.c_int64),
+                ("running_off", C.c_int64), ("grads_off", C.c_int64), ("grad_stride", C.c_int64),
+                ("arena_bytes", C.c_int64), ("snapshot_bytes", C.c_int64), ("flops_per_sample", C.c_double)]
+
+
+class Progress(C.Structure):
+    _fields_ = [("step", C.c_int64), ("epoch", C.c_int64), ("step_in_epoch", C.c_int64)]
+
+
+def _load():
+    if not os.path.exists(_LIB_PATH):
+        from . import build as _b
+        _b.build()
+    return C.CDLL(_LIB_PATH)
+
+
+lib = _load()
+lib.edl_last_error.restype = C.c_char_p
+_i64p = C.POINTER(C.c_int64)
+_f32p = C.POINTER(C.c_float)
+
+_SIGS = {
+    "edl_query": [C.POINTER(Config), C.POINTER(Sizes)],
+    "edl_tensor_count": [C.POINTER(Config), C.POINTER(C.c_int32)],
+    "edl_tensor_info": [C.POINTER(Config), C.c_int32, C.c_char_p, C.c_size_t, _i64p, _i64p, _i64p],
+    "edl_init_params_host": [C.POINTER(Config), C.c_uint64, _f32p],
+    "edl_shard_host": [C.c_uint64, C.c_int64, C.c_int64, C.c_int32, C.c_int64, C.c_int64, _i64p, _i64p],
+    "edl_init": [C.POINTER(C.c_void_p), C.POINTER(Config), C.c_uint64, C.c_void_p, C.c_size_t, C.c_void_p],
+    "edl_bind_dataset": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64],
+    "edl_shard": [C.c_void_p, C.c_int64, C.c_int32, C.c_int64, C.c_int64, _i64p, _i64p],
+    "edl_step": [C.c_void_p, C.c_int32, _i64p, _i64p, _f32p],
+    "edl_gradients": [C.c_void_p, C.c_int32, _i64p, _i64p, _f32p],
+    "edl_apply": [C.c_void_p, C.c_int32],
+    "edl_snapshot": [C.c_void_p, C.c_void_p, C.c_size_t, C.POINTER(C.c_size_t)],
+    "edl_restore": [C.c_void_p, C.c_void_p, C.c_size_t],
+    "edl_get_progress": [C.c_void_p, C.POINTER(Progress)],
+    "edl_get_params": [C.c_void_p, _f32p],
+    "edl_get_momentum": [C.c_void_p, _f32p],
+    "edl_get_running": [C.c_void_p, _f32p],
+    "edl_get_grad": [C.c_void_p, C.c_int32, _f32p],
+    "edl_get_losses": [C.c_void_p, C.c_int32, _f32p],
+    "edl_set_params": [C.c_void_p, _f32p],
+    "edl_shutdown": [C.c_void_p],
+    "edl_average_update": [C.c_int32, C.POINTER(C.c_void_p), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
+                           C.c_float, C.c_float, C.c_float, C.c_void_p],
+    "edl_copy": [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p],
+}
+for _name, _args in _SIGS.items():
+    _fn = getattr(lib, _name)
+    _fn.argtypes = _args
+    _fn.restype = C.c_int32
+EXPORTS = ["edl_last_error"] + list(_SIGS)
+
+
+def _check(rc):
+    if rc != 0:
+        raise EdlError(rc, lib.edl_last_error().decode())
+
+
+def make_config(model, dtype="f32", N=1024, B=64, p_max=8, max_shard=None, lr=0.1, momentum=0.9, wd=5e-4,
+                H=0, W=0, C_=0, classes=0, arch=()):
+    cfg = Config()
+    cfg.model = MODELS[model] if isinstance(model, str) else model
+    cfg.dtype = DTYPES[dtype] if isinstance(dtype, str) else dtype
+    cfg.N, cfg.B, cfg.p_max = N, B, p_max
+    cfg.max_shard = B if max_shard is None else max_shard
+    cfg.lr, cfg.momentum, cfg.wd = lr, momentum, wd
+    cfg.H, cfg.W, cfg.C, cfg.classes = H, W, C_, classes
+    for i, a in enumerate(arch):
+        cfg.arch[i] = a
+    return cfg
+
+
+def edl_query(cfg):
+    s = Sizes()
+    _check(lib.edl_query(C.byref(cfg), C.byref(s)))
+    return s
+
+
+def edl_tensor_table(cfg):
+    """[(name, offset, size, fan_in)] of the flat parameter vector."""
+    n = C.c_int32()
+    _check(lib.edl_tensor_count(C.byref(cfg), C.byref(n)))
+    out = []
+    buf = C.create_string_buffer(64)
+    off, size, fan = C.c_int64(), C.c_int64(), C.c_int64()
+    for i in range(n.value):
+        _check(lib.edl_tensor_info(C.byref(cfg), i, buf, 64, C.byref(off), C.byref(size), C.byref(fan)))
+        out.append((buf.value.decode(), off.value, size.value, fan.value))
+    return out
+
+
+def edl_init_params_host(cfg, seed):
+    P = edl_query(cfg).P
+    out = np.empty(P, dtype=np.float32)
+    _check(lib.edl_init_params_host(C.byref(cfg), seed, out.ctypes.data_as(_f32p)))
+    return out
+
+
+def edl_shard_host(seed, N, B, p, epoch, step_in_epoch):
+    idx = np.empty(max(B, 1), dtype=np.int64)
+    off = np.empty(max(p, 0) + 1, dtype=np.int64)
+    _check(lib.edl_shard_host(seed, N, B, p, epoch, step_in_epoch, idx.ctypes.data_as(_i64p), off.ctypes.data_as(_i64p)))
+    return idx, off
+
+
+def edl_average_update(grads, w, v, w16, lr, momentum, wd, stream=0):
+    """grads: list of float32 device tensors; w, v: float32 device tensors;
+    w16: bfloat16 device tensor or None."""
+    p = len(grads)
+    ptrs = (C.c_void_p * p)(*[g.data_ptr() for g in grads])
+    _check(lib.edl_average_update(p, ptrs, w.data_ptr(), v.data_ptr(), w16.data_ptr() if w16 is not None else None,
+                                  w.numel(), lr, momentum, wd, stream))
+
+
+def edl_copy(dst, src, nbytes, stream=0):
+    _check(lib.edl_copy(dst.data_ptr(), src.data_ptr(), nbytes, stream))
+
+
+class Job:
+    """One elastic job on one GPU.  Allocates the arena with torch and hands
+    raw pointers to the library."""
+
+    def __init__(self, cfg, seed, device="cuda:0", stream=None):
+        import torch
+        self.torch = torch
+        self.cfg = cfg
+        self.sizes = edl_query(cfg)
+        self.device = torch.device(device)
+        self.arena = torch.empty(self.sizes.arena_bytes, dtype=torch.uint8, device=self.device)
+        self.stream = stream
+        sp = stream.cuda_stream if stream is not None else 0
+        self._h = C.c_void_p()
+        _check(lib.edl_init(C.byref(self._h), C.byref(cfg), seed, self.arena.data_ptr(), self.arena.numel(), sp))
+        self.P, self.R = self.sizes.P, self.sizes.R
+        self._data = None
+
+    def bind_dataset(self, x, y):
+        """x: float32 [N,H,W,C] device tensor, y: int32 [N] device tensor."""
+        assert x.is_contiguous() and y.is_contiguous()
+        self._data = (x, y)
+        _check(lib.edl_bind_dataset(self._h, x.data_ptr(), y.data_ptr(), x.shape[0]))
+
+    def shard(self, B, p, epoch, step_in_epoch):
+        idx = np.empty(B, dtype=np.int64)
+        off = np.empty(p + 1, dtype=np.int64)
+        _check(lib.edl_shard(self._h, B, p, epoch, step_in_epoch, idx.ctypes.data_as(_i64p), off.ctypes.data_as(_i64p)))
+        return idx, off
+
+    def _call_step(self, fn, p, idx, off, want_loss):
+        loss = C.c_float()
+        ip = idx.ctypes.data_as(_i64p) if idx is not None else None
+        op = off.ctypes.data_as(_i64p) if off is not None else None
+        _check(fn(self._h, p, ip, op, C.byref(loss) if want_loss else None))
+        return loss.value if want_loss else None
+
+    def step(self, p, idx=None, off=None, want_loss=True):
+        return self._call_step(lib.edl_step, p, idx, off, want_loss)
+
+    def gradients(self, p, idx=None, off=None, want_loss=True):
+        return self._call_step(lib.edl_gradients, p, idx, off, want_loss)
+
+    def apply(self, p):
+        _check(lib.edl_apply(self._h, p))
+
+    def snapshot(self, dst=None):
+        if dst is None:
+            dst = self.torch.empty(self.sizes.snapshot_bytes, dtype=self.torch.uint8, device=self.device)
+        n = C.c_size_t()
+        _check(lib.edl_snapshot(self._h, dst.data_ptr(), dst.numel(), C.byref(n)))
+        return dst
+
+    def restore(self, src):
+        _check(lib.edl_restore(self._h, src.data_ptr(), src.numel()))
+
+    def progress(self):
+        pr = Progress()
+        _check(lib.edl_get_progress(self._h, C.byref(pr)))
+        return pr.step, pr.epoch, pr.step_in_epoch
+
+    def _get(self, fn, n, *pre):
+        out = np.empty(n, dtype=np.float32)
+        _check(fn(self._h, *pre, out.ctypes.data_as(_f32p)))
+        return out
+
+    def params(self):
+        return self._get(lib.edl_get_params, self.P)
+
+    def momentum(self):
+        return self._get(lib.edl_get_momentum, self.P)
+
+    def running(self):
+        return self._get(lib.edl_get_running, self.R)
+
+    def grad(self, k):
+        return self._get(lib.edl_get_grad, self.P, k)
+
+    def losses(self, p):
+        return self._get(lib.edl_get_losses, p, p)
+
+    def set_params(self, w):
+        w = np.ascontiguousarray(w, dtype=np.float32)
+        _check(lib.edl_set_params(self._h, w.ctypes.data_as(_f32p)))
+
+    def sync(self):
+        if self.stream is not None:
+            self.stream.synchronize()
+        else:
+            self.torch.cuda.synchronize(self.device)
+
+    def shutdown(self):
+        if self._h:
+            _check(lib.edl_shutdown(self._h))
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.shutdown()
+        except Exception:
+            pass

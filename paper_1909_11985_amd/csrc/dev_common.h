@@ -1,0 +1,47 @@
+// Device-side helpers shared by the HIP kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace edl {
+
+typedef uint16_t bf16_t;  // raw bfloat16 bits
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+
+// round to nearest even; NaN stays NaN
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    static constexpr int VEC = 4;  // elements per 16-byte vector
+    static __device__ __forceinline__ float to_f32(float v) { return v; }
+    static __device__ __forceinline__ float from_f32(float v) { return v; }
+};
+template <> struct Elem<bf16_t> {
+    static constexpr int VEC = 8;
+    static __device__ __forceinline__ float to_f32(bf16_t v) { return bf16_to_f32(v); }
+    static __device__ __forceinline__ bf16_t from_f32(float v) { return f32_to_bf16(v); }
+};
+
+// 16-byte vector of T with element access
+template <typename T> union Vec16 {
+    uint4 u;
+    T e[16 / sizeof(T)];
+};
+
+template <typename T> __device__ __forceinline__ Vec16<T> load_vec(const T* p) {
+    Vec16<T> v;
+    v.u = *reinterpret_cast<const uint4*>(p);
+    return v;
+}
+template <typename T> __device__ __forceinline__ void store_vec(T* p, const Vec16<T>& v) {
+    *reinterpret_cast<uint4*>(p) = v.u;
+}
+
+}  // namespace edl

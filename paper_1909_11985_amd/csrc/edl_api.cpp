@@ -1,0 +1,609 @@
+// C boundary and step executor: carves the caller's arena, runs the layer
+// list forward and backward for each worker's shard, then the fused
+// aggregation + update.  See include/edl.h for the contract of every call.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <vector>
+
+#include "graph.h"
+#include "kernels.h"
+
+using namespace edl;
+
+#define HIP_TRY(expr)                                                                      \
+    do {                                                                                   \
+        hipError_t e_ = (expr);                                                            \
+        if (e_ != hipSuccess) {                                                            \
+            set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+            return EDL_EHIP;                                                               \
+        }                                                                                  \
+    } while (0)
+
+namespace {
+
+constexpr int64_t kAlign = 256;
+constexpr int kIdxSlots = 4;
+
+int64_t align_up(int64_t v, int64_t a = kAlign) { return (v + a - 1) / a * a; }
+
+// header of the state image (little endian, packed by construction)
+struct SnapshotHeader {
+    uint32_t magic, version, model, dtype;
+    uint64_t seed;
+    int64_t N, B, step, epoch, step_in_epoch;
+    float lr, momentum, wd;
+    uint32_t pad0;
+    int64_t P, R;
+};
+static_assert(sizeof(SnapshotHeader) == 96, "snapshot header layout");
+
+struct Layout {
+    int64_t params = 0, momentum = 0, running = 0, shadow = 0, grads = 0, grad_stride = 0;
+    int64_t idx = 0, labels = 0, row_loss = 0, losses = 0, partial = 0, coef = 0, wgrad_scratch = 0;
+    int64_t wgrad_scratch_bytes = 0;
+    std::vector<int64_t> act, grad;      // per tensor (storage owners only; -1 otherwise)
+    std::vector<int64_t> wT;             // per op: transposed weight copy (-1 if not needed)
+    std::vector<int64_t> bn_save;        // per op
+    std::vector<int64_t> pool_arg;       // per op
+    int64_t total = 0;
+};
+
+int validate(const edl_config& c) {
+    if (c.dtype != EDL_DTYPE_F32 && c.dtype != EDL_DTYPE_BF16) { set_error("unknown dtype %d", c.dtype); return EDL_EINVAL; }
+    if (c.N <= 0 || c.B <= 0 || c.p_max <= 0 || c.max_shard <= 0) { set_error("N, B, p_max, max_shard must be positive"); return EDL_EINVAL; }
+    if (c.p_max > kMaxP) { set_error("p_max %d exceeds %d", c.p_max, kMaxP); return EDL_EINVAL; }
+    if (c.N % c.B) { set_error("N=%lld is not a multiple of B=%lld", (long long)c.N, (long long)c.B); return EDL_EINDIVISIBLE; }
+    if (c.max_shard > c.B) { set_error("max_shard exceeds B"); return EDL_EINVAL; }
+    return EDL_OK;
+}
+
+int storage_of(const Graph& g, int t) { return g.tensors[(size_t)t].alias_of >= 0 ? g.tensors[(size_t)t].alias_of : t; }
+
+ConvGeom geom_of(const Graph& g, const Op& op, int n) {
+    const Tensor& tx = g.tensors[(size_t)op.x];
+    const Tensor& ty = g.tensors[(size_t)op.y];
+    ConvGeom q;
+    q.N = n; q.H = tx.H; q.W = tx.W; q.C = tx.C;
+    q.K = op.K; q.R = op.R; q.S = op.S; q.stride = op.stride; q.pad = op.pad; q.Ho = ty.H; q.Wo = ty.W;
+    return q;
+}
+
+void plan_layout(const edl_config& c, const Graph& g, Layout& L) {
+    const int64_t esz = c.dtype == EDL_DTYPE_BF16 ? 2 : 4;
+    int64_t o = 0;
+    auto take = [&](int64_t bytes) { const int64_t at = o; o += align_up(bytes); return at; };
+    L.params = take(4 * g.P);
+    L.momentum = take(4 * g.P);
+    L.running = take(4 * std::max<int64_t>(g.R, 1));
+    L.shadow = c.dtype == EDL_DTYPE_BF16 ? take(2 * g.P) : -1;
+    L.grad_stride = align_up(4 * g.P) / 4;
+    L.grads = take(4 * L.grad_stride * c.p_max);
+    L.idx = take(8 * c.B);
+    L.labels = take(4 * (int64_t)c.max_shard);
+    L.row_loss = take(4 * (int64_t)c.max_shard);
+    L.losses = take(4 * kMaxP);
+    int cmax = 1;
+    for (const Op& op : g.ops)
+        if (op.kind == OP_CONV || op.kind == OP_BN) cmax = std::max(cmax, op.K);
+    L.partial = take(4 * 2 * (int64_t)kRedRowBlocks * cmax);
+    L.coef = take(4 * 2 * (int64_t)cmax);
+    const size_t nt = g.tensors.size();
+    L.act.assign(nt, -1);
+    L.grad.assign(nt, -1);
+    for (size_t t = 0; t < nt; ++t) {
+        if (g.tensors[t].alias_of >= 0) continue;
+        const int64_t elems = g.tensors[t].elems() * c.max_shard;
+        L.act[t] = take(elems * (g.tensors[t].fp32 ? 4 : esz));
+        if (t != 0) L.grad[t] = take(elems * esz);
+    }
+    const size_t no = g.ops.size();
+    L.wT.assign(no, -1);
+    L.bn_save.assign(no, -1);
+    L.pool_arg.assign(no, -1);
+    L.wgrad_scratch_bytes = 0;
+    for (size_t i = 0; i < no; ++i) {
+        const Op& op = g.ops[i];
+        if (op.kind == OP_CONV) {
+            const Tensor& tx = g.tensors[(size_t)op.x];
+            if (storage_of(g, op.x) != 0) L.wT[i] = take((int64_t)op.K * op.R * op.S * tx.C * esz);
+            L.wgrad_scratch_bytes = std::max<int64_t>(L.wgrad_scratch_bytes,
+                                                      (int64_t)conv_wgrad_scratch_bytes(geom_of(g, op, c.max_shard)));
+        } else if (op.kind == OP_BN) {
+            L.bn_save[i] = take(4 * 2 * (int64_t)op.K);
+        } else if (op.kind == OP_MAXPOOL) {
+            L.pool_arg[i] = take(g.tensors[(size_t)op.y].elems() * c.max_shard);
+        }
+    }
+    L.wgrad_scratch = take(std::max<int64_t>(L.wgrad_scratch_bytes, 16));
+    L.total = o;
+}
+
+}  // namespace
+
+struct edl_handle {
+    edl_config cfg;
+    uint64_t seed;
+    Graph g;
+    Layout L;
+    char* arena;
+    hipStream_t st;
+    const float* data_x = nullptr;
+    const int32_t* data_y = nullptr;
+    edl_progress prog = {0, 0, 0};
+    bool weights_dirty = true;
+    // cached permutation of the current epoch
+    int64_t perm_epoch = -1;
+    std::vector<int64_t> perm;
+    // pinned staging
+    int64_t* idx_host[kIdxSlots] = {nullptr, nullptr, nullptr, nullptr};
+    hipEvent_t idx_event[kIdxSlots];
+    int idx_slot = 0;
+    float* loss_host = nullptr;
+
+    template <typename T> T* at(int64_t off) const { return reinterpret_cast<T*>(arena + off); }
+    float* w() const { return at<float>(L.params); }
+    float* v() const { return at<float>(L.momentum); }
+    float* running() const { return at<float>(L.running); }
+    float* grad_buf(int k) const { return at<float>(L.grads) + (int64_t)k * L.grad_stride; }
+    void* act(int t) const { return arena + L.act[(size_t)storage_of(g, t)]; }
+    void* grad(int t) const { return arena + L.grad[(size_t)storage_of(g, t)]; }
+};
+
+extern "C" {
+
+const char* edl_last_error(void) { return get_error(); }
+
+int32_t edl_query(const edl_config* cfg, edl_sizes* out) {
+    if (!cfg || !out) { set_error("null argument"); return EDL_EINVAL; }
+    int rc = validate(*cfg);
+    if (rc) return rc;
+    Graph g;
+    rc = build_graph(*cfg, g);
+    if (rc) return rc;
+    Layout L;
+    plan_layout(*cfg, g, L);
+    out->P = g.P;
+    out->R = g.R;
+    out->params_off = L.params;
+    out->momentum_off = L.momentum;
+    out->running_off = L.running;
+    out->grads_off = L.grads;
+    out->grad_stride = L.grad_stride;
+    out->arena_bytes = L.total;
+    out->snapshot_bytes = EDL_SNAPSHOT_HEADER_BYTES + 4 * (2 * g.P + g.R);
+    out->flops_per_sample = g.flops_per_sample();
+    return EDL_OK;
+}
+
+int32_t edl_tensor_count(const edl_config* cfg, int32_t* out_count) {
+    if (!cfg || !out_count) { set_error("null argument"); return EDL_EINVAL; }
+    Graph g;
+    const int rc = build_graph(*cfg, g);
+    if (rc) return rc;
+    *out_count = (int32_t)g.params.size();
+    return EDL_OK;
+}
+
+int32_t edl_tensor_info(const edl_config* cfg, int32_t i, char* name_buf, size_t name_cap, int64_t* out_offset,
+                        int64_t* out_size, int64_t* out_fan_in) {
+    if (!cfg) { set_error("null argument"); return EDL_EINVAL; }
+    Graph g;
+    const int rc = build_graph(*cfg, g);
+    if (rc) return rc;
+    if (i < 0 || (size_t)i >= g.params.size()) { set_error("tensor index %d out of range", i); return EDL_ERANGE; }
+    const ParamTensor& pt = g.params[(size_t)i];
+    if (name_buf && name_cap) snprintf(name_buf, name_cap, "%s", pt.name.c_str());
+    if (out_offset) *out_offset = pt.off;
+    if (out_size) *out_size = pt.size;
+    if (out_fan_in) *out_fan_in = pt.fan_in;
+    return EDL_OK;
+}
+
+int32_t edl_init_params_host(const edl_config* cfg, uint64_t seed, float* out_params) {
+    if (!cfg || !out_params) { set_error("null argument"); return EDL_EINVAL; }
+    Graph g;
+    const int rc = build_graph(*cfg, g);
+    if (rc) return rc;
+    he_init(g, seed, out_params);
+    return EDL_OK;
+}
+
+int32_t edl_shard_host(uint64_t seed, int64_t N, int64_t B, int32_t p, int64_t epoch, int64_t step_in_epoch,
+                       int64_t* out_idx, int64_t* out_off) {
+    if (!out_idx || !out_off) { set_error("null argument"); return EDL_EINVAL; }
+    if (N <= 0 || B <= 0 || p <= 0 || epoch < 0) { set_error("N, B, p must be positive and epoch non-negative"); return EDL_EINVAL; }
+    if (B % p || N % B) { set_error("B=%lld must divide by p=%d and N=%lld by B", (long long)B, p, (long long)N); return EDL_EINDIVISIBLE; }
+    if (step_in_epoch < 0 || step_in_epoch >= N / B) { set_error("step_in_epoch %lld outside the epoch", (long long)step_in_epoch); return EDL_ERANGE; }
+    std::vector<int64_t> perm;
+    epoch_permutation(seed, epoch, N, perm);
+    memcpy(out_idx, perm.data() + step_in_epoch * B, sizeof(int64_t) * (size_t)B);
+    for (int k = 0; k <= p; ++k) out_off[k] = (int64_t)k * (B / p);
+    return EDL_OK;
+}
+
+static int refresh_weight_copies(edl_handle* h) {
+    // the bf16 copy is written by the update kernel; after init / restore /
+    // set_params it is made here.  The transposed copies always are.
+    const int dt = h->cfg.dtype;
+    if (dt == EDL_DTYPE_BF16) launch_cast_bf16(h->w(), h->at<uint16_t>(h->L.shadow), h->g.P, h->st);
+    return EDL_OK;
+}
+
+static void transpose_weights(edl_handle* h) {
+    for (size_t i = 0; i < h->g.ops.size(); ++i) {
+        const Op& op = h->g.ops[i];
+        if (op.kind != OP_CONV || h->L.wT[i] < 0) continue;
+        const Tensor& tx = h->g.tensors[(size_t)op.x];
+        launch_weight_transpose(h->cfg.dtype, h->w() + op.w_off, h->arena + h->L.wT[i], op.K, op.R * op.S, tx.C, h->st);
+    }
+}
+
+int32_t edl_init(edl_handle** out, const edl_config* cfg, uint64_t seed, void* dev_arena, size_t arena_bytes,
+                 void* hip_stream) {
+    if (!out || !cfg || !dev_arena) { set_error("null argument"); return EDL_EINVAL; }
+    int rc = validate(*cfg);
+    if (rc) return rc;
+    if (((uintptr_t)dev_arena) % kAlign) { set_error("arena must be 256-byte aligned"); return EDL_EINVAL; }
+    edl_handle* h = new edl_handle();
+    h->cfg = *cfg;
+    h->seed = seed;
+    rc = build_graph(*cfg, h->g);
+    if (rc) { delete h; return rc; }
+    plan_layout(*cfg, h->g, h->L);
+    if ((int64_t)arena_bytes < h->L.total) {
+        set_error("arena of %zu bytes is smaller than the %lld needed", arena_bytes, (long long)h->L.total);
+        delete h;
+        return EDL_ENOMEM;
+    }
+    // a conv output feeding a batch norm must have no other consumer (its gradient is written, not added)
+    h->arena = (char*)dev_arena;
+    h->st = (hipStream_t)hip_stream;
+    for (int s = 0; s < kIdxSlots; ++s) {
+        HIP_TRY(hipHostMalloc((void**)&h->idx_host[s], sizeof(int64_t) * (size_t)cfg->B, hipHostMallocDefault));
+        HIP_TRY(hipEventCreateWithFlags(&h->idx_event[s], hipEventDisableTiming));
+    }
+    HIP_TRY(hipHostMalloc((void**)&h->loss_host, sizeof(float) * kMaxP, hipHostMallocDefault));
+    std::vector<float> init((size_t)h->g.P);
+    he_init(h->g, seed, init.data());
+    HIP_TRY(hipMemcpyAsync(h->w(), init.data(), sizeof(float) * (size_t)h->g.P, hipMemcpyHostToDevice, h->st));
+    launch_fill_f32(h->v(), 0.f, h->g.P, h->st);
+    for (const Op& op : h->g.ops)
+        if (op.kind == OP_BN) {
+            launch_fill_f32(h->running() + op.run_off, 0.f, op.K, h->st);
+            launch_fill_f32(h->running() + op.run_off + op.K, 1.f, op.K, h->st);
+        }
+    HIP_TRY(hipStreamSynchronize(h->st));   // init[] leaves scope
+    h->weights_dirty = true;
+    HIP_TRY(hipGetLastError());
+    *out = h;
+    return EDL_OK;
+}
+
+int32_t edl_bind_dataset(edl_handle* h, const float* dev_x, const int32_t* dev_y, int64_t N) {
+    if (!h || !dev_x || !dev_y) { set_error("null argument"); return EDL_EINVAL; }
+    if (N != h->cfg.N) { set_error("data set has %lld samples, the job was created for %lld", (long long)N, (long long)h->cfg.N); return EDL_EINVAL; }
+    h->data_x = dev_x;
+    h->data_y = dev_y;
+    return EDL_OK;
+}
+
+int32_t edl_shard(const edl_handle* h, int64_t B, int32_t p, int64_t epoch, int64_t step_in_epoch, int64_t* out_idx,
+                  int64_t* out_off) {
+    if (!h) { set_error("null handle"); return EDL_EINVAL; }
+    return edl_shard_host(h->seed, h->cfg.N, B, p, epoch, step_in_epoch, out_idx, out_off);
+}
+
+// forward + backward of one worker's shard: n samples whose indices are at
+// dev_idx; gradient into G; mean loss into dev_loss[0]
+static int run_shard(edl_handle* h, const int64_t* dev_idx, int n, float* G, float* dev_loss, bool update_running) {
+    const Graph& g = h->g;
+    const int dt = h->cfg.dtype;
+    hipStream_t st = h->st;
+    const bool bf = dt == EDL_DTYPE_BF16;
+    float* partial = h->at<float>(h->L.partial);
+    float* coef = h->at<float>(h->L.coef);
+    const Tensor& tin = g.tensors[0];
+    launch_gather(dt, h->data_x, h->data_y, dev_idx, n, tin.elems(), h->act(0), h->at<int32_t>(h->L.labels), st);
+    // ---- forward ----
+    for (size_t i = 0; i < g.ops.size(); ++i) {
+        const Op& op = g.ops[i];
+        switch (op.kind) {
+            case OP_CONV: {
+                const void* wsrc = bf ? (const void*)(h->at<uint16_t>(h->L.shadow) + op.w_off) : (const void*)(h->w() + op.w_off);
+                launch_conv_fwd(dt, geom_of(g, op, n), h->act(op.x), wsrc, op.bias ? h->w() + op.b_off : nullptr, op.relu,
+                                g.tensors[(size_t)op.y].fp32, h->act(op.y), st);
+                break;
+            }
+            case OP_BN: {
+                const Tensor& t = g.tensors[(size_t)op.x];
+                launch_bn_forward(dt, h->act(op.x), op.res >= 0 ? h->act(op.res) : nullptr, h->act(op.y), h->w() + op.w_off,
+                                  h->w() + op.b_off, h->at<float>(h->L.bn_save[i]),
+                                  update_running ? h->running() + op.run_off : nullptr, (int64_t)n * t.H * t.W, t.C, op.relu,
+                                  partial, st);
+                break;
+            }
+            case OP_MAXPOOL: {
+                const Tensor& tx = g.tensors[(size_t)op.x];
+                const Tensor& ty = g.tensors[(size_t)op.y];
+                launch_maxpool_forward(dt, h->act(op.x), h->act(op.y), h->at<uint8_t>(h->L.pool_arg[i]), n, tx.H, tx.W, tx.C,
+                                       op.R, op.stride, op.pad, ty.H, ty.W, st);
+                break;
+            }
+            case OP_GAVGPOOL: {
+                const Tensor& tx = g.tensors[(size_t)op.x];
+                launch_gavgpool_forward(dt, h->act(op.x), h->act(op.y), n, tx.H * tx.W, tx.C, st);
+                break;
+            }
+            case OP_LOSS:
+                launch_softmax_ce(dt, (const float*)h->act(op.x), h->at<int32_t>(h->L.labels), h->grad(op.x),
+                                  h->at<float>(h->L.row_loss), dev_loss, n, g.classes, st);
+                break;
+        }
+    }
+    // ---- backward ----
+    std::vector<char> written(g.tensors.size(), 0);
+    for (size_t ii = g.ops.size(); ii-- > 0;) {
+        const Op& op = g.ops[ii];
+        switch (op.kind) {
+            case OP_LOSS:
+                written[(size_t)storage_of(g, op.x)] = 1;
+                break;
+            case OP_CONV: {
+                const ConvGeom q = geom_of(g, op, n);
+                const int64_t M = (int64_t)n * q.Ho * q.Wo;
+                launch_bias_relu_backward(dt, h->act(op.y), h->grad(op.y), op.bias ? G + op.b_off : nullptr, M, op.K,
+                                          op.relu, partial, st);
+                launch_conv_wgrad(dt, q, h->act(op.x), h->grad(op.y), G + op.w_off, h->at<float>(h->L.wgrad_scratch),
+                                  (size_t)h->L.wgrad_scratch_bytes, st);
+                const int sx = storage_of(g, op.x);
+                if (sx != 0) {
+                    launch_conv_dgrad(dt, q, h->grad(op.y), h->arena + h->L.wT[ii], written[(size_t)sx] != 0, h->grad(op.x), st);
+                    written[(size_t)sx] = 1;
+                }
+                break;
+            }
+            case OP_BN: {
+                const Tensor& t = g.tensors[(size_t)op.x];
+                const int sx = storage_of(g, op.x);
+                void* dres = nullptr;
+                bool dres_acc = false;
+                if (op.res >= 0 && storage_of(g, op.res) != 0) {
+                    const int sr = storage_of(g, op.res);
+                    dres = h->grad(op.res);
+                    dres_acc = written[(size_t)sr] != 0;
+                    written[(size_t)sr] = 1;
+                }
+                launch_bn_backward(dt, h->act(op.x), h->act(op.y), h->grad(op.y), h->grad(op.x), dres, dres_acc,
+                                   h->w() + op.w_off, h->at<float>(h->L.bn_save[ii]), G + op.w_off, G + op.b_off,
+                                   (int64_t)n * t.H * t.W, t.C, op.relu, partial, coef, st);
+                written[(size_t)sx] = 1;
+                break;
+            }
+            case OP_MAXPOOL: {
+                const Tensor& tx = g.tensors[(size_t)op.x];
+                const Tensor& ty = g.tensors[(size_t)op.y];
+                const int sx = storage_of(g, op.x);
+                if (sx != 0) {
+                    launch_maxpool_backward(dt, h->grad(op.y), h->at<uint8_t>(h->L.pool_arg[ii]), h->grad(op.x),
+                                            written[(size_t)sx] != 0, n, tx.H, tx.W, tx.C, op.R, op.stride, op.pad, ty.H,
+                                            ty.W, st);
+                    written[(size_t)sx] = 1;
+                }
+                break;
+            }
+            case OP_GAVGPOOL: {
+                const Tensor& tx = g.tensors[(size_t)op.x];
+                const int sx = storage_of(g, op.x);
+                if (sx != 0) {
+                    launch_gavgpool_backward(dt, h->grad(op.y), h->grad(op.x), written[(size_t)sx] != 0, n, tx.H * tx.W, tx.C, st);
+                    written[(size_t)sx] = 1;
+                }
+                break;
+            }
+        }
+    }
+    return EDL_OK;
+}
+
+static int check_p(const edl_handle* h, int32_t p) {
+    if (p <= 0 || p > h->cfg.p_max) { set_error("p=%d outside [1, p_max=%d]", p, h->cfg.p_max); return EDL_EINVAL; }
+    if (h->cfg.B % p) { set_error("B=%lld is not a multiple of p=%d", (long long)h->cfg.B, p); return EDL_EINDIVISIBLE; }
+    if (h->cfg.B / p > h->cfg.max_shard) { set_error("shard of %lld samples exceeds max_shard=%d", (long long)(h->cfg.B / p), h->cfg.max_shard); return EDL_ENOMEM; }
+    return EDL_OK;
+}
+
+int32_t edl_gradients(edl_handle* h, int32_t p, const int64_t* idx, const int64_t* off, float* out_loss) {
+    if (!h) { set_error("null handle"); return EDL_EINVAL; }
+    int rc = check_p(h, p);
+    if (rc) return rc;
+    if (!h->data_x) { set_error("no data set bound"); return EDL_EINVAL; }
+    if ((idx == nullptr) != (off == nullptr)) { set_error("idx and off must both be given or both be NULL"); return EDL_EINVAL; }
+    const int64_t B = h->cfg.B, n = B / p;
+    const int slot = h->idx_slot;
+    h->idx_slot = (slot + 1) % kIdxSlots;
+    HIP_TRY(hipEventSynchronize(h->idx_event[slot]));
+    int64_t* stage = h->idx_host[slot];
+    if (idx) {
+        for (int k = 0; k <= p; ++k)
+            if (off[k] != k * n) { set_error("off[%d]=%lld: shards must be B/p=%lld samples each", k, (long long)off[k], (long long)n); return EDL_ERANGE; }
+        for (int64_t i = 0; i < B; ++i) {
+            if (idx[i] < 0 || idx[i] >= h->cfg.N) { set_error("idx[%lld]=%lld outside [0,N)", (long long)i, (long long)idx[i]); return EDL_ERANGE; }
+            stage[i] = idx[i];
+        }
+    } else {
+        if (h->perm_epoch != h->prog.epoch) {
+            epoch_permutation(h->seed, h->prog.epoch, h->cfg.N, h->perm);
+            h->perm_epoch = h->prog.epoch;
+        }
+        memcpy(stage, h->perm.data() + h->prog.step_in_epoch * B, sizeof(int64_t) * (size_t)B);
+    }
+    int64_t* dev_idx = h->at<int64_t>(h->L.idx);
+    HIP_TRY(hipMemcpyAsync(dev_idx, stage, sizeof(int64_t) * (size_t)B, hipMemcpyHostToDevice, h->st));
+    HIP_TRY(hipEventRecord(h->idx_event[slot], h->st));
+    if (h->weights_dirty) {
+        refresh_weight_copies(h);
+        h->weights_dirty = false;
+    }
+    transpose_weights(h);
+    float* dev_losses = h->at<float>(h->L.losses);
+    for (int k = 0; k < p; ++k) {
+        rc = run_shard(h, dev_idx + (int64_t)k * n, (int)n, h->grad_buf(k), dev_losses + k, k == 0);
+        if (rc) return rc;
+    }
+    HIP_TRY(hipGetLastError());
+    if (out_loss) {
+        HIP_TRY(hipMemcpyAsync(h->loss_host, dev_losses, sizeof(float) * (size_t)p, hipMemcpyDeviceToHost, h->st));
+        HIP_TRY(hipStreamSynchronize(h->st));
+        double s = 0;
+        for (int k = 0; k < p; ++k) s += h->loss_host[k];
+        *out_loss = (float)(s / p);
+    }
+    return EDL_OK;
+}
+
+int32_t edl_apply(edl_handle* h, int32_t p) {
+    if (!h) { set_error("null handle"); return EDL_EINVAL; }
+    const int rc = check_p(h, p);
+    if (rc) return rc;
+    GradPtrs gp = {};
+    for (int k = 0; k < p; ++k) gp.g[k] = h->grad_buf(k);
+    launch_average_update(p, gp, h->w(), h->v(), h->cfg.dtype == EDL_DTYPE_BF16 ? h->at<uint16_t>(h->L.shadow) : nullptr,
+                          h->g.P, h->cfg.lr, h->cfg.momentum, h->cfg.wd, h->st);
+    HIP_TRY(hipGetLastError());
+    h->prog.step += 1;
+    h->prog.step_in_epoch += 1;
+    if (h->prog.step_in_epoch == h->cfg.N / h->cfg.B) {
+        h->prog.step_in_epoch = 0;
+        h->prog.epoch += 1;
+    }
+    return EDL_OK;
+}
+
+int32_t edl_step(edl_handle* h, int32_t p, const int64_t* idx, const int64_t* off, float* out_loss) {
+    const int rc = edl_gradients(h, p, idx, off, out_loss);
+    if (rc) return rc;
+    return edl_apply(h, p);
+}
+
+int32_t edl_snapshot(edl_handle* h, void* dev_dst, size_t cap, size_t* out_written) {
+    if (!h || !dev_dst) { set_error("null argument"); return EDL_EINVAL; }
+    const int64_t P = h->g.P, R = h->g.R;
+    const size_t need = EDL_SNAPSHOT_HEADER_BYTES + 4 * (size_t)(2 * P + R);
+    if (cap < need) { set_error("snapshot needs %zu bytes, buffer has %zu", need, cap); return EDL_ENOMEM; }
+    alignas(8) char hdr[EDL_SNAPSHOT_HEADER_BYTES];
+    memset(hdr, 0, sizeof(hdr));
+    SnapshotHeader sh = {};
+    sh.magic = EDL_SNAPSHOT_MAGIC; sh.version = 1; sh.model = (uint32_t)h->cfg.model; sh.dtype = (uint32_t)h->cfg.dtype;
+    sh.seed = h->seed; sh.N = h->cfg.N; sh.B = h->cfg.B;
+    sh.step = h->prog.step; sh.epoch = h->prog.epoch; sh.step_in_epoch = h->prog.step_in_epoch;
+    sh.lr = h->cfg.lr; sh.momentum = h->cfg.momentum; sh.wd = h->cfg.wd; sh.P = P; sh.R = R;
+    memcpy(hdr, &sh, sizeof(sh));
+    char* dst = (char*)dev_dst;
+    HIP_TRY(hipMemcpyAsync(dst, hdr, sizeof(hdr), hipMemcpyHostToDevice, h->st));
+    HIP_TRY(hipStreamSynchronize(h->st));   // hdr is on this stack frame
+    launch_copy(dst + EDL_SNAPSHOT_HEADER_BYTES, h->w(), 4 * (size_t)P, h->st);
+    launch_copy(dst + EDL_SNAPSHOT_HEADER_BYTES + 4 * (size_t)P, h->v(), 4 * (size_t)P, h->st);
+    launch_copy(dst + EDL_SNAPSHOT_HEADER_BYTES + 8 * (size_t)P, h->running(), 4 * (size_t)R, h->st);
+    HIP_TRY(hipGetLastError());
+    if (out_written) *out_written = need;
+    return EDL_OK;
+}
+
+int32_t edl_restore(edl_handle* h, const void* dev_src, size_t len) {
+    if (!h || !dev_src) { set_error("null argument"); return EDL_EINVAL; }
+    const int64_t P = h->g.P, R = h->g.R;
+    const size_t need = EDL_SNAPSHOT_HEADER_BYTES + 4 * (size_t)(2 * P + R);
+    if (len < need) { set_error("snapshot image of %zu bytes is shorter than %zu", len, need); return EDL_ERANGE; }
+    SnapshotHeader sh;
+    HIP_TRY(hipMemcpyAsync(&sh, dev_src, sizeof(sh), hipMemcpyDeviceToHost, h->st));
+    HIP_TRY(hipStreamSynchronize(h->st));
+    if (sh.magic != EDL_SNAPSHOT_MAGIC || sh.version != 1) { set_error("not a snapshot image"); return EDL_EINVAL; }
+    if (sh.P != P || sh.R != R || (int32_t)sh.model != h->cfg.model) { set_error("snapshot is of another model (P=%lld, R=%lld)", (long long)sh.P, (long long)sh.R); return EDL_EINVAL; }
+    if (sh.N != h->cfg.N || sh.B != h->cfg.B) { set_error("snapshot is of a job with N=%lld B=%lld", (long long)sh.N, (long long)sh.B); return EDL_EINVAL; }
+    const char* src = (const char*)dev_src;
+    launch_copy(h->w(), src + EDL_SNAPSHOT_HEADER_BYTES, 4 * (size_t)P, h->st);
+    launch_copy(h->v(), src + EDL_SNAPSHOT_HEADER_BYTES + 4 * (size_t)P, 4 * (size_t)P, h->st);
+    launch_copy(h->running(), src + EDL_SNAPSHOT_HEADER_BYTES + 8 * (size_t)P, 4 * (size_t)R, h->st);
+    HIP_TRY(hipGetLastError());
+    h->seed = sh.seed;                      // job meta-data travels with the model
+    h->prog.step = sh.step; h->prog.epoch = sh.epoch; h->prog.step_in_epoch = sh.step_in_epoch;
+    h->perm_epoch = -1;
+    h->weights_dirty = true;
+    return EDL_OK;
+}
+
+int32_t edl_get_progress(const edl_handle* h, edl_progress* out) {
+    if (!h || !out) { set_error("null argument"); return EDL_EINVAL; }
+    *out = h->prog;
+    return EDL_OK;
+}
+
+static int d2h(edl_handle* h, float* dst, const float* src, int64_t n) {
+    if (!h || !dst) { set_error("null argument"); return EDL_EINVAL; }
+    HIP_TRY(hipMemcpyAsync(dst, src, sizeof(float) * (size_t)n, hipMemcpyDeviceToHost, h->st));
+    HIP_TRY(hipStreamSynchronize(h->st));
+    return EDL_OK;
+}
+
+int32_t edl_get_params(edl_handle* h, float* host_dst) { return h ? d2h(h, host_dst, h->w(), h->g.P) : EDL_EINVAL; }
+int32_t edl_get_momentum(edl_handle* h, float* host_dst) { return h ? d2h(h, host_dst, h->v(), h->g.P) : EDL_EINVAL; }
+int32_t edl_get_running(edl_handle* h, float* host_dst) { return h ? d2h(h, host_dst, h->running(), h->g.R) : EDL_EINVAL; }
+int32_t edl_get_grad(edl_handle* h, int32_t k, float* host_dst) {
+    if (!h || k < 0 || k >= h->cfg.p_max) { set_error("gradient buffer %d outside [0,p_max)", k); return EDL_EINVAL; }
+    return d2h(h, host_dst, h->grad_buf(k), h->g.P);
+}
+int32_t edl_get_losses(edl_handle* h, int32_t p, float* host_dst) {
+    if (!h || p <= 0 || p > kMaxP) { set_error("bad p"); return EDL_EINVAL; }
+    return d2h(h, host_dst, h->at<float>(h->L.losses), p);
+}
+
+int32_t edl_set_params(edl_handle* h, const float* host_src) {
+    if (!h || !host_src) { set_error("null argument"); return EDL_EINVAL; }
+    HIP_TRY(hipMemcpyAsync(h->w(), host_src, sizeof(float) * (size_t)h->g.P, hipMemcpyHostToDevice, h->st));
+    HIP_TRY(hipStreamSynchronize(h->st));
+    h->weights_dirty = true;
+    return EDL_OK;
+}
+
+int32_t edl_shutdown(edl_handle* h) {
+    if (!h) { set_error("null handle"); return EDL_EINVAL; }
+    (void)hipStreamSynchronize(h->st);
+    for (int s = 0; s < kIdxSlots; ++s) {
+        if (h->idx_host[s]) (void)hipHostFree(h->idx_host[s]);
+        (void)hipEventDestroy(h->idx_event[s]);
+    }
+    if (h->loss_host) (void)hipHostFree(h->loss_host);
+    delete h;
+    return EDL_OK;
+}
+
+int32_t edl_average_update(int32_t p, const float* const* dev_grads, float* dev_w, float* dev_v, uint16_t* dev_w16,
+                           int64_t P, float lr, float momentum, float wd, void* hip_stream) {
+    if (!dev_grads || !dev_w || !dev_v) { set_error("null argument"); return EDL_EINVAL; }
+    if (p <= 0 || p > kMaxP) { set_error("p=%d outside [1,%d]", p, kMaxP); return EDL_EINVAL; }
+    if (P < 0) { set_error("negative P"); return EDL_EINVAL; }
+    if (P == 0) return EDL_OK;
+    GradPtrs gp = {};
+    uintptr_t bits = (uintptr_t)dev_w | (uintptr_t)dev_v | (uintptr_t)dev_w16;
+    for (int k = 0; k < p; ++k) {
+        if (!dev_grads[k]) { set_error("gradient pointer %d is NULL", k); return EDL_EINVAL; }
+        gp.g[k] = dev_grads[k];
+        bits |= (uintptr_t)dev_grads[k];
+    }
+    if (bits & 15) { set_error("pointers must be 16-byte aligned"); return EDL_EINVAL; }
+    launch_average_update(p, gp, dev_w, dev_v, dev_w16, P, lr, momentum, wd, (hipStream_t)hip_stream);
+    HIP_TRY(hipGetLastError());
+    return EDL_OK;
+}
+
+int32_t edl_copy(void* dev_dst, const void* dev_src, size_t bytes, void* hip_stream) {
+    if (!dev_dst || !dev_src) { set_error("null argument"); return EDL_EINVAL; }
+    launch_copy(dev_dst, dev_src, bytes, (hipStream_t)hip_stream);
+    HIP_TRY(hipGetLastError());
+    return EDL_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,208 @@
+// Pooling and the softmax cross-entropy loss.  All HBM- or latency-bound.
+#include "dev_common.h"
+#include "kernels.h"
+
+namespace edl {
+
+static inline int ew_grid(int64_t total) {
+    int64_t b = (total + 255) / 256;
+    if (b > 256 * 32) b = 256 * 32;
+    if (b < 1) b = 1;
+    return (int)b;
+}
+
+// ---------------------------------------------------------------------------
+// max pool: one lane per output element (channel innermost, so neighbouring
+// lanes read neighbouring channels).  arg = r*k + s of the first maximum in
+// row-major window order (255 = no tap in range, which cannot happen for the
+// geometries used).
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void maxpool_fwd_kernel(const T* __restrict__ x, T* __restrict__ y,
+                                                          uint8_t* __restrict__ arg, int N, int H, int W, int C, int k,
+                                                          int stride, int pad, int Ho, int Wo) {
+    const int64_t total = (int64_t)N * Ho * Wo * C;
+    const int64_t step = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += step) {
+        const int c = (int)(i % C);
+        int64_t t = i / C;
+        const int wo = (int)(t % Wo); t /= Wo;
+        const int ho = (int)(t % Ho);
+        const int n = (int)(t / Ho);
+        float best = 0.f;
+        int where = 255;
+        for (int r = 0; r < k; ++r) {
+            const int h = ho * stride - pad + r;
+            if (h < 0 || h >= H) continue;
+            for (int s = 0; s < k; ++s) {
+                const int w = wo * stride - pad + s;
+                if (w < 0 || w >= W) continue;
+                const float v = Elem<T>::to_f32(x[(((int64_t)n * H + h) * W + w) * C + c]);
+                if (where == 255 || v > best) { best = v; where = r * k + s; }
+            }
+        }
+        y[i] = Elem<T>::from_f32(best);
+        arg[i] = (uint8_t)where;
+    }
+}
+
+// gather form of the backward: an input element collects dy from every window
+// that recorded it as its arg-max (no atomics, deterministic)
+template <typename T>
+__global__ __launch_bounds__(256) void maxpool_bwd_kernel(const T* __restrict__ dy, const uint8_t* __restrict__ arg,
+                                                          T* dx, int accumulate, int N, int H, int W, int C, int k,
+                                                          int stride, int pad, int Ho, int Wo) {
+    const int64_t total = (int64_t)N * H * W * C;
+    const int64_t step = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += step) {
+        const int c = (int)(i % C);
+        int64_t t = i / C;
+        const int w = (int)(t % W); t /= W;
+        const int h = (int)(t % H);
+        const int n = (int)(t / H);
+        float g = 0.f;
+        for (int r = 0; r < k; ++r) {
+            const int hn = h + pad - r;
+            if (hn < 0 || hn % stride) continue;
+            const int ho = hn / stride;
+            if (ho >= Ho) continue;
+            for (int s = 0; s < k; ++s) {
+                const int wn = w + pad - s;
+                if (wn < 0 || wn % stride) continue;
+                const int wo = wn / stride;
+                if (wo >= Wo) continue;
+                const int64_t o = (((int64_t)n * Ho + ho) * Wo + wo) * C + c;
+                if (arg[o] == r * k + s) g += Elem<T>::to_f32(dy[o]);
+            }
+        }
+        if (accumulate) g += Elem<T>::to_f32(dx[i]);
+        dx[i] = Elem<T>::from_f32(g);
+    }
+}
+
+void launch_maxpool_forward(int dtype, const void* x, void* y, uint8_t* arg, int N, int H, int W, int C, int k,
+                            int stride, int pad, int Ho, int Wo, hipStream_t st) {
+    const int grid = ew_grid((int64_t)N * Ho * Wo * C);
+    if (dtype == 1)
+        hipLaunchKernelGGL(maxpool_fwd_kernel<bf16_t>, dim3(grid), dim3(256), 0, st, (const bf16_t*)x, (bf16_t*)y, arg, N,
+                           H, W, C, k, stride, pad, Ho, Wo);
+    else
+        hipLaunchKernelGGL(maxpool_fwd_kernel<float>, dim3(grid), dim3(256), 0, st, (const float*)x, (float*)y, arg, N, H,
+                           W, C, k, stride, pad, Ho, Wo);
+}
+
+void launch_maxpool_backward(int dtype, const void* dy, const uint8_t* arg, void* dx, bool accumulate, int N, int H,
+                             int W, int C, int k, int stride, int pad, int Ho, int Wo, hipStream_t st) {
+    const int grid = ew_grid((int64_t)N * H * W * C);
+    if (dtype == 1)
+        hipLaunchKernelGGL(maxpool_bwd_kernel<bf16_t>, dim3(grid), dim3(256), 0, st, (const bf16_t*)dy, arg, (bf16_t*)dx,
+                           accumulate ? 1 : 0, N, H, W, C, k, stride, pad, Ho, Wo);
+    else
+        hipLaunchKernelGGL(maxpool_bwd_kernel<float>, dim3(grid), dim3(256), 0, st, (const float*)dy, arg, (float*)dx,
+                           accumulate ? 1 : 0, N, H, W, C, k, stride, pad, Ho, Wo);
+}
+
+// ---------------------------------------------------------------------------
+// global average pool: y[n][c] = mean over the HW pixels
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void gavgpool_fwd_kernel(const T* __restrict__ x, T* __restrict__ y, int N, int HW, int C) {
+    const int64_t total = (int64_t)N * C;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int c = (int)(i % C);
+        const int64_t n = i / C;
+        float s = 0.f;
+        for (int q = 0; q < HW; ++q) s += Elem<T>::to_f32(x[(n * HW + q) * C + c]);
+        y[i] = Elem<T>::from_f32(s / (float)HW);
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void gavgpool_bwd_kernel(const T* __restrict__ dy, T* dx, int accumulate, int N, int HW,
+                                                           int C) {
+    const int64_t total = (int64_t)N * HW * C;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int c = (int)(i % C);
+        const int64_t n = i / ((int64_t)HW * C);
+        float g = Elem<T>::to_f32(dy[n * C + c]) / (float)HW;
+        if (accumulate) g += Elem<T>::to_f32(dx[i]);
+        dx[i] = Elem<T>::from_f32(g);
+    }
+}
+
+void launch_gavgpool_forward(int dtype, const void* x, void* y, int N, int HW, int C, hipStream_t st) {
+    const int grid = ew_grid((int64_t)N * C);
+    if (dtype == 1)
+        hipLaunchKernelGGL(gavgpool_fwd_kernel<bf16_t>, dim3(grid), dim3(256), 0, st, (const bf16_t*)x, (bf16_t*)y, N, HW, C);
+    else
+        hipLaunchKernelGGL(gavgpool_fwd_kernel<float>, dim3(grid), dim3(256), 0, st, (const float*)x, (float*)y, N, HW, C);
+}
+
+void launch_gavgpool_backward(int dtype, const void* dy, void* dx, bool accumulate, int N, int HW, int C,
+                              hipStream_t st) {
+    const int grid = ew_grid((int64_t)N * HW * C);
+    if (dtype == 1)
+        hipLaunchKernelGGL(gavgpool_bwd_kernel<bf16_t>, dim3(grid), dim3(256), 0, st, (const bf16_t*)dy, (bf16_t*)dx,
+                           accumulate ? 1 : 0, N, HW, C);
+    else
+        hipLaunchKernelGGL(gavgpool_bwd_kernel<float>, dim3(grid), dim3(256), 0, st, (const float*)dy, (float*)dx,
+                           accumulate ? 1 : 0, N, HW, C);
+}
+
+// ---------------------------------------------------------------------------
+// softmax cross-entropy: one workgroup per sample.  loss_i = log(sum exp(z -
+// max)) - (z_label - max); dz = (softmax - onehot) / n.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ float block_reduce(float v, float* sm, bool is_max) {
+    for (int o = 32; o > 0; o >>= 1) {
+        const float other = __shfl_xor(v, o, 64);
+        v = is_max ? fmaxf(v, other) : v + other;
+    }
+    const int wave = threadIdx.x >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sm[wave] = v;
+    __syncthreads();
+    float r = sm[0];
+    for (int i = 1; i < (int)(blockDim.x >> 6); ++i) r = is_max ? fmaxf(r, sm[i]) : r + sm[i];
+    return r;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void softmax_ce_kernel(const float* __restrict__ logits, const int32_t* __restrict__ labels,
+                                                         T* __restrict__ dlogits, float* __restrict__ row_loss, int n, int C) {
+    __shared__ float sm[4];
+    const int i = blockIdx.x;
+    const float* z = logits + (int64_t)i * C;
+    float mx = -INFINITY;
+    for (int c = threadIdx.x; c < C; c += blockDim.x) mx = fmaxf(mx, z[c]);
+    mx = block_reduce(mx, sm, true);
+    float s = 0.f;
+    for (int c = threadIdx.x; c < C; c += blockDim.x) s += expf(z[c] - mx);
+    s = block_reduce(s, sm, false);
+    const int label = labels[i];
+    const float inv = 1.f / s, invn = 1.f / (float)n;
+    for (int c = threadIdx.x; c < C; c += blockDim.x) {
+        const float pr = expf(z[c] - mx) * inv;
+        dlogits[(int64_t)i * C + c] = Elem<T>::from_f32((pr - (c == label ? 1.f : 0.f)) * invn);
+    }
+    if (threadIdx.x == 0) row_loss[i] = logf(s) - (z[label] - mx);
+}
+
+// mean of the n per-sample losses, summed in sample order by one wave
+__global__ void loss_mean_kernel(const float* __restrict__ row_loss, int n, float* __restrict__ out) {
+    float s = 0.f;
+    for (int i = threadIdx.x; i < n; i += 64) s += row_loss[i];
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+    if (threadIdx.x == 0) out[0] = s / (float)n;
+}
+
+void launch_softmax_ce(int dtype, const float* logits, const int32_t* labels, void* dlogits, float* row_loss,
+                       float* loss_out, int n, int C, hipStream_t st) {
+    if (dtype == 1)
+        hipLaunchKernelGGL(softmax_ce_kernel<bf16_t>, dim3(n), dim3(256), 0, st, logits, labels, (bf16_t*)dlogits, row_loss, n, C);
+    else
+        hipLaunchKernelGGL(softmax_ce_kernel<float>, dim3(n), dim3(256), 0, st, logits, labels, (float*)dlogits, row_loss, n, C);
+    hipLaunchKernelGGL(loss_mean_kernel, dim3(1), dim3(64), 0, st, row_loss, n, loss_out);
+}
+
+}  // namespace edl

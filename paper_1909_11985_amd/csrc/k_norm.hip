@@ -1,0 +1,338 @@
+// Batch norm (training mode, statistics of the worker's own shard) and the
+// bias / ReLU backward, all as per-channel column reductions over a row-major
+// [M][C] activation matrix followed by an elementwise pass.  HBM-bound.
+//
+// Reduction scheme (deterministic, no atomics): the rows are cut into at most
+// kRedRowBlocks blocks; a workgroup of TX x TY lanes owns 32*VEC channels of
+// one row block, each lane accumulating one 16-byte channel vector over every
+// TY-th row in float32; lanes are combined through LDS; a second tiny kernel
+// adds the row blocks in float64.
+#include "dev_common.h"
+#include "kernels.h"
+
+namespace edl {
+
+constexpr float kBnEps = 1e-5f;
+constexpr float kBnRunningMomentum = 0.1f;
+
+struct RedShape {
+    int TX, TY, cvecs, row_blocks, rows_per_block;
+    dim3 grid, block;
+};
+
+static RedShape red_shape(int64_t M, int C, int VEC) {
+    RedShape s;
+    s.cvecs = (C + VEC - 1) / VEC;
+    int tx = 1;
+    while (tx < s.cvecs && tx < 32) tx <<= 1;
+    s.TX = tx;
+    s.TY = 256 / tx;
+    const int col_blocks = (s.cvecs + tx - 1) / tx;
+    // aim at ~2048 workgroups, at least TY*4 rows each
+    int64_t rb = 2048 / col_blocks;
+    const int64_t max_rb = (M + (int64_t)s.TY * 4 - 1) / ((int64_t)s.TY * 4);
+    if (rb > max_rb) rb = max_rb;
+    if (rb > kRedRowBlocks) rb = kRedRowBlocks;
+    if (rb < 1) rb = 1;
+    s.rows_per_block = (int)((M + rb - 1) / rb);
+    s.row_blocks = (int)((M + s.rows_per_block - 1) / s.rows_per_block);
+    s.grid = dim3(col_blocks, s.row_blocks);
+    s.block = dim3(s.TX, s.TY);
+    return s;
+}
+
+// Loads VEC channels of row r starting at channel c0 (zero beyond C).
+template <typename T, int VEC>
+__device__ __forceinline__ void load_row(const T* base, int64_t r, int C, int c0, float (&out)[VEC]) {
+    if (VEC > 1) {
+        const Vec16<T> v = load_vec(base + r * C + c0);
+        #pragma unroll
+        for (int e = 0; e < VEC; ++e) out[e] = Elem<T>::to_f32(v.e[e]);
+    } else {
+        out[0] = Elem<T>::to_f32(base[r * C + c0]);
+    }
+}
+
+template <typename T, int VEC>
+__device__ __forceinline__ void store_row(T* base, int64_t r, int C, int c0, const float (&in)[VEC]) {
+    if (VEC > 1) {
+        Vec16<T> v;
+        #pragma unroll
+        for (int e = 0; e < VEC; ++e) v.e[e] = Elem<T>::from_f32(in[e]);
+        store_vec(base + r * C + c0, v);
+    } else {
+        base[r * C + c0] = Elem<T>::from_f32(in[0]);
+    }
+}
+
+// KIND 0: a = x, b = x^2                       (batch-norm statistics)
+// KIND 1: a = dy', b = dy' * xhat              (batch-norm backward sums), dy' = dy * (y>0) if relu
+// KIND 2: a = dy' (written back in place), b=0 (bias gradient / ReLU mask)
+template <typename T, int VEC, int KIND>
+__global__ __launch_bounds__(256) void colreduce_kernel(const T* __restrict__ x, const T* __restrict__ y, T* dy,
+                                                        const float* __restrict__ mean_rstd, int64_t M, int C,
+                                                        int rows_per_block, int relu, float* __restrict__ partial) {
+    __shared__ float red[2][256 * VEC];
+    const int tx = threadIdx.x, ty = threadIdx.y, TX = blockDim.x, TY = blockDim.y;
+    const int c0 = (blockIdx.x * TX + tx) * VEC;
+    const bool active = c0 < C;
+    float a[VEC], b[VEC];
+    #pragma unroll
+    for (int e = 0; e < VEC; ++e) { a[e] = 0.f; b[e] = 0.f; }
+    float mu[VEC], rs[VEC];
+    if (KIND == 1 && active) {
+        #pragma unroll
+        for (int e = 0; e < VEC; ++e) { mu[e] = mean_rstd[c0 + e]; rs[e] = mean_rstd[C + c0 + e]; }
+    }
+    const int64_t r0 = (int64_t)blockIdx.y * rows_per_block;
+    int64_t r1 = r0 + rows_per_block;
+    if (r1 > M) r1 = M;
+    if (active) {
+        for (int64_t r = r0 + ty; r < r1; r += TY) {
+            if (KIND == 0) {
+                float xv[VEC];
+                load_row<T, VEC>(x, r, C, c0, xv);
+                #pragma unroll
+                for (int e = 0; e < VEC; ++e) { a[e] += xv[e]; b[e] += xv[e] * xv[e]; }
+            } else {
+                float g[VEC];
+                load_row<T, VEC>(dy, r, C, c0, g);
+                if (relu) {
+                    float yv[VEC];
+                    load_row<T, VEC>(y, r, C, c0, yv);
+                    #pragma unroll
+                    for (int e = 0; e < VEC; ++e) g[e] = yv[e] > 0.f ? g[e] : 0.f;
+                }
+                if (KIND == 1) {
+                    float xv[VEC];
+                    load_row<T, VEC>(x, r, C, c0, xv);
+                    #pragma unroll
+                    for (int e = 0; e < VEC; ++e) { a[e] += g[e]; b[e] += g[e] * ((xv[e] - mu[e]) * rs[e]); }
+                } else {
+                    if (relu) store_row<T, VEC>(dy, r, C, c0, g);
+                    #pragma unroll
+                    for (int e = 0; e < VEC; ++e) a[e] += g[e];
+                }
+            }
+        }
+    }
+    const int lane = ty * TX + tx;
+    #pragma unroll
+    for (int e = 0; e < VEC; ++e) { red[0][lane * VEC + e] = a[e]; red[1][lane * VEC + e] = b[e]; }
+    __syncthreads();
+    if (ty == 0 && active) {
+        for (int j = 1; j < TY; ++j) {
+            #pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                a[e] += red[0][(j * TX + tx) * VEC + e];
+                b[e] += red[1][(j * TX + tx) * VEC + e];
+            }
+        }
+        float* pa = partial + ((int64_t)blockIdx.y * 2 + 0) * C;
+        float* pb = partial + ((int64_t)blockIdx.y * 2 + 1) * C;
+        #pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            if (c0 + e < C) { pa[c0 + e] = a[e]; pb[c0 + e] = b[e]; }
+        }
+    }
+}
+
+// mean / rstd from the partial sums; running statistics of the worker whose
+// model a joiner would receive (unbiased variance, momentum 0.1)
+__global__ void bn_stats_finalize_kernel(const float* __restrict__ partial, int row_blocks, int64_t M, int C,
+                                         float* __restrict__ mean_rstd, float* running) {
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= C) return;
+    double s = 0, q = 0;
+    for (int j = 0; j < row_blocks; ++j) {
+        s += (double)partial[((int64_t)j * 2 + 0) * C + c];
+        q += (double)partial[((int64_t)j * 2 + 1) * C + c];
+    }
+    const double mean = s / (double)M;
+    double var = q / (double)M - mean * mean;
+    if (var < 0) var = 0;
+    mean_rstd[c] = (float)mean;
+    mean_rstd[C + c] = (float)(1.0 / sqrt(var + (double)kBnEps));
+    if (running) {
+        const double unbiased = M > 1 ? var * (double)M / (double)(M - 1) : var;
+        running[c] = (1.f - kBnRunningMomentum) * running[c] + kBnRunningMomentum * (float)mean;
+        running[C + c] = (1.f - kBnRunningMomentum) * running[C + c] + kBnRunningMomentum * (float)unbiased;
+    }
+}
+
+// dgamma = sum dy'*xhat, dbeta = sum dy'; coef = {dbeta/M, dgamma/M}
+__global__ void bn_bwd_finalize_kernel(const float* __restrict__ partial, int row_blocks, int64_t M, int C,
+                                       float* __restrict__ dgamma, float* __restrict__ dbeta, float* __restrict__ coef) {
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= C) return;
+    double s = 0, q = 0;
+    for (int j = 0; j < row_blocks; ++j) {
+        s += (double)partial[((int64_t)j * 2 + 0) * C + c];
+        q += (double)partial[((int64_t)j * 2 + 1) * C + c];
+    }
+    dbeta[c] = (float)s;
+    dgamma[c] = (float)q;
+    coef[c] = (float)(s / (double)M);
+    coef[C + c] = (float)(q / (double)M);
+}
+
+__global__ void bias_finalize_kernel(const float* __restrict__ partial, int row_blocks, int C, float* __restrict__ dbias) {
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= C) return;
+    double s = 0;
+    for (int j = 0; j < row_blocks; ++j) s += (double)partial[((int64_t)j * 2 + 0) * C + c];
+    dbias[c] = (float)s;
+}
+
+// y = relu(gamma * (x - mean) * rstd + beta + res)
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ x, const T* __restrict__ res, T* __restrict__ y,
+                                                       const float* __restrict__ gamma, const float* __restrict__ beta,
+                                                       const float* __restrict__ mean_rstd, int64_t M, int C, int cvecs,
+                                                       int relu) {
+    const int64_t total = M * cvecs;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+        const int64_t r = i / cvecs;
+        const int c0 = (int)(i - r * cvecs) * VEC;
+        float xv[VEC], out[VEC];
+        load_row<T, VEC>(x, r, C, c0, xv);
+        #pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            const float sc = gamma[c0 + e] * mean_rstd[C + c0 + e];
+            out[e] = (xv[e] - mean_rstd[c0 + e]) * sc + beta[c0 + e];
+        }
+        if (res) {
+            float rv[VEC];
+            load_row<T, VEC>(res, r, C, c0, rv);
+            #pragma unroll
+            for (int e = 0; e < VEC; ++e) out[e] += rv[e];
+        }
+        if (relu) {
+            #pragma unroll
+            for (int e = 0; e < VEC; ++e) out[e] = out[e] > 0.f ? out[e] : 0.f;
+        }
+        store_row<T, VEC>(y, r, C, c0, out);
+    }
+}
+
+// dx = gamma*rstd*(dy' - coef0 - xhat*coef1) ; dres (+)= dy'
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const T* __restrict__ x, const T* __restrict__ y,
+                                                           const T* __restrict__ dy, T* __restrict__ dx, T* dres,
+                                                           int dres_acc, const float* __restrict__ gamma,
+                                                           const float* __restrict__ mean_rstd,
+                                                           const float* __restrict__ coef, int64_t M, int C, int cvecs,
+                                                           int relu) {
+    const int64_t total = M * cvecs;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+        const int64_t r = i / cvecs;
+        const int c0 = (int)(i - r * cvecs) * VEC;
+        float xv[VEC], g[VEC], out[VEC];
+        load_row<T, VEC>(x, r, C, c0, xv);
+        load_row<T, VEC>(dy, r, C, c0, g);
+        if (relu) {
+            float yv[VEC];
+            load_row<T, VEC>(y, r, C, c0, yv);
+            #pragma unroll
+            for (int e = 0; e < VEC; ++e) g[e] = yv[e] > 0.f ? g[e] : 0.f;
+        }
+        #pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            const float rs = mean_rstd[C + c0 + e];
+            const float xh = (xv[e] - mean_rstd[c0 + e]) * rs;
+            out[e] = gamma[c0 + e] * rs * (g[e] - coef[c0 + e] - xh * coef[C + c0 + e]);
+        }
+        store_row<T, VEC>(dx, r, C, c0, out);
+        if (dres) {
+            if (dres_acc) {
+                float old[VEC];
+                load_row<T, VEC>(dres, r, C, c0, old);
+                #pragma unroll
+                for (int e = 0; e < VEC; ++e) g[e] += old[e];
+            }
+            store_row<T, VEC>(dres, r, C, c0, g);
+        }
+    }
+}
+
+static inline int ew_grid(int64_t total) {
+    int64_t b = (total + 255) / 256;
+    if (b > 256 * 32) b = 256 * 32;
+    if (b < 1) b = 1;
+    return (int)b;
+}
+
+template <typename T, int VEC>
+static void bn_forward_t(const void* x, const void* res, void* y, const float* gamma, const float* beta,
+                         float* save, float* running, int64_t M, int C, bool relu, float* partial, hipStream_t st) {
+    const RedShape s = red_shape(M, C, VEC);
+    hipLaunchKernelGGL((colreduce_kernel<T, VEC, 0>), s.grid, s.block, 0, st, (const T*)x, (const T*)nullptr, (T*)nullptr,
+                       (const float*)nullptr, M, C, s.rows_per_block, 0, partial);
+    hipLaunchKernelGGL(bn_stats_finalize_kernel, dim3((C + 127) / 128), dim3(128), 0, st, partial, s.row_blocks, M, C,
+                       save, running);
+    hipLaunchKernelGGL((bn_apply_kernel<T, VEC>), dim3(ew_grid(M * s.cvecs)), dim3(256), 0, st, (const T*)x,
+                       (const T*)res, (T*)y, gamma, beta, save, M, C, s.cvecs, relu ? 1 : 0);
+}
+
+void launch_bn_forward(int dtype, const void* x, const void* res, void* y, const float* gamma, const float* beta,
+                       float* save, float* running, int64_t M, int C, bool relu, float* partial, hipStream_t st) {
+    if (dtype == 1) {
+        if (C % 8 == 0) bn_forward_t<bf16_t, 8>(x, res, y, gamma, beta, save, running, M, C, relu, partial, st);
+        else bn_forward_t<bf16_t, 1>(x, res, y, gamma, beta, save, running, M, C, relu, partial, st);
+    } else {
+        if (C % 4 == 0) bn_forward_t<float, 4>(x, res, y, gamma, beta, save, running, M, C, relu, partial, st);
+        else bn_forward_t<float, 1>(x, res, y, gamma, beta, save, running, M, C, relu, partial, st);
+    }
+}
+
+template <typename T, int VEC>
+static void bn_backward_t(const void* x, const void* y, const void* dy, void* dx, void* dres, bool dres_acc,
+                          const float* gamma, const float* save, float* dgamma, float* dbeta, int64_t M, int C,
+                          bool relu, float* partial, float* coef, hipStream_t st) {
+    const RedShape s = red_shape(M, C, VEC);
+    hipLaunchKernelGGL((colreduce_kernel<T, VEC, 1>), s.grid, s.block, 0, st, (const T*)x, (const T*)y, (T*)dy, save, M, C,
+                       s.rows_per_block, relu ? 1 : 0, partial);
+    hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3((C + 127) / 128), dim3(128), 0, st, partial, s.row_blocks, M, C,
+                       dgamma, dbeta, coef);
+    hipLaunchKernelGGL((bn_bwd_apply_kernel<T, VEC>), dim3(ew_grid(M * s.cvecs)), dim3(256), 0, st, (const T*)x,
+                       (const T*)y, (const T*)dy, (T*)dx, (T*)dres, dres_acc ? 1 : 0, gamma, save, coef, M, C, s.cvecs,
+                       relu ? 1 : 0);
+}
+
+void launch_bn_backward(int dtype, const void* x, const void* y, const void* dy, void* dx, void* dres,
+                        bool dres_accumulate, const float* gamma, const float* save, float* dgamma, float* dbeta,
+                        int64_t M, int C, bool relu, float* partial, float* coef, hipStream_t st) {
+    if (dtype == 1) {
+        if (C % 8 == 0) bn_backward_t<bf16_t, 8>(x, y, dy, dx, dres, dres_accumulate, gamma, save, dgamma, dbeta, M, C, relu, partial, coef, st);
+        else bn_backward_t<bf16_t, 1>(x, y, dy, dx, dres, dres_accumulate, gamma, save, dgamma, dbeta, M, C, relu, partial, coef, st);
+    } else {
+        if (C % 4 == 0) bn_backward_t<float, 4>(x, y, dy, dx, dres, dres_accumulate, gamma, save, dgamma, dbeta, M, C, relu, partial, coef, st);
+        else bn_backward_t<float, 1>(x, y, dy, dx, dres, dres_accumulate, gamma, save, dgamma, dbeta, M, C, relu, partial, coef, st);
+    }
+}
+
+template <typename T, int VEC>
+static void bias_relu_backward_t(const void* y, void* dy, float* dbias, int64_t M, int C, bool relu, float* partial,
+                                 hipStream_t st) {
+    const RedShape s = red_shape(M, C, VEC);
+    hipLaunchKernelGGL((colreduce_kernel<T, VEC, 2>), s.grid, s.block, 0, st, (const T*)nullptr, (const T*)y, (T*)dy,
+                       (const float*)nullptr, M, C, s.rows_per_block, relu ? 1 : 0, partial);
+    if (dbias)
+        hipLaunchKernelGGL(bias_finalize_kernel, dim3((C + 127) / 128), dim3(128), 0, st, partial, s.row_blocks, C, dbias);
+}
+
+void launch_bias_relu_backward(int dtype, const void* y, void* dy, float* dbias, int64_t M, int C, bool relu,
+                               float* partial, hipStream_t st) {
+    if (!relu && !dbias) return;
+    if (dtype == 1) {
+        if (C % 8 == 0) bias_relu_backward_t<bf16_t, 8>(y, dy, dbias, M, C, relu, partial, st);
+        else bias_relu_backward_t<bf16_t, 1>(y, dy, dbias, M, C, relu, partial, st);
+    } else {
+        if (C % 4 == 0) bias_relu_backward_t<float, 4>(y, dy, dbias, M, C, relu, partial, st);
+        else bias_relu_backward_t<float, 1>(y, dy, dbias, M, C, relu, partial, st);
+    }
+}
+
+}  // namespace edl

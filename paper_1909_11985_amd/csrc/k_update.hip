@@ -1,0 +1,212 @@
+// HBM-bound kernels of the step: aggregation of the workers' gradients fused
+// with the momentum-SGD update (the all-reduce + optimizer of section 2.1 on
+// one GPU), the state copy a joining worker receives (section 4.2), and the
+// sample gather that stands for the prefetch pipeline (section 4.4).
+#include "dev_common.h"
+#include "kernels.h"
+
+namespace edl {
+
+static inline int grid_for(int64_t work_items, int block, int max_blocks) {
+    int64_t b = (work_items + block - 1) / block;
+    if (b < 1) b = 1;
+    if (b > max_blocks) b = max_blocks;
+    return (int)b;
+}
+
+// ---------------------------------------------------------------------------
+// g = (sum_k G_k)/p + wd*w ; v = momentum*v + g ; w = w - lr*v ; w16 = bf16(w)
+// One 16-byte vector per lane per stream; p+2 read streams and 2 (+1) write
+// streams, all fully coalesced.  NP > 0 fixes p at compile time so that all
+// p loads are in flight together.
+// ---------------------------------------------------------------------------
+template <int NP, bool SHADOW>
+__global__ __launch_bounds__(256) void average_update_kernel(GradPtrs gp, int p, float* __restrict__ w,
+                                                             float* __restrict__ v, uint16_t* __restrict__ w16,
+                                                             int64_t nvec, int64_t P, float lr, float momentum,
+                                                             float wd) {
+    const int np = NP > 0 ? NP : p;
+    const float fp = (float)np;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += stride) {
+        float4 s = reinterpret_cast<const float4*>(gp.g[0])[i];
+        if (NP > 0) {
+            float4 t[NP > 1 ? NP - 1 : 1];
+            #pragma unroll
+            for (int k = 1; k < NP; ++k) t[k - 1] = reinterpret_cast<const float4*>(gp.g[k])[i];
+            #pragma unroll
+            for (int k = 1; k < NP; ++k) { s.x += t[k - 1].x; s.y += t[k - 1].y; s.z += t[k - 1].z; s.w += t[k - 1].w; }
+        } else {
+            for (int k = 1; k < np; ++k) {
+                const float4 t = reinterpret_cast<const float4*>(gp.g[k])[i];
+                s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+            }
+        }
+        float4 wi = reinterpret_cast<float4*>(w)[i];
+        float4 vi = reinterpret_cast<float4*>(v)[i];
+        vi.x = momentum * vi.x + (s.x / fp + wd * wi.x);
+        vi.y = momentum * vi.y + (s.y / fp + wd * wi.y);
+        vi.z = momentum * vi.z + (s.z / fp + wd * wi.z);
+        vi.w = momentum * vi.w + (s.w / fp + wd * wi.w);
+        wi.x -= lr * vi.x; wi.y -= lr * vi.y; wi.z -= lr * vi.z; wi.w -= lr * vi.w;
+        reinterpret_cast<float4*>(v)[i] = vi;
+        reinterpret_cast<float4*>(w)[i] = wi;
+        if (SHADOW) {
+            uint2 o;
+            o.x = (uint32_t)f32_to_bf16(wi.x) | ((uint32_t)f32_to_bf16(wi.y) << 16);
+            o.y = (uint32_t)f32_to_bf16(wi.z) | ((uint32_t)f32_to_bf16(wi.w) << 16);
+            reinterpret_cast<uint2*>(w16)[i] = o;
+        }
+    }
+    // ragged tail (P not a multiple of 4): the first few lanes of block 0
+    if (blockIdx.x == 0 && threadIdx.x < (unsigned)(P - nvec * 4)) {
+        const int64_t i = nvec * 4 + threadIdx.x;
+        float s = gp.g[0][i];
+        for (int k = 1; k < np; ++k) s += gp.g[k][i];
+        float wi = w[i];
+        const float vi = momentum * v[i] + (s / fp + wd * wi);
+        wi -= lr * vi;
+        v[i] = vi;
+        w[i] = wi;
+        if (SHADOW) w16[i] = f32_to_bf16(wi);
+    }
+}
+
+void launch_average_update(int p, const GradPtrs& grads, float* w, float* v, uint16_t* w16, int64_t P, float lr,
+                           float momentum, float wd, hipStream_t st) {
+    const int64_t nvec = P / 4;
+    const int grid = grid_for(nvec, 256, 256 * 16);
+#define EDL_UPD(NP)                                                                                             \
+    do {                                                                                                        \
+        if (w16) hipLaunchKernelGGL((average_update_kernel<NP, true>), dim3(grid), dim3(256), 0, st, grads, p, w, v,  \
+                                    w16, nvec, P, lr, momentum, wd);                                            \
+        else hipLaunchKernelGGL((average_update_kernel<NP, false>), dim3(grid), dim3(256), 0, st, grads, p, w, v,     \
+                                w16, nvec, P, lr, momentum, wd);                                                \
+    } while (0)
+    switch (p) {
+        case 1: EDL_UPD(1); break;
+        case 2: EDL_UPD(2); break;
+        case 4: EDL_UPD(4); break;
+        case 8: EDL_UPD(8); break;
+        default: EDL_UPD(0); break;
+    }
+#undef EDL_UPD
+}
+
+// ---------------------------------------------------------------------------
+// plain copy (snapshot / restore): 16-byte vectors when source, destination
+// and length allow it (the large state arrays do), else 4-byte or 1-byte units
+// ---------------------------------------------------------------------------
+template <typename U>
+__global__ __launch_bounds__(256) void copy_kernel(U* __restrict__ dst, const U* __restrict__ src, int64_t n) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+}
+
+void launch_copy(void* dst, const void* src, size_t bytes, hipStream_t st) {
+    if (bytes == 0) return;
+    const uintptr_t bits = (uintptr_t)dst | (uintptr_t)src | (uintptr_t)bytes;
+    if ((bits & 15) == 0) {
+        const int64_t n = (int64_t)(bytes / 16);
+        hipLaunchKernelGGL(copy_kernel<uint4>, dim3(grid_for(n, 256, 256 * 16)), dim3(256), 0, st, (uint4*)dst, (const uint4*)src, n);
+    } else if ((bits & 3) == 0) {
+        const int64_t n = (int64_t)(bytes / 4);
+        hipLaunchKernelGGL(copy_kernel<uint32_t>, dim3(grid_for(n, 256, 256 * 16)), dim3(256), 0, st, (uint32_t*)dst, (const uint32_t*)src, n);
+    } else {
+        const int64_t n = (int64_t)bytes;
+        hipLaunchKernelGGL(copy_kernel<uint8_t>, dim3(grid_for(n, 256, 256 * 16)), dim3(256), 0, st, (uint8_t*)dst, (const uint8_t*)src, n);
+    }
+}
+
+__global__ __launch_bounds__(256) void fill_kernel(float* dst, float value, int64_t n) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = value;
+}
+
+void launch_fill_f32(float* dst, float value, int64_t n, hipStream_t st) {
+    if (n <= 0) return;
+    hipLaunchKernelGGL(fill_kernel, dim3(grid_for(n, 256, 4096)), dim3(256), 0, st, dst, value, n);
+}
+
+__global__ __launch_bounds__(256) void cast_bf16_kernel(const float* __restrict__ src, uint16_t* __restrict__ dst,
+                                                        int64_t n) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = f32_to_bf16(src[i]);
+}
+
+void launch_cast_bf16(const float* src, uint16_t* dst, int64_t n, hipStream_t st) {
+    if (n <= 0) return;
+    hipLaunchKernelGGL(cast_bf16_kernel, dim3(grid_for(n, 256, 4096)), dim3(256), 0, st, src, dst, n);
+}
+
+// ---------------------------------------------------------------------------
+// dst[c][t][k] = cast(src[k][t][c]),  t = kernel tap.  32x32 tiles through LDS
+// so that both the read (c innermost) and the write (k innermost) coalesce.
+// grid: (ceil(C/32), ceil(K/32), taps)
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void weight_transpose_kernel(const float* __restrict__ src, T* __restrict__ dst, int K,
+                                                               int RS, int C) {
+    __shared__ float tile[32][33];
+    const int t = blockIdx.z;
+    const int c0 = blockIdx.x * 32, k0 = blockIdx.y * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
+    for (int i = ty; i < 32; i += 8) {
+        const int k = k0 + i, c = c0 + tx;
+        tile[i][tx] = (k < K && c < C) ? src[((int64_t)k * RS + t) * C + c] : 0.f;
+    }
+    __syncthreads();
+    for (int i = ty; i < 32; i += 8) {
+        const int c = c0 + i, k = k0 + tx;
+        if (c < C && k < K) dst[((int64_t)c * RS + t) * K + k] = Elem<T>::from_f32(tile[tx][i]);
+    }
+}
+
+void launch_weight_transpose(int dtype, const float* src, void* dst, int K, int RS, int C, hipStream_t st) {
+    dim3 grid((C + 31) / 32, (K + 31) / 32, RS);
+    if (dtype == 1)
+        hipLaunchKernelGGL(weight_transpose_kernel<bf16_t>, grid, dim3(256), 0, st, src, (bf16_t*)dst, K, RS, C);
+    else
+        hipLaunchKernelGGL(weight_transpose_kernel<float>, grid, dim3(256), 0, st, src, (float*)dst, K, RS, C);
+}
+
+// ---------------------------------------------------------------------------
+// out_x[i][:] = cast(data_x[idx[i]][:]) ; out_y[i] = data_y[idx[i]]
+// grid: (chunks of the sample, n)
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void gather_kernel(const float* __restrict__ data_x, const int32_t* __restrict__ data_y,
+                                                     const int64_t* __restrict__ idx, int64_t sample_elems,
+                                                     T* __restrict__ out_x, int32_t* __restrict__ out_y) {
+    const int i = blockIdx.y;
+    const int64_t s = idx[i];
+    const float* src = data_x + s * sample_elems;
+    T* dst = out_x + (int64_t)i * sample_elems;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t t0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if ((sample_elems & 3) == 0) {
+        for (int64_t q = t0; q < sample_elems / 4; q += stride) {
+            const float4 f = reinterpret_cast<const float4*>(src)[q];
+            dst[4 * q + 0] = Elem<T>::from_f32(f.x);
+            dst[4 * q + 1] = Elem<T>::from_f32(f.y);
+            dst[4 * q + 2] = Elem<T>::from_f32(f.z);
+            dst[4 * q + 3] = Elem<T>::from_f32(f.w);
+        }
+    } else {
+        for (int64_t q = t0; q < sample_elems; q += stride) dst[q] = Elem<T>::from_f32(src[q]);
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) out_y[i] = data_y[s];
+}
+
+void launch_gather(int dtype, const float* data_x, const int32_t* data_y, const int64_t* idx, int n,
+                   int64_t sample_elems, void* out_x, int32_t* out_y, hipStream_t st) {
+    dim3 grid(grid_for(sample_elems / 4 + 1, 256, 64), n);
+    if (dtype == 1)
+        hipLaunchKernelGGL(gather_kernel<bf16_t>, grid, dim3(256), 0, st, data_x, data_y, idx, sample_elems,
+                           (bf16_t*)out_x, out_y);
+    else
+        hipLaunchKernelGGL(gather_kernel<float>, grid, dim3(256), 0, st, data_x, data_y, idx, sample_elems,
+                           (float*)out_x, out_y);
+}
+
+}  // namespace edl

@@ -1,0 +1,76 @@
+// Host-callable launchers of the HIP kernels.  `dtype` is EDL_DTYPE_*: the
+// element type of activation tensors and of the weight copies the matrix
+// cores read.  Every launcher only queues work on `st`.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <cstddef>
+#include <cstdint>
+
+namespace edl {
+
+constexpr int kMaxP = 16;           // gradient buffers one update launch can average
+constexpr int kRedRowBlocks = 64;   // upper bound of row blocks in column reductions
+
+struct GradPtrs { const float* g[kMaxP]; };
+
+// ---- aggregation + update, copies ----------------------------------------
+void launch_average_update(int p, const GradPtrs& grads, float* w, float* v, uint16_t* w16, int64_t P,
+                           float lr, float momentum, float wd, hipStream_t st);
+void launch_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
+void launch_fill_f32(float* dst, float value, int64_t n, hipStream_t st);
+// dst[c][r][s][k] = cast(src[k][r][s][c])  (weights for the input-gradient contraction)
+void launch_weight_transpose(int dtype, const float* src, void* dst, int K, int RS, int C, hipStream_t st);
+// dst = cast(src) for float32 -> bf16 (weight copy after restore / set_params)
+void launch_cast_bf16(const float* src, uint16_t* dst, int64_t n, hipStream_t st);
+
+// ---- input --------------------------------------------------------------
+void launch_gather(int dtype, const float* data_x, const int32_t* data_y, const int64_t* idx, int n,
+                   int64_t sample_elems, void* out_x, int32_t* out_y, hipStream_t st);
+
+// ---- implicit-GEMM convolution --------------------------------------------
+enum ConvMode { CONV_FWD = 0, CONV_DGRAD = 1, CONV_WGRAD = 2 };
+
+struct ConvGeom {
+    int N, H, W, C;          // input images
+    int K, R, S, stride, pad, Ho, Wo;
+};
+
+// y = conv(x, w) (+bias) (ReLU); y is float32 if out_fp32 else dtype
+void launch_conv_fwd(int dtype, const ConvGeom& g, const void* x, const void* w, const float* bias, bool relu,
+                     bool out_fp32, void* y, hipStream_t st);
+// dx (+)= conv^T(dy, wT); wT is the [C][R][S][K] copy
+void launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dy, const void* wT, bool accumulate, void* dx,
+                       hipStream_t st);
+// dw = x^T * dy, float32 [K][R][S][C]; scratch holds split partial sums
+void launch_conv_wgrad(int dtype, const ConvGeom& g, const void* x, const void* dy, float* dw, float* scratch,
+                       size_t scratch_bytes, hipStream_t st);
+size_t conv_wgrad_scratch_bytes(const ConvGeom& g);
+
+// ---- batch norm, bias / ReLU backward --------------------------------------
+// partial: float32 scratch of 2 * kRedRowBlocks * C floats
+void launch_bn_forward(int dtype, const void* x, const void* res, void* y, const float* gamma, const float* beta,
+                       float* save_mean_rstd /*[2C]*/, float* running /*[2C] or null*/, int64_t M, int C,
+                       bool relu, float* partial, hipStream_t st);
+void launch_bn_backward(int dtype, const void* x, const void* y, const void* dy, void* dx, void* dres,
+                        bool dres_accumulate, const float* gamma, const float* save_mean_rstd,
+                        float* dgamma, float* dbeta, int64_t M, int C, bool relu, float* partial, float* coef /*[2C]*/,
+                        hipStream_t st);
+// dy <- dy * (y > 0) in place if relu; dbias[c] = sum_rows dy (if dbias)
+void launch_bias_relu_backward(int dtype, const void* y, void* dy, float* dbias, int64_t M, int C, bool relu,
+                               float* partial, hipStream_t st);
+
+// ---- pooling --------------------------------------------------------------
+void launch_maxpool_forward(int dtype, const void* x, void* y, uint8_t* arg, int N, int H, int W, int C, int k,
+                            int stride, int pad, int Ho, int Wo, hipStream_t st);
+void launch_maxpool_backward(int dtype, const void* dy, const uint8_t* arg, void* dx, bool accumulate, int N, int H,
+                             int W, int C, int k, int stride, int pad, int Ho, int Wo, hipStream_t st);
+void launch_gavgpool_forward(int dtype, const void* x, void* y, int N, int HW, int C, hipStream_t st);
+void launch_gavgpool_backward(int dtype, const void* dy, void* dx, bool accumulate, int N, int HW, int C,
+                              hipStream_t st);
+
+// ---- loss -------------------------------------------------------------------
+// logits float32 [n][C]; dlogits in dtype; loss_out[0] = mean over the n rows
+void launch_softmax_ce(int dtype, const float* logits, const int32_t* labels, void* dlogits, float* row_loss,
+                       float* loss_out, int n, int C, hipStream_t st);
+
+}  // namespace edl

@@ -1,0 +1,185 @@
+"""Parity of the HIP path against the CPU oracle, through the C boundary.
+Needs an MI355X: run with -m gpu."""
+import numpy as np
+import pytest
+
+import synth_inputs
+from oracle import oracle as O
+from parity_util import TOL, relerr, run_parity
+
+pytestmark = pytest.mark.gpu
+
+
+def _torch():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return torch
+
+
+# ---------------------------------------------------------------- aggregation + update
+@pytest.mark.parametrize("p", [1, 2, 3, 4, 8])
+@pytest.mark.parametrize("P", [4096 * 5, 100003, 3])
+@pytest.mark.parametrize("shadow", [False, True])
+def test_average_update_matches_oracle(p, P, shadow):
+    torch = _torch()
+    import paper_1909_11985_amd as E
+    grads = synth_inputs.gradient_buffers(3, p, P)
+    w = synth_inputs.vector(4, P)
+    v = synth_inputs.vector(5, P, 0.1)
+    dg = [torch.from_numpy(g).cuda() for g in grads]
+    dw, dv = torch.from_numpy(w).cuda(), torch.from_numpy(v).cuda()
+    d16 = torch.zeros(P, dtype=torch.bfloat16, device="cuda") if shadow else None
+    ow, ov = w.astype(np.float64), v.astype(np.float64)
+    for _ in range(3):
+        E.edl_average_update(dg, dw, dv, d16, 0.1, 0.9, 5e-4)
+        ow, ov = O.sgd_momentum_update(ow, ov, [g.astype(np.float64) for g in grads], 0.1, 0.9, 5e-4)
+    torch.cuda.synchronize()
+    gw, gv = dw.cpu().numpy(), dv.cpu().numpy()
+    np.testing.assert_allclose(gw, ow, rtol=2e-6, atol=1e-7)
+    np.testing.assert_allclose(gv, ov, rtol=2e-6, atol=1e-7)
+    if shadow:
+        # the bf16 copy is the kernel's own float32 result rounded to nearest even
+        want = O.round_bf16(gw).astype(np.float32)
+        got = d16.float().cpu().numpy()
+        np.testing.assert_array_equal(got.view(np.uint32), want.view(np.uint32))
+
+
+def test_average_update_rejects_bad_arguments():
+    torch = _torch()
+    import paper_1909_11985_amd as E
+    w = torch.zeros(64, device="cuda")
+    with pytest.raises(E.EdlError):
+        E.edl_average_update([w] * 17, w, w, None, 0.1, 0.9, 0.0)
+    with pytest.raises(E.EdlError):
+        E.edl_average_update([w[1:]], w[1:], w[1:], None, 0.1, 0.9, 0.0)     # misaligned
+
+
+@pytest.mark.parametrize("nbytes,shift", [(0, 0), (1 << 20, 0), (1000003, 0), (4096, 4), (4099, 1)])
+def test_copy_is_exact(nbytes, shift):
+    torch = _torch()
+    import paper_1909_11985_amd as E
+    src = torch.randint(0, 256, (nbytes + 64,), dtype=torch.uint8, device="cuda")
+    dst = torch.zeros(nbytes + 64, dtype=torch.uint8, device="cuda")
+    if nbytes:
+        E.edl_copy(dst[shift:], src[shift:], nbytes)
+    torch.cuda.synchronize()
+    assert torch.equal(dst[shift:shift + nbytes], src[shift:shift + nbytes])
+    assert int(dst[shift + nbytes:].sum()) == 0 and int(dst[:shift].sum()) == 0
+
+
+# ---------------------------------------------------------------- whole iteration, small nets
+TINY = {
+    "mlp": dict(H=1, W=1, C=24, classes=5, arch=(20, 12)),                 # odd sizes: scalar load paths
+    "resnet20": dict(H=12, W=12, C=3, classes=6, arch=(8, 2, 1)),
+    "resnet50": dict(H=32, W=32, C=3, classes=10, arch=(8, 1, 1, 0, 0)),
+    "vgg16": dict(H=32, W=32, C=3, classes=7, arch=(8, 16)),
+}
+
+
+@pytest.mark.parametrize("model", list(TINY))
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_tiny_nets(model, dtype):
+    lr = 0.01 if model == "vgg16" else 0.1
+    r = run_parity(model, dtype, N=48, B=24, schedule=[2, 1, 4, 3], lr=lr, **TINY[model])
+    tol = TOL[dtype]
+    assert r["grad"] < tol and r["param"] < tol and r["momentum"] < tol and r["loss"] < tol, r
+    assert r["running"] < tol
+
+
+# ---------------------------------------------------------------- the configurations of the baseline
+def test_config1_mlp_fp32():
+    """MLP 784-256-256-10, global batch 64 as p=4 shards of 16, 5 steps."""
+    r = run_parity("mlp", "f32", N=1024, B=64, schedule=[4] * 5)
+    assert r["grad"] < TOL["f32"] and r["param"] < TOL["f32"] and r["loss"] < 1e-5, r
+
+
+def test_config2_resnet20_fp32_p_changes():
+    """ResNet-20, global batch 128, p = 2 -> 4 -> 8 at steps 10 / 20, 30 steps (crosses an epoch)."""
+    r = run_parity("resnet20", "f32", N=2048, B=128, schedule=[2] * 10 + [4] * 10 + [8] * 10,
+                   check_every_step=False)
+    assert r["grad"] < TOL["f32"] and r["param"] < TOL["f32"], r
+    assert r["job"].progress() == (30, 1, 14)
+
+
+def test_resnet20_bf16():
+    r = run_parity("resnet20", "bf16", N=256, B=64, schedule=[2, 4, 1])
+    assert r["grad"] < TOL["bf16"] and r["param"] < TOL["bf16"], r
+
+
+def test_resnet50_bf16_reduced_resolution():
+    """Full ResNet-50 layer table on 64x64 images (the oracle at 224x224 takes minutes per step)."""
+    r = run_parity("resnet50", "bf16", N=64, B=32, schedule=[1, 2, 1], H=64, W=64)
+    assert r["grad"] < TOL["bf16"] and r["param"] < TOL["bf16"], r
+
+
+def test_resnet50_fp32_reduced_resolution():
+    r = run_parity("resnet50", "f32", N=32, B=16, schedule=[1, 2], H=64, W=64)
+    assert r["grad"] < TOL["f32"] and r["param"] < TOL["f32"], r
+
+
+def test_vgg16_bf16_reduced_width():
+    """VGG-16 layer table at 64x64 with narrower fully connected layers."""
+    r = run_parity("vgg16", "bf16", N=32, B=16, schedule=[1, 2], H=64, W=64, arch=(64, 512), lr=0.01)
+    assert r["grad"] < TOL["bf16"] and r["param"] < TOL["bf16"], r
+
+
+# ---------------------------------------------------------------- snapshot
+def test_snapshot_bytes_and_resume():
+    torch = _torch()
+    r = run_parity("resnet20", "f32", N=48, B=24, schedule=[2, 4], verbose=False, **TINY["resnet20"])
+    job, orc = r["job"], r["oracle"]
+    snap = job.snapshot()
+    torch.cuda.synchronize()
+    blob = snap.cpu().numpy().tobytes()
+    ob = orc.snapshot()
+    assert len(blob) == len(ob)
+    assert blob[:96] == ob[:96]                                   # header: meta-data and progress, byte for byte
+    P, R = job.P, job.R
+    hb = O.SNAPSHOT_HEADER_BYTES
+    assert np.array_equal(np.frombuffer(blob, np.float32, P, hb), job.params())
+    assert np.array_equal(np.frombuffer(blob, np.float32, P, hb + 4 * P), job.momentum())
+    assert np.array_equal(np.frombuffer(blob, np.float32, R, hb + 8 * P), job.running())
+    # the joiner: another job object, different seed, receives the image; both continue identically
+    import paper_1909_11985_amd as E
+    joiner = E.Job(job.cfg, 99)
+    joiner.bind_dataset(*job._data)
+    joiner.restore(snap)
+    assert joiner.progress() == job.progress()
+    for p in (4, 1, 2):
+        la = job.step(p)
+        lb = joiner.step(p)
+        assert la == lb
+    assert np.array_equal(job.params(), joiner.params()) and np.array_equal(job.momentum(), joiner.momentum())
+    assert np.array_equal(job.running(), joiner.running())
+
+
+def test_step_is_deterministic():
+    a = run_parity("resnet50", "bf16", N=48, B=24, schedule=[2, 3], verbose=False, **TINY["resnet50"])
+    b = run_parity("resnet50", "bf16", N=48, B=24, schedule=[2, 3], verbose=False, **TINY["resnet50"])
+    assert np.array_equal(a["job"].params(), b["job"].params())
+
+
+# ---------------------------------------------------------------- argument checking
+def test_step_rejects_bad_requests():
+    torch = _torch()
+    import paper_1909_11985_amd as E
+    from paper_1909_11985_amd.binding import make_config
+    cfg = make_config("mlp", N=64, B=16, p_max=4, max_shard=8, C_=8, arch=(8, 8), classes=3)
+    job = E.Job(cfg, 0)
+    with pytest.raises(E.EdlError) as ei:
+        job.step(2)
+    assert ei.value.code == -1                                     # no data set bound
+    x, y = synth_inputs.dataset(0, 64, 1, 1, 8, 3)
+    job.bind_dataset(torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda())
+    for p, code in [(0, -1), (5, -1), (3, -2), (1, -3)]:
+        with pytest.raises(E.EdlError) as ei:
+            job.step(p)
+        assert ei.value.code == code
+    idx, off = job.shard(16, 2, 0, 0)
+    bad = idx.copy(); bad[3] = 64
+    with pytest.raises(E.EdlError) as ei:
+        job.step(2, bad, off)
+    assert ei.value.code == -4
+    assert job.progress() == (0, 0, 0)                             # failed calls leave the cursor alone
+    job.step(2, idx, off)
+    assert job.progress() == (1, 0, 1)

@@ -1,0 +1,85 @@
+"""CPU-only checks of the C boundary: the library loads, exports every symbol
+the header declares, and its host logic (shard assignment, initialisation,
+parameter layout) agrees with the oracle.  No compute call is made."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import oracle as O
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def E():
+    import paper_1909_11985_amd as E
+    return E
+
+
+def test_every_declared_symbol_is_exported(E):
+    text = open(os.path.join(ROOT, "include", "edl.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(edl_[a-z0-9_]+)\s*\(", text))
+    assert len(declared) >= 20
+    for name in sorted(declared):
+        assert hasattr(E.lib, name), name
+    from paper_1909_11985_amd import binding
+    assert declared == set(binding.EXPORTS)
+
+
+@pytest.mark.parametrize("seed", [0, 7, 2**63 + 5])
+@pytest.mark.parametrize("N,B", [(64, 8), (1024, 64), (2048, 128), (2048, 256)])
+def test_shard_assignment_is_bit_exact(E, seed, N, B):
+    for epoch in (0, 1, 5):
+        for t in (0, N // B - 1):
+            for p in (1, 2, 4, 8):
+                idx, off = E.edl_shard_host(seed, N, B, p, epoch, t)
+                io, oo = O.shard(seed, N, B, p, epoch, t)
+                assert idx.dtype == np.int64 and np.array_equal(idx, io) and np.array_equal(off, oo)
+
+
+def test_shard_errors(E):
+    for args, code in [((0, 64, 8, 3, 0, 0), -2), ((0, 60, 8, 2, 0, 0), -2), ((0, 64, 8, 2, 0, 8), -4),
+                       ((0, 64, 8, 0, 0, 0), -1), ((0, 64, 8, 2, -1, 0), -1)]:
+        with pytest.raises(E.EdlError) as ei:
+            E.edl_shard_host(*args)
+        assert ei.value.code == code, args
+
+
+@pytest.mark.parametrize("model", ["mlp", "resnet20", "resnet50", "vgg16"])
+def test_parameter_layout_and_init_match_the_oracle(E, model):
+    from paper_1909_11985_amd.binding import make_config
+    cfg = make_config(model, N=64, B=32, p_max=2)
+    g = O.BUILDERS[model]()
+    table = E.edl_tensor_table(cfg)
+    assert table == [(n, o, int(np.prod(s)), f) for n, o, s, f in g.tensors]
+    s = E.edl_query(cfg)
+    assert (s.P, s.R) == (g.P, g.R)
+    assert s.snapshot_bytes == O.SNAPSHOT_HEADER_BYTES + 4 * (2 * g.P + g.R)
+    if model != "vgg16":                      # 138M Gaussians: covered on the GPU machine through the parity runs
+        w = E.edl_init_params_host(cfg, 3)
+        wo = O.he_init(g, 3)
+        # both sides run Box-Muller in double and round to float32; allow a last-place difference of libm
+        assert np.max(np.abs(w - wo)) <= 2.0 ** -23 * np.max(np.abs(wo))
+        assert np.mean(w.astype(np.float64) != wo) < 1e-5
+
+
+def test_query_rejects_bad_configurations(E):
+    from paper_1909_11985_amd.binding import make_config
+    for kw, code in [(dict(N=60, B=32), -2), (dict(p_max=17), -1), (dict(p_max=0), -1), (dict(model=9), -1), (dict(dtype=5), -1)]:
+        base = dict(model="resnet50", N=64, B=32, p_max=2)
+        base.update(kw)
+        with pytest.raises(E.EdlError) as ei:
+            E.edl_query(make_config(**base))
+        assert ei.value.code == code, kw
+
+
+def test_flops_per_sample(E):
+    from paper_1909_11985_amd.binding import make_config
+    # forward multiply-adds: 784*256 + 256*256 + 256*10; the first layer has no input gradient
+    s = E.edl_query(make_config("mlp", N=64, B=32, p_max=2))
+    assert s.flops_per_sample == 2 * (2 * 784 * 256 + 3 * 256 * 256 + 3 * 256 * 10)
+    r = E.edl_query(make_config("resnet50", N=64, B=32, p_max=2))
+    assert 23e9 < r.flops_per_sample < 25e9
