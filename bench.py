@@ -1,0 +1,209 @@
+#!/usr/bin/env python3
+"""Benchmark of the elastic data-parallel training step on one MI355X.
+
+    python bench.py --gpus 1 --steps 20 --warmup 3
+
+A "step" is one pass of the whole hot path: shard assignment, gather + cast,
+forward and backward of every worker's shard, aggregation of the p gradient
+buffers fused with the momentum-SGD update.  The default workload is the one
+the headline metric is quoted on: ResNet-50, bf16 activations with float32
+master weights and momentum, one worker's shard of 32 samples of 224x224x3
+synthetic N(0,1) images with 1000 uniform labels.  Inputs are resident in HBM
+before the timed region.
+
+Prints ONE JSON line.  Besides the contract fields it carries
+  roofline      the kernel family that takes the most time in the step, timed with HIP
+                events on the launch stream (the library's own profiling hooks)
+  cpu_baseline  the CPU oracle, as it stands, timed on a bounded sample of the same workload
+  update, snapshot   the HBM-bound parts of the metric on the VGG-16-sized state
+                (138,357,544 parameters): achieved GB/s against the 8 TB/s peak
+  kernels       per-family time, launches and achieved rate of one step
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+VGG16_P = 138357544
+
+WORKLOADS = {
+    # name: (model, dtype, N, B, p, geometry overrides, lr)
+    "resnet50_bf16_b32": ("resnet50", "bf16", 1024, 32, 1, {}, 0.1),
+    "vgg16_bf16_b32": ("vgg16", "bf16", 256, 32, 1, {}, 0.01),
+    "resnet20_f32_b128_p2": ("resnet20", "f32", 2048, 128, 2, {}, 0.1),
+    "mlp_f32_b64_p4": ("mlp", "f32", 1024, 64, 4, {}, 0.1),
+}
+DEFAULT_HWC = {"mlp": (1, 1, 784, 10), "resnet20": (32, 32, 3, 10), "resnet50": (224, 224, 3, 1000),
+               "vgg16": (224, 224, 3, 1000)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="resnet50_bf16_b32", choices=sorted(WORKLOADS))
+    ap.add_argument("--p", type=int, default=0, help="override the parallelism (shards of the global batch)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-state-bench", action="store_true", help="skip the VGG-16-sized update / snapshot timing")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the p workers are shards of the batch on that GPU); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import synth_inputs
+    import paper_1909_11985_amd as E
+    from paper_1909_11985_amd.binding import make_config
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    model, dtype, N, B, p, geom, lr = WORKLOADS[args.workload]
+    if args.p:
+        p = args.p
+    H, W, C, classes = DEFAULT_HWC[model]
+    x, y = synth_inputs.dataset(1, N, H, W, C, classes)
+    cfg = make_config(model, dtype=dtype, N=N, B=B, p_max=max(p, 1), max_shard=B // p, lr=lr, **geom)
+    job = E.Job(cfg, 0)
+    dx, dy = torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda()
+    job.bind_dataset(dx, dy)
+    sizes = job.sizes
+
+    for _ in range(args.warmup):
+        job.step(p, want_loss=False)
+    job.sync()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        job.step(p, want_loss=False)
+    job.sync()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = B * args.steps / (t1 - t0)
+    loss = job.step(p, want_loss=True)
+    assert np.isfinite(loss), "training diverged"
+
+    # ---- per-kernel timing of a few more steps (HIP events on the launch stream) ----
+    prof_steps = 3
+    E.edl_profile(True)
+    for _ in range(prof_steps):
+        job.step(p, want_loss=False)
+    job.sync()
+    rep = E.edl_profile_report()
+    E.edl_profile(False)
+    kernels = []
+    for r in rep:
+        ms = r["ms"] / prof_steps
+        k = dict(name=r["name"], launches_per_step=r["launches"] / prof_steps, ms_per_step=round(ms, 4),
+                 avg_launch_us=round(1e3 * r["ms"] / max(r["launches"], 1), 2))
+        if r["flops"] > 0:
+            k["tflops"] = round(r["flops"] / r["ms"] / 1e9, 2)
+        k["gbs"] = round(r["bytes"] / r["ms"] / 1e6, 1)
+        kernels.append(k)
+    kernels.sort(key=lambda k: -k["ms_per_step"])
+    dom = max(rep, key=lambda r: r["ms"])
+    if dom["flops"] > 0:
+        achieved = dom["flops"] / dom["ms"] / 1e9
+        peak = MFMA_PEAK_TFLOPS[dtype]
+        roofline = dict(bound="mfma", kernel=dom["name"], achieved=round(achieved, 2), peak=peak, unit="TFLOP/s",
+                        frac=round(achieved / peak, 4), traffic=None,
+                        avg_launch_us=round(1e3 * dom["ms"] / dom["launches"], 2),
+                        launches_per_step=dom["launches"] / prof_steps)
+    else:
+        achieved = dom["bytes"] / dom["ms"] / 1e6
+        roofline = dict(bound="hbm", kernel=dom["name"], achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                        frac=round(achieved / HBM_PEAK_GBS, 4), traffic=None,
+                        avg_launch_us=round(1e3 * dom["ms"] / dom["launches"], 2),
+                        launches_per_step=dom["launches"] / prof_steps)
+    conv_ms = sum(r["ms"] for r in rep if r["flops"] > 0) / prof_steps
+    conv_flops = sum(r["flops"] for r in rep if r["flops"] > 0) / prof_steps
+    step_summary = dict(
+        flops_per_sample=sizes.flops_per_sample,
+        step_tflops=round(sizes.flops_per_sample * B / (ms_per_step * 1e-3) / 1e12, 2),
+        step_frac_of_mfma_peak=round(sizes.flops_per_sample * B / (ms_per_step * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS[dtype], 4),
+        contraction_ms_per_step=round(conv_ms, 3),
+        contraction_tflops=round(conv_flops / max(conv_ms, 1e-9) / 1e9, 2),
+        kernel_ms_per_step=round(sum(r["ms"] for r in rep) / prof_steps, 3))
+
+    # ---- the HBM-bound half of the metric on the VGG-16-sized state ----
+    update, snapshot = None, None
+    job_P = sizes.P
+    job.shutdown()
+    del job
+    if not args.no_state_bench:
+        P = VGG16_P
+        update = []
+        w = torch.from_numpy(synth_inputs.vector(4, P)).cuda()
+        v = torch.zeros(P, device="cuda")
+        w16 = torch.empty(P, dtype=torch.bfloat16, device="cuda")
+        g0 = synth_inputs.gradient_buffers(3, 1, P)[0]
+        grads = [torch.from_numpy(g0).cuda() for _ in range(8)]
+        for pp in (1, 2, 4, 8):
+            for _ in range(2):
+                E.edl_average_update(grads[:pp], w, v, w16, 0.01, 0.9, 5e-4)
+            torch.cuda.synchronize()
+            E.edl_profile(True)
+            for _ in range(10):
+                E.edl_average_update(grads[:pp], w, v, w16, 0.01, 0.9, 5e-4)
+            torch.cuda.synchronize()
+            r = [q for q in E.edl_profile_report() if q["name"] == "average_update"][0]
+            E.edl_profile(False)
+            gbs = r["bytes"] / r["ms"] / 1e6
+            update.append(dict(p=pp, P=P, bytes_per_param=4 * pp + 18, us=round(1e3 * r["ms"] / r["launches"], 1),
+                               gbs=round(gbs, 1), frac_of_hbm_peak=round(gbs / HBM_PEAK_GBS, 4)))
+        del grads
+        nbytes = 8 * P
+        src = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        dst = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        for _ in range(2):
+            E.edl_copy(dst, src, nbytes)
+        torch.cuda.synchronize()
+        E.edl_profile(True)
+        for _ in range(10):
+            E.edl_copy(dst, src, nbytes)
+        torch.cuda.synchronize()
+        r = [q for q in E.edl_profile_report() if q["name"] == "copy"][0]
+        E.edl_profile(False)
+        gbs = r["bytes"] / r["ms"] / 1e6
+        snapshot = dict(state_bytes=nbytes, us=round(1e3 * r["ms"] / r["launches"], 1), gbs=round(gbs, 1),
+                        frac_of_hbm_peak=round(gbs / HBM_PEAK_GBS, 4))
+        del src, dst, w, v, w16
+
+    # ---- the oracle on the host cores, on a bounded sample of the same workload ----
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        from oracle import oracle as O
+        n_cpu = {"resnet50": 16, "vgg16": 4, "resnet20": B // p, "mlp": B // p}[model]
+        orc = O.Oracle(model, 0, N, n_cpu, lr=lr)
+        xs, ys = x[:n_cpu].astype(np.float64), y[:n_cpu]
+        tc0 = time.perf_counter()
+        orc.forward_backward(xs, ys)
+        tc1 = time.perf_counter()
+        cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        cpu_baseline = dict(value=round(n_cpu / (tc1 - tc0), 3), unit="samples/s", cores=cores, kind="oracle",
+                            sample="forward+backward of one shard of %d samples of the same workload (%.1f s)"
+                                   % (n_cpu, tc1 - tc0))
+
+    out = {
+        "metric": "training samples/s per MI355X (ResNet-50 bf16); grad-avg+update HBM GB/s",
+        "value": round(value, 2), "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": dtype, "data": "synthetic",
+        "config": {"workload": args.workload, "global_batch": B, "p": p, "shard": B // p, "image": [H, W, C],
+                   "classes": classes, "parameters": job_P, "dataset_samples": N},
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "step": step_summary,
+        "update": update, "snapshot": snapshot, "kernels": kernels[:14],
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

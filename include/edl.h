@@ -164,6 +164,36 @@ int32_t edl_get_running(edl_handle* h, float* host_dst /* [R] */);
 int32_t edl_get_grad(edl_handle* h, int32_t k, float* host_dst /* [P] */);
 int32_t edl_get_losses(edl_handle* h, int32_t p, float* host_dst /* [p] */);
 int32_t edl_set_params(edl_handle* h, const float* host_src /* [P] */);
+int32_t edl_set_momentum(edl_handle* h, const float* host_src /* [P] */);
+
+/* Debugging hooks: run the two halves of one worker's pass separately and read
+ * or overwrite activation tensors in between, so that a test can take the
+ * sign / arg-max decisions of the backward pass from given activations.
+ * Tensor 0 is the input batch; tensors are numbered in the order the layer
+ * list creates them (a flattened view is a tensor of its own whose alias_of
+ * names the tensor it shares storage with, else -1).  Host buffers are
+ * float32 [n][H][W][C] whatever the job's dtype; `which` = 0 activation,
+ * 1 gradient w.r.t. the activation.  All of these synchronise the stream.
+ * edl_debug_set_tensor overwrites an activation (which = 0) or gradient (1) buffer.
+ * edl_debug_forward: gather idx[0..n) (host) and run the forward pass, mean
+ * loss readable through edl_get_losses(.., 1, ..); running statistics are not
+ * touched.  edl_debug_backward: recompute the loss gradient from the current
+ * logits and run the backward pass into gradient buffer k. */
+int32_t edl_debug_tensor_count(const edl_handle* h, int32_t* out_count);
+int32_t edl_debug_tensor_shape(const edl_handle* h, int32_t t, int32_t* H, int32_t* W, int32_t* C, int32_t* alias_of);
+int32_t edl_debug_forward(edl_handle* h, const int64_t* idx, int32_t n);
+int32_t edl_debug_backward(edl_handle* h, int32_t n, int32_t k);
+int32_t edl_debug_get_tensor(edl_handle* h, int32_t t, int32_t which, int32_t n, float* host_dst);
+int32_t edl_debug_set_tensor(edl_handle* h, int32_t t, int32_t which, int32_t n, const float* host_src);
+/* One layer alone, on whatever its input buffers hold: forward writes the layer's
+ * output activation (and the batch statistics / arg-max it keeps for its
+ * backward); backward reads the gradient buffer of its output and overwrites
+ * the gradient buffers of its inputs and its slice of gradient buffer k.  The
+ * loss layer reads the labels given by edl_debug_set_labels (host int32[n]). */
+int32_t edl_debug_op_count(const edl_handle* h, int32_t* out_count);
+int32_t edl_debug_forward_op(edl_handle* h, int32_t op, int32_t n);
+int32_t edl_debug_backward_op(edl_handle* h, int32_t op, int32_t n, int32_t k);
+int32_t edl_debug_set_labels(edl_handle* h, const int32_t* labels, int32_t n);
 
 int32_t edl_shutdown(edl_handle* h);
 
@@ -175,6 +205,16 @@ int32_t edl_shutdown(edl_handle* h);
 int32_t edl_average_update(int32_t p, const float* const* dev_grads, float* dev_w, float* dev_v,
                            uint16_t* dev_w16, int64_t P, float lr, float momentum, float wd,
                            void* hip_stream);
+
+/* Measurement: with profiling on, every kernel launch of this library (any
+ * handle, and the stand-alone calls) is bracketed by a HIP event pair on the
+ * stream it is launched on.  edl_profile_report waits for those events, writes
+ * a NUL-terminated JSON array of {"name","launches","ms","flops","bytes"}
+ * (totals per kernel family; flops and bytes are the algorithmic work of the
+ * launches) into buf and forgets the records.  EDL_ENOMEM if cap is too small
+ * (out_needed then holds the size to bring). */
+int32_t edl_profile(int32_t enable);
+int32_t edl_profile_report(char* buf, size_t cap, size_t* out_needed);
 
 /* Stand-alone vectorised device-to-device copy used by edl_snapshot. */
 int32_t edl_copy(void* dev_dst, const void* dev_src, size_t bytes, void* hip_stream);

@@ -492,21 +492,30 @@ class Oracle:
                 z = act[op["x"]].reshape(x.shape[0], -1)
                 loss, prob = softmax_ce_forward(z, labels)
                 saved[i] = prob
+        self.last_act = act            # name -> activation, "x", "t1", "t2", ... in creation order
         # backward
         G = np.zeros(g.P)
         grad = {}
 
+        self.last_dy, self.last_dx = {}, {}     # per op: gradient of its output as used; {input: its contribution}
+        cur = [None]
+
         def add(name, val):
             if name == "x":
                 return
+            self.last_dx.setdefault(cur[0], {})[name] = q(val)
             grad[name] = q(grad[name] + val) if name in grad else q(val)
 
         for i in range(len(g.ops) - 1, -1, -1):
             op = g.ops[i]
             kind = op["kind"]
+            cur[0] = i
+            if "y" in op and op["y"] in grad:
+                self.last_dy[i] = grad[op["y"]]
             if kind == "loss":
                 dz = softmax_ce_backward(saved[i], labels)
                 grad[op["x"]] = q(dz.reshape(act[op["x"]].shape))
+                self.last_dx[i] = {op["x"]: grad[op["x"]]}
             elif kind == "conv":
                 dy = grad.pop(op["y"])
                 if op["relu"]:

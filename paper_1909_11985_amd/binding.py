@@ -74,10 +74,24 @@ _SIGS = {
     "edl_get_grad": [C.c_void_p, C.c_int32, _f32p],
     "edl_get_losses": [C.c_void_p, C.c_int32, _f32p],
     "edl_set_params": [C.c_void_p, _f32p],
+    "edl_set_momentum": [C.c_void_p, _f32p],
+    "edl_debug_tensor_count": [C.c_void_p, C.POINTER(C.c_int32)],
+    "edl_debug_tensor_shape": [C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32),
+                               C.POINTER(C.c_int32), C.POINTER(C.c_int32)],
+    "edl_debug_forward": [C.c_void_p, _i64p, C.c_int32],
+    "edl_debug_backward": [C.c_void_p, C.c_int32, C.c_int32],
+    "edl_debug_get_tensor": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, _f32p],
+    "edl_debug_set_tensor": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, _f32p],
+    "edl_debug_op_count": [C.c_void_p, C.POINTER(C.c_int32)],
+    "edl_debug_forward_op": [C.c_void_p, C.c_int32, C.c_int32],
+    "edl_debug_backward_op": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32],
+    "edl_debug_set_labels": [C.c_void_p, C.POINTER(C.c_int32), C.c_int32],
     "edl_shutdown": [C.c_void_p],
     "edl_average_update": [C.c_int32, C.POINTER(C.c_void_p), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
                            C.c_float, C.c_float, C.c_float, C.c_void_p],
     "edl_copy": [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p],
+    "edl_profile": [C.c_int32],
+    "edl_profile_report": [C.c_char_p, C.c_size_t, C.POINTER(C.c_size_t)],
 }
 for _name, _args in _SIGS.items():
     _fn = getattr(lib, _name)
@@ -149,6 +163,20 @@ def edl_average_update(grads, w, v, w16, lr, momentum, wd, stream=0):
 
 def edl_copy(dst, src, nbytes, stream=0):
     _check(lib.edl_copy(dst.data_ptr(), src.data_ptr(), nbytes, stream))
+
+
+def edl_profile(enable):
+    _check(lib.edl_profile(1 if enable else 0))
+
+
+def edl_profile_report():
+    """List of dicts {name, launches, ms, flops, bytes}: totals since profiling was switched on
+    (or since the last report)."""
+    import json
+    buf = C.create_string_buffer(1 << 16)
+    need = C.c_size_t()
+    _check(lib.edl_profile_report(buf, len(buf), C.byref(need)))
+    return json.loads(buf.value.decode())
 
 
 class Job:
@@ -229,12 +257,66 @@ class Job:
     def grad(self, k):
         return self._get(lib.edl_get_grad, self.P, k)
 
+    def grad_slice(self, k, off, size):
+        """float32 host copy of G_k[off:off+size] (a view of the arena, no library call)."""
+        self.sync()
+        base = self.sizes.grads_off + 4 * (k * self.sizes.grad_stride + off)
+        return self.arena[base:base + 4 * size].view(self.torch.float32).cpu().numpy()
+
     def losses(self, p):
         return self._get(lib.edl_get_losses, p, p)
 
     def set_params(self, w):
         w = np.ascontiguousarray(w, dtype=np.float32)
         _check(lib.edl_set_params(self._h, w.ctypes.data_as(_f32p)))
+
+    def set_momentum(self, v):
+        v = np.ascontiguousarray(v, dtype=np.float32)
+        _check(lib.edl_set_momentum(self._h, v.ctypes.data_as(_f32p)))
+
+    # -- debugging hooks ---------------------------------------------------
+    def debug_tensors(self):
+        """[(H, W, C, alias_of)] for every activation tensor."""
+        n = C.c_int32()
+        _check(lib.edl_debug_tensor_count(self._h, C.byref(n)))
+        out = []
+        for t in range(n.value):
+            H, W, Cc, al = C.c_int32(), C.c_int32(), C.c_int32(), C.c_int32()
+            _check(lib.edl_debug_tensor_shape(self._h, t, C.byref(H), C.byref(W), C.byref(Cc), C.byref(al)))
+            out.append((H.value, W.value, Cc.value, al.value))
+        return out
+
+    def debug_forward(self, idx):
+        idx = np.ascontiguousarray(idx, dtype=np.int64)
+        _check(lib.edl_debug_forward(self._h, idx.ctypes.data_as(_i64p), len(idx)))
+
+    def debug_backward(self, n, k=0):
+        _check(lib.edl_debug_backward(self._h, n, k))
+
+    def debug_get(self, t, n, which=0):
+        H, W, Cc, _ = self.debug_tensors()[t]
+        out = np.empty((n, H, W, Cc), dtype=np.float32)
+        _check(lib.edl_debug_get_tensor(self._h, t, which, n, out.ctypes.data_as(_f32p)))
+        return out
+
+    def debug_set(self, t, a, which=0):
+        a = np.ascontiguousarray(a, dtype=np.float32)
+        _check(lib.edl_debug_set_tensor(self._h, t, which, a.shape[0], a.ctypes.data_as(_f32p)))
+
+    def debug_op_count(self):
+        n = C.c_int32()
+        _check(lib.edl_debug_op_count(self._h, C.byref(n)))
+        return n.value
+
+    def debug_forward_op(self, op, n):
+        _check(lib.edl_debug_forward_op(self._h, op, n))
+
+    def debug_backward_op(self, op, n, k=0):
+        _check(lib.edl_debug_backward_op(self._h, op, n, k))
+
+    def debug_set_labels(self, labels):
+        labels = np.ascontiguousarray(labels, dtype=np.int32)
+        _check(lib.edl_debug_set_labels(self._h, labels.ctypes.data_as(C.POINTER(C.c_int32)), len(labels)))
 
     def sync(self):
         if self.stream is not None:

@@ -10,6 +10,7 @@
 
 #include "graph.h"
 #include "kernels.h"
+#include "profiler.h"
 
 using namespace edl;
 
@@ -298,17 +299,19 @@ int32_t edl_shard(const edl_handle* h, int64_t B, int32_t p, int64_t epoch, int6
 
 // forward + backward of one worker's shard: n samples whose indices are at
 // dev_idx; gradient into G; mean loss into dev_loss[0]
-static int run_shard(edl_handle* h, const int64_t* dev_idx, int n, float* G, float* dev_loss, bool update_running) {
+// op_lo..op_hi: the slice of the layer list to run (the whole list in normal use;
+// single layers from the debugging hooks, which then skip the gather)
+static void forward_shard(edl_handle* h, const int64_t* dev_idx, int n, float* dev_loss, bool update_running,
+                          size_t op_lo = 0, size_t op_hi = (size_t)-1) {
     const Graph& g = h->g;
     const int dt = h->cfg.dtype;
     hipStream_t st = h->st;
     const bool bf = dt == EDL_DTYPE_BF16;
     float* partial = h->at<float>(h->L.partial);
-    float* coef = h->at<float>(h->L.coef);
     const Tensor& tin = g.tensors[0];
-    launch_gather(dt, h->data_x, h->data_y, dev_idx, n, tin.elems(), h->act(0), h->at<int32_t>(h->L.labels), st);
-    // ---- forward ----
-    for (size_t i = 0; i < g.ops.size(); ++i) {
+    if (dev_idx) launch_gather(dt, h->data_x, h->data_y, dev_idx, n, tin.elems(), h->act(0), h->at<int32_t>(h->L.labels), st);
+    if (op_hi > g.ops.size()) op_hi = g.ops.size();
+    for (size_t i = op_lo; i < op_hi; ++i) {
         const Op& op = g.ops[i];
         switch (op.kind) {
             case OP_CONV: {
@@ -343,9 +346,17 @@ static int run_shard(edl_handle* h, const int64_t* dev_idx, int n, float* G, flo
                 break;
         }
     }
-    // ---- backward ----
+}
+
+static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, size_t op_hi = (size_t)-1) {
+    const Graph& g = h->g;
+    const int dt = h->cfg.dtype;
+    hipStream_t st = h->st;
+    float* partial = h->at<float>(h->L.partial);
+    float* coef = h->at<float>(h->L.coef);
     std::vector<char> written(g.tensors.size(), 0);
-    for (size_t ii = g.ops.size(); ii-- > 0;) {
+    if (op_hi > g.ops.size()) op_hi = g.ops.size();
+    for (size_t ii = op_hi; ii-- > op_lo;) {
         const Op& op = g.ops[ii];
         switch (op.kind) {
             case OP_LOSS:
@@ -405,7 +416,6 @@ static int run_shard(edl_handle* h, const int64_t* dev_idx, int n, float* G, flo
             }
         }
     }
-    return EDL_OK;
 }
 
 static int check_p(const edl_handle* h, int32_t p) {
@@ -450,8 +460,8 @@ int32_t edl_gradients(edl_handle* h, int32_t p, const int64_t* idx, const int64_
     transpose_weights(h);
     float* dev_losses = h->at<float>(h->L.losses);
     for (int k = 0; k < p; ++k) {
-        rc = run_shard(h, dev_idx + (int64_t)k * n, (int)n, h->grad_buf(k), dev_losses + k, k == 0);
-        if (rc) return rc;
+        forward_shard(h, dev_idx + (int64_t)k * n, (int)n, dev_losses + k, k == 0);
+        backward_shard(h, (int)n, h->grad_buf(k));
     }
     HIP_TRY(hipGetLastError());
     if (out_loss) {
@@ -568,6 +578,154 @@ int32_t edl_set_params(edl_handle* h, const float* host_src) {
     return EDL_OK;
 }
 
+// ---------------------------------------------------------------- debugging hooks
+static inline float host_bf16_to_f32(uint16_t v) { uint32_t u = (uint32_t)v << 16; float f; memcpy(&f, &u, 4); return f; }
+static inline uint16_t host_f32_to_bf16(float f) {
+    uint32_t u; memcpy(&u, &f, 4);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+int32_t edl_debug_tensor_count(const edl_handle* h, int32_t* out) {
+    if (!h || !out) { set_error("null argument"); return EDL_EINVAL; }
+    *out = (int32_t)h->g.tensors.size();
+    return EDL_OK;
+}
+
+int32_t edl_debug_tensor_shape(const edl_handle* h, int32_t t, int32_t* H, int32_t* W, int32_t* C, int32_t* alias_of) {
+    if (!h || t < 0 || (size_t)t >= h->g.tensors.size()) { set_error("tensor %d out of range", t); return EDL_ERANGE; }
+    const Tensor& x = h->g.tensors[(size_t)t];
+    if (H) *H = x.H;
+    if (W) *W = x.W;
+    if (C) *C = x.C;
+    if (alias_of) *alias_of = x.alias_of;
+    return EDL_OK;
+}
+
+static int debug_prepare(edl_handle* h, int32_t n) {
+    if (!h) { set_error("null handle"); return EDL_EINVAL; }
+    if (n <= 0 || n > h->cfg.max_shard || n > h->cfg.B) { set_error("n=%d outside [1, max_shard]", n); return EDL_EINVAL; }
+    if (h->weights_dirty) { refresh_weight_copies(h); h->weights_dirty = false; }
+    transpose_weights(h);
+    return EDL_OK;
+}
+
+int32_t edl_debug_forward(edl_handle* h, const int64_t* idx, int32_t n) {
+    int rc = debug_prepare(h, n);
+    if (rc) return rc;
+    if (!idx || !h->data_x) { set_error("idx and a bound data set are needed"); return EDL_EINVAL; }
+    for (int i = 0; i < n; ++i)
+        if (idx[i] < 0 || idx[i] >= h->cfg.N) { set_error("idx[%d] outside [0,N)", i); return EDL_ERANGE; }
+    HIP_TRY(hipStreamSynchronize(h->st));
+    memcpy(h->idx_host[0], idx, sizeof(int64_t) * (size_t)n);
+    HIP_TRY(hipMemcpyAsync(h->at<int64_t>(h->L.idx), h->idx_host[0], sizeof(int64_t) * (size_t)n, hipMemcpyHostToDevice, h->st));
+    forward_shard(h, h->at<int64_t>(h->L.idx), n, h->at<float>(h->L.losses), false);
+    HIP_TRY(hipStreamSynchronize(h->st));
+    HIP_TRY(hipGetLastError());
+    return EDL_OK;
+}
+
+int32_t edl_debug_backward(edl_handle* h, int32_t n, int32_t k) {
+    int rc = debug_prepare(h, n);
+    if (rc) return rc;
+    if (k < 0 || k >= h->cfg.p_max) { set_error("gradient buffer %d outside [0,p_max)", k); return EDL_EINVAL; }
+    const Graph& g = h->g;
+    launch_softmax_ce(h->cfg.dtype, (const float*)h->act(g.logits), h->at<int32_t>(h->L.labels), h->grad(g.logits),
+                      h->at<float>(h->L.row_loss), h->at<float>(h->L.losses), n, g.classes, h->st);
+    backward_shard(h, n, h->grad_buf(k));
+    HIP_TRY(hipStreamSynchronize(h->st));
+    HIP_TRY(hipGetLastError());
+    return EDL_OK;
+}
+
+int32_t edl_debug_op_count(const edl_handle* h, int32_t* out) {
+    if (!h || !out) { set_error("null argument"); return EDL_EINVAL; }
+    *out = (int32_t)h->g.ops.size();
+    return EDL_OK;
+}
+
+int32_t edl_debug_forward_op(edl_handle* h, int32_t op, int32_t n) {
+    int rc = debug_prepare(h, n);
+    if (rc) return rc;
+    if (op < 0 || (size_t)op >= h->g.ops.size()) { set_error("layer %d out of range", op); return EDL_ERANGE; }
+    forward_shard(h, nullptr, n, h->at<float>(h->L.losses), false, (size_t)op, (size_t)op + 1);
+    HIP_TRY(hipStreamSynchronize(h->st));
+    HIP_TRY(hipGetLastError());
+    return EDL_OK;
+}
+
+int32_t edl_debug_backward_op(edl_handle* h, int32_t op, int32_t n, int32_t k) {
+    int rc = debug_prepare(h, n);
+    if (rc) return rc;
+    if (op < 0 || (size_t)op >= h->g.ops.size()) { set_error("layer %d out of range", op); return EDL_ERANGE; }
+    if (k < 0 || k >= h->cfg.p_max) { set_error("gradient buffer %d outside [0,p_max)", k); return EDL_EINVAL; }
+    backward_shard(h, n, h->grad_buf(k), (size_t)op, (size_t)op + 1);
+    HIP_TRY(hipStreamSynchronize(h->st));
+    HIP_TRY(hipGetLastError());
+    return EDL_OK;
+}
+
+int32_t edl_debug_set_labels(edl_handle* h, const int32_t* labels, int32_t n) {
+    if (!h || !labels || n <= 0 || n > h->cfg.max_shard) { set_error("bad argument"); return EDL_EINVAL; }
+    HIP_TRY(hipMemcpyAsync(h->at<int32_t>(h->L.labels), labels, sizeof(int32_t) * (size_t)n, hipMemcpyHostToDevice, h->st));
+    HIP_TRY(hipStreamSynchronize(h->st));
+    return EDL_OK;
+}
+
+static int debug_tensor_ptr(edl_handle* h, int32_t t, int32_t which, int32_t n, char** ptr, int64_t* elems, bool* is_f32) {
+    if (!h) { set_error("null handle"); return EDL_EINVAL; }
+    if (t < 0 || (size_t)t >= h->g.tensors.size()) { set_error("tensor %d out of range", t); return EDL_ERANGE; }
+    if (n <= 0 || n > h->cfg.max_shard) { set_error("n=%d outside [1, max_shard]", n); return EDL_EINVAL; }
+    const int s = storage_of(h->g, t);
+    if (which == 1 && s == 0) { set_error("the input image has no gradient buffer"); return EDL_EINVAL; }
+    *ptr = which == 0 ? (char*)h->act(t) : (char*)h->grad(t);
+    *elems = h->g.tensors[(size_t)t].elems() * n;
+    *is_f32 = h->cfg.dtype == EDL_DTYPE_F32 || (which == 0 && h->g.tensors[(size_t)s].fp32);
+    return EDL_OK;
+}
+
+int32_t edl_debug_get_tensor(edl_handle* h, int32_t t, int32_t which, int32_t n, float* host_dst) {
+    char* ptr; int64_t elems; bool f32;
+    const int rc = debug_tensor_ptr(h, t, which, n, &ptr, &elems, &f32);
+    if (rc) return rc;
+    if (!host_dst) { set_error("null argument"); return EDL_EINVAL; }
+    if (f32) {
+        HIP_TRY(hipMemcpyAsync(host_dst, ptr, 4 * (size_t)elems, hipMemcpyDeviceToHost, h->st));
+        HIP_TRY(hipStreamSynchronize(h->st));
+    } else {
+        std::vector<uint16_t> tmp((size_t)elems);
+        HIP_TRY(hipMemcpyAsync(tmp.data(), ptr, 2 * (size_t)elems, hipMemcpyDeviceToHost, h->st));
+        HIP_TRY(hipStreamSynchronize(h->st));
+        for (int64_t i = 0; i < elems; ++i) host_dst[i] = host_bf16_to_f32(tmp[(size_t)i]);
+    }
+    return EDL_OK;
+}
+
+int32_t edl_debug_set_tensor(edl_handle* h, int32_t t, int32_t which, int32_t n, const float* host_src) {
+    char* ptr; int64_t elems; bool f32;
+    const int rc = debug_tensor_ptr(h, t, which, n, &ptr, &elems, &f32);
+    if (rc) return rc;
+    if (!host_src) { set_error("null argument"); return EDL_EINVAL; }
+    if (f32) {
+        HIP_TRY(hipMemcpyAsync(ptr, host_src, 4 * (size_t)elems, hipMemcpyHostToDevice, h->st));
+        HIP_TRY(hipStreamSynchronize(h->st));
+    } else {
+        std::vector<uint16_t> tmp((size_t)elems);
+        for (int64_t i = 0; i < elems; ++i) tmp[(size_t)i] = host_f32_to_bf16(host_src[i]);
+        HIP_TRY(hipMemcpyAsync(ptr, tmp.data(), 2 * (size_t)elems, hipMemcpyHostToDevice, h->st));
+        HIP_TRY(hipStreamSynchronize(h->st));
+    }
+    return EDL_OK;
+}
+
+int32_t edl_set_momentum(edl_handle* h, const float* host_src) {
+    if (!h || !host_src) { set_error("null argument"); return EDL_EINVAL; }
+    HIP_TRY(hipMemcpyAsync(h->v(), host_src, sizeof(float) * (size_t)h->g.P, hipMemcpyHostToDevice, h->st));
+    HIP_TRY(hipStreamSynchronize(h->st));
+    return EDL_OK;
+}
+
 int32_t edl_shutdown(edl_handle* h) {
     if (!h) { set_error("null handle"); return EDL_EINVAL; }
     (void)hipStreamSynchronize(h->st);
@@ -577,6 +735,19 @@ int32_t edl_shutdown(edl_handle* h) {
     }
     if (h->loss_host) (void)hipHostFree(h->loss_host);
     delete h;
+    return EDL_OK;
+}
+
+int32_t edl_profile(int32_t enable) {
+    prof_enable(enable != 0);
+    return EDL_OK;
+}
+
+int32_t edl_profile_report(char* buf, size_t cap, size_t* out_needed) {
+    const long n = prof_report(buf, cap);
+    if (n < 0) { set_error("reading the timing events failed"); return EDL_EHIP; }
+    if (out_needed) *out_needed = (size_t)n + 1;
+    if ((size_t)n + 1 > cap) { set_error("report needs %ld bytes", n + 1); return EDL_ENOMEM; }
     return EDL_OK;
 }
 

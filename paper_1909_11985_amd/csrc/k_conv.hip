@@ -23,6 +23,7 @@
 // float32 partial tiles are added by a second kernel in split order.
 #include "dev_common.h"
 #include "kernels.h"
+#include "profiler.h"
 
 namespace edl {
 
@@ -388,8 +389,27 @@ static void launch_cfg(TileCfg t, dim3 grid, const ConvArgs& a, hipStream_t st) 
     }
 }
 
+static const char* conv_label(int dtype, int mode, TileCfg t) {
+    static const char* names[2][3][4] = {
+        {{"conv_fwd_f32_128x128", "conv_fwd_f32_128x64", "conv_fwd_f32_128x32", "conv_fwd_f32_64x64"},
+         {"conv_dgrad_f32_128x128", "conv_dgrad_f32_128x64", "conv_dgrad_f32_128x32", "conv_dgrad_f32_64x64"},
+         {"conv_wgrad_f32_128x128", "conv_wgrad_f32_128x64", "conv_wgrad_f32_128x32", "conv_wgrad_f32_64x64"}},
+        {{"conv_fwd_bf16_128x128", "conv_fwd_bf16_128x64", "conv_fwd_bf16_128x32", "conv_fwd_bf16_64x64"},
+         {"conv_dgrad_bf16_128x128", "conv_dgrad_bf16_128x64", "conv_dgrad_bf16_128x32", "conv_dgrad_bf16_64x64"},
+         {"conv_wgrad_bf16_128x128", "conv_wgrad_bf16_128x64", "conv_wgrad_bf16_128x32", "conv_wgrad_bf16_64x64"}}};
+    return names[dtype == 1 ? 1 : 0][mode][(int)t];
+}
+
 template <int MODE>
 static void launch_mode(int dtype, TileCfg t, dim3 grid, const ConvArgs& a, hipStream_t st) {
+    // algorithmic work: 2*M*N*K flops; operands and result touched once
+    const double esz = dtype == 1 ? 2.0 : 4.0;
+    const double flops = 2.0 * (double)a.M * a.Nn * a.Kred;
+    double bytes;
+    if (MODE == CONV_FWD) bytes = esz * ((double)a.N * a.H * a.W * a.C + (double)a.Nn * a.Kred) + (a.out_fp32 ? 4.0 : esz) * (double)a.M * a.Nn;
+    else if (MODE == CONV_DGRAD) bytes = esz * ((double)a.N * a.Ho * a.Wo * a.K + (double)a.Nn * a.Kred + (double)a.M * a.Nn);
+    else bytes = esz * ((double)a.Kred * a.K + (double)a.N * a.H * a.W * a.C) + 4.0 * (double)a.M * a.Nn;
+    ProfScope ps(conv_label(dtype, MODE, t), flops, bytes, st);
     if (dtype == 1) launch_cfg<bf16_t, MODE>(t, grid, a, st);
     else launch_cfg<float, MODE>(t, grid, a, st);
 }
@@ -488,6 +508,7 @@ void launch_conv_wgrad(int dtype, const ConvGeom& g, const void* x, const void* 
     if (!direct) {
         int64_t blocks = (n + 255) / 256;
         if (blocks > 4096) blocks = 4096;
+        ProfScope ps("wgrad_reduce", 0.0, 4.0 * (double)n * (p.splits + 1), st);
         hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((int)blocks), dim3(256), 0, st, scratch, dw, n, p.splits);
     }
 }

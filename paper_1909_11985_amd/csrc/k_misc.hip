@@ -1,6 +1,7 @@
 // Pooling and the softmax cross-entropy loss.  All HBM- or latency-bound.
 #include "dev_common.h"
 #include "kernels.h"
+#include "profiler.h"
 
 namespace edl {
 
@@ -83,6 +84,8 @@ __global__ __launch_bounds__(256) void maxpool_bwd_kernel(const T* __restrict__ 
 void launch_maxpool_forward(int dtype, const void* x, void* y, uint8_t* arg, int N, int H, int W, int C, int k,
                             int stride, int pad, int Ho, int Wo, hipStream_t st) {
     const int grid = ew_grid((int64_t)N * Ho * Wo * C);
+    const double esz = dtype == 1 ? 2.0 : 4.0;
+    ProfScope ps("maxpool_fwd", 0.0, esz * (double)N * H * W * C + (esz + 1.0) * (double)N * Ho * Wo * C, st);
     if (dtype == 1)
         hipLaunchKernelGGL(maxpool_fwd_kernel<bf16_t>, dim3(grid), dim3(256), 0, st, (const bf16_t*)x, (bf16_t*)y, arg, N,
                            H, W, C, k, stride, pad, Ho, Wo);
@@ -94,6 +97,8 @@ void launch_maxpool_forward(int dtype, const void* x, void* y, uint8_t* arg, int
 void launch_maxpool_backward(int dtype, const void* dy, const uint8_t* arg, void* dx, bool accumulate, int N, int H,
                              int W, int C, int k, int stride, int pad, int Ho, int Wo, hipStream_t st) {
     const int grid = ew_grid((int64_t)N * H * W * C);
+    const double esz = dtype == 1 ? 2.0 : 4.0;
+    ProfScope ps("maxpool_bwd", 0.0, esz * (double)N * H * W * C * (accumulate ? 2.0 : 1.0) + (esz + 1.0) * (double)N * Ho * Wo * C, st);
     if (dtype == 1)
         hipLaunchKernelGGL(maxpool_bwd_kernel<bf16_t>, dim3(grid), dim3(256), 0, st, (const bf16_t*)dy, arg, (bf16_t*)dx,
                            accumulate ? 1 : 0, N, H, W, C, k, stride, pad, Ho, Wo);
@@ -132,6 +137,7 @@ __global__ __launch_bounds__(256) void gavgpool_bwd_kernel(const T* __restrict__
 
 void launch_gavgpool_forward(int dtype, const void* x, void* y, int N, int HW, int C, hipStream_t st) {
     const int grid = ew_grid((int64_t)N * C);
+    ProfScope ps("gavgpool_fwd", 0.0, (dtype == 1 ? 2.0 : 4.0) * (double)N * (HW + 1) * C, st);
     if (dtype == 1)
         hipLaunchKernelGGL(gavgpool_fwd_kernel<bf16_t>, dim3(grid), dim3(256), 0, st, (const bf16_t*)x, (bf16_t*)y, N, HW, C);
     else
@@ -141,6 +147,7 @@ void launch_gavgpool_forward(int dtype, const void* x, void* y, int N, int HW, i
 void launch_gavgpool_backward(int dtype, const void* dy, void* dx, bool accumulate, int N, int HW, int C,
                               hipStream_t st) {
     const int grid = ew_grid((int64_t)N * HW * C);
+    ProfScope ps("gavgpool_bwd", 0.0, (dtype == 1 ? 2.0 : 4.0) * (double)N * (HW + 1) * C, st);
     if (dtype == 1)
         hipLaunchKernelGGL(gavgpool_bwd_kernel<bf16_t>, dim3(grid), dim3(256), 0, st, (const bf16_t*)dy, (bf16_t*)dx,
                            accumulate ? 1 : 0, N, HW, C);
@@ -198,6 +205,7 @@ __global__ void loss_mean_kernel(const float* __restrict__ row_loss, int n, floa
 
 void launch_softmax_ce(int dtype, const float* logits, const int32_t* labels, void* dlogits, float* row_loss,
                        float* loss_out, int n, int C, hipStream_t st) {
+    ProfScope ps("softmax_ce", 0.0, (4.0 + (dtype == 1 ? 2.0 : 4.0)) * (double)n * C, st);
     if (dtype == 1)
         hipLaunchKernelGGL(softmax_ce_kernel<bf16_t>, dim3(n), dim3(256), 0, st, logits, labels, (bf16_t*)dlogits, row_loss, n, C);
     else

@@ -9,6 +9,7 @@
 // adds the row blocks in float64.
 #include "dev_common.h"
 #include "kernels.h"
+#include "profiler.h"
 
 namespace edl {
 
@@ -268,10 +269,15 @@ template <typename T, int VEC>
 static void bn_forward_t(const void* x, const void* res, void* y, const float* gamma, const float* beta,
                          float* save, float* running, int64_t M, int C, bool relu, float* partial, hipStream_t st) {
     const RedShape s = red_shape(M, C, VEC);
+    const double tb = (double)sizeof(T) * (double)M * C;   // bytes of one [M][C] tensor
+    {
+    ProfScope ps("bn_stats", 0.0, tb, st);
     hipLaunchKernelGGL((colreduce_kernel<T, VEC, 0>), s.grid, s.block, 0, st, (const T*)x, (const T*)nullptr, (T*)nullptr,
                        (const float*)nullptr, M, C, s.rows_per_block, 0, partial);
+    }
     hipLaunchKernelGGL(bn_stats_finalize_kernel, dim3((C + 127) / 128), dim3(128), 0, st, partial, s.row_blocks, M, C,
                        save, running);
+    ProfScope ps("bn_apply", 0.0, tb * (res ? 3.0 : 2.0), st);
     hipLaunchKernelGGL((bn_apply_kernel<T, VEC>), dim3(ew_grid(M * s.cvecs)), dim3(256), 0, st, (const T*)x,
                        (const T*)res, (T*)y, gamma, beta, save, M, C, s.cvecs, relu ? 1 : 0);
 }
@@ -292,10 +298,15 @@ static void bn_backward_t(const void* x, const void* y, const void* dy, void* dx
                           const float* gamma, const float* save, float* dgamma, float* dbeta, int64_t M, int C,
                           bool relu, float* partial, float* coef, hipStream_t st) {
     const RedShape s = red_shape(M, C, VEC);
+    const double tb = (double)sizeof(T) * (double)M * C;
+    {
+    ProfScope ps("bn_bwd_reduce", 0.0, tb * (relu ? 3.0 : 2.0), st);
     hipLaunchKernelGGL((colreduce_kernel<T, VEC, 1>), s.grid, s.block, 0, st, (const T*)x, (const T*)y, (T*)dy, save, M, C,
                        s.rows_per_block, relu ? 1 : 0, partial);
+    }
     hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3((C + 127) / 128), dim3(128), 0, st, partial, s.row_blocks, M, C,
                        dgamma, dbeta, coef);
+    ProfScope ps("bn_bwd_apply", 0.0, tb * ((relu ? 3.0 : 2.0) + 1.0 + (dres ? (dres_acc ? 2.0 : 1.0) : 0.0)), st);
     hipLaunchKernelGGL((bn_bwd_apply_kernel<T, VEC>), dim3(ew_grid(M * s.cvecs)), dim3(256), 0, st, (const T*)x,
                        (const T*)y, (const T*)dy, (T*)dx, (T*)dres, dres_acc ? 1 : 0, gamma, save, coef, M, C, s.cvecs,
                        relu ? 1 : 0);
@@ -317,6 +328,8 @@ template <typename T, int VEC>
 static void bias_relu_backward_t(const void* y, void* dy, float* dbias, int64_t M, int C, bool relu, float* partial,
                                  hipStream_t st) {
     const RedShape s = red_shape(M, C, VEC);
+    const double tb = (double)sizeof(T) * (double)M * C;
+    ProfScope ps("bias_relu_bwd", 0.0, tb * (relu ? 3.0 : 1.0), st);
     hipLaunchKernelGGL((colreduce_kernel<T, VEC, 2>), s.grid, s.block, 0, st, (const T*)nullptr, (const T*)y, (T*)dy,
                        (const float*)nullptr, M, C, s.rows_per_block, relu ? 1 : 0, partial);
     if (dbias)

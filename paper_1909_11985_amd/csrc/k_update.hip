@@ -4,6 +4,7 @@
 // sample gather that stands for the prefetch pipeline (section 4.4).
 #include "dev_common.h"
 #include "kernels.h"
+#include "profiler.h"
 
 namespace edl {
 
@@ -76,6 +77,8 @@ void launch_average_update(int p, const GradPtrs& grads, float* w, float* v, uin
                            float momentum, float wd, hipStream_t st) {
     const int64_t nvec = P / 4;
     const int grid = grid_for(nvec, 256, 256 * 16);
+    // p gradient reads + w, v read and written (+ the bf16 copy)
+    ProfScope ps("average_update", 0.0, (4.0 * p + 16.0 + (w16 ? 2.0 : 0.0)) * (double)P, st);
 #define EDL_UPD(NP)                                                                                             \
     do {                                                                                                        \
         if (w16) hipLaunchKernelGGL((average_update_kernel<NP, true>), dim3(grid), dim3(256), 0, st, grads, p, w, v,  \
@@ -105,6 +108,7 @@ __global__ __launch_bounds__(256) void copy_kernel(U* __restrict__ dst, const U*
 
 void launch_copy(void* dst, const void* src, size_t bytes, hipStream_t st) {
     if (bytes == 0) return;
+    ProfScope ps("copy", 0.0, 2.0 * (double)bytes, st);
     const uintptr_t bits = (uintptr_t)dst | (uintptr_t)src | (uintptr_t)bytes;
     if ((bits & 15) == 0) {
         const int64_t n = (int64_t)(bytes / 16);
@@ -164,6 +168,7 @@ __global__ __launch_bounds__(256) void weight_transpose_kernel(const float* __re
 
 void launch_weight_transpose(int dtype, const float* src, void* dst, int K, int RS, int C, hipStream_t st) {
     dim3 grid((C + 31) / 32, (K + 31) / 32, RS);
+    ProfScope ps("weight_transpose", 0.0, (4.0 + (dtype == 1 ? 2.0 : 4.0)) * (double)K * RS * C, st);
     if (dtype == 1)
         hipLaunchKernelGGL(weight_transpose_kernel<bf16_t>, grid, dim3(256), 0, st, src, (bf16_t*)dst, K, RS, C);
     else
@@ -201,6 +206,7 @@ __global__ __launch_bounds__(256) void gather_kernel(const float* __restrict__ d
 void launch_gather(int dtype, const float* data_x, const int32_t* data_y, const int64_t* idx, int n,
                    int64_t sample_elems, void* out_x, int32_t* out_y, hipStream_t st) {
     dim3 grid(grid_for(sample_elems / 4 + 1, 256, 64), n);
+    ProfScope ps("gather", 0.0, (4.0 + (dtype == 1 ? 2.0 : 4.0)) * (double)sample_elems * n, st);
     if (dtype == 1)
         hipLaunchKernelGGL(gather_kernel<bf16_t>, grid, dim3(256), 0, st, data_x, data_y, idx, sample_elems,
                            (bf16_t*)out_x, out_y);

@@ -104,7 +104,166 @@ def run_parity(model, dtype, N, B, schedule, seed=0, data_seed=1, lr=0.1, moment
             if verbose:
                 print("  step %d: loss gpu %.6f oracle %.6f | param worst %.3e (%s) whole %.3e" %
                       (t, loss, lo, e, name, whole), flush=True)
+        elif verbose:
+            print("  step %d p=%d: loss gpu %.6f oracle %.6f" % (t, p, loss, lo), flush=True)
         res["loss"] = max(res["loss"], abs(loss - lo) / max(abs(lo), 1e-30))
         assert np.isfinite(loss)
     res["job"], res["oracle"], res["table"] = job, orc, table
+    return res
+
+
+def forced_parity(model, dtype, n, N=None, seed=0, data_seed=1, H=0, W=0, C=0, classes=0, arch=(), emulate=None,
+                  perturb=0.05, verbose=True):
+    """One worker's whole backward pass with the decisions pinned: every layer's
+    forward is run on the oracle's inputs (which also refreshes the batch
+    statistics and arg-max positions the layer keeps), its output is then
+    replaced by the oracle's, and finally the HIP backward runs through the
+    whole layer list in one go.  Its flat gradient is compared with the oracle's.
+    Returns dict(fwd=worst layer-output error, loss=..., grad=worst per-tensor, grad_whole=...)."""
+    import torch
+    import paper_1909_11985_amd as E
+    from paper_1909_11985_amd.binding import make_config
+
+    N = N or n
+    dH, dW, dC, dK = DEFAULT_HWC[model]
+    hh, ww, cc, kk = H or dH, W or dW, C or dC, classes or dK
+    x, y = synth_inputs.dataset(data_seed, N, hh, ww, cc, kk)
+    cfg = make_config(model, dtype=dtype, N=N, B=n, p_max=1, max_shard=n, H=H, W=W, C_=C, classes=classes, arch=arch)
+    job = E.Job(cfg, seed)
+    job.bind_dataset(torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda())
+    if emulate is None:
+        emulate = dtype == "bf16"
+    orc = O.Oracle(model, seed, N, n, emulate_bf16=emulate, graph_kwargs=oracle_kwargs(model, H, W, C, classes, arch))
+    table = E.edl_tensor_table(cfg)
+    if perturb:
+        rng = np.random.default_rng(seed + 100)
+        orc.w = (orc.w + perturb * rng.standard_normal(orc.w.size) * (np.abs(orc.w) + 0.1)).astype(np.float32).astype(np.float64)
+        job.set_params(orc.w)
+    idx = np.arange(n, dtype=np.int64)
+    loss_o, G = orc.forward_backward(x[idx].astype(np.float64), y[idx])
+    job.debug_forward(idx)
+    tensors = job.debug_tensors()
+
+    def tid(name):
+        return 0 if name == "x" else int(name[1:])
+
+    def shaped(name):
+        th, tw, tc, _ = tensors[tid(name)]
+        return orc.last_act[name].reshape(n, th, tw, tc)
+
+    ops = [op for op in orc.graph.ops if op["kind"] != "flatten"]
+    fwd, fwd_name, loss_g = 0.0, "", None
+    for gi, op in enumerate(ops):
+        job.debug_set(tid(op["x"]), shaped(op["x"]))
+        job.debug_forward_op(gi, n)
+        if op["kind"] == "loss":
+            loss_g = float(job.losses(1)[0])
+            continue
+        e = relerr(job.debug_get(tid(op["y"]), n), shaped(op["y"]))
+        if e > fwd:
+            fwd, fwd_name = e, op.get("name", op["kind"])
+        job.debug_set(tid(op["y"]), shaped(op["y"]))
+    job.debug_backward(n, 0)
+    g = job.grad(0)
+    worst, worst_name, whole = per_tensor_relerr(table, g, G)
+    res = dict(fwd=fwd, fwd_name=fwd_name, loss=abs(loss_g - loss_o) / abs(loss_o), grad=worst, grad_name=worst_name,
+               grad_whole=whole)
+    if verbose:
+        print("  %s %s n=%d: layer outputs worst %.3e (%s) loss %.3e | pinned backward grad worst %.3e (%s) whole %.3e"
+              % (model, dtype, n, fwd, fwd_name, res["loss"], worst, worst_name, whole), flush=True)
+    job.shutdown()
+    return res
+
+
+def layerwise_parity(model, dtype, n, N=None, seed=0, data_seed=1, H=0, W=0, C=0, classes=0, arch=(), emulate=None,
+                     perturb=0.05, verbose=True):
+    """Every layer of the model on its own, at the shapes it has inside the
+    network: the layer's inputs (and, for the backward, its output and the
+    gradient of its output) are the oracle's tensors written into the HIP
+    buffers, so each HIP kernel is compared with the oracle's layer on equal
+    inputs and no error of an earlier layer is carried along.
+    Returns dict(fwd=worst output error, dx=worst input-gradient error, dw=worst parameter-gradient error)."""
+    import torch
+    import paper_1909_11985_amd as E
+    from paper_1909_11985_amd.binding import make_config
+
+    N = N or n
+    dH, dW, dC, dK = DEFAULT_HWC[model]
+    hh, ww, cc, kk = H or dH, W or dW, C or dC, classes or dK
+    x, y = synth_inputs.dataset(data_seed, N, hh, ww, cc, kk)
+    cfg = make_config(model, dtype=dtype, N=N, B=n, p_max=1, max_shard=n, H=H, W=W, C_=C, classes=classes, arch=arch)
+    job = E.Job(cfg, seed)
+    job.bind_dataset(torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda())
+    if emulate is None:
+        emulate = dtype == "bf16"
+    orc = O.Oracle(model, seed, N, n, emulate_bf16=emulate, graph_kwargs=oracle_kwargs(model, H, W, C, classes, arch))
+    if perturb:
+        rng = np.random.default_rng(seed + 100)
+        orc.w = (orc.w + perturb * rng.standard_normal(orc.w.size) * (np.abs(orc.w) + 0.1)).astype(np.float32).astype(np.float64)
+        job.set_params(orc.w)
+    idx = np.arange(n, dtype=np.int64)
+    loss_o, G = orc.forward_backward(x[idx].astype(np.float64), y[idx])
+    job.debug_forward(idx)                     # gathers the input batch and the labels
+    tensors = job.debug_tensors()
+
+    def tid(name):
+        return 0 if name == "x" else int(name[1:])
+
+    def shaped(name, a):
+        th, tw, tc, _ = tensors[tid(name)]
+        return np.asarray(a).reshape(n, th, tw, tc)
+
+    ops = [(oi, op) for oi, op in enumerate(orc.graph.ops) if op["kind"] != "flatten"]
+    assert len(ops) == job.debug_op_count()
+    res = dict(fwd=0.0, dx=0.0, dw=0.0, worst="")
+
+    def note(key, e, what):
+        if e > res[key]:
+            res[key] = e
+            res["worst_" + key] = what
+
+    for gi, (oi, op) in enumerate(ops):
+        kind = op["kind"]
+        label = op.get("name", kind)
+        job.debug_set(tid(op["x"]), shaped(op["x"], orc.last_act[op["x"]]))
+        if kind == "bn" and op["res"] is not None:
+            job.debug_set(tid(op["res"]), shaped(op["res"], orc.last_act[op["res"]]))
+        job.debug_forward_op(gi, n)
+        if kind == "loss":
+            note("fwd", abs(float(job.losses(1)[0]) - loss_o) / abs(loss_o), "loss")
+            dz = job.debug_get(tid(op["x"]), n, which=1)
+            note("dx", relerr(dz, shaped(op["x"], orc.last_dx[oi][op["x"]])), "loss")
+            continue
+        out = job.debug_get(tid(op["y"]), n)
+        e_f = relerr(out, shaped(op["y"], orc.last_act[op["y"]]))
+        note("fwd", e_f, label)
+        # backward: decisions (ReLU sign) from the oracle's output, upstream gradient from the oracle
+        job.debug_set(tid(op["y"]), shaped(op["y"], orc.last_act[op["y"]]))
+        job.debug_set(tid(op["y"]), shaped(op["y"], orc.last_dy[oi]), which=1)
+        job.debug_backward_op(gi, n, 0)
+        e_x = 0.0
+        for name, contrib in orc.last_dx.get(oi, {}).items():
+            if tid(name) == 0 or tensors[tid(name)][3] == 0:
+                continue                      # the input batch has no gradient buffer
+            got = job.debug_get(tid(name), n, which=1)
+            e_x = max(e_x, relerr(got, shaped(name, contrib)))
+        note("dx", e_x, label)
+        e_w = 0.0
+        if kind == "conv":
+            wsize = op["K"] * op["R"] * op["S"] * orc.last_act[op["x"]].shape[-1]
+            e_w = relerr(job.grad_slice(0, op["w_off"], wsize), G[op["w_off"]:op["w_off"] + wsize])
+            if op["b_off"] is not None:
+                e_w = max(e_w, relerr(job.grad_slice(0, op["b_off"], op["K"]), G[op["b_off"]:op["b_off"] + op["K"]]))
+        elif kind == "bn":
+            cch = op["C"]
+            e_w = max(relerr(job.grad_slice(0, op["g_off"], cch), G[op["g_off"]:op["g_off"] + cch]),
+                      relerr(job.grad_slice(0, op["b_off"], cch), G[op["b_off"]:op["b_off"] + cch]))
+        note("dw", e_w, label)
+        if verbose:
+            print("    %-16s %-8s fwd %.2e  dx %.2e  dw %.2e" % (label, kind, e_f, e_x, e_w), flush=True)
+    if verbose:
+        print("  %s %s n=%d layerwise: fwd %.3e (%s) dx %.3e (%s) dw %.3e (%s)" %
+              (model, dtype, n, res["fwd"], res.get("worst_fwd"), res["dx"], res.get("worst_dx"), res["dw"],
+               res.get("worst_dw")), flush=True)
+    job.shutdown()
     return res
