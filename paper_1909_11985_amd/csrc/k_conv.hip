@@ -40,7 +40,23 @@ struct ConvArgs {
     int relu, out_fp32, accumulate;
     int vecA, vecB;
     int ksplit;  // reduction elements per blockIdx.z
+    unsigned bytesA, bytesB;  // extents of the two operands (for the range-checked vector loads)
 };
+
+// 16-byte load through a buffer descriptor: an offset at or beyond the
+// descriptor's extent returns zeros, so padding taps, ragged tile edges and
+// the tail of the reduction need no branch and every load of a tile can be in
+// flight at once.
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+constexpr unsigned kOutOfRange = 0x80000000u;   // operands are smaller than 2 GiB (checked by the launchers)
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
+}
+__device__ __forceinline__ uint4 buffer_load16(__amdgpu_buffer_rsrc_t r, unsigned byte_offset) {
+    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, byte_offset, 0, 0);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
 
 template <typename T> struct Frag;
 template <> struct Frag<bf16_t> {
@@ -64,7 +80,7 @@ struct RowCtx {
     bool valid;
 };
 
-template <typename T, int MODE>
+template <int MODE>
 __device__ __forceinline__ RowCtx make_row(const ConvArgs& a, int m) {
     RowCtx c;
     c.valid = m < a.M;
@@ -86,43 +102,104 @@ __device__ __forceinline__ RowCtx make_row(const ConvArgs& a, int m) {
     return c;
 }
 
-// element offset of A[m][kk] for forward / dgrad; ok = inside the image
+// Element offset of A[m][.] at kernel tap (r,s), channel ch, for forward /
+// dgrad; ok = the tap falls inside the image (and, for dgrad, on the stride grid).
 template <int MODE>
-__device__ __forceinline__ int64_t a_offset(const ConvArgs& a, const RowCtx& c, int kk, bool& ok) {
+__device__ __forceinline__ int64_t a_offset_tap(const ConvArgs& a, const RowCtx& c, int r, int s, int ch, bool& ok) {
     if (MODE == CONV_FWD) {
-        const int tap = kk / a.C, ch = kk - tap * a.C;
-        const int r = tap / a.S, s = tap - r * a.S;
         const int h = c.h0 + r, w = c.w0 + s;
-        ok = c.valid && kk < a.Kred && (unsigned)h < (unsigned)a.H && (unsigned)w < (unsigned)a.W;
+        ok = c.valid && (unsigned)h < (unsigned)a.H && (unsigned)w < (unsigned)a.W;
         return c.base + ((int64_t)r * a.W + s) * a.C + ch;
     } else {
-        const int tap = kk / a.K, k = kk - tap * a.K;
-        const int r = tap / a.S, s = tap - r * a.S;
         const int hn = c.h0 - r, wn = c.w0 - s;
         int ho = hn, wo = wn;
         bool on_grid = true;
-        if (a.stride != 1) {
+        if (a.stride == 2) {
+            ho = hn >> 1;
+            wo = wn >> 1;
+            on_grid = ((hn | wn) & 1) == 0;
+        } else if (a.stride != 1) {
             ho = hn / a.stride;
             wo = wn / a.stride;
             on_grid = (ho * a.stride == hn) && (wo * a.stride == wn);
         }
-        ok = c.valid && kk < a.Kred && hn >= 0 && wn >= 0 && on_grid && ho < a.Ho && wo < a.Wo;
-        return c.base + ((int64_t)ho * a.Wo + wo) * a.K + k;
+        ok = c.valid && hn >= 0 && wn >= 0 && on_grid && ho < a.Ho && wo < a.Wo;
+        return c.base + ((int64_t)ho * a.Wo + wo) * a.K + ch;
     }
 }
 
-template <typename T, int MODE, int WM, int WN, int TM, int TN>
+// the same from a flat reduction index (used by the element-wise path only)
+template <int MODE>
+__device__ __forceinline__ int64_t a_offset(const ConvArgs& a, const RowCtx& c, int kk, bool& ok) {
+    const int inner = MODE == CONV_FWD ? a.C : a.K;
+    const int tap = kk / inner, ch = kk - tap * inner;
+    const int r = tap / a.S, s = tap - r * a.S;
+    const int64_t off = a_offset_tap<MODE>(a, c, r, s, ch, ok);
+    ok = ok && kk < a.Kred;
+    return off;
+}
+
+// Vector-path byte offset for forward / dgrad in 32-bit arithmetic (operands
+// are below 2 GiB there); tap_off is (r*W + s)*C + ch for the forward pass.
+template <int MODE, typename T>
+__device__ __forceinline__ unsigned a_voffset(const ConvArgs& a, const RowCtx& c, int r, int s, int ch, int tap_off, bool in_k) {
+    if (MODE == CONV_FWD) {
+        const int h = c.h0 + r, w = c.w0 + s;
+        const bool ok = in_k && c.valid && (unsigned)h < (unsigned)a.H && (unsigned)w < (unsigned)a.W;
+        return ok ? (unsigned)((int)c.base + tap_off) * (unsigned)sizeof(T) : kOutOfRange;
+    } else {
+        const int hn = c.h0 - r, wn = c.w0 - s;
+        int ho = hn, wo = wn;
+        bool on_grid = true;
+        if (a.stride == 2) {
+            ho = hn >> 1;
+            wo = wn >> 1;
+            on_grid = ((hn | wn) & 1) == 0;
+        } else if (a.stride != 1) {
+            ho = hn / a.stride;
+            wo = wn / a.stride;
+            on_grid = (ho * a.stride == hn) && (wo * a.stride == wn);
+        }
+        const bool ok = in_k && c.valid && (hn | wn) >= 0 && on_grid && ho < a.Ho && wo < a.Wo;
+        return ok ? (unsigned)((int)c.base + (ho * a.Wo + wo) * a.K + ch) * (unsigned)sizeof(T) : kOutOfRange;
+    }
+}
+
+// Tile storage in LDS
+//   forward / dgrad: rows of BK reduction elements, padded by one 16-byte vector; a fragment is one
+//                    16-byte read (row = lane%32, slice = lane/32).
+//   wgrad:           32-bit words [reduction word][row], a word holding the reduction elements 2q, 2q+1
+//                    of one row for bf16 (one element for float32); a fragment is four one-word reads,
+//                    and the global vectors (channels innermost) go in without any 16-bit scatter.
+template <typename T, int MODE, int WM, int WN, int TM, int TN, int BK>
 __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
-    constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BK = 32;
+    constexpr bool WG = MODE == CONV_WGRAD;
+    constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
     constexpr int VEC = Elem<T>::VEC;
     constexpr int LDK = BK + VEC;
-    constexpr int KV = BK / VEC;                 // vectors per tile row (reduction innermost)
-    constexpr int ITER_A = (MODE == CONV_WGRAD) ? (BK * (BM / VEC) + 255) / 256 : (BM * KV + 255) / 256;
-    constexpr int ITER_B = (MODE == CONV_WGRAD) ? (BK * (BN / VEC) + 255) / 256 : (BN * KV + 255) / 256;
+    constexpr int KV = BK / VEC;                    // fwd/dgrad: vectors per tile row
+    constexpr int KPD = sizeof(T) == 2 ? 2 : 1;     // wgrad: reduction elements per 32-bit word
+    constexpr int KD = BK / KPD;                    // wgrad: words along the reduction
+    constexpr int LDPA = BM + 8, LDPB = BN + 8;     // wgrad: words per reduction word-row
+    constexpr int RVA = BM / VEC, RVB = BN / VEC;   // wgrad: channel vectors per pixel
+    constexpr int TOT_A = WG ? KD * RVA : BM * KV;  // work items per tile (wgrad: KPD vectors each)
+    constexpr int TOT_B = WG ? KD * RVB : BN * KV;
+    constexpr int ITER_A = (TOT_A + 255) / 256, ITER_B = (TOT_B + 255) / 256;
+    constexpr int NRA = WG ? ITER_A * KPD : ITER_A, NRB = WG ? ITER_B * KPD : ITER_B;
+    constexpr int A_STAGE = WG ? KD * LDPA * 4 : BM * LDK * (int)sizeof(T);   // bytes per LDS stage
+    constexpr int B_STAGE = WG ? KD * LDPB * 4 : BN * LDK * (int)sizeof(T);
+    // epilogue staging: the rows of one wave row, as float32
+    constexpr int STAGE_ROWS = TM * 32, STAGE_LD = BN + 4;
+    constexpr int TILE_BYTES = 2 * (A_STAGE + B_STAGE);
+    constexpr int STAGE_BYTES = STAGE_ROWS * STAGE_LD * 4;
+    constexpr int SMEM_BYTES = TILE_BYTES > STAGE_BYTES ? TILE_BYTES : STAGE_BYTES;
     static_assert(WM * WN == 4, "four waves per workgroup");
+    static_assert(256 % KV == 0 && 256 % RVA == 0 && 256 % RVB == 0, "per-thread column of the tile must be fixed");
+    static_assert(KD == 32, "four fragment groups of eight words");
 
-    __shared__ __attribute__((aligned(16))) T As[BM * LDK];
-    __shared__ __attribute__((aligned(16))) T Bs[BN * LDK];
+    __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM_BYTES];
+    unsigned char* const As = smem;                  // [2] stages
+    unsigned char* const Bs = smem + 2 * A_STAGE;
 
     const T* __restrict__ Ag = (const T*)a.A;
     const T* __restrict__ Bg = (const T*)a.B;
@@ -134,151 +211,220 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
     if (kend > a.Kred) kend = a.Kred;
     const int nk = (kend - kbeg + BK - 1) / BK;
 
-    Vec16<T> ra[ITER_A], rb[ITER_B];
+    Vec16<T> ra[NRA], rb[NRB];
+    const __amdgpu_buffer_rsrc_t rsrcA = make_rsrc(a.A, a.bytesA), rsrcB = make_rsrc(a.B, a.bytesB);
 
-    // ---- per-thread constants of the gathers --------------------------------
-    RowCtx rowA[ITER_A];
+    // ---- per-thread state of the gathers; advanced by BK after every tile ------
+    RowCtx rowA[WG ? 1 : ITER_A];
+    int64_t offB[WG ? 1 : ITER_B];   // fwd/dgrad: start of the weight row
+    bool okB[WG ? 1 : ITER_B];
+    int tr = 0, ts = 0, tc = 0, tap_off = 0;   // fwd/dgrad: kernel tap and channel of this thread's vector
+    int kcur = 0;                    // reduction index of this thread's vector (fwd/dgrad) or of the tile (wgrad)
+    int64_t offA[WG ? ITER_A : 1];   // wgrad: offset of dy[first pixel of the item][first row of the item]
+    int pn[WG ? ITER_B : 1], pho[WG ? ITER_B : 1], pwo[WG ? ITER_B : 1];   // wgrad: first pixel of the item
     int wg_r = 0, wg_s = 0, wg_c = 0;  // wgrad: tap and channel of this thread's B rows
-    if (MODE != CONV_WGRAD) {
+    int dn = 0, dho = 0, dwo = 0;    // wgrad: BK pixels as (images, rows, columns)
+    if (!WG) {
+        const int inner = MODE == CONV_FWD ? a.C : a.K;
+        kcur = kbeg + (tid % KV) * VEC;
+        const int tap = kcur / inner;
+        tc = kcur - tap * inner;
+        tr = tap / a.S;
+        ts = tap - tr * a.S;
+        tap_off = (tr * a.W + ts) * a.C + tc;
         #pragma unroll
-        for (int it = 0; it < ITER_A; ++it) {
-            const int v = tid + it * 256;
-            rowA[it] = make_row<T, MODE>(a, m0 + v / KV);
+        for (int it = 0; it < ITER_A; ++it) rowA[it] = make_row<MODE>(a, m0 + (tid + it * 256) / KV);
+        #pragma unroll
+        for (int it = 0; it < ITER_B; ++it) {
+            const int j = n0 + (tid + it * 256) / KV;
+            okB[it] = j < a.Nn && (tid + it * 256) < TOT_B;
+            offB[it] = (int64_t)j * a.Kred;
         }
     } else {
-        constexpr int RVB = BN / VEC;
         const int j0 = n0 + (tid % RVB) * VEC;
         const int tap = j0 / a.C;
         wg_c = j0 - tap * a.C;
         wg_r = tap / a.S;
         wg_s = tap - wg_r * a.S;
+        const int hw = a.Ho * a.Wo;
+        dn = BK / hw;
+        dho = (BK - dn * hw) / a.Wo;
+        dwo = BK - dn * hw - dho * a.Wo;
+        #pragma unroll
+        for (int it = 0; it < ITER_A; ++it)
+            offA[it] = (int64_t)(kbeg + ((tid + it * 256) / RVA) * KPD) * a.K + m0 + (tid % RVA) * VEC;
+        #pragma unroll
+        for (int it = 0; it < ITER_B; ++it) {
+            const int mm = kbeg + ((tid + it * 256) / RVB) * KPD;
+            pn[it] = mm / hw;
+            const int rem = mm - pn[it] * hw;
+            pho[it] = rem / a.Wo;
+            pwo[it] = rem - pho[it] * a.Wo;
+        }
+        kcur = kbeg;
     }
 
-    auto load_tiles = [&](int k0) {
-        if (MODE != CONV_WGRAD) {
-            // A: pixel rows, reduction innermost
+    auto load_tiles = [&]() {
+        if (!WG) {
+            const bool in_k = kcur < kend;
             #pragma unroll
             for (int it = 0; it < ITER_A; ++it) {
-                const int v = tid + it * 256;
-                const int kk0 = k0 + (v % KV) * VEC;
                 ra[it].u = make_uint4(0, 0, 0, 0);
-                if (BM * KV % 256 != 0 && v >= BM * KV) continue;
+                if (TOT_A % 256 != 0 && tid + it * 256 >= TOT_A) continue;
                 if (a.vecA) {
-                    bool ok;
-                    const int64_t off = a_offset<MODE>(a, rowA[it], kk0, ok);
-                    if (ok && kk0 < kend) ra[it] = load_vec(Ag + off);
+                    ra[it].u = buffer_load16(rsrcA, a_voffset<MODE, T>(a, rowA[it], tr, ts, tc, tap_off, in_k));
                 } else {
                     #pragma unroll
                     for (int e = 0; e < VEC; ++e) {
                         bool ok;
-                        const int64_t off = a_offset<MODE>(a, rowA[it], kk0 + e, ok);
-                        if (ok && kk0 + e < kend) ra[it].e[e] = Ag[off];
+                        const int64_t off = a_offset<MODE>(a, rowA[it], kcur + e, ok);
+                        if (ok && kcur + e < kend) ra[it].e[e] = Ag[off];
                     }
                 }
             }
-            // B: weight rows, contiguous in the reduction index
             #pragma unroll
             for (int it = 0; it < ITER_B; ++it) {
-                const int v = tid + it * 256;
-                const int kk0 = k0 + (v % KV) * VEC;
-                const int j = n0 + v / KV;
                 rb[it].u = make_uint4(0, 0, 0, 0);
-                if (BN * KV % 256 != 0 && v >= BN * KV) continue;
-                if (j < a.Nn) {
-                    const int64_t off = (int64_t)j * a.Kred + kk0;
-                    if (a.vecB) {
-                        if (kk0 < kend) rb[it] = load_vec(Bg + off);
-                    } else {
-                        #pragma unroll
-                        for (int e = 0; e < VEC; ++e)
-                            if (kk0 + e < kend) rb[it].e[e] = Bg[off + e];
-                    }
+                if (a.vecB) {
+                    rb[it].u = buffer_load16(rsrcB, (okB[it] && in_k) ? (unsigned)((int)offB[it] + kcur) * (unsigned)sizeof(T) : kOutOfRange);
+                } else if (okB[it]) {
+                    #pragma unroll
+                    for (int e = 0; e < VEC; ++e)
+                        if (kcur + e < kend) rb[it].e[e] = Bg[offB[it] + kcur + e];
                 }
+            }
+            // advance this thread's vector by BK along (r, s, channel)
+            const int inner = MODE == CONV_FWD ? a.C : a.K;
+            kcur += BK;
+            tc += BK;
+            tap_off += BK;
+            if (tc >= inner) {
+                do {
+                    tc -= inner;
+                    if (++ts == a.S) { ts = 0; ++tr; }
+                } while (tc >= inner);
+                tap_off = (tr * a.W + ts) * a.C + tc;
             }
         } else {
-            // A = dy[pixel][k]: vectors along k for one pixel
-            constexpr int RVA = BM / VEC;
             #pragma unroll
             for (int it = 0; it < ITER_A; ++it) {
-                const int v = tid + it * 256;
-                const int row0 = m0 + (v % RVA) * VEC;
-                const int mm = k0 + v / RVA;
-                ra[it].u = make_uint4(0, 0, 0, 0);
-                if (BK * RVA % 256 != 0 && v >= BK * RVA) continue;
-                if (mm < kend) {
-                    const int64_t off = (int64_t)mm * a.K + row0;
+                const bool live = !(TOT_A % 256 != 0 && tid + it * 256 >= TOT_A);
+                const int mm = kcur + ((tid + it * 256) / RVA) * KPD;
+                const int row0 = m0 + (tid % RVA) * VEC;
+                #pragma unroll
+                for (int pp = 0; pp < KPD; ++pp) {
+                    Vec16<T>& dst = ra[it * KPD + pp];
+                    dst.u = make_uint4(0, 0, 0, 0);
+                    const bool ok = live && mm + pp < kend;
                     if (a.vecA) {
-                        if (row0 < a.M) ra[it] = load_vec(Ag + off);
-                    } else {
+                        dst.u = buffer_load16(rsrcA, (ok && row0 < a.M) ? (unsigned)((int)offA[it] + pp * a.K) * (unsigned)sizeof(T) : kOutOfRange);
+                    } else if (ok) {
                         #pragma unroll
                         for (int e = 0; e < VEC; ++e)
-                            if (row0 + e < a.M) ra[it].e[e] = Ag[off + e];
+                            if (row0 + e < a.M) dst.e[e] = Ag[offA[it] + (int64_t)pp * a.K + e];
                     }
                 }
+                offA[it] += (int64_t)BK * a.K;
             }
-            // B = x gathered at (pixel, tap): vectors along c
-            constexpr int RVB = BN / VEC;
-            const int hw = a.Ho * a.Wo;
             #pragma unroll
             for (int it = 0; it < ITER_B; ++it) {
-                const int v = tid + it * 256;
-                const int mm = k0 + v / RVB;
-                rb[it].u = make_uint4(0, 0, 0, 0);
-                if (BK * RVB % 256 != 0 && v >= BK * RVB) continue;
-                if (mm < kend) {
-                    const int n = mm / hw, rem = mm - n * hw;
-                    const int ho = rem / a.Wo, wo = rem - ho * a.Wo;
-                    const int hb = ho * a.stride - a.pad, wb = wo * a.stride - a.pad;
+                const bool live = !(TOT_B % 256 != 0 && tid + it * 256 >= TOT_B);
+                const int mm = kcur + ((tid + it * 256) / RVB) * KPD;
+                int qn = pn[it], qho = pho[it], qwo = pwo[it];
+                #pragma unroll
+                for (int pp = 0; pp < KPD; ++pp) {
+                    Vec16<T>& dst = rb[it * KPD + pp];
+                    dst.u = make_uint4(0, 0, 0, 0);
+                    const bool okp = live && mm + pp < kend;
+                    const int hb = qho * a.stride - a.pad, wb = qwo * a.stride - a.pad;
                     if (a.vecB) {
-                        const int j0 = n0 + (v % RVB) * VEC;
+                        const int j0 = n0 + (tid % RVB) * VEC;
                         const int h = hb + wg_r, w = wb + wg_s;
-                        if (j0 < a.Nn && (unsigned)h < (unsigned)a.H && (unsigned)w < (unsigned)a.W)
-                            rb[it] = load_vec(Bg + (((int64_t)n * a.H + h) * a.W + w) * a.C + wg_c);
-                    } else {
+                        const bool ok = okp && j0 < a.Nn && (unsigned)h < (unsigned)a.H && (unsigned)w < (unsigned)a.W;
+                        const unsigned off = (unsigned)(((qn * a.H + h) * a.W + w) * a.C + wg_c) * (unsigned)sizeof(T);
+                        dst.u = buffer_load16(rsrcB, ok ? off : kOutOfRange);
+                    } else if (okp) {
                         #pragma unroll
                         for (int e = 0; e < VEC; ++e) {
-                            const int j = n0 + (v % RVB) * VEC + e;
+                            const int j = n0 + (tid % RVB) * VEC + e;
                             const int tap = j / a.C, ch = j - tap * a.C;
                             const int r = tap / a.S, s = tap - r * a.S;
                             const int h = hb + r, w = wb + s;
                             if (j < a.Nn && (unsigned)h < (unsigned)a.H && (unsigned)w < (unsigned)a.W)
-                                rb[it].e[e] = Bg[(((int64_t)n * a.H + h) * a.W + w) * a.C + ch];
+                                dst.e[e] = Bg[(((int64_t)qn * a.H + h) * a.W + w) * a.C + ch];
                         }
                     }
+                    // the next pixel of the pair
+                    if (++qwo == a.Wo) { qwo = 0; if (++qho == a.Ho) { qho = 0; ++qn; } }
                 }
+                // advance the item's first pixel by BK
+                pwo[it] += dwo;
+                if (pwo[it] >= a.Wo) { pwo[it] -= a.Wo; ++pho[it]; }
+                pho[it] += dho;
+                if (pho[it] >= a.Ho) { pho[it] -= a.Ho; ++pn[it]; }
+                pn[it] += dn;
             }
+            kcur += BK;
         }
     };
 
-    auto store_tiles = [&]() {
-        if (MODE != CONV_WGRAD) {
+    auto store_tiles = [&](int buf) {
+        if (!WG) {
+            T* const Ad = reinterpret_cast<T*>(As + buf * A_STAGE);
+            T* const Bd = reinterpret_cast<T*>(Bs + buf * B_STAGE);
             #pragma unroll
             for (int it = 0; it < ITER_A; ++it) {
                 const int v = tid + it * 256;
-                if (BM * KV % 256 != 0 && v >= BM * KV) continue;
-                store_vec(&As[(v / KV) * LDK + (v % KV) * VEC], ra[it]);
+                if (TOT_A % 256 != 0 && v >= TOT_A) continue;
+                store_vec(&Ad[(v / KV) * LDK + (v % KV) * VEC], ra[it]);
             }
             #pragma unroll
             for (int it = 0; it < ITER_B; ++it) {
                 const int v = tid + it * 256;
-                if (BN * KV % 256 != 0 && v >= BN * KV) continue;
-                store_vec(&Bs[(v / KV) * LDK + (v % KV) * VEC], rb[it]);
+                if (TOT_B % 256 != 0 && v >= TOT_B) continue;
+                store_vec(&Bd[(v / KV) * LDK + (v % KV) * VEC], rb[it]);
             }
         } else {
-            constexpr int RVA = BM / VEC, RVB = BN / VEC;
+            uint32_t* const Ad = reinterpret_cast<uint32_t*>(As + buf * A_STAGE);
+            uint32_t* const Bd = reinterpret_cast<uint32_t*>(Bs + buf * B_STAGE);
             #pragma unroll
             for (int it = 0; it < ITER_A; ++it) {
                 const int v = tid + it * 256;
-                if (BK * RVA % 256 != 0 && v >= BK * RVA) continue;
-                #pragma unroll
-                for (int e = 0; e < VEC; ++e) As[((v % RVA) * VEC + e) * LDK + v / RVA] = ra[it].e[e];
+                if (TOT_A % 256 != 0 && v >= TOT_A) continue;
+                uint32_t* dst = &Ad[(v / RVA) * LDPA + (v % RVA) * VEC];
+                if (KPD == 2) {
+                    // word e = (pixel 2q, pixel 2q+1) of channel e
+                    const uint16_t* p0 = reinterpret_cast<const uint16_t*>(&ra[it * KPD]);
+                    const uint16_t* p1 = reinterpret_cast<const uint16_t*>(&ra[it * KPD + KPD - 1]);
+                    uint4 lo, hi;
+                    lo.x = p0[0] | ((uint32_t)p1[0] << 16); lo.y = p0[1] | ((uint32_t)p1[1] << 16);
+                    lo.z = p0[2] | ((uint32_t)p1[2] << 16); lo.w = p0[3] | ((uint32_t)p1[3] << 16);
+                    hi.x = p0[4] | ((uint32_t)p1[4] << 16); hi.y = p0[5] | ((uint32_t)p1[5] << 16);
+                    hi.z = p0[6] | ((uint32_t)p1[6] << 16); hi.w = p0[7] | ((uint32_t)p1[7] << 16);
+                    *reinterpret_cast<uint4*>(dst) = lo;
+                    *reinterpret_cast<uint4*>(dst + 4) = hi;
+                } else {
+                    *reinterpret_cast<uint4*>(dst) = ra[it].u;
+                }
             }
             #pragma unroll
             for (int it = 0; it < ITER_B; ++it) {
                 const int v = tid + it * 256;
-                if (BK * RVB % 256 != 0 && v >= BK * RVB) continue;
-                #pragma unroll
-                for (int e = 0; e < VEC; ++e) Bs[((v % RVB) * VEC + e) * LDK + v / RVB] = rb[it].e[e];
+                if (TOT_B % 256 != 0 && v >= TOT_B) continue;
+                uint32_t* dst = &Bd[(v / RVB) * LDPB + (v % RVB) * VEC];
+                if (KPD == 2) {
+                    const uint16_t* p0 = reinterpret_cast<const uint16_t*>(&rb[it * KPD]);
+                    const uint16_t* p1 = reinterpret_cast<const uint16_t*>(&rb[it * KPD + KPD - 1]);
+                    uint4 lo, hi;
+                    lo.x = p0[0] | ((uint32_t)p1[0] << 16); lo.y = p0[1] | ((uint32_t)p1[1] << 16);
+                    lo.z = p0[2] | ((uint32_t)p1[2] << 16); lo.w = p0[3] | ((uint32_t)p1[3] << 16);
+                    hi.x = p0[4] | ((uint32_t)p1[4] << 16); hi.y = p0[5] | ((uint32_t)p1[5] << 16);
+                    hi.z = p0[6] | ((uint32_t)p1[6] << 16); hi.w = p0[7] | ((uint32_t)p1[7] << 16);
+                    *reinterpret_cast<uint4*>(dst) = lo;
+                    *reinterpret_cast<uint4*>(dst + 4) = hi;
+                } else {
+                    *reinterpret_cast<uint4*>(dst) = rb[it].u;
+                }
             }
         }
     };
@@ -291,58 +437,150 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
             #pragma unroll
             for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
 
-    if (nk > 0) load_tiles(kbeg);
+    // two LDS stages: the global loads of tile kt+1 are in flight during the
+    // MFMAs of tile kt and land in the other stage; one barrier per tile
+    if (nk > 0) {
+        load_tiles();
+        store_tiles(0);
+    }
+    __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
-        store_tiles();
-        __syncthreads();
-        if (kt + 1 < nk) load_tiles(kbeg + (kt + 1) * BK);
-        constexpr int KG = 2 * VEC;  // reduction elements one fragment pair covers
+        const int buf = kt & 1;
+        if (kt + 1 < nk) load_tiles();
         #pragma unroll
-        for (int g = 0; g < BK / KG; ++g) {
+        for (int g = 0; g < 4; ++g) {
             uint4 fa[TM], fb[TN];
-            #pragma unroll
-            for (int i = 0; i < TM; ++i)
-                fa[i] = *reinterpret_cast<const uint4*>(&As[((wm * TM + i) * 32 + (lane & 31)) * LDK + g * KG + (lane >> 5) * VEC]);
-            #pragma unroll
-            for (int j = 0; j < TN; ++j)
-                fb[j] = *reinterpret_cast<const uint4*>(&Bs[((wn * TN + j) * 32 + (lane & 31)) * LDK + g * KG + (lane >> 5) * VEC]);
+            if (!WG) {
+                constexpr int KG = 2 * VEC;  // reduction elements one fragment pair covers
+                const T* const Ab = reinterpret_cast<const T*>(As + buf * A_STAGE);
+                const T* const Bb = reinterpret_cast<const T*>(Bs + buf * B_STAGE);
+                #pragma unroll
+                for (int i = 0; i < TM; ++i)
+                    fa[i] = *reinterpret_cast<const uint4*>(&Ab[((wm * TM + i) * 32 + (lane & 31)) * LDK + g * KG + (lane >> 5) * VEC]);
+                #pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    fb[j] = *reinterpret_cast<const uint4*>(&Bb[((wn * TN + j) * 32 + (lane & 31)) * LDK + g * KG + (lane >> 5) * VEC]);
+            } else {
+                const uint32_t* const Ab = reinterpret_cast<const uint32_t*>(As + buf * A_STAGE) + (g * 8 + (lane >> 5) * 4) * LDPA + (lane & 31);
+                const uint32_t* const Bb = reinterpret_cast<const uint32_t*>(Bs + buf * B_STAGE) + (g * 8 + (lane >> 5) * 4) * LDPB + (lane & 31);
+                #pragma unroll
+                for (int i = 0; i < TM; ++i) {
+                    const uint32_t* q = Ab + (wm * TM + i) * 32;
+                    fa[i] = make_uint4(q[0], q[LDPA], q[2 * LDPA], q[3 * LDPA]);
+                }
+                #pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const uint32_t* q = Bb + (wn * TN + j) * 32;
+                    fb[j] = make_uint4(q[0], q[LDPB], q[2 * LDPB], q[3 * LDPB]);
+                }
+            }
             #pragma unroll
             for (int i = 0; i < TM; ++i)
                 #pragma unroll
                 for (int j = 0; j < TN; ++j) Frag<T>::mma(fa[i], fb[j], acc[i][j]);
         }
+        if (kt + 1 < nk) store_tiles(buf ^ 1);
         __syncthreads();
     }
 
-    // ---- epilogue: lane holds column lane%32, rows (q/4)*8 + (lane/32)*4 + q%4 ----
-    #pragma unroll
-    for (int i = 0; i < TM; ++i) {
+    // ---- epilogue: lane holds column lane%32, rows (q/4)*8 + (lane/32)*4 + q%4 of each 32x32 tile ----
+    constexpr bool OUT_F32 = WG || sizeof(T) == 4;       // element type of the vector-path output
+    constexpr int OSZ = OUT_F32 ? 4 : 2;
+    constexpr int OVEC = 16 / OSZ;
+    const bool direct_f32 = (MODE == CONV_FWD) && a.out_fp32 && !OUT_F32;
+    if ((a.Nn % OVEC) != 0 || direct_f32) {
+        // ragged width (or float32 logits from a bf16 net): element-wise stores
         #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int col = n0 + (wn * TN + j) * 32 + (lane & 31);
-            if (col >= a.Nn) continue;
-            const float bias = (MODE == CONV_FWD && a.bias) ? a.bias[col] : 0.f;
+        for (int i = 0; i < TM; ++i) {
             #pragma unroll
-            for (int q = 0; q < 16; ++q) {
-                const int row = m0 + (wm * TM + i) * 32 + (q >> 2) * 8 + (lane >> 5) * 4 + (q & 3);
-                if (row >= a.M) continue;
-                float v = acc[i][j][q];
-                if (MODE == CONV_FWD) {
-                    v += bias;
-                    if (a.relu) v = v > 0.f ? v : 0.f;
-                    const int64_t o = (int64_t)row * a.Nn + col;
-                    if (a.out_fp32) ((float*)a.out)[o] = v;
-                    else ((T*)a.out)[o] = Elem<T>::from_f32(v);
-                } else if (MODE == CONV_DGRAD) {
-                    const int64_t o = (int64_t)row * a.Nn + col;
-                    T* dst = (T*)a.out;
-                    if (a.accumulate) v += Elem<T>::to_f32(dst[o]);
-                    dst[o] = Elem<T>::from_f32(v);
-                } else {
-                    ((float*)a.out)[((int64_t)blockIdx.z * a.M + row) * a.Nn + col] = v;
+            for (int j = 0; j < TN; ++j) {
+                const int col = n0 + (wn * TN + j) * 32 + (lane & 31);
+                if (col >= a.Nn) continue;
+                const float bias = (MODE == CONV_FWD && a.bias) ? a.bias[col] : 0.f;
+                #pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    const int row = m0 + (wm * TM + i) * 32 + (q >> 2) * 8 + (lane >> 5) * 4 + (q & 3);
+                    if (row >= a.M) continue;
+                    float v = acc[i][j][q];
+                    if (MODE == CONV_FWD) {
+                        v += bias;
+                        if (a.relu) v = v > 0.f ? v : 0.f;
+                        const int64_t o = (int64_t)row * a.Nn + col;
+                        if (a.out_fp32) ((float*)a.out)[o] = v;
+                        else ((T*)a.out)[o] = Elem<T>::from_f32(v);
+                    } else if (MODE == CONV_DGRAD) {
+                        const int64_t o = (int64_t)row * a.Nn + col;
+                        T* dst = (T*)a.out;
+                        if (a.accumulate) v += Elem<T>::to_f32(dst[o]);
+                        dst[o] = Elem<T>::from_f32(v);
+                    } else {
+                        ((float*)a.out)[((int64_t)blockIdx.z * a.M + row) * a.Nn + col] = v;
+                    }
                 }
             }
         }
+        return;
+    }
+    // staged: one wave row at a time goes through LDS as float32 (one word per
+    // lane and row, conflict-free), then leaves as 16-byte vectors along the output row
+    float* const stage = reinterpret_cast<float*>(smem);
+    unsigned char* const outp = (unsigned char*)a.out + (WG ? (int64_t)blockIdx.z * a.M * a.Nn * 4 : 0);
+    #pragma unroll
+    for (int pass = 0; pass < WM; ++pass) {
+        if (wm == pass) {
+            #pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                #pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const int cl = (wn * TN + j) * 32 + (lane & 31);
+                    const int col = n0 + cl;
+                    const float bias = (MODE == CONV_FWD && a.bias && col < a.Nn) ? a.bias[col] : 0.f;
+                    float* sp = stage + (i * 32 + (lane >> 5) * 4) * STAGE_LD + cl;
+                    #pragma unroll
+                    for (int q = 0; q < 16; ++q) {
+                        float v = acc[i][j][q];
+                        if (MODE == CONV_FWD) {
+                            v += bias;
+                            if (a.relu) v = fmaxf(v, 0.f);
+                        }
+                        sp[((q >> 2) * 8 + (q & 3)) * STAGE_LD] = v;
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        constexpr int CV = BN / OVEC;
+        #pragma unroll 2
+        for (int v = tid; v < STAGE_ROWS * CV; v += 256) {
+            const int rl = v / CV, cv = v - rl * CV;
+            const int row = m0 + pass * STAGE_ROWS + rl, col = n0 + cv * OVEC;
+            if (row < a.M && col < a.Nn) {
+                const float* sp = stage + rl * STAGE_LD + cv * OVEC;
+                unsigned char* dst = outp + ((int64_t)row * a.Nn + col) * OSZ;
+                if (OUT_F32) {
+                    float4 o = *reinterpret_cast<const float4*>(sp);
+                    if (MODE == CONV_DGRAD && a.accumulate) {
+                        const float4 old = *reinterpret_cast<const float4*>(dst);
+                        o.x += old.x; o.y += old.y; o.z += old.z; o.w += old.w;
+                    }
+                    *reinterpret_cast<float4*>(dst) = o;
+                } else {
+                    float4 o0 = *reinterpret_cast<const float4*>(sp), o1 = *reinterpret_cast<const float4*>(sp + 4);
+                    if (MODE == CONV_DGRAD && a.accumulate) {
+                        const uint4 old = *reinterpret_cast<const uint4*>(dst);
+                        o0.x += __uint_as_float(old.x << 16); o0.y += __uint_as_float(old.x & 0xffff0000u);
+                        o0.z += __uint_as_float(old.y << 16); o0.w += __uint_as_float(old.y & 0xffff0000u);
+                        o1.x += __uint_as_float(old.z << 16); o1.y += __uint_as_float(old.z & 0xffff0000u);
+                        o1.z += __uint_as_float(old.w << 16); o1.w += __uint_as_float(old.w & 0xffff0000u);
+                    }
+                    uint4 pk;
+                    pk.x = pack2_bf16(o0.x, o0.y); pk.y = pack2_bf16(o0.z, o0.w);
+                    pk.z = pack2_bf16(o1.x, o1.y); pk.w = pack2_bf16(o1.z, o1.w);
+                    *reinterpret_cast<uint4*>(dst) = pk;
+                }
+            }
+        }
+        __syncthreads();
     }
 }
 
@@ -361,6 +599,9 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restri
 // host side: tile selection and launch
 // ---------------------------------------------------------------------------
 enum TileCfg { T128x128, T128x64, T128x32, T64x64 };
+
+// reduction elements per tile: eight 16-byte vectors per row for either type
+template <typename T> constexpr int kConvBK = 8 * Elem<T>::VEC;
 
 static TileCfg pick_tile(int M, int Nn, int* bm, int* bn) {
     TileCfg t;
@@ -381,11 +622,12 @@ static TileCfg pick_tile(int M, int Nn, int* bm, int* bn) {
 
 template <typename T, int MODE>
 static void launch_cfg(TileCfg t, dim3 grid, const ConvArgs& a, hipStream_t st) {
+    constexpr int BK = kConvBK<T>;
     switch (t) {
-        case T128x128: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 2, 2>), grid, dim3(256), 0, st, a); break;
-        case T128x64: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 2, 1>), grid, dim3(256), 0, st, a); break;
-        case T128x32: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 4, 1, 1, 1>), grid, dim3(256), 0, st, a); break;
-        default: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 1, 1>), grid, dim3(256), 0, st, a); break;
+        case T128x128: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 2, 2, BK>), grid, dim3(256), 0, st, a); break;
+        case T128x64: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 2, 1, BK>), grid, dim3(256), 0, st, a); break;
+        case T128x32: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 4, 1, 1, 1, BK>), grid, dim3(256), 0, st, a); break;
+        default: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 1, 1, BK>), grid, dim3(256), 0, st, a); break;
     }
 }
 
@@ -428,7 +670,10 @@ void launch_conv_fwd(int dtype, const ConvGeom& g, const void* x, const void* w,
     a.A = x; a.B = w; a.out = y; a.bias = bias;
     a.M = g.N * g.Ho * g.Wo; a.Nn = g.K; a.Kred = g.R * g.S * g.C;
     a.relu = relu; a.out_fp32 = out_fp32;
-    a.vecA = (g.C % VEC == 0); a.vecB = (a.Kred % VEC == 0);
+    const double esz = dtype == 1 ? 2.0 : 4.0;
+    const double bA = esz * (double)g.N * g.H * g.W * g.C, bB = esz * (double)a.Nn * a.Kred;
+    a.vecA = (g.C % VEC == 0) && bA < 2147483648.0; a.vecB = (a.Kred % VEC == 0) && bB < 2147483648.0;
+    a.bytesA = a.vecA ? (unsigned)bA : 0; a.bytesB = a.vecB ? (unsigned)bB : 0;
     a.ksplit = a.Kred;
     int bm, bn;
     const TileCfg t = pick_tile(a.M, a.Nn, &bm, &bn);
@@ -442,7 +687,10 @@ void launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dy, const void*
     a.A = dy; a.B = wT; a.out = dx;
     a.M = g.N * g.H * g.W; a.Nn = g.C; a.Kred = g.R * g.S * g.K;
     a.accumulate = accumulate;
-    a.vecA = (g.K % VEC == 0); a.vecB = (a.Kred % VEC == 0);
+    const double esz = dtype == 1 ? 2.0 : 4.0;
+    const double bA = esz * (double)g.N * g.Ho * g.Wo * g.K, bB = esz * (double)a.Nn * a.Kred;
+    a.vecA = (g.K % VEC == 0) && bA < 2147483648.0; a.vecB = (a.Kred % VEC == 0) && bB < 2147483648.0;
+    a.bytesA = a.vecA ? (unsigned)bA : 0; a.bytesB = a.vecB ? (unsigned)bB : 0;
     a.ksplit = a.Kred;
     int bm, bn;
     const TileCfg t = pick_tile(a.M, a.Nn, &bm, &bn);
@@ -455,12 +703,19 @@ struct WgradPlan {
     int64_t tiles;
 };
 
+// Tile and split of the weight gradient.  Its output is small and its
+// reduction (the pixels) long, so parallelism comes from cutting the reduction;
+// every split costs a float32 partial tile that is written and read again, so
+// layers whose output already gives enough tiles are split little or not at all.
 static WgradPlan plan_wgrad(const ConvGeom& g) {
     WgradPlan p;
     const int M = g.K, Nn = g.R * g.S * g.C, Kred = g.N * g.Ho * g.Wo;
-    // tile choice by shape only (the split supplies the parallelism)
+    const int64_t t128 = (int64_t)((M + 127) / 128) * ((Nn + 127) / 128);
+    const int64_t t64 = (int64_t)((M + 63) / 64) * ((Nn + 63) / 64);
     if (Nn <= 32) p.t = T128x32;
     else if (M <= 64 || Nn <= 64) p.t = (Nn <= 64 && M >= 128) ? T128x64 : T64x64;
+    else if (t128 >= 128) p.t = T128x128;
+    else if (t64 >= 256) p.t = T64x64;
     else p.t = T128x128;
     switch (p.t) {
         case T128x128: p.bm = 128; p.bn = 128; break;
@@ -469,12 +724,12 @@ static WgradPlan plan_wgrad(const ConvGeom& g) {
         default: p.bm = 64; p.bn = 64; break;
     }
     p.tiles = (int64_t)((M + p.bm - 1) / p.bm) * ((Nn + p.bn - 1) / p.bn);
-    int64_t splits = (1024 + p.tiles - 1) / p.tiles;
-    const int64_t max_splits = (Kred + 127) / 128;  // at least 4 reduction steps per split
+    int64_t splits = (512 + p.tiles - 1) / p.tiles;
+    const int64_t max_splits = (Kred + 255) / 256;  // at least 4 reduction steps per split
     if (splits > max_splits) splits = max_splits;
     if (splits < 1) splits = 1;
     int64_t ks = (Kred + splits - 1) / splits;
-    ks = (ks + 31) / 32 * 32;
+    ks = (ks + 63) / 64 * 64;
     p.ksplit = (int)ks;
     p.splits = (int)((Kred + ks - 1) / ks);
     return p;
@@ -493,7 +748,10 @@ void launch_conv_wgrad(int dtype, const ConvGeom& g, const void* x, const void* 
     ConvArgs a = base_args(g);
     a.A = dy; a.B = x;
     a.M = g.K; a.Nn = g.R * g.S * g.C; a.Kred = g.N * g.Ho * g.Wo;
-    a.vecA = (g.K % VEC == 0); a.vecB = (g.C % VEC == 0);
+    const double esz = dtype == 1 ? 2.0 : 4.0;
+    const double bA = esz * (double)a.Kred * g.K, bB = esz * (double)g.N * g.H * g.W * g.C;
+    a.vecA = (g.K % VEC == 0) && bA < 2147483648.0; a.vecB = (g.C % VEC == 0) && bB < 2147483648.0;
+    a.bytesA = a.vecA ? (unsigned)bA : 0; a.bytesB = a.vecB ? (unsigned)bB : 0;
     a.ksplit = p.ksplit;
     const int64_t n = (int64_t)a.M * a.Nn;
     const bool direct = p.splits <= 1 || scratch == nullptr || scratch_bytes < (size_t)p.splits * n * sizeof(float);

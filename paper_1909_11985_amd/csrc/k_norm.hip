@@ -30,7 +30,7 @@ static RedShape red_shape(int64_t M, int C, int VEC) {
     s.TY = 256 / tx;
     const int col_blocks = (s.cvecs + tx - 1) / tx;
     // aim at ~2048 workgroups, at least TY*4 rows each
-    int64_t rb = 2048 / col_blocks;
+    int64_t rb = (2048 + col_blocks - 1) / col_blocks;
     const int64_t max_rb = (M + (int64_t)s.TY * 4 - 1) / ((int64_t)s.TY * 4);
     if (rb > max_rb) rb = max_rb;
     if (rb > kRedRowBlocks) rb = kRedRowBlocks;
@@ -138,17 +138,32 @@ __global__ __launch_bounds__(256) void colreduce_kernel(const T* __restrict__ x,
     }
 }
 
+// Sum of the row blocks' partial sums of one channel: 32 lanes take every 32nd
+// block in float64, then a butterfly.  blockDim = 256 = 8 channels x 32 lanes.
+__device__ __forceinline__ void sum_partials(const float* __restrict__ partial, int row_blocks, int C, int c, int sub,
+                                             double& s, double& q) {
+    s = 0;
+    q = 0;
+    if (c < C) {
+        for (int j = sub; j < row_blocks; j += 32) {
+            s += (double)partial[((int64_t)j * 2 + 0) * C + c];
+            q += (double)partial[((int64_t)j * 2 + 1) * C + c];
+        }
+    }
+    for (int o = 16; o > 0; o >>= 1) {
+        s += __shfl_xor(s, o, 64);
+        q += __shfl_xor(q, o, 64);
+    }
+}
+
 // mean / rstd from the partial sums; running statistics of the worker whose
 // model a joiner would receive (unbiased variance, momentum 0.1)
-__global__ void bn_stats_finalize_kernel(const float* __restrict__ partial, int row_blocks, int64_t M, int C,
-                                         float* __restrict__ mean_rstd, float* running) {
-    const int c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c >= C) return;
-    double s = 0, q = 0;
-    for (int j = 0; j < row_blocks; ++j) {
-        s += (double)partial[((int64_t)j * 2 + 0) * C + c];
-        q += (double)partial[((int64_t)j * 2 + 1) * C + c];
-    }
+__global__ __launch_bounds__(256) void bn_stats_finalize_kernel(const float* __restrict__ partial, int row_blocks, int64_t M,
+                                                                int C, float* __restrict__ mean_rstd, float* running) {
+    const int c = blockIdx.x * 8 + (threadIdx.x >> 5), sub = threadIdx.x & 31;
+    double s, q;
+    sum_partials(partial, row_blocks, C, c, sub, s, q);
+    if (c >= C || sub != 0) return;
     const double mean = s / (double)M;
     double var = q / (double)M - mean * mean;
     if (var < 0) var = 0;
@@ -162,26 +177,25 @@ __global__ void bn_stats_finalize_kernel(const float* __restrict__ partial, int 
 }
 
 // dgamma = sum dy'*xhat, dbeta = sum dy'; coef = {dbeta/M, dgamma/M}
-__global__ void bn_bwd_finalize_kernel(const float* __restrict__ partial, int row_blocks, int64_t M, int C,
-                                       float* __restrict__ dgamma, float* __restrict__ dbeta, float* __restrict__ coef) {
-    const int c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c >= C) return;
-    double s = 0, q = 0;
-    for (int j = 0; j < row_blocks; ++j) {
-        s += (double)partial[((int64_t)j * 2 + 0) * C + c];
-        q += (double)partial[((int64_t)j * 2 + 1) * C + c];
-    }
+__global__ __launch_bounds__(256) void bn_bwd_finalize_kernel(const float* __restrict__ partial, int row_blocks, int64_t M,
+                                                              int C, float* __restrict__ dgamma, float* __restrict__ dbeta,
+                                                              float* __restrict__ coef) {
+    const int c = blockIdx.x * 8 + (threadIdx.x >> 5), sub = threadIdx.x & 31;
+    double s, q;
+    sum_partials(partial, row_blocks, C, c, sub, s, q);
+    if (c >= C || sub != 0) return;
     dbeta[c] = (float)s;
     dgamma[c] = (float)q;
     coef[c] = (float)(s / (double)M);
     coef[C + c] = (float)(q / (double)M);
 }
 
-__global__ void bias_finalize_kernel(const float* __restrict__ partial, int row_blocks, int C, float* __restrict__ dbias) {
-    const int c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c >= C) return;
-    double s = 0;
-    for (int j = 0; j < row_blocks; ++j) s += (double)partial[((int64_t)j * 2 + 0) * C + c];
+__global__ __launch_bounds__(256) void bias_finalize_kernel(const float* __restrict__ partial, int row_blocks, int C,
+                                                            float* __restrict__ dbias) {
+    const int c = blockIdx.x * 8 + (threadIdx.x >> 5), sub = threadIdx.x & 31;
+    double s, q;
+    sum_partials(partial, row_blocks, C, c, sub, s, q);
+    if (c >= C || sub != 0) return;
     dbias[c] = (float)s;
 }
 
@@ -275,7 +289,7 @@ static void bn_forward_t(const void* x, const void* res, void* y, const float* g
     hipLaunchKernelGGL((colreduce_kernel<T, VEC, 0>), s.grid, s.block, 0, st, (const T*)x, (const T*)nullptr, (T*)nullptr,
                        (const float*)nullptr, M, C, s.rows_per_block, 0, partial);
     }
-    hipLaunchKernelGGL(bn_stats_finalize_kernel, dim3((C + 127) / 128), dim3(128), 0, st, partial, s.row_blocks, M, C,
+    hipLaunchKernelGGL(bn_stats_finalize_kernel, dim3((C + 7) / 8), dim3(256), 0, st, partial, s.row_blocks, M, C,
                        save, running);
     ProfScope ps("bn_apply", 0.0, tb * (res ? 3.0 : 2.0), st);
     hipLaunchKernelGGL((bn_apply_kernel<T, VEC>), dim3(ew_grid(M * s.cvecs)), dim3(256), 0, st, (const T*)x,
@@ -304,7 +318,7 @@ static void bn_backward_t(const void* x, const void* y, const void* dy, void* dx
     hipLaunchKernelGGL((colreduce_kernel<T, VEC, 1>), s.grid, s.block, 0, st, (const T*)x, (const T*)y, (T*)dy, save, M, C,
                        s.rows_per_block, relu ? 1 : 0, partial);
     }
-    hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3((C + 127) / 128), dim3(128), 0, st, partial, s.row_blocks, M, C,
+    hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3((C + 7) / 8), dim3(256), 0, st, partial, s.row_blocks, M, C,
                        dgamma, dbeta, coef);
     ProfScope ps("bn_bwd_apply", 0.0, tb * ((relu ? 3.0 : 2.0) + 1.0 + (dres ? (dres_acc ? 2.0 : 1.0) : 0.0)), st);
     hipLaunchKernelGGL((bn_bwd_apply_kernel<T, VEC>), dim3(ew_grid(M * s.cvecs)), dim3(256), 0, st, (const T*)x,
@@ -333,7 +347,7 @@ static void bias_relu_backward_t(const void* y, void* dy, float* dbias, int64_t 
     hipLaunchKernelGGL((colreduce_kernel<T, VEC, 2>), s.grid, s.block, 0, st, (const T*)nullptr, (const T*)y, (T*)dy,
                        (const float*)nullptr, M, C, s.rows_per_block, relu ? 1 : 0, partial);
     if (dbias)
-        hipLaunchKernelGGL(bias_finalize_kernel, dim3((C + 127) / 128), dim3(128), 0, st, partial, s.row_blocks, C, dbias);
+        hipLaunchKernelGGL(bias_finalize_kernel, dim3((C + 7) / 8), dim3(256), 0, st, partial, s.row_blocks, C, dbias);
 }
 
 void launch_bias_relu_backward(int dtype, const void* y, void* dy, float* dbias, int64_t M, int C, bool relu,

@@ -9,7 +9,7 @@
 namespace edl {
 
 constexpr int kMaxP = 16;           // gradient buffers one update launch can average
-constexpr int kRedRowBlocks = 64;   // upper bound of row blocks in column reductions
+constexpr int kRedRowBlocks = 1024;   // upper bound of row blocks in column reductions
 
 struct GradPtrs { const float* g[kMaxP]; };
 
