@@ -173,7 +173,7 @@ def edl_profile_report():
     """List of dicts {name, launches, ms, flops, bytes}: totals since profiling was switched on
     (or since the last report)."""
     import json
-    buf = C.create_string_buffer(1 << 16)
+    buf = C.create_string_buffer(1 << 18)
     need = C.c_size_t()
     _check(lib.edl_profile_report(buf, len(buf), C.byref(need)))
     return json.loads(buf.value.decode())

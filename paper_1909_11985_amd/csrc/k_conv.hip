@@ -21,6 +21,11 @@
 // reduction index (the pixel) is the slow index in memory, so its tiles are
 // transposed on the way into LDS; its reduction is cut into splits whose
 // float32 partial tiles are added by a second kernel in split order.
+#include <cstdio>
+#include <cstdlib>
+#include <deque>
+#include <string>
+
 #include "dev_common.h"
 #include "kernels.h"
 #include "profiler.h"
@@ -171,7 +176,11 @@ __device__ __forceinline__ unsigned a_voffset(const ConvArgs& a, const RowCtx& c
 //   wgrad:           32-bit words [reduction word][row], a word holding the reduction elements 2q, 2q+1
 //                    of one row for bf16 (one element for float32); a fragment is four one-word reads,
 //                    and the global vectors (channels innermost) go in without any 16-bit scatter.
-template <typename T, int MODE, int WM, int WN, int TM, int TN, int BK>
+// FAST: both operands take the 16-byte vector loads and the output width is a
+// multiple of a vector, so the kernel has no element-wise paths at all (a
+// run-time choice between the two inside the loop would force a wait after
+// every load).
+template <typename T, int MODE, int WM, int WN, int TM, int TN, int BK, bool FAST>
 __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
     constexpr bool WG = MODE == CONV_WGRAD;
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
@@ -195,7 +204,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
     constexpr int SMEM_BYTES = TILE_BYTES > STAGE_BYTES ? TILE_BYTES : STAGE_BYTES;
     static_assert(WM * WN == 4, "four waves per workgroup");
     static_assert(256 % KV == 0 && 256 % RVA == 0 && 256 % RVB == 0, "per-thread column of the tile must be fixed");
-    static_assert(KD == 32, "four fragment groups of eight words");
+    static_assert(!WG || KD == 32, "wgrad: four fragment groups of eight words");
 
     __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM_BYTES];
     unsigned char* const As = smem;                  // [2] stages
@@ -271,7 +280,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
             for (int it = 0; it < ITER_A; ++it) {
                 ra[it].u = make_uint4(0, 0, 0, 0);
                 if (TOT_A % 256 != 0 && tid + it * 256 >= TOT_A) continue;
-                if (a.vecA) {
+                if (FAST || a.vecA) {
                     ra[it].u = buffer_load16(rsrcA, a_voffset<MODE, T>(a, rowA[it], tr, ts, tc, tap_off, in_k));
                 } else {
                     #pragma unroll
@@ -285,7 +294,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
             #pragma unroll
             for (int it = 0; it < ITER_B; ++it) {
                 rb[it].u = make_uint4(0, 0, 0, 0);
-                if (a.vecB) {
+                if (FAST || a.vecB) {
                     rb[it].u = buffer_load16(rsrcB, (okB[it] && in_k) ? (unsigned)((int)offB[it] + kcur) * (unsigned)sizeof(T) : kOutOfRange);
                 } else if (okB[it]) {
                     #pragma unroll
@@ -316,7 +325,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
                     Vec16<T>& dst = ra[it * KPD + pp];
                     dst.u = make_uint4(0, 0, 0, 0);
                     const bool ok = live && mm + pp < kend;
-                    if (a.vecA) {
+                    if (FAST || a.vecA) {
                         dst.u = buffer_load16(rsrcA, (ok && row0 < a.M) ? (unsigned)((int)offA[it] + pp * a.K) * (unsigned)sizeof(T) : kOutOfRange);
                     } else if (ok) {
                         #pragma unroll
@@ -337,7 +346,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
                     dst.u = make_uint4(0, 0, 0, 0);
                     const bool okp = live && mm + pp < kend;
                     const int hb = qho * a.stride - a.pad, wb = qwo * a.stride - a.pad;
-                    if (a.vecB) {
+                    if (FAST || a.vecB) {
                         const int j0 = n0 + (tid % RVB) * VEC;
                         const int h = hb + wg_r, w = wb + wg_s;
                         const bool ok = okp && j0 < a.Nn && (unsigned)h < (unsigned)a.H && (unsigned)w < (unsigned)a.W;
@@ -447,8 +456,9 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
     for (int kt = 0; kt < nk; ++kt) {
         const int buf = kt & 1;
         if (kt + 1 < nk) load_tiles();
+        constexpr int NG = WG ? 4 : BK / (2 * VEC);   // fragment groups per tile
         #pragma unroll
-        for (int g = 0; g < 4; ++g) {
+        for (int g = 0; g < NG; ++g) {
             uint4 fa[TM], fb[TN];
             if (!WG) {
                 constexpr int KG = 2 * VEC;  // reduction elements one fragment pair covers
@@ -488,7 +498,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
     constexpr int OSZ = OUT_F32 ? 4 : 2;
     constexpr int OVEC = 16 / OSZ;
     const bool direct_f32 = (MODE == CONV_FWD) && a.out_fp32 && !OUT_F32;
-    if ((a.Nn % OVEC) != 0 || direct_f32) {
+    if (!FAST && ((a.Nn % OVEC) != 0 || direct_f32)) {
         // ragged width (or float32 logits from a bf16 net): element-wise stores
         #pragma unroll
         for (int i = 0; i < TM; ++i) {
@@ -621,13 +631,17 @@ static TileCfg pick_tile(int M, int Nn, int* bm, int* bn) {
 }
 
 template <typename T, int MODE>
-static void launch_cfg(TileCfg t, dim3 grid, const ConvArgs& a, hipStream_t st) {
+static void launch_cfg(TileCfg t, bool fast, dim3 grid, const ConvArgs& a, hipStream_t st) {
     constexpr int BK = kConvBK<T>;
+    if (!fast) {   // element-wise kernel: one tile shape only
+        hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 1, 1, BK, false>), grid, dim3(256), 0, st, a);
+        return;
+    }
     switch (t) {
-        case T128x128: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 2, 2, BK>), grid, dim3(256), 0, st, a); break;
-        case T128x64: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 2, 1, BK>), grid, dim3(256), 0, st, a); break;
-        case T128x32: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 4, 1, 1, 1, BK>), grid, dim3(256), 0, st, a); break;
-        default: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 1, 1, BK>), grid, dim3(256), 0, st, a); break;
+        case T128x128: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 2, 2, BK, true>), grid, dim3(256), 0, st, a); break;
+        case T128x64: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 2, 1, BK, true>), grid, dim3(256), 0, st, a); break;
+        case T128x32: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 4, 1, 1, 1, BK, true>), grid, dim3(256), 0, st, a); break;
+        default: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 1, 1, BK, true>), grid, dim3(256), 0, st, a); break;
     }
 }
 
@@ -642,8 +656,20 @@ static const char* conv_label(int dtype, int mode, TileCfg t) {
     return names[dtype == 1 ? 1 : 0][mode][(int)t];
 }
 
+static bool conv_fast(int dtype, int mode, const ConvArgs& a) {
+    const int ovec = (mode == CONV_WGRAD || dtype != 1) ? 4 : 8;
+    const bool direct_f32 = mode == CONV_FWD && a.out_fp32 && dtype == 1;
+    return a.vecA && a.vecB && a.Nn % ovec == 0 && !direct_f32;
+}
+
 template <int MODE>
 static void launch_mode(int dtype, TileCfg t, dim3 grid, const ConvArgs& a, hipStream_t st) {
+    const bool fast = conv_fast(dtype, MODE, a);
+    if (!fast) {
+        t = T64x64;
+        grid.x = (a.M + 63) / 64;
+        grid.y = (a.Nn + 63) / 64;
+    }
     // algorithmic work: 2*M*N*K flops; operands and result touched once
     const double esz = dtype == 1 ? 2.0 : 4.0;
     const double flops = 2.0 * (double)a.M * a.Nn * a.Kred;
@@ -651,9 +677,21 @@ static void launch_mode(int dtype, TileCfg t, dim3 grid, const ConvArgs& a, hipS
     if (MODE == CONV_FWD) bytes = esz * ((double)a.N * a.H * a.W * a.C + (double)a.Nn * a.Kred) + (a.out_fp32 ? 4.0 : esz) * (double)a.M * a.Nn;
     else if (MODE == CONV_DGRAD) bytes = esz * ((double)a.N * a.Ho * a.Wo * a.K + (double)a.Nn * a.Kred + (double)a.M * a.Nn);
     else bytes = esz * ((double)a.Kred * a.K + (double)a.N * a.H * a.W * a.C) + 4.0 * (double)a.M * a.Nn;
-    ProfScope ps(conv_label(dtype, MODE, t), flops, bytes, st);
-    if (dtype == 1) launch_cfg<bf16_t, MODE>(t, grid, a, st);
-    else launch_cfg<float, MODE>(t, grid, a, st);
+    const char* label = conv_label(dtype, MODE, t);
+    static const bool by_shape = getenv("EDL_PROFILE_BY_SHAPE") != nullptr;
+    if (by_shape && prof_enabled()) {
+        // one profile line per distinct problem shape instead of per kernel family
+        static std::deque<std::string> names;
+        char buf[160];
+        snprintf(buf, sizeof(buf), "%s M=%d N=%d K=%d r%d s%d grid=%ux%ux%u", label, a.M, a.Nn, a.Kred, a.R, a.stride, grid.x, grid.y, grid.z);
+        const char* found = nullptr;
+        for (const std::string& n : names) if (n == buf) { found = n.c_str(); break; }
+        if (!found) { names.emplace_back(buf); found = names.back().c_str(); }
+        label = found;
+    }
+    ProfScope ps(label, flops, bytes, st);
+    if (dtype == 1) launch_cfg<bf16_t, MODE>(t, fast, grid, a, st);
+    else launch_cfg<float, MODE>(t, fast, grid, a, st);
 }
 
 static ConvArgs base_args(const ConvGeom& g) {
