@@ -45,6 +45,7 @@ struct Layout {
     int64_t params = 0, momentum = 0, running = 0, shadow = 0, grads = 0, grad_stride = 0;
     int64_t idx = 0, labels = 0, row_loss = 0, losses = 0, partial = 0, coef = 0, wgrad_scratch = 0;
     int64_t wgrad_scratch_bytes = 0;
+    int64_t ttable = 0;                  // TransposeEntry[] for the one-launch weight transpose
     std::vector<int64_t> act, grad;      // per tensor (storage owners only; -1 otherwise)
     std::vector<int64_t> wT;             // per op: transposed weight copy (-1 if not needed)
     std::vector<int64_t> bn_save;        // per op
@@ -119,6 +120,7 @@ void plan_layout(const edl_config& c, const Graph& g, Layout& L) {
         }
     }
     L.wgrad_scratch = take(std::max<int64_t>(L.wgrad_scratch_bytes, 16));
+    L.ttable = take((int64_t)sizeof(TransposeEntry) * std::max<size_t>(no, 1));
     L.total = o;
 }
 
@@ -138,6 +140,8 @@ struct edl_handle {
     // cached permutation of the current epoch
     int64_t perm_epoch = -1;
     std::vector<int64_t> perm;
+    int t_entries = 0, t_tiles = 0;      // one-launch weight transpose
+    double t_bytes = 0;
     // pinned staging
     int64_t* idx_host[kIdxSlots] = {nullptr, nullptr, nullptr, nullptr};
     hipEvent_t idx_event[kIdxSlots];
@@ -234,12 +238,8 @@ static int refresh_weight_copies(edl_handle* h) {
 }
 
 static void transpose_weights(edl_handle* h) {
-    for (size_t i = 0; i < h->g.ops.size(); ++i) {
-        const Op& op = h->g.ops[i];
-        if (op.kind != OP_CONV || h->L.wT[i] < 0) continue;
-        const Tensor& tx = h->g.tensors[(size_t)op.x];
-        launch_weight_transpose(h->cfg.dtype, h->w() + op.w_off, h->arena + h->L.wT[i], op.K, op.R * op.S, tx.C, h->st);
-    }
+    launch_weight_transpose_all(h->cfg.dtype, h->w(), h->arena, h->at<TransposeEntry>(h->L.ttable), h->t_entries,
+                                h->t_tiles, h->t_bytes, h->st);
 }
 
 int32_t edl_init(edl_handle** out, const edl_config* cfg, uint64_t seed, void* dev_arena, size_t arena_bytes,
@@ -276,7 +276,27 @@ int32_t edl_init(edl_handle** out, const edl_config* cfg, uint64_t seed, void* d
             launch_fill_f32(h->running() + op.run_off, 0.f, op.K, h->st);
             launch_fill_f32(h->running() + op.run_off + op.K, 1.f, op.K, h->st);
         }
-    HIP_TRY(hipStreamSynchronize(h->st));   // init[] leaves scope
+    {
+        std::vector<TransposeEntry> tab;
+        const double esz = cfg->dtype == EDL_DTYPE_BF16 ? 2.0 : 4.0;
+        for (size_t i = 0; i < h->g.ops.size(); ++i) {
+            const Op& op = h->g.ops[i];
+            if (op.kind != OP_CONV || h->L.wT[i] < 0) continue;
+            const Tensor& tx = h->g.tensors[(size_t)op.x];
+            TransposeEntry te;
+            te.src_off = op.w_off; te.dst_off = h->L.wT[i];
+            te.K = op.K; te.RS = op.R * op.S; te.C = tx.C;
+            te.tile_start = h->t_tiles;
+            h->t_tiles += ((te.C + 31) / 32) * ((te.K + 31) / 32) * te.RS;
+            h->t_bytes += (4.0 + esz) * (double)te.K * te.RS * te.C;
+            tab.push_back(te);
+        }
+        h->t_entries = (int)tab.size();
+        if (!tab.empty())
+            HIP_TRY(hipMemcpyAsync(h->at<TransposeEntry>(h->L.ttable), tab.data(), sizeof(TransposeEntry) * tab.size(),
+                                   hipMemcpyHostToDevice, h->st));
+        HIP_TRY(hipStreamSynchronize(h->st));   // init[] and tab[] leave scope
+    }
     h->weights_dirty = true;
     HIP_TRY(hipGetLastError());
     *out = h;

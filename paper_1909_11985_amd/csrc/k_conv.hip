@@ -46,6 +46,13 @@ struct ConvArgs {
     int vecA, vecB;
     int ksplit;  // reduction elements per blockIdx.z
     unsigned bytesA, bytesB;  // extents of the two operands (for the range-checked vector loads)
+    // dgrad of a strided convolution, one launch per residue class of the input
+    // pixel (h % stride, w % stride) = (ph, pw): only the taps r = r0, r0+stride, ...
+    // (nr of them) and s = s0, ... (ns) reach such a pixel, so the reduction runs
+    // over nr*ns*K instead of R*S*K.  Hc x Wc pixels per image are in the class.
+    // For stride 1 (and the other modes): ph = pw = r0 = s0 = 0, nr = R, ns = S.
+    int ph, pw, Hc, Wc, r0, s0, nr, ns;
+    int ldb;     // fwd/dgrad: elements between consecutive rows of B
 };
 
 // 16-byte load through a buffer descriptor: an offset at or beyond the
@@ -97,11 +104,11 @@ __device__ __forceinline__ RowCtx make_row(const ConvArgs& a, int m) {
         c.w0 = wo * a.stride - a.pad;
         c.base = (((int64_t)n * a.H + c.h0) * a.W + c.w0) * a.C;
     } else {
-        const int hw = a.H * a.W;
+        const int hw = a.Hc * a.Wc;
         const int n = m / hw, rem = m - n * hw;
-        const int h = rem / a.W, w = rem - h * a.W;
-        c.h0 = h + a.pad;
-        c.w0 = w + a.pad;
+        const int hq = rem / a.Wc, wq = rem - hq * a.Wc;
+        c.h0 = a.ph + hq * a.stride + a.pad;
+        c.w0 = a.pw + wq * a.stride + a.pad;
         c.base = (int64_t)n * a.Ho * a.Wo * a.K;
     }
     return c;
@@ -138,7 +145,9 @@ template <int MODE>
 __device__ __forceinline__ int64_t a_offset(const ConvArgs& a, const RowCtx& c, int kk, bool& ok) {
     const int inner = MODE == CONV_FWD ? a.C : a.K;
     const int tap = kk / inner, ch = kk - tap * inner;
-    const int r = tap / a.S, s = tap - r * a.S;
+    int r, s;
+    if (MODE == CONV_FWD) { r = tap / a.S; s = tap - r * a.S; }
+    else { const int ri = tap / a.ns; r = a.r0 + ri * a.stride; s = a.s0 + (tap - ri * a.ns) * a.stride; }
     const int64_t off = a_offset_tap<MODE>(a, c, r, s, ch, ok);
     ok = ok && kk < a.Kred;
     return off;
@@ -168,6 +177,17 @@ __device__ __forceinline__ unsigned a_voffset(const ConvArgs& a, const RowCtx& c
         const bool ok = in_k && c.valid && (hn | wn) >= 0 && on_grid && ho < a.Ho && wo < a.Wo;
         return ok ? (unsigned)((int)c.base + (ho * a.Wo + wo) * a.K + ch) * (unsigned)sizeof(T) : kOutOfRange;
     }
+}
+
+// Row of the output matrix a tile row is stored to: the tile row itself, except
+// for a residue class of a strided dgrad, whose rows are every stride-th pixel.
+template <int MODE>
+__device__ __forceinline__ int64_t out_row(const ConvArgs& a, int row) {
+    if (MODE != CONV_DGRAD || a.stride == 1) return row;
+    const int hw = a.Hc * a.Wc;
+    const int n = row / hw, rem = row - n * hw;
+    const int hq = rem / a.Wc, wq = rem - hq * a.Wc;
+    return ((int64_t)n * a.H + a.ph + hq * a.stride) * a.W + a.pw + wq * a.stride;
 }
 
 // Tile storage in LDS
@@ -238,16 +258,23 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
         kcur = kbeg + (tid % KV) * VEC;
         const int tap = kcur / inner;
         tc = kcur - tap * inner;
-        tr = tap / a.S;
-        ts = tap - tr * a.S;
-        tap_off = (tr * a.W + ts) * a.C + tc;
+        if (MODE == CONV_FWD) {
+            tr = tap / a.S;
+            ts = tap - tr * a.S;
+            tap_off = (tr * a.W + ts) * a.C + tc;
+        } else {
+            const int ri = a.ns > 0 ? tap / a.ns : 0;
+            tr = a.r0 + ri * a.stride;
+            ts = a.s0 + (tap - ri * a.ns) * a.stride;
+            tap_off = (tr * a.S + ts) * a.K + tc;      // position inside a row of the transposed weights
+        }
         #pragma unroll
         for (int it = 0; it < ITER_A; ++it) rowA[it] = make_row<MODE>(a, m0 + (tid + it * 256) / KV);
         #pragma unroll
         for (int it = 0; it < ITER_B; ++it) {
             const int j = n0 + (tid + it * 256) / KV;
             okB[it] = j < a.Nn && (tid + it * 256) < TOT_B;
-            offB[it] = (int64_t)j * a.Kred;
+            offB[it] = (int64_t)j * a.ldb;
         }
     } else {
         const int j0 = n0 + (tid % RVB) * VEC;
@@ -295,11 +322,18 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
             for (int it = 0; it < ITER_B; ++it) {
                 rb[it].u = make_uint4(0, 0, 0, 0);
                 if (FAST || a.vecB) {
-                    rb[it].u = buffer_load16(rsrcB, (okB[it] && in_k) ? (unsigned)((int)offB[it] + kcur) * (unsigned)sizeof(T) : kOutOfRange);
+                    const int boff = MODE == CONV_FWD ? kcur : tap_off;
+                    rb[it].u = buffer_load16(rsrcB, (okB[it] && in_k) ? (unsigned)((int)offB[it] + boff) * (unsigned)sizeof(T) : kOutOfRange);
                 } else if (okB[it]) {
                     #pragma unroll
-                    for (int e = 0; e < VEC; ++e)
-                        if (kcur + e < kend) rb[it].e[e] = Bg[offB[it] + kcur + e];
+                    for (int e = 0; e < VEC; ++e) {
+                        int boff = kcur + e;
+                        if (MODE == CONV_DGRAD) {
+                            const int tap = (kcur + e) / a.K, ri = a.ns > 0 ? tap / a.ns : 0;
+                            boff = ((a.r0 + ri * a.stride) * a.S + a.s0 + (tap - ri * a.ns) * a.stride) * a.K + (kcur + e - tap * a.K);
+                        }
+                        if (kcur + e < kend) rb[it].e[e] = Bg[offB[it] + boff];
+                    }
                 }
             }
             // advance this thread's vector by BK along (r, s, channel)
@@ -308,11 +342,20 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
             tc += BK;
             tap_off += BK;
             if (tc >= inner) {
-                do {
-                    tc -= inner;
-                    if (++ts == a.S) { ts = 0; ++tr; }
-                } while (tc >= inner);
-                tap_off = (tr * a.W + ts) * a.C + tc;
+                if (MODE == CONV_FWD) {
+                    do {
+                        tc -= inner;
+                        if (++ts == a.S) { ts = 0; ++tr; }
+                    } while (tc >= inner);
+                    tap_off = (tr * a.W + ts) * a.C + tc;
+                } else {
+                    do {
+                        tc -= inner;
+                        ts += a.stride;
+                        if (ts >= a.S) { ts = a.s0; tr += a.stride; }
+                    } while (tc >= inner);
+                    tap_off = (tr * a.S + ts) * a.K + tc;
+                }
             }
         } else {
             #pragma unroll
@@ -519,7 +562,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
                         if (a.out_fp32) ((float*)a.out)[o] = v;
                         else ((T*)a.out)[o] = Elem<T>::from_f32(v);
                     } else if (MODE == CONV_DGRAD) {
-                        const int64_t o = (int64_t)row * a.Nn + col;
+                        const int64_t o = out_row<MODE>(a, row) * a.Nn + col;
                         T* dst = (T*)a.out;
                         if (a.accumulate) v += Elem<T>::to_f32(dst[o]);
                         dst[o] = Elem<T>::from_f32(v);
@@ -566,7 +609,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
             const int row = m0 + pass * STAGE_ROWS + rl, col = n0 + cv * OVEC;
             if (row < a.M && col < a.Nn) {
                 const float* sp = stage + rl * STAGE_LD + cv * OVEC;
-                unsigned char* dst = outp + ((int64_t)row * a.Nn + col) * OSZ;
+                unsigned char* dst = outp + (out_row<MODE>(a, row) * a.Nn + col) * OSZ;
                 if (OUT_F32) {
                     float4 o = *reinterpret_cast<const float4*>(sp);
                     if (MODE == CONV_DGRAD && a.accumulate) {
@@ -594,14 +637,37 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
     }
 }
 
-// dw[i] = sum over splits, in split order
+// dw[i] = sum over splits, in split order.  One 16-byte vector per lane and
+// split (the splits' loads are independent, so they are all in flight together).
+template <int VECW>
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restrict__ part, float* __restrict__ dw, int64_t n,
                                                            int splits) {
+    const int64_t nv = n / VECW;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
-        float s = part[i];
-        for (int k = 1; k < splits; ++k) s += part[(int64_t)k * n + i];
-        dw[i] = s;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nv; i += stride) {
+        if (VECW == 4) {
+            float4 s = reinterpret_cast<const float4*>(part)[i];
+            int k = 1;
+            for (; k + 3 < splits; k += 4) {
+                const float4 t0 = reinterpret_cast<const float4*>(part + (int64_t)k * n)[i];
+                const float4 t1 = reinterpret_cast<const float4*>(part + (int64_t)(k + 1) * n)[i];
+                const float4 t2 = reinterpret_cast<const float4*>(part + (int64_t)(k + 2) * n)[i];
+                const float4 t3 = reinterpret_cast<const float4*>(part + (int64_t)(k + 3) * n)[i];
+                s.x += t0.x; s.y += t0.y; s.z += t0.z; s.w += t0.w;
+                s.x += t1.x; s.y += t1.y; s.z += t1.z; s.w += t1.w;
+                s.x += t2.x; s.y += t2.y; s.z += t2.z; s.w += t2.w;
+                s.x += t3.x; s.y += t3.y; s.z += t3.z; s.w += t3.w;
+            }
+            for (; k < splits; ++k) {
+                const float4 t = reinterpret_cast<const float4*>(part + (int64_t)k * n)[i];
+                s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+            }
+            reinterpret_cast<float4*>(dw)[i] = s;
+        } else {
+            float s = part[i];
+            for (int k = 1; k < splits; ++k) s += part[(int64_t)k * n + i];
+            dw[i] = s;
+        }
     }
 }
 
@@ -698,6 +764,7 @@ static ConvArgs base_args(const ConvGeom& g) {
     ConvArgs a = {};
     a.N = g.N; a.H = g.H; a.W = g.W; a.C = g.C; a.K = g.K; a.R = g.R; a.S = g.S;
     a.stride = g.stride; a.pad = g.pad; a.Ho = g.Ho; a.Wo = g.Wo;
+    a.ph = a.pw = a.r0 = a.s0 = 0; a.nr = g.R; a.ns = g.S; a.Hc = g.H; a.Wc = g.W;
     return a;
 }
 
@@ -713,6 +780,7 @@ void launch_conv_fwd(int dtype, const ConvGeom& g, const void* x, const void* w,
     a.vecA = (g.C % VEC == 0) && bA < 2147483648.0; a.vecB = (a.Kred % VEC == 0) && bB < 2147483648.0;
     a.bytesA = a.vecA ? (unsigned)bA : 0; a.bytesB = a.vecB ? (unsigned)bB : 0;
     a.ksplit = a.Kred;
+    a.ldb = a.Kred;
     int bm, bn;
     const TileCfg t = pick_tile(a.M, a.Nn, &bm, &bn);
     launch_mode<CONV_FWD>(dtype, t, dim3((a.M + bm - 1) / bm, (a.Nn + bn - 1) / bn, 1), a, st);
@@ -723,16 +791,32 @@ void launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dy, const void*
     const int VEC = dtype == 1 ? 8 : 4;
     ConvArgs a = base_args(g);
     a.A = dy; a.B = wT; a.out = dx;
-    a.M = g.N * g.H * g.W; a.Nn = g.C; a.Kred = g.R * g.S * g.K;
+    a.Nn = g.C;
+    a.ldb = g.R * g.S * g.K;
     a.accumulate = accumulate;
     const double esz = dtype == 1 ? 2.0 : 4.0;
-    const double bA = esz * (double)g.N * g.Ho * g.Wo * g.K, bB = esz * (double)a.Nn * a.Kred;
-    a.vecA = (g.K % VEC == 0) && bA < 2147483648.0; a.vecB = (a.Kred % VEC == 0) && bB < 2147483648.0;
+    const double bA = esz * (double)g.N * g.Ho * g.Wo * g.K, bB = esz * (double)a.Nn * a.ldb;
+    a.vecA = (g.K % VEC == 0) && bA < 2147483648.0; a.vecB = (a.ldb % VEC == 0) && bB < 2147483648.0;
     a.bytesA = a.vecA ? (unsigned)bA : 0; a.bytesB = a.vecB ? (unsigned)bB : 0;
-    a.ksplit = a.Kred;
-    int bm, bn;
-    const TileCfg t = pick_tile(a.M, a.Nn, &bm, &bn);
-    launch_mode<CONV_DGRAD>(dtype, t, dim3((a.M + bm - 1) / bm, (a.Nn + bn - 1) / bn, 1), a, st);
+    // one launch per residue class of the input pixel modulo the stride
+    for (int ph = 0; ph < g.stride && ph < g.H; ++ph) {
+        for (int pw = 0; pw < g.stride && pw < g.W; ++pw) {
+            a.ph = ph; a.pw = pw;
+            a.Hc = (g.H - ph + g.stride - 1) / g.stride;
+            a.Wc = (g.W - pw + g.stride - 1) / g.stride;
+            a.r0 = (ph + g.pad) % g.stride;
+            a.s0 = (pw + g.pad) % g.stride;
+            a.nr = a.r0 < g.R ? (g.R - a.r0 + g.stride - 1) / g.stride : 0;
+            a.ns = a.s0 < g.S ? (g.S - a.s0 + g.stride - 1) / g.stride : 0;
+            a.M = g.N * a.Hc * a.Wc;
+            a.Kred = a.nr * a.ns * g.K;
+            a.ksplit = a.Kred > 0 ? a.Kred : 1;
+            if (a.Kred == 0 && accumulate) continue;      // nothing reaches these pixels
+            int bm, bn;
+            const TileCfg t = pick_tile(a.M, a.Nn, &bm, &bn);
+            launch_mode<CONV_DGRAD>(dtype, t, dim3((a.M + bm - 1) / bm, (a.Nn + bn - 1) / bn, 1), a, st);
+        }
+    }
 }
 
 struct WgradPlan {
@@ -802,10 +886,17 @@ void launch_conv_wgrad(int dtype, const ConvGeom& g, const void* x, const void* 
     const dim3 grid((a.M + p.bm - 1) / p.bm, (a.Nn + p.bn - 1) / p.bn, direct ? 1 : p.splits);
     launch_mode<CONV_WGRAD>(dtype, p.t, grid, a, st);
     if (!direct) {
-        int64_t blocks = (n + 255) / 256;
-        if (blocks > 4096) blocks = 4096;
         ProfScope ps("wgrad_reduce", 0.0, 4.0 * (double)n * (p.splits + 1), st);
-        hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((int)blocks), dim3(256), 0, st, scratch, dw, n, p.splits);
+        // dw may sit at any float offset of the flat gradient vector: vectors only if it is 16-byte aligned
+        if (n % 4 == 0 && ((uintptr_t)dw & 15) == 0) {
+            int64_t blocks = (n / 4 + 255) / 256;
+            if (blocks > 8192) blocks = 8192;
+            hipLaunchKernelGGL(wgrad_reduce_kernel<4>, dim3((int)blocks), dim3(256), 0, st, scratch, dw, n, p.splits);
+        } else {
+            int64_t blocks = (n + 255) / 256;
+            if (blocks > 8192) blocks = 8192;
+            hipLaunchKernelGGL(wgrad_reduce_kernel<1>, dim3((int)blocks), dim3(256), 0, st, scratch, dw, n, p.splits);
+        }
     }
 }
 

@@ -81,11 +81,113 @@ __global__ __launch_bounds__(256) void maxpool_bwd_kernel(const T* __restrict__ 
     }
 }
 
+// 16-byte channel vectors per lane (C a multiple of the vector width)
+template <typename T>
+__global__ __launch_bounds__(256) void maxpool_fwd_vec_kernel(const T* __restrict__ x, T* __restrict__ y,
+                                                              uint8_t* __restrict__ arg, int N, int H, int W, int C, int k,
+                                                              int stride, int pad, int Ho, int Wo) {
+    constexpr int VEC = Elem<T>::VEC;
+    const int cv = C / VEC;
+    const int64_t total = (int64_t)N * Ho * Wo * cv;
+    const int64_t step = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += step) {
+        const int c0 = (int)(i % cv) * VEC;
+        int64_t t = i / cv;
+        const int wo = (int)(t % Wo); t /= Wo;
+        const int ho = (int)(t % Ho);
+        const int n = (int)(t / Ho);
+        float best[VEC];
+        int where[VEC];
+        #pragma unroll
+        for (int e = 0; e < VEC; ++e) { best[e] = 0.f; where[e] = 255; }
+        for (int r = 0; r < k; ++r) {
+            const int h = ho * stride - pad + r;
+            if (h < 0 || h >= H) continue;
+            for (int s = 0; s < k; ++s) {
+                const int w = wo * stride - pad + s;
+                if (w < 0 || w >= W) continue;
+                const Vec16<T> v = load_vec(x + (((int64_t)n * H + h) * W + w) * C + c0);
+                #pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    const float f = Elem<T>::to_f32(v.e[e]);
+                    if (where[e] == 255 || f > best[e]) { best[e] = f; where[e] = r * k + s; }
+                }
+            }
+        }
+        const int64_t o = ((((int64_t)n * Ho + ho) * Wo + wo) * C) + c0;
+        Vec16<T> out;
+        #pragma unroll
+        for (int e = 0; e < VEC; ++e) { out.e[e] = Elem<T>::from_f32(best[e]); arg[o + e] = (uint8_t)where[e]; }
+        store_vec(y + o, out);
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void maxpool_bwd_vec_kernel(const T* __restrict__ dy, const uint8_t* __restrict__ arg,
+                                                              T* dx, int accumulate, int N, int H, int W, int C, int k,
+                                                              int stride, int pad, int Ho, int Wo) {
+    constexpr int VEC = Elem<T>::VEC;
+    const int cv = C / VEC;
+    const int64_t total = (int64_t)N * H * W * cv;
+    const int64_t step = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += step) {
+        const int c0 = (int)(i % cv) * VEC;
+        int64_t t = i / cv;
+        const int w = (int)(t % W); t /= W;
+        const int h = (int)(t % H);
+        const int n = (int)(t / H);
+        float g[VEC];
+        #pragma unroll
+        for (int e = 0; e < VEC; ++e) g[e] = 0.f;
+        for (int r = 0; r < k; ++r) {
+            const int hn = h + pad - r;
+            if (hn < 0 || hn % stride) continue;
+            const int ho = hn / stride;
+            if (ho >= Ho) continue;
+            for (int s = 0; s < k; ++s) {
+                const int wn = w + pad - s;
+                if (wn < 0 || wn % stride) continue;
+                const int wo = wn / stride;
+                if (wo >= Wo) continue;
+                const int64_t o = (((int64_t)n * Ho + ho) * Wo + wo) * C + c0;
+                const Vec16<T> v = load_vec(dy + o);
+                uint8_t am[VEC];
+                if (VEC == 8) *reinterpret_cast<uint2*>(am) = *reinterpret_cast<const uint2*>(arg + o);
+                else *reinterpret_cast<uint32_t*>(am) = *reinterpret_cast<const uint32_t*>(arg + o);
+                #pragma unroll
+                for (int e = 0; e < VEC; ++e)
+                    if (am[e] == r * k + s) g[e] += Elem<T>::to_f32(v.e[e]);
+            }
+        }
+        const int64_t xo = (((int64_t)n * H + h) * W + w) * C + c0;
+        if (accumulate) {
+            const Vec16<T> old = load_vec(dx + xo);
+            #pragma unroll
+            for (int e = 0; e < VEC; ++e) g[e] += Elem<T>::to_f32(old.e[e]);
+        }
+        Vec16<T> out;
+        #pragma unroll
+        for (int e = 0; e < VEC; ++e) out.e[e] = Elem<T>::from_f32(g[e]);
+        store_vec(dx + xo, out);
+    }
+}
+
 void launch_maxpool_forward(int dtype, const void* x, void* y, uint8_t* arg, int N, int H, int W, int C, int k,
                             int stride, int pad, int Ho, int Wo, hipStream_t st) {
     const int grid = ew_grid((int64_t)N * Ho * Wo * C);
     const double esz = dtype == 1 ? 2.0 : 4.0;
     ProfScope ps("maxpool_fwd", 0.0, esz * (double)N * H * W * C + (esz + 1.0) * (double)N * Ho * Wo * C, st);
+    const int vec = dtype == 1 ? 8 : 4;
+    if (C % vec == 0) {
+        const int vgrid = ew_grid((int64_t)N * Ho * Wo * (C / vec));
+        if (dtype == 1)
+            hipLaunchKernelGGL(maxpool_fwd_vec_kernel<bf16_t>, dim3(vgrid), dim3(256), 0, st, (const bf16_t*)x, (bf16_t*)y, arg,
+                               N, H, W, C, k, stride, pad, Ho, Wo);
+        else
+            hipLaunchKernelGGL(maxpool_fwd_vec_kernel<float>, dim3(vgrid), dim3(256), 0, st, (const float*)x, (float*)y, arg, N,
+                               H, W, C, k, stride, pad, Ho, Wo);
+        return;
+    }
     if (dtype == 1)
         hipLaunchKernelGGL(maxpool_fwd_kernel<bf16_t>, dim3(grid), dim3(256), 0, st, (const bf16_t*)x, (bf16_t*)y, arg, N,
                            H, W, C, k, stride, pad, Ho, Wo);
@@ -99,6 +201,17 @@ void launch_maxpool_backward(int dtype, const void* dy, const uint8_t* arg, void
     const int grid = ew_grid((int64_t)N * H * W * C);
     const double esz = dtype == 1 ? 2.0 : 4.0;
     ProfScope ps("maxpool_bwd", 0.0, esz * (double)N * H * W * C * (accumulate ? 2.0 : 1.0) + (esz + 1.0) * (double)N * Ho * Wo * C, st);
+    const int vec = dtype == 1 ? 8 : 4;
+    if (C % vec == 0) {
+        const int vgrid = ew_grid((int64_t)N * H * W * (C / vec));
+        if (dtype == 1)
+            hipLaunchKernelGGL(maxpool_bwd_vec_kernel<bf16_t>, dim3(vgrid), dim3(256), 0, st, (const bf16_t*)dy, arg,
+                               (bf16_t*)dx, accumulate ? 1 : 0, N, H, W, C, k, stride, pad, Ho, Wo);
+        else
+            hipLaunchKernelGGL(maxpool_bwd_vec_kernel<float>, dim3(vgrid), dim3(256), 0, st, (const float*)dy, arg, (float*)dx,
+                               accumulate ? 1 : 0, N, H, W, C, k, stride, pad, Ho, Wo);
+        return;
+    }
     if (dtype == 1)
         hipLaunchKernelGGL(maxpool_bwd_kernel<bf16_t>, dim3(grid), dim3(256), 0, st, (const bf16_t*)dy, arg, (bf16_t*)dx,
                            accumulate ? 1 : 0, N, H, W, C, k, stride, pad, Ho, Wo);

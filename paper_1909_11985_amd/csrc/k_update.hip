@@ -175,6 +175,45 @@ void launch_weight_transpose(int dtype, const float* src, void* dst, int K, int 
         hipLaunchKernelGGL(weight_transpose_kernel<float>, grid, dim3(256), 0, st, src, (float*)dst, K, RS, C);
 }
 
+// All layers in one launch: workgroup b finds its layer in the table by its
+// first-tile index, then does the same 32x32 tile.
+template <typename T>
+__global__ __launch_bounds__(256) void weight_transpose_all_kernel(const float* __restrict__ w, unsigned char* __restrict__ arena,
+                                                                   const TransposeEntry* __restrict__ tab, int entries) {
+    __shared__ float tile[32][33];
+    int e = 0;
+    while (e + 1 < entries && (int)blockIdx.x >= tab[e + 1].tile_start) ++e;
+    const TransposeEntry te = tab[e];
+    int b = blockIdx.x - te.tile_start;
+    const int tiles_c = (te.C + 31) / 32, tiles_k = (te.K + 31) / 32;
+    const int cx = b % tiles_c; b /= tiles_c;
+    const int ky = b % tiles_k;
+    const int t = b / tiles_k;
+    const float* src = w + te.src_off;
+    T* dst = reinterpret_cast<T*>(arena + te.dst_off);
+    const int c0 = cx * 32, k0 = ky * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    for (int i = ty; i < 32; i += 8) {
+        const int k = k0 + i, c = c0 + tx;
+        tile[i][tx] = (k < te.K && c < te.C) ? src[((int64_t)k * te.RS + t) * te.C + c] : 0.f;
+    }
+    __syncthreads();
+    for (int i = ty; i < 32; i += 8) {
+        const int c = c0 + i, k = k0 + tx;
+        if (c < te.C && k < te.K) dst[((int64_t)c * te.RS + t) * te.K + k] = Elem<T>::from_f32(tile[tx][i]);
+    }
+}
+
+void launch_weight_transpose_all(int dtype, const float* w, void* arena, const TransposeEntry* dev_table, int entries,
+                                 int total_tiles, double bytes, hipStream_t st) {
+    if (entries <= 0 || total_tiles <= 0) return;
+    ProfScope ps("weight_transpose", 0.0, bytes, st);
+    if (dtype == 1)
+        hipLaunchKernelGGL(weight_transpose_all_kernel<bf16_t>, dim3(total_tiles), dim3(256), 0, st, w, (unsigned char*)arena, dev_table, entries);
+    else
+        hipLaunchKernelGGL(weight_transpose_all_kernel<float>, dim3(total_tiles), dim3(256), 0, st, w, (unsigned char*)arena, dev_table, entries);
+}
+
 // ---------------------------------------------------------------------------
 // out_x[i][:] = cast(data_x[idx[i]][:]) ; out_y[i] = data_y[idx[i]]
 // grid: (chunks of the sample, n)

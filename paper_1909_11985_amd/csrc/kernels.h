@@ -20,6 +20,15 @@ void launch_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
 void launch_fill_f32(float* dst, float value, int64_t n, hipStream_t st);
 // dst[c][r][s][k] = cast(src[k][r][s][c])  (weights for the input-gradient contraction)
 void launch_weight_transpose(int dtype, const float* src, void* dst, int K, int RS, int C, hipStream_t st);
+// the same for every layer of a model in one launch, from a table in device memory
+struct TransposeEntry {
+    int64_t src_off;     // floats from the start of the parameter vector
+    int64_t dst_off;     // bytes from the start of the arena
+    int K, RS, C;
+    int tile_start;      // index of the layer's first 32x32 tile among all layers' tiles
+};
+void launch_weight_transpose_all(int dtype, const float* w, void* arena, const TransposeEntry* dev_table, int entries,
+                                 int total_tiles, double bytes, hipStream_t st);
 // dst = cast(src) for float32 -> bf16 (weight copy after restore / set_params)
 void launch_cast_bf16(const float* src, uint16_t* dst, int64_t n, hipStream_t st);
 
