@@ -113,6 +113,12 @@ void plan_layout(const edl_config& c, const Graph& g, Layout& L) {
             if (storage_of(g, op.x) != 0) L.wT[i] = take((int64_t)op.K * op.R * op.S * tx.C * esz);
             L.wgrad_scratch_bytes = std::max<int64_t>(L.wgrad_scratch_bytes,
                                                       (int64_t)conv_wgrad_scratch_bytes(geom_of(g, op, c.max_shard)));
+            // the cut of a forward / dgrad reduction depends on the shard size: cover every size up to the largest
+            for (int n = 1; n <= c.max_shard; n = n < 8 ? n + 1 : n + n / 4)
+                L.wgrad_scratch_bytes = std::max<int64_t>(L.wgrad_scratch_bytes,
+                                                          (int64_t)conv_splitk_scratch_bytes(c.dtype, geom_of(g, op, n)));
+            L.wgrad_scratch_bytes = std::max<int64_t>(L.wgrad_scratch_bytes,
+                                                      (int64_t)conv_splitk_scratch_bytes(c.dtype, geom_of(g, op, c.max_shard)));
         } else if (op.kind == OP_BN) {
             L.bn_save[i] = take(4 * 2 * (int64_t)op.K);
         } else if (op.kind == OP_MAXPOOL) {
@@ -337,7 +343,8 @@ static void forward_shard(edl_handle* h, const int64_t* dev_idx, int n, float* d
             case OP_CONV: {
                 const void* wsrc = bf ? (const void*)(h->at<uint16_t>(h->L.shadow) + op.w_off) : (const void*)(h->w() + op.w_off);
                 launch_conv_fwd(dt, geom_of(g, op, n), h->act(op.x), wsrc, op.bias ? h->w() + op.b_off : nullptr, op.relu,
-                                g.tensors[(size_t)op.y].fp32, h->act(op.y), st);
+                                g.tensors[(size_t)op.y].fp32, h->act(op.y), h->at<float>(h->L.wgrad_scratch),
+                                (size_t)h->L.wgrad_scratch_bytes, st);
                 break;
             }
             case OP_BN: {
@@ -391,7 +398,8 @@ static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, siz
                                   (size_t)h->L.wgrad_scratch_bytes, st);
                 const int sx = storage_of(g, op.x);
                 if (sx != 0) {
-                    launch_conv_dgrad(dt, q, h->grad(op.y), h->arena + h->L.wT[ii], written[(size_t)sx] != 0, h->grad(op.x), st);
+                    launch_conv_dgrad(dt, q, h->grad(op.y), h->arena + h->L.wT[ii], written[(size_t)sx] != 0, h->grad(op.x),
+                                      h->at<float>(h->L.wgrad_scratch), (size_t)h->L.wgrad_scratch_bytes, st);
                     written[(size_t)sx] = 1;
                 }
                 break;

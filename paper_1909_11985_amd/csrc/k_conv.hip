@@ -23,6 +23,7 @@
 // float32 partial tiles are added by a second kernel in split order.
 #include <cstdio>
 #include <cstdlib>
+#include <algorithm>
 #include <deque>
 #include <string>
 
@@ -53,6 +54,7 @@ struct ConvArgs {
     // For stride 1 (and the other modes): ph = pw = r0 = s0 = 0, nr = R, ns = S.
     int ph, pw, Hc, Wc, r0, s0, nr, ns;
     int ldb;     // fwd/dgrad: elements between consecutive rows of B
+    float* partial;  // fwd/dgrad with a cut reduction: float32 [split][M][Nn] partial sums, else null
 };
 
 // 16-byte load through a buffer descriptor: an offset at or beyond the
@@ -540,8 +542,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
     constexpr bool OUT_F32 = WG || sizeof(T) == 4;       // element type of the vector-path output
     constexpr int OSZ = OUT_F32 ? 4 : 2;
     constexpr int OVEC = 16 / OSZ;
-    const bool direct_f32 = (MODE == CONV_FWD) && a.out_fp32 && !OUT_F32;
-    if (!FAST && ((a.Nn % OVEC) != 0 || direct_f32)) {
+    if (!FAST) {
         // ragged width (or float32 logits from a bf16 net): element-wise stores
         #pragma unroll
         for (int i = 0; i < TM; ++i) {
@@ -578,6 +579,8 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
     // lane and row, conflict-free), then leaves as 16-byte vectors along the output row
     float* const stage = reinterpret_cast<float*>(smem);
     unsigned char* const outp = (unsigned char*)a.out + (WG ? (int64_t)blockIdx.z * a.M * a.Nn * 4 : 0);
+    const bool to_partial = !WG && a.partial != nullptr;     // cut reduction: raw float32 sums, finished by another kernel
+    const bool f32_out = (MODE == CONV_FWD) && a.out_fp32 && !OUT_F32;
     #pragma unroll
     for (int pass = 0; pass < WM; ++pass) {
         if (wm == pass) {
@@ -592,7 +595,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
                     #pragma unroll
                     for (int q = 0; q < 16; ++q) {
                         float v = acc[i][j][q];
-                        if (MODE == CONV_FWD) {
+                        if (MODE == CONV_FWD && !to_partial) {
                             v += bias;
                             if (a.relu) v = fmaxf(v, 0.f);
                         }
@@ -609,6 +612,13 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
             const int row = m0 + pass * STAGE_ROWS + rl, col = n0 + cv * OVEC;
             if (row < a.M && col < a.Nn) {
                 const float* sp = stage + rl * STAGE_LD + cv * OVEC;
+                if (to_partial || f32_out) {
+                    float* d = to_partial ? a.partial + ((int64_t)blockIdx.z * a.M + row) * a.Nn + col
+                                          : (float*)a.out + (int64_t)row * a.Nn + col;
+                    #pragma unroll
+                    for (int e = 0; e < OVEC; e += 4) *reinterpret_cast<float4*>(d + e) = *reinterpret_cast<const float4*>(sp + e);
+                    continue;
+                }
                 unsigned char* dst = outp + (out_row<MODE>(a, row) * a.Nn + col) * OSZ;
                 if (OUT_F32) {
                     float4 o = *reinterpret_cast<const float4*>(sp);
@@ -671,6 +681,38 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restri
     }
 }
 
+// Finish of a forward / dgrad whose reduction was cut: sum the splits in order,
+// add the bias / apply ReLU (forward) or add the existing gradient (dgrad), and
+// store in the output type.  Four outputs per lane.
+template <typename T>
+__global__ __launch_bounds__(256) void splitk_finish_kernel(const float* __restrict__ part, void* out, const float* __restrict__ bias,
+                                                            int64_t M, int Nn, int splits, int relu, int out_fp32, int accumulate) {
+    const int64_t n4 = M * Nn / 4, mn = M * Nn;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (int64_t)gridDim.x * blockDim.x) {
+        float4 s = reinterpret_cast<const float4*>(part)[i];
+        for (int k = 1; k < splits; ++k) {
+            const float4 t = reinterpret_cast<const float4*>(part + (int64_t)k * mn)[i];
+            s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+        }
+        const int col = (int)((i * 4) % Nn);
+        if (bias) { s.x += bias[col]; s.y += bias[col + 1]; s.z += bias[col + 2]; s.w += bias[col + 3]; }
+        if (relu) { s.x = fmaxf(s.x, 0.f); s.y = fmaxf(s.y, 0.f); s.z = fmaxf(s.z, 0.f); s.w = fmaxf(s.w, 0.f); }
+        if (out_fp32 || sizeof(T) == 4) {
+            float4* d = reinterpret_cast<float4*>(out) + i;
+            if (accumulate) { const float4 o = *d; s.x += o.x; s.y += o.y; s.z += o.z; s.w += o.w; }
+            *d = s;
+        } else {
+            uint2* d = reinterpret_cast<uint2*>(out) + i;
+            if (accumulate) {
+                const uint2 o = *d;
+                s.x += __uint_as_float(o.x << 16); s.y += __uint_as_float(o.x & 0xffff0000u);
+                s.z += __uint_as_float(o.y << 16); s.w += __uint_as_float(o.y & 0xffff0000u);
+            }
+            *d = make_uint2(pack2_bf16(s.x, s.y), pack2_bf16(s.z, s.w));
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------
 // host side: tile selection and launch
 // ---------------------------------------------------------------------------
@@ -679,13 +721,19 @@ enum TileCfg { T128x128, T128x64, T128x32, T64x64 };
 // reduction elements per tile: eight 16-byte vectors per row for either type
 template <typename T> constexpr int kConvBK = 8 * Elem<T>::VEC;
 
+static int env_int(const char* name, int dflt) {
+    const char* v = getenv(name);
+    return v ? atoi(v) : dflt;
+}
+
 static TileCfg pick_tile(int M, int Nn, int* bm, int* bn) {
+    static const int min128 = env_int("EDL_TUNE_MIN128", 256);
     TileCfg t;
     if (Nn <= 32) t = T128x32;
     else if (Nn <= 64) t = (M >= 128) ? T128x64 : T64x64;
     else {
         const int64_t tiles = (int64_t)((M + 127) / 128) * ((Nn + 127) / 128);
-        t = (tiles >= 256 && M >= 128) ? T128x128 : T64x64;
+        t = (tiles >= min128 && M >= 128) ? T128x128 : T64x64;
     }
     switch (t) {
         case T128x128: *bm = 128; *bn = 128; break;
@@ -724,8 +772,7 @@ static const char* conv_label(int dtype, int mode, TileCfg t) {
 
 static bool conv_fast(int dtype, int mode, const ConvArgs& a) {
     const int ovec = (mode == CONV_WGRAD || dtype != 1) ? 4 : 8;
-    const bool direct_f32 = mode == CONV_FWD && a.out_fp32 && dtype == 1;
-    return a.vecA && a.vecB && a.Nn % ovec == 0 && !direct_f32;
+    return a.vecA && a.vecB && a.Nn % ovec == 0;
 }
 
 template <int MODE>
@@ -768,8 +815,53 @@ static ConvArgs base_args(const ConvGeom& g) {
     return a;
 }
 
+// Cut of the reduction for forward / dgrad problems that give too few tiles to
+// fill the chip but have a long reduction (late stages at small batch, fully
+// connected layers): returns the number of splits (1 = none).
+static int plan_splitk(int dtype, int M, int Nn, int Kred, int bm, int bn, int* ksplit) {
+    const int BK = dtype == 1 ? 64 : 32;
+    const int64_t tiles = (int64_t)((M + bm - 1) / bm) * ((Nn + bn - 1) / bn);
+    const int nk = (Kred + BK - 1) / BK;
+    int splits = 1;
+    static const int max_tiles = env_int("EDL_TUNE_SPLITK_TILES", 400), target = env_int("EDL_TUNE_SPLITK_TARGET", 768);
+    if (tiles < max_tiles && nk >= 8) {
+        splits = (int)((target + tiles - 1) / tiles);
+        if (splits > nk / 4) splits = nk / 4;
+        if (splits > 8) splits = 8;
+        if (splits < 1) splits = 1;
+    }
+    int ks = (nk + splits - 1) / splits * BK;
+    *ksplit = ks;
+    return (Kred + ks - 1) / ks;
+}
+
+template <typename T>
+static void launch_finish(const ConvArgs& a, int splits, hipStream_t st) {
+    const int64_t n4 = (int64_t)a.M * a.Nn / 4;
+    int64_t blocks = (n4 + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    ProfScope ps("splitk_finish", 0.0, 4.0 * (double)a.M * a.Nn * splits + (a.out_fp32 ? 4.0 : (double)sizeof(T)) * (double)a.M * a.Nn, st);
+    hipLaunchKernelGGL(splitk_finish_kernel<T>, dim3((int)blocks), dim3(256), 0, st, a.partial, a.out, a.bias, (int64_t)a.M, a.Nn, splits,
+                       a.relu, a.out_fp32, a.accumulate);
+}
+
+size_t conv_splitk_scratch_bytes(int dtype, const ConvGeom& g) {
+    size_t need = 0;
+    for (int mode = 0; mode < 2; ++mode) {
+        if (mode == 1 && g.stride != 1) continue;
+        const int M = mode == 0 ? g.N * g.Ho * g.Wo : g.N * g.H * g.W;
+        const int Nn = mode == 0 ? g.K : g.C;
+        const int Kred = mode == 0 ? g.R * g.S * g.C : g.R * g.S * g.K;
+        int bm, bn, ks;
+        pick_tile(M, Nn, &bm, &bn);
+        const int splits = plan_splitk(dtype, M, Nn, Kred, bm, bn, &ks);
+        if (splits > 1) need = std::max(need, (size_t)splits * M * Nn * sizeof(float));
+    }
+    return need;
+}
+
 void launch_conv_fwd(int dtype, const ConvGeom& g, const void* x, const void* w, const float* bias, bool relu,
-                     bool out_fp32, void* y, hipStream_t st) {
+                     bool out_fp32, void* y, float* scratch, size_t scratch_bytes, hipStream_t st) {
     const int VEC = dtype == 1 ? 8 : 4;
     ConvArgs a = base_args(g);
     a.A = x; a.B = w; a.out = y; a.bias = bias;
@@ -783,11 +875,21 @@ void launch_conv_fwd(int dtype, const ConvGeom& g, const void* x, const void* w,
     a.ldb = a.Kred;
     int bm, bn;
     const TileCfg t = pick_tile(a.M, a.Nn, &bm, &bn);
-    launch_mode<CONV_FWD>(dtype, t, dim3((a.M + bm - 1) / bm, (a.Nn + bn - 1) / bn, 1), a, st);
+    int splits = 1, ks = a.Kred;
+    if (conv_fast(dtype, CONV_FWD, a)) {
+        splits = plan_splitk(dtype, a.M, a.Nn, a.Kred, bm, bn, &ks);
+        if (splits > 1 && (scratch == nullptr || scratch_bytes < (size_t)splits * a.M * a.Nn * sizeof(float))) splits = 1;
+    }
+    if (splits > 1) { a.ksplit = ks; a.partial = scratch; }
+    launch_mode<CONV_FWD>(dtype, t, dim3((a.M + bm - 1) / bm, (a.Nn + bn - 1) / bn, splits), a, st);
+    if (splits > 1) {
+        if (dtype == 1) launch_finish<bf16_t>(a, splits, st);
+        else launch_finish<float>(a, splits, st);
+    }
 }
 
 void launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dy, const void* wT, bool accumulate, void* dx,
-                       hipStream_t st) {
+                       float* scratch, size_t scratch_bytes, hipStream_t st) {
     const int VEC = dtype == 1 ? 8 : 4;
     ConvArgs a = base_args(g);
     a.A = dy; a.B = wT; a.out = dx;
@@ -811,10 +913,21 @@ void launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dy, const void*
             a.M = g.N * a.Hc * a.Wc;
             a.Kred = a.nr * a.ns * g.K;
             a.ksplit = a.Kred > 0 ? a.Kred : 1;
+            a.partial = nullptr;
             if (a.Kred == 0 && accumulate) continue;      // nothing reaches these pixels
             int bm, bn;
             const TileCfg t = pick_tile(a.M, a.Nn, &bm, &bn);
-            launch_mode<CONV_DGRAD>(dtype, t, dim3((a.M + bm - 1) / bm, (a.Nn + bn - 1) / bn, 1), a, st);
+            int splits = 1, ks = a.ksplit;
+            if (g.stride == 1 && conv_fast(dtype, CONV_DGRAD, a)) {
+                splits = plan_splitk(dtype, a.M, a.Nn, a.Kred, bm, bn, &ks);
+                if (splits > 1 && (scratch == nullptr || scratch_bytes < (size_t)splits * a.M * a.Nn * sizeof(float))) splits = 1;
+            }
+            if (splits > 1) { a.ksplit = ks; a.partial = scratch; }
+            launch_mode<CONV_DGRAD>(dtype, t, dim3((a.M + bm - 1) / bm, (a.Nn + bn - 1) / bn, splits), a, st);
+            if (splits > 1) {
+                if (dtype == 1) launch_finish<bf16_t>(a, splits, st);
+                else launch_finish<float>(a, splits, st);
+            }
         }
     }
 }
@@ -846,7 +959,8 @@ static WgradPlan plan_wgrad(const ConvGeom& g) {
         default: p.bm = 64; p.bn = 64; break;
     }
     p.tiles = (int64_t)((M + p.bm - 1) / p.bm) * ((Nn + p.bn - 1) / p.bn);
-    int64_t splits = (512 + p.tiles - 1) / p.tiles;
+    static const int target = env_int("EDL_TUNE_WGRAD_BLOCKS", 512);
+    int64_t splits = (target + p.tiles - 1) / p.tiles;
     const int64_t max_splits = (Kred + 255) / 256;  // at least 4 reduction steps per split
     if (splits > max_splits) splits = max_splits;
     if (splits < 1) splits = 1;

@@ -46,10 +46,12 @@ struct ConvGeom {
 
 // y = conv(x, w) (+bias) (ReLU); y is float32 if out_fp32 else dtype
 void launch_conv_fwd(int dtype, const ConvGeom& g, const void* x, const void* w, const float* bias, bool relu,
-                     bool out_fp32, void* y, hipStream_t st);
+                     bool out_fp32, void* y, float* scratch, size_t scratch_bytes, hipStream_t st);
 // dx (+)= conv^T(dy, wT); wT is the [C][R][S][K] copy
 void launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dy, const void* wT, bool accumulate, void* dx,
-                       hipStream_t st);
+                       float* scratch, size_t scratch_bytes, hipStream_t st);
+// float32 scratch a forward / dgrad launch may use to cut a long reduction of a small problem
+size_t conv_splitk_scratch_bytes(int dtype, const ConvGeom& g);
 // dw = x^T * dy, float32 [K][R][S][C]; scratch holds split partial sums
 void launch_conv_wgrad(int dtype, const ConvGeom& g, const void* x, const void* dy, float* dw, float* scratch,
                        size_t scratch_bytes, hipStream_t st);
