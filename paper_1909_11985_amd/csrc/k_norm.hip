@@ -274,7 +274,7 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const T* __restrict__
 
 static inline int ew_grid(int64_t total) {
     int64_t b = (total + 255) / 256;
-    if (b > 256 * 32) b = 256 * 32;
+    if (b > (1 << 30)) b = 1 << 30;
     if (b < 1) b = 1;
     return (int)b;
 }
