@@ -145,7 +145,16 @@ __device__ __forceinline__ void sum_partials(const float* __restrict__ partial, 
     s = 0;
     q = 0;
     if (c < C) {
-        for (int j = sub; j < row_blocks; j += 32) {
+        int j = sub;
+        for (; j + 96 < row_blocks; j += 128) {     // four independent loads per sum in flight
+            const float s0 = partial[((int64_t)j * 2 + 0) * C + c], q0 = partial[((int64_t)j * 2 + 1) * C + c];
+            const float s1 = partial[((int64_t)(j + 32) * 2 + 0) * C + c], q1 = partial[((int64_t)(j + 32) * 2 + 1) * C + c];
+            const float s2 = partial[((int64_t)(j + 64) * 2 + 0) * C + c], q2 = partial[((int64_t)(j + 64) * 2 + 1) * C + c];
+            const float s3 = partial[((int64_t)(j + 96) * 2 + 0) * C + c], q3 = partial[((int64_t)(j + 96) * 2 + 1) * C + c];
+            s += (double)s0; s += (double)s1; s += (double)s2; s += (double)s3;
+            q += (double)q0; q += (double)q1; q += (double)q2; q += (double)q3;
+        }
+        for (; j < row_blocks; j += 32) {
             s += (double)partial[((int64_t)j * 2 + 0) * C + c];
             q += (double)partial[((int64_t)j * 2 + 1) * C + c];
         }
