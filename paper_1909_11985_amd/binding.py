@@ -11,7 +11,7 @@ import os
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libedl.so")
+_LIB_PATH = os.environ.get("EDL_LIBRARY") or os.path.join(_HERE, "libedl.so")   # EDL_LIBRARY: another build of the same library
 
 MODELS = {"mlp": 0, "resnet20": 1, "resnet50": 2, "vgg16": 3}
 DTYPES = {"f32": 0, "bf16": 1}

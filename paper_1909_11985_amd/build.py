@@ -12,7 +12,7 @@ FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Wall", "-Wno-u
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
-def build(verbose: bool = False) -> str:
+def build(verbose: bool = False, extra=(), lib=LIB) -> str:
     objs = []
     procs = []
     os.makedirs(os.path.join(HERE, "_build"), exist_ok=True)
@@ -20,7 +20,7 @@ def build(verbose: bool = False) -> str:
         src = os.path.join(CSRC, s)
         obj = os.path.join(HERE, "_build", s + ".o")
         objs.append(obj)
-        cmd = ["hipcc", "-x", "hip", "-c", src, "-o", obj] + FLAGS
+        cmd = ["hipcc", "-x", "hip", "-c", src, "-o", obj] + FLAGS + list(extra)
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((s, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
@@ -35,8 +35,8 @@ def build(verbose: bool = False) -> str:
             print("== %s ==\n%s" % (s, out))
     if failed:
         raise RuntimeError("hipcc failed")
-    subprocess.run(["hipcc", "-shared", "-o", LIB] + objs + ["--offload-arch=gfx950", "-lpthread"], check=True)
-    return LIB
+    subprocess.run(["hipcc", "-shared", "-o", lib] + objs + ["--offload-arch=gfx950", "-lpthread"], check=True)
+    return lib
 
 
 if __name__ == "__main__":

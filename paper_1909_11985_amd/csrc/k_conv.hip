@@ -55,7 +55,14 @@ struct ConvArgs {
     int ph, pw, Hc, Wc, r0, s0, nr, ns;
     int ldb;     // fwd/dgrad: elements between consecutive rows of B
     float* partial;  // fwd/dgrad with a cut reduction: float32 [split][M][Nn] partial sums, else null
+    // ceil(2^40 / d) for d = channels per tap and d = taps per kernel row: n / d == (n * magic) >> 40
+    // for n * d < 2^40, which keeps the tap bookkeeping of the load loop free of branches
+    unsigned long long magic_inner, magic_taps;
 };
+
+__device__ __forceinline__ int fast_div(int n, unsigned long long magic) {
+    return (int)(((unsigned long long)(unsigned)n * magic) >> 40);
+}
 
 // 16-byte load through a buffer descriptor: an offset at or beyond the
 // descriptor's extent returns zeros, so padding taps, ragged tile edges and
@@ -202,7 +209,7 @@ __device__ __forceinline__ int64_t out_row(const ConvArgs& a, int row) {
 // multiple of a vector, so the kernel has no element-wise paths at all (a
 // run-time choice between the two inside the loop would force a wait after
 // every load).
-template <typename T, int MODE, int WM, int WN, int TM, int TN, int BK, bool FAST>
+template <typename T, int MODE, int WM, int WN, int TM, int TN, int BK, bool FAST, int PF>
 __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
     constexpr bool WG = MODE == CONV_WGRAD;
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
@@ -242,7 +249,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
     if (kend > a.Kred) kend = a.Kred;
     const int nk = (kend - kbeg + BK - 1) / BK;
 
-    Vec16<T> ra[NRA], rb[NRB];
+    Vec16<T> ra[PF][NRA], rb[PF][NRB];   // PF register sets: the loads of the next PF tiles are in flight
     const __amdgpu_buffer_rsrc_t rsrcA = make_rsrc(a.A, a.bytesA), rsrcB = make_rsrc(a.B, a.bytesB);
 
     // ---- per-thread state of the gathers; advanced by BK after every tile ------
@@ -302,30 +309,30 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
         kcur = kbeg;
     }
 
-    auto load_tiles = [&]() {
+    auto load_tiles = [&](int set) {
         if (!WG) {
             const bool in_k = kcur < kend;
             #pragma unroll
             for (int it = 0; it < ITER_A; ++it) {
-                ra[it].u = make_uint4(0, 0, 0, 0);
+                ra[set][it].u = make_uint4(0, 0, 0, 0);
                 if (TOT_A % 256 != 0 && tid + it * 256 >= TOT_A) continue;
                 if (FAST || a.vecA) {
-                    ra[it].u = buffer_load16(rsrcA, a_voffset<MODE, T>(a, rowA[it], tr, ts, tc, tap_off, in_k));
+                    ra[set][it].u = buffer_load16(rsrcA, a_voffset<MODE, T>(a, rowA[it], tr, ts, tc, tap_off, in_k));
                 } else {
                     #pragma unroll
                     for (int e = 0; e < VEC; ++e) {
                         bool ok;
                         const int64_t off = a_offset<MODE>(a, rowA[it], kcur + e, ok);
-                        if (ok && kcur + e < kend) ra[it].e[e] = Ag[off];
+                        if (ok && kcur + e < kend) ra[set][it].e[e] = Ag[off];
                     }
                 }
             }
             #pragma unroll
             for (int it = 0; it < ITER_B; ++it) {
-                rb[it].u = make_uint4(0, 0, 0, 0);
+                rb[set][it].u = make_uint4(0, 0, 0, 0);
                 if (FAST || a.vecB) {
                     const int boff = MODE == CONV_FWD ? kcur : tap_off;
-                    rb[it].u = buffer_load16(rsrcB, (okB[it] && in_k) ? (unsigned)((int)offB[it] + boff) * (unsigned)sizeof(T) : kOutOfRange);
+                    rb[set][it].u = buffer_load16(rsrcB, (okB[it] && in_k) ? (unsigned)((int)offB[it] + boff) * (unsigned)sizeof(T) : kOutOfRange);
                 } else if (okB[it]) {
                     #pragma unroll
                     for (int e = 0; e < VEC; ++e) {
@@ -334,30 +341,25 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
                             const int tap = (kcur + e) / a.K, ri = a.ns > 0 ? tap / a.ns : 0;
                             boff = ((a.r0 + ri * a.stride) * a.S + a.s0 + (tap - ri * a.ns) * a.stride) * a.K + (kcur + e - tap * a.K);
                         }
-                        if (kcur + e < kend) rb[it].e[e] = Bg[offB[it] + boff];
+                        if (kcur + e < kend) rb[set][it].e[e] = Bg[offB[it] + boff];
                     }
                 }
             }
-            // advance this thread's vector by BK along (r, s, channel)
+            // advance this thread's vector by BK along (r, s, channel); no branches, so that the
+            // loads issued above stay in flight across the following code
             const int inner = MODE == CONV_FWD ? a.C : a.K;
             kcur += BK;
-            tc += BK;
-            tap_off += BK;
-            if (tc >= inner) {
-                if (MODE == CONV_FWD) {
-                    do {
-                        tc -= inner;
-                        if (++ts == a.S) { ts = 0; ++tr; }
-                    } while (tc >= inner);
-                    tap_off = (tr * a.W + ts) * a.C + tc;
-                } else {
-                    do {
-                        tc -= inner;
-                        ts += a.stride;
-                        if (ts >= a.S) { ts = a.s0; tr += a.stride; }
-                    } while (tc >= inner);
-                    tap_off = (tr * a.S + ts) * a.K + tc;
-                }
+            const int tap = fast_div(kcur, a.magic_inner);
+            tc = kcur - tap * inner;
+            const int ri = fast_div(tap, a.magic_taps);
+            if (MODE == CONV_FWD) {
+                tr = ri;
+                ts = tap - ri * a.S;
+                tap_off = (tr * a.W + ts) * a.C + tc;
+            } else {
+                tr = a.r0 + ri * a.stride;
+                ts = a.s0 + (tap - ri * a.ns) * a.stride;
+                tap_off = (tr * a.S + ts) * a.K + tc;
             }
         } else {
             #pragma unroll
@@ -367,7 +369,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
                 const int row0 = m0 + (tid % RVA) * VEC;
                 #pragma unroll
                 for (int pp = 0; pp < KPD; ++pp) {
-                    Vec16<T>& dst = ra[it * KPD + pp];
+                    Vec16<T>& dst = ra[set][it * KPD + pp];
                     dst.u = make_uint4(0, 0, 0, 0);
                     const bool ok = live && mm + pp < kend;
                     if (FAST || a.vecA) {
@@ -387,7 +389,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
                 int qn = pn[it], qho = pho[it], qwo = pwo[it];
                 #pragma unroll
                 for (int pp = 0; pp < KPD; ++pp) {
-                    Vec16<T>& dst = rb[it * KPD + pp];
+                    Vec16<T>& dst = rb[set][it * KPD + pp];
                     dst.u = make_uint4(0, 0, 0, 0);
                     const bool okp = live && mm + pp < kend;
                     const int hb = qho * a.stride - a.pad, wb = qwo * a.stride - a.pad;
@@ -422,7 +424,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
         }
     };
 
-    auto store_tiles = [&](int buf) {
+    auto store_tiles = [&](int set, int buf) {
         if (!WG) {
             T* const Ad = reinterpret_cast<T*>(As + buf * A_STAGE);
             T* const Bd = reinterpret_cast<T*>(Bs + buf * B_STAGE);
@@ -430,13 +432,13 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
             for (int it = 0; it < ITER_A; ++it) {
                 const int v = tid + it * 256;
                 if (TOT_A % 256 != 0 && v >= TOT_A) continue;
-                store_vec(&Ad[(v / KV) * LDK + (v % KV) * VEC], ra[it]);
+                store_vec(&Ad[(v / KV) * LDK + (v % KV) * VEC], ra[set][it]);
             }
             #pragma unroll
             for (int it = 0; it < ITER_B; ++it) {
                 const int v = tid + it * 256;
                 if (TOT_B % 256 != 0 && v >= TOT_B) continue;
-                store_vec(&Bd[(v / KV) * LDK + (v % KV) * VEC], rb[it]);
+                store_vec(&Bd[(v / KV) * LDK + (v % KV) * VEC], rb[set][it]);
             }
         } else {
             uint32_t* const Ad = reinterpret_cast<uint32_t*>(As + buf * A_STAGE);
@@ -448,8 +450,8 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
                 uint32_t* dst = &Ad[(v / RVA) * LDPA + (v % RVA) * VEC];
                 if (KPD == 2) {
                     // word e = (pixel 2q, pixel 2q+1) of channel e
-                    const uint16_t* p0 = reinterpret_cast<const uint16_t*>(&ra[it * KPD]);
-                    const uint16_t* p1 = reinterpret_cast<const uint16_t*>(&ra[it * KPD + KPD - 1]);
+                    const uint16_t* p0 = reinterpret_cast<const uint16_t*>(&ra[set][it * KPD]);
+                    const uint16_t* p1 = reinterpret_cast<const uint16_t*>(&ra[set][it * KPD + KPD - 1]);
                     uint4 lo, hi;
                     lo.x = p0[0] | ((uint32_t)p1[0] << 16); lo.y = p0[1] | ((uint32_t)p1[1] << 16);
                     lo.z = p0[2] | ((uint32_t)p1[2] << 16); lo.w = p0[3] | ((uint32_t)p1[3] << 16);
@@ -458,7 +460,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
                     *reinterpret_cast<uint4*>(dst) = lo;
                     *reinterpret_cast<uint4*>(dst + 4) = hi;
                 } else {
-                    *reinterpret_cast<uint4*>(dst) = ra[it].u;
+                    *reinterpret_cast<uint4*>(dst) = ra[set][it].u;
                 }
             }
             #pragma unroll
@@ -467,8 +469,8 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
                 if (TOT_B % 256 != 0 && v >= TOT_B) continue;
                 uint32_t* dst = &Bd[(v / RVB) * LDPB + (v % RVB) * VEC];
                 if (KPD == 2) {
-                    const uint16_t* p0 = reinterpret_cast<const uint16_t*>(&rb[it * KPD]);
-                    const uint16_t* p1 = reinterpret_cast<const uint16_t*>(&rb[it * KPD + KPD - 1]);
+                    const uint16_t* p0 = reinterpret_cast<const uint16_t*>(&rb[set][it * KPD]);
+                    const uint16_t* p1 = reinterpret_cast<const uint16_t*>(&rb[set][it * KPD + KPD - 1]);
                     uint4 lo, hi;
                     lo.x = p0[0] | ((uint32_t)p1[0] << 16); lo.y = p0[1] | ((uint32_t)p1[1] << 16);
                     lo.z = p0[2] | ((uint32_t)p1[2] << 16); lo.w = p0[3] | ((uint32_t)p1[3] << 16);
@@ -477,7 +479,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
                     *reinterpret_cast<uint4*>(dst) = lo;
                     *reinterpret_cast<uint4*>(dst + 4) = hi;
                 } else {
-                    *reinterpret_cast<uint4*>(dst) = rb[it].u;
+                    *reinterpret_cast<uint4*>(dst) = rb[set][it].u;
                 }
             }
         }
@@ -491,51 +493,61 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
             #pragma unroll
             for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
 
-    // two LDS stages: the global loads of tile kt+1 are in flight during the
-    // MFMAs of tile kt and land in the other stage; one barrier per tile
-    if (nk > 0) {
-        load_tiles();
-        store_tiles(0);
-    }
+    // Software pipeline: two LDS stages and PF register sets.  While tile k is
+    // contracted from LDS stage k%2, the global loads of tiles k+1 .. k+PF are in
+    // flight; tile k+1 is moved from its registers to the other stage after the
+    // MFMAs of tile k.  One barrier per tile.
+    static_assert(PF == 1 || PF % 2 == 0, "the LDS stage of a tile must be known at compile time");
+    // Loads past the end of the reduction are issued too: their offsets are out of
+    // range, so they touch no memory and return zeros, and the number of loads in
+    // flight at every wait is then a compile-time constant.
+    #pragma unroll
+    for (int u = 0; u < PF; ++u) load_tiles(u);
+    store_tiles(0, 0);
     __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < nk) load_tiles();
-        constexpr int NG = WG ? 4 : BK / (2 * VEC);   // fragment groups per tile
+    for (int kt = 0; kt < nk; kt += PF) {
         #pragma unroll
-        for (int g = 0; g < NG; ++g) {
-            uint4 fa[TM], fb[TN];
-            if (!WG) {
-                constexpr int KG = 2 * VEC;  // reduction elements one fragment pair covers
-                const T* const Ab = reinterpret_cast<const T*>(As + buf * A_STAGE);
-                const T* const Bb = reinterpret_cast<const T*>(Bs + buf * B_STAGE);
+        for (int u = 0; u < PF; ++u) {
+            const int k = kt + u;
+            if (k >= nk) break;
+            const int buf = PF == 1 ? (k & 1) : (u & 1);
+            load_tiles(u);
+            constexpr int NG = WG ? 4 : BK / (2 * VEC);   // fragment groups per tile
+            #pragma unroll
+            for (int g = 0; g < NG; ++g) {
+                uint4 fa[TM], fb[TN];
+                if (!WG) {
+                    constexpr int KG = 2 * VEC;  // reduction elements one fragment pair covers
+                    const T* const Ab = reinterpret_cast<const T*>(As + buf * A_STAGE);
+                    const T* const Bb = reinterpret_cast<const T*>(Bs + buf * B_STAGE);
+                    #pragma unroll
+                    for (int i = 0; i < TM; ++i)
+                        fa[i] = *reinterpret_cast<const uint4*>(&Ab[((wm * TM + i) * 32 + (lane & 31)) * LDK + g * KG + (lane >> 5) * VEC]);
+                    #pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        fb[j] = *reinterpret_cast<const uint4*>(&Bb[((wn * TN + j) * 32 + (lane & 31)) * LDK + g * KG + (lane >> 5) * VEC]);
+                } else {
+                    const uint32_t* const Ab = reinterpret_cast<const uint32_t*>(As + buf * A_STAGE) + (g * 8 + (lane >> 5) * 4) * LDPA + (lane & 31);
+                    const uint32_t* const Bb = reinterpret_cast<const uint32_t*>(Bs + buf * B_STAGE) + (g * 8 + (lane >> 5) * 4) * LDPB + (lane & 31);
+                    #pragma unroll
+                    for (int i = 0; i < TM; ++i) {
+                        const uint32_t* q = Ab + (wm * TM + i) * 32;
+                        fa[i] = make_uint4(q[0], q[LDPA], q[2 * LDPA], q[3 * LDPA]);
+                    }
+                    #pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        const uint32_t* q = Bb + (wn * TN + j) * 32;
+                        fb[j] = make_uint4(q[0], q[LDPB], q[2 * LDPB], q[3 * LDPB]);
+                    }
+                }
                 #pragma unroll
                 for (int i = 0; i < TM; ++i)
-                    fa[i] = *reinterpret_cast<const uint4*>(&Ab[((wm * TM + i) * 32 + (lane & 31)) * LDK + g * KG + (lane >> 5) * VEC]);
-                #pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    fb[j] = *reinterpret_cast<const uint4*>(&Bb[((wn * TN + j) * 32 + (lane & 31)) * LDK + g * KG + (lane >> 5) * VEC]);
-            } else {
-                const uint32_t* const Ab = reinterpret_cast<const uint32_t*>(As + buf * A_STAGE) + (g * 8 + (lane >> 5) * 4) * LDPA + (lane & 31);
-                const uint32_t* const Bb = reinterpret_cast<const uint32_t*>(Bs + buf * B_STAGE) + (g * 8 + (lane >> 5) * 4) * LDPB + (lane & 31);
-                #pragma unroll
-                for (int i = 0; i < TM; ++i) {
-                    const uint32_t* q = Ab + (wm * TM + i) * 32;
-                    fa[i] = make_uint4(q[0], q[LDPA], q[2 * LDPA], q[3 * LDPA]);
-                }
-                #pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    const uint32_t* q = Bb + (wn * TN + j) * 32;
-                    fb[j] = make_uint4(q[0], q[LDPB], q[2 * LDPB], q[3 * LDPB]);
-                }
+                    #pragma unroll
+                    for (int j = 0; j < TN; ++j) Frag<T>::mma(fa[i], fb[j], acc[i][j]);
             }
-            #pragma unroll
-            for (int i = 0; i < TM; ++i)
-                #pragma unroll
-                for (int j = 0; j < TN; ++j) Frag<T>::mma(fa[i], fb[j], acc[i][j]);
+            store_tiles((u + 1) % PF, buf ^ 1);
+            __syncthreads();
         }
-        if (kt + 1 < nk) store_tiles(buf ^ 1);
-        __syncthreads();
     }
 
     // ---- epilogue: lane holds column lane%32, rows (q/4)*8 + (lane/32)*4 + q%4 of each 32x32 tile ----
@@ -718,6 +730,16 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(const float* __restr
 // ---------------------------------------------------------------------------
 enum TileCfg { T128x128, T128x64, T128x32, T64x64 };
 
+#ifndef EDL_PF_BIG
+#define EDL_PF_BIG 1
+#endif
+#ifndef EDL_PF_SMALL
+#define EDL_PF_SMALL 1
+#endif
+#ifndef EDL_BK_SMALL_MULT
+#define EDL_BK_SMALL_MULT 1
+#endif
+
 // reduction elements per tile: eight 16-byte vectors per row for either type
 template <typename T> constexpr int kConvBK = 8 * Elem<T>::VEC;
 
@@ -747,15 +769,18 @@ static TileCfg pick_tile(int M, int Nn, int* bm, int* bn) {
 template <typename T, int MODE>
 static void launch_cfg(TileCfg t, bool fast, dim3 grid, const ConvArgs& a, hipStream_t st) {
     constexpr int BK = kConvBK<T>;
+    // register sets of loads in flight: the small tile has few registers per set and the least work per tile
+    constexpr int PF_BIG = EDL_PF_BIG, PF_SMALL = EDL_PF_SMALL;
+    constexpr int BK_SMALL = MODE == CONV_WGRAD ? BK : EDL_BK_SMALL_MULT * BK;
     if (!fast) {   // element-wise kernel: one tile shape only
-        hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 1, 1, BK, false>), grid, dim3(256), 0, st, a);
+        hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 1, 1, BK, false, 1>), grid, dim3(256), 0, st, a);
         return;
     }
     switch (t) {
-        case T128x128: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 2, 2, BK, true>), grid, dim3(256), 0, st, a); break;
-        case T128x64: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 2, 1, BK, true>), grid, dim3(256), 0, st, a); break;
-        case T128x32: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 4, 1, 1, 1, BK, true>), grid, dim3(256), 0, st, a); break;
-        default: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 1, 1, BK, true>), grid, dim3(256), 0, st, a); break;
+        case T128x128: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 2, 2, BK, true, PF_BIG>), grid, dim3(256), 0, st, a); break;
+        case T128x64: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 2, 1, BK, true, PF_BIG>), grid, dim3(256), 0, st, a); break;
+        case T128x32: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 4, 1, 1, 1, BK, true, PF_BIG>), grid, dim3(256), 0, st, a); break;
+        default: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 1, 1, BK_SMALL, true, PF_SMALL>), grid, dim3(256), 0, st, a); break;
     }
 }
 
@@ -770,14 +795,24 @@ static const char* conv_label(int dtype, int mode, TileCfg t) {
     return names[dtype == 1 ? 1 : 0][mode][(int)t];
 }
 
+static unsigned long long magic_of(int d) {
+    if (d <= 0) return 0;
+    return ((1ull << 40) + (unsigned long long)d - 1) / (unsigned long long)d;
+}
+
 static bool conv_fast(int dtype, int mode, const ConvArgs& a) {
     const int ovec = (mode == CONV_WGRAD || dtype != 1) ? 4 : 8;
     return a.vecA && a.vecB && a.Nn % ovec == 0;
 }
 
 template <int MODE>
-static void launch_mode(int dtype, TileCfg t, dim3 grid, const ConvArgs& a, hipStream_t st) {
-    const bool fast = conv_fast(dtype, MODE, a);
+static void launch_mode(int dtype, TileCfg t, dim3 grid, const ConvArgs& a_in, hipStream_t st) {
+    ConvArgs a = a_in;
+    if (MODE == CONV_FWD) { a.magic_inner = magic_of(a.C); a.magic_taps = magic_of(a.S); }
+    else if (MODE == CONV_DGRAD) { a.magic_inner = magic_of(a.K); a.magic_taps = magic_of(a.ns); }
+    // the multiply-shift division is exact while (reduction index) * (divisor) < 2^40
+    const bool magic_ok = MODE == CONV_WGRAD || (double)a.Kred * (double)(MODE == CONV_FWD ? a.C : a.K) < 1e12;
+    const bool fast = conv_fast(dtype, MODE, a) && magic_ok;
     if (!fast) {
         t = T64x64;
         grid.x = (a.M + 63) / 64;
