@@ -46,6 +46,9 @@ struct Layout {
     int64_t idx = 0, labels = 0, row_loss = 0, losses = 0, partial = 0, coef = 0, wgrad_scratch = 0;
     int64_t wgrad_scratch_bytes = 0;
     int64_t ttable = 0;                  // TransposeEntry[] for the one-launch weight transpose
+    int cpad = 0;                        // channels of the stored input images (>= the logical count, see input_pad)
+    std::vector<int64_t> wpad;           // per op: zero-padded weight copy of a convolution on padded images (-1 if none)
+    int64_t dwpad = 0;                   // float32 gradient of such weights before it is compacted
     std::vector<int64_t> act, grad;      // per tensor (storage owners only; -1 otherwise)
     std::vector<int64_t> wT;             // per op: transposed weight copy (-1 if not needed)
     std::vector<int64_t> bn_save;        // per op
@@ -73,8 +76,27 @@ ConvGeom geom_of(const Graph& g, const Op& op, int n) {
     return q;
 }
 
+// Images whose channel count is not a multiple of the 16-byte vector (RGB) are
+// stored with every pixel padded to one vector, so that the first convolution
+// runs on the vector path.  Not when a flattened view of the images exists.
+int input_pad(const edl_config& c, const Graph& g) {
+    const int vec = c.dtype == EDL_DTYPE_BF16 ? 8 : 4;
+    const int C = g.tensors[0].C;
+    if (C % vec == 0 || C > vec) return C;
+    for (const Tensor& t : g.tensors)
+        if (t.alias_of == 0) return C;
+    return vec;
+}
+
+ConvGeom geom_padded(const Graph& g, const Op& op, int n, int cpad) {
+    ConvGeom q = geom_of(g, op, n);
+    if (op.x == 0) q.C = cpad;
+    return q;
+}
+
 void plan_layout(const edl_config& c, const Graph& g, Layout& L) {
     const int64_t esz = c.dtype == EDL_DTYPE_BF16 ? 2 : 4;
+    L.cpad = input_pad(c, g);
     int64_t o = 0;
     auto take = [&](int64_t bytes) { const int64_t at = o; o += align_up(bytes); return at; };
     L.params = take(4 * g.P);
@@ -97,12 +119,15 @@ void plan_layout(const edl_config& c, const Graph& g, Layout& L) {
     L.grad.assign(nt, -1);
     for (size_t t = 0; t < nt; ++t) {
         if (g.tensors[t].alias_of >= 0) continue;
-        const int64_t elems = g.tensors[t].elems() * c.max_shard;
+        int64_t elems = g.tensors[t].elems() * c.max_shard;
+        if (t == 0) elems = (int64_t)g.tensors[0].H * g.tensors[0].W * L.cpad * c.max_shard;
         L.act[t] = take(elems * (g.tensors[t].fp32 ? 4 : esz));
         if (t != 0) L.grad[t] = take(elems * esz);
     }
     const size_t no = g.ops.size();
     L.wT.assign(no, -1);
+    L.wpad.assign(no, -1);
+    int64_t dwpad_bytes = 16;
     L.bn_save.assign(no, -1);
     L.pool_arg.assign(no, -1);
     L.wgrad_scratch_bytes = 0;
@@ -111,8 +136,12 @@ void plan_layout(const edl_config& c, const Graph& g, Layout& L) {
         if (op.kind == OP_CONV) {
             const Tensor& tx = g.tensors[(size_t)op.x];
             if (storage_of(g, op.x) != 0) L.wT[i] = take((int64_t)op.K * op.R * op.S * tx.C * esz);
+            else if (op.x == 0 && L.cpad != tx.C) {
+                L.wpad[i] = take((int64_t)op.K * op.R * op.S * L.cpad * esz);
+                dwpad_bytes = std::max<int64_t>(dwpad_bytes, (int64_t)op.K * op.R * op.S * L.cpad * 4);
+            }
             L.wgrad_scratch_bytes = std::max<int64_t>(L.wgrad_scratch_bytes,
-                                                      (int64_t)conv_wgrad_scratch_bytes(geom_of(g, op, c.max_shard)));
+                                                      (int64_t)conv_wgrad_scratch_bytes(geom_padded(g, op, c.max_shard, L.cpad)));
             // the cut of a forward / dgrad reduction depends on the shard size: cover every size up to the largest
             for (int n = 1; n <= c.max_shard; n = n < 8 ? n + 1 : n + n / 4)
                 L.wgrad_scratch_bytes = std::max<int64_t>(L.wgrad_scratch_bytes,
@@ -126,6 +155,7 @@ void plan_layout(const edl_config& c, const Graph& g, Layout& L) {
         }
     }
     L.wgrad_scratch = take(std::max<int64_t>(L.wgrad_scratch_bytes, 16));
+    L.dwpad = take(dwpad_bytes);
     L.ttable = take((int64_t)sizeof(TransposeEntry) * std::max<size_t>(no, 1));
     L.total = o;
 }
@@ -246,6 +276,12 @@ static int refresh_weight_copies(edl_handle* h) {
 static void transpose_weights(edl_handle* h) {
     launch_weight_transpose_all(h->cfg.dtype, h->w(), h->arena, h->at<TransposeEntry>(h->L.ttable), h->t_entries,
                                 h->t_tiles, h->t_bytes, h->st);
+    for (size_t i = 0; i < h->g.ops.size(); ++i)
+        if (h->L.wpad[i] >= 0) {
+            const Op& op = h->g.ops[i];
+            launch_pad_weights(h->cfg.dtype, h->w() + op.w_off, h->arena + h->L.wpad[i], (int64_t)op.K * op.R * op.S,
+                               h->g.tensors[0].C, h->L.cpad, h->st);
+        }
 }
 
 int32_t edl_init(edl_handle** out, const edl_config* cfg, uint64_t seed, void* dev_arena, size_t arena_bytes,
@@ -335,14 +371,21 @@ static void forward_shard(edl_handle* h, const int64_t* dev_idx, int n, float* d
     const bool bf = dt == EDL_DTYPE_BF16;
     float* partial = h->at<float>(h->L.partial);
     const Tensor& tin = g.tensors[0];
-    if (dev_idx) launch_gather(dt, h->data_x, h->data_y, dev_idx, n, tin.elems(), h->act(0), h->at<int32_t>(h->L.labels), st);
+    if (dev_idx) {
+        if (h->L.cpad != tin.C)
+            launch_gather_pad(dt, h->data_x, h->data_y, dev_idx, n, (int64_t)tin.H * tin.W, tin.C, h->act(0),
+                              h->at<int32_t>(h->L.labels), st);
+        else
+            launch_gather(dt, h->data_x, h->data_y, dev_idx, n, tin.elems(), h->act(0), h->at<int32_t>(h->L.labels), st);
+    }
     if (op_hi > g.ops.size()) op_hi = g.ops.size();
     for (size_t i = op_lo; i < op_hi; ++i) {
         const Op& op = g.ops[i];
         switch (op.kind) {
             case OP_CONV: {
                 const void* wsrc = bf ? (const void*)(h->at<uint16_t>(h->L.shadow) + op.w_off) : (const void*)(h->w() + op.w_off);
-                launch_conv_fwd(dt, geom_of(g, op, n), h->act(op.x), wsrc, op.bias ? h->w() + op.b_off : nullptr, op.relu,
+                if (h->L.wpad[i] >= 0) wsrc = h->arena + h->L.wpad[i];
+                launch_conv_fwd(dt, geom_padded(g, op, n, h->L.cpad), h->act(op.x), wsrc, op.bias ? h->w() + op.b_off : nullptr, op.relu,
                                 g.tensors[(size_t)op.y].fp32, h->act(op.y), h->at<float>(h->L.wgrad_scratch),
                                 (size_t)h->L.wgrad_scratch_bytes, st);
                 break;
@@ -390,12 +433,15 @@ static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, siz
                 written[(size_t)storage_of(g, op.x)] = 1;
                 break;
             case OP_CONV: {
-                const ConvGeom q = geom_of(g, op, n);
+                const ConvGeom q = geom_padded(g, op, n, h->L.cpad);
                 const int64_t M = (int64_t)n * q.Ho * q.Wo;
+                const bool padded = h->L.wpad[ii] >= 0;
                 launch_bias_relu_backward(dt, h->act(op.y), h->grad(op.y), op.bias ? G + op.b_off : nullptr, M, op.K,
                                           op.relu, partial, st);
-                launch_conv_wgrad(dt, q, h->act(op.x), h->grad(op.y), G + op.w_off, h->at<float>(h->L.wgrad_scratch),
-                                  (size_t)h->L.wgrad_scratch_bytes, st);
+                launch_conv_wgrad(dt, q, h->act(op.x), h->grad(op.y), padded ? h->at<float>(h->L.dwpad) : G + op.w_off,
+                                  h->at<float>(h->L.wgrad_scratch), (size_t)h->L.wgrad_scratch_bytes, st);
+                if (padded)
+                    launch_unpad_rows(h->at<float>(h->L.dwpad), G + op.w_off, (int64_t)op.K * op.R * op.S, g.tensors[0].C, h->L.cpad, st);
                 const int sx = storage_of(g, op.x);
                 if (sx != 0) {
                     launch_conv_dgrad(dt, q, h->grad(op.y), h->arena + h->L.wT[ii], written[(size_t)sx] != 0, h->grad(op.x),
@@ -709,6 +755,7 @@ static int debug_tensor_ptr(edl_handle* h, int32_t t, int32_t which, int32_t n, 
     if (which == 1 && s == 0) { set_error("the input image has no gradient buffer"); return EDL_EINVAL; }
     *ptr = which == 0 ? (char*)h->act(t) : (char*)h->grad(t);
     *elems = h->g.tensors[(size_t)t].elems() * n;
+    if (s == 0 && h->L.cpad != h->g.tensors[0].C) { set_error("the input batch is stored channel-padded; it is set by edl_debug_forward only"); return EDL_EINVAL; }
     *is_f32 = h->cfg.dtype == EDL_DTYPE_F32 || (which == 0 && h->g.tensors[(size_t)s].fp32);
     return EDL_OK;
 }

@@ -257,6 +257,67 @@ __global__ __launch_bounds__(256) void gather_kernel(const float* __restrict__ d
     if (blockIdx.x == 0 && threadIdx.x == 0) out_y[i] = data_y[s];
 }
 
+// The same for images whose channel count is not a multiple of the vector
+// width: every pixel is written as one 16-byte vector, padded with zeros, so
+// that the first convolution can take the vector path.  grid: (pixel chunks, n)
+template <typename T>
+__global__ __launch_bounds__(256) void gather_pad_kernel(const float* __restrict__ data_x, const int32_t* __restrict__ data_y,
+                                                         const int64_t* __restrict__ idx, int64_t pixels, int C,
+                                                         T* __restrict__ out_x, int32_t* __restrict__ out_y) {
+    constexpr int VEC = Elem<T>::VEC;
+    const int i = blockIdx.y;
+    const int64_t s = idx[i];
+    const float* src = data_x + s * pixels * C;
+    T* dst = out_x + (int64_t)i * pixels * VEC;
+    for (int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q < pixels; q += (int64_t)gridDim.x * blockDim.x) {
+        Vec16<T> v;
+        #pragma unroll
+        for (int e = 0; e < VEC; ++e) v.e[e] = Elem<T>::from_f32(e < C ? src[q * C + e] : 0.f);
+        store_vec(dst + q * VEC, v);
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) out_y[i] = data_y[s];
+}
+
+void launch_gather_pad(int dtype, const float* data_x, const int32_t* data_y, const int64_t* idx, int n, int64_t pixels,
+                       int C, void* out_x, int32_t* out_y, hipStream_t st) {
+    dim3 grid(grid_for(pixels, 256, 256), n);
+    ProfScope ps("gather", 0.0, (4.0 * C + 16.0) * (double)pixels * n, st);
+    if (dtype == 1)
+        hipLaunchKernelGGL(gather_pad_kernel<bf16_t>, grid, dim3(256), 0, st, data_x, data_y, idx, pixels, C, (bf16_t*)out_x, out_y);
+    else
+        hipLaunchKernelGGL(gather_pad_kernel<float>, grid, dim3(256), 0, st, data_x, data_y, idx, pixels, C, (float*)out_x, out_y);
+}
+
+// dst[k][t][0..Cp) = cast(src[k][t][0..C)), zero beyond C  (weights of a convolution on padded images)
+template <typename T>
+__global__ __launch_bounds__(256) void pad_weights_kernel(const float* __restrict__ src, T* __restrict__ dst, int64_t rows, int C, int Cp) {
+    const int64_t total = rows * Cp;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t r = i / Cp;
+        const int c = (int)(i - r * Cp);
+        dst[i] = Elem<T>::from_f32(c < C ? src[r * C + c] : 0.f);
+    }
+}
+
+void launch_pad_weights(int dtype, const float* src, void* dst, int64_t rows, int C, int Cp, hipStream_t st) {
+    const int grid = grid_for(rows * Cp, 256, 4096);
+    if (dtype == 1) hipLaunchKernelGGL(pad_weights_kernel<bf16_t>, dim3(grid), dim3(256), 0, st, src, (bf16_t*)dst, rows, C, Cp);
+    else hipLaunchKernelGGL(pad_weights_kernel<float>, dim3(grid), dim3(256), 0, st, src, (float*)dst, rows, C, Cp);
+}
+
+// dst[r][0..C) = src[r][0..C) of rows of Cp floats (gradient of the padded weights back to the flat vector)
+__global__ __launch_bounds__(256) void unpad_rows_kernel(const float* __restrict__ src, float* __restrict__ dst, int64_t rows, int C, int Cp) {
+    const int64_t total = rows * C;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t r = i / C;
+        dst[i] = src[r * Cp + (i - r * C)];
+    }
+}
+
+void launch_unpad_rows(const float* src, float* dst, int64_t rows, int C, int Cp, hipStream_t st) {
+    hipLaunchKernelGGL(unpad_rows_kernel, dim3(grid_for(rows * C, 256, 4096)), dim3(256), 0, st, src, dst, rows, C, Cp);
+}
+
 void launch_gather(int dtype, const float* data_x, const int32_t* data_y, const int64_t* idx, int n,
                    int64_t sample_elems, void* out_x, int32_t* out_y, hipStream_t st) {
     dim3 grid(grid_for(sample_elems / 4 + 1, 256, 64), n);

@@ -36,6 +36,13 @@ void launch_cast_bf16(const float* src, uint16_t* dst, int64_t n, hipStream_t st
 void launch_gather(int dtype, const float* data_x, const int32_t* data_y, const int64_t* idx, int n,
                    int64_t sample_elems, void* out_x, int32_t* out_y, hipStream_t st);
 
+// images with C channels written as pixels of one zero-padded 16-byte vector each
+void launch_gather_pad(int dtype, const float* data_x, const int32_t* data_y, const int64_t* idx, int n, int64_t pixels,
+                       int C, void* out_x, int32_t* out_y, hipStream_t st);
+// weights [rows][C] float32 -> [rows][Cp] dtype, zero padded; and the way back for their gradient
+void launch_pad_weights(int dtype, const float* src, void* dst, int64_t rows, int C, int Cp, hipStream_t st);
+void launch_unpad_rows(const float* src, float* dst, int64_t rows, int C, int Cp, hipStream_t st);
+
 // ---- implicit-GEMM convolution --------------------------------------------
 enum ConvMode { CONV_FWD = 0, CONV_DGRAD = 1, CONV_WGRAD = 2 };
 

@@ -154,7 +154,8 @@ def forced_parity(model, dtype, n, N=None, seed=0, data_seed=1, H=0, W=0, C=0, c
     ops = [op for op in orc.graph.ops if op["kind"] != "flatten"]
     fwd, fwd_name, loss_g = 0.0, "", None
     for gi, op in enumerate(ops):
-        job.debug_set(tid(op["x"]), shaped(op["x"]))
+        if tid(op["x"]) != 0:                    # the input batch itself was gathered by debug_forward
+            job.debug_set(tid(op["x"]), shaped(op["x"]))
         job.debug_forward_op(gi, n)
         if op["kind"] == "loss":
             loss_g = float(job.losses(1)[0])
@@ -225,7 +226,8 @@ def layerwise_parity(model, dtype, n, N=None, seed=0, data_seed=1, H=0, W=0, C=0
     for gi, (oi, op) in enumerate(ops):
         kind = op["kind"]
         label = op.get("name", kind)
-        job.debug_set(tid(op["x"]), shaped(op["x"], orc.last_act[op["x"]]))
+        if tid(op["x"]) != 0:                    # the input batch itself was gathered by debug_forward
+            job.debug_set(tid(op["x"]), shaped(op["x"], orc.last_act[op["x"]]))
         if kind == "bn" and op["res"] is not None:
             job.debug_set(tid(op["res"]), shaped(op["res"], orc.last_act[op["res"]]))
         job.debug_forward_op(gi, n)
