@@ -129,37 +129,33 @@ __global__ __launch_bounds__(256) void colreduce_kernel(const T* __restrict__ x,
                 b[e] += red[1][(j * TX + tx) * VEC + e];
             }
         }
-        float* pa = partial + ((int64_t)blockIdx.y * 2 + 0) * C;
-        float* pb = partial + ((int64_t)blockIdx.y * 2 + 1) * C;
+        // partial[sum kind][channel][row block]: a channel's partial sums are contiguous for the finishing kernel
         #pragma unroll
         for (int e = 0; e < VEC; ++e) {
-            if (c0 + e < C) { pa[c0 + e] = a[e]; pb[c0 + e] = b[e]; }
+            if (c0 + e < C) {
+                partial[(int64_t)(c0 + e) * kRedRowBlocks + blockIdx.y] = a[e];
+                partial[(int64_t)(C + c0 + e) * kRedRowBlocks + blockIdx.y] = b[e];
+            }
         }
     }
 }
 
-// Sum of the row blocks' partial sums of one channel: 32 lanes take every 32nd
-// block in float64, then a butterfly.  blockDim = 256 = 8 channels x 32 lanes.
+// Sum of the row blocks' partial sums of one channel: one wave per channel, lane
+// L takes blocks L, L+64, ... (coalesced) in float64, then a butterfly.
+// blockDim = 256 = 4 channels x 64 lanes.
 __device__ __forceinline__ void sum_partials(const float* __restrict__ partial, int row_blocks, int C, int c, int sub,
                                              double& s, double& q) {
     s = 0;
     q = 0;
     if (c < C) {
-        int j = sub;
-        for (; j + 96 < row_blocks; j += 128) {     // four independent loads per sum in flight
-            const float s0 = partial[((int64_t)j * 2 + 0) * C + c], q0 = partial[((int64_t)j * 2 + 1) * C + c];
-            const float s1 = partial[((int64_t)(j + 32) * 2 + 0) * C + c], q1 = partial[((int64_t)(j + 32) * 2 + 1) * C + c];
-            const float s2 = partial[((int64_t)(j + 64) * 2 + 0) * C + c], q2 = partial[((int64_t)(j + 64) * 2 + 1) * C + c];
-            const float s3 = partial[((int64_t)(j + 96) * 2 + 0) * C + c], q3 = partial[((int64_t)(j + 96) * 2 + 1) * C + c];
-            s += (double)s0; s += (double)s1; s += (double)s2; s += (double)s3;
-            q += (double)q0; q += (double)q1; q += (double)q2; q += (double)q3;
-        }
-        for (; j < row_blocks; j += 32) {
-            s += (double)partial[((int64_t)j * 2 + 0) * C + c];
-            q += (double)partial[((int64_t)j * 2 + 1) * C + c];
+        const float* ps = partial + (int64_t)c * kRedRowBlocks;
+        const float* pq = partial + (int64_t)(C + c) * kRedRowBlocks;
+        for (int j = sub; j < row_blocks; j += 64) {
+            s += (double)ps[j];
+            q += (double)pq[j];
         }
     }
-    for (int o = 16; o > 0; o >>= 1) {
+    for (int o = 32; o > 0; o >>= 1) {
         s += __shfl_xor(s, o, 64);
         q += __shfl_xor(q, o, 64);
     }
@@ -169,7 +165,7 @@ __device__ __forceinline__ void sum_partials(const float* __restrict__ partial, 
 // model a joiner would receive (unbiased variance, momentum 0.1)
 __global__ __launch_bounds__(256) void bn_stats_finalize_kernel(const float* __restrict__ partial, int row_blocks, int64_t M,
                                                                 int C, float* __restrict__ mean_rstd, float* running) {
-    const int c = blockIdx.x * 8 + (threadIdx.x >> 5), sub = threadIdx.x & 31;
+    const int c = blockIdx.x * 4 + (threadIdx.x >> 6), sub = threadIdx.x & 63;
     double s, q;
     sum_partials(partial, row_blocks, C, c, sub, s, q);
     if (c >= C || sub != 0) return;
@@ -189,7 +185,7 @@ __global__ __launch_bounds__(256) void bn_stats_finalize_kernel(const float* __r
 __global__ __launch_bounds__(256) void bn_bwd_finalize_kernel(const float* __restrict__ partial, int row_blocks, int64_t M,
                                                               int C, float* __restrict__ dgamma, float* __restrict__ dbeta,
                                                               float* __restrict__ coef) {
-    const int c = blockIdx.x * 8 + (threadIdx.x >> 5), sub = threadIdx.x & 31;
+    const int c = blockIdx.x * 4 + (threadIdx.x >> 6), sub = threadIdx.x & 63;
     double s, q;
     sum_partials(partial, row_blocks, C, c, sub, s, q);
     if (c >= C || sub != 0) return;
@@ -201,7 +197,7 @@ __global__ __launch_bounds__(256) void bn_bwd_finalize_kernel(const float* __res
 
 __global__ __launch_bounds__(256) void bias_finalize_kernel(const float* __restrict__ partial, int row_blocks, int C,
                                                             float* __restrict__ dbias) {
-    const int c = blockIdx.x * 8 + (threadIdx.x >> 5), sub = threadIdx.x & 31;
+    const int c = blockIdx.x * 4 + (threadIdx.x >> 6), sub = threadIdx.x & 63;
     double s, q;
     sum_partials(partial, row_blocks, C, c, sub, s, q);
     if (c >= C || sub != 0) return;
@@ -298,7 +294,7 @@ static void bn_forward_t(const void* x, const void* res, void* y, const float* g
     hipLaunchKernelGGL((colreduce_kernel<T, VEC, 0>), s.grid, s.block, 0, st, (const T*)x, (const T*)nullptr, (T*)nullptr,
                        (const float*)nullptr, M, C, s.rows_per_block, 0, partial);
     }
-    hipLaunchKernelGGL(bn_stats_finalize_kernel, dim3((C + 7) / 8), dim3(256), 0, st, partial, s.row_blocks, M, C,
+    hipLaunchKernelGGL(bn_stats_finalize_kernel, dim3((C + 3) / 4), dim3(256), 0, st, partial, s.row_blocks, M, C,
                        save, running);
     ProfScope ps("bn_apply", 0.0, tb * (res ? 3.0 : 2.0), st);
     hipLaunchKernelGGL((bn_apply_kernel<T, VEC>), dim3(ew_grid(M * s.cvecs)), dim3(256), 0, st, (const T*)x,
@@ -327,7 +323,7 @@ static void bn_backward_t(const void* x, const void* y, const void* dy, void* dx
     hipLaunchKernelGGL((colreduce_kernel<T, VEC, 1>), s.grid, s.block, 0, st, (const T*)x, (const T*)y, (T*)dy, save, M, C,
                        s.rows_per_block, relu ? 1 : 0, partial);
     }
-    hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3((C + 7) / 8), dim3(256), 0, st, partial, s.row_blocks, M, C,
+    hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3((C + 3) / 4), dim3(256), 0, st, partial, s.row_blocks, M, C,
                        dgamma, dbeta, coef);
     ProfScope ps("bn_bwd_apply", 0.0, tb * ((relu ? 3.0 : 2.0) + 1.0 + (dres ? (dres_acc ? 2.0 : 1.0) : 0.0)), st);
     hipLaunchKernelGGL((bn_bwd_apply_kernel<T, VEC>), dim3(ew_grid(M * s.cvecs)), dim3(256), 0, st, (const T*)x,
@@ -356,7 +352,7 @@ static void bias_relu_backward_t(const void* y, void* dy, float* dbias, int64_t 
     hipLaunchKernelGGL((colreduce_kernel<T, VEC, 2>), s.grid, s.block, 0, st, (const T*)nullptr, (const T*)y, (T*)dy,
                        (const float*)nullptr, M, C, s.rows_per_block, relu ? 1 : 0, partial);
     if (dbias)
-        hipLaunchKernelGGL(bias_finalize_kernel, dim3((C + 7) / 8), dim3(256), 0, st, partial, s.row_blocks, C, dbias);
+        hipLaunchKernelGGL(bias_finalize_kernel, dim3((C + 3) / 4), dim3(256), 0, st, partial, s.row_blocks, C, dbias);
 }
 
 void launch_bias_relu_backward(int dtype, const void* y, void* dy, float* dbias, int64_t M, int C, bool relu,

@@ -2,6 +2,7 @@
 // with the momentum-SGD update (the all-reduce + optimizer of section 2.1 on
 // one GPU), the state copy a joining worker receives (section 4.2), and the
 // sample gather that stands for the prefetch pipeline (section 4.4).
+#include <algorithm>
 #include <cstdlib>
 
 #include "dev_common.h"
@@ -23,50 +24,56 @@ static inline int grid_for(int64_t work_items, int block, int max_blocks) {
 // streams, all fully coalesced.  NP > 0 fixes p at compile time so that all
 // p loads are in flight together.
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ float4 ld_stream(const float4* p, bool nt) {
-    if (!nt) return *p;
-    float4 v;
-    v.x = __builtin_nontemporal_load(&p->x); v.y = __builtin_nontemporal_load(&p->y);
-    v.z = __builtin_nontemporal_load(&p->z); v.w = __builtin_nontemporal_load(&p->w);
-    return v;
-}
-
-template <int NP, bool SHADOW, bool NT>
+// One lane handles VPT consecutive 16-byte vectors of every stream.
+template <int NP, bool SHADOW, int VPT>
 __global__ __launch_bounds__(256) void average_update_kernel(GradPtrs gp, int p, float* __restrict__ w,
                                                              float* __restrict__ v, uint16_t* __restrict__ w16,
                                                              int64_t nvec, int64_t P, float lr, float momentum,
                                                              float wd) {
     const int np = NP > 0 ? NP : p;
     const float fp = (float)np;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += stride) {
-        float4 s = ld_stream(reinterpret_cast<const float4*>(gp.g[0]) + i, NT);
+    const int64_t i0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * VPT;
+    if (i0 < nvec) {
+        float4 s[VPT], wi[VPT], vi[VPT];
+        #pragma unroll
+        for (int u = 0; u < VPT; ++u) {
+            const int64_t i = i0 + u < nvec ? i0 + u : nvec - 1;     // the last lane may repeat a vector (same result)
+            s[u] = reinterpret_cast<const float4*>(gp.g[0])[i];
+            wi[u] = reinterpret_cast<float4*>(w)[i];
+            vi[u] = reinterpret_cast<float4*>(v)[i];
+        }
         if (NP > 0) {
-            float4 t[NP > 1 ? NP - 1 : 1];
             #pragma unroll
-            for (int k = 1; k < NP; ++k) t[k - 1] = ld_stream(reinterpret_cast<const float4*>(gp.g[k]) + i, NT);
-            #pragma unroll
-            for (int k = 1; k < NP; ++k) { s.x += t[k - 1].x; s.y += t[k - 1].y; s.z += t[k - 1].z; s.w += t[k - 1].w; }
+            for (int k = 1; k < NP; ++k) {
+                #pragma unroll
+                for (int u = 0; u < VPT; ++u) {
+                    const int64_t i = i0 + u < nvec ? i0 + u : nvec - 1;
+                    const float4 t = reinterpret_cast<const float4*>(gp.g[k])[i];
+                    s[u].x += t.x; s[u].y += t.y; s[u].z += t.z; s[u].w += t.w;
+                }
+            }
         } else {
             for (int k = 1; k < np; ++k) {
-                const float4 t = reinterpret_cast<const float4*>(gp.g[k])[i];
-                s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+                #pragma unroll
+                for (int u = 0; u < VPT; ++u) {
+                    const int64_t i = i0 + u < nvec ? i0 + u : nvec - 1;
+                    const float4 t = reinterpret_cast<const float4*>(gp.g[k])[i];
+                    s[u].x += t.x; s[u].y += t.y; s[u].z += t.z; s[u].w += t.w;
+                }
             }
         }
-        float4 wi = reinterpret_cast<float4*>(w)[i];
-        float4 vi = reinterpret_cast<float4*>(v)[i];
-        vi.x = momentum * vi.x + (s.x / fp + wd * wi.x);
-        vi.y = momentum * vi.y + (s.y / fp + wd * wi.y);
-        vi.z = momentum * vi.z + (s.z / fp + wd * wi.z);
-        vi.w = momentum * vi.w + (s.w / fp + wd * wi.w);
-        wi.x -= lr * vi.x; wi.y -= lr * vi.y; wi.z -= lr * vi.z; wi.w -= lr * vi.w;
-        reinterpret_cast<float4*>(v)[i] = vi;
-        reinterpret_cast<float4*>(w)[i] = wi;
-        if (SHADOW) {
-            uint2 o;
-            o.x = (uint32_t)f32_to_bf16(wi.x) | ((uint32_t)f32_to_bf16(wi.y) << 16);
-            o.y = (uint32_t)f32_to_bf16(wi.z) | ((uint32_t)f32_to_bf16(wi.w) << 16);
-            reinterpret_cast<uint2*>(w16)[i] = o;
+        #pragma unroll
+        for (int u = 0; u < VPT; ++u) {
+            if (i0 + u >= nvec) break;
+            const int64_t i = i0 + u;
+            vi[u].x = momentum * vi[u].x + (s[u].x / fp + wd * wi[u].x);
+            vi[u].y = momentum * vi[u].y + (s[u].y / fp + wd * wi[u].y);
+            vi[u].z = momentum * vi[u].z + (s[u].z / fp + wd * wi[u].z);
+            vi[u].w = momentum * vi[u].w + (s[u].w / fp + wd * wi[u].w);
+            wi[u].x -= lr * vi[u].x; wi[u].y -= lr * vi[u].y; wi[u].z -= lr * vi[u].z; wi[u].w -= lr * vi[u].w;
+            reinterpret_cast<float4*>(v)[i] = vi[u];
+            reinterpret_cast<float4*>(w)[i] = wi[u];
+            if (SHADOW) reinterpret_cast<uint2*>(w16)[i] = make_uint2(pack2_bf16(wi[u].x, wi[u].y), pack2_bf16(wi[u].z, wi[u].w));
         }
     }
     // ragged tail (P not a multiple of 4): the first few lanes of block 0
@@ -83,23 +90,26 @@ __global__ __launch_bounds__(256) void average_update_kernel(GradPtrs gp, int p,
     }
 }
 
+template <int NP, int VPT>
+static void launch_update_t(int grid, const GradPtrs& grads, int p, float* w, float* v, uint16_t* w16, int64_t nvec, int64_t P,
+                            float lr, float momentum, float wd, hipStream_t st) {
+    if (w16) hipLaunchKernelGGL((average_update_kernel<NP, true, VPT>), dim3(grid), dim3(256), 0, st, grads, p, w, v, w16, nvec, P, lr, momentum, wd);
+    else hipLaunchKernelGGL((average_update_kernel<NP, false, VPT>), dim3(grid), dim3(256), 0, st, grads, p, w, v, w16, nvec, P, lr, momentum, wd);
+}
+
 void launch_average_update(int p, const GradPtrs& grads, float* w, float* v, uint16_t* w16, int64_t P, float lr,
                            float momentum, float wd, hipStream_t st) {
     const int64_t nvec = P / 4;
-    // one vector per lane and no loop: measured ~20% faster than a grid-stride loop over a few thousand workgroups
-    static const int max_blocks = getenv("EDL_TUNE_UPD_BLOCKS") ? atoi(getenv("EDL_TUNE_UPD_BLOCKS")) : (1 << 30);
-    static const bool nt = getenv("EDL_TUNE_UPD_NT") != nullptr;
-    const int grid = grid_for(nvec, 256, max_blocks);
+    // one workgroup per 256*VPT vectors, no grid-stride loop (measured ~20% faster than looping over a few thousand workgroups)
+    static const int vpt = getenv("EDL_TUNE_UPD_VPT") ? atoi(getenv("EDL_TUNE_UPD_VPT")) : 1;
+    const int64_t per_block = 256 * (vpt == 2 ? 2 : 1);
+    const int grid = (int)std::max<int64_t>(1, (nvec + per_block - 1) / per_block);
     // p gradient reads + w, v read and written (+ the bf16 copy)
     ProfScope ps("average_update", 0.0, (4.0 * p + 16.0 + (w16 ? 2.0 : 0.0)) * (double)P, st);
-#define EDL_UPD(NP)                                                                                             \
-    do {                                                                                                        \
-        if (w16 && nt) hipLaunchKernelGGL((average_update_kernel<NP, true, true>), dim3(grid), dim3(256), 0, st, grads, p, w, v,  \
-                                    w16, nvec, P, lr, momentum, wd);                                            \
-        else if (w16) hipLaunchKernelGGL((average_update_kernel<NP, true, false>), dim3(grid), dim3(256), 0, st, grads, p, w, v,  \
-                                    w16, nvec, P, lr, momentum, wd);                                            \
-        else hipLaunchKernelGGL((average_update_kernel<NP, false, false>), dim3(grid), dim3(256), 0, st, grads, p, w, v,     \
-                                w16, nvec, P, lr, momentum, wd);                                                \
+#define EDL_UPD(NP)                                                                                   \
+    do {                                                                                              \
+        if (vpt == 2) launch_update_t<NP, 2>(grid, grads, p, w, v, w16, nvec, P, lr, momentum, wd, st); \
+        else launch_update_t<NP, 1>(grid, grads, p, w, v, w16, nvec, P, lr, momentum, wd, st);          \
     } while (0)
     switch (p) {
         case 1: EDL_UPD(1); break;
