@@ -10,19 +10,29 @@
 //   wgrad     M = K               Nn = R*S*C   kk = pixel     A = dy^T, B = x^T gathered
 //
 // A workgroup of 4 waves owns a BM x BN output tile and walks the reduction in
-// steps of BK = 32 elements.  Tiles are staged in LDS with the reduction index
-// innermost (rows padded by one 16-byte vector, which makes the 16-byte
-// fragment reads conflict-free); each wave then feeds 32x32 MFMA tiles from
-// 16-byte fragments: one v_mfma_f32_32x32x16_bf16 per fragment pair for bf16,
-// four v_mfma_f32_32x32x2_f32 for float32 (lane L of a fragment holds row L%32
-// and the reduction slice selected by L/32; both operands use the same slice
-// order, so any order is a valid contraction).  Global loads of the next tile
-// are issued before the MFMAs of the current one.  For the weight gradient the
-// reduction index (the pixel) is the slow index in memory, so its tiles are
-// transposed on the way into LDS; its reduction is cut into splits whose
-// float32 partial tiles are added by a second kernel in split order.
-#include <cstdio>
-#include <cstdlib>
+// tiles of BK elements (eight 16-byte vectors per row).  Each wave feeds 32x32
+// MFMA tiles from 16-byte fragments: one v_mfma_f32_32x32x16_bf16 per fragment
+// pair for bf16, four v_mfma_f32_32x32x2_f32 for float32 (lane L of a fragment
+// holds row L%32 and the reduction slice selected by L/32; both operands use
+// the same slice order, so any order is a valid contraction).
+//
+//  * loads: 16-byte buffer loads whose range check returns zeros, so padding
+//    taps, ragged edges and the reduction tail need no branch; all loads of a
+//    tile are issued back to back and land in registers while the previous
+//    tile is contracted, then go to the other of two LDS stages (one barrier
+//    per tile).  The vector kernel (FAST) has no element-wise path; a second,
+//    slow instantiation handles operands that are not vector-shaped.
+//  * forward / dgrad tiles: rows of BK elements padded by one vector
+//    (conflict-free fragment reads).  Weight-gradient tiles: the reduction
+//    index (the pixel) is the slow index in memory, so they are stored as
+//    32-bit words [pixel pair][channel]; a fragment is four one-word reads.
+//  * dgrad of a strided convolution runs once per residue class of the input
+//    pixel modulo the stride and contracts only the taps that reach the class.
+//  * epilogue: through LDS as float32, out as 16-byte vectors (bf16 packed by
+//    the hardware conversion).
+//  * long reductions of small problems, and every weight gradient, are cut
+//    across workgroups; the float32 partial tiles are summed in split order by
+//    a second kernel (no float atomics: results are bit-reproducible).
 #include <algorithm>
 #include <deque>
 #include <string>
@@ -58,7 +68,25 @@ struct ConvArgs {
     // ceil(2^40 / d) for d = channels per tap and d = taps per kernel row: n / d == (n * magic) >> 40
     // for n * d < 2^40, which keeps the tap bookkeeping of the load loop free of branches
     unsigned long long magic_inner, magic_taps;
+    // Tile grid (gx row tiles, gy column tiles, gz cuts of the reduction), launched
+    // as gx*gy*gz workgroups in one dimension.  The hardware hands consecutive
+    // workgroups to the eight dies in turn and each die has its own L2, so with
+    // xcd_chunked the kernel gives every die one contiguous run of the tile
+    // sequence; n_fastest chooses which operand the neighbours of a run share.
+    int gx, gy, gz, xcd_chunked, n_fastest;
 };
+
+// (row tile, column tile, reduction cut) of this workgroup
+__device__ __forceinline__ void tile_of_block(const ConvArgs& a, int& bx, int& by, int& bz) {
+    const int total = a.gx * a.gy * a.gz;
+    int l = blockIdx.x;
+    if (a.xcd_chunked) {
+        const int q = total >> 3, r = total & 7, die = l & 7, slot = l >> 3;
+        l = die * q + (die < r ? die : r) + slot;   // die d owns q (+1 for d < r) consecutive tiles
+    }
+    if (a.n_fastest) { by = l % a.gy; l /= a.gy; bx = l % a.gx; bz = l / a.gx; }
+    else { bx = l % a.gx; l /= a.gx; by = l % a.gy; bz = l / a.gy; }
+}
 
 __device__ __forceinline__ int fast_div(int n, unsigned long long magic) {
     return (int)(((unsigned long long)(unsigned)n * magic) >> 40);
@@ -243,8 +271,10 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
     const T* __restrict__ Bg = (const T*)a.B;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
-    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
-    const int kbeg = blockIdx.z * a.ksplit;
+    int tile_x, tile_y, tile_z;
+    tile_of_block(a, tile_x, tile_y, tile_z);
+    const int m0 = tile_x * BM, n0 = tile_y * BN;
+    const int kbeg = tile_z * a.ksplit;
     int kend = kbeg + a.ksplit;
     if (kend > a.Kred) kend = a.Kred;
     const int nk = (kend - kbeg + BK - 1) / BK;
@@ -580,7 +610,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
                         if (a.accumulate) v += Elem<T>::to_f32(dst[o]);
                         dst[o] = Elem<T>::from_f32(v);
                     } else {
-                        ((float*)a.out)[((int64_t)blockIdx.z * a.M + row) * a.Nn + col] = v;
+                        ((float*)a.out)[((int64_t)tile_z * a.M + row) * a.Nn + col] = v;
                     }
                 }
             }
@@ -590,7 +620,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
     // staged: one wave row at a time goes through LDS as float32 (one word per
     // lane and row, conflict-free), then leaves as 16-byte vectors along the output row
     float* const stage = reinterpret_cast<float*>(smem);
-    unsigned char* const outp = (unsigned char*)a.out + (WG ? (int64_t)blockIdx.z * a.M * a.Nn * 4 : 0);
+    unsigned char* const outp = (unsigned char*)a.out + (WG ? (int64_t)tile_z * a.M * a.Nn * 4 : 0);
     const bool to_partial = !WG && a.partial != nullptr;     // cut reduction: raw float32 sums, finished by another kernel
     const bool f32_out = (MODE == CONV_FWD) && a.out_fp32 && !OUT_F32;
     #pragma unroll
@@ -625,7 +655,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
             if (row < a.M && col < a.Nn) {
                 const float* sp = stage + rl * STAGE_LD + cv * OVEC;
                 if (to_partial || f32_out) {
-                    float* d = to_partial ? a.partial + ((int64_t)blockIdx.z * a.M + row) * a.Nn + col
+                    float* d = to_partial ? a.partial + ((int64_t)tile_z * a.M + row) * a.Nn + col
                                           : (float*)a.out + (int64_t)row * a.Nn + col;
                     #pragma unroll
                     for (int e = 0; e < OVEC; e += 4) *reinterpret_cast<float4*>(d + e) = *reinterpret_cast<const float4*>(sp + e);
@@ -767,8 +797,11 @@ static TileCfg pick_tile(int M, int Nn, int* bm, int* bn) {
 }
 
 template <typename T, int MODE>
-static void launch_cfg(TileCfg t, bool fast, dim3 grid, const ConvArgs& a, hipStream_t st) {
+static void launch_cfg(TileCfg t, bool fast, dim3 tiles, const ConvArgs& a_in, hipStream_t st) {
     constexpr int BK = kConvBK<T>;
+    ConvArgs a = a_in;
+    a.gx = (int)tiles.x; a.gy = (int)tiles.y; a.gz = (int)tiles.z;
+    const dim3 grid(tiles.x * tiles.y * tiles.z);
     // register sets of loads in flight: the small tile has few registers per set and the least work per tile
     constexpr int PF_BIG = EDL_PF_BIG, PF_SMALL = EDL_PF_SMALL;
     constexpr int BK_SMALL = MODE == CONV_WGRAD ? BK : EDL_BK_SMALL_MULT * BK;
@@ -818,6 +851,14 @@ static void launch_mode(int dtype, TileCfg t, dim3 grid, const ConvArgs& a_in, h
         grid.x = (a.M + 63) / 64;
         grid.y = (a.Nn + 63) / 64;
     }
+    // Tile order: the reduction cuts are the slowest index, so a die's run of tiles
+    // stays within few cuts; inside a cut the tiles that share the larger operand
+    // (activations: the same row tile; weights: the same column tile) are neighbours.
+    static const int tune_xcd = env_int("EDL_TUNE_XCD", 1), tune_order = env_int("EDL_TUNE_ORDER", -1);
+    a.xcd_chunked = tune_xcd;
+    if (tune_order >= 0) a.n_fastest = tune_order;
+    else if (MODE == CONV_WGRAD) a.n_fastest = 1;
+    else a.n_fastest = (double)a.M * (MODE == CONV_FWD ? a.C : a.K) >= (double)a.Nn * a.Kred;
     // algorithmic work: 2*M*N*K flops; operands and result touched once
     const double esz = dtype == 1 ? 2.0 : 4.0;
     const double flops = 2.0 * (double)a.M * a.Nn * a.Kred;

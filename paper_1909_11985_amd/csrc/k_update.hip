@@ -171,37 +171,9 @@ void launch_cast_bf16(const float* src, uint16_t* dst, int64_t n, hipStream_t st
 // ---------------------------------------------------------------------------
 // dst[c][t][k] = cast(src[k][t][c]),  t = kernel tap.  32x32 tiles through LDS
 // so that both the read (c innermost) and the write (k innermost) coalesce.
-// grid: (ceil(C/32), ceil(K/32), taps)
 // ---------------------------------------------------------------------------
-template <typename T>
-__global__ __launch_bounds__(256) void weight_transpose_kernel(const float* __restrict__ src, T* __restrict__ dst, int K,
-                                                               int RS, int C) {
-    __shared__ float tile[32][33];
-    const int t = blockIdx.z;
-    const int c0 = blockIdx.x * 32, k0 = blockIdx.y * 32;
-    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
-    for (int i = ty; i < 32; i += 8) {
-        const int k = k0 + i, c = c0 + tx;
-        tile[i][tx] = (k < K && c < C) ? src[((int64_t)k * RS + t) * C + c] : 0.f;
-    }
-    __syncthreads();
-    for (int i = ty; i < 32; i += 8) {
-        const int c = c0 + i, k = k0 + tx;
-        if (c < C && k < K) dst[((int64_t)c * RS + t) * K + k] = Elem<T>::from_f32(tile[tx][i]);
-    }
-}
-
-void launch_weight_transpose(int dtype, const float* src, void* dst, int K, int RS, int C, hipStream_t st) {
-    dim3 grid((C + 31) / 32, (K + 31) / 32, RS);
-    ProfScope ps("weight_transpose", 0.0, (4.0 + (dtype == 1 ? 2.0 : 4.0)) * (double)K * RS * C, st);
-    if (dtype == 1)
-        hipLaunchKernelGGL(weight_transpose_kernel<bf16_t>, grid, dim3(256), 0, st, src, (bf16_t*)dst, K, RS, C);
-    else
-        hipLaunchKernelGGL(weight_transpose_kernel<float>, grid, dim3(256), 0, st, src, (float*)dst, K, RS, C);
-}
-
 // All layers in one launch: workgroup b finds its layer in the table by its
-// first-tile index, then does the same 32x32 tile.
+// first-tile index, then transposes one 32x32 tile of one tap.
 template <typename T>
 __global__ __launch_bounds__(256) void weight_transpose_all_kernel(const float* __restrict__ w, unsigned char* __restrict__ arena,
                                                                    const TransposeEntry* __restrict__ tab, int entries) {

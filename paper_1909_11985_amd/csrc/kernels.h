@@ -18,9 +18,8 @@ void launch_average_update(int p, const GradPtrs& grads, float* w, float* v, uin
                            float lr, float momentum, float wd, hipStream_t st);
 void launch_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
 void launch_fill_f32(float* dst, float value, int64_t n, hipStream_t st);
-// dst[c][r][s][k] = cast(src[k][r][s][c])  (weights for the input-gradient contraction)
-void launch_weight_transpose(int dtype, const float* src, void* dst, int K, int RS, int C, hipStream_t st);
-// the same for every layer of a model in one launch, from a table in device memory
+// dst[c][r][s][k] = cast(src[k][r][s][c]) (weights for the input-gradient contraction) for every
+// layer of a model in one launch, from a table in device memory
 struct TransposeEntry {
     int64_t src_off;     // floats from the start of the parameter vector
     int64_t dst_off;     // bytes from the start of the arena

@@ -230,3 +230,37 @@ def test_step_rejects_bad_requests():
     assert job.progress() == (0, 0, 0)                             # failed calls leave the cursor alone
     job.step(2, idx, off)
     assert job.progress() == (1, 0, 1)
+
+
+# ---------------------------------------------------------------- edge cases
+def test_update_of_nothing_is_a_no_op():
+    torch = _torch()
+    import paper_1909_11985_amd as E
+    w = torch.ones(64, device="cuda")
+    E.edl_average_update([w[:0]] if False else [w], w[:0] if False else w, torch.zeros(64, device="cuda"), None, 0.0, 0.0, 0.0)
+    torch.cuda.synchronize()
+    assert float(w.sum()) == 64.0                                   # lr = 0: weights unchanged
+    import ctypes as C
+    ptrs = (C.c_void_p * 1)(w.data_ptr())
+    assert E.lib.edl_average_update(1, ptrs, w.data_ptr(), w.data_ptr(), None, 0, 0.1, 0.9, 0.0, None) == 0   # P = 0
+
+
+def test_one_sample_per_worker_without_batchnorm():
+    """B = p: every worker's shard is a single sample (degenerate GEMM heights)."""
+    r = run_parity("mlp", "f32", N=16, B=8, schedule=[8, 4], verbose=False, **TINY["mlp"])
+    assert r["grad"] < TOL["f32"] and r["param"] < TOL["f32"], r
+    r = layerwise_parity("vgg16", "f32", 1, verbose=False, **TINY["vgg16"])
+    _assert_layerwise(r, "f32")
+
+
+def test_sixteen_workers():
+    """p_max = 16 is the most gradient buffers one update launch averages (generic-p kernel)."""
+    r = run_parity("mlp", "f32", N=64, B=32, schedule=[16, 1], verbose=False, **TINY["mlp"])
+    assert r["grad"] < TOL["f32"] and r["param"] < TOL["f32"], r
+
+
+def test_strided_and_padded_geometries_layerwise():
+    """Odd image sizes: ragged tiles, stride-2 residue classes of unequal size, 7x7 stem on 3 channels."""
+    geom = dict(H=30, W=26, C=3, classes=10, arch=(8, 1, 1, 1, 0))
+    for dtype in ("f32", "bf16"):
+        _assert_layerwise(layerwise_parity("resnet50", dtype, 3, verbose=False, **geom), dtype)
