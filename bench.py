@@ -105,7 +105,30 @@ def main():
     loss = job.step(p, want_loss=True)
     assert np.isfinite(loss), "training diverged"
 
-    # ---- per-kernel timing of a few more steps (HIP events on the launch stream) ----
+    # ---- per-kernel timing (HIP events on the launch stream) ----
+    # The timed steps above run the weight gradients on a second stream beside the
+    # rest of the backward pass.  Per-kernel durations are taken with one kernel at
+    # a time: a second job whose library keeps everything on one stream, timed
+    # plainly first (one_stream_ms_per_step) and then with an event pair per launch.
+    job.shutdown()
+    del job
+    prior = os.environ.get("EDL_TUNE_WGRAD_STREAM")
+    os.environ["EDL_TUNE_WGRAD_STREAM"] = "0"
+    job = E.Job(cfg, 0)
+    if prior is None:
+        del os.environ["EDL_TUNE_WGRAD_STREAM"]
+    else:
+        os.environ["EDL_TUNE_WGRAD_STREAM"] = prior
+    job.bind_dataset(dx, dy)
+    for _ in range(2):
+        job.step(p, want_loss=False)
+    job.sync()
+    cal_steps = max(3, args.steps // 2)
+    tc0 = time.perf_counter()
+    for _ in range(cal_steps):
+        job.step(p, want_loss=False)
+    job.sync()
+    one_stream_ms = (time.perf_counter() - tc0) * 1e3 / cal_steps
     prof_steps = 3
     E.edl_profile(True)
     for _ in range(prof_steps):
@@ -114,13 +137,13 @@ def main():
     rep = E.edl_profile_report()
     E.edl_profile(False)
     # An event pair reads longer than the kernel it brackets (the events' own
-    # dispatch).  The untimed steps keep the stream saturated (rocprofv3's kernel
-    # durations add up to the same step time), so what the pairs add is the
+    # dispatch).  The plain one-stream steps keep the stream saturated (rocprofv3's
+    # kernel durations add up to the same step time), so what the pairs add is the
     # bracketed total minus the plain step time, shared equally over the launches.
     rep = [r for r in rep if not r["name"].startswith("_")]
     launches = sum(r["launches"] for r in rep)
     raw_ms = sum(r["ms"] for r in rep)
-    overhead_ms = max(0.0, (raw_ms / prof_steps - ms_per_step) * prof_steps / max(launches, 1))
+    overhead_ms = max(0.0, (raw_ms / prof_steps - one_stream_ms) * prof_steps / max(launches, 1))
     for r in rep:
         r["ms_raw"] = r["ms"]
         r["ms"] = max(r["ms"] - overhead_ms * r["launches"], 0.05 * r["ms"])
@@ -158,7 +181,8 @@ def main():
         step_frac_of_mfma_peak=round(sizes.flops_per_sample * B / (ms_per_step * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS[dtype], 4),
         contraction_ms_per_step=round(conv_ms, 3),
         contraction_tflops=round(conv_flops / max(conv_ms, 1e-9) / 1e9, 2),
-        kernel_ms_per_step=round(sum(r["ms"] for r in rep) / prof_steps, 3))
+        kernel_ms_per_step=round(sum(r["ms"] for r in rep) / prof_steps, 3),
+        one_stream_ms_per_step=round(one_stream_ms, 4))
 
     # ---- the HBM-bound half of the metric on the VGG-16-sized state ----
     update, snapshot = None, None

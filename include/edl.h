@@ -192,6 +192,10 @@ int32_t edl_debug_set_tensor(edl_handle* h, int32_t t, int32_t which, int32_t n,
  * loss layer reads the labels given by edl_debug_set_labels (host int32[n]). */
 int32_t edl_debug_op_count(const edl_handle* h, int32_t* out_count);
 int32_t edl_debug_forward_op(edl_handle* h, int32_t op, int32_t n);
+/* Layers op_lo .. op_hi-1 in order, as they run inside a step (a convolution
+ * directly followed by its batch norm hands the batch statistics over instead
+ * of the batch norm reading the tensor again). */
+int32_t edl_debug_forward_range(edl_handle* h, int32_t op_lo, int32_t op_hi, int32_t n);
 int32_t edl_debug_backward_op(edl_handle* h, int32_t op, int32_t n, int32_t k);
 int32_t edl_debug_set_labels(edl_handle* h, const int32_t* labels, int32_t n);
 

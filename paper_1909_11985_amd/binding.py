@@ -84,6 +84,7 @@ _SIGS = {
     "edl_debug_set_tensor": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, _f32p],
     "edl_debug_op_count": [C.c_void_p, C.POINTER(C.c_int32)],
     "edl_debug_forward_op": [C.c_void_p, C.c_int32, C.c_int32],
+    "edl_debug_forward_range": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32],
     "edl_debug_backward_op": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32],
     "edl_debug_set_labels": [C.c_void_p, C.POINTER(C.c_int32), C.c_int32],
     "edl_shutdown": [C.c_void_p],
@@ -310,6 +311,9 @@ class Job:
 
     def debug_forward_op(self, op, n):
         _check(lib.edl_debug_forward_op(self._h, op, n))
+
+    def debug_forward_range(self, op_lo, op_hi, n):
+        _check(lib.edl_debug_forward_range(self._h, op_lo, op_hi, n))
 
     def debug_backward_op(self, op, n, k=0):
         _check(lib.edl_debug_backward_op(self._h, op, n, k))

@@ -27,6 +27,7 @@ namespace {
 
 constexpr int64_t kAlign = 256;
 constexpr int kIdxSlots = 4;
+constexpr int kReadyEvents = 64;   // ring of "dy is final" events for the second stream
 
 int64_t align_up(int64_t v, int64_t a = kAlign) { return (v + a - 1) / a * a; }
 
@@ -45,6 +46,9 @@ struct Layout {
     int64_t params = 0, momentum = 0, running = 0, shadow = 0, grads = 0, grad_stride = 0;
     int64_t idx = 0, labels = 0, row_loss = 0, losses = 0, partial = 0, coef = 0, wgrad_scratch = 0;
     int64_t wgrad_scratch_bytes = 0;
+    // partial sums of forward / dgrad reductions that are cut; apart from the weight-gradient
+    // scratch because weight gradients may run on the second stream meanwhile
+    int64_t splitk_scratch = 0, splitk_scratch_bytes = 0;
     int64_t ttable = 0;                  // TransposeEntry[] for the one-launch weight transpose
     int cpad = 0;                        // channels of the stored input images (>= the logical count, see input_pad)
     std::vector<int64_t> wpad;           // per op: zero-padded weight copy of a convolution on padded images (-1 if none)
@@ -131,6 +135,7 @@ void plan_layout(const edl_config& c, const Graph& g, Layout& L) {
     L.bn_save.assign(no, -1);
     L.pool_arg.assign(no, -1);
     L.wgrad_scratch_bytes = 0;
+    L.splitk_scratch_bytes = 0;
     for (size_t i = 0; i < no; ++i) {
         const Op& op = g.ops[i];
         if (op.kind == OP_CONV) {
@@ -144,10 +149,10 @@ void plan_layout(const edl_config& c, const Graph& g, Layout& L) {
                                                       (int64_t)conv_wgrad_scratch_bytes(geom_padded(g, op, c.max_shard, L.cpad)));
             // the cut of a forward / dgrad reduction depends on the shard size: cover every size up to the largest
             for (int n = 1; n <= c.max_shard; n = n < 8 ? n + 1 : n + n / 4)
-                L.wgrad_scratch_bytes = std::max<int64_t>(L.wgrad_scratch_bytes,
-                                                          (int64_t)conv_splitk_scratch_bytes(c.dtype, geom_of(g, op, n)));
-            L.wgrad_scratch_bytes = std::max<int64_t>(L.wgrad_scratch_bytes,
-                                                      (int64_t)conv_splitk_scratch_bytes(c.dtype, geom_of(g, op, c.max_shard)));
+                L.splitk_scratch_bytes = std::max<int64_t>(L.splitk_scratch_bytes,
+                                                           (int64_t)conv_splitk_scratch_bytes(c.dtype, geom_of(g, op, n)));
+            L.splitk_scratch_bytes = std::max<int64_t>(L.splitk_scratch_bytes,
+                                                       (int64_t)conv_splitk_scratch_bytes(c.dtype, geom_of(g, op, c.max_shard)));
         } else if (op.kind == OP_BN) {
             L.bn_save[i] = take(4 * 2 * (int64_t)op.K);
         } else if (op.kind == OP_MAXPOOL) {
@@ -155,6 +160,7 @@ void plan_layout(const edl_config& c, const Graph& g, Layout& L) {
         }
     }
     L.wgrad_scratch = take(std::max<int64_t>(L.wgrad_scratch_bytes, 16));
+    L.splitk_scratch = take(std::max<int64_t>(L.splitk_scratch_bytes, 16));
     L.dwpad = take(dwpad_bytes);
     L.ttable = take((int64_t)sizeof(TransposeEntry) * std::max<size_t>(no, 1));
     L.total = o;
@@ -183,6 +189,11 @@ struct edl_handle {
     hipEvent_t idx_event[kIdxSlots];
     int idx_slot = 0;
     float* loss_host = nullptr;
+    // second stream for the weight gradients (null: everything on st)
+    hipStream_t side = nullptr;
+    hipEvent_t ev_ready[kReadyEvents];
+    hipEvent_t ev_side_done = nullptr;
+    int ev_slot = 0;
 
     template <typename T> T* at(int64_t off) const { return reinterpret_cast<T*>(arena + off); }
     float* w() const { return at<float>(L.params); }
@@ -309,6 +320,14 @@ int32_t edl_init(edl_handle** out, const edl_config* cfg, uint64_t seed, void* d
         HIP_TRY(hipEventCreateWithFlags(&h->idx_event[s], hipEventDisableTiming));
     }
     HIP_TRY(hipHostMalloc((void**)&h->loss_host, sizeof(float) * kMaxP, hipHostMallocDefault));
+    {
+        const char* v = getenv("EDL_TUNE_WGRAD_STREAM");
+        if (!v || atoi(v) != 0) {
+            HIP_TRY(hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking));
+            for (int e = 0; e < kReadyEvents; ++e) HIP_TRY(hipEventCreateWithFlags(&h->ev_ready[e], hipEventDisableTiming));
+            HIP_TRY(hipEventCreateWithFlags(&h->ev_side_done, hipEventDisableTiming));
+        }
+    }
     std::vector<float> init((size_t)h->g.P);
     he_init(h->g, seed, init.data());
     HIP_TRY(hipMemcpyAsync(h->w(), init.data(), sizeof(float) * (size_t)h->g.P, hipMemcpyHostToDevice, h->st));
@@ -379,15 +398,19 @@ static void forward_shard(edl_handle* h, const int64_t* dev_idx, int n, float* d
             launch_gather(dt, h->data_x, h->data_y, dev_idx, n, tin.elems(), h->act(0), h->at<int32_t>(h->L.labels), st);
     }
     if (op_hi > g.ops.size()) op_hi = g.ops.size();
+    int stats_row_blocks = 0;   // > 0: the convolution just launched left the next batch norm's partial sums
     for (size_t i = op_lo; i < op_hi; ++i) {
         const Op& op = g.ops[i];
         switch (op.kind) {
             case OP_CONV: {
                 const void* wsrc = bf ? (const void*)(h->at<uint16_t>(h->L.shadow) + op.w_off) : (const void*)(h->w() + op.w_off);
                 if (h->L.wpad[i] >= 0) wsrc = h->arena + h->L.wpad[i];
-                launch_conv_fwd(dt, geom_padded(g, op, n, h->L.cpad), h->act(op.x), wsrc, op.bias ? h->w() + op.b_off : nullptr, op.relu,
-                                g.tensors[(size_t)op.y].fp32, h->act(op.y), h->at<float>(h->L.wgrad_scratch),
-                                (size_t)h->L.wgrad_scratch_bytes, st);
+                // the batch norm that follows (in this call) can take its sums from the convolution's epilogue
+                const bool bn_next = i + 1 < op_hi && g.ops[i + 1].kind == OP_BN && g.ops[i + 1].x == op.y;
+                stats_row_blocks = launch_conv_fwd(dt, geom_padded(g, op, n, h->L.cpad), h->act(op.x), wsrc,
+                                                   op.bias ? h->w() + op.b_off : nullptr, op.relu, g.tensors[(size_t)op.y].fp32,
+                                                   h->act(op.y), h->at<float>(h->L.splitk_scratch),
+                                                   (size_t)h->L.splitk_scratch_bytes, bn_next ? partial : nullptr, st);
                 break;
             }
             case OP_BN: {
@@ -395,7 +418,8 @@ static void forward_shard(edl_handle* h, const int64_t* dev_idx, int n, float* d
                 launch_bn_forward(dt, h->act(op.x), op.res >= 0 ? h->act(op.res) : nullptr, h->act(op.y), h->w() + op.w_off,
                                   h->w() + op.b_off, h->at<float>(h->L.bn_save[i]),
                                   update_running ? h->running() + op.run_off : nullptr, (int64_t)n * t.H * t.W, t.C, op.relu,
-                                  partial, st);
+                                  partial, stats_row_blocks, st);
+                stats_row_blocks = 0;
                 break;
             }
             case OP_MAXPOOL: {
@@ -426,6 +450,9 @@ static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, siz
     float* coef = h->at<float>(h->L.coef);
     std::vector<char> written(g.tensors.size(), 0);
     if (op_hi > g.ops.size()) op_hi = g.ops.size();
+    // per-kernel timing wants one kernel at a time
+    const bool overlap = h->side != nullptr && !prof_enabled();
+    bool used_side = false;
     for (size_t ii = op_hi; ii-- > op_lo;) {
         const Op& op = g.ops[ii];
         switch (op.kind) {
@@ -438,14 +465,26 @@ static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, siz
                 const bool padded = h->L.wpad[ii] >= 0;
                 launch_bias_relu_backward(dt, h->act(op.y), h->grad(op.y), op.bias ? G + op.b_off : nullptr, M, op.K,
                                           op.relu, partial, st);
+                // The weight gradient needs only dy (final from here on) and the layer's input, and nothing
+                // before the update reads it: it runs on the second stream, beside the chain of input
+                // gradients, whose short kernels leave part of the chip idle.
+                hipStream_t ws = st;
+                if (overlap) {
+                    hipEvent_t ev = h->ev_ready[h->ev_slot];
+                    h->ev_slot = (h->ev_slot + 1) % kReadyEvents;
+                    if (hipEventRecord(ev, st) == hipSuccess && hipStreamWaitEvent(h->side, ev, 0) == hipSuccess) {
+                        ws = h->side;
+                        used_side = true;
+                    }
+                }
                 launch_conv_wgrad(dt, q, h->act(op.x), h->grad(op.y), padded ? h->at<float>(h->L.dwpad) : G + op.w_off,
-                                  h->at<float>(h->L.wgrad_scratch), (size_t)h->L.wgrad_scratch_bytes, st);
+                                  h->at<float>(h->L.wgrad_scratch), (size_t)h->L.wgrad_scratch_bytes, ws);
                 if (padded)
-                    launch_unpad_rows(h->at<float>(h->L.dwpad), G + op.w_off, (int64_t)op.K * op.R * op.S, g.tensors[0].C, h->L.cpad, st);
+                    launch_unpad_rows(h->at<float>(h->L.dwpad), G + op.w_off, (int64_t)op.K * op.R * op.S, g.tensors[0].C, h->L.cpad, ws);
                 const int sx = storage_of(g, op.x);
                 if (sx != 0) {
                     launch_conv_dgrad(dt, q, h->grad(op.y), h->arena + h->L.wT[ii], written[(size_t)sx] != 0, h->grad(op.x),
-                                      h->at<float>(h->L.wgrad_scratch), (size_t)h->L.wgrad_scratch_bytes, st);
+                                      h->at<float>(h->L.splitk_scratch), (size_t)h->L.splitk_scratch_bytes, st);
                     written[(size_t)sx] = 1;
                 }
                 break;
@@ -489,6 +528,11 @@ static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, siz
                 break;
             }
         }
+    }
+    // the next forward pass overwrites the activations the weight gradients read, and the update reads G
+    if (used_side) {
+        (void)hipEventRecord(h->ev_side_done, h->side);
+        (void)hipStreamWaitEvent(st, h->ev_side_done, 0);
     }
 }
 
@@ -729,6 +773,16 @@ int32_t edl_debug_forward_op(edl_handle* h, int32_t op, int32_t n) {
     return EDL_OK;
 }
 
+int32_t edl_debug_forward_range(edl_handle* h, int32_t op_lo, int32_t op_hi, int32_t n) {
+    int rc = debug_prepare(h, n);
+    if (rc) return rc;
+    if (op_lo < 0 || op_hi < op_lo || (size_t)op_hi > h->g.ops.size()) { set_error("layers [%d, %d) out of range", op_lo, op_hi); return EDL_ERANGE; }
+    forward_shard(h, nullptr, n, h->at<float>(h->L.losses), false, (size_t)op_lo, (size_t)op_hi);
+    HIP_TRY(hipStreamSynchronize(h->st));
+    HIP_TRY(hipGetLastError());
+    return EDL_OK;
+}
+
 int32_t edl_debug_backward_op(edl_handle* h, int32_t op, int32_t n, int32_t k) {
     int rc = debug_prepare(h, n);
     if (rc) return rc;
@@ -809,6 +863,12 @@ int32_t edl_shutdown(edl_handle* h) {
         (void)hipEventDestroy(h->idx_event[s]);
     }
     if (h->loss_host) (void)hipHostFree(h->loss_host);
+    if (h->side) {
+        (void)hipStreamSynchronize(h->side);
+        for (int e = 0; e < kReadyEvents; ++e) (void)hipEventDestroy(h->ev_ready[e]);
+        (void)hipEventDestroy(h->ev_side_done);
+        (void)hipStreamDestroy(h->side);
+    }
     delete h;
     return EDL_OK;
 }

@@ -65,6 +65,10 @@ struct ConvArgs {
     int ph, pw, Hc, Wc, r0, s0, nr, ns;
     int ldb;     // fwd/dgrad: elements between consecutive rows of B
     float* partial;  // fwd/dgrad with a cut reduction: float32 [split][M][Nn] partial sums, else null
+    // fwd, vector path, whole reduction: if not null, the column sums of the stored output and of its
+    // squares over this tile's rows go to stats[c * kRedRowBlocks + row tile] and
+    // stats[(Nn + c) * kRedRowBlocks + row tile] (the layout of the batch-norm reduction's partial sums)
+    float* stats;
     // ceil(2^40 / d) for d = channels per tap and d = taps per kernel row: n / d == (n * magic) >> 40
     // for n * d < 2^40, which keeps the tap bookkeeping of the load loop free of branches
     unsigned long long magic_inner, magic_taps;
@@ -623,6 +627,12 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
     unsigned char* const outp = (unsigned char*)a.out + (WG ? (int64_t)tile_z * a.M * a.Nn * 4 : 0);
     const bool to_partial = !WG && a.partial != nullptr;     // cut reduction: raw float32 sums, finished by another kernel
     const bool f32_out = (MODE == CONV_FWD) && a.out_fp32 && !OUT_F32;
+    // Every lane stores the same OVEC columns in each of its rows (256 is a multiple of the
+    // vectors per row), so column sums of what it stored stay in registers until the end.
+    const bool with_stats = MODE == CONV_FWD && a.stats != nullptr;
+    float csum[OVEC], csq[OVEC];
+    #pragma unroll
+    for (int e = 0; e < OVEC; ++e) csum[e] = csq[e] = 0.f;
     #pragma unroll
     for (int pass = 0; pass < WM; ++pass) {
         if (wm == pass) {
@@ -669,6 +679,10 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
                         o.x += old.x; o.y += old.y; o.z += old.z; o.w += old.w;
                     }
                     *reinterpret_cast<float4*>(dst) = o;
+                    if (with_stats) {
+                        csum[0] += o.x; csq[0] += o.x * o.x; csum[1] += o.y; csq[1] += o.y * o.y;
+                        csum[2] += o.z; csq[2] += o.z * o.z; csum[3] += o.w; csq[3] += o.w * o.w;
+                    }
                 } else {
                     float4 o0 = *reinterpret_cast<const float4*>(sp), o1 = *reinterpret_cast<const float4*>(sp + 4);
                     if (MODE == CONV_DGRAD && a.accumulate) {
@@ -682,10 +696,40 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
                     pk.x = pack2_bf16(o0.x, o0.y); pk.y = pack2_bf16(o0.z, o0.w);
                     pk.z = pack2_bf16(o1.x, o1.y); pk.w = pack2_bf16(o1.z, o1.w);
                     *reinterpret_cast<uint4*>(dst) = pk;
+                    if (with_stats) {   // of the rounded values, as a reader of the stored tensor would see them
+                        const uint32_t w4[4] = {pk.x, pk.y, pk.z, pk.w};
+                        #pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float lo = __uint_as_float(w4[e] << 16), hi = __uint_as_float(w4[e] & 0xffff0000u);
+                            csum[(2 * e) % OVEC] += lo; csq[(2 * e) % OVEC] += lo * lo;
+                            csum[(2 * e + 1) % OVEC] += hi; csq[(2 * e + 1) % OVEC] += hi * hi;
+                        }
+                    }
                 }
             }
         }
         __syncthreads();
+    }
+    if (with_stats) {
+        // lanes with the same column vector differ in tid / CV: sum over them in a fixed order
+        constexpr int CV = BN / OVEC, GROUPS = 256 / CV;
+        static_assert(2 * GROUPS * BN * 4 <= SMEM_BYTES, "column sums fit the tile memory");
+        float* const red = stage;
+        const int grp = tid / CV, c0 = (tid % CV) * OVEC;
+        #pragma unroll
+        for (int e = 0; e < OVEC; ++e) {
+            red[grp * BN + c0 + e] = csum[e];
+            red[(GROUPS + grp) * BN + c0 + e] = csq[e];
+        }
+        __syncthreads();
+        for (int c = tid; c < BN; c += 256) {
+            if (n0 + c >= a.Nn) continue;
+            float s1 = 0.f, s2 = 0.f;
+            #pragma unroll 8
+            for (int gq = 0; gq < GROUPS; ++gq) { s1 += red[gq * BN + c]; s2 += red[(GROUPS + gq) * BN + c]; }
+            a.stats[(int64_t)(n0 + c) * kRedRowBlocks + tile_x] = s1;
+            a.stats[(int64_t)(a.Nn + n0 + c) * kRedRowBlocks + tile_x] = s2;
+        }
     }
 }
 
@@ -769,6 +813,9 @@ enum TileCfg { T128x128, T128x64, T128x32, T64x64 };
 #ifndef EDL_BK_SMALL_MULT
 #define EDL_BK_SMALL_MULT 1
 #endif
+#ifndef EDL_BK_BIG_DIV
+#define EDL_BK_BIG_DIV 1
+#endif
 
 // reduction elements per tile: eight 16-byte vectors per row for either type
 template <typename T> constexpr int kConvBK = 8 * Elem<T>::VEC;
@@ -805,13 +852,14 @@ static void launch_cfg(TileCfg t, bool fast, dim3 tiles, const ConvArgs& a_in, h
     // register sets of loads in flight: the small tile has few registers per set and the least work per tile
     constexpr int PF_BIG = EDL_PF_BIG, PF_SMALL = EDL_PF_SMALL;
     constexpr int BK_SMALL = MODE == CONV_WGRAD ? BK : EDL_BK_SMALL_MULT * BK;
+    constexpr int BK_BIG = MODE == CONV_WGRAD ? BK : BK / EDL_BK_BIG_DIV;
     if (!fast) {   // element-wise kernel: one tile shape only
         hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 1, 1, BK, false, 1>), grid, dim3(256), 0, st, a);
         return;
     }
     switch (t) {
-        case T128x128: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 2, 2, BK, true, PF_BIG>), grid, dim3(256), 0, st, a); break;
-        case T128x64: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 2, 1, BK, true, PF_BIG>), grid, dim3(256), 0, st, a); break;
+        case T128x128: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 2, 2, BK_BIG, true, PF_BIG>), grid, dim3(256), 0, st, a); break;
+        case T128x64: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 2, 1, BK_BIG, true, PF_BIG>), grid, dim3(256), 0, st, a); break;
         case T128x32: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 4, 1, 1, 1, BK, true, PF_BIG>), grid, dim3(256), 0, st, a); break;
         default: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 1, 1, BK_SMALL, true, PF_SMALL>), grid, dim3(256), 0, st, a); break;
     }
@@ -936,8 +984,8 @@ size_t conv_splitk_scratch_bytes(int dtype, const ConvGeom& g) {
     return need;
 }
 
-void launch_conv_fwd(int dtype, const ConvGeom& g, const void* x, const void* w, const float* bias, bool relu,
-                     bool out_fp32, void* y, float* scratch, size_t scratch_bytes, hipStream_t st) {
+int launch_conv_fwd(int dtype, const ConvGeom& g, const void* x, const void* w, const float* bias, bool relu,
+                    bool out_fp32, void* y, float* scratch, size_t scratch_bytes, float* stats, hipStream_t st) {
     const int VEC = dtype == 1 ? 8 : 4;
     ConvArgs a = base_args(g);
     a.A = x; a.B = w; a.out = y; a.bias = bias;
@@ -957,11 +1005,17 @@ void launch_conv_fwd(int dtype, const ConvGeom& g, const void* x, const void* w,
         if (splits > 1 && (scratch == nullptr || scratch_bytes < (size_t)splits * a.M * a.Nn * sizeof(float))) splits = 1;
     }
     if (splits > 1) { a.ksplit = ks; a.partial = scratch; }
-    launch_mode<CONV_FWD>(dtype, t, dim3((a.M + bm - 1) / bm, (a.Nn + bn - 1) / bn, splits), a, st);
+    const int row_tiles = (a.M + bm - 1) / bm;
+    static const bool tune_stats = env_int("EDL_TUNE_FUSED_STATS", 1) != 0;
+    const bool fused = tune_stats && stats != nullptr && splits == 1 && !out_fp32 && row_tiles <= kRedRowBlocks &&
+                       conv_fast(dtype, CONV_FWD, a) && (double)a.Kred * (double)a.C < 1e12;
+    a.stats = fused ? stats : nullptr;
+    launch_mode<CONV_FWD>(dtype, t, dim3(row_tiles, (a.Nn + bn - 1) / bn, splits), a, st);
     if (splits > 1) {
         if (dtype == 1) launch_finish<bf16_t>(a, splits, st);
         else launch_finish<float>(a, splits, st);
     }
+    return fused ? row_tiles : 0;
 }
 
 void launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dy, const void* wT, bool accumulate, void* dx,

@@ -286,15 +286,17 @@ static inline int ew_grid(int64_t total) {
 
 template <typename T, int VEC>
 static void bn_forward_t(const void* x, const void* res, void* y, const float* gamma, const float* beta,
-                         float* save, float* running, int64_t M, int C, bool relu, float* partial, hipStream_t st) {
+                         float* save, float* running, int64_t M, int C, bool relu, float* partial, int stats_row_blocks,
+                         hipStream_t st) {
     const RedShape s = red_shape(M, C, VEC);
     const double tb = (double)sizeof(T) * (double)M * C;   // bytes of one [M][C] tensor
-    {
-    ProfScope ps("bn_stats", 0.0, tb, st);
-    hipLaunchKernelGGL((colreduce_kernel<T, VEC, 0>), s.grid, s.block, 0, st, (const T*)x, (const T*)nullptr, (T*)nullptr,
-                       (const float*)nullptr, M, C, s.rows_per_block, 0, partial);
+    if (stats_row_blocks <= 0) {   // else the producer of x left the partial sums
+        ProfScope ps("bn_stats", 0.0, tb, st);
+        hipLaunchKernelGGL((colreduce_kernel<T, VEC, 0>), s.grid, s.block, 0, st, (const T*)x, (const T*)nullptr, (T*)nullptr,
+                           (const float*)nullptr, M, C, s.rows_per_block, 0, partial);
+        stats_row_blocks = s.row_blocks;
     }
-    hipLaunchKernelGGL(bn_stats_finalize_kernel, dim3((C + 3) / 4), dim3(256), 0, st, partial, s.row_blocks, M, C,
+    hipLaunchKernelGGL(bn_stats_finalize_kernel, dim3((C + 3) / 4), dim3(256), 0, st, partial, stats_row_blocks, M, C,
                        save, running);
     ProfScope ps("bn_apply", 0.0, tb * (res ? 3.0 : 2.0), st);
     hipLaunchKernelGGL((bn_apply_kernel<T, VEC>), dim3(ew_grid(M * s.cvecs)), dim3(256), 0, st, (const T*)x,
@@ -302,13 +304,14 @@ static void bn_forward_t(const void* x, const void* res, void* y, const float* g
 }
 
 void launch_bn_forward(int dtype, const void* x, const void* res, void* y, const float* gamma, const float* beta,
-                       float* save, float* running, int64_t M, int C, bool relu, float* partial, hipStream_t st) {
+                       float* save, float* running, int64_t M, int C, bool relu, float* partial, int stats_row_blocks,
+                       hipStream_t st) {
     if (dtype == 1) {
-        if (C % 8 == 0) bn_forward_t<bf16_t, 8>(x, res, y, gamma, beta, save, running, M, C, relu, partial, st);
-        else bn_forward_t<bf16_t, 1>(x, res, y, gamma, beta, save, running, M, C, relu, partial, st);
+        if (C % 8 == 0) bn_forward_t<bf16_t, 8>(x, res, y, gamma, beta, save, running, M, C, relu, partial, stats_row_blocks, st);
+        else bn_forward_t<bf16_t, 1>(x, res, y, gamma, beta, save, running, M, C, relu, partial, stats_row_blocks, st);
     } else {
-        if (C % 4 == 0) bn_forward_t<float, 4>(x, res, y, gamma, beta, save, running, M, C, relu, partial, st);
-        else bn_forward_t<float, 1>(x, res, y, gamma, beta, save, running, M, C, relu, partial, st);
+        if (C % 4 == 0) bn_forward_t<float, 4>(x, res, y, gamma, beta, save, running, M, C, relu, partial, stats_row_blocks, st);
+        else bn_forward_t<float, 1>(x, res, y, gamma, beta, save, running, M, C, relu, partial, stats_row_blocks, st);
     }
 }
 

@@ -50,9 +50,12 @@ struct ConvGeom {
     int K, R, S, stride, pad, Ho, Wo;
 };
 
-// y = conv(x, w) (+bias) (ReLU); y is float32 if out_fp32 else dtype
-void launch_conv_fwd(int dtype, const ConvGeom& g, const void* x, const void* w, const float* bias, bool relu,
-                     bool out_fp32, void* y, float* scratch, size_t scratch_bytes, hipStream_t st);
+// y = conv(x, w) (+bias) (ReLU); y is float32 if out_fp32 else dtype.
+// stats (may be null): the batch-norm reduction's partial-sum scratch.  If the launch can, it also leaves
+// there the per-row-tile column sums of y and y*y and returns the number of row tiles (what
+// launch_bn_forward takes as stats_row_blocks); it returns 0 if it left none.
+int launch_conv_fwd(int dtype, const ConvGeom& g, const void* x, const void* w, const float* bias, bool relu,
+                    bool out_fp32, void* y, float* scratch, size_t scratch_bytes, float* stats, hipStream_t st);
 // dx (+)= conv^T(dy, wT); wT is the [C][R][S][K] copy
 void launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dy, const void* wT, bool accumulate, void* dx,
                        float* scratch, size_t scratch_bytes, hipStream_t st);
@@ -67,7 +70,8 @@ size_t conv_wgrad_scratch_bytes(const ConvGeom& g);
 // partial: float32 scratch of 2 * kRedRowBlocks * C floats
 void launch_bn_forward(int dtype, const void* x, const void* res, void* y, const float* gamma, const float* beta,
                        float* save_mean_rstd /*[2C]*/, float* running /*[2C] or null*/, int64_t M, int C,
-                       bool relu, float* partial, hipStream_t st);
+                       bool relu, float* partial, int stats_row_blocks /*> 0: partial already holds the sums*/,
+                       hipStream_t st);
 void launch_bn_backward(int dtype, const void* x, const void* y, const void* dy, void* dx, void* dres,
                         bool dres_accumulate, const float* gamma, const float* save_mean_rstd,
                         float* dgamma, float* dbeta, int64_t M, int C, bool relu, float* partial, float* coef /*[2C]*/,

@@ -107,6 +107,7 @@ def run_parity(model, dtype, N, B, schedule, seed=0, data_seed=1, lr=0.1, moment
         elif verbose:
             print("  step %d p=%d: loss gpu %.6f oracle %.6f" % (t, p, loss, lo), flush=True)
         res["loss"] = max(res["loss"], abs(loss - lo) / max(abs(lo), 1e-30))
+        res.setdefault("loss_steps", []).append(abs(loss - lo) / max(abs(lo), 1e-30))
         assert np.isfinite(loss)
     res["job"], res["oracle"], res["table"] = job, orc, table
     return res
@@ -269,3 +270,59 @@ def layerwise_parity(model, dtype, n, N=None, seed=0, data_seed=1, H=0, W=0, C=0
                res.get("worst_dw")), flush=True)
     job.shutdown()
     return res
+
+
+def conv_bn_pair_parity(model, dtype, n, N=None, seed=0, data_seed=1, H=0, W=0, C=0, classes=0, arch=(), emulate=None,
+                        perturb=0.05):
+    """Every convolution that a batch norm follows, run together with that batch
+    norm the way a step runs them (the batch statistics come out of the
+    convolution's own pass over its output), on the oracle's input of the
+    convolution.  Returns the worst error of the batch norms' outputs and the
+    number of pairs."""
+    import torch
+    import paper_1909_11985_amd as E
+    from paper_1909_11985_amd.binding import make_config
+
+    N = N or n
+    dH, dW, dC, dK = DEFAULT_HWC[model]
+    hh, ww, cc, kk = H or dH, W or dW, C or dC, classes or dK
+    x, y = synth_inputs.dataset(data_seed, N, hh, ww, cc, kk)
+    cfg = make_config(model, dtype=dtype, N=N, B=n, p_max=1, max_shard=n, H=H, W=W, C_=C, classes=classes, arch=arch)
+    job = E.Job(cfg, seed)
+    job.bind_dataset(torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda())
+    if emulate is None:
+        emulate = dtype == "bf16"
+    orc = O.Oracle(model, seed, N, n, emulate_bf16=emulate, graph_kwargs=oracle_kwargs(model, H, W, C, classes, arch))
+    if perturb:
+        rng = np.random.default_rng(seed + 100)
+        orc.w = (orc.w + perturb * rng.standard_normal(orc.w.size) * (np.abs(orc.w) + 0.1)).astype(np.float32).astype(np.float64)
+        job.set_params(orc.w)
+    idx = np.arange(n, dtype=np.int64)
+    orc.forward_backward(x[idx].astype(np.float64), y[idx])
+    job.debug_forward(idx)
+    tensors = job.debug_tensors()
+
+    def tid(name):
+        return 0 if name == "x" else int(name[1:])
+
+    def shaped(name, a):
+        th, tw, tc, _ = tensors[tid(name)]
+        return np.asarray(a).reshape(n, th, tw, tc)
+
+    ops = [op for op in orc.graph.ops if op["kind"] != "flatten"]
+    worst, pairs, where = 0.0, 0, ""
+    for gi in range(len(ops) - 1):
+        conv, bn = ops[gi], ops[gi + 1]
+        if conv["kind"] != "conv" or bn["kind"] != "bn" or bn["x"] != conv["y"]:
+            continue
+        if tid(conv["x"]) != 0:
+            job.debug_set(tid(conv["x"]), shaped(conv["x"], orc.last_act[conv["x"]]))
+        if bn["res"] is not None:
+            job.debug_set(tid(bn["res"]), shaped(bn["res"], orc.last_act[bn["res"]]))
+        job.debug_forward_range(gi, gi + 2, n)
+        e = relerr(job.debug_get(tid(bn["y"]), n), shaped(bn["y"], orc.last_act[bn["y"]]))
+        pairs += 1
+        if e > worst:
+            worst, where = e, bn.get("name", "bn")
+    job.shutdown()
+    return dict(fwd=worst, pairs=pairs, worst=where)

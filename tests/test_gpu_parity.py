@@ -5,7 +5,7 @@ import pytest
 
 import synth_inputs
 from oracle import oracle as O
-from parity_util import TOL, forced_parity, layerwise_parity, relerr, run_parity
+from parity_util import TOL, conv_bn_pair_parity, forced_parity, layerwise_parity, relerr, run_parity
 
 pytestmark = pytest.mark.gpu
 
@@ -113,6 +113,21 @@ def test_layerwise_model_shapes(model, dtype, n, kw):
     _assert_layerwise(layerwise_parity(model, dtype, n, verbose=False, **kw), dtype)
 
 
+@pytest.mark.parametrize("model,dtype,n,kw", [
+    ("resnet20", "f32", 12, TINY["resnet20"]), ("resnet20", "f32", 5, TINY["resnet20"]),
+    ("resnet20", "f32", 64, {}), ("resnet20", "bf16", 16, {}),
+    ("resnet50", "f32", 8, dict(H=64, W=64)), ("resnet50", "bf16", 16, dict(H=64, W=64)),
+    ("resnet50", "bf16", 32, {}),                                 # the shard bench.py times
+])
+def test_convolution_hands_batch_statistics_to_its_batch_norm(model, dtype, n, kw):
+    """Convolution + batch norm run as a pair, as inside a step: the batch norm's output against the
+    oracle's, from the oracle's input of the convolution."""
+    r = conv_bn_pair_parity(model, dtype, n, **kw)
+    print(r)
+    assert r["pairs"] > 0
+    assert r["fwd"] < TOL[dtype], r
+
+
 def test_layerwise_resnet50_bf16_at_the_benchmark_shape():
     """Every layer of ResNet-50 at 224x224 with the shard of 32 that bench.py times."""
     r = layerwise_parity("resnet50", "bf16", 32, verbose=False)
@@ -165,8 +180,13 @@ def test_config2_resnet20_fp32_p_changes():
 
 
 def test_free_running_resnet50_bf16():
-    """Full ResNet-50 layer table at 64x64, p = 1, 2, 1: losses follow the oracle's."""
-    r = run_parity("resnet50", "bf16", N=64, B=32, schedule=[1, 2, 1], H=64, W=64, check_every_step=False)
+    """Full ResNet-50 layer table at 64x64, p = 1, 2, 1: losses follow the oracle's.  The first loss is a
+    forward pass on equal weights and is held to the bf16 bar.  Later ones see weights moved by
+    free-running bf16 gradients, which decorrelate from the oracle's with depth (rounding decides ReLU
+    signs; the pinned tests above take that away), so they are held to the loss curve only, at a
+    learning rate at which this net does not blow up on white-noise images."""
+    r = run_parity("resnet50", "bf16", N=64, B=32, schedule=[1, 2, 1], H=64, W=64, lr=0.002, check_every_step=False)
+    assert r["loss_steps"][0] < TOL["bf16"], r
     assert r["loss"] < 0.1, r
 
 
