@@ -72,6 +72,9 @@ struct ConvArgs {
     // ceil(2^40 / d) for d = channels per tap and d = taps per kernel row: n / d == (n * magic) >> 40
     // for n * d < 2^40, which keeps the tap bookkeeping of the load loop free of branches
     unsigned long long magic_inner, magic_taps;
+    // the same for d = pixels per image and d = pixels per image row of the row index's pixel grid
+    // (output pixels in the forward pass, the residue class's input pixels in dgrad), and for the tile grid
+    unsigned long long magic_hw, magic_w, magic_gx, magic_gy;
     // Tile grid (gx row tiles, gy column tiles, gz cuts of the reduction), launched
     // as gx*gy*gz workgroups in one dimension.  The hardware hands consecutive
     // workgroups to the eight dies in turn and each die has its own L2, so with
@@ -79,6 +82,10 @@ struct ConvArgs {
     // sequence; n_fastest chooses which operand the neighbours of a run share.
     int gx, gy, gz, xcd_chunked, n_fastest;
 };
+
+__device__ __forceinline__ int fast_div(int n, unsigned long long magic) {
+    return (int)(((unsigned long long)(unsigned)n * magic) >> 40);
+}
 
 // (row tile, column tile, reduction cut) of this workgroup
 __device__ __forceinline__ void tile_of_block(const ConvArgs& a, int& bx, int& by, int& bz) {
@@ -88,13 +95,20 @@ __device__ __forceinline__ void tile_of_block(const ConvArgs& a, int& bx, int& b
         const int q = total >> 3, r = total & 7, die = l & 7, slot = l >> 3;
         l = die * q + (die < r ? die : r) + slot;   // die d owns q (+1 for d < r) consecutive tiles
     }
-    if (a.n_fastest) { by = l % a.gy; l /= a.gy; bx = l % a.gx; bz = l / a.gx; }
-    else { bx = l % a.gx; l /= a.gx; by = l % a.gy; bz = l / a.gy; }
+    const bool mg = a.magic_gx != 0;   // 0: the grid is too large for the multiply-shift division
+    if (a.n_fastest) {
+        const int t = mg ? fast_div(l, a.magic_gy) : l / a.gy;
+        by = l - t * a.gy;
+        bz = mg ? fast_div(t, a.magic_gx) : t / a.gx;
+        bx = t - bz * a.gx;
+    } else {
+        const int t = mg ? fast_div(l, a.magic_gx) : l / a.gx;
+        bx = l - t * a.gx;
+        bz = mg ? fast_div(t, a.magic_gy) : t / a.gy;
+        by = t - bz * a.gy;
+    }
 }
 
-__device__ __forceinline__ int fast_div(int n, unsigned long long magic) {
-    return (int)(((unsigned long long)(unsigned)n * magic) >> 40);
-}
 
 // 16-byte load through a buffer descriptor: an offset at or beyond the
 // descriptor's extent returns zeros, so padding taps, ragged tile edges and
@@ -133,21 +147,21 @@ struct RowCtx {
     bool valid;
 };
 
-template <int MODE>
+template <int MODE, bool FAST>
 __device__ __forceinline__ RowCtx make_row(const ConvArgs& a, int m) {
     RowCtx c;
     c.valid = m < a.M;
     if (MODE == CONV_FWD) {
         const int hw = a.Ho * a.Wo;
-        const int n = m / hw, rem = m - n * hw;
-        const int ho = rem / a.Wo, wo = rem - ho * a.Wo;
+        const int n = FAST ? fast_div(m, a.magic_hw) : m / hw, rem = m - n * hw;
+        const int ho = FAST ? fast_div(rem, a.magic_w) : rem / a.Wo, wo = rem - ho * a.Wo;
         c.h0 = ho * a.stride - a.pad;
         c.w0 = wo * a.stride - a.pad;
         c.base = (((int64_t)n * a.H + c.h0) * a.W + c.w0) * a.C;
     } else {
         const int hw = a.Hc * a.Wc;
-        const int n = m / hw, rem = m - n * hw;
-        const int hq = rem / a.Wc, wq = rem - hq * a.Wc;
+        const int n = FAST ? fast_div(m, a.magic_hw) : m / hw, rem = m - n * hw;
+        const int hq = FAST ? fast_div(rem, a.magic_w) : rem / a.Wc, wq = rem - hq * a.Wc;
         c.h0 = a.ph + hq * a.stride + a.pad;
         c.w0 = a.pw + wq * a.stride + a.pad;
         c.base = (int64_t)n * a.Ho * a.Wo * a.K;
@@ -222,12 +236,12 @@ __device__ __forceinline__ unsigned a_voffset(const ConvArgs& a, const RowCtx& c
 
 // Row of the output matrix a tile row is stored to: the tile row itself, except
 // for a residue class of a strided dgrad, whose rows are every stride-th pixel.
-template <int MODE>
+template <int MODE, bool FAST = false>
 __device__ __forceinline__ int64_t out_row(const ConvArgs& a, int row) {
     if (MODE != CONV_DGRAD || a.stride == 1) return row;
     const int hw = a.Hc * a.Wc;
-    const int n = row / hw, rem = row - n * hw;
-    const int hq = rem / a.Wc, wq = rem - hq * a.Wc;
+    const int n = FAST ? fast_div(row, a.magic_hw) : row / hw, rem = row - n * hw;
+    const int hq = FAST ? fast_div(rem, a.magic_w) : rem / a.Wc, wq = rem - hq * a.Wc;
     return ((int64_t)n * a.H + a.ph + hq * a.stride) * a.W + a.pw + wq * a.stride;
 }
 
@@ -299,20 +313,20 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
     if (!WG) {
         const int inner = MODE == CONV_FWD ? a.C : a.K;
         kcur = kbeg + (tid % KV) * VEC;
-        const int tap = kcur / inner;
+        const int tap = FAST ? fast_div(kcur, a.magic_inner) : kcur / inner;
         tc = kcur - tap * inner;
         if (MODE == CONV_FWD) {
-            tr = tap / a.S;
+            tr = FAST ? fast_div(tap, a.magic_taps) : tap / a.S;
             ts = tap - tr * a.S;
             tap_off = (tr * a.W + ts) * a.C + tc;
         } else {
-            const int ri = a.ns > 0 ? tap / a.ns : 0;
+            const int ri = FAST ? fast_div(tap, a.magic_taps) : (a.ns > 0 ? tap / a.ns : 0);
             tr = a.r0 + ri * a.stride;
             ts = a.s0 + (tap - ri * a.ns) * a.stride;
             tap_off = (tr * a.S + ts) * a.K + tc;      // position inside a row of the transposed weights
         }
         #pragma unroll
-        for (int it = 0; it < ITER_A; ++it) rowA[it] = make_row<MODE>(a, m0 + (tid + it * 256) / KV);
+        for (int it = 0; it < ITER_A; ++it) rowA[it] = make_row<MODE, FAST>(a, m0 + (tid + it * 256) / KV);
         #pragma unroll
         for (int it = 0; it < ITER_B; ++it) {
             const int j = n0 + (tid + it * 256) / KV;
@@ -671,7 +685,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
                     for (int e = 0; e < OVEC; e += 4) *reinterpret_cast<float4*>(d + e) = *reinterpret_cast<const float4*>(sp + e);
                     continue;
                 }
-                unsigned char* dst = outp + (out_row<MODE>(a, row) * a.Nn + col) * OSZ;
+                unsigned char* dst = outp + (out_row<MODE, true>(a, row) * a.Nn + col) * OSZ;
                 if (OUT_F32) {
                     float4 o = *reinterpret_cast<const float4*>(sp);
                     if (MODE == CONV_DGRAD && a.accumulate) {
@@ -843,11 +857,26 @@ static TileCfg pick_tile(int M, int Nn, int* bm, int* bn) {
     return t;
 }
 
+static unsigned long long magic_of(int d) {
+    if (d <= 0) return 0;
+    return ((1ull << 40) + (unsigned long long)d - 1) / (unsigned long long)d;
+}
+
+// n / d == (n * magic_of(d)) >> 40 for every 0 <= n <= n_max: the error term needs n * d < 2^40 and the
+// product must fit 64 bits
+static bool magic_fits(double n_max, int d) {
+    if (d <= 0) return true;
+    return n_max * (double)d < 1.0e12 && n_max * (double)magic_of(d) < 9.0e18;
+}
+
 template <typename T, int MODE>
 static void launch_cfg(TileCfg t, bool fast, dim3 tiles, const ConvArgs& a_in, hipStream_t st) {
     constexpr int BK = kConvBK<T>;
     ConvArgs a = a_in;
     a.gx = (int)tiles.x; a.gy = (int)tiles.y; a.gz = (int)tiles.z;
+    const double total = (double)a.gx * a.gy * a.gz;
+    const bool mg = magic_fits(total, a.gx) && magic_fits(total, a.gy);
+    a.magic_gx = mg ? magic_of(a.gx) : 0; a.magic_gy = mg ? magic_of(a.gy) : 0;
     const dim3 grid(tiles.x * tiles.y * tiles.z);
     // register sets of loads in flight: the small tile has few registers per set and the least work per tile
     constexpr int PF_BIG = EDL_PF_BIG, PF_SMALL = EDL_PF_SMALL;
@@ -876,14 +905,20 @@ static const char* conv_label(int dtype, int mode, TileCfg t) {
     return names[dtype == 1 ? 1 : 0][mode][(int)t];
 }
 
-static unsigned long long magic_of(int d) {
-    if (d <= 0) return 0;
-    return ((1ull << 40) + (unsigned long long)d - 1) / (unsigned long long)d;
-}
 
 static bool conv_fast(int dtype, int mode, const ConvArgs& a) {
     const int ovec = (mode == CONV_WGRAD || dtype != 1) ? 4 : 8;
     return a.vecA && a.vecB && a.Nn % ovec == 0;
+}
+
+// every multiply-shift division of the vector kernel is exact for this problem
+static bool conv_magic_ok(int mode, const ConvArgs& a) {
+    if (mode == CONV_WGRAD) return true;
+    const int inner = mode == CONV_FWD ? a.C : a.K, taps = mode == CONV_FWD ? a.S : a.ns;
+    const int pix = mode == CONV_FWD ? a.Ho * a.Wo : a.Hc * a.Wc, wpix = mode == CONV_FWD ? a.Wo : a.Wc;
+    const double kmax = (double)a.Kred + 256.0, mmax = (double)a.M + 256.0;
+    return magic_fits(kmax, inner) && magic_fits(kmax / (inner > 0 ? inner : 1) + 1.0, taps) &&
+           magic_fits(mmax, pix) && magic_fits((double)pix, wpix);
 }
 
 template <int MODE>
@@ -891,8 +926,9 @@ static void launch_mode(int dtype, TileCfg t, dim3 grid, const ConvArgs& a_in, h
     ConvArgs a = a_in;
     if (MODE == CONV_FWD) { a.magic_inner = magic_of(a.C); a.magic_taps = magic_of(a.S); }
     else if (MODE == CONV_DGRAD) { a.magic_inner = magic_of(a.K); a.magic_taps = magic_of(a.ns); }
-    // the multiply-shift division is exact while (reduction index) * (divisor) < 2^40
-    const bool magic_ok = MODE == CONV_WGRAD || (double)a.Kred * (double)(MODE == CONV_FWD ? a.C : a.K) < 1e12;
+    if (MODE == CONV_FWD) { a.magic_hw = magic_of(a.Ho * a.Wo); a.magic_w = magic_of(a.Wo); }
+    else if (MODE == CONV_DGRAD) { a.magic_hw = magic_of(a.Hc * a.Wc); a.magic_w = magic_of(a.Wc); }
+    const bool magic_ok = conv_magic_ok(MODE, a);
     const bool fast = conv_fast(dtype, MODE, a) && magic_ok;
     if (!fast) {
         t = T64x64;
@@ -1008,7 +1044,7 @@ int launch_conv_fwd(int dtype, const ConvGeom& g, const void* x, const void* w, 
     const int row_tiles = (a.M + bm - 1) / bm;
     static const bool tune_stats = env_int("EDL_TUNE_FUSED_STATS", 1) != 0;
     const bool fused = tune_stats && stats != nullptr && splits == 1 && !out_fp32 && row_tiles <= kRedRowBlocks &&
-                       conv_fast(dtype, CONV_FWD, a) && (double)a.Kred * (double)a.C < 1e12;
+                       conv_fast(dtype, CONV_FWD, a) && conv_magic_ok(CONV_FWD, a);
     a.stats = fused ? stats : nullptr;
     launch_mode<CONV_FWD>(dtype, t, dim3(row_tiles, (a.Nn + bn - 1) / bn, splits), a, st);
     if (splits > 1) {
