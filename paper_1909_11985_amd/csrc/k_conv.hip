@@ -786,29 +786,63 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restri
 // store in the output type.  Four outputs per lane.
 template <typename T>
 __global__ __launch_bounds__(256) void splitk_finish_kernel(const float* __restrict__ part, void* out, const float* __restrict__ bias,
-                                                            int64_t M, int Nn, int splits, int relu, int out_fp32, int accumulate) {
-    const int64_t n4 = M * Nn / 4, mn = M * Nn;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (int64_t)gridDim.x * blockDim.x) {
-        float4 s = reinterpret_cast<const float4*>(part)[i];
-        for (int k = 1; k < splits; ++k) {
-            const float4 t = reinterpret_cast<const float4*>(part + (int64_t)k * mn)[i];
-            s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
-        }
-        const int col = (int)((i * 4) % Nn);
-        if (bias) { s.x += bias[col]; s.y += bias[col + 1]; s.z += bias[col + 2]; s.w += bias[col + 3]; }
-        if (relu) { s.x = fmaxf(s.x, 0.f); s.y = fmaxf(s.y, 0.f); s.z = fmaxf(s.z, 0.f); s.w = fmaxf(s.w, 0.f); }
-        if (out_fp32 || sizeof(T) == 4) {
-            float4* d = reinterpret_cast<float4*>(out) + i;
-            if (accumulate) { const float4 o = *d; s.x += o.x; s.y += o.y; s.z += o.z; s.w += o.w; }
-            *d = s;
-        } else {
-            uint2* d = reinterpret_cast<uint2*>(out) + i;
-            if (accumulate) {
-                const uint2 o = *d;
-                s.x += __uint_as_float(o.x << 16); s.y += __uint_as_float(o.x & 0xffff0000u);
-                s.z += __uint_as_float(o.y << 16); s.w += __uint_as_float(o.y & 0xffff0000u);
+                                                            int64_t M, int Nn, int splits, int relu, int out_fp32, int accumulate,
+                                                            int rows_per_block, float* __restrict__ stats) {
+    // a workgroup owns 64 columns of rows_per_block rows: 16 lanes across (4 columns each), 16 rows at a time
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    const int col = (blockIdx.x * 16 + tx) * 4;
+    const bool active = col < Nn;
+    const int64_t mn = M * Nn;
+    const int64_t r0 = (int64_t)blockIdx.y * rows_per_block;
+    int64_t r1 = r0 + rows_per_block;
+    if (r1 > M) r1 = M;
+    float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (bias && active) bv = *reinterpret_cast<const float4*>(bias + col);
+    float cs[4] = {0.f, 0.f, 0.f, 0.f}, cq[4] = {0.f, 0.f, 0.f, 0.f};
+    if (active) {
+        for (int64_t r = r0 + ty; r < r1; r += 16) {
+            const int64_t i = r * Nn + col;
+            float4 s = *reinterpret_cast<const float4*>(part + i);
+            for (int k = 1; k < splits; ++k) {
+                const float4 t = *reinterpret_cast<const float4*>(part + (int64_t)k * mn + i);
+                s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
             }
-            *d = make_uint2(pack2_bf16(s.x, s.y), pack2_bf16(s.z, s.w));
+            s.x += bv.x; s.y += bv.y; s.z += bv.z; s.w += bv.w;
+            if (relu) { s.x = fmaxf(s.x, 0.f); s.y = fmaxf(s.y, 0.f); s.z = fmaxf(s.z, 0.f); s.w = fmaxf(s.w, 0.f); }
+            if (out_fp32 || sizeof(T) == 4) {
+                float4* d = reinterpret_cast<float4*>((float*)out + i);
+                if (accumulate) { const float4 o = *d; s.x += o.x; s.y += o.y; s.z += o.z; s.w += o.w; }
+                *d = s;
+            } else {
+                uint2* d = reinterpret_cast<uint2*>((bf16_t*)out + i);
+                if (accumulate) {
+                    const uint2 o = *d;
+                    s.x += __uint_as_float(o.x << 16); s.y += __uint_as_float(o.x & 0xffff0000u);
+                    s.z += __uint_as_float(o.y << 16); s.w += __uint_as_float(o.y & 0xffff0000u);
+                }
+                const uint2 pk = make_uint2(pack2_bf16(s.x, s.y), pack2_bf16(s.z, s.w));
+                *d = pk;
+                // what a reader of the stored tensor sees
+                s.x = __uint_as_float(pk.x << 16); s.y = __uint_as_float(pk.x & 0xffff0000u);
+                s.z = __uint_as_float(pk.y << 16); s.w = __uint_as_float(pk.y & 0xffff0000u);
+            }
+            cs[0] += s.x; cq[0] += s.x * s.x; cs[1] += s.y; cq[1] += s.y * s.y;
+            cs[2] += s.z; cq[2] += s.z * s.z; cs[3] += s.w; cq[3] += s.w * s.w;
+        }
+    }
+    if (stats == nullptr) return;
+    // column sums of the stored values and of their squares, per row block (the batch-norm reduction's layout)
+    __shared__ float red[2][16][64 + 1];
+    #pragma unroll
+    for (int e = 0; e < 4; ++e) { red[0][ty][tx * 4 + e] = cs[e]; red[1][ty][tx * 4 + e] = cq[e]; }
+    __syncthreads();
+    if (threadIdx.x < 128) {
+        const int kind = threadIdx.x >> 6, c = threadIdx.x & 63, cg = blockIdx.x * 64 + c;
+        if (cg < Nn) {
+            float t = 0.f;
+            #pragma unroll
+            for (int j = 0; j < 16; ++j) t += red[kind][j][c];
+            stats[(int64_t)(kind * Nn + cg) * kRedRowBlocks + blockIdx.y] = t;
         }
     }
 }
@@ -983,7 +1017,7 @@ static int plan_splitk(int dtype, int M, int Nn, int Kred, int bm, int bn, int* 
     const int64_t tiles = (int64_t)((M + bm - 1) / bm) * ((Nn + bn - 1) / bn);
     const int nk = (Kred + BK - 1) / BK;
     int splits = 1;
-    static const int max_tiles = env_int("EDL_TUNE_SPLITK_TILES", 400), target = env_int("EDL_TUNE_SPLITK_TARGET", 768);
+    static const int max_tiles = env_int("EDL_TUNE_SPLITK_TILES", 300), target = env_int("EDL_TUNE_SPLITK_TARGET", 768);
     if (tiles < max_tiles && nk >= 8) {
         splits = (int)((target + tiles - 1) / tiles);
         if (splits > nk / 4) splits = nk / 4;
@@ -995,14 +1029,22 @@ static int plan_splitk(int dtype, int M, int Nn, int Kred, int bm, int bn, int* 
     return (Kred + ks - 1) / ks;
 }
 
+// Returns the number of row blocks whose column sums it left in stats (0 if stats is null).
 template <typename T>
-static void launch_finish(const ConvArgs& a, int splits, hipStream_t st) {
-    const int64_t n4 = (int64_t)a.M * a.Nn / 4;
-    int64_t blocks = (n4 + 255) / 256;
-    if (blocks > 4096) blocks = 4096;
+static int launch_finish(const ConvArgs& a, int splits, float* stats, hipStream_t st) {
+    const int col_blocks = (a.Nn + 63) / 64;
+    // about 1024 workgroups, at least 16 rows each
+    int64_t rb = (1024 + col_blocks - 1) / col_blocks;
+    const int64_t max_rb = ((int64_t)a.M + 15) / 16;
+    if (rb > max_rb) rb = max_rb;
+    if (rb > kRedRowBlocks) rb = kRedRowBlocks;
+    if (rb < 1) rb = 1;
+    const int rows_per_block = (int)(((int64_t)a.M + rb - 1) / rb);
+    const int row_blocks = (int)(((int64_t)a.M + rows_per_block - 1) / rows_per_block);
     ProfScope ps("splitk_finish", 0.0, 4.0 * (double)a.M * a.Nn * splits + (a.out_fp32 ? 4.0 : (double)sizeof(T)) * (double)a.M * a.Nn, st);
-    hipLaunchKernelGGL(splitk_finish_kernel<T>, dim3((int)blocks), dim3(256), 0, st, a.partial, a.out, a.bias, (int64_t)a.M, a.Nn, splits,
-                       a.relu, a.out_fp32, a.accumulate);
+    hipLaunchKernelGGL(splitk_finish_kernel<T>, dim3(col_blocks, row_blocks), dim3(256), 0, st, a.partial, a.out, a.bias, (int64_t)a.M,
+                       a.Nn, splits, a.relu, a.out_fp32, a.accumulate, rows_per_block, stats);
+    return stats ? row_blocks : 0;
 }
 
 size_t conv_splitk_scratch_bytes(int dtype, const ConvGeom& g) {
@@ -1043,13 +1085,14 @@ int launch_conv_fwd(int dtype, const ConvGeom& g, const void* x, const void* w, 
     if (splits > 1) { a.ksplit = ks; a.partial = scratch; }
     const int row_tiles = (a.M + bm - 1) / bm;
     static const bool tune_stats = env_int("EDL_TUNE_FUSED_STATS", 1) != 0;
-    const bool fused = tune_stats && stats != nullptr && splits == 1 && !out_fp32 && row_tiles <= kRedRowBlocks &&
-                       conv_fast(dtype, CONV_FWD, a) && conv_magic_ok(CONV_FWD, a);
+    const bool want_stats = tune_stats && stats != nullptr && !out_fp32 && conv_fast(dtype, CONV_FWD, a) && conv_magic_ok(CONV_FWD, a);
+    // whole reduction in one workgroup: the epilogue leaves the sums; cut reduction: the finishing kernel does
+    const bool fused = want_stats && splits == 1 && row_tiles <= kRedRowBlocks;
     a.stats = fused ? stats : nullptr;
     launch_mode<CONV_FWD>(dtype, t, dim3(row_tiles, (a.Nn + bn - 1) / bn, splits), a, st);
     if (splits > 1) {
-        if (dtype == 1) launch_finish<bf16_t>(a, splits, st);
-        else launch_finish<float>(a, splits, st);
+        float* fs = want_stats ? stats : nullptr;
+        return dtype == 1 ? launch_finish<bf16_t>(a, splits, fs, st) : launch_finish<float>(a, splits, fs, st);
     }
     return fused ? row_tiles : 0;
 }
@@ -1091,8 +1134,8 @@ void launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dy, const void*
             if (splits > 1) { a.ksplit = ks; a.partial = scratch; }
             launch_mode<CONV_DGRAD>(dtype, t, dim3((a.M + bm - 1) / bm, (a.Nn + bn - 1) / bn, splits), a, st);
             if (splits > 1) {
-                if (dtype == 1) launch_finish<bf16_t>(a, splits, st);
-                else launch_finish<float>(a, splits, st);
+                if (dtype == 1) launch_finish<bf16_t>(a, splits, nullptr, st);
+                else launch_finish<float>(a, splits, nullptr, st);
             }
         }
     }
@@ -1125,7 +1168,7 @@ static WgradPlan plan_wgrad(const ConvGeom& g) {
         default: p.bm = 64; p.bn = 64; break;
     }
     p.tiles = (int64_t)((M + p.bm - 1) / p.bm) * ((Nn + p.bn - 1) / p.bn);
-    static const int target = env_int("EDL_TUNE_WGRAD_BLOCKS", 512);
+    static const int target = env_int("EDL_TUNE_WGRAD_BLOCKS", 256);
     int64_t splits = (target + p.tiles - 1) / p.tiles;
     const int64_t max_splits = (Kred + 255) / 256;  // at least 4 reduction steps per split
     if (splits > max_splits) splits = max_splits;
