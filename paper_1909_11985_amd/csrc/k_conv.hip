@@ -856,13 +856,13 @@ enum TileCfg { T128x128, T128x64, T128x32, T64x64 };
 #define EDL_PF_BIG 1
 #endif
 #ifndef EDL_PF_SMALL
-#define EDL_PF_SMALL 1
+#define EDL_PF_SMALL 2
 #endif
 #ifndef EDL_BK_SMALL_MULT
 #define EDL_BK_SMALL_MULT 1
 #endif
 #ifndef EDL_BK_BIG_DIV
-#define EDL_BK_BIG_DIV 1
+#define EDL_BK_BIG_DIV 2
 #endif
 
 // reduction elements per tile: eight 16-byte vectors per row for either type
@@ -912,7 +912,10 @@ static void launch_cfg(TileCfg t, bool fast, dim3 tiles, const ConvArgs& a_in, h
     const bool mg = magic_fits(total, a.gx) && magic_fits(total, a.gy);
     a.magic_gx = mg ? magic_of(a.gx) : 0; a.magic_gy = mg ? magic_of(a.gy) : 0;
     const dim3 grid(tiles.x * tiles.y * tiles.z);
-    // register sets of loads in flight: the small tile has few registers per set and the least work per tile
+    // Measured on ResNet-50 at a shard of 32: the 64x64 tile (few registers per set, the least MFMA work per
+    // reduction step, often fewer workgroups than the chip has room for) gains a third on long reductions from
+    // two register sets of loads in flight; the 128-wide tiles gain nothing from a second set but do from
+    // half-length reduction steps (half the LDS per workgroup, so more workgroups per CU).
     constexpr int PF_BIG = EDL_PF_BIG, PF_SMALL = EDL_PF_SMALL;
     constexpr int BK_SMALL = MODE == CONV_WGRAD ? BK : EDL_BK_SMALL_MULT * BK;
     constexpr int BK_BIG = MODE == CONV_WGRAD ? BK : BK / EDL_BK_BIG_DIV;
