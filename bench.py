@@ -255,7 +255,7 @@ def main():
         "config": {"workload": args.workload, "global_batch": B, "p": p, "shard": B // p, "image": [H, W, C],
                    "classes": classes, "parameters": job_P, "dataset_samples": N},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "step": step_summary,
-        "update": update, "snapshot": snapshot, "kernels": kernels[:14],
+        "update": update, "snapshot": snapshot, "kernels": kernels[:24],
     }
     print(json.dumps(out))
 

@@ -7,6 +7,8 @@
 // one row block, each lane accumulating one 16-byte channel vector over every
 // TY-th row in float32; lanes are combined through LDS; a second tiny kernel
 // adds the row blocks in float64.
+#include <type_traits>
+
 #include "dev_common.h"
 #include "kernels.h"
 #include "profiler.h"
@@ -89,33 +91,44 @@ __global__ __launch_bounds__(256) void colreduce_kernel(const T* __restrict__ x,
     int64_t r1 = r0 + rows_per_block;
     if (r1 > M) r1 = M;
     if (active) {
-        for (int64_t r = r0 + ty; r < r1; r += TY) {
-            if (KIND == 0) {
-                float xv[VEC];
-                load_row<T, VEC>(x, r, C, c0, xv);
-                #pragma unroll
-                for (int e = 0; e < VEC; ++e) { a[e] += xv[e]; b[e] += xv[e] * xv[e]; }
-            } else {
-                float g[VEC];
-                load_row<T, VEC>(dy, r, C, c0, g);
-                if (relu) {
-                    float yv[VEC];
-                    load_row<T, VEC>(y, r, C, c0, yv);
-                    #pragma unroll
-                    for (int e = 0; e < VEC; ++e) g[e] = yv[e] > 0.f ? g[e] : 0.f;
-                }
-                if (KIND == 1) {
-                    float xv[VEC];
-                    load_row<T, VEC>(x, r, C, c0, xv);
-                    #pragma unroll
-                    for (int e = 0; e < VEC; ++e) { a[e] += g[e]; b[e] += g[e] * ((xv[e] - mu[e]) * rs[e]); }
+        // U rows per trip, every load of a trip issued before the first use: the loads are unconditional
+        // (without ReLU y is a valid tensor that is read and ignored), so none of them waits for another.
+        auto rows = [&](int64_t r, auto ucount) {
+            constexpr int U = decltype(ucount)::value;
+            float xv[U][VEC], yv[U][VEC], g[U][VEC];
+            #pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int64_t rr = r + (int64_t)u * TY;
+                if (KIND == 0) {
+                    load_row<T, VEC>(x, rr, C, c0, xv[u]);
                 } else {
-                    if (relu) store_row<T, VEC>(dy, r, C, c0, g);
-                    #pragma unroll
-                    for (int e = 0; e < VEC; ++e) a[e] += g[e];
+                    load_row<T, VEC>(dy, rr, C, c0, g[u]);
+                    load_row<T, VEC>(y, rr, C, c0, yv[u]);
+                    if (KIND == 1) load_row<T, VEC>(x, rr, C, c0, xv[u]);
                 }
             }
-        }
+            #pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (KIND == 0) {
+                    #pragma unroll
+                    for (int e = 0; e < VEC; ++e) { a[e] += xv[u][e]; b[e] += xv[u][e] * xv[u][e]; }
+                } else {
+                    #pragma unroll
+                    for (int e = 0; e < VEC; ++e) g[u][e] = (!relu || yv[u][e] > 0.f) ? g[u][e] : 0.f;
+                    if (KIND == 1) {
+                        #pragma unroll
+                        for (int e = 0; e < VEC; ++e) { a[e] += g[u][e]; b[e] += g[u][e] * ((xv[u][e] - mu[e]) * rs[e]); }
+                    } else {
+                        if (relu) store_row<T, VEC>(dy, r + (int64_t)u * TY, C, c0, g[u]);
+                        #pragma unroll
+                        for (int e = 0; e < VEC; ++e) a[e] += g[u][e];
+                    }
+                }
+            }
+        };
+        int64_t r = r0 + ty;
+        for (; r + TY < r1; r += 2 * (int64_t)TY) rows(r, std::integral_constant<int, 2>());
+        if (r < r1) rows(r, std::integral_constant<int, 1>());
     }
     const int lane = ty * TX + tx;
     #pragma unroll
@@ -296,8 +309,11 @@ static void bn_forward_t(const void* x, const void* res, void* y, const float* g
                            (const float*)nullptr, M, C, s.rows_per_block, 0, partial);
         stats_row_blocks = s.row_blocks;
     }
-    hipLaunchKernelGGL(bn_stats_finalize_kernel, dim3((C + 3) / 4), dim3(256), 0, st, partial, stats_row_blocks, M, C,
-                       save, running);
+    {
+        ProfScope ps("bn_stats_finalize", 0.0, 8.0 * (double)stats_row_blocks * C, st);
+        hipLaunchKernelGGL(bn_stats_finalize_kernel, dim3((C + 3) / 4), dim3(256), 0, st, partial, stats_row_blocks, M, C,
+                           save, running);
+    }
     ProfScope ps("bn_apply", 0.0, tb * (res ? 3.0 : 2.0), st);
     hipLaunchKernelGGL((bn_apply_kernel<T, VEC>), dim3(ew_grid(M * s.cvecs)), dim3(256), 0, st, (const T*)x,
                        (const T*)res, (T*)y, gamma, beta, save, M, C, s.cvecs, relu ? 1 : 0);
@@ -323,11 +339,14 @@ static void bn_backward_t(const void* x, const void* y, const void* dy, void* dx
     const double tb = (double)sizeof(T) * (double)M * C;
     {
     ProfScope ps("bn_bwd_reduce", 0.0, tb * (relu ? 3.0 : 2.0), st);
-    hipLaunchKernelGGL((colreduce_kernel<T, VEC, 1>), s.grid, s.block, 0, st, (const T*)x, (const T*)y, (T*)dy, save, M, C,
-                       s.rows_per_block, relu ? 1 : 0, partial);
+    hipLaunchKernelGGL((colreduce_kernel<T, VEC, 1>), s.grid, s.block, 0, st, (const T*)x, (const T*)(relu ? y : x), (T*)dy, save,
+                       M, C, s.rows_per_block, relu ? 1 : 0, partial);
     }
-    hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3((C + 3) / 4), dim3(256), 0, st, partial, s.row_blocks, M, C,
-                       dgamma, dbeta, coef);
+    {
+        ProfScope ps("bn_bwd_finalize", 0.0, 8.0 * (double)s.row_blocks * C, st);
+        hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3((C + 3) / 4), dim3(256), 0, st, partial, s.row_blocks, M, C,
+                           dgamma, dbeta, coef);
+    }
     ProfScope ps("bn_bwd_apply", 0.0, tb * ((relu ? 3.0 : 2.0) + 1.0 + (dres ? (dres_acc ? 2.0 : 1.0) : 0.0)), st);
     hipLaunchKernelGGL((bn_bwd_apply_kernel<T, VEC>), dim3(ew_grid(M * s.cvecs)), dim3(256), 0, st, (const T*)x,
                        (const T*)y, (const T*)dy, (T*)dx, (T*)dres, dres_acc ? 1 : 0, gamma, save, coef, M, C, s.cvecs,
@@ -351,11 +370,15 @@ static void bias_relu_backward_t(const void* y, void* dy, float* dbias, int64_t 
                                  hipStream_t st) {
     const RedShape s = red_shape(M, C, VEC);
     const double tb = (double)sizeof(T) * (double)M * C;
-    ProfScope ps("bias_relu_bwd", 0.0, tb * (relu ? 3.0 : 1.0), st);
-    hipLaunchKernelGGL((colreduce_kernel<T, VEC, 2>), s.grid, s.block, 0, st, (const T*)nullptr, (const T*)y, (T*)dy,
-                       (const float*)nullptr, M, C, s.rows_per_block, relu ? 1 : 0, partial);
-    if (dbias)
+    {
+        ProfScope ps("bias_relu_bwd", 0.0, tb * (relu ? 3.0 : 1.0), st);
+        hipLaunchKernelGGL((colreduce_kernel<T, VEC, 2>), s.grid, s.block, 0, st, (const T*)nullptr, (const T*)(relu ? y : dy), (T*)dy,
+                           (const float*)nullptr, M, C, s.rows_per_block, relu ? 1 : 0, partial);
+    }
+    if (dbias) {
+        ProfScope ps("bias_finalize", 0.0, 4.0 * (double)s.row_blocks * C, st);
         hipLaunchKernelGGL(bias_finalize_kernel, dim3((C + 3) / 4), dim3(256), 0, st, partial, s.row_blocks, C, dbias);
+    }
 }
 
 void launch_bias_relu_backward(int dtype, const void* y, void* dy, float* dbias, int64_t M, int C, bool relu,

@@ -154,6 +154,7 @@ __global__ __launch_bounds__(256) void fill_kernel(float* dst, float value, int6
 
 void launch_fill_f32(float* dst, float value, int64_t n, hipStream_t st) {
     if (n <= 0) return;
+    ProfScope ps("fill", 0.0, 4.0 * (double)n, st);
     hipLaunchKernelGGL(fill_kernel, dim3(grid_for(n, 256, 4096)), dim3(256), 0, st, dst, value, n);
 }
 
@@ -165,6 +166,7 @@ __global__ __launch_bounds__(256) void cast_bf16_kernel(const float* __restrict_
 
 void launch_cast_bf16(const float* src, uint16_t* dst, int64_t n, hipStream_t st) {
     if (n <= 0) return;
+    ProfScope ps("cast_bf16", 0.0, 6.0 * (double)n, st);
     hipLaunchKernelGGL(cast_bf16_kernel, dim3(grid_for(n, 256, 4096)), dim3(256), 0, st, src, dst, n);
 }
 
@@ -283,6 +285,7 @@ __global__ __launch_bounds__(256) void pad_weights_kernel(const float* __restric
 
 void launch_pad_weights(int dtype, const float* src, void* dst, int64_t rows, int C, int Cp, hipStream_t st) {
     const int grid = grid_for(rows * Cp, 256, 4096);
+    ProfScope ps("pad_weights", 0.0, 4.0 * (double)rows * C + (dtype == 1 ? 2.0 : 4.0) * (double)rows * Cp, st);
     if (dtype == 1) hipLaunchKernelGGL(pad_weights_kernel<bf16_t>, dim3(grid), dim3(256), 0, st, src, (bf16_t*)dst, rows, C, Cp);
     else hipLaunchKernelGGL(pad_weights_kernel<float>, dim3(grid), dim3(256), 0, st, src, (float*)dst, rows, C, Cp);
 }
@@ -297,6 +300,7 @@ __global__ __launch_bounds__(256) void unpad_rows_kernel(const float* __restrict
 }
 
 void launch_unpad_rows(const float* src, float* dst, int64_t rows, int C, int Cp, hipStream_t st) {
+    ProfScope ps("unpad_rows", 0.0, 8.0 * (double)rows * C, st);
     hipLaunchKernelGGL(unpad_rows_kernel, dim3(grid_for(rows * C, 256, 4096)), dim3(256), 0, st, src, dst, rows, C, Cp);
 }
 
