@@ -163,7 +163,15 @@ __device__ __forceinline__ void sum_partials(const float* __restrict__ partial, 
     if (c < C) {
         const float* ps = partial + (int64_t)c * kRedRowBlocks;
         const float* pq = partial + (int64_t)(C + c) * kRedRowBlocks;
-        for (int j = sub; j < row_blocks; j += 64) {
+        // four loads of each kind in flight per lane (the partial sums of a channel are contiguous)
+        int j = sub;
+        for (; j + 192 < row_blocks; j += 256) {
+            const float s0 = ps[j], s1 = ps[j + 64], s2 = ps[j + 128], s3 = ps[j + 192];
+            const float q0 = pq[j], q1 = pq[j + 64], q2 = pq[j + 128], q3 = pq[j + 192];
+            s += (double)s0; s += (double)s1; s += (double)s2; s += (double)s3;
+            q += (double)q0; q += (double)q1; q += (double)q2; q += (double)q3;
+        }
+        for (; j < row_blocks; j += 64) {
             s += (double)ps[j];
             q += (double)pq[j];
         }

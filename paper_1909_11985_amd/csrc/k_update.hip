@@ -180,8 +180,12 @@ template <typename T>
 __global__ __launch_bounds__(256) void weight_transpose_all_kernel(const float* __restrict__ w, unsigned char* __restrict__ arena,
                                                                    const TransposeEntry* __restrict__ tab, int entries) {
     __shared__ float tile[32][33];
-    int e = 0;
-    while (e + 1 < entries && (int)blockIdx.x >= tab[e + 1].tile_start) ++e;
+    int e = 0, hi = entries - 1;   // last entry whose first tile is not beyond this workgroup's
+    while (e < hi) {
+        const int mid = (e + hi + 1) >> 1;
+        if ((int)blockIdx.x >= tab[mid].tile_start) e = mid;
+        else hi = mid - 1;
+    }
     const TransposeEntry te = tab[e];
     int b = blockIdx.x - te.tile_start;
     const int tiles_c = (te.C + 31) / 32, tiles_k = (te.K + 31) / 32;
