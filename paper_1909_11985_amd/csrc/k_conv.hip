@@ -647,8 +647,25 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
     float csum[OVEC], csq[OVEC];
     #pragma unroll
     for (int e = 0; e < OVEC; ++e) csum[e] = csq[e] = 0.f;
+    constexpr int CV = BN / OVEC;                              // vectors per stored row
+    constexpr int NV = (STAGE_ROWS * CV + 255) / 256;          // vectors per lane and pass
+    const bool add_old = MODE == CONV_DGRAD && a.accumulate && !to_partial;
     #pragma unroll
     for (int pass = 0; pass < WM; ++pass) {
+        // dgrad adding to an existing gradient: its vectors are fetched now, all at once and without a
+        // branch (a vector outside the matrix reads the start of the tensor and is ignored), and are
+        // there when the staged sums are
+        uint4 oldv[NV];
+        if (add_old) {
+            #pragma unroll
+            for (int k = 0; k < NV; ++k) {
+                const int v = tid + k * 256, rl = v / CV, cv = v - rl * CV;
+                const int row = m0 + pass * STAGE_ROWS + rl, col = n0 + cv * OVEC;
+                const bool inside = v < STAGE_ROWS * CV && row < a.M && col < a.Nn;
+                const unsigned char* src = inside ? outp + (out_row<MODE, true>(a, row) * a.Nn + col) * OSZ : outp;
+                oldv[k] = *reinterpret_cast<const uint4*>(src);
+            }
+        }
         if (wm == pass) {
             #pragma unroll
             for (int i = 0; i < TM; ++i) {
@@ -671,9 +688,10 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
             }
         }
         __syncthreads();
-        constexpr int CV = BN / OVEC;
-        #pragma unroll 2
-        for (int v = tid; v < STAGE_ROWS * CV; v += 256) {
+        #pragma unroll
+        for (int k = 0; k < NV; ++k) {
+            const int v = tid + k * 256;
+            if (v >= STAGE_ROWS * CV) break;
             const int rl = v / CV, cv = v - rl * CV;
             const int row = m0 + pass * STAGE_ROWS + rl, col = n0 + cv * OVEC;
             if (row < a.M && col < a.Nn) {
@@ -688,9 +706,9 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
                 unsigned char* dst = outp + (out_row<MODE, true>(a, row) * a.Nn + col) * OSZ;
                 if (OUT_F32) {
                     float4 o = *reinterpret_cast<const float4*>(sp);
-                    if (MODE == CONV_DGRAD && a.accumulate) {
-                        const float4 old = *reinterpret_cast<const float4*>(dst);
-                        o.x += old.x; o.y += old.y; o.z += old.z; o.w += old.w;
+                    if (add_old) {
+                        o.x += __uint_as_float(oldv[k].x); o.y += __uint_as_float(oldv[k].y);
+                        o.z += __uint_as_float(oldv[k].z); o.w += __uint_as_float(oldv[k].w);
                     }
                     *reinterpret_cast<float4*>(dst) = o;
                     if (with_stats) {
@@ -699,8 +717,8 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
                     }
                 } else {
                     float4 o0 = *reinterpret_cast<const float4*>(sp), o1 = *reinterpret_cast<const float4*>(sp + 4);
-                    if (MODE == CONV_DGRAD && a.accumulate) {
-                        const uint4 old = *reinterpret_cast<const uint4*>(dst);
+                    if (add_old) {
+                        const uint4 old = oldv[k];
                         o0.x += __uint_as_float(old.x << 16); o0.y += __uint_as_float(old.x & 0xffff0000u);
                         o0.z += __uint_as_float(old.y << 16); o0.w += __uint_as_float(old.y & 0xffff0000u);
                         o1.x += __uint_as_float(old.z << 16); o1.y += __uint_as_float(old.z & 0xffff0000u);
@@ -726,7 +744,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
     }
     if (with_stats) {
         // lanes with the same column vector differ in tid / CV: sum over them in a fixed order
-        constexpr int CV = BN / OVEC, GROUPS = 256 / CV;
+        constexpr int GROUPS = 256 / CV;
         static_assert(2 * GROUPS * BN * 4 <= SMEM_BYTES, "column sums fit the tile memory");
         float* const red = stage;
         const int grp = tid / CV, c0 = (tid % CV) * OVEC;

@@ -226,42 +226,38 @@ __global__ __launch_bounds__(256) void bias_finalize_kernel(const float* __restr
 }
 
 // y = relu(gamma * (x - mean) * rstd + beta + res)
-template <typename T, int VEC>
-__global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ x, const T* __restrict__ res, T* __restrict__ y,
-                                                       const float* __restrict__ gamma, const float* __restrict__ beta,
-                                                       const float* __restrict__ mean_rstd, int64_t M, int C, int cvecs,
-                                                       int relu) {
+// No load sits behind a run-time branch, so that all of a lane's loads are in flight together.
+template <typename T, int VEC, bool RES>
+__global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ x, const T* __restrict__ res,
+                                                       T* __restrict__ y, const float* __restrict__ gamma,
+                                                       const float* __restrict__ beta, const float* __restrict__ mean_rstd,
+                                                       int64_t M, int C, int cvecs, int relu) {
     const int64_t total = M * cvecs;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
         const int64_t r = i / cvecs;
         const int c0 = (int)(i - r * cvecs) * VEC;
-        float xv[VEC], out[VEC];
+        float xv[VEC], rv[VEC], out[VEC];
         load_row<T, VEC>(x, r, C, c0, xv);
+        if (RES) load_row<T, VEC>(res, r, C, c0, rv);
         #pragma unroll
         for (int e = 0; e < VEC; ++e) {
             const float sc = gamma[c0 + e] * mean_rstd[C + c0 + e];
             out[e] = (xv[e] - mean_rstd[c0 + e]) * sc + beta[c0 + e];
-        }
-        if (res) {
-            float rv[VEC];
-            load_row<T, VEC>(res, r, C, c0, rv);
-            #pragma unroll
-            for (int e = 0; e < VEC; ++e) out[e] += rv[e];
-        }
-        if (relu) {
-            #pragma unroll
-            for (int e = 0; e < VEC; ++e) out[e] = out[e] > 0.f ? out[e] : 0.f;
+            if (RES) out[e] += rv[e];
+            if (relu) out[e] = out[e] > 0.f ? out[e] : 0.f;
         }
         store_row<T, VEC>(y, r, C, c0, out);
     }
 }
 
 // dx = gamma*rstd*(dy' - coef0 - xhat*coef1) ; dres (+)= dy'
+// Unconditional loads as above: y is x when there is no ReLU, dres_old is dy when dres is not
+// accumulated into (both read and ignored).
 template <typename T, int VEC>
 __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const T* __restrict__ x, const T* __restrict__ y,
                                                            const T* __restrict__ dy, T* __restrict__ dx, T* dres,
-                                                           int dres_acc, const float* __restrict__ gamma,
+                                                           const T* dres_old, int dres_acc, const float* __restrict__ gamma,
                                                            const float* __restrict__ mean_rstd,
                                                            const float* __restrict__ coef, int64_t M, int C, int cvecs,
                                                            int relu) {
@@ -270,17 +266,14 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const T* __restrict__
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
         const int64_t r = i / cvecs;
         const int c0 = (int)(i - r * cvecs) * VEC;
-        float xv[VEC], g[VEC], out[VEC];
+        float xv[VEC], yv[VEC], g[VEC], old[VEC], out[VEC];
         load_row<T, VEC>(x, r, C, c0, xv);
         load_row<T, VEC>(dy, r, C, c0, g);
-        if (relu) {
-            float yv[VEC];
-            load_row<T, VEC>(y, r, C, c0, yv);
-            #pragma unroll
-            for (int e = 0; e < VEC; ++e) g[e] = yv[e] > 0.f ? g[e] : 0.f;
-        }
+        load_row<T, VEC>(y, r, C, c0, yv);
+        load_row<T, VEC>(dres_old, r, C, c0, old);
         #pragma unroll
         for (int e = 0; e < VEC; ++e) {
+            g[e] = (!relu || yv[e] > 0.f) ? g[e] : 0.f;
             const float rs = mean_rstd[C + c0 + e];
             const float xh = (xv[e] - mean_rstd[c0 + e]) * rs;
             out[e] = gamma[c0 + e] * rs * (g[e] - coef[c0 + e] - xh * coef[C + c0 + e]);
@@ -288,8 +281,6 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const T* __restrict__
         store_row<T, VEC>(dx, r, C, c0, out);
         if (dres) {
             if (dres_acc) {
-                float old[VEC];
-                load_row<T, VEC>(dres, r, C, c0, old);
                 #pragma unroll
                 for (int e = 0; e < VEC; ++e) g[e] += old[e];
             }
@@ -323,8 +314,12 @@ static void bn_forward_t(const void* x, const void* res, void* y, const float* g
                            save, running);
     }
     ProfScope ps("bn_apply", 0.0, tb * (res ? 3.0 : 2.0), st);
-    hipLaunchKernelGGL((bn_apply_kernel<T, VEC>), dim3(ew_grid(M * s.cvecs)), dim3(256), 0, st, (const T*)x,
-                       (const T*)res, (T*)y, gamma, beta, save, M, C, s.cvecs, relu ? 1 : 0);
+    if (res)
+        hipLaunchKernelGGL((bn_apply_kernel<T, VEC, true>), dim3(ew_grid(M * s.cvecs)), dim3(256), 0, st, (const T*)x,
+                           (const T*)res, (T*)y, gamma, beta, save, M, C, s.cvecs, relu ? 1 : 0);
+    else
+        hipLaunchKernelGGL((bn_apply_kernel<T, VEC, false>), dim3(ew_grid(M * s.cvecs)), dim3(256), 0, st, (const T*)x,
+                           (const T*)nullptr, (T*)y, gamma, beta, save, M, C, s.cvecs, relu ? 1 : 0);
 }
 
 void launch_bn_forward(int dtype, const void* x, const void* res, void* y, const float* gamma, const float* beta,
@@ -357,8 +352,8 @@ static void bn_backward_t(const void* x, const void* y, const void* dy, void* dx
     }
     ProfScope ps("bn_bwd_apply", 0.0, tb * ((relu ? 3.0 : 2.0) + 1.0 + (dres ? (dres_acc ? 2.0 : 1.0) : 0.0)), st);
     hipLaunchKernelGGL((bn_bwd_apply_kernel<T, VEC>), dim3(ew_grid(M * s.cvecs)), dim3(256), 0, st, (const T*)x,
-                       (const T*)y, (const T*)dy, (T*)dx, (T*)dres, dres_acc ? 1 : 0, gamma, save, coef, M, C, s.cvecs,
-                       relu ? 1 : 0);
+                       (const T*)(relu ? y : x), (const T*)dy, (T*)dx, (T*)dres, (const T*)((dres && dres_acc) ? dres : dy),
+                       (dres && dres_acc) ? 1 : 0, gamma, save, coef, M, C, s.cvecs, relu ? 1 : 0);
 }
 
 void launch_bn_backward(int dtype, const void* x, const void* y, const void* dy, void* dx, void* dres,
