@@ -140,6 +140,32 @@ template <> struct Frag<float> {
     }
 };
 
+// bf16 wgrad tiles in LDS: row = pixel of the reduction step, WIDTH channels per row, no padding; the
+// 16-channel (32-byte) chunks of a row are permuted by the row's low bits, so that the four pixel rows a
+// 16-lane group reads at once fall into different banks.
+template <int WIDTH>
+__device__ __forceinline__ int wg_lds_index(int pixel, int ch) {
+    constexpr int MASK = WIDTH / 16 >= 4 ? 3 : WIDTH / 16 - 1;
+    return pixel * WIDTH + ((((ch >> 4) ^ (pixel & MASK)) << 4) | (ch & 15));
+}
+
+// MFMA operand of a 32-channel tile for reduction pixels [p16 + 8*(lane/32), +8) from such an LDS tile.
+// ds_read_tr16_b64 hands lane l of a 16-lane group element (l % 4) of the four 16-bit values read by
+// lanes l/4, l/4 + 4, l/4 + 8, l/4 + 12 of the group (lane layout measured on gfx950).  With lane s
+// reading pixel s/4, channels 4*(s%4)..+3 of a 16-channel chunk, lane l therefore receives channel l of
+// the chunk for four consecutive pixels; two reads give the operand's eight.
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+template <int WIDTH>
+__device__ __forceinline__ uint4 tr_frag(const bf16_t* tile, int ch32, int p16, int lane) {
+    const int ch = ch32 + ((lane >> 4) & 1) * 16 + 4 * (lane & 3);
+    const int p0 = p16 + (lane >> 5) * 8 + ((lane & 15) >> 2);
+    typedef shortx4 __attribute__((address_space(3))) * lds_ptr;
+    const shortx4 r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(tile + wg_lds_index<WIDTH>(p0, ch)));
+    const shortx4 r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(tile + wg_lds_index<WIDTH>(p0 + 4, ch)));
+    const uint2 a = __builtin_bit_cast(uint2, r0), b = __builtin_bit_cast(uint2, r1);
+    return make_uint4(a.x, a.y, b.x, b.y);
+}
+
 // context of one tile row for the pixel-indexed operand of forward / dgrad
 struct RowCtx {
     int64_t base;
@@ -270,8 +296,11 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
     constexpr int TOT_B = WG ? KD * RVB : BN * KV;
     constexpr int ITER_A = (TOT_A + 255) / 256, ITER_B = (TOT_B + 255) / 256;
     constexpr int NRA = WG ? ITER_A * KPD : ITER_A, NRB = WG ? ITER_B * KPD : ITER_B;
-    constexpr int A_STAGE = WG ? KD * LDPA * 4 : BM * LDK * (int)sizeof(T);   // bytes per LDS stage
-    constexpr int B_STAGE = WG ? KD * LDPB * 4 : BN * LDK * (int)sizeof(T);
+    // wgrad in bf16 keeps its tiles as they are in memory, [pixel][channel], and transposes on the way out of
+    // LDS (ds_read_tr16_b64, see tr_frag); float32 wgrad keeps words [pixel][channel] read one by one
+    constexpr bool WGT = WG && sizeof(T) == 2;
+    constexpr int A_STAGE = WGT ? BK * BM * 2 : WG ? KD * LDPA * 4 : BM * LDK * (int)sizeof(T);   // bytes per LDS stage
+    constexpr int B_STAGE = WGT ? BK * BN * 2 : WG ? KD * LDPB * 4 : BN * LDK * (int)sizeof(T);
     // epilogue staging: the rows of one wave row, as float32
     constexpr int STAGE_ROWS = TM * 32, STAGE_LD = BN + 4;
     constexpr int TILE_BYTES = 2 * (A_STAGE + B_STAGE);
@@ -488,6 +517,25 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
                 if (TOT_B % 256 != 0 && v >= TOT_B) continue;
                 store_vec(&Bd[(v / KV) * LDK + (v % KV) * VEC], rb[set][it]);
             }
+        } else if (WGT) {
+            bf16_t* const Ad = reinterpret_cast<bf16_t*>(As + buf * A_STAGE);
+            bf16_t* const Bd = reinterpret_cast<bf16_t*>(Bs + buf * B_STAGE);
+            #pragma unroll
+            for (int it = 0; it < ITER_A; ++it) {
+                const int v = tid + it * 256;
+                if (TOT_A % 256 != 0 && v >= TOT_A) continue;
+                #pragma unroll
+                for (int pp = 0; pp < KPD; ++pp)
+                    *reinterpret_cast<uint4*>(&Ad[wg_lds_index<BM>((v / RVA) * KPD + pp, (v % RVA) * VEC)]) = ra[set][it * KPD + pp].u;
+            }
+            #pragma unroll
+            for (int it = 0; it < ITER_B; ++it) {
+                const int v = tid + it * 256;
+                if (TOT_B % 256 != 0 && v >= TOT_B) continue;
+                #pragma unroll
+                for (int pp = 0; pp < KPD; ++pp)
+                    *reinterpret_cast<uint4*>(&Bd[wg_lds_index<BN>((v / RVB) * KPD + pp, (v % RVB) * VEC)]) = rb[set][it * KPD + pp].u;
+            }
         } else {
             uint32_t* const Ad = reinterpret_cast<uint32_t*>(As + buf * A_STAGE);
             uint32_t* const Bd = reinterpret_cast<uint32_t*>(Bs + buf * B_STAGE);
@@ -574,6 +622,13 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
                     #pragma unroll
                     for (int j = 0; j < TN; ++j)
                         fb[j] = *reinterpret_cast<const uint4*>(&Bb[((wn * TN + j) * 32 + (lane & 31)) * LDK + g * KG + (lane >> 5) * VEC]);
+                } else if (WGT) {
+                    const bf16_t* const Ab = reinterpret_cast<const bf16_t*>(As + buf * A_STAGE);
+                    const bf16_t* const Bb = reinterpret_cast<const bf16_t*>(Bs + buf * B_STAGE);
+                    #pragma unroll
+                    for (int i = 0; i < TM; ++i) fa[i] = tr_frag<BM>(Ab, (wm * TM + i) * 32, g * 16, lane);
+                    #pragma unroll
+                    for (int j = 0; j < TN; ++j) fb[j] = tr_frag<BN>(Bb, (wn * TN + j) * 32, g * 16, lane);
                 } else {
                     const uint32_t* const Ab = reinterpret_cast<const uint32_t*>(As + buf * A_STAGE) + (g * 8 + (lane >> 5) * 4) * LDPA + (lane & 31);
                     const uint32_t* const Bb = reinterpret_cast<const uint32_t*>(Bs + buf * B_STAGE) + (g * 8 + (lane >> 5) * 4) * LDPB + (lane & 31);
