@@ -41,6 +41,12 @@
 #include "kernels.h"
 #include "profiler.h"
 
+// 1: LDS fragment reads run one fragment group ahead of the MFMAs (tiles of more than one MFMA per group;
+// measured -6% on the 128x128 weight gradient, nothing on the others)
+#ifndef EDL_FRAG_AHEAD
+#define EDL_FRAG_AHEAD 1
+#endif
+
 namespace edl {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
@@ -299,6 +305,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
     // wgrad in bf16 keeps its tiles as they are in memory, [pixel][channel], and transposes on the way out of
     // LDS (ds_read_tr16_b64, see tr_frag); float32 wgrad keeps words [pixel][channel] read one by one
     constexpr bool WGT = WG && sizeof(T) == 2;
+    constexpr bool FRAG_AHEAD = EDL_FRAG_AHEAD != 0 && TM * TN > 1;
     constexpr int A_STAGE = WGT ? BK * BM * 2 : WG ? KD * LDPA * 4 : BM * LDK * (int)sizeof(T);   // bytes per LDS stage
     constexpr int B_STAGE = WGT ? BK * BN * 2 : WG ? KD * LDPB * 4 : BN * LDK * (int)sizeof(T);
     // epilogue staging: the rows of one wave row, as float32
@@ -609,9 +616,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
             const int buf = PF == 1 ? (k & 1) : (u & 1);
             load_tiles(u);
             constexpr int NG = WG ? 4 : BK / (2 * VEC);   // fragment groups per tile
-            #pragma unroll
-            for (int g = 0; g < NG; ++g) {
-                uint4 fa[TM], fb[TN];
+            auto read_frags = [&](int g, uint4 (&fa)[TM], uint4 (&fb)[TN]) {
                 if (!WG) {
                     constexpr int KG = 2 * VEC;  // reduction elements one fragment pair covers
                     const T* const Ab = reinterpret_cast<const T*>(As + buf * A_STAGE);
@@ -643,10 +648,21 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
                         fb[j] = make_uint4(q[0], q[LDPB], q[2 * LDPB], q[3 * LDPB]);
                     }
                 }
+            };
+            // The fragments of group g+1 are read from LDS before the MFMAs of group g are issued
+            // (the fences keep the compiler from sinking the reads back to their first use), so the
+            // LDS latency of one group hides behind the matrix work of the one before.
+            uint4 fa[2][TM], fb[2][TN];
+            read_frags(0, fa[0], fb[0]);
+            #pragma unroll
+            for (int g = 0; g < NG; ++g) {
+                if (g + 1 < NG) read_frags(g + 1, fa[(g + 1) & 1], fb[(g + 1) & 1]);
+                if (FRAG_AHEAD) __builtin_amdgcn_sched_barrier(0);
                 #pragma unroll
                 for (int i = 0; i < TM; ++i)
                     #pragma unroll
-                    for (int j = 0; j < TN; ++j) Frag<T>::mma(fa[i], fb[j], acc[i][j]);
+                    for (int j = 0; j < TN; ++j) Frag<T>::mma(fa[g & 1][i], fb[g & 1][j], acc[i][j]);
+                if (FRAG_AHEAD) __builtin_amdgcn_sched_barrier(0);
             }
             store_tiles((u + 1) % PF, buf ^ 1);
             __syncthreads();
