@@ -185,7 +185,7 @@ def main():
         one_stream_ms_per_step=round(one_stream_ms, 4))
 
     # ---- the HBM-bound half of the metric on the VGG-16-sized state ----
-    update, snapshot = None, None
+    update, snapshot, attainable = None, None, None
     job_P = sizes.P
     job.shutdown()
     del job
@@ -231,6 +231,19 @@ def main():
         snapshot = dict(state_bytes=nbytes, us=round(1e3 * r["ms"] / r["launches"], 1), gbs=round(gbs, 1),
                         frac_of_hbm_peak=round(gbs / HBM_PEAK_GBS, 4))
         del src, dst, w, v, w16
+        # attainable matrix rate: register-resident MFMA loop in the workload's matrix instruction
+        sink = torch.zeros(1, device="cuda")
+        E.edl_mfma_rate(dtype, 256 * 8, 2000, sink)
+        torch.cuda.synchronize()
+        E.edl_profile(True)
+        for _ in range(3):
+            E.edl_mfma_rate(dtype, 256 * 8, 20000, sink)
+        torch.cuda.synchronize()
+        rr = E.edl_profile_report()
+        E.edl_profile(False)
+        r = [q for q in rr if q["name"].startswith("mfma_rate")][0]
+        attainable = dict(mfma_tflops=round(r["flops"] / (r["ms"] - overhead_ms * r["launches"]) / 1e9, 1),
+                          mfma_peak_tflops=MFMA_PEAK_TFLOPS[dtype], copy_gbs=snapshot["gbs"], hbm_peak_gbs=HBM_PEAK_GBS)
 
     # ---- the oracle on the host cores, on a bounded sample of the same workload ----
     cpu_baseline = None
@@ -255,7 +268,7 @@ def main():
         "config": {"workload": args.workload, "global_batch": B, "p": p, "shard": B // p, "image": [H, W, C],
                    "classes": classes, "parameters": job_P, "dataset_samples": N},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "step": step_summary,
-        "update": update, "snapshot": snapshot, "kernels": kernels[:24],
+        "update": update, "snapshot": snapshot, "attainable": attainable, "kernels": kernels[:24],
     }
     print(json.dumps(out))
 

@@ -223,6 +223,14 @@ int32_t edl_profile_report(char* buf, size_t cap, size_t* out_needed);
 /* Stand-alone vectorised device-to-device copy used by edl_snapshot. */
 int32_t edl_copy(void* dev_dst, const void* dev_src, size_t bytes, void* hip_stream);
 
+/* Measurement aid: a register-resident MFMA loop (no memory traffic), `blocks`
+ * workgroups of four waves, `iters` rounds of four independent 32x32 MFMAs per
+ * wave, in dtype's matrix instruction.  dev_sink: one float of device memory
+ * (never written in practice).  out_flops receives the flops the launch issues;
+ * time it with edl_profile ("mfma_rate_bf16" / "mfma_rate_f32").  What the
+ * convolutions' MFMA fractions can be held against besides the data-sheet peak. */
+int32_t edl_mfma_rate(int32_t dtype, int32_t blocks, int32_t iters, float* dev_sink, void* hip_stream, double* out_flops);
+
 #ifdef __cplusplus
 }
 #endif

@@ -91,6 +91,7 @@ _SIGS = {
     "edl_average_update": [C.c_int32, C.POINTER(C.c_void_p), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
                            C.c_float, C.c_float, C.c_float, C.c_void_p],
     "edl_copy": [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p],
+    "edl_mfma_rate": [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.POINTER(C.c_double)],
     "edl_profile": [C.c_int32],
     "edl_profile_report": [C.c_char_p, C.c_size_t, C.POINTER(C.c_size_t)],
 }
@@ -160,6 +161,13 @@ def edl_average_update(grads, w, v, w16, lr, momentum, wd, stream=0):
     ptrs = (C.c_void_p * p)(*[g.data_ptr() for g in grads])
     _check(lib.edl_average_update(p, ptrs, w.data_ptr(), v.data_ptr(), w16.data_ptr() if w16 is not None else None,
                                   w.numel(), lr, momentum, wd, stream))
+
+
+def edl_mfma_rate(dtype, blocks, iters, sink, stream=0):
+    """Launches the register-resident MFMA loop; returns the flops it issues (time it with edl_profile)."""
+    f = C.c_double(0)
+    _check(lib.edl_mfma_rate(DTYPES[dtype], blocks, iters, sink.data_ptr(), stream, C.byref(f)))
+    return f.value
 
 
 def edl_copy(dst, src, nbytes, stream=0):

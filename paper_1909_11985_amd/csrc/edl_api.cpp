@@ -905,6 +905,17 @@ int32_t edl_average_update(int32_t p, const float* const* dev_grads, float* dev_
     return EDL_OK;
 }
 
+int32_t edl_mfma_rate(int32_t dtype, int32_t blocks, int32_t iters, float* dev_sink, void* hip_stream, double* out_flops) {
+    if ((dtype != EDL_DTYPE_F32 && dtype != EDL_DTYPE_BF16) || blocks <= 0 || blocks > (1 << 20) || iters <= 0 || !dev_sink) {
+        set_error("bad argument");
+        return EDL_EINVAL;
+    }
+    const double flops = launch_mfma_rate(dtype, blocks, iters, dev_sink, (hipStream_t)hip_stream);
+    if (out_flops) *out_flops = flops;
+    HIP_TRY(hipGetLastError());
+    return EDL_OK;
+}
+
 int32_t edl_copy(void* dev_dst, const void* dev_src, size_t bytes, void* hip_stream) {
     if (!dev_dst || !dev_src) { set_error("null argument"); return EDL_EINVAL; }
     launch_copy(dev_dst, dev_src, bytes, (hipStream_t)hip_stream);

@@ -326,4 +326,48 @@ void launch_softmax_ce(int dtype, const float* logits, const int32_t* labels, vo
     hipLaunchKernelGGL(loss_mean_kernel, dim3(1), dim3(64), 0, st, row_loss, n, loss_out);
 }
 
+// ---------------------------------------------------------------------------
+// Attainable matrix rate: every wave keeps four independent 32x32 accumulators
+// and issues MFMAs on register operands only (no memory in the loop).  What the
+// convolutions' MFMA fractions can be held against besides the data sheet.
+// ---------------------------------------------------------------------------
+typedef float mfma_acc_t __attribute__((ext_vector_type(16)));
+typedef __bf16 mfma_bf16x8_t __attribute__((ext_vector_type(8)));
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void mfma_rate_kernel(int iters, float* __restrict__ sink) {
+    mfma_acc_t acc[4];
+    #pragma unroll
+    for (int q = 0; q < 4; ++q)
+        #pragma unroll
+        for (int e = 0; e < 16; ++e) acc[q][e] = 0.f;
+    const float seed = 1.0f + (float)(threadIdx.x & 7) * 0.125f;
+    mfma_bf16x8_t a, b;
+    #pragma unroll
+    for (int e = 0; e < 8; ++e) { a[e] = (__bf16)seed; b[e] = (__bf16)(1.0f / seed); }
+    for (int i = 0; i < iters; ++i) {
+        #pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (BF16) acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[q], 0, 0, 0);
+            else acc[q] = __builtin_amdgcn_mfma_f32_32x32x2f32(seed, 1.0f / seed, acc[q], 0, 0, 0);
+        }
+    }
+    float t = 0.f;
+    #pragma unroll
+    for (int q = 0; q < 4; ++q)
+        #pragma unroll
+        for (int e = 0; e < 16; ++e) t += acc[q][e];
+    if (t == 12345.678f) sink[0] = t;   // never true; keeps the accumulators alive
+}
+
+// flops issued: blocks * 4 waves * iters * 4 MFMAs * 2*32*32*k
+double launch_mfma_rate(int dtype, int blocks, int iters, float* sink, hipStream_t st) {
+    const double per_mfma = dtype == 1 ? 2.0 * 32 * 32 * 16 : 2.0 * 32 * 32 * 2;
+    const double flops = (double)blocks * 4.0 * (double)iters * 4.0 * per_mfma;
+    ProfScope ps(dtype == 1 ? "mfma_rate_bf16" : "mfma_rate_f32", flops, 0.0, st);
+    if (dtype == 1) hipLaunchKernelGGL(mfma_rate_kernel<true>, dim3(blocks), dim3(256), 0, st, iters, sink);
+    else hipLaunchKernelGGL(mfma_rate_kernel<false>, dim3(blocks), dim3(256), 0, st, iters, sink);
+    return flops;
+}
+
 }  // namespace edl

@@ -94,4 +94,7 @@ void launch_gavgpool_backward(int dtype, const void* dy, void* dx, bool accumula
 void launch_softmax_ce(int dtype, const float* logits, const int32_t* labels, void* dlogits, float* row_loss,
                        float* loss_out, int n, int C, hipStream_t st);
 
+// register-resident MFMA loop (attainable matrix rate); returns the flops the launch issues
+double launch_mfma_rate(int dtype, int blocks, int iters, float* sink, hipStream_t st);
+
 }  // namespace edl
