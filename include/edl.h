@@ -116,6 +116,45 @@ int32_t edl_init_params_host(const edl_config* cfg, uint64_t seed, float* out_pa
 int32_t edl_shard_host(uint64_t seed, int64_t N, int64_t B, int32_t p, int64_t epoch,
                        int64_t step_in_epoch, int64_t* out_idx, int64_t* out_off);
 
+/* Dynamic data pipeline (section 4.3): the leader's bookkeeping when the data
+ * set is cut into d partitions (meta-data only) that workers are given on
+ * demand.  Host only.  Partition j covers samples [j*s, min((j+1)*s, N)),
+ * s = ceil(N/d) (EDL_EINVAL if that leaves a partition empty or d > N); each
+ * epoch draws a permutation of the partitions from (seed, epoch) with the
+ * job's generator, so d = N with a fixed worker set gives edl_shard_host's
+ * assignment.
+ *
+ * edl_pipeline_next_batch assembles the next global mini-batch of B samples
+ * for the p workers named by worker_ids (host int64[p], distinct, in rank
+ * order; the caller chooses the names).  Workers of the previous call that
+ * are missing have left gracefully: the unread rest of their current
+ * partition goes back to the leader (in their old rank order) and is handed
+ * out again before any unassigned partition, first in first out.  New names
+ * are joiners and hold nothing.  Each worker is given B/p samples, read front
+ * to back from its current partition and then from the next piece the leader
+ * hands out; what a worker cannot be given because the epoch is running out
+ * is passed on to the workers after it (wrapping round once), so the batch
+ * has B samples but such a tail batch may have unequal shards.  An epoch ends
+ * when all N samples have been handed out; the next call starts the next one.
+ * out_idx: host int64[B]; out_off: host int64[p+1]; worker k reads
+ * out_idx[out_off[k] .. out_off[k+1]).  EDL_EINDIVISIBLE if B % p or N % B.
+ *
+ * edl_pipeline_save writes the leader's state (progress, handed-back pieces,
+ * every worker's partition and offset; the permutation follows from seed and
+ * epoch) as int64 words: EDL_ENOMEM if cap_words is too small, *out_words then
+ * holds the count to bring.  edl_pipeline_load creates a pipeline from such an
+ * image (EDL_EINVAL / EDL_ERANGE if it is not one).  The caller owns the
+ * pipeline until edl_pipeline_destroy.  Calls on one pipeline are not
+ * thread-safe. */
+typedef struct edl_pipeline edl_pipeline;
+int32_t edl_pipeline_create(uint64_t seed, int64_t N, int64_t d, edl_pipeline** out);
+int32_t edl_pipeline_next_batch(edl_pipeline* pl, int64_t B, int32_t p, const int64_t* worker_ids, int64_t* out_idx,
+                                int64_t* out_off);
+int32_t edl_pipeline_progress(const edl_pipeline* pl, int64_t* out_epoch, int64_t* out_consumed);
+int32_t edl_pipeline_save(const edl_pipeline* pl, int64_t* buf, size_t cap_words, size_t* out_words);
+int32_t edl_pipeline_load(const int64_t* buf, size_t words, edl_pipeline** out);
+int32_t edl_pipeline_destroy(edl_pipeline* pl);
+
 /* Create a job.  dev_arena: device memory of at least edl_query().arena_bytes,
  * 256-byte aligned, owned by the caller and alive until edl_shutdown.
  * Initialises parameters from the seed (He), zeroes momentum, sets running

@@ -91,6 +91,12 @@ _SIGS = {
     "edl_average_update": [C.c_int32, C.POINTER(C.c_void_p), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
                            C.c_float, C.c_float, C.c_float, C.c_void_p],
     "edl_copy": [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p],
+    "edl_pipeline_create": [C.c_uint64, C.c_int64, C.c_int64, C.POINTER(C.c_void_p)],
+    "edl_pipeline_next_batch": [C.c_void_p, C.c_int64, C.c_int32, _i64p, _i64p, _i64p],
+    "edl_pipeline_progress": [C.c_void_p, _i64p, _i64p],
+    "edl_pipeline_save": [C.c_void_p, _i64p, C.c_size_t, C.POINTER(C.c_size_t)],
+    "edl_pipeline_load": [_i64p, C.c_size_t, C.POINTER(C.c_void_p)],
+    "edl_pipeline_destroy": [C.c_void_p],
     "edl_mfma_rate": [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.POINTER(C.c_double)],
     "edl_profile": [C.c_int32],
     "edl_profile_report": [C.c_char_p, C.c_size_t, C.POINTER(C.c_size_t)],
@@ -186,6 +192,56 @@ def edl_profile_report():
     need = C.c_size_t()
     _check(lib.edl_profile_report(buf, len(buf), C.byref(need)))
     return json.loads(buf.value.decode())
+
+
+class Pipeline:
+    """The dynamic data pipeline of include/edl.h (edl_pipeline_*): host bookkeeping only."""
+
+    def __init__(self, seed=0, N=0, d=0, _handle=None):
+        if _handle is not None:
+            self._h = _handle
+            return
+        h = C.c_void_p()
+        _check(lib.edl_pipeline_create(seed, N, d, C.byref(h)))
+        self._h = h
+
+    def next_batch(self, B, worker_ids):
+        ids = np.ascontiguousarray(worker_ids, dtype=np.int64)
+        idx = np.empty(B, dtype=np.int64)
+        off = np.empty(len(ids) + 1, dtype=np.int64)
+        _check(lib.edl_pipeline_next_batch(self._h, B, len(ids), ids.ctypes.data_as(_i64p), idx.ctypes.data_as(_i64p),
+                                           off.ctypes.data_as(_i64p)))
+        return idx, off
+
+    def progress(self):
+        e, c = C.c_int64(), C.c_int64()
+        _check(lib.edl_pipeline_progress(self._h, C.byref(e), C.byref(c)))
+        return e.value, c.value
+
+    def save(self):
+        n = C.c_size_t(0)
+        lib.edl_pipeline_save(self._h, None, 0, C.byref(n))      # asks for the size
+        buf = np.empty(n.value, dtype=np.int64)
+        _check(lib.edl_pipeline_save(self._h, buf.ctypes.data_as(_i64p), buf.size, C.byref(n)))
+        return buf
+
+    @classmethod
+    def load(cls, image):
+        image = np.ascontiguousarray(image, dtype=np.int64)
+        h = C.c_void_p()
+        _check(lib.edl_pipeline_load(image.ctypes.data_as(_i64p), image.size, C.byref(h)))
+        return cls(_handle=h)
+
+    def close(self):
+        if self._h is not None:
+            lib.edl_pipeline_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 class Job:

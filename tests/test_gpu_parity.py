@@ -190,6 +190,43 @@ def test_free_running_resnet50_bf16():
     assert r["loss"] < 0.1, r
 
 
+# ---------------------------------------------------------------- training on the dynamic data pipeline's batches
+def test_training_on_pipeline_batches_with_joins_and_exits():
+    """The library's data pipeline (8 partitions of 12 samples) feeds edl_step while workers join and leave at
+    mini-batch boundaries; the oracle's pipeline feeds the oracle's step.  Same index lists, same model."""
+    torch = _torch()
+    import paper_1909_11985_amd as E
+    from paper_1909_11985_amd.binding import make_config
+    from oracle.pipeline import DataPipeline
+    from parity_util import DEFAULT_HWC, oracle_kwargs
+    import synth_inputs
+    model, N, B, d, seed = "mlp", 96, 24, 8, 3
+    kw = TINY[model]
+    x, y = synth_inputs.dataset(1, N, kw["H"], kw["W"], kw["C"], kw["classes"])
+    cfg = make_config(model, dtype="f32", N=N, B=B, p_max=4, max_shard=B, H=kw["H"], W=kw["W"], C_=kw["C"],
+                      classes=kw["classes"], arch=kw["arch"])
+    job = E.Job(cfg, seed)
+    job.bind_dataset(torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda())
+    orc = O.Oracle(model, seed, N, B, graph_kwargs=oracle_kwargs(model, kw["H"], kw["W"], kw["C"], kw["classes"], kw["arch"]))
+    lib_pipe, orc_pipe = E.Pipeline(seed, N, d), DataPipeline(seed, N, d)
+    # worker sets per mini-batch: 2 workers, two join, two of the first leave, one left alone, three again ...
+    sched = [[0, 1], [0, 1, 2, 3], [2, 3], [3], [3, 4, 5], [4, 5], [4, 5], [4, 6]]
+    seen = []
+    for workers in sched:
+        idx, off = lib_pipe.next_batch(B, workers)
+        ref_idx, ref_off = orc_pipe.next_batch(B, workers)
+        assert idx.tolist() == ref_idx and off.tolist() == ref_off
+        p = len(workers)
+        assert all(off[k] == k * (B // p) for k in range(p + 1)), "this schedule keeps the shards equal"
+        loss = job.step(p, idx, off)
+        lo = orc.step(p, x, y, np.asarray(ref_idx), np.asarray(ref_off))
+        assert abs(loss - lo) < 1e-5 * max(abs(lo), 1.0)
+        seen += idx.tolist()
+    assert sorted(seen[:N]) == list(range(N)) and sorted(seen[N:]) == list(range(N))   # two epochs, each once
+    assert relerr(job.params(), orc.w) < TOL["f32"]
+    assert relerr(job.momentum(), orc.v) < TOL["f32"]
+
+
 # ---------------------------------------------------------------- snapshot
 def test_snapshot_bytes_and_resume():
     torch = _torch()

@@ -83,3 +83,75 @@ def test_flops_per_sample(E):
     assert s.flops_per_sample == 2 * (2 * 784 * 256 + 3 * 256 * 256 + 3 * 256 * 10)
     r = E.edl_query(make_config("resnet50", N=64, B=32, p_max=2))
     assert 23e9 < r.flops_per_sample < 25e9
+
+
+# ---------------------------------------------------------------- dynamic data pipeline (host only)
+@pytest.mark.parametrize("N,d,B", [(240, 12, 24), (240, 7, 24), (1000, 36, 40), (512, 512, 64), (360, 1, 12)])
+def test_pipeline_matches_the_oracle_under_random_scaling(E, N, d, B):
+    """Bit-exact against the oracle's leader over three epochs of joins and graceful exits."""
+    import random
+    from oracle.pipeline import DataPipeline
+    rng = random.Random(N + 7 * d)
+    lib_p, orc_p = E.Pipeline(11, N, d), DataPipeline(11, N, d)
+    divisors = [p for p in range(1, B + 1) if B % p == 0 and p <= 12]
+    workers = [0]
+    for t in range(3 * (N // B)):
+        if rng.random() < 0.6:
+            p = rng.choice(divisors)
+            keep = [w for w in workers if rng.random() < 0.6][:p]
+            fresh = [w for w in range(50) if w not in workers]
+            rng.shuffle(fresh)
+            workers = keep + fresh[:p - len(keep)]
+            rng.shuffle(workers)
+        idx, off = lib_p.next_batch(B, workers)
+        ref_idx, ref_off = orc_p.next_batch(B, workers)
+        assert idx.tolist() == ref_idx and off.tolist() == ref_off, "mini-batch %d differs" % t
+        assert lib_p.progress() == (orc_p.epoch, orc_p.consumed)
+    lib_p.close()
+
+
+def test_pipeline_at_the_sections_example_size(E):
+    """1,000 partitions of 1,200 samples, 10 -> 15 -> 12 workers inside one epoch: same batches as the oracle."""
+    from oracle.pipeline import DataPipeline
+    N, d, B = 1_200_000, 1000, 600
+    lib_p, orc_p = E.Pipeline(1, N, d), DataPipeline(1, N, d)
+    steps = N // B
+    for t in range(steps):
+        workers = list(range(10)) if t < steps // 3 else list(range(15)) if t < steps // 2 else list(range(10)) + [10, 13]
+        idx, off = lib_p.next_batch(B, workers)
+        ref_idx, ref_off = orc_p.next_batch(B, workers)
+        assert np.array_equal(idx, np.asarray(ref_idx)) and off.tolist() == ref_off
+    assert lib_p.progress() == (0, N)
+
+
+def test_pipeline_save_load_and_errors(E):
+    a = E.Pipeline(8, 240, 16)
+    sched = [[0, 1], [0, 1, 2], [2, 0], [5, 6, 7, 8], [5], [5, 9, 10], [1, 2]]
+    for w in sched[:3]:
+        a.next_batch(24, w)
+    image = a.save()
+    b = E.Pipeline.load(image)
+    for w in sched[3:] * 3:
+        ia, oa = a.next_batch(24, w)
+        ib, ob = b.next_batch(24, w)
+        assert np.array_equal(ia, ib) and np.array_equal(oa, ob)
+    for bad in (image[:-1], np.concatenate([[7], image[1:]])):
+        with pytest.raises(E.EdlError):
+            E.Pipeline.load(bad)
+    broken = image.copy()
+    broken[7] = 10 ** 6                                       # cursor beyond d
+    with pytest.raises(E.EdlError):
+        E.Pipeline.load(broken)
+    with pytest.raises(E.EdlError):
+        E.Pipeline(0, 10, 11)
+    with pytest.raises(E.EdlError):
+        E.Pipeline(0, 10, 7)
+    with pytest.raises(E.EdlError) as ei:
+        a.next_batch(24, [3, 3])
+    assert ei.value.code == -1
+    with pytest.raises(E.EdlError) as ei:
+        a.next_batch(24, [0, 1, 2, 3, 4])
+    assert ei.value.code == -2
+    with pytest.raises(E.EdlError) as ei:
+        a.next_batch(36, [0, 1])                              # 36 does not divide 240
+    assert ei.value.code == -2
