@@ -189,6 +189,29 @@ int32_t edl_gradients(edl_handle* h, int32_t p, const int64_t* idx, const int64_
 /* Only the second half: average the p gradient buffers and update. */
 int32_t edl_apply(edl_handle* h, int32_t p);
 
+/* The scheduler's profile(min_p, max_p) operator (sections 3.2, 5): the job is
+ * run at every parallelism p in [min_p, max_p] that its configuration allows
+ * (p divides B, p <= p_max, B/p <= max_shard), from the largest down to the
+ * smallest, `steps` mini-batches each.  These are ordinary training steps: the
+ * model and the progress move on exactly as by `steps` calls of edl_step per p.
+ * Reported per p, timed with HIP events on the job's stream:
+ *   ms_per_step, samples_per_s    one mini-batch of B samples on this GPU (all
+ *                                 p shards back to back, then the update);
+ *   worker_samples_per_s  t(p)    what one worker sustains on its shard of B/p
+ *                                 samples: B / (time of the p gradient passes);
+ *   efficiency            t(p) / max over the profiled p of t(p) (the paper's
+ *                         GPU efficiency, with one GPU standing in for each
+ *                         worker and no gradient exchange).
+ * out: host array of cap entries, filled in the order run; *out_count = how
+ * many.  EDL_EINVAL if no p in the range is allowed, steps <= 0 or steps > 256;
+ * EDL_ENOMEM if cap is too small. */
+typedef struct {
+    int32_t p, shard;
+    double ms_per_step, samples_per_s, worker_samples_per_s, efficiency;
+} edl_parallelism_point;
+int32_t edl_profile_parallelism(edl_handle* h, int32_t min_p, int32_t max_p, int32_t steps, edl_parallelism_point* out,
+                                int32_t cap, int32_t* out_count);
+
 /* State image for a joining worker: header, w[P], v[P], running[R] (float32,
  * little endian), written to device memory dev_dst of capacity cap. */
 int32_t edl_snapshot(edl_handle* h, void* dev_dst, size_t cap, size_t* out_written);

@@ -91,6 +91,7 @@ _SIGS = {
     "edl_average_update": [C.c_int32, C.POINTER(C.c_void_p), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
                            C.c_float, C.c_float, C.c_float, C.c_void_p],
     "edl_copy": [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p],
+    "edl_profile_parallelism": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.POINTER(C.c_int32)],
     "edl_pipeline_create": [C.c_uint64, C.c_int64, C.c_int64, C.POINTER(C.c_void_p)],
     "edl_pipeline_next_batch": [C.c_void_p, C.c_int64, C.c_int32, _i64p, _i64p, _i64p],
     "edl_pipeline_progress": [C.c_void_p, _i64p, _i64p],
@@ -192,6 +193,11 @@ def edl_profile_report():
     need = C.c_size_t()
     _check(lib.edl_profile_report(buf, len(buf), C.byref(need)))
     return json.loads(buf.value.decode())
+
+
+class ParallelismPoint(C.Structure):
+    _fields_ = [("p", C.c_int32), ("shard", C.c_int32), ("ms_per_step", C.c_double), ("samples_per_s", C.c_double),
+                ("worker_samples_per_s", C.c_double), ("efficiency", C.c_double)]
 
 
 class Pipeline:
@@ -375,6 +381,14 @@ class Job:
 
     def debug_forward_op(self, op, n):
         _check(lib.edl_debug_forward_op(self._h, op, n))
+
+    def profile_parallelism(self, min_p, max_p, steps):
+        """The scheduler's profile(min_p, max_p): list of dicts, largest parallelism first."""
+        out = (ParallelismPoint * 64)()
+        n = C.c_int32(0)
+        _check(lib.edl_profile_parallelism(self._h, min_p, max_p, steps, C.cast(out, C.c_void_p), 64, C.byref(n)))
+        return [dict(p=o.p, shard=o.shard, ms_per_step=o.ms_per_step, samples_per_s=o.samples_per_s,
+                     worker_samples_per_s=o.worker_samples_per_s, efficiency=o.efficiency) for o in out[:n.value]]
 
     def debug_forward_range(self, op_lo, op_hi, n):
         _check(lib.edl_debug_forward_range(self._h, op_lo, op_hi, n))

@@ -616,6 +616,61 @@ int32_t edl_step(edl_handle* h, int32_t p, const int64_t* idx, const int64_t* of
     return edl_apply(h, p);
 }
 
+int32_t edl_profile_parallelism(edl_handle* h, int32_t min_p, int32_t max_p, int32_t steps, edl_parallelism_point* out,
+                                int32_t cap, int32_t* out_count) {
+    if (!h || !out || !out_count) { set_error("null argument"); return EDL_EINVAL; }
+    *out_count = 0;
+    if (steps <= 0 || steps > 256) { set_error("steps=%d outside [1, 256]", steps); return EDL_EINVAL; }
+    if (!h->data_x) { set_error("no data set bound"); return EDL_EINVAL; }
+    std::vector<int32_t> ps;
+    for (int32_t p = std::min(max_p, h->cfg.p_max); p >= std::max(min_p, 1); --p)
+        if (h->cfg.B % p == 0 && h->cfg.B / p <= h->cfg.max_shard) ps.push_back(p);
+    if (ps.empty()) { set_error("no parallelism in [%d, %d] fits B=%lld, p_max=%d, max_shard=%d", min_p, max_p, (long long)h->cfg.B, h->cfg.p_max, h->cfg.max_shard); return EDL_EINVAL; }
+    if ((size_t)cap < ps.size()) { set_error("%zu entries needed", ps.size()); return EDL_ENOMEM; }
+    std::vector<hipEvent_t> ev((size_t)steps * 2 + 1);
+    for (hipEvent_t& e : ev) HIP_TRY(hipEventCreate(&e));
+    int rc = EDL_OK;
+    for (size_t i = 0; i < ps.size() && rc == EDL_OK; ++i) {
+        const int32_t p = ps[i];
+        // ev[2t]: before the gradient passes of step t; ev[2t+1]: after them, before the update; ev[2*steps]: end
+        for (int t = 0; t < steps && rc == EDL_OK; ++t) {
+            if (hipEventRecord(ev[(size_t)2 * t], h->st) != hipSuccess) { set_error("hipEventRecord failed"); rc = EDL_EHIP; break; }
+            rc = edl_gradients(h, p, nullptr, nullptr, nullptr);
+            if (rc) break;
+            if (hipEventRecord(ev[(size_t)2 * t + 1], h->st) != hipSuccess) { set_error("hipEventRecord failed"); rc = EDL_EHIP; break; }
+            rc = edl_apply(h, p);
+        }
+        if (rc) break;
+        if (hipEventRecord(ev[(size_t)2 * steps], h->st) != hipSuccess || hipEventSynchronize(ev[(size_t)2 * steps]) != hipSuccess) {
+            set_error("timing events failed");
+            rc = EDL_EHIP;
+            break;
+        }
+        float total_ms = 0.f;
+        double grad_ms = 0.0;
+        (void)hipEventElapsedTime(&total_ms, ev[0], ev[(size_t)2 * steps]);
+        for (int t = 0; t < steps; ++t) {
+            float ms = 0.f;
+            (void)hipEventElapsedTime(&ms, ev[(size_t)2 * t], ev[(size_t)2 * t + 1]);
+            grad_ms += ms;
+        }
+        edl_parallelism_point& o = out[i];
+        o.p = p;
+        o.shard = (int32_t)(h->cfg.B / p);
+        o.ms_per_step = (double)total_ms / steps;
+        o.samples_per_s = (double)h->cfg.B / (o.ms_per_step * 1e-3);
+        o.worker_samples_per_s = (double)h->cfg.B / (grad_ms / steps * 1e-3);
+        o.efficiency = 0.0;
+    }
+    for (hipEvent_t e : ev) (void)hipEventDestroy(e);
+    if (rc) return rc;
+    double best = 0.0;
+    for (size_t i = 0; i < ps.size(); ++i) best = std::max(best, out[i].worker_samples_per_s);
+    for (size_t i = 0; i < ps.size(); ++i) out[i].efficiency = best > 0 ? out[i].worker_samples_per_s / best : 0.0;
+    *out_count = (int32_t)ps.size();
+    return EDL_OK;
+}
+
 int32_t edl_snapshot(edl_handle* h, void* dev_dst, size_t cap, size_t* out_written) {
     if (!h || !dev_dst) { set_error("null argument"); return EDL_EINVAL; }
     const int64_t P = h->g.P, R = h->g.R;

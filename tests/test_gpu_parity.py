@@ -227,6 +227,41 @@ def test_training_on_pipeline_batches_with_joins_and_exits():
     assert relerr(job.momentum(), orc.v) < TOL["f32"]
 
 
+# ---------------------------------------------------------------- the scheduler's profile(min_p, max_p)
+def test_profile_parallelism_scales_in_and_trains_like_the_same_steps():
+    """profile(1, 4) with 2 mini-batches per parallelism: runs p = 4, 3, 2, 1 (largest first), every step is an
+    ordinary training step (the model ends where the oracle's does after the same schedule), and the GPU
+    efficiency is t(p) over the best t(p)."""
+    torch = _torch()
+    import paper_1909_11985_amd as E
+    from paper_1909_11985_amd.binding import make_config
+    from parity_util import oracle_kwargs
+    model, N, B, seed = "mlp", 48, 24, 2
+    kw = TINY[model]
+    x, y = synth_inputs.dataset(1, N, kw["H"], kw["W"], kw["C"], kw["classes"])
+    cfg = make_config(model, dtype="f32", N=N, B=B, p_max=4, max_shard=B, H=kw["H"], W=kw["W"], C_=kw["C"],
+                      classes=kw["classes"], arch=kw["arch"])
+    job = E.Job(cfg, seed)
+    job.bind_dataset(torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda())
+    pts = job.profile_parallelism(1, 4, 2)
+    assert [pt["p"] for pt in pts] == [4, 3, 2, 1] and [pt["shard"] for pt in pts] == [6, 8, 12, 24]
+    assert all(pt["ms_per_step"] > 0 and pt["samples_per_s"] > 0 for pt in pts)
+    best = max(pt["worker_samples_per_s"] for pt in pts)
+    for pt in pts:
+        assert abs(pt["efficiency"] - pt["worker_samples_per_s"] / best) < 1e-12
+        assert pt["worker_samples_per_s"] >= pt["samples_per_s"]          # the update comes on top of the gradient passes
+    assert max(pt["efficiency"] for pt in pts) == 1.0
+    orc = O.Oracle(model, seed, N, B, graph_kwargs=oracle_kwargs(model, kw["H"], kw["W"], kw["C"], kw["classes"], kw["arch"]))
+    for p in (4, 4, 3, 3, 2, 2, 1, 1):
+        orc.step(p, x, y)
+    assert job.progress() == (8, orc.epoch, orc.step_in_epoch)
+    assert relerr(job.params(), orc.w) < TOL["f32"] and relerr(job.momentum(), orc.v) < TOL["f32"]
+    with pytest.raises(E.EdlError):
+        job.profile_parallelism(5, 7, 2)                                   # 5 and 7 do not divide 24, 6 > p_max
+    with pytest.raises(E.EdlError):
+        job.profile_parallelism(1, 4, 0)
+
+
 # ---------------------------------------------------------------- snapshot
 def test_snapshot_bytes_and_resume():
     torch = _torch()
