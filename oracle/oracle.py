@@ -201,14 +201,22 @@ def softmax_ce_backward(prob, labels):
     return dz / n
 
 
-def sgd_momentum_update(w, v, grads, lr, momentum, wd):
-    """Aggregate the p local gradients by their mean (in rank order), then
-    g = mean + wd*w ; v = momentum*v + g ; w = w - lr*v.  With momentum = wd = 0
-    this is the paper's SGD equation for equal shards."""
+def sgd_momentum_update(w, v, grads, lr, momentum, wd, weights=None):
+    """Aggregate the p local gradients (in rank order), then
+    g = aggregate + wd*w ; v = momentum*v + g ; w = w - lr*v.
+    weights None: the mean of the p gradients; with momentum = wd = 0 this is
+    the paper's SGD equation for equal shards.  weights given (shard sizes over
+    the batch size, for shards of unequal size): the sum of weights[k]*grads[k],
+    which is again the mean of the per-sample gradients of the whole batch."""
     acc = np.zeros_like(w)
-    for g in grads:
-        acc = acc + g
-    gbar = acc / len(grads)
+    if weights is None:
+        for g in grads:
+            acc = acc + g
+        gbar = acc / len(grads)
+    else:
+        for wk, g in zip(weights, grads):
+            acc = acc + wk * g
+        gbar = acc
     g = gbar + wd * w
     v_new = momentum * v + g
     w_new = w - lr * v_new
@@ -563,21 +571,33 @@ class Oracle:
         a joiner) is the one whose batch-norm running statistics are kept."""
         if idx is None:
             idx, off = shard(self.seed, self.N, self.B, p, self.epoch, self.step_in_epoch)
-        grads, losses = [], []
+        sizes = [int(off[k + 1] - off[k]) for k in range(p)]
+        grads, losses, live = [], [], []
         for k in range(p):
+            if sizes[k] == 0:
+                continue                      # a worker the data pipeline could give nothing
             sel = idx[off[k]:off[k + 1]]
             x = np.asarray(data_x[sel], dtype=np.float64)
-            loss, G = self.forward_backward(x, np.asarray(data_y[sel]), update_running=(k == 0))
+            loss, G = self.forward_backward(x, np.asarray(data_y[sel]), update_running=(not live))
+            live.append(k)
             grads.append(G)
             losses.append(loss)
-        self.w, self.v = sgd_momentum_update(self.w, self.v, grads, self.lr, self.momentum, self.wd)
+        if all(n == sizes[0] for n in sizes):
+            self.w, self.v = sgd_momentum_update(self.w, self.v, grads, self.lr, self.momentum, self.wd)
+            mean_loss = float(np.mean(losses))
+        else:
+            # shards of unequal size (a tail batch of the data pipeline, a mini-batch redone by the
+            # survivors of a failure): every worker weighs in with its share of the batch
+            wts = [sizes[k] / float(self.B) for k in live]
+            self.w, self.v = sgd_momentum_update(self.w, self.v, grads, self.lr, self.momentum, self.wd, weights=wts)
+            mean_loss = float(sum(wk * lk for wk, lk in zip(wts, losses)))
         self.last_grads, self.last_losses = grads, losses
         self.step_count += 1
         self.step_in_epoch += 1
         if self.step_in_epoch == self.N // self.B:
             self.step_in_epoch = 0
             self.epoch += 1
-        return float(np.mean(losses))
+        return mean_loss
 
     # -- what a joining worker receives ------------------------------------
     def snapshot(self) -> bytes:

@@ -84,6 +84,35 @@ def test_step_equals_sgd_equation_of_section_2_1():
     np.testing.assert_allclose(o.w, w0 - 0.2 / 8 * sum(per_sample), rtol=1e-11, atol=1e-13)
 
 
+@pytest.mark.parametrize("sizes", [[3, 1, 4], [5, 0, 3], [1, 7], [2, 2, 2, 2]])
+def test_unequal_shards_still_give_the_sgd_equation_of_section_2_1(sizes):
+    """Shards of unequal size (a tail mini-batch of the data pipeline, a mini-batch redone by the survivors of a
+    failure), every worker weighted by its share of the batch: the step is still w - lr/|B| * the sum of the
+    per-sample gradients of the whole mini-batch, and the reported loss the mean over the mini-batch."""
+    o, x, y = make("mlp", N=16, B=8, lr=0.2, momentum=0.0, wd=0.0)
+    w0 = o.w.copy()
+    idx, _ = O.shard(o.seed, o.N, o.B, 1, 0, 0)
+    per_sample = [o.forward_backward(x[i:i + 1].astype(np.float64), y[i:i + 1]) for i in idx]
+    off = np.concatenate([[0], np.cumsum(sizes)])
+    loss = o.step(len(sizes), x, y, idx, off)
+    np.testing.assert_allclose(o.w, w0 - 0.2 / 8 * sum(g for _, g in per_sample), rtol=1e-11, atol=1e-13)
+    assert abs(loss - np.mean([l for l, _ in per_sample])) < 1e-12
+
+
+def test_weighted_update_by_hand():
+    """w = 1, v = 0.5, gradients 2 and -1 with shares 3/4 and 1/4, lr 0.1, momentum 0.9, wd 0.01:
+    aggregate 1.25, g = 1.26, v = 0.45 + 1.26 = 1.71, w = 1 - 0.171 = 0.829."""
+    w, v = O.sgd_momentum_update(np.array([1.0]), np.array([0.5]), [np.array([2.0]), np.array([-1.0])], 0.1, 0.9, 0.01,
+                                 weights=[0.75, 0.25])
+    assert abs(v[0] - 1.71) < 1e-15 and abs(w[0] - 0.829) < 1e-15
+    # equal shares are the mean
+    g = [np.array([0.3, -2.0]), np.array([1.1, 0.5]), np.array([-0.7, 4.0])]
+    a = O.sgd_momentum_update(np.array([1.0, 2.0]), np.array([0.1, -0.1]), g, 0.05, 0.9, 5e-4)
+    b = O.sgd_momentum_update(np.array([1.0, 2.0]), np.array([0.1, -0.1]), g, 0.05, 0.9, 5e-4, weights=[1 / 3] * 3)
+    np.testing.assert_allclose(a[0], b[0], rtol=1e-15)
+    np.testing.assert_allclose(a[1], b[1], rtol=1e-15)
+
+
 def test_trajectory_independent_of_p_schedule_without_batchnorm():
     a, x, y = make("vgg16", N=16, B=8, lr=0.01)
     b, _, _ = make("vgg16", N=16, B=8, lr=0.01)
