@@ -175,18 +175,29 @@ int32_t edl_shard(const edl_handle* h, int64_t B, int32_t p, int64_t epoch, int6
  * p buffers are averaged and the fused momentum-SGD update
  *   g = mean_k G_k + wd*w ;  v = momentum*v + g ;  w = w - lr*v
  * is applied.  idx/off (host, as produced by edl_shard) may be NULL: then the
- * library takes the shards of its own progress cursor.  out_loss (host, may be
- * NULL) receives the mean of the workers' mean losses; asking for it
- * synchronises the stream, otherwise the call only queues work.
- * EDL_EINVAL p<=0 or p>p_max; EDL_EINDIVISIBLE B%p; EDL_ENOMEM B/p>max_shard;
- * EDL_ERANGE index outside [0,N) or offsets not those of equal shards. */
+ * library takes the equal shards of its own progress cursor.
+ * A caller's own cut may have shards of unequal size (a tail mini-batch of
+ * edl_pipeline_next_batch; the current mini-batch redone by the survivors of a
+ * failure, section 4.2's approximate recovery): off runs from 0 to B, every
+ * shard has at most max_shard samples, a shard may be empty (that worker then
+ * computes nothing), B need not be a multiple of p.  The aggregate is then
+ * sum_k (n_k/B) G_k, which keeps the step the mean of the per-sample gradients
+ * of the mini-batch; equal shards take the plain mean above (bit-identical to
+ * it).  The first worker that has samples keeps the running statistics.
+ * out_loss (host, may be NULL) receives the mean loss over the mini-batch
+ * (the mean of the workers' mean losses, weighted by n_k/B if unequal); asking
+ * for it synchronises the stream, otherwise the call only queues work.
+ * EDL_EINVAL p<=0 or p>p_max; without idx/off: EDL_EINDIVISIBLE B%p, EDL_ENOMEM
+ * B/p>max_shard; with them: EDL_ENOMEM a shard larger than max_shard, EDL_ERANGE
+ * index outside [0,N) or offsets not monotone from 0 to B. */
 int32_t edl_step(edl_handle* h, int32_t p, const int64_t* idx, const int64_t* off, float* out_loss);
 
 /* Only the first half of edl_step (gradients of the p shards, no update).  For
  * parity tests and profiling. */
 int32_t edl_gradients(edl_handle* h, int32_t p, const int64_t* idx, const int64_t* off, float* out_loss);
 
-/* Only the second half: average the p gradient buffers and update. */
+/* Only the second half: aggregate the gradient buffers of the last edl_gradients (by the mean, or by the
+ * shards' shares if they were unequal: p must then be that call's p) and update. */
 int32_t edl_apply(edl_handle* h, int32_t p);
 
 /* The scheduler's profile(min_p, max_p) operator (sections 3.2, 5): the job is

@@ -189,6 +189,9 @@ struct edl_handle {
     hipEvent_t idx_event[kIdxSlots];
     int idx_slot = 0;
     float* loss_host = nullptr;
+    // shard sizes of the last edl_gradients (what edl_apply weighs the gradient buffers by)
+    std::vector<int64_t> shard_n;
+    bool shards_equal = true;
     // second stream for the weight gradients (null: everything on st)
     hipStream_t side = nullptr;
     hipEvent_t ev_ready[kReadyEvents];
@@ -545,18 +548,32 @@ static int check_p(const edl_handle* h, int32_t p) {
 
 int32_t edl_gradients(edl_handle* h, int32_t p, const int64_t* idx, const int64_t* off, float* out_loss) {
     if (!h) { set_error("null handle"); return EDL_EINVAL; }
-    int rc = check_p(h, p);
-    if (rc) return rc;
     if (!h->data_x) { set_error("no data set bound"); return EDL_EINVAL; }
     if ((idx == nullptr) != (off == nullptr)) { set_error("idx and off must both be given or both be NULL"); return EDL_EINVAL; }
-    const int64_t B = h->cfg.B, n = B / p;
+    const int64_t B = h->cfg.B;
+    std::vector<int64_t> sizes;
+    if (idx) {
+        // the caller's cut of the mini-batch: any shard sizes that fit the workspace (equal ones in normal use)
+        if (p <= 0 || p > h->cfg.p_max) { set_error("p=%d outside [1, p_max=%d]", p, h->cfg.p_max); return EDL_EINVAL; }
+        if (off[0] != 0 || off[p] != B) { set_error("off must run from 0 to B=%lld", (long long)B); return EDL_ERANGE; }
+        for (int k = 0; k < p; ++k) {
+            const int64_t nk = off[k + 1] - off[k];
+            if (nk < 0) { set_error("off[%d] > off[%d]", k, k + 1); return EDL_ERANGE; }
+            if (nk > h->cfg.max_shard) { set_error("shard %d of %lld samples exceeds max_shard=%d", k, (long long)nk, h->cfg.max_shard); return EDL_ENOMEM; }
+            sizes.push_back(nk);
+        }
+    } else {
+        const int rc = check_p(h, p);
+        if (rc) return rc;
+        sizes.assign((size_t)p, B / p);
+    }
+    bool equal = true;
+    for (int64_t nk : sizes) equal = equal && nk == sizes[0];
     const int slot = h->idx_slot;
     h->idx_slot = (slot + 1) % kIdxSlots;
     HIP_TRY(hipEventSynchronize(h->idx_event[slot]));
     int64_t* stage = h->idx_host[slot];
     if (idx) {
-        for (int k = 0; k <= p; ++k)
-            if (off[k] != k * n) { set_error("off[%d]=%lld: shards must be B/p=%lld samples each", k, (long long)off[k], (long long)n); return EDL_ERANGE; }
         for (int64_t i = 0; i < B; ++i) {
             if (idx[i] < 0 || idx[i] >= h->cfg.N) { set_error("idx[%lld]=%lld outside [0,N)", (long long)i, (long long)idx[i]); return EDL_ERANGE; }
             stage[i] = idx[i];
@@ -568,6 +585,8 @@ int32_t edl_gradients(edl_handle* h, int32_t p, const int64_t* idx, const int64_
         }
         memcpy(stage, h->perm.data() + h->prog.step_in_epoch * B, sizeof(int64_t) * (size_t)B);
     }
+    h->shard_n = sizes;
+    h->shards_equal = equal;
     int64_t* dev_idx = h->at<int64_t>(h->L.idx);
     HIP_TRY(hipMemcpyAsync(dev_idx, stage, sizeof(int64_t) * (size_t)B, hipMemcpyHostToDevice, h->st));
     HIP_TRY(hipEventRecord(h->idx_event[slot], h->st));
@@ -577,29 +596,57 @@ int32_t edl_gradients(edl_handle* h, int32_t p, const int64_t* idx, const int64_
     }
     transpose_weights(h);
     float* dev_losses = h->at<float>(h->L.losses);
+    int64_t at = 0;
+    bool first = true;       // the first worker that has samples keeps the running statistics
     for (int k = 0; k < p; ++k) {
-        forward_shard(h, dev_idx + (int64_t)k * n, (int)n, dev_losses + k, k == 0);
-        backward_shard(h, (int)n, h->grad_buf(k));
+        const int64_t nk = sizes[(size_t)k];
+        if (nk > 0) {
+            forward_shard(h, dev_idx + at, (int)nk, dev_losses + k, first);
+            backward_shard(h, (int)nk, h->grad_buf(k));
+            first = false;
+        }
+        at += nk;
     }
     HIP_TRY(hipGetLastError());
     if (out_loss) {
         HIP_TRY(hipMemcpyAsync(h->loss_host, dev_losses, sizeof(float) * (size_t)p, hipMemcpyDeviceToHost, h->st));
         HIP_TRY(hipStreamSynchronize(h->st));
         double s = 0;
-        for (int k = 0; k < p; ++k) s += h->loss_host[k];
-        *out_loss = (float)(s / p);
+        if (equal) {
+            for (int k = 0; k < p; ++k) s += h->loss_host[k];
+            s /= p;
+        } else {   // the mean over the mini-batch: every worker's mean weighs in with its share
+            for (int k = 0; k < p; ++k)
+                if (sizes[(size_t)k] > 0) s += (double)h->loss_host[k] * ((double)sizes[(size_t)k] / (double)B);
+        }
+        *out_loss = (float)s;
     }
     return EDL_OK;
 }
 
 int32_t edl_apply(edl_handle* h, int32_t p) {
     if (!h) { set_error("null handle"); return EDL_EINVAL; }
-    const int rc = check_p(h, p);
-    if (rc) return rc;
-    GradPtrs gp = {};
-    for (int k = 0; k < p; ++k) gp.g[k] = h->grad_buf(k);
-    launch_average_update(p, gp, h->w(), h->v(), h->cfg.dtype == EDL_DTYPE_BF16 ? h->at<uint16_t>(h->L.shadow) : nullptr,
-                          h->g.P, h->cfg.lr, h->cfg.momentum, h->cfg.wd, h->st);
+    uint16_t* shadow = h->cfg.dtype == EDL_DTYPE_BF16 ? h->at<uint16_t>(h->L.shadow) : nullptr;
+    if (h->shards_equal) {
+        const int rc = check_p(h, p);
+        if (rc) return rc;
+        GradPtrs gp = {};
+        for (int k = 0; k < p; ++k) gp.g[k] = h->grad_buf(k);
+        launch_average_update(p, gp, h->w(), h->v(), shadow, h->g.P, h->cfg.lr, h->cfg.momentum, h->cfg.wd, h->st);
+    } else {
+        // shards of unequal size: each gradient buffer weighs in with its shard's share of the mini-batch
+        if ((size_t)p != h->shard_n.size()) { set_error("p=%d, but the gradients are of %zu shards", p, h->shard_n.size()); return EDL_EINVAL; }
+        GradPtrs gp = {};
+        ShardShares sh = {};
+        int np = 0;
+        for (int k = 0; k < p; ++k) {
+            if (h->shard_n[(size_t)k] == 0) continue;
+            gp.g[np] = h->grad_buf(k);
+            sh.share[np] = (float)((double)h->shard_n[(size_t)k] / (double)h->cfg.B);
+            ++np;
+        }
+        launch_weighted_update(np, gp, sh, h->w(), h->v(), shadow, h->g.P, h->cfg.lr, h->cfg.momentum, h->cfg.wd, h->st);
+    }
     HIP_TRY(hipGetLastError());
     h->prog.step += 1;
     h->prog.step_in_epoch += 1;

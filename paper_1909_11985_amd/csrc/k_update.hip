@@ -121,6 +121,33 @@ void launch_average_update(int p, const GradPtrs& grads, float* w, float* v, uin
 #undef EDL_UPD
 }
 
+// The same for shards of unequal size: the aggregate is sum_k share[k] * G_k, share[k] = the shard's
+// part of the mini-batch (section 2.1: the mean of the per-sample gradients of the mini-batch).  Rare (a tail
+// mini-batch of the data pipeline, a mini-batch redone by the survivors of a failure): one element per lane.
+template <bool SHADOW>
+__global__ __launch_bounds__(256) void weighted_update_kernel(GradPtrs gp, ShardShares sh, int np, float* __restrict__ w,
+                                                              float* __restrict__ v, uint16_t* __restrict__ w16, int64_t P,
+                                                              float lr, float momentum, float wd) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= P) return;
+    float s = sh.share[0] * gp.g[0][i];
+    for (int k = 1; k < np; ++k) s += sh.share[k] * gp.g[k][i];
+    float wi = w[i];
+    const float vi = momentum * v[i] + (s + wd * wi);
+    wi -= lr * vi;
+    v[i] = vi;
+    w[i] = wi;
+    if (SHADOW) w16[i] = f32_to_bf16(wi);
+}
+
+void launch_weighted_update(int np, const GradPtrs& grads, const ShardShares& shares, float* w, float* v, uint16_t* w16,
+                            int64_t P, float lr, float momentum, float wd, hipStream_t st) {
+    const int grid = (int)((P + 255) / 256);
+    ProfScope ps("weighted_update", 0.0, (4.0 * np + 16.0 + (w16 ? 2.0 : 0.0)) * (double)P, st);
+    if (w16) hipLaunchKernelGGL(weighted_update_kernel<true>, dim3(grid), dim3(256), 0, st, grads, shares, np, w, v, w16, P, lr, momentum, wd);
+    else hipLaunchKernelGGL(weighted_update_kernel<false>, dim3(grid), dim3(256), 0, st, grads, shares, np, w, v, w16, P, lr, momentum, wd);
+}
+
 // ---------------------------------------------------------------------------
 // plain copy (snapshot / restore): 16-byte vectors when source, destination
 // and length allow it (the large state arrays do), else 4-byte or 1-byte units

@@ -12,10 +12,14 @@ constexpr int kMaxP = 16;           // gradient buffers one update launch can av
 constexpr int kRedRowBlocks = 1024;   // upper bound of row blocks in column reductions
 
 struct GradPtrs { const float* g[kMaxP]; };
+struct ShardShares { float share[kMaxP]; };   // a shard's part of the mini-batch
 
 // ---- aggregation + update, copies ----------------------------------------
 void launch_average_update(int p, const GradPtrs& grads, float* w, float* v, uint16_t* w16, int64_t P,
                            float lr, float momentum, float wd, hipStream_t st);
+// aggregate = sum_k shares[k] * grads[k] (shards of unequal size)
+void launch_weighted_update(int np, const GradPtrs& grads, const ShardShares& shares, float* w, float* v, uint16_t* w16,
+                            int64_t P, float lr, float momentum, float wd, hipStream_t st);
 void launch_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
 void launch_fill_f32(float* dst, float value, int64_t n, hipStream_t st);
 // dst[c][r][s][k] = cast(src[k][r][s][c]) (weights for the input-gradient contraction) for every

@@ -262,6 +262,83 @@ def test_profile_parallelism_scales_in_and_trains_like_the_same_steps():
         job.profile_parallelism(1, 4, 0)
 
 
+# ---------------------------------------------------------------- shards of unequal size
+@pytest.mark.parametrize("model,dtype", [("mlp", "f32"), ("resnet20", "f32"), ("resnet50", "bf16")])
+def test_unequal_shards_weigh_in_with_their_share(model, dtype):
+    """A caller's cut with unequal (and one empty) shard: gradients per shard, the weighted aggregate and the
+    update against the oracle's; then the current mini-batch redone by three survivors of four workers
+    (approximate recovery): 24 samples as 8 + 8 + 8, and 11 + 11 + 10 of a batch of 32 would be the same path."""
+    torch = _torch()
+    import paper_1909_11985_amd as E
+    from paper_1909_11985_amd.binding import make_config
+    from parity_util import oracle_kwargs, per_tensor_relerr
+    N, B, seed = 48, 24, 1
+    kw = TINY[model]
+    x, y = synth_inputs.dataset(1, N, kw["H"], kw["W"], kw["C"], kw["classes"])
+    cfg = make_config(model, dtype=dtype, N=N, B=B, p_max=4, max_shard=12, lr=0.05, H=kw["H"], W=kw["W"], C_=kw["C"],
+                      classes=kw["classes"], arch=kw["arch"])
+    job = E.Job(cfg, seed)
+    job.bind_dataset(torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda())
+    orc = O.Oracle(model, seed, N, B, lr=0.05, emulate_bf16=(dtype == "bf16"), dtype_code=E.DTYPES[dtype],
+                   graph_kwargs=oracle_kwargs(model, kw["H"], kw["W"], kw["C"], kw["classes"], kw["arch"]))
+    table = E.edl_tensor_table(cfg)
+    idx, _ = job.shard(B, 1, 0, 0)
+    tol = TOL[dtype]
+    for sizes in ([5, 11, 8], [12, 0, 12], [7, 7, 7, 3]):
+        off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+        w0, v0 = job.params().astype(np.float64), job.momentum().astype(np.float64)
+        loss = job.gradients(len(sizes), idx, off)
+        live = [k for k, n in enumerate(sizes) if n]
+        G = [job.grad(k).astype(np.float64) for k in live]
+        job.apply(len(sizes))
+        # the aggregation + update alone: the oracle's formula on the library's own gradient buffers
+        w1, v1 = O.sgd_momentum_update(w0, v0, G, 0.05, 0.9, 5e-4, weights=[sizes[k] / B for k in live])
+        assert relerr(job.momentum(), v1) < 1e-6 and relerr(job.params(), w1) < 1e-6, sizes
+        lo = orc.step(len(sizes), x, y, idx, off)
+        assert abs(loss - lo) < tol * max(abs(lo), 1.0)
+        if dtype == "f32":      # free-running bf16 gradients of a deep net decorrelate (see the free-running tests)
+            for j, k in enumerate(live):
+                e, name, whole = per_tensor_relerr(table, G[j], orc.last_grads[j])
+                assert whole < tol, (sizes, k, name, e, whole)
+            assert relerr(job.params(), orc.w) < tol and relerr(job.momentum(), orc.v) < tol
+        else:
+            orc.w, orc.v = job.params().astype(np.float64), job.momentum().astype(np.float64)   # same model for the next cut
+    # a cut that does not fit the workspace, and cuts that are not cuts
+    for bad, code in (([13, 11], -3), ([12, 11], -4), ([8, -2, 12, 6], -4)):
+        off = np.concatenate([[0], np.cumsum(bad)]).astype(np.int64)
+        with pytest.raises(E.EdlError) as ei:
+            job.step(len(bad), idx, off)
+        assert ei.value.code == code, (bad, ei.value)
+
+
+def test_a_tail_batch_of_the_pipeline_trains():
+    """Two partitions of 12 half read by two workers, then a third worker joins when nothing is unassigned:
+    the pipeline's tail mini-batch has shards 6 + 6 + 0; edl_step takes it as it is."""
+    torch = _torch()
+    import paper_1909_11985_amd as E
+    from paper_1909_11985_amd.binding import make_config
+    from oracle.pipeline import DataPipeline
+    from parity_util import oracle_kwargs
+    model, N, B, seed = "mlp", 24, 12, 2
+    kw = TINY[model]
+    x, y = synth_inputs.dataset(1, N, kw["H"], kw["W"], kw["C"], kw["classes"])
+    cfg = make_config(model, dtype="f32", N=N, B=B, p_max=3, max_shard=B, H=kw["H"], W=kw["W"], C_=kw["C"],
+                      classes=kw["classes"], arch=kw["arch"])
+    job = E.Job(cfg, seed)
+    job.bind_dataset(torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda())
+    orc = O.Oracle(model, seed, N, B, graph_kwargs=oracle_kwargs(model, kw["H"], kw["W"], kw["C"], kw["classes"], kw["arch"]))
+    lib_pipe, orc_pipe = E.Pipeline(seed, N, 2), DataPipeline(seed, N, 2)
+    for workers in ([0, 1], [0, 1, 2]):
+        idx, off = lib_pipe.next_batch(B, workers)
+        ref_idx, ref_off = orc_pipe.next_batch(B, workers)
+        assert idx.tolist() == ref_idx and off.tolist() == ref_off
+        loss = job.step(len(workers), idx, off)
+        lo = orc.step(len(workers), x, y, np.asarray(ref_idx), np.asarray(ref_off))
+        assert abs(loss - lo) < 1e-5 * max(abs(lo), 1.0)
+    assert off.tolist() == [0, 6, 12, 12]
+    assert relerr(job.params(), orc.w) < TOL["f32"]
+
+
 # ---------------------------------------------------------------- snapshot
 def test_snapshot_bytes_and_resume():
     torch = _torch()
