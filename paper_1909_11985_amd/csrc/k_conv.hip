@@ -1018,7 +1018,17 @@ static void launch_cfg(TileCfg t, bool fast, dim3 tiles, const ConvArgs& a_in, h
         return;
     }
     switch (t) {
-        case T128x128: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 2, 2, BK_BIG, true, PF_BIG>), grid, dim3(256), 0, st, a); break;
+        case T128x128: {
+            // Long reductions (VGG-16's 3x3 layers: 1,152 to 4,608 elements) run faster on full-length reduction
+            // steps (half the barriers per MFMA: measured 159 -> 135 us forward, 174 -> 154 us dgrad on VGG-16);
+            // short ones (ResNet-50's 1x1 layers) want the smaller LDS footprint and more workgroups per CU.
+            static const int full_steps_from = env_int("EDL_TUNE_BK64_KRED", 1024);
+            if (BK_BIG != BK && a.Kred >= full_steps_from)
+                hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 2, 2, BK, true, PF_BIG>), grid, dim3(256), 0, st, a);
+            else
+                hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 2, 2, BK_BIG, true, PF_BIG>), grid, dim3(256), 0, st, a);
+            break;
+        }
         case T128x64: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 2, 1, BK_BIG, true, PF_BIG>), grid, dim3(256), 0, st, a); break;
         case T128x32: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 4, 1, 1, 1, BK, true, PF_BIG>), grid, dim3(256), 0, st, a); break;
         default: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 1, 1, BK_SMALL, true, PF_SMALL>), grid, dim3(256), 0, st, a); break;
