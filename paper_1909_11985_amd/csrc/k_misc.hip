@@ -172,6 +172,71 @@ __global__ __launch_bounds__(256) void maxpool_bwd_vec_kernel(const T* __restric
     }
 }
 
+// The same with the window positions that can reach an input pixel enumerated without branches: at most
+// NC = ceil(k / stride) per dimension.  All NC*NC loads are issued before the first use (a position outside
+// the output reads a clamped one and is ignored), instead of one load and one wait per tap.
+template <typename T, int NC>
+__global__ __launch_bounds__(256) void maxpool_bwd_win_kernel(const T* __restrict__ dy, const uint8_t* __restrict__ arg,
+                                                              T* dx, int accumulate, int N, int H, int W, int C, int k,
+                                                              int stride, int pad, int Ho, int Wo) {
+    constexpr int VEC = Elem<T>::VEC;
+    const int cv = C / VEC;
+    const int64_t total = (int64_t)N * H * W * cv;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const int c0 = (int)(i % cv) * VEC;
+    int64_t t = i / cv;
+    const int w = (int)(t % W); t /= W;
+    const int h = (int)(t % H);
+    const int n = (int)(t / H);
+    // output rows ho with ho*stride - pad <= h < ho*stride - pad + k: ho in [ho_hi - NC + 1, ho_hi]
+    const int ho_hi = (h + pad) / stride, wo_hi = (w + pad) / stride;
+    Vec16<T> v[NC][NC];
+    uint8_t am[NC][NC][VEC];
+    bool ok[NC][NC];
+    int tap[NC][NC];
+    #pragma unroll
+    for (int a = 0; a < NC; ++a) {
+        #pragma unroll
+        for (int b = 0; b < NC; ++b) {
+            const int ho = ho_hi - a, wo = wo_hi - b;
+            const int r = h + pad - ho * stride, s2 = w + pad - wo * stride;      // tap of this pixel in that window
+            ok[a][b] = ho >= 0 && wo >= 0 && ho < Ho && wo < Wo && r < k && s2 < k;
+            tap[a][b] = r * k + s2;
+            const int hc = ho < 0 ? 0 : (ho >= Ho ? Ho - 1 : ho), wc = wo < 0 ? 0 : (wo >= Wo ? Wo - 1 : wo);
+            const int64_t o = (((int64_t)n * Ho + hc) * Wo + wc) * C + c0;
+            v[a][b] = load_vec(dy + o);
+            if (VEC == 8) *reinterpret_cast<uint2*>(am[a][b]) = *reinterpret_cast<const uint2*>(arg + o);
+            else *reinterpret_cast<uint32_t*>(am[a][b]) = *reinterpret_cast<const uint32_t*>(arg + o);
+        }
+    }
+    const int64_t xo = (((int64_t)n * H + h) * W + w) * C + c0;
+    Vec16<T> old;
+    old.u = make_uint4(0, 0, 0, 0);
+    if (accumulate) old = load_vec(dx + xo);
+    float g[VEC];
+    #pragma unroll
+    for (int e = 0; e < VEC; ++e) g[e] = 0.f;
+    // taps in the order of the kernel above (r ascending, then s): the tap grows with a and b
+    #pragma unroll
+    for (int a = 0; a < NC; ++a) {
+        #pragma unroll
+        for (int b = 0; b < NC; ++b) {
+            #pragma unroll
+            for (int e = 0; e < VEC; ++e)
+                if (ok[a][b] && am[a][b][e] == tap[a][b]) g[e] += Elem<T>::to_f32(v[a][b].e[e]);
+        }
+    }
+    if (accumulate) {
+        #pragma unroll
+        for (int e = 0; e < VEC; ++e) g[e] += Elem<T>::to_f32(old.e[e]);
+    }
+    Vec16<T> out;
+    #pragma unroll
+    for (int e = 0; e < VEC; ++e) out.e[e] = Elem<T>::from_f32(g[e]);
+    store_vec(dx + xo, out);
+}
+
 void launch_maxpool_forward(int dtype, const void* x, void* y, uint8_t* arg, int N, int H, int W, int C, int k,
                             int stride, int pad, int Ho, int Wo, hipStream_t st) {
     const int grid = ew_grid((int64_t)N * Ho * Wo * C);
@@ -204,6 +269,16 @@ void launch_maxpool_backward(int dtype, const void* dy, const uint8_t* arg, void
     const int vec = dtype == 1 ? 8 : 4;
     if (C % vec == 0) {
         const int vgrid = ew_grid((int64_t)N * H * W * (C / vec));
+        const int nc = (k + stride - 1) / stride;
+        const int64_t lanes = (int64_t)N * H * W * (C / vec);
+        if (nc <= 2 && lanes < (int64_t)1 << 38) {
+            const dim3 g1((unsigned)((lanes + 255) / 256));
+            if (dtype == 1 && nc == 1) hipLaunchKernelGGL((maxpool_bwd_win_kernel<bf16_t, 1>), g1, dim3(256), 0, st, (const bf16_t*)dy, arg, (bf16_t*)dx, accumulate ? 1 : 0, N, H, W, C, k, stride, pad, Ho, Wo);
+            else if (dtype == 1) hipLaunchKernelGGL((maxpool_bwd_win_kernel<bf16_t, 2>), g1, dim3(256), 0, st, (const bf16_t*)dy, arg, (bf16_t*)dx, accumulate ? 1 : 0, N, H, W, C, k, stride, pad, Ho, Wo);
+            else if (nc == 1) hipLaunchKernelGGL((maxpool_bwd_win_kernel<float, 1>), g1, dim3(256), 0, st, (const float*)dy, arg, (float*)dx, accumulate ? 1 : 0, N, H, W, C, k, stride, pad, Ho, Wo);
+            else hipLaunchKernelGGL((maxpool_bwd_win_kernel<float, 2>), g1, dim3(256), 0, st, (const float*)dy, arg, (float*)dx, accumulate ? 1 : 0, N, H, W, C, k, stride, pad, Ho, Wo);
+            return;
+        }
         if (dtype == 1)
             hipLaunchKernelGGL(maxpool_bwd_vec_kernel<bf16_t>, dim3(vgrid), dim3(256), 0, st, (const bf16_t*)dy, arg,
                                (bf16_t*)dx, accumulate ? 1 : 0, N, H, W, C, k, stride, pad, Ho, Wo);
