@@ -189,6 +189,7 @@ struct edl_handle {
     hipEvent_t idx_event[kIdxSlots];
     int idx_slot = 0;
     float* loss_host = nullptr;
+    std::vector<int> readers;            // per tensor storage: how many layers read it (as input or as residual)
     // shard sizes of the last edl_gradients (what edl_apply weighs the gradient buffers by)
     std::vector<int64_t> shard_n;
     bool shards_equal = true;
@@ -318,6 +319,11 @@ int32_t edl_init(edl_handle** out, const edl_config* cfg, uint64_t seed, void* d
     // a conv output feeding a batch norm must have no other consumer (its gradient is written, not added)
     h->arena = (char*)dev_arena;
     h->st = (hipStream_t)hip_stream;
+    h->readers.assign(h->g.tensors.size(), 0);
+    for (const Op& op : h->g.ops) {
+        if (op.x >= 0) h->readers[(size_t)storage_of(h->g, op.x)] += 1;
+        if (op.kind == OP_BN && op.res >= 0) h->readers[(size_t)storage_of(h->g, op.res)] += 1;
+    }
     for (int s = 0; s < kIdxSlots; ++s) {
         HIP_TRY(hipHostMalloc((void**)&h->idx_host[s], sizeof(int64_t) * (size_t)cfg->B, hipHostMallocDefault));
         HIP_TRY(hipEventCreateWithFlags(&h->idx_event[s], hipEventDisableTiming));
@@ -456,6 +462,8 @@ static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, siz
     // per-kernel timing wants one kernel at a time
     const bool overlap = h->side != nullptr && !prof_enabled();
     bool used_side = false;
+    size_t fused_for = (size_t)-1;   // the layer whose masked gradient and column sums the dgrad after it left
+    int fused_rows = 0;
     for (size_t ii = op_hi; ii-- > op_lo;) {
         const Op& op = g.ops[ii];
         switch (op.kind) {
@@ -467,7 +475,7 @@ static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, siz
                 const int64_t M = (int64_t)n * q.Ho * q.Wo;
                 const bool padded = h->L.wpad[ii] >= 0;
                 launch_bias_relu_backward(dt, h->act(op.y), h->grad(op.y), op.bias ? G + op.b_off : nullptr, M, op.K,
-                                          op.relu, partial, st);
+                                          op.relu, partial, fused_for == ii ? fused_rows : 0, st);
                 // The weight gradient needs only dy (final from here on) and the layer's input, and nothing
                 // before the update reads it: it runs on the second stream, beside the chain of input
                 // gradients, whose short kernels leave part of the chip idle.
@@ -486,8 +494,26 @@ static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, siz
                     launch_unpad_rows(h->at<float>(h->L.dwpad), G + op.w_off, (int64_t)op.K * op.R * op.S, g.tensors[0].C, h->L.cpad, ws);
                 const int sx = storage_of(g, op.x);
                 if (sx != 0) {
-                    launch_conv_dgrad(dt, q, h->grad(op.y), h->arena + h->L.wT[ii], written[(size_t)sx] != 0, h->grad(op.x),
-                                      h->at<float>(h->L.splitk_scratch), (size_t)h->L.splitk_scratch_bytes, st);
+                    // If the layer just before in the list produced this convolution's input, ends in a ReLU and has
+                    // no other reader, its backward starts with the masked gradient and its column sums: the dgrad's
+                    // epilogue can leave both (see DgradMask), and that layer then skips its own reduction pass.
+                    DgradMask mask = {};
+                    const bool acc = written[(size_t)sx] != 0;
+                    if (ii > op_lo && !acc && h->readers[(size_t)sx] == 1) {
+                        const Op& prod = g.ops[ii - 1];
+                        if (prod.relu && storage_of(g, prod.y) == sx && (prod.kind == OP_BN || prod.kind == OP_CONV)) {
+                            mask.act = h->act(op.x);
+                            mask.sums = partial;
+                            if (prod.kind == OP_BN) {
+                                mask.xin = h->act(prod.x);
+                                mask.mean_rstd = h->at<float>(h->L.bn_save[ii - 1]);
+                            }
+                        }
+                    }
+                    const int rows = launch_conv_dgrad(dt, q, h->grad(op.y), h->arena + h->L.wT[ii], acc, h->grad(op.x),
+                                                       h->at<float>(h->L.splitk_scratch), (size_t)h->L.splitk_scratch_bytes,
+                                                       mask.act ? &mask : nullptr, st);
+                    if (rows > 0) { fused_for = ii - 1; fused_rows = rows; }
                     written[(size_t)sx] = 1;
                 }
                 break;
@@ -505,7 +531,7 @@ static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, siz
                 }
                 launch_bn_backward(dt, h->act(op.x), h->act(op.y), h->grad(op.y), h->grad(op.x), dres, dres_acc,
                                    h->w() + op.w_off, h->at<float>(h->L.bn_save[ii]), G + op.w_off, G + op.b_off,
-                                   (int64_t)n * t.H * t.W, t.C, op.relu, partial, coef, st);
+                                   (int64_t)n * t.H * t.W, t.C, op.relu, partial, coef, fused_for == ii ? fused_rows : 0, st);
                 written[(size_t)sx] = 1;
                 break;
             }

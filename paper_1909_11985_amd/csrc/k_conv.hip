@@ -75,6 +75,16 @@ struct ConvArgs {
     // squares over this tile's rows go to stats[c * kRedRowBlocks + row tile] and
     // stats[(Nn + c) * kRedRowBlocks + row tile] (the layout of the batch-norm reduction's partial sums)
     float* stats;
+    // dgrad, vector path, whole reduction, stride 1, not accumulating: the layer that produced this
+    // convolution's input ends in a ReLU, and its backward starts with "gradient times (activation > 0)"
+    // followed by per-channel sums of that.  With mask_act (the activation, same shape as the output) the
+    // gradient is stored already masked, and its column sums over the tile's rows go to msum (the layout of
+    // stats above): kind 0 = sum of the masked gradient; kind 1 = sum of masked gradient * (xin - mean) * rstd
+    // if xin (the producing batch norm's input) and mean_rstd ([mean[Nn], rstd[Nn]]) are given, else unused.
+    const void* mask_act;
+    const void* xin;
+    const float* mean_rstd;
+    float* msum;
     // ceil(2^40 / d) for d = channels per tap and d = taps per kernel row: n / d == (n * magic) >> 40
     // for n * d < 2^40, which keeps the tap bookkeeping of the load loop free of branches
     unsigned long long magic_inner, magic_taps;
@@ -721,6 +731,17 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
     constexpr int CV = BN / OVEC;                              // vectors per stored row
     constexpr int NV = (STAGE_ROWS * CV + 255) / 256;          // vectors per lane and pass
     const bool add_old = MODE == CONV_DGRAD && a.accumulate && !to_partial;
+    const bool masked = MODE == CONV_DGRAD && a.mask_act != nullptr && !to_partial;
+    const bool with_xhat = masked && a.xin != nullptr;
+    float mu[OVEC], rs[OVEC];      // of this lane's columns
+    #pragma unroll
+    for (int e = 0; e < OVEC; ++e) { mu[e] = 0.f; rs[e] = 0.f; }
+    if (with_xhat) {
+        const int c0 = n0 + (tid % CV) * OVEC;
+        #pragma unroll
+        for (int e = 0; e < OVEC; ++e)
+            if (c0 + e < a.Nn) { mu[e] = a.mean_rstd[c0 + e]; rs[e] = a.mean_rstd[a.Nn + c0 + e]; }
+    }
     #pragma unroll
     for (int pass = 0; pass < WM; ++pass) {
         // dgrad adding to an existing gradient: its vectors are fetched now, all at once and without a
@@ -735,6 +756,19 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
                 const bool inside = v < STAGE_ROWS * CV && row < a.M && col < a.Nn;
                 const unsigned char* src = inside ? outp + (out_row<MODE, true>(a, row) * a.Nn + col) * OSZ : outp;
                 oldv[k] = *reinterpret_cast<const uint4*>(src);
+            }
+        }
+        // the activation (and the batch norm's input) at the positions this lane stores, fetched the same way
+        uint4 actv[NV], xinv[NV];
+        if (masked) {
+            #pragma unroll
+            for (int k = 0; k < NV; ++k) {
+                const int v = tid + k * 256, rl = v / CV, cv = v - rl * CV;
+                const int row = m0 + pass * STAGE_ROWS + rl, col = n0 + cv * OVEC;
+                const bool inside = v < STAGE_ROWS * CV && row < a.M && col < a.Nn;
+                const int64_t at = inside ? ((int64_t)row * a.Nn + col) * OSZ : 0;
+                actv[k] = *reinterpret_cast<const uint4*>((const unsigned char*)a.mask_act + at);
+                if (with_xhat) xinv[k] = *reinterpret_cast<const uint4*>((const unsigned char*)a.xin + at);
             }
         }
         if (wm == pass) {
@@ -781,6 +815,18 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
                         o.x += __uint_as_float(oldv[k].x); o.y += __uint_as_float(oldv[k].y);
                         o.z += __uint_as_float(oldv[k].z); o.w += __uint_as_float(oldv[k].w);
                     }
+                    if (masked) {
+                        const float am[4] = {__uint_as_float(actv[k].x), __uint_as_float(actv[k].y), __uint_as_float(actv[k].z), __uint_as_float(actv[k].w)};
+                        o.x = am[0] > 0.f ? o.x : 0.f; o.y = am[1] > 0.f ? o.y : 0.f;
+                        o.z = am[2] > 0.f ? o.z : 0.f; o.w = am[3] > 0.f ? o.w : 0.f;
+                        const float gv[4] = {o.x, o.y, o.z, o.w};
+                        const float xv[4] = {__uint_as_float(xinv[k].x), __uint_as_float(xinv[k].y), __uint_as_float(xinv[k].z), __uint_as_float(xinv[k].w)};
+                        #pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            csum[e % OVEC] += gv[e];
+                            if (with_xhat) csq[e % OVEC] += gv[e] * ((xv[e] - mu[e % OVEC]) * rs[e % OVEC]);
+                        }
+                    }
                     *reinterpret_cast<float4*>(dst) = o;
                     if (with_stats) {
                         csum[0] += o.x; csq[0] += o.x * o.x; csum[1] += o.y; csq[1] += o.y * o.y;
@@ -795,10 +841,34 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
                         o1.x += __uint_as_float(old.z << 16); o1.y += __uint_as_float(old.z & 0xffff0000u);
                         o1.z += __uint_as_float(old.w << 16); o1.w += __uint_as_float(old.w & 0xffff0000u);
                     }
+                    if (masked) {   // activation > 0: a positive bf16 (sign clear, not zero)
+                        const uint32_t aw[4] = {actv[k].x, actv[k].y, actv[k].z, actv[k].w};
+                        float* const ov[8] = {&o0.x, &o0.y, &o0.z, &o0.w, &o1.x, &o1.y, &o1.z, &o1.w};
+                        #pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            if (!(__uint_as_float(aw[e] << 16) > 0.f)) *ov[2 * e] = 0.f;
+                            if (!(__uint_as_float(aw[e] & 0xffff0000u) > 0.f)) *ov[2 * e + 1] = 0.f;
+                        }
+                    }
                     uint4 pk;
                     pk.x = pack2_bf16(o0.x, o0.y); pk.y = pack2_bf16(o0.z, o0.w);
                     pk.z = pack2_bf16(o1.x, o1.y); pk.w = pack2_bf16(o1.z, o1.w);
                     *reinterpret_cast<uint4*>(dst) = pk;
+                    if (masked) {   // sums of the stored (rounded) gradient
+                        const uint32_t w4[4] = {pk.x, pk.y, pk.z, pk.w};
+                        const uint32_t xw[4] = {xinv[k].x, xinv[k].y, xinv[k].z, xinv[k].w};
+                        #pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float lo = __uint_as_float(w4[e] << 16), hi = __uint_as_float(w4[e] & 0xffff0000u);
+                            csum[(2 * e) % OVEC] += lo;
+                            csum[(2 * e + 1) % OVEC] += hi;
+                            if (with_xhat) {
+                                const float xl = __uint_as_float(xw[e] << 16), xh = __uint_as_float(xw[e] & 0xffff0000u);
+                                csq[(2 * e) % OVEC] += lo * ((xl - mu[(2 * e) % OVEC]) * rs[(2 * e) % OVEC]);
+                                csq[(2 * e + 1) % OVEC] += hi * ((xh - mu[(2 * e + 1) % OVEC]) * rs[(2 * e + 1) % OVEC]);
+                            }
+                        }
+                    }
                     if (with_stats) {   // of the rounded values, as a reader of the stored tensor would see them
                         const uint32_t w4[4] = {pk.x, pk.y, pk.z, pk.w};
                         #pragma unroll
@@ -813,7 +883,8 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
         }
         __syncthreads();
     }
-    if (with_stats) {
+    if (with_stats || masked) {
+        float* const sums = with_stats ? a.stats : a.msum;
         // lanes with the same column vector differ in tid / CV: sum over them in a fixed order
         constexpr int GROUPS = 256 / CV;
         static_assert(2 * GROUPS * BN * 4 <= SMEM_BYTES, "column sums fit the tile memory");
@@ -830,8 +901,8 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
             float s1 = 0.f, s2 = 0.f;
             #pragma unroll 8
             for (int gq = 0; gq < GROUPS; ++gq) { s1 += red[gq * BN + c]; s2 += red[(GROUPS + gq) * BN + c]; }
-            a.stats[(int64_t)(n0 + c) * kRedRowBlocks + tile_x] = s1;
-            a.stats[(int64_t)(a.Nn + n0 + c) * kRedRowBlocks + tile_x] = s2;
+            sums[(int64_t)(n0 + c) * kRedRowBlocks + tile_x] = s1;
+            sums[(int64_t)(a.Nn + n0 + c) * kRedRowBlocks + tile_x] = s2;
         }
     }
 }
@@ -1204,8 +1275,9 @@ int launch_conv_fwd(int dtype, const ConvGeom& g, const void* x, const void* w, 
     return fused ? row_tiles : 0;
 }
 
-void launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dy, const void* wT, bool accumulate, void* dx,
-                       float* scratch, size_t scratch_bytes, hipStream_t st) {
+int launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dy, const void* wT, bool accumulate, void* dx,
+                      float* scratch, size_t scratch_bytes, const DgradMask* mask, hipStream_t st) {
+    int fused_rows = 0;
     const int VEC = dtype == 1 ? 8 : 4;
     ConvArgs a = base_args(g);
     a.A = dy; a.B = wT; a.out = dx;
@@ -1239,13 +1311,24 @@ void launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dy, const void*
                 if (splits > 1 && (scratch == nullptr || scratch_bytes < (size_t)splits * a.M * a.Nn * sizeof(float))) splits = 1;
             }
             if (splits > 1) { a.ksplit = ks; a.partial = scratch; }
-            launch_mode<CONV_DGRAD>(dtype, t, dim3((a.M + bm - 1) / bm, (a.Nn + bn - 1) / bn, splits), a, st);
+            const int row_tiles = (a.M + bm - 1) / bm;
+            // masked store and column sums in the epilogue: one launch that covers every pixel and writes (not adds)
+            static const bool tune_mask = env_int("EDL_TUNE_FUSED_MASK", 1) != 0;
+            const bool fuse = tune_mask && mask != nullptr && mask->act != nullptr && g.stride == 1 && splits == 1 && !accumulate &&
+                              row_tiles <= kRedRowBlocks && conv_fast(dtype, CONV_DGRAD, a) && conv_magic_ok(CONV_DGRAD, a);
+            a.mask_act = fuse ? mask->act : nullptr;
+            a.xin = fuse ? mask->xin : nullptr;
+            a.mean_rstd = fuse ? mask->mean_rstd : nullptr;
+            a.msum = fuse ? mask->sums : nullptr;
+            if (fuse) fused_rows = row_tiles;
+            launch_mode<CONV_DGRAD>(dtype, t, dim3(row_tiles, (a.Nn + bn - 1) / bn, splits), a, st);
             if (splits > 1) {
                 if (dtype == 1) launch_finish<bf16_t>(a, splits, nullptr, st);
                 else launch_finish<float>(a, splits, nullptr, st);
             }
         }
     }
+    return fused_rows;
 }
 
 struct WgradPlan {

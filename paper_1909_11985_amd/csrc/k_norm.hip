@@ -337,17 +337,18 @@ void launch_bn_forward(int dtype, const void* x, const void* res, void* y, const
 template <typename T, int VEC>
 static void bn_backward_t(const void* x, const void* y, const void* dy, void* dx, void* dres, bool dres_acc,
                           const float* gamma, const float* save, float* dgamma, float* dbeta, int64_t M, int C,
-                          bool relu, float* partial, float* coef, hipStream_t st) {
+                          bool relu, float* partial, float* coef, int sums_row_blocks, hipStream_t st) {
     const RedShape s = red_shape(M, C, VEC);
     const double tb = (double)sizeof(T) * (double)M * C;
-    {
-    ProfScope ps("bn_bwd_reduce", 0.0, tb * (relu ? 3.0 : 2.0), st);
-    hipLaunchKernelGGL((colreduce_kernel<T, VEC, 1>), s.grid, s.block, 0, st, (const T*)x, (const T*)(relu ? y : x), (T*)dy, save,
-                       M, C, s.rows_per_block, relu ? 1 : 0, partial);
+    if (sums_row_blocks <= 0) {   // else the dgrad that produced dy left the sums
+        ProfScope ps("bn_bwd_reduce", 0.0, tb * (relu ? 3.0 : 2.0), st);
+        hipLaunchKernelGGL((colreduce_kernel<T, VEC, 1>), s.grid, s.block, 0, st, (const T*)x, (const T*)(relu ? y : x), (T*)dy, save,
+                           M, C, s.rows_per_block, relu ? 1 : 0, partial);
+        sums_row_blocks = s.row_blocks;
     }
     {
-        ProfScope ps("bn_bwd_finalize", 0.0, 8.0 * (double)s.row_blocks * C, st);
-        hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3((C + 3) / 4), dim3(256), 0, st, partial, s.row_blocks, M, C,
+        ProfScope ps("bn_bwd_finalize", 0.0, 8.0 * (double)sums_row_blocks * C, st);
+        hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3((C + 3) / 4), dim3(256), 0, st, partial, sums_row_blocks, M, C,
                            dgamma, dbeta, coef);
     }
     ProfScope ps("bn_bwd_apply", 0.0, tb * ((relu ? 3.0 : 2.0) + 1.0 + (dres ? (dres_acc ? 2.0 : 1.0) : 0.0)), st);
@@ -358,41 +359,43 @@ static void bn_backward_t(const void* x, const void* y, const void* dy, void* dx
 
 void launch_bn_backward(int dtype, const void* x, const void* y, const void* dy, void* dx, void* dres,
                         bool dres_accumulate, const float* gamma, const float* save, float* dgamma, float* dbeta,
-                        int64_t M, int C, bool relu, float* partial, float* coef, hipStream_t st) {
+                        int64_t M, int C, bool relu, float* partial, float* coef, int sums_row_blocks,
+                        hipStream_t st) {
     if (dtype == 1) {
-        if (C % 8 == 0) bn_backward_t<bf16_t, 8>(x, y, dy, dx, dres, dres_accumulate, gamma, save, dgamma, dbeta, M, C, relu, partial, coef, st);
-        else bn_backward_t<bf16_t, 1>(x, y, dy, dx, dres, dres_accumulate, gamma, save, dgamma, dbeta, M, C, relu, partial, coef, st);
+        if (C % 8 == 0) bn_backward_t<bf16_t, 8>(x, y, dy, dx, dres, dres_accumulate, gamma, save, dgamma, dbeta, M, C, relu, partial, coef, sums_row_blocks, st);
+        else bn_backward_t<bf16_t, 1>(x, y, dy, dx, dres, dres_accumulate, gamma, save, dgamma, dbeta, M, C, relu, partial, coef, sums_row_blocks, st);
     } else {
-        if (C % 4 == 0) bn_backward_t<float, 4>(x, y, dy, dx, dres, dres_accumulate, gamma, save, dgamma, dbeta, M, C, relu, partial, coef, st);
-        else bn_backward_t<float, 1>(x, y, dy, dx, dres, dres_accumulate, gamma, save, dgamma, dbeta, M, C, relu, partial, coef, st);
+        if (C % 4 == 0) bn_backward_t<float, 4>(x, y, dy, dx, dres, dres_accumulate, gamma, save, dgamma, dbeta, M, C, relu, partial, coef, sums_row_blocks, st);
+        else bn_backward_t<float, 1>(x, y, dy, dx, dres, dres_accumulate, gamma, save, dgamma, dbeta, M, C, relu, partial, coef, sums_row_blocks, st);
     }
 }
 
 template <typename T, int VEC>
 static void bias_relu_backward_t(const void* y, void* dy, float* dbias, int64_t M, int C, bool relu, float* partial,
-                                 hipStream_t st) {
+                                 int sums_row_blocks, hipStream_t st) {
     const RedShape s = red_shape(M, C, VEC);
     const double tb = (double)sizeof(T) * (double)M * C;
-    {
+    if (sums_row_blocks <= 0) {   // else dy is masked already and its column sums are in partial
         ProfScope ps("bias_relu_bwd", 0.0, tb * (relu ? 3.0 : 1.0), st);
         hipLaunchKernelGGL((colreduce_kernel<T, VEC, 2>), s.grid, s.block, 0, st, (const T*)nullptr, (const T*)(relu ? y : dy), (T*)dy,
                            (const float*)nullptr, M, C, s.rows_per_block, relu ? 1 : 0, partial);
+        sums_row_blocks = s.row_blocks;
     }
     if (dbias) {
-        ProfScope ps("bias_finalize", 0.0, 4.0 * (double)s.row_blocks * C, st);
-        hipLaunchKernelGGL(bias_finalize_kernel, dim3((C + 3) / 4), dim3(256), 0, st, partial, s.row_blocks, C, dbias);
+        ProfScope ps("bias_finalize", 0.0, 4.0 * (double)sums_row_blocks * C, st);
+        hipLaunchKernelGGL(bias_finalize_kernel, dim3((C + 3) / 4), dim3(256), 0, st, partial, sums_row_blocks, C, dbias);
     }
 }
 
 void launch_bias_relu_backward(int dtype, const void* y, void* dy, float* dbias, int64_t M, int C, bool relu,
-                               float* partial, hipStream_t st) {
+                               float* partial, int sums_row_blocks, hipStream_t st) {
     if (!relu && !dbias) return;
     if (dtype == 1) {
-        if (C % 8 == 0) bias_relu_backward_t<bf16_t, 8>(y, dy, dbias, M, C, relu, partial, st);
-        else bias_relu_backward_t<bf16_t, 1>(y, dy, dbias, M, C, relu, partial, st);
+        if (C % 8 == 0) bias_relu_backward_t<bf16_t, 8>(y, dy, dbias, M, C, relu, partial, sums_row_blocks, st);
+        else bias_relu_backward_t<bf16_t, 1>(y, dy, dbias, M, C, relu, partial, sums_row_blocks, st);
     } else {
-        if (C % 4 == 0) bias_relu_backward_t<float, 4>(y, dy, dbias, M, C, relu, partial, st);
-        else bias_relu_backward_t<float, 1>(y, dy, dbias, M, C, relu, partial, st);
+        if (C % 4 == 0) bias_relu_backward_t<float, 4>(y, dy, dbias, M, C, relu, partial, sums_row_blocks, st);
+        else bias_relu_backward_t<float, 1>(y, dy, dbias, M, C, relu, partial, sums_row_blocks, st);
     }
 }
 

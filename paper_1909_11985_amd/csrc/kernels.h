@@ -60,9 +60,21 @@ struct ConvGeom {
 // launch_bn_forward takes as stats_row_blocks); it returns 0 if it left none.
 int launch_conv_fwd(int dtype, const ConvGeom& g, const void* x, const void* w, const float* bias, bool relu,
                     bool out_fp32, void* y, float* scratch, size_t scratch_bytes, float* stats, hipStream_t st);
-// dx (+)= conv^T(dy, wT); wT is the [C][R][S][K] copy
-void launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dy, const void* wT, bool accumulate, void* dx,
-                       float* scratch, size_t scratch_bytes, hipStream_t st);
+// What the layer that produced the convolution's input wants from the gradient dx when it ends in a ReLU:
+// dx * (act > 0), and per-channel sums of that over the rows (plain, and times (xin - mean) * rstd if xin is
+// given: a batch norm's backward sums).  sums: the column-reduction partial-sum scratch.
+struct DgradMask {
+    const void* act;          // the producer's output (= this convolution's input), dtype elements
+    const void* xin;          // the producing batch norm's input, or null
+    const float* mean_rstd;   // with xin: mean[C], rstd[C]
+    float* sums;
+};
+// dx (+)= conv^T(dy, wT); wT is the [C][R][S][K] copy.  mask (may be null): if the launch can (stride 1, one
+// launch over all pixels, writing), dx is stored already masked and the sums are left in mask->sums; returns
+// the number of row tiles summed (what the producer's backward takes as its row-block count), else 0 and dx
+// is the plain gradient.
+int launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dy, const void* wT, bool accumulate, void* dx,
+                      float* scratch, size_t scratch_bytes, const DgradMask* mask, hipStream_t st);
 // float32 scratch a forward / dgrad launch may use to cut a long reduction of a small problem
 size_t conv_splitk_scratch_bytes(int dtype, const ConvGeom& g);
 // dw = x^T * dy, float32 [K][R][S][C]; scratch holds split partial sums
@@ -76,13 +88,16 @@ void launch_bn_forward(int dtype, const void* x, const void* res, void* y, const
                        float* save_mean_rstd /*[2C]*/, float* running /*[2C] or null*/, int64_t M, int C,
                        bool relu, float* partial, int stats_row_blocks /*> 0: partial already holds the sums*/,
                        hipStream_t st);
+// sums_row_blocks > 0: partial already holds the two backward sums over that many row blocks (left there by
+// the dgrad that produced dy, which is then also masked already)
 void launch_bn_backward(int dtype, const void* x, const void* y, const void* dy, void* dx, void* dres,
                         bool dres_accumulate, const float* gamma, const float* save_mean_rstd,
                         float* dgamma, float* dbeta, int64_t M, int C, bool relu, float* partial, float* coef /*[2C]*/,
-                        hipStream_t st);
-// dy <- dy * (y > 0) in place if relu; dbias[c] = sum_rows dy (if dbias)
+                        int sums_row_blocks, hipStream_t st);
+// dy <- dy * (y > 0) in place if relu; dbias[c] = sum_rows dy (if dbias).
+// sums_row_blocks > 0: dy is masked already and partial holds its column sums over that many row blocks.
 void launch_bias_relu_backward(int dtype, const void* y, void* dy, float* dbias, int64_t M, int C, bool relu,
-                               float* partial, hipStream_t st);
+                               float* partial, int sums_row_blocks, hipStream_t st);
 
 // ---- pooling --------------------------------------------------------------
 void launch_maxpool_forward(int dtype, const void* x, void* y, uint8_t* arg, int N, int H, int W, int C, int k,
