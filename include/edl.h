@@ -270,6 +270,10 @@ int32_t edl_debug_forward_op(edl_handle* h, int32_t op, int32_t n);
  * of the batch norm reading the tensor again). */
 int32_t edl_debug_forward_range(edl_handle* h, int32_t op_lo, int32_t op_hi, int32_t n);
 int32_t edl_debug_backward_op(edl_handle* h, int32_t op, int32_t n, int32_t k);
+/* Layers op_hi-1 .. op_lo backward in that order, as they run inside a step (a
+ * convolution's input-gradient pass can hand the masked gradient and its
+ * column sums to the layer before it). */
+int32_t edl_debug_backward_range(edl_handle* h, int32_t op_lo, int32_t op_hi, int32_t n, int32_t k);
 int32_t edl_debug_set_labels(edl_handle* h, const int32_t* labels, int32_t n);
 
 int32_t edl_shutdown(edl_handle* h);

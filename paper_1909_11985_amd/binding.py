@@ -86,6 +86,7 @@ _SIGS = {
     "edl_debug_forward_op": [C.c_void_p, C.c_int32, C.c_int32],
     "edl_debug_forward_range": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32],
     "edl_debug_backward_op": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32],
+    "edl_debug_backward_range": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32],
     "edl_debug_set_labels": [C.c_void_p, C.POINTER(C.c_int32), C.c_int32],
     "edl_shutdown": [C.c_void_p],
     "edl_average_update": [C.c_int32, C.POINTER(C.c_void_p), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
@@ -395,6 +396,9 @@ class Job:
 
     def debug_backward_op(self, op, n, k=0):
         _check(lib.edl_debug_backward_op(self._h, op, n, k))
+
+    def debug_backward_range(self, op_lo, op_hi, n, k=0):
+        _check(lib.edl_debug_backward_range(self._h, op_lo, op_hi, n, k))
 
     def debug_set_labels(self, labels):
         labels = np.ascontiguousarray(labels, dtype=np.int32)

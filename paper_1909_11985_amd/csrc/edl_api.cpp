@@ -922,6 +922,18 @@ int32_t edl_debug_backward_op(edl_handle* h, int32_t op, int32_t n, int32_t k) {
     return EDL_OK;
 }
 
+int32_t edl_debug_backward_range(edl_handle* h, int32_t op_lo, int32_t op_hi, int32_t n, int32_t k) {
+    int rc = debug_prepare(h, n);
+    if (rc) return rc;
+    if (op_lo < 0 || op_hi < op_lo || (size_t)op_hi > h->g.ops.size()) { set_error("layers [%d, %d) out of range", op_lo, op_hi); return EDL_ERANGE; }
+    if (k < 0 || k >= h->cfg.p_max) { set_error("gradient buffer %d outside [0,p_max)", k); return EDL_EINVAL; }
+    backward_shard(h, n, h->grad_buf(k), (size_t)op_lo, (size_t)op_hi);
+    HIP_TRY(hipStreamSynchronize(h->st));
+    HIP_TRY(hipGetLastError());
+    return EDL_OK;
+}
+
+
 int32_t edl_debug_set_labels(edl_handle* h, const int32_t* labels, int32_t n) {
     if (!h || !labels || n <= 0 || n > h->cfg.max_shard) { set_error("bad argument"); return EDL_EINVAL; }
     HIP_TRY(hipMemcpyAsync(h->at<int32_t>(h->L.labels), labels, sizeof(int32_t) * (size_t)n, hipMemcpyHostToDevice, h->st));

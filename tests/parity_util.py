@@ -326,3 +326,84 @@ def conv_bn_pair_parity(model, dtype, n, N=None, seed=0, data_seed=1, H=0, W=0, 
             worst, where = e, bn.get("name", "bn")
     job.shutdown()
     return dict(fwd=worst, pairs=pairs, worst=where)
+
+
+def relu_producer_pair_parity(model, dtype, n, N=None, seed=0, data_seed=1, H=0, W=0, C=0, classes=0, arch=(), emulate=None,
+                              perturb=0.05):
+    """Every convolution whose input comes from the layer listed just before it, ending in a ReLU and read by
+    nobody else (a batch norm or a convolution with bias and ReLU), run backward together with that layer the
+    way a step runs them: the convolution's input-gradient pass stores the gradient masked and leaves the
+    producer's column sums.  Inputs are the oracle's; compared are the producer's input gradient and parameter
+    gradients.  Returns the worst errors and the number of pairs."""
+    import torch
+    import paper_1909_11985_amd as E
+    from paper_1909_11985_amd.binding import make_config
+
+    N = N or n
+    dH, dW, dC, dK = DEFAULT_HWC[model]
+    hh, ww, cc, kk = H or dH, W or dW, C or dC, classes or dK
+    x, y = synth_inputs.dataset(data_seed, N, hh, ww, cc, kk)
+    cfg = make_config(model, dtype=dtype, N=N, B=n, p_max=1, max_shard=n, H=H, W=W, C_=C, classes=classes, arch=arch)
+    job = E.Job(cfg, seed)
+    job.bind_dataset(torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda())
+    if emulate is None:
+        emulate = dtype == "bf16"
+    orc = O.Oracle(model, seed, N, n, emulate_bf16=emulate, graph_kwargs=oracle_kwargs(model, H, W, C, classes, arch))
+    if perturb:
+        rng = np.random.default_rng(seed + 100)
+        orc.w = (orc.w + perturb * rng.standard_normal(orc.w.size) * (np.abs(orc.w) + 0.1)).astype(np.float32).astype(np.float64)
+        job.set_params(orc.w)
+    idx = np.arange(n, dtype=np.int64)
+    _, G = orc.forward_backward(x[idx].astype(np.float64), y[idx])
+    job.debug_forward(idx)
+    tensors = job.debug_tensors()
+
+    def tid(name):
+        return 0 if name == "x" else int(name[1:])
+
+    def shaped(name, a):
+        th, tw, tc, _ = tensors[tid(name)]
+        return np.asarray(a).reshape(n, th, tw, tc)
+
+    ops = [(oi, op) for oi, op in enumerate(orc.graph.ops) if op["kind"] != "flatten"]
+    readers = {}
+    for _, op in ops:
+        readers[op["x"]] = readers.get(op["x"], 0) + 1
+        if op["kind"] == "bn" and op["res"] is not None:
+            readers[op["res"]] = readers.get(op["res"], 0) + 1
+    res = dict(dx=0.0, dw=0.0, pairs=0, worst="")
+    for gi in range(1, len(ops)):
+        (poi, prod), (coi, cons) = ops[gi - 1], ops[gi]
+        if cons["kind"] != "conv" or prod["kind"] not in ("bn", "conv") or not prod.get("relu"):
+            continue
+        if prod["y"] != cons["x"] or readers.get(cons["x"], 0) != 1 or tid(prod["x"]) == 0:
+            continue
+        # the producer's forward on the oracle's inputs (refreshes the statistics it keeps), then the oracle's output
+        job.debug_set(tid(prod["x"]), shaped(prod["x"], orc.last_act[prod["x"]]))
+        if prod["kind"] == "bn" and prod["res"] is not None:
+            job.debug_set(tid(prod["res"]), shaped(prod["res"], orc.last_act[prod["res"]]))
+        job.debug_forward_op(gi - 1, n)
+        job.debug_set(tid(prod["y"]), shaped(prod["y"], orc.last_act[prod["y"]]))
+        job.debug_set(tid(cons["y"]), shaped(cons["y"], orc.last_act[cons["y"]]))
+        job.debug_set(tid(cons["y"]), shaped(cons["y"], orc.last_dy[coi]), which=1)
+        job.debug_backward_range(gi - 1, gi + 1, n, 0)
+        e_x = 0.0
+        for name, contrib in orc.last_dx.get(poi, {}).items():
+            if tid(name) == 0 or tensors[tid(name)][3] == 0:
+                continue
+            e_x = max(e_x, relerr(job.debug_get(tid(name), n, which=1), shaped(name, contrib)))
+        if prod["kind"] == "bn":
+            cch = prod["C"]
+            e_w = max(relerr(job.grad_slice(0, prod["g_off"], cch), G[prod["g_off"]:prod["g_off"] + cch]),
+                      relerr(job.grad_slice(0, prod["b_off"], cch), G[prod["b_off"]:prod["b_off"] + cch]))
+        else:
+            wsize = prod["K"] * prod["R"] * prod["S"] * orc.last_act[prod["x"]].shape[-1]
+            e_w = relerr(job.grad_slice(0, prod["w_off"], wsize), G[prod["w_off"]:prod["w_off"] + wsize])
+            if prod["b_off"] is not None:
+                e_w = max(e_w, relerr(job.grad_slice(0, prod["b_off"], prod["K"]), G[prod["b_off"]:prod["b_off"] + prod["K"]]))
+        res["pairs"] += 1
+        if e_x > res["dx"] or e_w > res["dw"]:
+            res["worst"] = prod.get("name", prod["kind"])
+        res["dx"], res["dw"] = max(res["dx"], e_x), max(res["dw"], e_w)
+    job.shutdown()
+    return res

@@ -5,7 +5,8 @@ import pytest
 
 import synth_inputs
 from oracle import oracle as O
-from parity_util import TOL, conv_bn_pair_parity, forced_parity, layerwise_parity, relerr, run_parity
+from parity_util import (TOL, conv_bn_pair_parity, forced_parity, layerwise_parity, relerr, relu_producer_pair_parity,
+                         run_parity)
 
 pytestmark = pytest.mark.gpu
 
@@ -126,6 +127,21 @@ def test_convolution_hands_batch_statistics_to_its_batch_norm(model, dtype, n, k
     print(r)
     assert r["pairs"] > 0
     assert r["fwd"] < TOL[dtype], r
+
+
+@pytest.mark.parametrize("model,dtype,n,kw", [
+    ("resnet50", "f32", 12, TINY["resnet50"]), ("resnet50", "bf16", 16, dict(H=64, W=64)),
+    ("resnet50", "f32", 8, dict(H=64, W=64)), ("vgg16", "f32", 12, TINY["vgg16"]),
+    ("vgg16", "bf16", 4, dict(H=64, W=64, arch=(64, 512))),
+    ("resnet50", "bf16", 32, {}),                                 # the shard bench.py times
+])
+def test_input_gradient_pass_hands_masked_gradient_and_sums_to_its_producer(model, dtype, n, kw):
+    """ReLU-ending producer + convolution run backward as a pair, as inside a step: the producer's input gradient
+    and parameter gradients against the oracle's, from the oracle's tensors."""
+    r = relu_producer_pair_parity(model, dtype, n, **kw)
+    print(r)
+    assert r["pairs"] > 0
+    assert r["dx"] < TOL[dtype] and r["dw"] < TOL[dtype], r
 
 
 def test_layerwise_resnet50_bf16_at_the_benchmark_shape():
