@@ -36,11 +36,16 @@ WORKLOADS = {
     # name: (model, dtype, N, B, p, geometry overrides, lr)
     "resnet50_bf16_b32": ("resnet50", "bf16", 1024, 32, 1, {}, 0.1),
     "vgg16_bf16_b32": ("vgg16", "bf16", 256, 32, 1, {}, 0.01),
+    # the other networks of the paper's section 6
+    "resnet101_bf16_b32": ("resnet50", "bf16", 256, 32, 1, dict(arch=(64, 3, 4, 23, 3)), 0.1),
+    "resnet152_bf16_b32": ("resnet50", "bf16", 256, 32, 1, dict(arch=(64, 3, 8, 36, 3)), 0.1),
+    "vgg19_bf16_b32": ("vgg16", "bf16", 256, 32, 1, dict(arch=(64, 4096, 2, 2, 4, 4, 4)), 0.01),
+    "alexnet_bf16_b128": ("alexnet", "bf16", 512, 128, 1, {}, 0.001),
     "resnet20_f32_b128_p2": ("resnet20", "f32", 2048, 128, 2, {}, 0.1),
     "mlp_f32_b64_p4": ("mlp", "f32", 1024, 64, 4, {}, 0.1),
 }
 DEFAULT_HWC = {"mlp": (1, 1, 784, 10), "resnet20": (32, 32, 3, 10), "resnet50": (224, 224, 3, 1000),
-               "vgg16": (224, 224, 3, 1000)}
+               "vgg16": (224, 224, 3, 1000), "alexnet": (224, 224, 3, 1000)}
 
 
 def committed_traffic(workload, kernel):
@@ -249,8 +254,14 @@ def main():
     cpu_baseline = None
     if not args.no_cpu_baseline:
         from oracle import oracle as O
-        n_cpu = {"resnet50": 16, "vgg16": 4, "resnet20": B // p, "mlp": B // p}[model]
-        orc = O.Oracle(model, 0, N, n_cpu, lr=lr)
+        n_cpu = {"resnet50": 16, "vgg16": 4, "alexnet": 32, "resnet20": B // p, "mlp": B // p}[model]
+        gkw = {}
+        if model == "resnet50" and "arch" in geom:
+            gkw = dict(blocks=tuple(geom["arch"][1:5]))
+            n_cpu = 8
+        if model == "vgg16" and "arch" in geom:
+            gkw = dict(groups=tuple(geom["arch"][2:7]))
+        orc = O.Oracle(model, 0, N, n_cpu, lr=lr, graph_kwargs=gkw)
         xs, ys = x[:n_cpu].astype(np.float64), y[:n_cpu]
         tc0 = time.perf_counter()
         orc.forward_backward(xs, ys)

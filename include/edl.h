@@ -43,7 +43,10 @@ extern "C" {
 
 enum { EDL_OK = 0, EDL_EINVAL = -1, EDL_EINDIVISIBLE = -2, EDL_ENOMEM = -3, EDL_ERANGE = -4, EDL_EHIP = -5 };
 
-enum { EDL_MODEL_MLP = 0, EDL_MODEL_RESNET20 = 1, EDL_MODEL_RESNET50 = 2, EDL_MODEL_VGG16 = 3 };
+/* The networks of the paper's evaluation (section 6) are all reachable: ResNet-50 / -101 / -152 are
+ * EDL_MODEL_RESNET50 with stage depths {3,4,6,3} / {3,4,23,3} / {3,8,36,3}; VGG-16 / VGG-19 are
+ * EDL_MODEL_VGG16 with group depths {2,2,3,3,3} / {2,2,4,4,4}; AlexNet is EDL_MODEL_ALEXNET. */
+enum { EDL_MODEL_MLP = 0, EDL_MODEL_RESNET20 = 1, EDL_MODEL_RESNET50 = 2, EDL_MODEL_VGG16 = 3, EDL_MODEL_ALEXNET = 4 };
 
 /* arithmetic type of activations and of the weight copies the matrix cores
  * read; master weights, momentum and gradients are float32 in both cases */
@@ -67,9 +70,12 @@ typedef struct edl_config {
      *   MLP      {hidden1, hidden2}                     default {256, 256}; input is H*W*C features
      *   RESNET20 {width of stage 1, stages, blocks}     default {16, 3, 3}
      *   RESNET50 {base width, blocks of stages 1..4}    default {64, 3, 4, 6, 3}; 0 blocks ends the net
-     *   VGG16    {base width, fc width}                 default {64, 4096} */
+     *   VGG16    {base width, fc width, convolutions of groups 1..5}
+     *                                                   default {64, 4096, 2, 2, 3, 3, 3}
+     *   ALEXNET  {base width, fc width}                 default {64, 4096}; the five convolutions are
+     *                                                   base x {1, 3, 6, 4, 4} wide */
     int32_t H, W, C, classes;
-    int32_t arch[6];
+    int32_t arch[8];
 } edl_config;
 
 /* byte sizes and offsets inside the caller's arena (all offsets 256-byte aligned) */

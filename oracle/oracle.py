@@ -357,10 +357,12 @@ def build_resnet50(H=224, W=224, C=3, classes=1000, base=64, blocks=(3, 4, 6, 3)
     return g
 
 
-def build_vgg16(H=224, W=224, C=3, classes=1000, base=64, fc=4096):
+def build_vgg16(H=224, W=224, C=3, classes=1000, base=64, fc=4096, groups=(2, 2, 3, 3, 3)):
+    """VGG: groups (2,2,3,3,3) is the 16-layer net, (2,2,4,4,4) the 19-layer one (both appear in the
+    tables of section 6)."""
     g = Graph(H, W, C)
     t = "x"
-    plan = [(base, 2), (2 * base, 2), (4 * base, 3), (8 * base, 3), (8 * base, 3)]
+    plan = list(zip([base, 2 * base, 4 * base, 8 * base, 8 * base], groups))
     i = 0
     for width, reps in plan:
         for _ in range(reps):
@@ -375,9 +377,34 @@ def build_vgg16(H=224, W=224, C=3, classes=1000, base=64, fc=4096):
     return g
 
 
-MODEL_IDS = {"mlp": 0, "resnet20": 1, "resnet50": 2, "vgg16": 3}
+def build_alexnet(H=224, W=224, C=3, classes=1000, base=64, fc=4096):
+    """AlexNet (a row of the tables of section 6) in its single-tower form: five biased convolutions
+    with ReLU, 3x3/2 max pools after the 1st, 2nd and 5th, three fully connected layers; no response
+    normalisation, no dropout."""
+    g = Graph(H, W, C)
+    t = g.conv("x", base, 11, 4, 2, True, True, "conv1")
+    t = g.maxpool(t, 3, 2, 0)
+    t = g.conv(t, 3 * base, 5, 1, 2, True, True, "conv2")
+    t = g.maxpool(t, 3, 2, 0)
+    t = g.conv(t, 6 * base, 3, 1, 1, True, True, "conv3")
+    t = g.conv(t, 4 * base, 3, 1, 1, True, True, "conv4")
+    t = g.conv(t, 4 * base, 3, 1, 1, True, True, "conv5")
+    t = g.maxpool(t, 3, 2, 0)
+    t = g.flatten(t)
+    t = g.conv(t, fc, 1, 1, 0, True, True, "fc1")
+    t = g.conv(t, fc, 1, 1, 0, True, True, "fc2")
+    t = g.conv(t, classes, 1, 1, 0, True, False, "fc3")
+    g.loss(t)
+    return g
+
+
+MODEL_IDS = {"mlp": 0, "resnet20": 1, "resnet50": 2, "vgg16": 3, "alexnet": 4}
 BUILDERS = {"mlp": build_mlp, "resnet20": build_resnet20, "resnet50": build_resnet50,
-            "vgg16": build_vgg16}
+            "vgg16": build_vgg16, "alexnet": build_alexnet}
+# the deeper members of the two families named in section 6, as (builder, keyword arguments)
+VARIANTS = {"resnet101": ("resnet50", dict(blocks=(3, 4, 23, 3))),
+            "resnet152": ("resnet50", dict(blocks=(3, 8, 36, 3))),
+            "vgg19": ("vgg16", dict(groups=(2, 2, 4, 4, 4)))}
 
 
 # ----------------------------------------------------------------------------

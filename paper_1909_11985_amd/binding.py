@@ -13,7 +13,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("EDL_LIBRARY") or os.path.join(_HERE, "libedl.so")   # EDL_LIBRARY: another build of the same library
 
-MODELS = {"mlp": 0, "resnet20": 1, "resnet50": 2, "vgg16": 3}
+MODELS = {"mlp": 0, "resnet20": 1, "resnet50": 2, "vgg16": 3, "alexnet": 4}
 DTYPES = {"f32": 0, "bf16": 1}
 
 
@@ -28,7 +28,7 @@ class Config(C.Structure):
                 ("p_max", C.c_int32), ("max_shard", C.c_int32),
                 ("lr", C.c_float), ("momentum", C.c_float), ("wd", C.c_float),
                 ("H", C.c_int32), ("W", C.c_int32), ("C", C.c_int32), ("classes", C.c_int32),
-                ("arch", C.c_int32 * 6)]
+                ("arch", C.c_int32 * 8)]
 
 
 class Sizes(C.Structure):

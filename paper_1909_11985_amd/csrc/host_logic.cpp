@@ -271,13 +271,14 @@ static void build_resnet50(const edl_config& c, Graph& g) {
     g.loss(t);
 }
 
-// 13 biased 3x3 convolutions with ReLU in groups of 2,2,3,3,3, a 2x2/2 max
-// pool after each group, three fully connected layers.  No batch norm, no
-// dropout.
+// Biased 3x3 convolutions with ReLU in five groups (2,2,3,3,3 of them for the
+// 16-layer net, 2,2,4,4,4 for the 19-layer one), a 2x2/2 max pool after each
+// group, three fully connected layers.  No batch norm, no dropout.
 static void build_vgg16(const edl_config& c, Graph& g) {
     const int H = pick(c.H, 224), W = pick(c.W, 224), C = pick(c.C, 3), classes = pick(c.classes, 1000);
     const int base = pick(c.arch[0], 64), fc = pick(c.arch[1], 4096);
-    const int reps[5] = {2, 2, 3, 3, 3};
+    int reps[5] = {2, 2, 3, 3, 3};
+    if (c.arch[2] > 0) for (int i = 0; i < 5; ++i) reps[i] = c.arch[2 + i];
     const int mult[5] = {1, 2, 4, 8, 8};
     int t = g.add_tensor(H, W, C);
     int i = 0;
@@ -296,6 +297,29 @@ static void build_vgg16(const edl_config& c, Graph& g) {
     g.loss(t);
 }
 
+// Five biased convolutions with ReLU (11x11/4 pad 2, 5x5 pad 2, three 3x3
+// pad 1; base x {1,3,6,4,4} channels), a 3x3/2 max pool after the first, the
+// second and the fifth, three fully connected layers.  The single-tower form
+// without response normalisation; no dropout.
+static void build_alexnet(const edl_config& c, Graph& g) {
+    const int H = pick(c.H, 224), W = pick(c.W, 224), C = pick(c.C, 3), classes = pick(c.classes, 1000);
+    const int base = pick(c.arch[0], 64), fc = pick(c.arch[1], 4096);
+    int t = g.add_tensor(H, W, C);
+    t = g.conv(t, base, 11, 4, 2, true, true, "conv1");
+    t = g.maxpool(t, 3, 2, 0);
+    t = g.conv(t, 3 * base, 5, 1, 2, true, true, "conv2");
+    t = g.maxpool(t, 3, 2, 0);
+    t = g.conv(t, 6 * base, 3, 1, 1, true, true, "conv3");
+    t = g.conv(t, 4 * base, 3, 1, 1, true, true, "conv4");
+    t = g.conv(t, 4 * base, 3, 1, 1, true, true, "conv5");
+    t = g.maxpool(t, 3, 2, 0);
+    t = g.flatten(t);
+    t = g.conv(t, fc, 1, 1, 0, true, true, "fc1");
+    t = g.conv(t, fc, 1, 1, 0, true, true, "fc2");
+    t = g.conv(t, classes, 1, 1, 0, true, false, "fc3");
+    g.loss(t);
+}
+
 int build_graph(const edl_config& cfg, Graph& g) {
     g = Graph();
     switch (cfg.model) {
@@ -303,6 +327,7 @@ int build_graph(const edl_config& cfg, Graph& g) {
         case EDL_MODEL_RESNET20: build_resnet20(cfg, g); break;
         case EDL_MODEL_RESNET50: build_resnet50(cfg, g); break;
         case EDL_MODEL_VGG16: build_vgg16(cfg, g); break;
+        case EDL_MODEL_ALEXNET: build_alexnet(cfg, g); break;
         default: set_error("unknown model %d", cfg.model); return EDL_EINVAL;
     }
     for (const Tensor& t : g.tensors)

@@ -50,11 +50,15 @@ def oracle_kwargs(model, H=0, W=0, C=0, classes=0, arch=()):
         kw["blocks"] = tuple(b for b in arch[1:5] if b > 0)
     elif model == "vgg16" and arch:
         kw["base"], kw["fc"] = arch[0], arch[1]
+        if len(arch) >= 7 and arch[2] > 0:
+            kw["groups"] = tuple(arch[2:7])
+    elif model == "alexnet" and arch:
+        kw["base"], kw["fc"] = arch[0], arch[1]
     return kw
 
 
 DEFAULT_HWC = {"mlp": (1, 1, 784, 10), "resnet20": (32, 32, 3, 10), "resnet50": (224, 224, 3, 1000),
-               "vgg16": (224, 224, 3, 1000)}
+               "vgg16": (224, 224, 3, 1000), "alexnet": (224, 224, 3, 1000)}
 
 
 def run_parity(model, dtype, N, B, schedule, seed=0, data_seed=1, lr=0.1, momentum=0.9, wd=5e-4,

@@ -84,6 +84,14 @@ TINY = {
     "resnet20": dict(H=12, W=12, C=3, classes=6, arch=(8, 2, 1)),
     "resnet50": dict(H=32, W=32, C=3, classes=10, arch=(8, 1, 1, 0, 0)),
     "vgg16": dict(H=32, W=32, C=3, classes=7, arch=(8, 16)),
+    "alexnet": dict(H=67, W=67, C=3, classes=7, arch=(8, 16)),
+}
+# the other networks of the paper's section 6, as (model table, geometry)
+DEEP = {
+    "resnet101": ("resnet50", dict(H=64, W=64, arch=(64, 3, 4, 23, 3))),
+    "resnet152": ("resnet50", dict(H=64, W=64, arch=(64, 3, 8, 36, 3))),
+    "vgg19": ("vgg16", dict(H=64, W=64, arch=(64, 512, 2, 2, 4, 4, 4))),
+    "alexnet": ("alexnet", dict(H=131, W=131, arch=(64, 512))),
 }
 # the bf16 chain amplifies last-place differences; see the comment above
 PINNED_WHOLE_TOL = {"f32": 1e-4, "bf16": 5e-2}
@@ -112,6 +120,14 @@ def test_layerwise_tiny_nets(model, dtype):
 ])
 def test_layerwise_model_shapes(model, dtype, n, kw):
     _assert_layerwise(layerwise_parity(model, dtype, n, verbose=False, **kw), dtype)
+
+
+@pytest.mark.parametrize("name", list(DEEP))
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_layerwise_other_networks_of_the_evaluation(name, dtype):
+    """ResNet-101 / -152, VGG-19 and AlexNet at their real widths and depths, on a reduced image."""
+    model, kw = DEEP[name]
+    _assert_layerwise(layerwise_parity(model, dtype, 8, verbose=False, **kw), dtype)
 
 
 @pytest.mark.parametrize("model,dtype,n,kw", [
@@ -151,6 +167,13 @@ def test_layerwise_resnet50_bf16_at_the_benchmark_shape():
     _assert_layerwise(r, "bf16")
 
 
+def test_layerwise_alexnet_bf16_at_full_size():
+    """Every layer of AlexNet at 224x224 (11x11/4 and 5x5 windows, 3x3/2 pools without padding)."""
+    r = layerwise_parity("alexnet", "bf16", 32, verbose=False)
+    print(r)
+    _assert_layerwise(r, "bf16")
+
+
 @pytest.mark.parametrize("model,dtype,n,kw", [
     ("mlp", "f32", 12, TINY["mlp"]), ("resnet20", "f32", 12, TINY["resnet20"]),
     ("resnet50", "f32", 12, TINY["resnet50"]), ("vgg16", "f32", 12, TINY["vgg16"]),
@@ -158,6 +181,8 @@ def test_layerwise_resnet50_bf16_at_the_benchmark_shape():
     ("resnet20", "f32", 32, {}), ("resnet20", "bf16", 32, {}),
     ("resnet50", "f32", 16, dict(H=64, W=64)), ("resnet50", "bf16", 16, dict(H=64, W=64)),
     ("vgg16", "bf16", 8, dict(H=64, W=64, arch=(64, 512))),
+    ("alexnet", "f32", 12, TINY["alexnet"]), ("alexnet", "bf16", 8, DEEP["alexnet"][1]),
+    ("vgg16", "bf16", 8, DEEP["vgg19"][1]), ("resnet50", "bf16", 8, DEEP["resnet101"][1]),
 ])
 def test_pinned_backward_chain(model, dtype, n, kw):
     r = forced_parity(model, dtype, n, **kw)
@@ -173,10 +198,10 @@ def test_config1_mlp_fp32():
     assert r["grad"] < TOL["f32"] and r["param"] < TOL["f32"] and r["loss"] < 1e-5, r
 
 
-@pytest.mark.parametrize("model", ["mlp", "vgg16", "resnet20"])
+@pytest.mark.parametrize("model", ["mlp", "vgg16", "resnet20", "alexnet"])
 def test_free_running_tiny_fp32(model):
     """Several steps with p changing every step (shards of 12, 24, 6, 8 samples)."""
-    lr = 0.01 if model == "vgg16" else 0.1
+    lr = 0.01 if model in ("vgg16", "alexnet") else 0.1
     r = run_parity(model, "f32", N=48, B=24, schedule=[2, 1, 4, 3], lr=lr, **TINY[model])
     assert r["grad"] < TOL["f32"] and r["param"] < TOL["f32"] and r["momentum"] < TOL["f32"], r
     assert r["running"] < TOL["f32"] and r["loss"] < 1e-5

@@ -17,6 +17,10 @@ TINY = {
     "resnet50": dict(model="resnet50", kw=dict(H=16, W=16, C=3, classes=5, base=4, blocks=(1, 1)),
                      hwc=(16, 16, 3), classes=5),
     "vgg16": dict(model="vgg16", kw=dict(H=32, W=32, C=3, classes=4, base=2, fc=8), hwc=(32, 32, 3), classes=4),
+    "vgg19": dict(model="vgg16", kw=dict(H=32, W=32, C=3, classes=4, base=2, fc=8, groups=(2, 2, 4, 4, 4)),
+                  hwc=(32, 32, 3), classes=4),
+    # 67 -> 16 -> 7 -> 3 -> 1: the smallest side that leaves every pool a full window, plus a ragged edge
+    "alexnet": dict(model="alexnet", kw=dict(H=67, W=67, C=3, classes=4, base=2, fc=8), hwc=(67, 67, 3), classes=4),
 }
 
 
@@ -32,7 +36,8 @@ def test_param_counts_match_the_published_architectures():
         if line.startswith("#"):
             continue
         name, count = line.split()
-        assert O.BUILDERS[name]().P == int(count)
+        builder, kw = O.VARIANTS.get(name, (name, {}))
+        assert O.BUILDERS[builder](**kw).P == int(count), name
 
 
 @pytest.mark.parametrize("name", list(TINY))
@@ -60,7 +65,7 @@ def test_gradient_by_central_differences(name):
     assert worst < 1e-6, worst
 
 
-@pytest.mark.parametrize("name", ["mlp", "vgg16"])
+@pytest.mark.parametrize("name", ["mlp", "vgg16", "alexnet"])
 @pytest.mark.parametrize("p", [1, 2, 4, 8])
 def test_elasticity_invariant_without_batchnorm(name, p):
     """Section 3.1 / section 4: with the aggregate batch fixed, the mean of the
