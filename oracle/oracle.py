@@ -19,12 +19,15 @@ What it computes, in the paper's terms:
 * section 4.2: a joining worker receives the model of ONE existing worker
   (here: parameters, momentum, running statistics of worker 0, progress).
 
-Readings the paper leaves open (optimizer = momentum SGD with weight decay,
+* section 3.2, Listing 1: the optimizer the elastic optimizer wraps may be a
+  variant of SGD such as Adam (adam_update: Algorithm 1 of Kingma & Ba).
+
+Readings the paper leaves open (default optimizer = momentum SGD with weight decay,
 mean aggregation, per-worker batch-norm statistics, generator constants) are
 listed in the design notes of this repository.
 
 Parity pins: tests/test_oracle_*.py (finite differences, library routines on
-special cases, closed forms of the update, brute-force shard invariants).
+special cases, closed forms of both updates, brute-force shard invariants).
 Unpinned: the specific permutation constants (any permutation satisfies the
 paper) and the bf16 rounding points of emulate_bf16 mode.
 """
@@ -201,26 +204,50 @@ def softmax_ce_backward(prob, labels):
     return dz / n
 
 
-def sgd_momentum_update(w, v, grads, lr, momentum, wd, weights=None):
-    """Aggregate the p local gradients (in rank order), then
-    g = aggregate + wd*w ; v = momentum*v + g ; w = w - lr*v.
-    weights None: the mean of the p gradients; with momentum = wd = 0 this is
-    the paper's SGD equation for equal shards.  weights given (shard sizes over
-    the batch size, for shards of unequal size): the sum of weights[k]*grads[k],
-    which is again the mean of the per-sample gradients of the whole batch."""
-    acc = np.zeros_like(w)
+def aggregate_gradients(grads, weights=None):
+    """The p local gradients added in rank order.  weights None: their mean
+    (equal shards, the SGD equation of section 2.1).  weights given (shard sizes
+    over the batch size, for shards of unequal size): the sum of
+    weights[k]*grads[k], which is again the mean of the per-sample gradients of
+    the whole batch."""
+    acc = np.zeros_like(grads[0])
     if weights is None:
         for g in grads:
             acc = acc + g
-        gbar = acc / len(grads)
-    else:
-        for wk, g in zip(weights, grads):
-            acc = acc + wk * g
-        gbar = acc
-    g = gbar + wd * w
+        return acc / len(grads)
+    for wk, g in zip(weights, grads):
+        acc = acc + wk * g
+    return acc
+
+
+def sgd_momentum_update(w, v, grads, lr, momentum, wd, weights=None):
+    """Aggregate the p local gradients (in rank order), then
+    g = aggregate + wd*w ; v = momentum*v + g ; w = w - lr*v.
+    With momentum = wd = 0 this is the paper's SGD equation."""
+    g = aggregate_gradients(grads, weights) + wd * w
     v_new = momentum * v + g
     w_new = w - lr * v_new
     return w_new, v_new
+
+
+def adam_update(w, m, s, grads, t, lr, beta1, beta2, eps, wd, weights=None):
+    """The variant of SGD that the paper's usage example wraps (section 3.2,
+    Listing 1: an Adam optimizer inside the elastic optimizer), applied to the
+    aggregated gradient.  The steps are those of Algorithm 1 of Kingma & Ba,
+    "Adam: a method for stochastic optimization"; t counts updates from 1:
+        g = aggregate + wd*w
+        m = beta1*m + (1-beta1)*g          s = beta2*s + (1-beta2)*g*g
+        mhat = m / (1 - beta1**t)          shat = s / (1 - beta2**t)
+        w = w - lr * mhat / (sqrt(shat) + eps)
+    Weight decay enters as in the momentum update (an L2 term in the gradient);
+    the paper does not say.  Returns (w, m, s)."""
+    g = aggregate_gradients(grads, weights) + wd * w
+    m_new = beta1 * m + (1.0 - beta1) * g
+    s_new = beta2 * s + (1.0 - beta2) * g * g
+    mhat = m_new / (1.0 - beta1 ** t)
+    shat = s_new / (1.0 - beta2 ** t)
+    w_new = w - lr * mhat / (np.sqrt(shat) + eps)
+    return w_new, m_new, s_new
 
 
 # ----------------------------------------------------------------------------
@@ -445,17 +472,25 @@ SNAPSHOT_MAGIC = 0x314C4445      # "EDL1"
 SNAPSHOT_HEADER_BYTES = 256
 
 
+OPTIMIZER_IDS = {"momentum": 0, "adam": 1}
+
+
 class Oracle:
     def __init__(self, model: str, seed: int, N: int, B: int, lr=0.1, momentum=0.9, wd=5e-4,
-                 emulate_bf16=False, graph_kwargs=None, dtype_code=0):
+                 emulate_bf16=False, graph_kwargs=None, dtype_code=0, optimizer="momentum",
+                 beta2=0.999, eps=1e-8):
+        """optimizer "momentum": momentum-SGD with `momentum`; "adam": Adam, whose beta1 is `momentum`."""
         self.model = model
+        self.optimizer, self.beta2, self.eps = optimizer, beta2, eps
+        assert optimizer in OPTIMIZER_IDS
         self.graph = BUILDERS[model](**(graph_kwargs or {}))
         self.seed, self.N, self.B = seed, N, B
         self.lr, self.momentum, self.wd = lr, momentum, wd
         self.emulate_bf16 = emulate_bf16
         self.dtype_code = dtype_code
         self.w = he_init(self.graph, seed)
-        self.v = np.zeros_like(self.w)
+        self.v = np.zeros_like(self.w)          # momentum, or Adam's first moment
+        self.s = np.zeros_like(self.w)          # Adam's second moment (unused otherwise)
         self.running = np.zeros(self.graph.R)
         for op in self.graph.ops:
             if op["kind"] == "bn":
@@ -610,14 +645,18 @@ class Oracle:
             grads.append(G)
             losses.append(loss)
         if all(n == sizes[0] for n in sizes):
-            self.w, self.v = sgd_momentum_update(self.w, self.v, grads, self.lr, self.momentum, self.wd)
+            wts = None
             mean_loss = float(np.mean(losses))
         else:
             # shards of unequal size (a tail batch of the data pipeline, a mini-batch redone by the
             # survivors of a failure): every worker weighs in with its share of the batch
             wts = [sizes[k] / float(self.B) for k in live]
-            self.w, self.v = sgd_momentum_update(self.w, self.v, grads, self.lr, self.momentum, self.wd, weights=wts)
             mean_loss = float(sum(wk * lk for wk, lk in zip(wts, losses)))
+        if self.optimizer == "adam":
+            self.w, self.v, self.s = adam_update(self.w, self.v, self.s, grads, self.step_count + 1, self.lr,
+                                                 self.momentum, self.beta2, self.eps, self.wd, weights=wts)
+        else:
+            self.w, self.v = sgd_momentum_update(self.w, self.v, grads, self.lr, self.momentum, self.wd, weights=wts)
         self.last_grads, self.last_losses = grads, losses
         self.step_count += 1
         self.step_in_epoch += 1
@@ -628,22 +667,30 @@ class Oracle:
 
     # -- what a joining worker receives ------------------------------------
     def snapshot(self) -> bytes:
-        """Header (job meta-data and progress), then parameters, momentum and
+        """Header (job meta-data and progress), then parameters, the optimizer's
+        state (momentum; for Adam the first and then the second moment) and
         running statistics as float32.  Little endian."""
-        hdr = struct.pack("<IIIIQqqqqqfffIqq", SNAPSHOT_MAGIC, 1, MODEL_IDS[self.model], self.dtype_code,
+        adam = self.optimizer == "adam"
+        hdr = struct.pack("<IIIIQqqqqqfffIqqff", SNAPSHOT_MAGIC, 1, MODEL_IDS[self.model], self.dtype_code,
                           self.seed, self.N, self.B, self.step_count, self.epoch, self.step_in_epoch,
-                          self.lr, self.momentum, self.wd, 0, self.graph.P, self.graph.R)
+                          self.lr, self.momentum, self.wd, OPTIMIZER_IDS[self.optimizer], self.graph.P, self.graph.R,
+                          self.beta2 if adam else 0.0, self.eps if adam else 0.0)
         hdr = hdr + b"\0" * (SNAPSHOT_HEADER_BYTES - len(hdr))
         return (hdr + self.w.astype(np.float32).tobytes() + self.v.astype(np.float32).tobytes()
+                + (self.s.astype(np.float32).tobytes() if adam else b"")
                 + self.running.astype(np.float32).tobytes())
 
     def restore(self, blob: bytes):
         P, R = self.graph.P, self.graph.R
         f = struct.unpack_from("<IIIIQqqqqqfffIqq", blob, 0)
-        assert f[0] == SNAPSHOT_MAGIC and f[14] == P and f[15] == R
+        assert f[0] == SNAPSHOT_MAGIC and f[14] == P and f[15] == R and f[13] == OPTIMIZER_IDS[self.optimizer]
         self.seed, self.N, self.B = f[4], f[5], f[6]      # job meta-data travels with the model
         self.step_count, self.epoch, self.step_in_epoch = f[7], f[8], f[9]
         o = SNAPSHOT_HEADER_BYTES
         self.w = np.frombuffer(blob, np.float32, P, o).astype(np.float64)
         self.v = np.frombuffer(blob, np.float32, P, o + 4 * P).astype(np.float64)
-        self.running = np.frombuffer(blob, np.float32, R, o + 8 * P).astype(np.float64)
+        o += 8 * P
+        if self.optimizer == "adam":
+            self.s = np.frombuffer(blob, np.float32, P, o).astype(np.float64)
+            o += 4 * P
+        self.running = np.frombuffer(blob, np.float32, R, o).astype(np.float64)
