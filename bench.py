@@ -217,7 +217,24 @@ def main():
             gbs = r["bytes"] / r["ms"] / 1e6
             update.append(dict(p=pp, P=P, bytes_per_param=4 * pp + 18, us=round(1e3 * r["ms"] / r["launches"], 1),
                                gbs=round(gbs, 1), frac_of_hbm_peak=round(gbs / HBM_PEAK_GBS, 4)))
-        del grads
+        # the same aggregation fused with the Adam update (one more state array read and written)
+        s2 = torch.zeros(P, device="cuda")
+        for pp in (1, 8):
+            for t in (1, 2):
+                E.edl_adam_update(grads[:pp], w, v, s2, w16, 0.001, 0.9, 0.999, 1e-8, 5e-4, t)
+            torch.cuda.synchronize()
+            E.edl_profile(True)
+            for t in range(3, 13):
+                E.edl_adam_update(grads[:pp], w, v, s2, w16, 0.001, 0.9, 0.999, 1e-8, 5e-4, t)
+            torch.cuda.synchronize()
+            rr = E.edl_profile_report()
+            r = [q for q in rr if q["name"] == "adam_update"][0]
+            r["ms"] -= overhead_ms * r["launches"]
+            E.edl_profile(False)
+            gbs = r["bytes"] / r["ms"] / 1e6
+            update.append(dict(optimizer="adam", p=pp, P=P, bytes_per_param=4 * pp + 26, us=round(1e3 * r["ms"] / r["launches"], 1),
+                               gbs=round(gbs, 1), frac_of_hbm_peak=round(gbs / HBM_PEAK_GBS, 4)))
+        del grads, s2
         nbytes = 8 * P
         src = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
         dst = torch.empty(nbytes, dtype=torch.uint8, device="cuda")

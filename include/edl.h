@@ -48,6 +48,14 @@ enum { EDL_OK = 0, EDL_EINVAL = -1, EDL_EINDIVISIBLE = -2, EDL_ENOMEM = -3, EDL_
  * EDL_MODEL_VGG16 with group depths {2,2,3,3,3} / {2,2,4,4,4}; AlexNet is EDL_MODEL_ALEXNET. */
 enum { EDL_MODEL_MLP = 0, EDL_MODEL_RESNET20 = 1, EDL_MODEL_RESNET50 = 2, EDL_MODEL_VGG16 = 3, EDL_MODEL_ALEXNET = 4 };
 
+/* The variant of SGD that applies the aggregated gradient (section 2.1 names SGD "or its variants such
+ * as Adam"; the usage example of section 3.2 wraps an Adam optimizer).  With g = aggregate + wd*w:
+ *   MOMENTUM  v = momentum*v + g;  w -= lr*v
+ *   ADAM      m = beta1*m + (1-beta1)*g;  s = beta2*s + (1-beta2)*g*g;
+ *             w -= lr * (m / (1-beta1^t)) / (sqrt(s / (1-beta2^t)) + eps),   t = updates so far + 1
+ *             (Algorithm 1 of Kingma & Ba; beta1 is the configuration's `momentum`). */
+enum { EDL_OPT_MOMENTUM = 0, EDL_OPT_ADAM = 1 };
+
 /* arithmetic type of activations and of the weight copies the matrix cores
  * read; master weights, momentum and gradients are float32 in both cases */
 enum { EDL_DTYPE_F32 = 0, EDL_DTYPE_BF16 = 1 };
@@ -76,6 +84,8 @@ typedef struct edl_config {
      *                                                   base x {1, 3, 6, 4, 4} wide */
     int32_t H, W, C, classes;
     int32_t arch[8];
+    int32_t optimizer;  /* EDL_OPT_*; `momentum` above is Adam's beta1 */
+    float beta2, eps;   /* Adam only: 0 <= beta2 < 1, eps >= 0 (ignored by EDL_OPT_MOMENTUM) */
 } edl_config;
 
 /* byte sizes and offsets inside the caller's arena (all offsets 256-byte aligned) */
@@ -83,13 +93,14 @@ typedef struct edl_sizes {
     int64_t P;              /* parameters */
     int64_t R;              /* running-statistics floats (per batch-norm layer: mean[C], var[C]) */
     int64_t params_off;     /* float32 w[P] */
-    int64_t momentum_off;   /* float32 v[P] */
-    int64_t running_off;    /* float32 [R]   (params, momentum, running are contiguous) */
+    int64_t momentum_off;   /* float32 v[P]: the momentum, or Adam's first moment */
+    int64_t running_off;    /* float32 [R] */
     int64_t grads_off;      /* float32 G[p_max][P_padded] */
     int64_t grad_stride;    /* floats between consecutive workers' gradient buffers */
     int64_t arena_bytes;    /* total the caller must provide to edl_init */
-    int64_t snapshot_bytes; /* EDL_SNAPSHOT_HEADER_BYTES + 4*(2P + R) */
+    int64_t snapshot_bytes; /* EDL_SNAPSHOT_HEADER_BYTES + 4*(2P + R), with Adam 4*(3P + R) */
     double flops_per_sample; /* multiply-add flops of forward + both backward contractions */
+    int64_t second_off;     /* float32 s[P]: Adam's second moment; -1 with EDL_OPT_MOMENTUM */
 } edl_sizes;
 
 /* progress of the job: what notify_batch_end() counts */
@@ -229,8 +240,10 @@ typedef struct {
 int32_t edl_profile_parallelism(edl_handle* h, int32_t min_p, int32_t max_p, int32_t steps, edl_parallelism_point* out,
                                 int32_t cap, int32_t* out_count);
 
-/* State image for a joining worker: header, w[P], v[P], running[R] (float32,
- * little endian), written to device memory dev_dst of capacity cap. */
+/* State image for a joining worker: header, w[P], v[P], with Adam s[P], then
+ * running[R] (float32, little endian), written to device memory dev_dst of
+ * capacity cap.  The header names the optimizer; edl_restore refuses (EDL_EINVAL)
+ * an image of another model, job size or optimizer. */
 int32_t edl_snapshot(edl_handle* h, void* dev_dst, size_t cap, size_t* out_written);
 int32_t edl_restore(edl_handle* h, const void* dev_src, size_t len);
 
@@ -244,6 +257,9 @@ int32_t edl_get_grad(edl_handle* h, int32_t k, float* host_dst /* [P] */);
 int32_t edl_get_losses(edl_handle* h, int32_t p, float* host_dst /* [p] */);
 int32_t edl_set_params(edl_handle* h, const float* host_src /* [P] */);
 int32_t edl_set_momentum(edl_handle* h, const float* host_src /* [P] */);
+/* Adam's second moment; EDL_EINVAL for a job with another optimizer */
+int32_t edl_get_second_moment(edl_handle* h, float* host_dst /* [P] */);
+int32_t edl_set_second_moment(edl_handle* h, const float* host_src /* [P] */);
 
 /* Debugging hooks: run the two halves of one worker's pass separately and read
  * or overwrite activation tensors in between, so that a test can take the
@@ -292,6 +308,13 @@ int32_t edl_shutdown(edl_handle* h);
 int32_t edl_average_update(int32_t p, const float* const* dev_grads, float* dev_w, float* dev_v,
                            uint16_t* dev_w16, int64_t P, float lr, float momentum, float wd,
                            void* hip_stream);
+
+/* The same with the Adam update (see EDL_OPT_ADAM): dev_m, dev_s float32[P] are the two moments, t >= 1
+ * the number of this update (bias corrections 1/(1-beta^t) are formed on the host in double).  shares, if
+ * not NULL, is a HOST array of p weights and the aggregate is sum_k shares[k]*G_k instead of the mean. */
+int32_t edl_adam_update(int32_t p, const float* const* dev_grads, const float* shares, float* dev_w, float* dev_m,
+                        float* dev_s, uint16_t* dev_w16, int64_t P, float lr, float beta1, float beta2, float eps,
+                        float wd, int64_t t, void* hip_stream);
 
 /* Measurement: with profiling on, every kernel launch of this library (any
  * handle, and the stand-alone calls) is bracketed by a HIP event pair on the

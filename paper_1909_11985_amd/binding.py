@@ -28,13 +28,14 @@ class Config(C.Structure):
                 ("p_max", C.c_int32), ("max_shard", C.c_int32),
                 ("lr", C.c_float), ("momentum", C.c_float), ("wd", C.c_float),
                 ("H", C.c_int32), ("W", C.c_int32), ("C", C.c_int32), ("classes", C.c_int32),
-                ("arch", C.c_int32 * 8)]
+                ("arch", C.c_int32 * 8), ("optimizer", C.c_int32), ("beta2", C.c_float), ("eps", C.c_float)]
 
 
 class Sizes(C.Structure):
     _fields_ = [("P", C.c_int64), ("R", C.c_int64), ("params_off", C.c_int64), ("momentum_off", C.c_int64),
                 ("running_off", C.c_int64), ("grads_off", C.c_int64), ("grad_stride", C.c_int64),
-                ("arena_bytes", C.c_int64), ("snapshot_bytes", C.c_int64), ("flops_per_sample", C.c_double)]
+                ("arena_bytes", C.c_int64), ("snapshot_bytes", C.c_int64), ("flops_per_sample", C.c_double),
+                ("second_off", C.c_int64)]
 
 
 class Progress(C.Structure):
@@ -75,6 +76,8 @@ _SIGS = {
     "edl_get_losses": [C.c_void_p, C.c_int32, _f32p],
     "edl_set_params": [C.c_void_p, _f32p],
     "edl_set_momentum": [C.c_void_p, _f32p],
+    "edl_get_second_moment": [C.c_void_p, _f32p],
+    "edl_set_second_moment": [C.c_void_p, _f32p],
     "edl_debug_tensor_count": [C.c_void_p, C.POINTER(C.c_int32)],
     "edl_debug_tensor_shape": [C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32),
                                C.POINTER(C.c_int32), C.POINTER(C.c_int32)],
@@ -91,6 +94,8 @@ _SIGS = {
     "edl_shutdown": [C.c_void_p],
     "edl_average_update": [C.c_int32, C.POINTER(C.c_void_p), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
                            C.c_float, C.c_float, C.c_float, C.c_void_p],
+    "edl_adam_update": [C.c_int32, C.POINTER(C.c_void_p), C.POINTER(C.c_float), C.c_void_p, C.c_void_p, C.c_void_p,
+                        C.c_void_p, C.c_int64, C.c_float, C.c_float, C.c_float, C.c_float, C.c_float, C.c_int64, C.c_void_p],
     "edl_copy": [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p],
     "edl_profile_parallelism": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.POINTER(C.c_int32)],
     "edl_pipeline_create": [C.c_uint64, C.c_int64, C.c_int64, C.POINTER(C.c_void_p)],
@@ -104,7 +109,11 @@ _SIGS = {
     "edl_profile_report": [C.c_char_p, C.c_size_t, C.POINTER(C.c_size_t)],
 }
 for _name, _args in _SIGS.items():
-    _fn = getattr(lib, _name)
+    try:
+        _fn = getattr(lib, _name)
+    except AttributeError:
+        raise ImportError("%s lacks %s: it is older than include/edl.h; rebuild it with "
+                          "`python paper_1909_11985_amd/build.py`" % (_LIB_PATH, _name)) from None
     _fn.argtypes = _args
     _fn.restype = C.c_int32
 EXPORTS = ["edl_last_error"] + list(_SIGS)
@@ -115,8 +124,12 @@ def _check(rc):
         raise EdlError(rc, lib.edl_last_error().decode())
 
 
+OPTIMIZERS = {"momentum": 0, "adam": 1}
+
+
 def make_config(model, dtype="f32", N=1024, B=64, p_max=8, max_shard=None, lr=0.1, momentum=0.9, wd=5e-4,
-                H=0, W=0, C_=0, classes=0, arch=()):
+                H=0, W=0, C_=0, classes=0, arch=(), optimizer="momentum", beta2=0.999, eps=1e-8):
+    """optimizer "adam": `momentum` is its beta1."""
     cfg = Config()
     cfg.model = MODELS[model] if isinstance(model, str) else model
     cfg.dtype = DTYPES[dtype] if isinstance(dtype, str) else dtype
@@ -126,6 +139,8 @@ def make_config(model, dtype="f32", N=1024, B=64, p_max=8, max_shard=None, lr=0.
     cfg.H, cfg.W, cfg.C, cfg.classes = H, W, C_, classes
     for i, a in enumerate(arch):
         cfg.arch[i] = a
+    cfg.optimizer = OPTIMIZERS[optimizer] if isinstance(optimizer, str) else optimizer
+    cfg.beta2, cfg.eps = beta2, eps
     return cfg
 
 
@@ -169,6 +184,16 @@ def edl_average_update(grads, w, v, w16, lr, momentum, wd, stream=0):
     ptrs = (C.c_void_p * p)(*[g.data_ptr() for g in grads])
     _check(lib.edl_average_update(p, ptrs, w.data_ptr(), v.data_ptr(), w16.data_ptr() if w16 is not None else None,
                                   w.numel(), lr, momentum, wd, stream))
+
+
+def edl_adam_update(grads, w, m, s, w16, lr, beta1, beta2, eps, wd, t, shares=None, stream=0):
+    """grads: list of float32 device tensors; w, m, s: float32 device tensors; w16: bfloat16 device tensor or
+    None; t: number of this update (from 1); shares: optional weights of the gradients (else their mean)."""
+    p = len(grads)
+    ptrs = (C.c_void_p * p)(*[g.data_ptr() for g in grads])
+    sh = None if shares is None else (C.c_float * p)(*[float(x) for x in shares])
+    _check(lib.edl_adam_update(p, ptrs, sh, w.data_ptr(), m.data_ptr(), s.data_ptr(),
+                               w16.data_ptr() if w16 is not None else None, w.numel(), lr, beta1, beta2, eps, wd, t, stream))
 
 
 def edl_mfma_rate(dtype, blocks, iters, sink, stream=0):
@@ -323,6 +348,9 @@ class Job:
     def momentum(self):
         return self._get(lib.edl_get_momentum, self.P)
 
+    def second_moment(self):
+        return self._get(lib.edl_get_second_moment, self.P)
+
     def running(self):
         return self._get(lib.edl_get_running, self.R)
 
@@ -345,6 +373,10 @@ class Job:
     def set_momentum(self, v):
         v = np.ascontiguousarray(v, dtype=np.float32)
         _check(lib.edl_set_momentum(self._h, v.ctypes.data_as(_f32p)))
+
+    def set_second_moment(self, s):
+        s = np.ascontiguousarray(s, dtype=np.float32)
+        _check(lib.edl_set_second_moment(self._h, s.ctypes.data_as(_f32p)))
 
     # -- debugging hooks ---------------------------------------------------
     def debug_tensors(self):

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cmath>
 #include <cstdio>
 #include <cstring>
 #include <vector>
@@ -37,13 +38,14 @@ struct SnapshotHeader {
     uint64_t seed;
     int64_t N, B, step, epoch, step_in_epoch;
     float lr, momentum, wd;
-    uint32_t pad0;
+    uint32_t optimizer;
     int64_t P, R;
+    float beta2, eps;      // Adam only, else 0
 };
-static_assert(sizeof(SnapshotHeader) == 96, "snapshot header layout");
+static_assert(sizeof(SnapshotHeader) == 104, "snapshot header layout");
 
 struct Layout {
-    int64_t params = 0, momentum = 0, running = 0, shadow = 0, grads = 0, grad_stride = 0;
+    int64_t params = 0, momentum = 0, second = -1, running = 0, shadow = 0, grads = 0, grad_stride = 0;
     int64_t idx = 0, labels = 0, row_loss = 0, losses = 0, partial = 0, coef = 0, wgrad_scratch = 0;
     int64_t wgrad_scratch_bytes = 0;
     // partial sums of forward / dgrad reductions that are cut; apart from the weight-gradient
@@ -66,6 +68,12 @@ int validate(const edl_config& c) {
     if (c.p_max > kMaxP) { set_error("p_max %d exceeds %d", c.p_max, kMaxP); return EDL_EINVAL; }
     if (c.N % c.B) { set_error("N=%lld is not a multiple of B=%lld", (long long)c.N, (long long)c.B); return EDL_EINDIVISIBLE; }
     if (c.max_shard > c.B) { set_error("max_shard exceeds B"); return EDL_EINVAL; }
+    if (c.optimizer != EDL_OPT_MOMENTUM && c.optimizer != EDL_OPT_ADAM) { set_error("unknown optimizer %d", c.optimizer); return EDL_EINVAL; }
+    if (c.optimizer == EDL_OPT_ADAM &&
+        !(c.momentum >= 0.f && c.momentum < 1.f && c.beta2 >= 0.f && c.beta2 < 1.f && c.eps >= 0.f)) {
+        set_error("Adam needs 0 <= beta1 (momentum), beta2 < 1 and eps >= 0");
+        return EDL_EINVAL;
+    }
     return EDL_OK;
 }
 
@@ -105,6 +113,7 @@ void plan_layout(const edl_config& c, const Graph& g, Layout& L) {
     auto take = [&](int64_t bytes) { const int64_t at = o; o += align_up(bytes); return at; };
     L.params = take(4 * g.P);
     L.momentum = take(4 * g.P);
+    if (c.optimizer == EDL_OPT_ADAM) L.second = take(4 * g.P);
     L.running = take(4 * std::max<int64_t>(g.R, 1));
     L.shadow = c.dtype == EDL_DTYPE_BF16 ? take(2 * g.P) : -1;
     L.grad_stride = align_up(4 * g.P) / 4;
@@ -202,6 +211,9 @@ struct edl_handle {
     template <typename T> T* at(int64_t off) const { return reinterpret_cast<T*>(arena + off); }
     float* w() const { return at<float>(L.params); }
     float* v() const { return at<float>(L.momentum); }
+    float* s2() const { return at<float>(L.second); }                     // Adam only
+    bool adam() const { return cfg.optimizer == EDL_OPT_ADAM; }
+    int64_t state_floats() const { return (adam() ? 3 : 2) * g.P + g.R; }   // w, optimizer slots, running
     float* running() const { return at<float>(L.running); }
     float* grad_buf(int k) const { return at<float>(L.grads) + (int64_t)k * L.grad_stride; }
     void* act(int t) const { return arena + L.act[(size_t)storage_of(g, t)]; }
@@ -229,8 +241,9 @@ int32_t edl_query(const edl_config* cfg, edl_sizes* out) {
     out->grads_off = L.grads;
     out->grad_stride = L.grad_stride;
     out->arena_bytes = L.total;
-    out->snapshot_bytes = EDL_SNAPSHOT_HEADER_BYTES + 4 * (2 * g.P + g.R);
+    out->snapshot_bytes = EDL_SNAPSHOT_HEADER_BYTES + 4 * ((cfg->optimizer == EDL_OPT_ADAM ? 3 : 2) * g.P + g.R);
     out->flops_per_sample = g.flops_per_sample();
+    out->second_off = L.second;
     return EDL_OK;
 }
 
@@ -341,6 +354,7 @@ int32_t edl_init(edl_handle** out, const edl_config* cfg, uint64_t seed, void* d
     he_init(h->g, seed, init.data());
     HIP_TRY(hipMemcpyAsync(h->w(), init.data(), sizeof(float) * (size_t)h->g.P, hipMemcpyHostToDevice, h->st));
     launch_fill_f32(h->v(), 0.f, h->g.P, h->st);
+    if (h->adam()) launch_fill_f32(h->s2(), 0.f, h->g.P, h->st);
     for (const Op& op : h->g.ops)
         if (op.kind == OP_BN) {
             launch_fill_f32(h->running() + op.run_off, 0.f, op.K, h->st);
@@ -650,6 +664,19 @@ int32_t edl_gradients(edl_handle* h, int32_t p, const int64_t* idx, const int64_
     return EDL_OK;
 }
 
+// bias corrections of update number t, formed in double
+static void adam_corrections(double beta1, double beta2, int64_t t, float* c1, float* c2) {
+    *c1 = (float)(1.0 / (1.0 - std::pow(beta1, (double)t)));
+    *c2 = (float)(1.0 / (1.0 - std::pow(beta2, (double)t)));
+}
+
+static void apply_adam(edl_handle* h, int np, const GradPtrs& gp, const ShardShares* sh, uint16_t* shadow) {
+    float c1, c2;
+    adam_corrections(h->cfg.momentum, h->cfg.beta2, h->prog.step + 1, &c1, &c2);
+    launch_adam_update(np, gp, sh, h->w(), h->v(), h->s2(), shadow, h->g.P, h->cfg.lr, h->cfg.momentum, h->cfg.beta2,
+                       h->cfg.eps, h->cfg.wd, c1, c2, h->st);
+}
+
 int32_t edl_apply(edl_handle* h, int32_t p) {
     if (!h) { set_error("null handle"); return EDL_EINVAL; }
     uint16_t* shadow = h->cfg.dtype == EDL_DTYPE_BF16 ? h->at<uint16_t>(h->L.shadow) : nullptr;
@@ -658,7 +685,8 @@ int32_t edl_apply(edl_handle* h, int32_t p) {
         if (rc) return rc;
         GradPtrs gp = {};
         for (int k = 0; k < p; ++k) gp.g[k] = h->grad_buf(k);
-        launch_average_update(p, gp, h->w(), h->v(), shadow, h->g.P, h->cfg.lr, h->cfg.momentum, h->cfg.wd, h->st);
+        if (h->adam()) apply_adam(h, p, gp, nullptr, shadow);
+        else launch_average_update(p, gp, h->w(), h->v(), shadow, h->g.P, h->cfg.lr, h->cfg.momentum, h->cfg.wd, h->st);
     } else {
         // shards of unequal size: each gradient buffer weighs in with its shard's share of the mini-batch
         if ((size_t)p != h->shard_n.size()) { set_error("p=%d, but the gradients are of %zu shards", p, h->shard_n.size()); return EDL_EINVAL; }
@@ -671,7 +699,8 @@ int32_t edl_apply(edl_handle* h, int32_t p) {
             sh.share[np] = (float)((double)h->shard_n[(size_t)k] / (double)h->cfg.B);
             ++np;
         }
-        launch_weighted_update(np, gp, sh, h->w(), h->v(), shadow, h->g.P, h->cfg.lr, h->cfg.momentum, h->cfg.wd, h->st);
+        if (h->adam()) apply_adam(h, np, gp, &sh, shadow);
+        else launch_weighted_update(np, gp, sh, h->w(), h->v(), shadow, h->g.P, h->cfg.lr, h->cfg.momentum, h->cfg.wd, h->st);
     }
     HIP_TRY(hipGetLastError());
     h->prog.step += 1;
@@ -747,7 +776,7 @@ int32_t edl_profile_parallelism(edl_handle* h, int32_t min_p, int32_t max_p, int
 int32_t edl_snapshot(edl_handle* h, void* dev_dst, size_t cap, size_t* out_written) {
     if (!h || !dev_dst) { set_error("null argument"); return EDL_EINVAL; }
     const int64_t P = h->g.P, R = h->g.R;
-    const size_t need = EDL_SNAPSHOT_HEADER_BYTES + 4 * (size_t)(2 * P + R);
+    const size_t need = EDL_SNAPSHOT_HEADER_BYTES + 4 * (size_t)h->state_floats();
     if (cap < need) { set_error("snapshot needs %zu bytes, buffer has %zu", need, cap); return EDL_ENOMEM; }
     alignas(8) char hdr[EDL_SNAPSHOT_HEADER_BYTES];
     memset(hdr, 0, sizeof(hdr));
@@ -756,13 +785,17 @@ int32_t edl_snapshot(edl_handle* h, void* dev_dst, size_t cap, size_t* out_writt
     sh.seed = h->seed; sh.N = h->cfg.N; sh.B = h->cfg.B;
     sh.step = h->prog.step; sh.epoch = h->prog.epoch; sh.step_in_epoch = h->prog.step_in_epoch;
     sh.lr = h->cfg.lr; sh.momentum = h->cfg.momentum; sh.wd = h->cfg.wd; sh.P = P; sh.R = R;
+    sh.optimizer = (uint32_t)h->cfg.optimizer;
+    if (h->adam()) { sh.beta2 = h->cfg.beta2; sh.eps = h->cfg.eps; }
     memcpy(hdr, &sh, sizeof(sh));
     char* dst = (char*)dev_dst;
     HIP_TRY(hipMemcpyAsync(dst, hdr, sizeof(hdr), hipMemcpyHostToDevice, h->st));
     HIP_TRY(hipStreamSynchronize(h->st));   // hdr is on this stack frame
     launch_copy(dst + EDL_SNAPSHOT_HEADER_BYTES, h->w(), 4 * (size_t)P, h->st);
     launch_copy(dst + EDL_SNAPSHOT_HEADER_BYTES + 4 * (size_t)P, h->v(), 4 * (size_t)P, h->st);
-    launch_copy(dst + EDL_SNAPSHOT_HEADER_BYTES + 8 * (size_t)P, h->running(), 4 * (size_t)R, h->st);
+    size_t at = EDL_SNAPSHOT_HEADER_BYTES + 8 * (size_t)P;
+    if (h->adam()) { launch_copy(dst + at, h->s2(), 4 * (size_t)P, h->st); at += 4 * (size_t)P; }
+    launch_copy(dst + at, h->running(), 4 * (size_t)R, h->st);
     HIP_TRY(hipGetLastError());
     if (out_written) *out_written = need;
     return EDL_OK;
@@ -771,7 +804,7 @@ int32_t edl_snapshot(edl_handle* h, void* dev_dst, size_t cap, size_t* out_writt
 int32_t edl_restore(edl_handle* h, const void* dev_src, size_t len) {
     if (!h || !dev_src) { set_error("null argument"); return EDL_EINVAL; }
     const int64_t P = h->g.P, R = h->g.R;
-    const size_t need = EDL_SNAPSHOT_HEADER_BYTES + 4 * (size_t)(2 * P + R);
+    const size_t need = EDL_SNAPSHOT_HEADER_BYTES + 4 * (size_t)h->state_floats();
     if (len < need) { set_error("snapshot image of %zu bytes is shorter than %zu", len, need); return EDL_ERANGE; }
     SnapshotHeader sh;
     HIP_TRY(hipMemcpyAsync(&sh, dev_src, sizeof(sh), hipMemcpyDeviceToHost, h->st));
@@ -779,10 +812,13 @@ int32_t edl_restore(edl_handle* h, const void* dev_src, size_t len) {
     if (sh.magic != EDL_SNAPSHOT_MAGIC || sh.version != 1) { set_error("not a snapshot image"); return EDL_EINVAL; }
     if (sh.P != P || sh.R != R || (int32_t)sh.model != h->cfg.model) { set_error("snapshot is of another model (P=%lld, R=%lld)", (long long)sh.P, (long long)sh.R); return EDL_EINVAL; }
     if (sh.N != h->cfg.N || sh.B != h->cfg.B) { set_error("snapshot is of a job with N=%lld B=%lld", (long long)sh.N, (long long)sh.B); return EDL_EINVAL; }
+    if ((int32_t)sh.optimizer != h->cfg.optimizer) { set_error("snapshot is of a job with optimizer %u", sh.optimizer); return EDL_EINVAL; }
     const char* src = (const char*)dev_src;
     launch_copy(h->w(), src + EDL_SNAPSHOT_HEADER_BYTES, 4 * (size_t)P, h->st);
     launch_copy(h->v(), src + EDL_SNAPSHOT_HEADER_BYTES + 4 * (size_t)P, 4 * (size_t)P, h->st);
-    launch_copy(h->running(), src + EDL_SNAPSHOT_HEADER_BYTES + 8 * (size_t)P, 4 * (size_t)R, h->st);
+    size_t at = EDL_SNAPSHOT_HEADER_BYTES + 8 * (size_t)P;
+    if (h->adam()) { launch_copy(h->s2(), src + at, 4 * (size_t)P, h->st); at += 4 * (size_t)P; }
+    launch_copy(h->running(), src + at, 4 * (size_t)R, h->st);
     HIP_TRY(hipGetLastError());
     h->seed = sh.seed;                      // job meta-data travels with the model
     h->prog.step = sh.step; h->prog.epoch = sh.epoch; h->prog.step_in_epoch = sh.step_in_epoch;
@@ -806,6 +842,10 @@ static int d2h(edl_handle* h, float* dst, const float* src, int64_t n) {
 
 int32_t edl_get_params(edl_handle* h, float* host_dst) { return h ? d2h(h, host_dst, h->w(), h->g.P) : EDL_EINVAL; }
 int32_t edl_get_momentum(edl_handle* h, float* host_dst) { return h ? d2h(h, host_dst, h->v(), h->g.P) : EDL_EINVAL; }
+int32_t edl_get_second_moment(edl_handle* h, float* host_dst) {
+    if (!h || !h->adam()) { set_error("not an Adam job"); return EDL_EINVAL; }
+    return d2h(h, host_dst, h->s2(), h->g.P);
+}
 int32_t edl_get_running(edl_handle* h, float* host_dst) { return h ? d2h(h, host_dst, h->running(), h->g.R) : EDL_EINVAL; }
 int32_t edl_get_grad(edl_handle* h, int32_t k, float* host_dst) {
     if (!h || k < 0 || k >= h->cfg.p_max) { set_error("gradient buffer %d outside [0,p_max)", k); return EDL_EINVAL; }
@@ -995,6 +1035,14 @@ int32_t edl_set_momentum(edl_handle* h, const float* host_src) {
     return EDL_OK;
 }
 
+int32_t edl_set_second_moment(edl_handle* h, const float* host_src) {
+    if (!h || !host_src) { set_error("null argument"); return EDL_EINVAL; }
+    if (!h->adam()) { set_error("not an Adam job"); return EDL_EINVAL; }
+    HIP_TRY(hipMemcpyAsync(h->s2(), host_src, sizeof(float) * (size_t)h->g.P, hipMemcpyHostToDevice, h->st));
+    HIP_TRY(hipStreamSynchronize(h->st));
+    return EDL_OK;
+}
+
 int32_t edl_shutdown(edl_handle* h) {
     if (!h) { set_error("null handle"); return EDL_EINVAL; }
     (void)hipStreamSynchronize(h->st);
@@ -1041,6 +1089,32 @@ int32_t edl_average_update(int32_t p, const float* const* dev_grads, float* dev_
     }
     if (bits & 15) { set_error("pointers must be 16-byte aligned"); return EDL_EINVAL; }
     launch_average_update(p, gp, dev_w, dev_v, dev_w16, P, lr, momentum, wd, (hipStream_t)hip_stream);
+    HIP_TRY(hipGetLastError());
+    return EDL_OK;
+}
+
+int32_t edl_adam_update(int32_t p, const float* const* dev_grads, const float* shares, float* dev_w, float* dev_m,
+                        float* dev_s, uint16_t* dev_w16, int64_t P, float lr, float beta1, float beta2, float eps,
+                        float wd, int64_t t, void* hip_stream) {
+    if (!dev_grads || !dev_w || !dev_m || !dev_s) { set_error("null argument"); return EDL_EINVAL; }
+    if (p <= 0 || p > kMaxP) { set_error("p=%d outside [1,%d]", p, kMaxP); return EDL_EINVAL; }
+    if (P < 0 || t < 1) { set_error("negative P or t < 1"); return EDL_EINVAL; }
+    if (!(beta1 >= 0.f && beta1 < 1.f && beta2 >= 0.f && beta2 < 1.f && eps >= 0.f)) { set_error("betas must lie in [0,1), eps >= 0"); return EDL_EINVAL; }
+    if (P == 0) return EDL_OK;
+    GradPtrs gp = {};
+    ShardShares sh = {};
+    uintptr_t bits = (uintptr_t)dev_w | (uintptr_t)dev_m | (uintptr_t)dev_s | (uintptr_t)dev_w16;
+    for (int k = 0; k < p; ++k) {
+        if (!dev_grads[k]) { set_error("gradient pointer %d is NULL", k); return EDL_EINVAL; }
+        gp.g[k] = dev_grads[k];
+        bits |= (uintptr_t)dev_grads[k];
+        if (shares) sh.share[k] = shares[k];
+    }
+    if (bits & 15) { set_error("pointers must be 16-byte aligned"); return EDL_EINVAL; }
+    float c1, c2;
+    adam_corrections(beta1, beta2, t, &c1, &c2);
+    launch_adam_update(p, gp, shares ? &sh : nullptr, dev_w, dev_m, dev_s, dev_w16, P, lr, beta1, beta2, eps, wd, c1, c2,
+                       (hipStream_t)hip_stream);
     HIP_TRY(hipGetLastError());
     return EDL_OK;
 }

@@ -149,6 +149,105 @@ void launch_weighted_update(int np, const GradPtrs& grads, const ShardShares& sh
 }
 
 // ---------------------------------------------------------------------------
+// Adam on the aggregated gradient (the optimizer of the usage example in
+// section 3.2; steps of Algorithm 1 of Kingma & Ba):
+//   g = aggregate + wd*w ; m = b1*m + (1-b1)*g ; s = b2*s + (1-b2)*g*g ;
+//   w = w - lr * (m*c1) / (sqrt(s*c2) + eps) ; w16 = bf16(w)
+// with c1 = 1/(1-b1^t), c2 = 1/(1-b2^t) formed by the host.  p+3 read streams,
+// 3 (+1) write streams, one 16-byte vector per lane per stream.  NP > 0 fixes p
+// at compile time (all p loads in flight); WEIGHTED takes sum_k share[k]*G_k
+// instead of the mean.
+// ---------------------------------------------------------------------------
+struct AdamCoef { float lr, b1, b2, eps, wd, c1, c2; };
+
+__device__ __forceinline__ void adam_one(float g, float& w, float& m, float& s, const AdamCoef& a) {
+    g += a.wd * w;
+    m = a.b1 * m + (1.0f - a.b1) * g;
+    s = a.b2 * s + (1.0f - a.b2) * (g * g);
+    w -= a.lr * (m * a.c1) / (sqrtf(s * a.c2) + a.eps);
+}
+
+template <int NP, bool WEIGHTED, bool SHADOW>
+__global__ __launch_bounds__(256) void adam_update_kernel(GradPtrs gp, ShardShares sh, int p, float* __restrict__ w,
+                                                          float* __restrict__ m, float* __restrict__ s,
+                                                          uint16_t* __restrict__ w16, int64_t nvec, int64_t P, AdamCoef a) {
+    const int np = NP > 0 ? NP : p;
+    const float inv_p = 1.0f / (float)np;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < nvec) {
+        float4 wi = reinterpret_cast<float4*>(w)[i];
+        float4 mi = reinterpret_cast<float4*>(m)[i];
+        float4 si = reinterpret_cast<float4*>(s)[i];
+        float4 g = reinterpret_cast<const float4*>(gp.g[0])[i];
+        if (WEIGHTED) { g.x *= sh.share[0]; g.y *= sh.share[0]; g.z *= sh.share[0]; g.w *= sh.share[0]; }
+        if (NP > 0) {
+            float4 t[NP > 1 ? NP - 1 : 1];
+            #pragma unroll
+            for (int k = 1; k < NP; ++k) t[k - 1] = reinterpret_cast<const float4*>(gp.g[k])[i];
+            #pragma unroll
+            for (int k = 1; k < NP; ++k) {
+                const float c = WEIGHTED ? sh.share[k] : 1.0f;
+                g.x += c * t[k - 1].x; g.y += c * t[k - 1].y; g.z += c * t[k - 1].z; g.w += c * t[k - 1].w;
+            }
+        } else {
+            for (int k = 1; k < np; ++k) {
+                const float4 t = reinterpret_cast<const float4*>(gp.g[k])[i];
+                const float c = WEIGHTED ? sh.share[k] : 1.0f;
+                g.x += c * t.x; g.y += c * t.y; g.z += c * t.z; g.w += c * t.w;
+            }
+        }
+        if (!WEIGHTED) { g.x *= inv_p; g.y *= inv_p; g.z *= inv_p; g.w *= inv_p; }
+        adam_one(g.x, wi.x, mi.x, si.x, a);
+        adam_one(g.y, wi.y, mi.y, si.y, a);
+        adam_one(g.z, wi.z, mi.z, si.z, a);
+        adam_one(g.w, wi.w, mi.w, si.w, a);
+        reinterpret_cast<float4*>(m)[i] = mi;
+        reinterpret_cast<float4*>(s)[i] = si;
+        reinterpret_cast<float4*>(w)[i] = wi;
+        if (SHADOW) reinterpret_cast<uint2*>(w16)[i] = make_uint2(pack2_bf16(wi.x, wi.y), pack2_bf16(wi.z, wi.w));
+    }
+    // ragged tail (P not a multiple of 4): the first few lanes of block 0
+    if (blockIdx.x == 0 && threadIdx.x < (unsigned)(P - nvec * 4)) {
+        const int64_t j = nvec * 4 + threadIdx.x;
+        float g = gp.g[0][j] * (WEIGHTED ? sh.share[0] : 1.0f);
+        for (int k = 1; k < np; ++k) g += gp.g[k][j] * (WEIGHTED ? sh.share[k] : 1.0f);
+        if (!WEIGHTED) g *= inv_p;
+        float wj = w[j], mj = m[j], sj = s[j];
+        adam_one(g, wj, mj, sj, a);
+        m[j] = mj; s[j] = sj; w[j] = wj;
+        if (SHADOW) w16[j] = f32_to_bf16(wj);
+    }
+}
+
+template <int NP, bool WEIGHTED>
+static void launch_adam_t(int grid, const GradPtrs& grads, const ShardShares& sh, int p, float* w, float* m, float* s,
+                          uint16_t* w16, int64_t nvec, int64_t P, const AdamCoef& a, hipStream_t st) {
+    if (w16) hipLaunchKernelGGL((adam_update_kernel<NP, WEIGHTED, true>), dim3(grid), dim3(256), 0, st, grads, sh, p, w, m, s, w16, nvec, P, a);
+    else hipLaunchKernelGGL((adam_update_kernel<NP, WEIGHTED, false>), dim3(grid), dim3(256), 0, st, grads, sh, p, w, m, s, w16, nvec, P, a);
+}
+
+void launch_adam_update(int p, const GradPtrs& grads, const ShardShares* shares, float* w, float* m, float* s, uint16_t* w16,
+                        int64_t P, float lr, float beta1, float beta2, float eps, float wd, float c1, float c2, hipStream_t st) {
+    const int64_t nvec = P / 4;
+    const int grid = (int)std::max<int64_t>(1, (nvec + 255) / 256);
+    const AdamCoef a = {lr, beta1, beta2, eps, wd, c1, c2};
+    // p gradient reads + w, m, s read and written (+ the bf16 copy)
+    ProfScope ps("adam_update", 0.0, (4.0 * p + 24.0 + (w16 ? 2.0 : 0.0)) * (double)P, st);
+    const ShardShares none = {};
+    if (shares) {
+        launch_adam_t<0, true>(grid, grads, *shares, p, w, m, s, w16, nvec, P, a, st);
+        return;
+    }
+    switch (p) {
+        case 1: launch_adam_t<1, false>(grid, grads, none, p, w, m, s, w16, nvec, P, a, st); break;
+        case 2: launch_adam_t<2, false>(grid, grads, none, p, w, m, s, w16, nvec, P, a, st); break;
+        case 4: launch_adam_t<4, false>(grid, grads, none, p, w, m, s, w16, nvec, P, a, st); break;
+        case 8: launch_adam_t<8, false>(grid, grads, none, p, w, m, s, w16, nvec, P, a, st); break;
+        default: launch_adam_t<0, false>(grid, grads, none, p, w, m, s, w16, nvec, P, a, st); break;
+    }
+}
+
+// ---------------------------------------------------------------------------
 // plain copy (snapshot / restore): 16-byte vectors when source, destination
 // and length allow it (the large state arrays do), else 4-byte or 1-byte units
 // ---------------------------------------------------------------------------

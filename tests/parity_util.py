@@ -62,7 +62,8 @@ DEFAULT_HWC = {"mlp": (1, 1, 784, 10), "resnet20": (32, 32, 3, 10), "resnet50": 
 
 
 def run_parity(model, dtype, N, B, schedule, seed=0, data_seed=1, lr=0.1, momentum=0.9, wd=5e-4,
-               H=0, W=0, C=0, classes=0, arch=(), emulate=None, check_every_step=True, verbose=True):
+               H=0, W=0, C=0, classes=0, arch=(), emulate=None, check_every_step=True, verbose=True,
+               optimizer="momentum", beta2=0.999, eps=1e-8):
     """schedule: list of p, one per step.  Returns dict of worst errors."""
     import torch
     import paper_1909_11985_amd as E
@@ -73,18 +74,20 @@ def run_parity(model, dtype, N, B, schedule, seed=0, data_seed=1, lr=0.1, moment
     x, y = synth_inputs.dataset(data_seed, N, hh, ww, cc, kk)
     p_max = max(schedule)
     cfg = make_config(model, dtype=dtype, N=N, B=B, p_max=p_max, max_shard=B // min(schedule), lr=lr,
-                      momentum=momentum, wd=wd, H=H, W=W, C_=C, classes=classes, arch=arch)
+                      momentum=momentum, wd=wd, H=H, W=W, C_=C, classes=classes, arch=arch,
+                      optimizer=optimizer, beta2=beta2, eps=eps)
     job = E.Job(cfg, seed)
     job.bind_dataset(torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda())
     if emulate is None:
         emulate = dtype == "bf16"
     orc = O.Oracle(model, seed, N, B, lr=lr, momentum=momentum, wd=wd, emulate_bf16=emulate,
-                   graph_kwargs=oracle_kwargs(model, H, W, C, classes, arch), dtype_code=E.DTYPES[dtype])
+                   graph_kwargs=oracle_kwargs(model, H, W, C, classes, arch), dtype_code=E.DTYPES[dtype],
+                   optimizer=optimizer, beta2=beta2, eps=eps)
     table = E.edl_tensor_table(cfg)
     assert [(n, o, int(np.prod(s)), f) for n, o, s, f in orc.graph.tensors] == table
     w0 = job.params()
     assert relerr(w0, orc.w) < 3e-7, "initial models differ"
-    res = dict(grad=0.0, grad_whole=0.0, param=0.0, param_whole=0.0, loss=0.0, momentum=0.0, running=0.0)
+    res = dict(grad=0.0, grad_whole=0.0, param=0.0, param_whole=0.0, loss=0.0, momentum=0.0, second=0.0, running=0.0)
     for t, p in enumerate(schedule):
         idx, off = job.shard(B, p, *job.progress()[1:])
         io, oo = O.shard(seed, N, B, p, orc.epoch, orc.step_in_epoch)
@@ -103,6 +106,8 @@ def run_parity(model, dtype, N, B, schedule, seed=0, data_seed=1, lr=0.1, moment
             res["param"] = max(res["param"], e)
             res["param_whole"] = max(res["param_whole"], whole)
             res["momentum"] = max(res["momentum"], relerr(job.momentum(), orc.v))
+            if optimizer == "adam":
+                res["second"] = max(res["second"], relerr(job.second_moment(), orc.s))
             if orc.graph.R:
                 res["running"] = max(res["running"], relerr(job.running(), orc.running))
             if verbose:

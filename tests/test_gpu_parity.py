@@ -45,6 +45,78 @@ def test_average_update_matches_oracle(p, P, shadow):
         np.testing.assert_array_equal(got.view(np.uint32), want.view(np.uint32))
 
 
+F32 = lambda v: float(np.float32(v))       # a coefficient as the library's float32 configuration holds it
+
+
+def _host_data(job):
+    """The data set bound to a job, as host arrays."""
+    x, y = job._data
+    return x.cpu().numpy(), y.cpu().numpy()
+
+
+def _cfg_geom(kw):
+    """Geometry keywords of the parity helpers -> those of make_config."""
+    out = dict(kw)
+    if "C" in out:
+        out["C_"] = out.pop("C")
+    return out
+
+
+@pytest.mark.parametrize("p,shares", [(1, None), (2, None), (3, None), (4, None), (8, None), (3, (0.5, 0.125, 0.375)),
+                                      (2, (0.75, 0.25))])
+@pytest.mark.parametrize("P", [4096 * 5, 100003, 3])
+@pytest.mark.parametrize("shadow", [False, True])
+def test_adam_update_matches_oracle(p, shares, P, shadow):
+    """Four consecutive Adam updates (t = 1..4, fresh gradients each time) on caller buffers."""
+    torch = _torch()
+    import paper_1909_11985_amd as E
+    w = synth_inputs.vector(4, P)
+    dw = torch.from_numpy(w).cuda()
+    dm_dev, ds = torch.zeros(P, device="cuda"), torch.zeros(P, device="cuda")
+    d16 = torch.zeros(P, dtype=torch.bfloat16, device="cuda") if shadow else None
+    lr, b1, b2, eps, wd = F32(0.01), F32(0.9), F32(0.999), F32(1e-8), F32(5e-4)
+    ow, om, os_ = w.astype(np.float64), np.zeros(P), np.zeros(P)
+    # Adam divides by the gradient's own magnitude, so where the p gradients cancel, the float32 rounding of
+    # their sum (a few units in the last place of sum_k |G_k|) is not small against the sum, and the weight
+    # moves differently by up to lr * that error / (sqrt(shat) + eps).  The bound below carries this through
+    # the first moment; everywhere else it is a few float32 roundings.
+    u = 2.0 ** -24
+    dm, bound = np.zeros(P), np.zeros(P)
+    for t in range(1, 5):
+        grads = synth_inputs.gradient_buffers(10 + t, p, P)
+        dg = [torch.from_numpy(g).cuda() for g in grads]
+        E.edl_adam_update(dg, dw, dm_dev, ds, d16, lr, b1, b2, eps, wd, t, shares=shares)
+        wts = [1.0 / p] * p if shares is None else list(shares)
+        ow, om, os_ = O.adam_update(ow, om, os_, [g.astype(np.float64) for g in grads], t, lr, b1, b2, eps, wd,
+                                    weights=None if shares is None else wts)
+        torch.cuda.synchronize()
+        mag = sum(wk * np.abs(g.astype(np.float64)) for wk, g in zip(wts, grads)) + wd * np.abs(ow)
+        dm = b1 * dm + (1 - b1) * (p + 3) * u * mag
+        shat = os_ / (1 - b2 ** t)
+        bound += lr * (dm / (1 - b1 ** t)) / (np.sqrt(shat) + eps) + 8 * u * lr + 2 * u * np.abs(ow)
+    gw, gm, gs = dw.cpu().numpy(), dm_dev.cpu().numpy(), ds.cpu().numpy()
+    assert np.all(np.abs(gm - om) <= 2 * dm + 1e-12)
+    np.testing.assert_allclose(gs, os_, rtol=1e-5, atol=1e-12)
+    assert np.all(np.abs(gw - ow) <= 2 * bound), float(np.max(np.abs(gw - ow) / bound))
+    assert np.linalg.norm(gw - ow) <= 1e-6 * np.linalg.norm(ow)
+    if shadow:
+        want = O.round_bf16(gw).astype(np.float32)
+        np.testing.assert_array_equal(d16.float().cpu().numpy().view(np.uint32), want.view(np.uint32))
+
+
+def test_adam_update_rejects_bad_arguments():
+    torch = _torch()
+    import paper_1909_11985_amd as E
+    w = torch.zeros(64, device="cuda")
+    for kw in [dict(t=0), dict(b1=1.0), dict(b2=-0.1), dict(eps=-1.0)]:
+        a = dict(lr=0.1, b1=0.9, b2=0.999, eps=1e-8, wd=0.0, t=1)
+        a.update(kw)
+        with pytest.raises(E.EdlError):
+            E.edl_adam_update([w], w, w, w, None, a["lr"], a["b1"], a["b2"], a["eps"], a["wd"], a["t"])
+    with pytest.raises(E.EdlError):
+        E.edl_adam_update([w[1:]], w[1:], w[1:], w[1:], None, 0.1, 0.9, 0.999, 1e-8, 0.0, 1)      # misaligned
+
+
 def test_average_update_rejects_bad_arguments():
     torch = _torch()
     import paper_1909_11985_amd as E
@@ -378,6 +450,75 @@ def test_a_tail_batch_of_the_pipeline_trains():
         assert abs(loss - lo) < 1e-5 * max(abs(lo), 1.0)
     assert off.tolist() == [0, 6, 12, 12]
     assert relerr(job.params(), orc.w) < TOL["f32"]
+
+
+# ---------------------------------------------------------------- Adam jobs
+@pytest.mark.parametrize("model", ["mlp", "resnet20", "vgg16"])
+def test_free_running_adam_fp32(model):
+    """A whole job under Adam with p changing every step: gradients, both moments, parameters and running
+    statistics against the oracle's."""
+    r = run_parity(model, "f32", N=48, B=24, schedule=[2, 1, 4, 3], lr=F32(0.001), momentum=F32(0.9), wd=F32(5e-4),
+                   optimizer="adam", beta2=F32(0.999), eps=F32(1e-8), verbose=False, **TINY[model])
+    assert r["grad"] < TOL["f32"] and r["momentum"] < TOL["f32"] and r["second"] < 2 * TOL["f32"], r
+    assert r["param"] < TOL["f32"] and r["running"] < TOL["f32"] and r["loss"] < 1e-5, r
+    assert relerr(r["job"].params(), O.he_init(r["oracle"].graph, 0)) > 1e-3        # the model did move
+
+
+def test_adam_update_inside_a_bf16_job():
+    """ResNet-50 (reduced) in bf16 under Adam: the gradients of the two sides differ by bf16 roundings, so the
+    update is checked by itself - the oracle's formula on the library's own gradient buffers - and the
+    losses of the free-running job against the oracle's."""
+    torch = _torch()
+    kw = TINY["resnet50"]
+    lr, b1, b2, eps, wd = F32(0.001), F32(0.9), F32(0.999), F32(1e-6), F32(5e-4)
+    r = run_parity("resnet50", "bf16", N=96, B=24, schedule=[1, 3], lr=lr, momentum=b1, wd=wd, optimizer="adam",
+                   beta2=b2, eps=eps, verbose=False, **kw)
+    job, orc = r["job"], r["oracle"]
+    w, m, s2 = (a.astype(np.float64) for a in (job.params(), job.momentum(), job.second_moment()))
+    for t, p in [(3, 2), (4, 3)]:
+        idx, off = job.shard(24, p, *job.progress()[1:])
+        loss = job.gradients(p, idx, off)
+        G = [job.grad(k).astype(np.float64) for k in range(p)]
+        job.apply(p)
+        w, m, s2 = O.adam_update(w, m, s2, G, t, lr, b1, b2, eps, wd)
+        assert relerr(job.momentum(), m) < 1e-5 and relerr(job.second_moment(), s2) < 1e-5
+        assert relerr(job.params(), w) < 1e-6
+        w, m, s2 = (a.astype(np.float64) for a in (job.params(), job.momentum(), job.second_moment()))
+        lo = orc.step(p, *_host_data(job))
+        assert abs(loss - lo) / lo < 0.05, (loss, lo)
+
+
+def test_adam_snapshot_bytes_and_resume():
+    torch = _torch()
+    r = run_parity("resnet20", "f32", N=48, B=24, schedule=[2, 4, 1], lr=F32(0.001), optimizer="adam", verbose=False,
+                   **TINY["resnet20"])
+    job, orc = r["job"], r["oracle"]
+    snap = job.snapshot()
+    torch.cuda.synchronize()
+    blob = snap.cpu().numpy().tobytes()
+    ob = orc.snapshot()
+    P, R = job.P, job.R
+    hb = O.SNAPSHOT_HEADER_BYTES
+    assert len(blob) == len(ob) == hb + 4 * (3 * P + R)
+    assert blob[:104] == ob[:104]                                 # header incl. optimizer id, beta2, eps
+    assert np.array_equal(np.frombuffer(blob, np.float32, P, hb + 4 * P), job.momentum())
+    assert np.array_equal(np.frombuffer(blob, np.float32, P, hb + 8 * P), job.second_moment())
+    assert np.array_equal(np.frombuffer(blob, np.float32, R, hb + 12 * P), job.running())
+    import paper_1909_11985_amd as E
+    from paper_1909_11985_amd.binding import make_config
+    joiner = E.Job(job.cfg, 99)
+    joiner.bind_dataset(*job._data)
+    joiner.restore(snap)
+    for p in (4, 1, 2):
+        assert job.step(p) == joiner.step(p)
+    assert np.array_equal(job.params(), joiner.params()) and np.array_equal(job.second_moment(), joiner.second_moment())
+    # a momentum job refuses the image
+    other = E.Job(make_config("resnet20", N=48, B=24, p_max=4, max_shard=24, **_cfg_geom(TINY["resnet20"])), 0)
+    with pytest.raises(E.EdlError) as ei:
+        other.restore(snap)
+    assert ei.value.code == -1
+    with pytest.raises(E.EdlError):
+        other.second_moment()
 
 
 # ---------------------------------------------------------------- snapshot

@@ -70,6 +70,22 @@ def test_parameter_layout_and_init_match_the_oracle(E, model):
         assert np.mean(w.astype(np.float64) != wo) < 1e-5
 
 
+def test_adam_configuration_sizes_and_checks(E):
+    from paper_1909_11985_amd.binding import make_config
+    a = E.edl_query(make_config("resnet20", N=64, B=32, p_max=2))
+    b = E.edl_query(make_config("resnet20", N=64, B=32, p_max=2, optimizer="adam"))
+    assert a.second_off == -1 and b.second_off == b.momentum_off + (b.running_off - b.momentum_off) // 2
+    assert b.second_off % 256 == 0 and b.running_off - b.second_off >= 4 * b.P
+    assert b.snapshot_bytes == a.snapshot_bytes + 4 * a.P and b.arena_bytes >= a.arena_bytes + 4 * a.P
+    for kw in [dict(momentum=1.0), dict(beta2=1.0), dict(beta2=-0.5), dict(eps=-1e-8), dict(optimizer=7)]:
+        base = dict(model="mlp", N=64, B=32, p_max=2, optimizer="adam")
+        base.update(kw)
+        with pytest.raises(E.EdlError) as ei:
+            E.edl_query(make_config(**base))
+        assert ei.value.code == -1, kw
+    E.edl_query(make_config("mlp", N=64, B=32, p_max=2, momentum=1.5))      # momentum-SGD does not restrict it
+
+
 def test_query_rejects_bad_configurations(E):
     from paper_1909_11985_amd.binding import make_config
     for kw, code in [(dict(N=60, B=32), -2), (dict(p_max=17), -1), (dict(p_max=0), -1), (dict(model=9), -1), (dict(dtype=5), -1)]:
