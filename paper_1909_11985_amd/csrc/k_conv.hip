@@ -47,6 +47,12 @@
 #define EDL_FRAG_AHEAD 1
 #endif
 
+// 1: the vector kernels of forward / dgrad load their tiles from global memory straight into LDS
+// (16 bytes per lane, no register staging, PF + 1 LDS stages); 0: through registers, two stages
+#ifndef EDL_DIRECT_LDS
+#define EDL_DIRECT_LDS 1
+#endif
+
 namespace edl {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
@@ -91,6 +97,7 @@ struct ConvArgs {
     // the same for d = pixels per image and d = pixels per image row of the row index's pixel grid
     // (output pixels in the forward pass, the residue class's input pixels in dgrad), and for the tile grid
     unsigned long long magic_hw, magic_w, magic_gx, magic_gy;
+    int stride_shift;                  // dgrad vector path: log2 of the stride (a power of two there)
     // Tile grid (gx row tiles, gy column tiles, gz cuts of the reduction), launched
     // as gx*gy*gz workgroups in one dimension.  The hardware hands consecutive
     // workgroups to the eight dies in turn and each die has its own L2, so with
@@ -136,6 +143,27 @@ constexpr unsigned kOutOfRange = 0x80000000u;   // operands are smaller than 2 G
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned bytes) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
 }
+// The same load, landing in LDS instead of registers: lane L's 16 bytes go to LDS byte address
+// lds_wave_base + 16*L (lds_wave_base is wave-uniform and travels in M0); a lane whose offset is out of range
+// writes zeros.  The instruction is issued from inline assembly, so the compiler does not know of the
+// outstanding LDS write: the caller orders it against LDS reads with wait_vmcnt<> and a barrier, and no other
+// code of the kernel may use M0.
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ i32x4 make_rsrc_words(const void* p, unsigned bytes) {
+    const uint64_t a = (uint64_t)p;
+    const i32x4 r = {(int)(uint32_t)a, (int)((uint32_t)(a >> 32) & 0xffffu), (int)bytes, 0x00020000};
+    return r;
+}
+__device__ __forceinline__ void buffer_load16_to_lds(i32x4 rsrc, unsigned lds_wave_base, unsigned byte_offset) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :: "s"(lds_wave_base), "v"(byte_offset), "s"(rsrc) : "memory");
+}
+// waits until at most N of this wave's vector-memory loads are outstanding (they complete in order)
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
+
 __device__ __forceinline__ uint4 buffer_load16(__amdgpu_buffer_rsrc_t r, unsigned byte_offset) {
     const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, byte_offset, 0, 0);
     return make_uint4(v.x, v.y, v.z, v.w);
@@ -256,23 +284,18 @@ template <int MODE, typename T>
 __device__ __forceinline__ unsigned a_voffset(const ConvArgs& a, const RowCtx& c, int r, int s, int ch, int tap_off, bool in_k) {
     if (MODE == CONV_FWD) {
         const int h = c.h0 + r, w = c.w0 + s;
-        const bool ok = in_k && c.valid && (unsigned)h < (unsigned)a.H && (unsigned)w < (unsigned)a.W;
-        return ok ? (unsigned)((int)c.base + tap_off) * (unsigned)sizeof(T) : kOutOfRange;
+        const bool ok = in_k & c.valid & ((unsigned)h < (unsigned)a.H) & ((unsigned)w < (unsigned)a.W);
+        // the offset is formed unconditionally and pushed out of range by its top bit: a select between
+        // the two would be compiled into a predicated region, which splits the loop's basic block
+        return ((unsigned)((int)c.base + tap_off) * (unsigned)sizeof(T)) | (ok ? 0u : kOutOfRange);
     } else {
+        // no branch on the stride (the loop this runs in must stay one basic block): the vector path is taken
+        // for strides that are powers of two only.  Negative coordinates are discarded by `ok`.
         const int hn = c.h0 - r, wn = c.w0 - s;
-        int ho = hn, wo = wn;
-        bool on_grid = true;
-        if (a.stride == 2) {
-            ho = hn >> 1;
-            wo = wn >> 1;
-            on_grid = ((hn | wn) & 1) == 0;
-        } else if (a.stride != 1) {
-            ho = hn / a.stride;
-            wo = wn / a.stride;
-            on_grid = (ho * a.stride == hn) && (wo * a.stride == wn);
-        }
-        const bool ok = in_k && c.valid && (hn | wn) >= 0 && on_grid && ho < a.Ho && wo < a.Wo;
-        return ok ? (unsigned)((int)c.base + (ho * a.Wo + wo) * a.K + ch) * (unsigned)sizeof(T) : kOutOfRange;
+        const int ho = hn >> a.stride_shift, wo = wn >> a.stride_shift;
+        const bool on_grid = ((hn | wn) & (a.stride - 1)) == 0;
+        const bool ok = in_k & c.valid & ((hn | wn) >= 0) & on_grid & (ho < a.Ho) & (wo < a.Wo);
+        return ((unsigned)((int)c.base + (ho * a.Wo + wo) * a.K + ch) * (unsigned)sizeof(T)) | (ok ? 0u : kOutOfRange);
     }
 }
 
@@ -298,11 +321,10 @@ __device__ __forceinline__ int64_t out_row(const ConvArgs& a, int row) {
 // run-time choice between the two inside the loop would force a wait after
 // every load).
 template <typename T, int MODE, int WM, int WN, int TM, int TN, int BK, bool FAST, int PF>
-__global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
+__global__ __launch_bounds__(256, 2) void conv_igemm_kernel(ConvArgs a) {   // at least two waves per SIMD: 256 registers
     constexpr bool WG = MODE == CONV_WGRAD;
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
     constexpr int VEC = Elem<T>::VEC;
-    constexpr int LDK = BK + VEC;
     constexpr int KV = BK / VEC;                    // fwd/dgrad: vectors per tile row
     constexpr int KPD = sizeof(T) == 2 ? 2 : 1;     // wgrad: reduction elements per 32-bit word
     constexpr int KD = BK / KPD;                    // wgrad: words along the reduction
@@ -316,11 +338,19 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
     // LDS (ds_read_tr16_b64, see tr_frag); float32 wgrad keeps words [pixel][channel] read one by one
     constexpr bool WGT = WG && sizeof(T) == 2;
     constexpr bool FRAG_AHEAD = EDL_FRAG_AHEAD != 0 && TM * TN > 1;
+    // Tiles loaded straight into LDS: rows of BK elements without padding (RB = 64 or 128 bytes); a wave's load
+    // instruction fills 64 consecutive 16-byte slots (whole rows), and the slot of chunk c of row r is
+    // c ^ ((r / RPL) % KV) with RPL = rows per 256 bytes, which keeps the fragment reads conflict-free.
+    constexpr int RB = BK * (int)sizeof(T), RPL = RB > 256 ? 1 : 256 / RB;
+    constexpr bool DIRECT = EDL_DIRECT_LDS != 0 && FAST && !WG && TOT_A % 256 == 0 && TOT_B % 256 == 0 &&
+                            (RB == 64 || RB == 128);
+    constexpr int NST = DIRECT ? PF + 1 : 2;         // LDS stages
+    constexpr int LDK = DIRECT ? BK : BK + VEC;
     constexpr int A_STAGE = WGT ? BK * BM * 2 : WG ? KD * LDPA * 4 : BM * LDK * (int)sizeof(T);   // bytes per LDS stage
     constexpr int B_STAGE = WGT ? BK * BN * 2 : WG ? KD * LDPB * 4 : BN * LDK * (int)sizeof(T);
     // epilogue staging: the rows of one wave row, as float32
     constexpr int STAGE_ROWS = TM * 32, STAGE_LD = BN + 4;
-    constexpr int TILE_BYTES = 2 * (A_STAGE + B_STAGE);
+    constexpr int TILE_BYTES = NST * (A_STAGE + B_STAGE);
     constexpr int STAGE_BYTES = STAGE_ROWS * STAGE_LD * 4;
     constexpr int SMEM_BYTES = TILE_BYTES > STAGE_BYTES ? TILE_BYTES : STAGE_BYTES;
     static_assert(WM * WN == 4, "four waves per workgroup");
@@ -328,8 +358,8 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
     static_assert(!WG || KD == 32, "wgrad: four fragment groups of eight words");
 
     __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM_BYTES];
-    unsigned char* const As = smem;                  // [2] stages
-    unsigned char* const Bs = smem + 2 * A_STAGE;
+    unsigned char* const As = smem;                  // [NST] stages
+    unsigned char* const Bs = smem + NST * A_STAGE;
 
     const T* __restrict__ Ag = (const T*)a.A;
     const T* __restrict__ Bg = (const T*)a.B;
@@ -345,6 +375,11 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
 
     Vec16<T> ra[PF][NRA], rb[PF][NRB];   // PF register sets: the loads of the next PF tiles are in flight
     const __amdgpu_buffer_rsrc_t rsrcA = make_rsrc(a.A, a.bytesA), rsrcB = make_rsrc(a.B, a.bytesB);
+    const i32x4 wordsA = make_rsrc_words(a.A, a.bytesA), wordsB = make_rsrc_words(a.B, a.bytesB);
+    // LDS byte address of the 64 slots this wave's first load of a tile fills (DIRECT)
+    const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
+    const unsigned ldsA_wave = __builtin_amdgcn_readfirstlane(lds_base + wave * 1024);
+    const unsigned ldsB_wave = ldsA_wave + NST * A_STAGE;
 
     // ---- per-thread state of the gathers; advanced by BK after every tile ------
     RowCtx rowA[WG ? 1 : ITER_A];
@@ -358,7 +393,10 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
     int dn = 0, dho = 0, dwo = 0;    // wgrad: BK pixels as (images, rows, columns)
     if (!WG) {
         const int inner = MODE == CONV_FWD ? a.C : a.K;
-        kcur = kbeg + (tid % KV) * VEC;
+        // DIRECT: the lane fills slot tid % KV of its rows, which holds chunk slot ^ ((row / RPL) % KV); a lane's
+        // rows are 256 / KV apart, so this is the same chunk for all of them
+        const int chunk = DIRECT ? ((tid % KV) ^ ((tid / KV / RPL) % KV)) : tid % KV;
+        kcur = kbeg + chunk * VEC;
         const int tap = FAST ? fast_div(kcur, a.magic_inner) : kcur / inner;
         tc = kcur - tap * inner;
         if (MODE == CONV_FWD) {
@@ -404,7 +442,34 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
     }
 
     auto load_tiles = [&](int set) {
-        if (!WG) {
+        if (DIRECT) {
+            // `set` is the LDS stage
+            const bool in_k = kcur < kend;
+            #pragma unroll
+            for (int it = 0; it < ITER_A; ++it)
+                buffer_load16_to_lds(wordsA, ldsA_wave + set * A_STAGE + it * 4096,
+                                     a_voffset<MODE, T>(a, rowA[it], tr, ts, tc, tap_off, in_k));
+            #pragma unroll
+            for (int it = 0; it < ITER_B; ++it) {
+                const int boff = MODE == CONV_FWD ? kcur : tap_off;
+                buffer_load16_to_lds(wordsB, ldsB_wave + set * B_STAGE + it * 4096,
+                                     (okB[it] && in_k) ? (unsigned)((int)offB[it] + boff) * (unsigned)sizeof(T) : kOutOfRange);
+            }
+            const int inner = MODE == CONV_FWD ? a.C : a.K;
+            kcur += BK;
+            const int tap = fast_div(kcur, a.magic_inner);
+            tc = kcur - tap * inner;
+            const int ri = fast_div(tap, a.magic_taps);
+            if (MODE == CONV_FWD) {
+                tr = ri;
+                ts = tap - ri * a.S;
+                tap_off = (tr * a.W + ts) * a.C + tc;
+            } else {
+                tr = a.r0 + ri * a.stride;
+                ts = a.s0 + (tap - ri * a.ns) * a.stride;
+                tap_off = (tr * a.S + ts) * a.K + tc;
+            }
+        } else if (!WG) {
             const bool in_k = kcur < kend;
             #pragma unroll
             for (int it = 0; it < ITER_A; ++it) {
@@ -614,68 +679,98 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
     // Loads past the end of the reduction are issued too: their offsets are out of
     // range, so they touch no memory and return zeros, and the number of loads in
     // flight at every wait is then a compile-time constant.
-    #pragma unroll
-    for (int u = 0; u < PF; ++u) load_tiles(u);
-    store_tiles(0, 0);
-    __syncthreads();
-    for (int kt = 0; kt < nk; kt += PF) {
-        #pragma unroll
-        for (int u = 0; u < PF; ++u) {
-            const int k = kt + u;
-            if (k >= nk) break;
-            const int buf = PF == 1 ? (k & 1) : (u & 1);
-            load_tiles(u);
-            constexpr int NG = WG ? 4 : BK / (2 * VEC);   // fragment groups per tile
-            auto read_frags = [&](int g, uint4 (&fa)[TM], uint4 (&fb)[TN]) {
-                if (!WG) {
-                    constexpr int KG = 2 * VEC;  // reduction elements one fragment pair covers
-                    const T* const Ab = reinterpret_cast<const T*>(As + buf * A_STAGE);
-                    const T* const Bb = reinterpret_cast<const T*>(Bs + buf * B_STAGE);
-                    #pragma unroll
-                    for (int i = 0; i < TM; ++i)
-                        fa[i] = *reinterpret_cast<const uint4*>(&Ab[((wm * TM + i) * 32 + (lane & 31)) * LDK + g * KG + (lane >> 5) * VEC]);
-                    #pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        fb[j] = *reinterpret_cast<const uint4*>(&Bb[((wn * TN + j) * 32 + (lane & 31)) * LDK + g * KG + (lane >> 5) * VEC]);
-                } else if (WGT) {
-                    const bf16_t* const Ab = reinterpret_cast<const bf16_t*>(As + buf * A_STAGE);
-                    const bf16_t* const Bb = reinterpret_cast<const bf16_t*>(Bs + buf * B_STAGE);
-                    #pragma unroll
-                    for (int i = 0; i < TM; ++i) fa[i] = tr_frag<BM>(Ab, (wm * TM + i) * 32, g * 16, lane);
-                    #pragma unroll
-                    for (int j = 0; j < TN; ++j) fb[j] = tr_frag<BN>(Bb, (wn * TN + j) * 32, g * 16, lane);
-                } else {
-                    const uint32_t* const Ab = reinterpret_cast<const uint32_t*>(As + buf * A_STAGE) + (g * 8 + (lane >> 5) * 4) * LDPA + (lane & 31);
-                    const uint32_t* const Bb = reinterpret_cast<const uint32_t*>(Bs + buf * B_STAGE) + (g * 8 + (lane >> 5) * 4) * LDPB + (lane & 31);
-                    #pragma unroll
-                    for (int i = 0; i < TM; ++i) {
-                        const uint32_t* q = Ab + (wm * TM + i) * 32;
-                        fa[i] = make_uint4(q[0], q[LDPA], q[2 * LDPA], q[3 * LDPA]);
-                    }
-                    #pragma unroll
-                    for (int j = 0; j < TN; ++j) {
-                        const uint32_t* q = Bb + (wn * TN + j) * 32;
-                        fb[j] = make_uint4(q[0], q[LDPB], q[2 * LDPB], q[3 * LDPB]);
-                    }
-                }
-            };
-            // The fragments of group g+1 are read from LDS before the MFMAs of group g are issued
-            // (the fences keep the compiler from sinking the reads back to their first use), so the
-            // LDS latency of one group hides behind the matrix work of the one before.
-            uint4 fa[2][TM], fb[2][TN];
-            read_frags(0, fa[0], fb[0]);
-            #pragma unroll
-            for (int g = 0; g < NG; ++g) {
-                if (g + 1 < NG) read_frags(g + 1, fa[(g + 1) & 1], fb[(g + 1) & 1]);
-                if (FRAG_AHEAD) __builtin_amdgcn_sched_barrier(0);
+    // contraction of the tile in LDS stage `buf`
+    auto contract = [&](int buf) {
+        constexpr int NG = WG ? 4 : BK / (2 * VEC);   // fragment groups per tile
+        auto read_frags = [&](int g, uint4 (&fa)[TM], uint4 (&fb)[TN]) {
+            if (!WG) {
+                const T* const Ab = reinterpret_cast<const T*>(As + buf * A_STAGE);
+                const T* const Bb = reinterpret_cast<const T*>(Bs + buf * B_STAGE);
+                // chunk of the row this lane reads, and the slot the tile keeps it in
+                const int chunk = 2 * g + (lane >> 5);
+                const int slot = DIRECT ? (chunk ^ (((lane & 31) / RPL) % KV)) : chunk;
                 #pragma unroll
                 for (int i = 0; i < TM; ++i)
-                    #pragma unroll
-                    for (int j = 0; j < TN; ++j) Frag<T>::mma(fa[g & 1][i], fb[g & 1][j], acc[i][j]);
-                if (FRAG_AHEAD) __builtin_amdgcn_sched_barrier(0);
+                    fa[i] = *reinterpret_cast<const uint4*>(&Ab[((wm * TM + i) * 32 + (lane & 31)) * LDK + slot * VEC]);
+                #pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    fb[j] = *reinterpret_cast<const uint4*>(&Bb[((wn * TN + j) * 32 + (lane & 31)) * LDK + slot * VEC]);
+            } else if (WGT) {
+                const bf16_t* const Ab = reinterpret_cast<const bf16_t*>(As + buf * A_STAGE);
+                const bf16_t* const Bb = reinterpret_cast<const bf16_t*>(Bs + buf * B_STAGE);
+                #pragma unroll
+                for (int i = 0; i < TM; ++i) fa[i] = tr_frag<BM>(Ab, (wm * TM + i) * 32, g * 16, lane);
+                #pragma unroll
+                for (int j = 0; j < TN; ++j) fb[j] = tr_frag<BN>(Bb, (wn * TN + j) * 32, g * 16, lane);
+            } else {
+                const uint32_t* const Ab = reinterpret_cast<const uint32_t*>(As + buf * A_STAGE) + (g * 8 + (lane >> 5) * 4) * LDPA + (lane & 31);
+                const uint32_t* const Bb = reinterpret_cast<const uint32_t*>(Bs + buf * B_STAGE) + (g * 8 + (lane >> 5) * 4) * LDPB + (lane & 31);
+                #pragma unroll
+                for (int i = 0; i < TM; ++i) {
+                    const uint32_t* q = Ab + (wm * TM + i) * 32;
+                    fa[i] = make_uint4(q[0], q[LDPA], q[2 * LDPA], q[3 * LDPA]);
+                }
+                #pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const uint32_t* q = Bb + (wn * TN + j) * 32;
+                    fb[j] = make_uint4(q[0], q[LDPB], q[2 * LDPB], q[3 * LDPB]);
+                }
             }
-            store_tiles((u + 1) % PF, buf ^ 1);
-            __syncthreads();
+        };
+        // The fragments of group g+1 are read from LDS before the MFMAs of group g are issued
+        // (the fences keep the compiler from sinking the reads back to their first use), so the
+        // LDS latency of one group hides behind the matrix work of the one before.
+        uint4 fa[2][TM], fb[2][TN];
+        read_frags(0, fa[0], fb[0]);
+        #pragma unroll
+        for (int g = 0; g < NG; ++g) {
+            if (g + 1 < NG) read_frags(g + 1, fa[(g + 1) & 1], fb[(g + 1) & 1]);
+            if (FRAG_AHEAD) __builtin_amdgcn_sched_barrier(0);
+            #pragma unroll
+            for (int i = 0; i < TM; ++i)
+                #pragma unroll
+                for (int j = 0; j < TN; ++j) Frag<T>::mma(fa[g & 1][i], fb[g & 1][j], acc[i][j]);
+            if (FRAG_AHEAD) __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    if (DIRECT) {
+        // NST LDS stages filled by direct loads, no registers in between: while tile k is contracted from
+        // stage k % NST, the loads of tiles k+1 .. k+NST-1 are in flight.  Per tile: wait until this wave's
+        // loads of tile k have landed (loads complete in order, so all but those of the NST-2 younger tiles),
+        // barrier (every wave's part of tile k is in LDS and every wave is done reading tile k-1), then
+        // refill the stage tile k-1 was in.  Loads past the end of the reduction write zeros into a stage
+        // nobody reads; all of them have landed before the epilogue reuses the memory.
+        constexpr int PER_TILE = ITER_A + ITER_B;
+        #pragma unroll
+        for (int u = 0; u < NST - 1; ++u) load_tiles(u);
+        for (int kt = 0; kt < nk; kt += NST) {
+            #pragma unroll
+            for (int u = 0; u < NST; ++u) {
+                if (kt + u >= nk) break;
+                wait_vmcnt<(NST - 2) * PER_TILE>();
+                __syncthreads();
+                load_tiles((u + NST - 1) % NST);
+                contract(u);
+            }
+        }
+        wait_vmcnt<0>();
+        __syncthreads();
+    } else {
+        #pragma unroll
+        for (int u = 0; u < PF; ++u) load_tiles(u);
+        store_tiles(0, 0);
+        __syncthreads();
+        for (int kt = 0; kt < nk; kt += PF) {
+            #pragma unroll
+            for (int u = 0; u < PF; ++u) {
+                const int k = kt + u;
+                if (k >= nk) break;
+                const int buf = PF == 1 ? (k & 1) : (u & 1);
+                load_tiles(u);
+                contract(buf);
+                store_tiles((u + 1) % PF, buf ^ 1);
+                __syncthreads();
+            }
         }
     }
 
@@ -1140,6 +1235,7 @@ static void launch_mode(int dtype, TileCfg t, dim3 grid, const ConvArgs& a_in, h
     else if (MODE == CONV_DGRAD) { a.magic_inner = magic_of(a.K); a.magic_taps = magic_of(a.ns); }
     if (MODE == CONV_FWD) { a.magic_hw = magic_of(a.Ho * a.Wo); a.magic_w = magic_of(a.Wo); }
     else if (MODE == CONV_DGRAD) { a.magic_hw = magic_of(a.Hc * a.Wc); a.magic_w = magic_of(a.Wc); }
+    a.stride_shift = a.stride >= 4 ? 2 : a.stride >= 2 ? 1 : 0;
     const bool magic_ok = conv_magic_ok(MODE, a);
     const bool fast = conv_fast(dtype, MODE, a) && magic_ok;
     if (!fast) {
@@ -1286,7 +1382,9 @@ int launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dy, const void* 
     a.accumulate = accumulate;
     const double esz = dtype == 1 ? 2.0 : 4.0;
     const double bA = esz * (double)g.N * g.Ho * g.Wo * g.K, bB = esz * (double)a.Nn * a.ldb;
-    a.vecA = (g.K % VEC == 0) && bA < 2147483648.0; a.vecB = (a.ldb % VEC == 0) && bB < 2147483648.0;
+    // the vector gather of dy divides pixel coordinates by the stride with a shift
+    const bool stride_pow2 = g.stride == 1 || g.stride == 2 || g.stride == 4;
+    a.vecA = (g.K % VEC == 0) && bA < 2147483648.0 && stride_pow2; a.vecB = (a.ldb % VEC == 0) && bB < 2147483648.0;
     a.bytesA = a.vecA ? (unsigned)bA : 0; a.bytesB = a.vecB ? (unsigned)bB : 0;
     // one launch per residue class of the input pixel modulo the stride
     for (int ph = 0; ph < g.stride && ph < g.H; ++ph) {
