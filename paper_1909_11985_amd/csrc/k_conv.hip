@@ -52,6 +52,10 @@
 #ifndef EDL_DIRECT_LDS
 #define EDL_DIRECT_LDS 1
 #endif
+// the same for the bf16 weight gradient
+#ifndef EDL_DIRECT_WG
+#define EDL_DIRECT_WG 1
+#endif
 
 namespace edl {
 
@@ -344,7 +348,13 @@ __global__ __launch_bounds__(256, 2) void conv_igemm_kernel(ConvArgs a) {   // a
     constexpr int RB = BK * (int)sizeof(T), RPL = RB > 256 ? 1 : 256 / RB;
     constexpr bool DIRECT = EDL_DIRECT_LDS != 0 && FAST && !WG && TOT_A % 256 == 0 && TOT_B % 256 == 0 &&
                             (RB == 64 || RB == 128);
-    constexpr int NST = DIRECT ? PF + 1 : 2;         // LDS stages
+    // The bf16 weight gradient the same way: its tiles are rows of pixels as they are in memory, so a
+    // wave's load fills whole pixel rows; item v is the 16-byte slot v % RV of pixel v / RV.
+    constexpr bool DIRECT_WG = EDL_DIRECT_LDS != 0 && EDL_DIRECT_WG != 0 && FAST && WGT;
+    constexpr int DA = DIRECT_WG ? BK * RVA / 256 : 1, DB = DIRECT_WG ? BK * RVB / 256 : 1;   // loads per tile
+    static_assert(!DIRECT_WG || (BK * RVA % 256 == 0 && BK * RVB % 256 == 0), "whole waves of slots");
+    constexpr bool DMA = DIRECT || DIRECT_WG;
+    constexpr int NST = DMA ? PF + 1 : 2;            // LDS stages
     constexpr int LDK = DIRECT ? BK : BK + VEC;
     constexpr int A_STAGE = WGT ? BK * BM * 2 : WG ? KD * LDPA * 4 : BM * LDK * (int)sizeof(T);   // bytes per LDS stage
     constexpr int B_STAGE = WGT ? BK * BN * 2 : WG ? KD * LDPB * 4 : BN * LDK * (int)sizeof(T);
@@ -387,9 +397,12 @@ __global__ __launch_bounds__(256, 2) void conv_igemm_kernel(ConvArgs a) {   // a
     bool okB[WG ? 1 : ITER_B];
     int tr = 0, ts = 0, tc = 0, tap_off = 0;   // fwd/dgrad: kernel tap and channel of this thread's vector
     int kcur = 0;                    // reduction index of this thread's vector (fwd/dgrad) or of the tile (wgrad)
-    int64_t offA[WG ? ITER_A : 1];   // wgrad: offset of dy[first pixel of the item][first row of the item]
-    int pn[WG ? ITER_B : 1], pho[WG ? ITER_B : 1], pwo[WG ? ITER_B : 1];   // wgrad: first pixel of the item
+    constexpr int NOA = DIRECT_WG ? DA : WG ? ITER_A : 1, NPB = DIRECT_WG ? DB : WG ? ITER_B : 1;
+    int64_t offA[NOA];               // wgrad: offset of dy[first pixel of the item][first row of the item]
+    int pn[NPB], pho[NPB], pwo[NPB]; // wgrad: first pixel of the item
+    bool rowA_ok = true;             // wgrad, direct loads: this lane's channels of dy exist
     int wg_r = 0, wg_s = 0, wg_c = 0;  // wgrad: tap and channel of this thread's B rows
+    bool wg_j_ok = true;
     int dn = 0, dho = 0, dwo = 0;    // wgrad: BK pixels as (images, rows, columns)
     if (!WG) {
         const int inner = MODE == CONV_FWD ? a.C : a.K;
@@ -417,6 +430,35 @@ __global__ __launch_bounds__(256, 2) void conv_igemm_kernel(ConvArgs a) {   // a
             okB[it] = j < a.Nn && (tid + it * 256) < TOT_B;
             offB[it] = (int64_t)j * a.ldb;
         }
+    } else if (DIRECT_WG) {
+        // slot p of pixel row x holds the 8 channels starting at (((p >> 1) ^ (x & MASK)) << 4) | ((p & 1) << 3)
+        // (wg_lds_index); a lane's pixels are a multiple of 4 apart, so its channels are the same in all of them
+        constexpr int MASKA = BM / 16 >= 4 ? 3 : BM / 16 - 1, MASKB = BN / 16 >= 4 ? 3 : BN / 16 - 1;
+        const int pa = tid % RVA, pb = tid % RVB;
+        const int chA = ((((pa >> 1) ^ ((tid / RVA) & MASKA)) << 4) | ((pa & 1) << 3));
+        const int chB = ((((pb >> 1) ^ ((tid / RVB) & MASKB)) << 4) | ((pb & 1) << 3));
+        rowA_ok = m0 + chA < a.M;
+        const int j0 = n0 + chB;
+        const int tap = j0 / a.C;
+        wg_c = j0 - tap * a.C;
+        wg_r = tap / a.S;
+        wg_s = tap - wg_r * a.S;
+        const int hw = a.Ho * a.Wo;
+        dn = BK / hw;
+        dho = (BK - dn * hw) / a.Wo;
+        dwo = BK - dn * hw - dho * a.Wo;
+        #pragma unroll
+        for (int it = 0; it < DA; ++it) offA[it] = (int64_t)(kbeg + (tid + it * 256) / RVA) * a.K + m0 + chA;
+        #pragma unroll
+        for (int it = 0; it < DB; ++it) {
+            const int mm = kbeg + (tid + it * 256) / RVB;
+            pn[it] = mm / hw;
+            const int rem = mm - pn[it] * hw;
+            pho[it] = rem / a.Wo;
+            pwo[it] = rem - pho[it] * a.Wo;
+        }
+        wg_j_ok = j0 < a.Nn;
+        kcur = kbeg;
     } else {
         const int j0 = n0 + (tid % RVB) * VEC;
         const int tap = j0 / a.C;
@@ -469,6 +511,33 @@ __global__ __launch_bounds__(256, 2) void conv_igemm_kernel(ConvArgs a) {   // a
                 ts = a.s0 + (tap - ri * a.ns) * a.stride;
                 tap_off = (tr * a.S + ts) * a.K + tc;
             }
+        } else if (DIRECT_WG) {
+            // `set` is the LDS stage; pixel rows past the end of the reduction come in as zeros
+            #pragma unroll
+            for (int it = 0; it < DA; ++it) {
+                const bool ok = rowA_ok & (kcur + (tid + it * 256) / RVA < kend);
+                buffer_load16_to_lds(wordsA, ldsA_wave + set * A_STAGE + it * 4096,
+                                     ((unsigned)(int)offA[it] * (unsigned)sizeof(T)) | (ok ? 0u : kOutOfRange));
+                offA[it] += (int64_t)BK * a.K;
+            }
+            #pragma unroll
+            for (int it = 0; it < DB; ++it) {
+                const int h = pho[it] * a.stride - a.pad + wg_r, w = pwo[it] * a.stride - a.pad + wg_s;
+                const bool ok = wg_j_ok & (kcur + (tid + it * 256) / RVB < kend) & ((unsigned)h < (unsigned)a.H) &
+                                ((unsigned)w < (unsigned)a.W);
+                const unsigned off = (unsigned)(((pn[it] * a.H + h) * a.W + w) * a.C + wg_c) * (unsigned)sizeof(T);
+                buffer_load16_to_lds(wordsB, ldsB_wave + set * B_STAGE + it * 4096, off | (ok ? 0u : kOutOfRange));
+                // advance the item's pixel by BK
+                int qw = pwo[it] + dwo, qh = pho[it] + dho, qn = pn[it] + dn;
+                const bool cw = qw >= a.Wo;
+                qw -= cw ? a.Wo : 0;
+                qh += cw ? 1 : 0;
+                const bool chh = qh >= a.Ho;
+                qh -= chh ? a.Ho : 0;
+                qn += chh ? 1 : 0;
+                pwo[it] = qw; pho[it] = qh; pn[it] = qn;
+            }
+            kcur += BK;
         } else if (!WG) {
             const bool in_k = kcur < kend;
             #pragma unroll
@@ -733,14 +802,14 @@ __global__ __launch_bounds__(256, 2) void conv_igemm_kernel(ConvArgs a) {   // a
             if (FRAG_AHEAD) __builtin_amdgcn_sched_barrier(0);
         }
     };
-    if (DIRECT) {
+    if (DMA) {
         // NST LDS stages filled by direct loads, no registers in between: while tile k is contracted from
         // stage k % NST, the loads of tiles k+1 .. k+NST-1 are in flight.  Per tile: wait until this wave's
         // loads of tile k have landed (loads complete in order, so all but those of the NST-2 younger tiles),
         // barrier (every wave's part of tile k is in LDS and every wave is done reading tile k-1), then
         // refill the stage tile k-1 was in.  Loads past the end of the reduction write zeros into a stage
         // nobody reads; all of them have landed before the epilogue reuses the memory.
-        constexpr int PER_TILE = ITER_A + ITER_B;
+        constexpr int PER_TILE = DIRECT_WG ? DA + DB : ITER_A + ITER_B;
         #pragma unroll
         for (int u = 0; u < NST - 1; ++u) load_tiles(u);
         for (int kt = 0; kt < nk; kt += NST) {
