@@ -35,11 +35,11 @@ VGG16_P = 138357544
 WORKLOADS = {
     # name: (model, dtype, N, B, p, geometry overrides, lr)
     "resnet50_bf16_b32": ("resnet50", "bf16", 1024, 32, 1, {}, 0.1),
-    "vgg16_bf16_b32": ("vgg16", "bf16", 256, 32, 1, {}, 0.01),
+    "vgg16_bf16_b32": ("vgg16", "bf16", 256, 32, 1, {}, 0.001),
     # the other networks of the paper's section 6
     "resnet101_bf16_b32": ("resnet50", "bf16", 256, 32, 1, dict(arch=(64, 3, 4, 23, 3)), 0.1),
     "resnet152_bf16_b32": ("resnet50", "bf16", 256, 32, 1, dict(arch=(64, 3, 8, 36, 3)), 0.1),
-    "vgg19_bf16_b32": ("vgg16", "bf16", 256, 32, 1, dict(arch=(64, 4096, 2, 2, 4, 4, 4)), 0.01),
+    "vgg19_bf16_b32": ("vgg16", "bf16", 256, 32, 1, dict(arch=(64, 4096, 2, 2, 4, 4, 4)), 0.001),
     "alexnet_bf16_b128": ("alexnet", "bf16", 512, 128, 1, {}, 0.001),
     "resnet20_f32_b128_p2": ("resnet20", "f32", 2048, 128, 2, {}, 0.1),
     "mlp_f32_b64_p4": ("mlp", "f32", 1024, 64, 4, {}, 0.1),

@@ -239,6 +239,13 @@ def test_layerwise_resnet50_bf16_at_the_benchmark_shape():
     _assert_layerwise(r, "bf16")
 
 
+def test_layerwise_vgg16_bf16_at_full_size():
+    """Every layer of VGG-16 at 224x224 (reductions up to 25088 long, 200704-row outputs), four samples."""
+    r = layerwise_parity("vgg16", "bf16", 4, verbose=False)
+    print(r)
+    _assert_layerwise(r, "bf16")
+
+
 def test_layerwise_alexnet_bf16_at_full_size():
     """Every layer of AlexNet at 224x224 (11x11/4 and 5x5 windows, 3x3/2 pools without padding)."""
     r = layerwise_parity("alexnet", "bf16", 32, verbose=False)
