@@ -199,6 +199,7 @@ struct edl_handle {
     int idx_slot = 0;
     float* loss_host = nullptr;
     std::vector<int> readers;            // per tensor storage: how many layers read it (as input or as residual)
+    std::vector<int> first_reader;       // per tensor storage: the first of them in the layer list (the last to run backward)
     // shard sizes of the last edl_gradients (what edl_apply weighs the gradient buffers by)
     std::vector<int64_t> shard_n;
     bool shards_equal = true;
@@ -333,9 +334,16 @@ int32_t edl_init(edl_handle** out, const edl_config* cfg, uint64_t seed, void* d
     h->arena = (char*)dev_arena;
     h->st = (hipStream_t)hip_stream;
     h->readers.assign(h->g.tensors.size(), 0);
-    for (const Op& op : h->g.ops) {
-        if (op.x >= 0) h->readers[(size_t)storage_of(h->g, op.x)] += 1;
-        if (op.kind == OP_BN && op.res >= 0) h->readers[(size_t)storage_of(h->g, op.res)] += 1;
+    h->first_reader.assign(h->g.tensors.size(), -1);
+    for (size_t i = 0; i < h->g.ops.size(); ++i) {
+        const Op& op = h->g.ops[i];
+        auto reads = [&](int t) {
+            const size_t sx = (size_t)storage_of(h->g, t);
+            h->readers[sx] += 1;
+            if (h->first_reader[sx] < 0) h->first_reader[sx] = (int)i;
+        };
+        if (op.x >= 0) reads(op.x);
+        if (op.kind == OP_BN && op.res >= 0) reads(op.res);
     }
     for (int s = 0; s < kIdxSlots; ++s) {
         HIP_TRY(hipHostMalloc((void**)&h->idx_host[s], sizeof(int64_t) * (size_t)cfg->B, hipHostMallocDefault));
@@ -508,12 +516,17 @@ static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, siz
                     launch_unpad_rows(h->at<float>(h->L.dwpad), G + op.w_off, (int64_t)op.K * op.R * op.S, g.tensors[0].C, h->L.cpad, ws);
                 const int sx = storage_of(g, op.x);
                 if (sx != 0) {
-                    // If the layer just before in the list produced this convolution's input, ends in a ReLU and has
-                    // no other reader, its backward starts with the masked gradient and its column sums: the dgrad's
-                    // epilogue can leave both (see DgradMask), and that layer then skips its own reduction pass.
+                    // If the layer just before in the list produced this convolution's input and ends in a ReLU, and
+                    // this convolution is the first reader of that tensor in the list (so every other reader, such as
+                    // the shortcut of a residual block, has already added its part), that layer's backward starts with
+                    // the masked gradient and its column sums: the dgrad's epilogue can leave both (see DgradMask),
+                    // and that layer then skips its own reduction pass.
                     DgradMask mask = {};
                     const bool acc = written[(size_t)sx] != 0;
-                    if (ii > op_lo && !acc && h->readers[(size_t)sx] == 1) {
+                    static const bool fuse_joins = getenv("EDL_TUNE_FUSED_MASK_JOIN") ? atoi(getenv("EDL_TUNE_FUSED_MASK_JOIN")) != 0 : true;
+                    const bool last_writer = h->first_reader[(size_t)sx] == ii &&
+                                             (h->readers[(size_t)sx] == 1 ? !acc : (fuse_joins && acc));
+                    if (ii > op_lo && last_writer) {
                         const Op& prod = g.ops[ii - 1];
                         if (prod.relu && storage_of(g, prod.y) == sx && (prod.kind == OP_BN || prod.kind == OP_CONV)) {
                             mask.act = h->act(op.x);

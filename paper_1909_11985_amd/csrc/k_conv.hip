@@ -744,7 +744,7 @@ __global__ __launch_bounds__(256, 2) void conv_igemm_kernel(ConvArgs a) {   // a
     // contracted from LDS stage k%2, the global loads of tiles k+1 .. k+PF are in
     // flight; tile k+1 is moved from its registers to the other stage after the
     // MFMAs of tile k.  One barrier per tile.
-    static_assert(PF == 1 || PF % 2 == 0, "the LDS stage of a tile must be known at compile time");
+    static_assert(DMA || PF == 1 || PF % 2 == 0, "the LDS stage of a tile must be known at compile time");
     // Loads past the end of the reduction are issued too: their offsets are out of
     // range, so they touch no memory and return zeros, and the number of loads in
     // flight at every wait is then a compile-time constant.
@@ -1188,6 +1188,15 @@ enum TileCfg { T128x128, T128x64, T128x32, T64x64 };
 #ifndef EDL_BK_BIG_DIV
 #define EDL_BK_BIG_DIV 2
 #endif
+#ifndef EDL_BK_SMALL_DIV
+#define EDL_BK_SMALL_DIV 1
+#endif
+#ifndef EDL_PF_BIG_HALF
+#define EDL_PF_BIG_HALF EDL_PF_BIG
+#endif
+#ifndef EDL_PF_WG_SMALL
+#define EDL_PF_WG_SMALL 2
+#endif
 
 // reduction elements per tile: eight 16-byte vectors per row for either type
 template <typename T> constexpr int kConvBK = 8 * Elem<T>::VEC;
@@ -1245,8 +1254,9 @@ static void launch_cfg(TileCfg t, bool fast, dim3 tiles, const ConvArgs& a_in, h
     // reduction step, often fewer workgroups than the chip has room for) gains a third on long reductions from
     // two register sets of loads in flight; the 128-wide tiles gain nothing from a second set but do from
     // half-length reduction steps (half the LDS per workgroup, so more workgroups per CU).
-    constexpr int PF_BIG = EDL_PF_BIG, PF_SMALL = EDL_PF_SMALL;
-    constexpr int BK_SMALL = MODE == CONV_WGRAD ? BK : EDL_BK_SMALL_MULT * BK;
+    constexpr int PF_BIG = EDL_PF_BIG, PF_SMALL = MODE == CONV_WGRAD ? EDL_PF_WG_SMALL : EDL_PF_SMALL;
+    constexpr int PF_HALF = MODE == CONV_WGRAD ? EDL_PF_BIG : EDL_PF_BIG_HALF;   // 128-wide tiles on half-length steps
+    constexpr int BK_SMALL = MODE == CONV_WGRAD ? BK : EDL_BK_SMALL_MULT * BK / EDL_BK_SMALL_DIV;
     constexpr int BK_BIG = MODE == CONV_WGRAD ? BK : BK / EDL_BK_BIG_DIV;
     if (!fast) {   // element-wise kernel: one tile shape only
         hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 1, 1, BK, false, 1>), grid, dim3(256), 0, st, a);
@@ -1261,10 +1271,10 @@ static void launch_cfg(TileCfg t, bool fast, dim3 tiles, const ConvArgs& a_in, h
             if (BK_BIG != BK && a.Kred >= full_steps_from)
                 hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 2, 2, BK, true, PF_BIG>), grid, dim3(256), 0, st, a);
             else
-                hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 2, 2, BK_BIG, true, PF_BIG>), grid, dim3(256), 0, st, a);
+                hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 2, 2, BK_BIG, true, PF_HALF>), grid, dim3(256), 0, st, a);
             break;
         }
-        case T128x64: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 2, 1, BK_BIG, true, PF_BIG>), grid, dim3(256), 0, st, a); break;
+        case T128x64: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 2, 1, BK_BIG, true, PF_HALF>), grid, dim3(256), 0, st, a); break;
         case T128x32: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 4, 1, 1, 1, BK, true, PF_BIG>), grid, dim3(256), 0, st, a); break;
         default: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 1, 1, BK_SMALL, true, PF_SMALL>), grid, dim3(256), 0, st, a); break;
     }
@@ -1479,9 +1489,10 @@ int launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dy, const void* 
             }
             if (splits > 1) { a.ksplit = ks; a.partial = scratch; }
             const int row_tiles = (a.M + bm - 1) / bm;
-            // masked store and column sums in the epilogue: one launch that covers every pixel and writes (not adds)
+            // masked store and column sums in the epilogue: one launch that covers every pixel and leaves the
+            // final gradient (it may add to what other readers of the tensor have left there)
             static const bool tune_mask = env_int("EDL_TUNE_FUSED_MASK", 1) != 0;
-            const bool fuse = tune_mask && mask != nullptr && mask->act != nullptr && g.stride == 1 && splits == 1 && !accumulate &&
+            const bool fuse = tune_mask && mask != nullptr && mask->act != nullptr && g.stride == 1 && splits == 1 &&
                               row_tiles <= kRedRowBlocks && conv_fast(dtype, CONV_DGRAD, a) && conv_magic_ok(CONV_DGRAD, a);
             a.mask_act = fuse ? mask->act : nullptr;
             a.xin = fuse ? mask->xin : nullptr;
