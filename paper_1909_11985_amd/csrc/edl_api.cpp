@@ -171,7 +171,7 @@ void plan_layout(const edl_config& c, const Graph& g, Layout& L) {
     L.wgrad_scratch = take(std::max<int64_t>(L.wgrad_scratch_bytes, 16));
     L.splitk_scratch = take(std::max<int64_t>(L.splitk_scratch_bytes, 16));
     L.dwpad = take(dwpad_bytes);
-    L.ttable = take((int64_t)sizeof(TransposeEntry) * std::max<size_t>(no, 1));
+    L.ttable = take((int64_t)sizeof(TransposeEntry) * 2 * std::max<size_t>(no, 1));   // element-wise entries, then vector ones
     L.total = o;
 }
 
@@ -191,8 +191,10 @@ struct edl_handle {
     // cached permutation of the current epoch
     int64_t perm_epoch = -1;
     std::vector<int64_t> perm;
-    int t_entries = 0, t_tiles = 0;      // one-launch weight transpose
+    int t_entries = 0, t_tiles = 0;      // one-launch weight transpose (element-wise entries)
     double t_bytes = 0;
+    int tv_entries = 0, tv_tiles = 0;    // ... and the bf16 layers of vector-friendly shape
+    double tv_bytes = 0;
     // pinned staging
     int64_t* idx_host[kIdxSlots] = {nullptr, nullptr, nullptr, nullptr};
     hipEvent_t idx_event[kIdxSlots];
@@ -305,6 +307,9 @@ static int refresh_weight_copies(edl_handle* h) {
 static void transpose_weights(edl_handle* h) {
     launch_weight_transpose_all(h->cfg.dtype, h->w(), h->arena, h->at<TransposeEntry>(h->L.ttable), h->t_entries,
                                 h->t_tiles, h->t_bytes, h->st);
+    if (h->tv_entries > 0)
+        launch_weight_transpose_bf16(h->at<uint16_t>(h->L.shadow), h->arena, h->at<TransposeEntry>(h->L.ttable) + h->g.ops.size(),
+                                     h->tv_entries, h->tv_tiles, h->tv_bytes, h->st);
     for (size_t i = 0; i < h->g.ops.size(); ++i)
         if (h->L.wpad[i] >= 0) {
             const Op& op = h->g.ops[i];
@@ -369,7 +374,9 @@ int32_t edl_init(edl_handle** out, const edl_config* cfg, uint64_t seed, void* d
             launch_fill_f32(h->running() + op.run_off + op.K, 1.f, op.K, h->st);
         }
     {
-        std::vector<TransposeEntry> tab;
+        // bf16 layers of vector-friendly shape are transposed from the bf16 copy of the weights in 64x64
+        // tiles; the others element by element from the float32 weights
+        std::vector<TransposeEntry> tab, tabv;
         const double esz = cfg->dtype == EDL_DTYPE_BF16 ? 2.0 : 4.0;
         for (size_t i = 0; i < h->g.ops.size(); ++i) {
             const Op& op = h->g.ops[i];
@@ -378,15 +385,26 @@ int32_t edl_init(edl_handle** out, const edl_config* cfg, uint64_t seed, void* d
             TransposeEntry te;
             te.src_off = op.w_off; te.dst_off = h->L.wT[i];
             te.K = op.K; te.RS = op.R * op.S; te.C = tx.C;
-            te.tile_start = h->t_tiles;
-            h->t_tiles += ((te.C + 31) / 32) * ((te.K + 31) / 32) * te.RS;
-            h->t_bytes += (4.0 + esz) * (double)te.K * te.RS * te.C;
-            tab.push_back(te);
+            if (cfg->dtype == EDL_DTYPE_BF16 && te.K % 8 == 0 && te.C % 8 == 0 && op.w_off % 8 == 0) {
+                te.tile_start = h->tv_tiles;
+                h->tv_tiles += ((te.C + 63) / 64) * ((te.K + 63) / 64) * te.RS;
+                h->tv_bytes += 4.0 * (double)te.K * te.RS * te.C;
+                tabv.push_back(te);
+            } else {
+                te.tile_start = h->t_tiles;
+                h->t_tiles += ((te.C + 31) / 32) * ((te.K + 31) / 32) * te.RS;
+                h->t_bytes += (4.0 + esz) * (double)te.K * te.RS * te.C;
+                tab.push_back(te);
+            }
         }
         h->t_entries = (int)tab.size();
+        h->tv_entries = (int)tabv.size();
         if (!tab.empty())
             HIP_TRY(hipMemcpyAsync(h->at<TransposeEntry>(h->L.ttable), tab.data(), sizeof(TransposeEntry) * tab.size(),
                                    hipMemcpyHostToDevice, h->st));
+        if (!tabv.empty())
+            HIP_TRY(hipMemcpyAsync(h->at<TransposeEntry>(h->L.ttable) + h->g.ops.size(), tabv.data(),
+                                   sizeof(TransposeEntry) * tabv.size(), hipMemcpyHostToDevice, h->st));
         HIP_TRY(hipStreamSynchronize(h->st));   // init[] and tab[] leave scope
     }
     h->weights_dirty = true;

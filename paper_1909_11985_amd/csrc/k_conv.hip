@@ -1335,8 +1335,12 @@ static void launch_mode(int dtype, TileCfg t, dim3 grid, const ConvArgs& a_in, h
     const double flops = 2.0 * (double)a.M * a.Nn * a.Kred;
     double bytes;
     if (MODE == CONV_FWD) bytes = esz * ((double)a.N * a.H * a.W * a.C + (double)a.Nn * a.Kred) + (a.out_fp32 ? 4.0 : esz) * (double)a.M * a.Nn;
-    else if (MODE == CONV_DGRAD) bytes = esz * ((double)a.N * a.Ho * a.Wo * a.K + (double)a.Nn * a.Kred + (double)a.M * a.Nn);
-    else bytes = esz * ((double)a.Kred * a.K + (double)a.N * a.H * a.W * a.C) + 4.0 * (double)a.M * a.Nn;
+    else if (MODE == CONV_DGRAD) {
+        // dy, weights, dx; plus what a fused epilogue reads at every output position: the gradient already
+        // there, the activation that masks it, the batch norm's input for the second sum
+        const double extra = (a.accumulate ? 1.0 : 0.0) + (a.mask_act ? 1.0 : 0.0) + (a.xin ? 1.0 : 0.0);
+        bytes = esz * ((double)a.N * a.Ho * a.Wo * a.K + (double)a.Nn * a.Kred + (1.0 + extra) * (double)a.M * a.Nn);
+    } else bytes = esz * ((double)a.Kred * a.K + (double)a.N * a.H * a.W * a.C) + 4.0 * (double)a.M * a.Nn;
     const char* label = conv_label(dtype, MODE, t);
     static const bool by_shape = getenv("EDL_PROFILE_BY_SHAPE") != nullptr;
     if (by_shape && prof_enabled()) {

@@ -333,6 +333,59 @@ __global__ __launch_bounds__(256) void weight_transpose_all_kernel(const float* 
     }
 }
 
+// The same for bf16 layers whose K and C are multiples of 8, from the bf16 copy of the weights (two bytes
+// read per element instead of four): 64x64 tiles, 16-byte loads and stores.  tile_start counts 64x64 tiles.
+__global__ __launch_bounds__(256) void weight_transpose_bf16_kernel(const uint16_t* __restrict__ w16, unsigned char* __restrict__ arena,
+                                                                    const TransposeEntry* __restrict__ tab, int entries) {
+    constexpr int LD = 68;   // elements per tile row in LDS: rows 8-byte aligned, column reads spread over the banks
+    __shared__ __attribute__((aligned(16))) uint16_t tile[64 * LD];
+    int e = 0, hi = entries - 1;
+    while (e < hi) {
+        const int mid = (e + hi + 1) >> 1;
+        if ((int)blockIdx.x >= tab[mid].tile_start) e = mid;
+        else hi = mid - 1;
+    }
+    const TransposeEntry te = tab[e];
+    int b = blockIdx.x - te.tile_start;
+    const int tiles_c = (te.C + 63) / 64, tiles_k = (te.K + 63) / 64;
+    const int cx = b % tiles_c; b /= tiles_c;
+    const int ky = b % tiles_k;
+    const int t = b / tiles_k;
+    const uint16_t* src = w16 + te.src_off;
+    uint16_t* dst = reinterpret_cast<uint16_t*>(arena + te.dst_off);
+    const int c0 = cx * 64, k0 = ky * 64;
+    #pragma unroll
+    for (int v = threadIdx.x; v < 512; v += 256) {
+        const int i = v >> 3, j = v & 7;
+        const int k = k0 + i, c = c0 + j * 8;
+        uint4 val = make_uint4(0, 0, 0, 0);
+        if (k < te.K && c < te.C) val = *reinterpret_cast<const uint4*>(src + ((int64_t)k * te.RS + t) * te.C + c);
+        uint2* d = reinterpret_cast<uint2*>(&tile[i * LD + j * 8]);
+        d[0] = make_uint2(val.x, val.y);
+        d[1] = make_uint2(val.z, val.w);
+    }
+    __syncthreads();
+    #pragma unroll
+    for (int v = threadIdx.x; v < 512; v += 256) {
+        const int ci = v >> 3, kj = v & 7;
+        const int c = c0 + ci, k = k0 + kj * 8;
+        if (c < te.C && k < te.K) {
+            uint32_t o[4];
+            #pragma unroll
+            for (int q = 0; q < 4; ++q)
+                o[q] = (uint32_t)tile[(kj * 8 + 2 * q) * LD + ci] | ((uint32_t)tile[(kj * 8 + 2 * q + 1) * LD + ci] << 16);
+            *reinterpret_cast<uint4*>(dst + ((int64_t)c * te.RS + t) * te.K + k) = make_uint4(o[0], o[1], o[2], o[3]);
+        }
+    }
+}
+
+void launch_weight_transpose_bf16(const uint16_t* w16, void* arena, const TransposeEntry* dev_table, int entries,
+                                  int total_tiles, double bytes, hipStream_t st) {
+    if (entries <= 0 || total_tiles <= 0) return;
+    ProfScope ps("weight_transpose", 0.0, bytes, st);
+    hipLaunchKernelGGL(weight_transpose_bf16_kernel, dim3(total_tiles), dim3(256), 0, st, w16, (unsigned char*)arena, dev_table, entries);
+}
+
 void launch_weight_transpose_all(int dtype, const float* w, void* arena, const TransposeEntry* dev_table, int entries,
                                  int total_tiles, double bytes, hipStream_t st) {
     if (entries <= 0 || total_tiles <= 0) return;

@@ -36,6 +36,9 @@ struct TransposeEntry {
 };
 void launch_weight_transpose_all(int dtype, const float* w, void* arena, const TransposeEntry* dev_table, int entries,
                                  int total_tiles, double bytes, hipStream_t st);
+// bf16 layers with K and C multiples of 8, from the bf16 copy of the weights; tile_start counts 64x64 tiles
+void launch_weight_transpose_bf16(const uint16_t* w16, void* arena, const TransposeEntry* dev_table, int entries,
+                                  int total_tiles, double bytes, hipStream_t st);
 // dst = cast(src) for float32 -> bf16 (weight copy after restore / set_params)
 void launch_cast_bf16(const float* src, uint16_t* dst, int64_t n, hipStream_t st);
 
