@@ -1206,8 +1206,9 @@ static int env_int(const char* name, int dflt) {
     return v ? atoi(v) : dflt;
 }
 
-// short_fwd: a forward problem of one or two reduction steps, where the epilogue is most of the
-// workgroup's time; twice as many workgroups of half the width measured 10-20% faster there
+// short_fwd: a problem whose epilogue is most of the workgroup's time (a forward pass of one or two
+// reduction steps, an input-gradient pass whose epilogue adds, masks and sums); twice as many workgroups of
+// half the width measured faster there
 static TileCfg pick_tile(int M, int Nn, int* bm, int* bn, bool short_fwd = false) {
     static const int min128 = env_int("EDL_TUNE_MIN128", 256);
     TileCfg t;
