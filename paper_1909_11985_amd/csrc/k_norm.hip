@@ -252,15 +252,15 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ x, 
 }
 
 // dx = gamma*rstd*(dy' - coef0 - xhat*coef1) ; dres (+)= dy'
-// Unconditional loads as above: y is x when there is no ReLU, dres_old is dy when dres is not
-// accumulated into (both read and ignored).
-template <typename T, int VEC>
+// MASK: dy' = dy * (y > 0) is formed here (else dy arrives masked, or there is no ReLU, and y is not read);
+// ACC: dres already holds a gradient that dy' is added to.  Compile-time, so that no load sits behind a
+// run-time branch and none is issued that is not needed.
+template <typename T, int VEC, bool MASK, bool ACC>
 __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const T* __restrict__ x, const T* __restrict__ y,
                                                            const T* __restrict__ dy, T* __restrict__ dx, T* dres,
-                                                           const T* dres_old, int dres_acc, const float* __restrict__ gamma,
+                                                           const float* __restrict__ gamma,
                                                            const float* __restrict__ mean_rstd,
-                                                           const float* __restrict__ coef, int64_t M, int C, int cvecs,
-                                                           int relu) {
+                                                           const float* __restrict__ coef, int64_t M, int C, int cvecs) {
     const int64_t total = M * cvecs;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
@@ -269,18 +269,18 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const T* __restrict__
         float xv[VEC], yv[VEC], g[VEC], old[VEC], out[VEC];
         load_row<T, VEC>(x, r, C, c0, xv);
         load_row<T, VEC>(dy, r, C, c0, g);
-        load_row<T, VEC>(y, r, C, c0, yv);
-        load_row<T, VEC>(dres_old, r, C, c0, old);
+        if (MASK) load_row<T, VEC>(y, r, C, c0, yv);
+        if (ACC) load_row<T, VEC>(dres, r, C, c0, old);
         #pragma unroll
         for (int e = 0; e < VEC; ++e) {
-            g[e] = (!relu || yv[e] > 0.f) ? g[e] : 0.f;
+            if (MASK) g[e] = yv[e] > 0.f ? g[e] : 0.f;
             const float rs = mean_rstd[C + c0 + e];
             const float xh = (xv[e] - mean_rstd[c0 + e]) * rs;
             out[e] = gamma[c0 + e] * rs * (g[e] - coef[c0 + e] - xh * coef[C + c0 + e]);
         }
         store_row<T, VEC>(dx, r, C, c0, out);
         if (dres) {
-            if (dres_acc) {
+            if (ACC) {
                 #pragma unroll
                 for (int e = 0; e < VEC; ++e) g[e] += old[e];
             }
@@ -340,6 +340,7 @@ static void bn_backward_t(const void* x, const void* y, const void* dy, void* dx
                           bool relu, float* partial, float* coef, int sums_row_blocks, hipStream_t st) {
     const RedShape s = red_shape(M, C, VEC);
     const double tb = (double)sizeof(T) * (double)M * C;
+    const bool fused = sums_row_blocks > 0;
     if (sums_row_blocks <= 0) {   // else the dgrad that produced dy left the sums
         ProfScope ps("bn_bwd_reduce", 0.0, tb * (relu ? 3.0 : 2.0), st);
         hipLaunchKernelGGL((colreduce_kernel<T, VEC, 1>), s.grid, s.block, 0, st, (const T*)x, (const T*)(relu ? y : x), (T*)dy, save,
@@ -351,10 +352,17 @@ static void bn_backward_t(const void* x, const void* y, const void* dy, void* dx
         hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3((C + 3) / 4), dim3(256), 0, st, partial, sums_row_blocks, M, C,
                            dgamma, dbeta, coef);
     }
-    ProfScope ps("bn_bwd_apply", 0.0, tb * ((relu ? 3.0 : 2.0) + 1.0 + (dres ? (dres_acc ? 2.0 : 1.0) : 0.0)), st);
-    hipLaunchKernelGGL((bn_bwd_apply_kernel<T, VEC>), dim3(ew_grid(M * s.cvecs)), dim3(256), 0, st, (const T*)x,
-                       (const T*)(relu ? y : x), (const T*)dy, (T*)dx, (T*)dres, (const T*)((dres && dres_acc) ? dres : dy),
-                       (dres && dres_acc) ? 1 : 0, gamma, save, coef, M, C, s.cvecs, relu ? 1 : 0);
+    // the dgrad that left the sums also left dy masked: the activation is then not read again
+    const bool mask = relu && !fused;
+    const bool acc = dres && dres_acc;
+    ProfScope ps("bn_bwd_apply", 0.0, tb * ((mask ? 3.0 : 2.0) + 1.0 + (dres ? (acc ? 2.0 : 1.0) : 0.0)), st);
+    const dim3 grid(ew_grid(M * s.cvecs));
+#define EDL_BN_BWD_APPLY(MASK, ACC)                                                                                       \
+    hipLaunchKernelGGL((bn_bwd_apply_kernel<T, VEC, MASK, ACC>), grid, dim3(256), 0, st, (const T*)x, (const T*)y, (const T*)dy, \
+                       (T*)dx, (T*)dres, gamma, save, coef, M, C, s.cvecs)
+    if (mask) { if (acc) EDL_BN_BWD_APPLY(true, true); else EDL_BN_BWD_APPLY(true, false); }
+    else { if (acc) EDL_BN_BWD_APPLY(false, true); else EDL_BN_BWD_APPLY(false, false); }
+#undef EDL_BN_BWD_APPLY
 }
 
 void launch_bn_backward(int dtype, const void* x, const void* y, const void* dy, void* dx, void* dres,
