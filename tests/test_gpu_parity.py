@@ -239,6 +239,37 @@ def test_layerwise_resnet50_bf16_at_the_benchmark_shape():
     _assert_layerwise(r, "bf16")
 
 
+_FORCED_TILE_SCRIPT = r"""
+import sys
+sys.path.insert(0, sys.argv[1]); sys.path.insert(0, sys.argv[2])
+from parity_util import TOL, layerwise_parity, forced_parity
+cases = [("resnet50", dict(H=64, W=64)), ("resnet50", dict(H=32, W=32, C=3, classes=10, arch=(8, 1, 1, 0, 0))),
+         ("vgg16", dict(H=64, W=64, arch=(64, 512))), ("resnet20", {})]
+for model, kw in cases:
+    for dtype, n in (("bf16", 9), ("f32", 5)):
+        r = layerwise_parity(model, dtype, n, verbose=False, **kw)
+        assert r["fwd"] < TOL[dtype] and r["dx"] < TOL[dtype] and r["dw"] < TOL[dtype], (model, dtype, r)
+r = forced_parity("resnet50", "bf16", 8, H=64, W=64)
+assert r["fwd"] < TOL["bf16"] and r["loss"] < TOL["bf16"] and r["grad_whole"] < 5e-2, r
+print("ok")
+"""
+
+
+@pytest.mark.parametrize("tile", [0, 1, 2, 3])
+def test_layerwise_under_every_tile_shape(tile):
+    """The tile heuristics pick one shape per layer; here every forward / dgrad launch is forced onto 128x128,
+    128x64, 128x32 or 64x64 tiles in turn (the library reads the knob once, hence the child process), on shapes
+    with ragged rows and columns, so that each kernel variant meets each kind of layer."""
+    import os
+    import subprocess
+    import sys
+    here = os.path.dirname(os.path.abspath(__file__))
+    env = dict(os.environ, EDL_TUNE_FORCE_TILE=str(tile))
+    out = subprocess.run([sys.executable, "-c", _FORCED_TILE_SCRIPT, os.path.dirname(here), here], env=env,
+                         capture_output=True, text=True, timeout=600)
+    assert out.returncode == 0 and out.stdout.strip().endswith("ok"), out.stdout[-2000:] + out.stderr[-2000:]
+
+
 def test_layerwise_vgg16_bf16_at_full_size():
     """Every layer of VGG-16 at 224x224 (reductions up to 25088 long, 200704-row outputs), four samples."""
     r = layerwise_parity("vgg16", "bf16", 4, verbose=False)
