@@ -47,6 +47,7 @@ static_assert(sizeof(SnapshotHeader) == 104, "snapshot header layout");
 struct Layout {
     int64_t params = 0, momentum = 0, second = -1, running = 0, shadow = 0, grads = 0, grad_stride = 0;
     int64_t idx = 0, labels = 0, row_loss = 0, losses = 0, partial = 0, coef = 0, wgrad_scratch = 0;
+    int64_t wide_sums = 0, wide_sums_floats = 0;   // partial column sums of launches with more row tiles than `partial` holds
     int64_t wgrad_scratch_bytes = 0;
     // partial sums of forward / dgrad reductions that are cut; apart from the weight-gradient
     // scratch because weight gradients may run on the second stream meanwhile
@@ -162,6 +163,8 @@ void plan_layout(const edl_config& c, const Graph& g, Layout& L) {
                                                            (int64_t)conv_splitk_scratch_bytes(c.dtype, geom_of(g, op, n)));
             L.splitk_scratch_bytes = std::max<int64_t>(L.splitk_scratch_bytes,
                                                        (int64_t)conv_splitk_scratch_bytes(c.dtype, geom_of(g, op, c.max_shard)));
+            L.wide_sums_floats = std::max<int64_t>(L.wide_sums_floats,
+                                                   (int64_t)conv_wide_sums_floats(c.dtype, geom_padded(g, op, c.max_shard, L.cpad)));
         } else if (op.kind == OP_BN) {
             L.bn_save[i] = take(4 * 2 * (int64_t)op.K);
         } else if (op.kind == OP_MAXPOOL) {
@@ -169,6 +172,7 @@ void plan_layout(const edl_config& c, const Graph& g, Layout& L) {
         }
     }
     L.wgrad_scratch = take(std::max<int64_t>(L.wgrad_scratch_bytes, 16));
+    L.wide_sums = take(std::max<int64_t>(4 * L.wide_sums_floats, 16));
     L.splitk_scratch = take(std::max<int64_t>(L.splitk_scratch_bytes, 16));
     L.dwpad = take(dwpad_bytes);
     L.ttable = take((int64_t)sizeof(TransposeEntry) * 2 * std::max<size_t>(no, 1));   // element-wise entries, then vector ones
@@ -459,7 +463,8 @@ static void forward_shard(edl_handle* h, const int64_t* dev_idx, int n, float* d
                 stats_row_blocks = launch_conv_fwd(dt, geom_padded(g, op, n, h->L.cpad), h->act(op.x), wsrc,
                                                    op.bias ? h->w() + op.b_off : nullptr, op.relu, g.tensors[(size_t)op.y].fp32,
                                                    h->act(op.y), h->at<float>(h->L.splitk_scratch),
-                                                   (size_t)h->L.splitk_scratch_bytes, bn_next ? partial : nullptr, st);
+                                                   (size_t)h->L.splitk_scratch_bytes, bn_next ? partial : nullptr,
+                                                   WideSums{h->at<float>(h->L.wide_sums), (size_t)h->L.wide_sums_floats}, st);
                 break;
             }
             case OP_BN: {
@@ -549,6 +554,7 @@ static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, siz
                         if (prod.relu && storage_of(g, prod.y) == sx && (prod.kind == OP_BN || prod.kind == OP_CONV)) {
                             mask.act = h->act(op.x);
                             mask.sums = partial;
+                            mask.wide = WideSums{h->at<float>(h->L.wide_sums), (size_t)h->L.wide_sums_floats};
                             if (prod.kind == OP_BN) {
                                 mask.xin = h->act(prod.x);
                                 mask.mean_rstd = h->at<float>(h->L.bn_save[ii - 1]);

@@ -102,6 +102,7 @@ struct ConvArgs {
     // (output pixels in the forward pass, the residue class's input pixels in dgrad), and for the tile grid
     unsigned long long magic_hw, magic_w, magic_gx, magic_gy;
     int stride_shift;                  // dgrad vector path: log2 of the stride (a power of two there)
+    int red_stride;                    // floats between the partial column sums of consecutive channels
     // Tile grid (gx row tiles, gy column tiles, gz cuts of the reduction), launched
     // as gx*gy*gz workgroups in one dimension.  The hardware hands consecutive
     // workgroups to the eight dies in turn and each die has its own L2, so with
@@ -1065,8 +1066,8 @@ __global__ __launch_bounds__(256, 2) void conv_igemm_kernel(ConvArgs a) {   // a
             float s1 = 0.f, s2 = 0.f;
             #pragma unroll 8
             for (int gq = 0; gq < GROUPS; ++gq) { s1 += red[gq * BN + c]; s2 += red[(GROUPS + gq) * BN + c]; }
-            sums[(int64_t)(n0 + c) * kRedRowBlocks + tile_x] = s1;
-            sums[(int64_t)(a.Nn + n0 + c) * kRedRowBlocks + tile_x] = s2;
+            sums[(int64_t)(n0 + c) * a.red_stride + tile_x] = s1;
+            sums[(int64_t)(a.Nn + n0 + c) * a.red_stride + tile_x] = s2;
         }
     }
 }
@@ -1364,7 +1365,54 @@ static ConvArgs base_args(const ConvGeom& g) {
     a.N = g.N; a.H = g.H; a.W = g.W; a.C = g.C; a.K = g.K; a.R = g.R; a.S = g.S;
     a.stride = g.stride; a.pad = g.pad; a.Ho = g.Ho; a.Wo = g.Wo;
     a.ph = a.pw = a.r0 = a.s0 = 0; a.nr = g.R; a.ns = g.S; a.Hc = g.H; a.Wc = g.W;
+    a.red_stride = kRedRowBlocks;
     return a;
+}
+
+// Partial column sums of a launch with more row tiles than the reduction scratch has room for:
+// out[r][j] = sum of wide[r][j*group .. (j+1)*group), in order; r = (sum kind, channel).
+__global__ __launch_bounds__(256) void compact_sums_kernel(const float* __restrict__ wide, int tiles, int group, int out_tiles,
+                                                           float* __restrict__ out) {
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    const int r = blockIdx.y;
+    if (j >= out_tiles) return;
+    const float* src = wide + (int64_t)r * tiles;
+    int e = (j + 1) * group;
+    if (e > tiles) e = tiles;
+    float s = 0.f;
+    for (int i = j * group; i < e; ++i) s += src[i];
+    out[(int64_t)r * kRedRowBlocks + j] = s;
+}
+
+// Where an epilogue leaves its column sums: the reduction scratch itself if the row tiles fit it, else the wide
+// buffer (compacted afterwards by finish_sums), else nowhere (nullptr: the separate reduction kernel runs).
+static float* sums_target(float* sums, const WideSums& wide, int row_tiles, int channels, int* stride) {
+    *stride = kRedRowBlocks;
+    if (sums == nullptr || row_tiles <= kRedRowBlocks) return sums;
+    if (wide.buf == nullptr || wide.floats < (size_t)2 * channels * row_tiles) return nullptr;
+    *stride = row_tiles;
+    return wide.buf;
+}
+
+// Returns the number of partial sums per channel now in `sums`.
+static int finish_sums(float* sums, const WideSums& wide, int row_tiles, int channels, hipStream_t st) {
+    if (row_tiles <= kRedRowBlocks) return row_tiles;
+    const int group = (row_tiles + kRedRowBlocks - 1) / kRedRowBlocks;
+    const int out_tiles = (row_tiles + group - 1) / group;
+    ProfScope ps("compact_sums", 0.0, 4.0 * 2.0 * channels * ((double)row_tiles + out_tiles), st);
+    hipLaunchKernelGGL(compact_sums_kernel, dim3((out_tiles + 255) / 256, 2 * channels), dim3(256), 0, st, wide.buf, row_tiles, group,
+                       out_tiles, sums);
+    return out_tiles;
+}
+
+size_t conv_wide_sums_floats(int dtype, const ConvGeom& g) {
+    (void)dtype;
+    // the narrowest row tile is 64 rows
+    const int64_t fwd_tiles = ((int64_t)g.N * g.Ho * g.Wo + 63) / 64, dgrad_tiles = ((int64_t)g.N * g.H * g.W + 63) / 64;
+    size_t need = 0;
+    if (fwd_tiles > kRedRowBlocks) need = std::max(need, (size_t)(2 * fwd_tiles * g.K));
+    if (dgrad_tiles > kRedRowBlocks && g.stride == 1) need = std::max(need, (size_t)(2 * dgrad_tiles * g.C));
+    return need;
 }
 
 // Cut of the reduction for forward / dgrad problems that give too few tiles to
@@ -1421,7 +1469,7 @@ size_t conv_splitk_scratch_bytes(int dtype, const ConvGeom& g) {
 }
 
 int launch_conv_fwd(int dtype, const ConvGeom& g, const void* x, const void* w, const float* bias, bool relu,
-                    bool out_fp32, void* y, float* scratch, size_t scratch_bytes, float* stats, hipStream_t st) {
+                    bool out_fp32, void* y, float* scratch, size_t scratch_bytes, float* stats, WideSums wide, hipStream_t st) {
     const int VEC = dtype == 1 ? 8 : 4;
     ConvArgs a = base_args(g);
     a.A = x; a.B = w; a.out = y; a.bias = bias;
@@ -1445,14 +1493,15 @@ int launch_conv_fwd(int dtype, const ConvGeom& g, const void* x, const void* w, 
     static const bool tune_stats = env_int("EDL_TUNE_FUSED_STATS", 1) != 0;
     const bool want_stats = tune_stats && stats != nullptr && !out_fp32 && conv_fast(dtype, CONV_FWD, a) && conv_magic_ok(CONV_FWD, a);
     // whole reduction in one workgroup: the epilogue leaves the sums; cut reduction: the finishing kernel does
-    const bool fused = want_stats && splits == 1 && row_tiles <= kRedRowBlocks;
-    a.stats = fused ? stats : nullptr;
+    float* const target = (want_stats && splits == 1) ? sums_target(stats, wide, row_tiles, a.Nn, &a.red_stride) : nullptr;
+    const bool fused = target != nullptr;
+    a.stats = target;
     launch_mode<CONV_FWD>(dtype, t, dim3(row_tiles, (a.Nn + bn - 1) / bn, splits), a, st);
     if (splits > 1) {
         float* fs = want_stats ? stats : nullptr;
         return dtype == 1 ? launch_finish<bf16_t>(a, splits, fs, st) : launch_finish<float>(a, splits, fs, st);
     }
-    return fused ? row_tiles : 0;
+    return fused ? finish_sums(stats, wide, row_tiles, a.Nn, st) : 0;
 }
 
 int launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dy, const void* wT, bool accumulate, void* dx,
@@ -1502,14 +1551,17 @@ int launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dy, const void* 
             // masked store and column sums in the epilogue: one launch that covers every pixel and leaves the
             // final gradient (it may add to what other readers of the tensor have left there)
             static const bool tune_mask = env_int("EDL_TUNE_FUSED_MASK", 1) != 0;
-            const bool fuse = tune_mask && mask != nullptr && mask->act != nullptr && g.stride == 1 && splits == 1 &&
-                              row_tiles <= kRedRowBlocks && conv_fast(dtype, CONV_DGRAD, a) && conv_magic_ok(CONV_DGRAD, a);
+            float* target = nullptr;
+            if (tune_mask && mask != nullptr && mask->act != nullptr && g.stride == 1 && splits == 1 &&
+                conv_fast(dtype, CONV_DGRAD, a) && conv_magic_ok(CONV_DGRAD, a))
+                target = sums_target(mask->sums, mask->wide, row_tiles, a.Nn, &a.red_stride);
+            const bool fuse = target != nullptr;
             a.mask_act = fuse ? mask->act : nullptr;
             a.xin = fuse ? mask->xin : nullptr;
             a.mean_rstd = fuse ? mask->mean_rstd : nullptr;
-            a.msum = fuse ? mask->sums : nullptr;
-            if (fuse) fused_rows = row_tiles;
+            a.msum = target;
             launch_mode<CONV_DGRAD>(dtype, t, dim3(row_tiles, (a.Nn + bn - 1) / bn, splits), a, st);
+            if (fuse) fused_rows = finish_sums(mask->sums, mask->wide, row_tiles, a.Nn, st);
             if (splits > 1) {
                 if (dtype == 1) launch_finish<bf16_t>(a, splits, nullptr, st);
                 else launch_finish<float>(a, splits, nullptr, st);

@@ -65,8 +65,13 @@ struct ConvGeom {
 // stats (may be null): the batch-norm reduction's partial-sum scratch.  If the launch can, it also leaves
 // there the per-row-tile column sums of y and y*y and returns the number of row tiles (what
 // launch_bn_forward takes as stats_row_blocks); it returns 0 if it left none.
+// Partial column sums of launches with more than kRedRowBlocks row tiles are written into `wide`
+// (2 * channels * row tiles floats, if it is large enough) and summed in groups into the standard scratch.
+struct WideSums { float* buf; size_t floats; };
 int launch_conv_fwd(int dtype, const ConvGeom& g, const void* x, const void* w, const float* bias, bool relu,
-                    bool out_fp32, void* y, float* scratch, size_t scratch_bytes, float* stats, hipStream_t st);
+                    bool out_fp32, void* y, float* scratch, size_t scratch_bytes, float* stats, WideSums wide, hipStream_t st);
+// floats `wide` must hold for this layer's forward statistics and input-gradient sums (0 if never needed)
+size_t conv_wide_sums_floats(int dtype, const ConvGeom& g);
 // What the layer that produced the convolution's input wants from the gradient dx when it ends in a ReLU:
 // dx * (act > 0), and per-channel sums of that over the rows (plain, and times (xin - mean) * rstd if xin is
 // given: a batch norm's backward sums).  sums: the column-reduction partial-sum scratch.
@@ -75,6 +80,7 @@ struct DgradMask {
     const void* xin;          // the producing batch norm's input, or null
     const float* mean_rstd;   // with xin: mean[C], rstd[C]
     float* sums;
+    WideSums wide;
 };
 // dx (+)= conv^T(dy, wT); wT is the [C][R][S][K] copy.  mask (may be null): if the launch can (stride 1, one
 // launch over all pixels, writing), dx is stored already masked and the sums are left in mask->sums; returns
