@@ -17,15 +17,20 @@
 // the same slice order, so any order is a valid contraction).
 //
 //  * loads: 16-byte buffer loads whose range check returns zeros, so padding
-//    taps, ragged edges and the reduction tail need no branch; all loads of a
-//    tile are issued back to back and land in registers while the previous
-//    tile is contracted, then go to the other of two LDS stages (one barrier
-//    per tile).  The vector kernel (FAST) has no element-wise path; a second,
-//    slow instantiation handles operands that are not vector-shaped.
-//  * forward / dgrad tiles: rows of BK elements padded by one vector
-//    (conflict-free fragment reads).  Weight-gradient tiles: the reduction
-//    index (the pixel) is the slow index in memory, so they are stored as
-//    32-bit words [pixel pair][channel]; a fragment is four one-word reads.
+//    taps, ragged edges and the reduction tail need no branch.  The vector
+//    kernel (FAST) sends them straight into LDS (buffer_load ... lds: lane L's
+//    16 bytes land at M0 + 16*L), PF+1 LDS stages deep, with explicit vmcnt
+//    waits and one barrier per tile; it has no element-wise path.  The float32
+//    weight gradient, and a second, slow instantiation for operands that are
+//    not vector-shaped, keep the register-staged path: their loads land in
+//    registers while the previous tile is contracted, then go to the other of
+//    two LDS stages.
+//  * forward / dgrad tiles: rows of BK elements; on the direct path unpadded,
+//    the 16-byte chunks of a row XOR-swizzled by the row index, otherwise padded
+//    by one vector (conflict-free fragment reads either way).  Weight-gradient
+//    tiles: the reduction index (the pixel) is the slow index in memory; bf16
+//    tiles stay [pixel][channel] and are transposed on the way out of LDS
+//    (ds_read_tr16_b64), float32 tiles are 32-bit words read one by one.
 //  * dgrad of a strided convolution runs once per residue class of the input
 //    pixel modulo the stride and contracts only the taps that reach the class.
 //  * epilogue: through LDS as float32, out as 16-byte vectors (bf16 packed by
