@@ -62,6 +62,67 @@ def committed_traffic(workload, kernel):
     return None
 
 
+def run_elastic(args, np, torch, synth_inputs, E, make_config):
+    """The elastic schedule of the fifth configuration: the aggregate batch stays 256 while the parallelism goes
+    1 -> 2 -> 4 -> 8 -> 4; at every adjustment the state image a joining worker receives is taken and restored
+    into a second job object (the joiner), which then takes the same step as the job it joined."""
+    B, N = 256, 1024
+    steps = args.steps if "--steps" in sys.argv else 10
+    schedule = [1, 2, 4, 8, 4]
+    x, y = synth_inputs.dataset(1, N, 224, 224, 3, 1000)
+    cfg = make_config("resnet50", dtype="bf16", N=N, B=B, p_max=8, max_shard=B, lr=0.1)
+    job = E.Job(cfg, 0)
+    joiner = E.Job(cfg, 7)
+    dx, dy = torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda()
+    job.bind_dataset(dx, dy)
+    joiner.bind_dataset(dx, dy)
+    for _ in range(args.warmup):
+        job.step(schedule[0], want_loss=False)
+    job.sync()
+    snap = torch.empty(job.sizes.snapshot_bytes, dtype=torch.uint8, device="cuda")
+    phases = []
+    t_all0 = time.perf_counter()
+    for i, p in enumerate(schedule):
+        snapshot_us = restore_us = None
+        if i > 0:      # an adjustment: the joiner receives the model of one existing worker
+            job.sync()
+            t0 = time.perf_counter()
+            job.snapshot(snap)
+            job.sync()
+            t1 = time.perf_counter()
+            joiner.restore(snap)
+            joiner.sync()
+            t2 = time.perf_counter()
+            snapshot_us, restore_us = (t1 - t0) * 1e6, (t2 - t1) * 1e6
+            la, lb = job.step(p), joiner.step(p)          # both continue from the same state
+            assert la == lb and joiner.progress() == job.progress(), "the joiner did not continue as the job it joined"
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            job.step(p, want_loss=False)
+        job.sync()
+        t1 = time.perf_counter()
+        phases.append(dict(p=p, shard=B // p, steps=steps, ms_per_step=round((t1 - t0) * 1e3 / steps, 3),
+                           samples_per_s=round(B * steps / (t1 - t0), 1),
+                           snapshot_us=None if snapshot_us is None else round(snapshot_us, 1),
+                           restore_us=None if restore_us is None else round(restore_us, 1)))
+    job.sync()
+    t_all1 = time.perf_counter()
+    loss = job.step(schedule[-1])
+    assert np.isfinite(loss), "training diverged"
+    total_steps = steps * len(schedule) + (len(schedule) - 1)
+    out = {
+        "metric": "training samples/s per MI355X (ResNet-50 bf16); grad-avg+update HBM GB/s",
+        "value": round(B * total_steps / (t_all1 - t_all0), 2), "unit": "samples/s", "n_gpus": 1, "steps": total_steps,
+        "warmup": args.warmup, "ms_per_step": round((t_all1 - t_all0) * 1e3 / total_steps, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "resnet50_bf16_b256_elastic", "global_batch": B, "schedule": schedule, "steps_per_phase": steps,
+                   "image": [224, 224, 3], "classes": 1000, "parameters": int(job.sizes.P), "dataset_samples": N,
+                   "snapshot_bytes": int(job.sizes.snapshot_bytes)},
+        "phases": phases,
+    }
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -71,6 +132,9 @@ def main():
     ap.add_argument("--p", type=int, default=0, help="override the parallelism (shards of the global batch)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-state-bench", action="store_true", help="skip the VGG-16-sized update / snapshot timing")
+    ap.add_argument("--elastic", action="store_true",
+                    help="the elastic schedule instead: ResNet-50 bf16, global batch 256 as p = 1, 2, 4, 8, 4 shards, "
+                         "--steps mini-batches per phase (10 if not given), a snapshot and a joiner's restore at every adjustment")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the p workers are shards of the batch on that GPU); "
@@ -86,6 +150,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    if args.elastic:
+        run_elastic(args, np, torch, synth_inputs, E, make_config)
+        return
     model, dtype, N, B, p, geom, lr = WORKLOADS[args.workload]
     if args.p:
         p = args.p

@@ -341,6 +341,29 @@ def test_free_running_resnet50_bf16():
     assert r["loss"] < 0.1, r
 
 
+def test_config5_elastic_schedule_resnet50_bf16():
+    """The elastic schedule: the aggregate batch stays fixed while p goes 1 -> 2 -> 4 -> 8 -> 4 (here on 64x64
+    images, batch 32, one mini-batch per phase).  The shard index sets are the oracle's bit for bit at every p
+    (asserted inside run_parity), the losses follow the oracle's, and at every adjustment a joiner that receives
+    the state image continues exactly as the job it joined."""
+    torch = _torch()
+    import paper_1909_11985_amd as E
+    schedule = [1, 2, 4, 8, 4]
+    r = run_parity("resnet50", "bf16", N=64, B=32, schedule=schedule, H=64, W=64, lr=0.002, check_every_step=False)
+    assert r["loss_steps"][0] < TOL["bf16"], r
+    assert r["loss"] < 0.1, r
+    assert r["job"].progress() == (5, 2, 1)
+    job = r["job"]
+    joiner = E.Job(job.cfg, 123)
+    joiner.bind_dataset(*job._data)
+    for p in schedule:
+        snap = job.snapshot()
+        joiner.restore(snap)
+        assert joiner.progress() == job.progress()
+        assert job.step(p) == joiner.step(p)
+        assert np.array_equal(job.params(), joiner.params()) and np.array_equal(job.running(), joiner.running())
+
+
 # ---------------------------------------------------------------- training on the dynamic data pipeline's batches
 def test_training_on_pipeline_batches_with_joins_and_exits():
     """The library's data pipeline (8 partitions of 12 samples) feeds edl_step while workers join and leave at
