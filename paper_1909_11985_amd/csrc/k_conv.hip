@@ -195,12 +195,19 @@ template <> struct Frag<float> {
 };
 
 // bf16 wgrad tiles in LDS: row = pixel of the reduction step, WIDTH channels per row, no padding; the
-// 16-channel (32-byte) chunks of a row are permuted by the row's low bits, so that the four pixel rows a
-// 16-lane group reads at once fall into different banks.
+// 16-channel (32-byte) chunks of a row are permuted by the row's low bits.  A transposing read (tr_frag) takes,
+// per 32 lanes, two neighbouring chunks of four consecutive pixel rows; those eight 32-byte pieces must fall
+// into the eight different 32-byte bank groups.  Rows of 256 bytes (WIDTH 128) all start at the same bank, so
+// the row moves its chunk pair by two chunks per row (XOR with 2 * (pixel % 4); XOR with pixel % 4, as the
+// narrower tiles use, would put the pairs of rows 0/1 and 2/3 on top of each other: measured as 11% of the
+// kernel's time in LDS bank conflicts).  Rows of 128 and 64 bytes are already spread by their own offsets.
+template <int WIDTH>
+__device__ __forceinline__ int wg_swizzle(int pixel) {
+    return WIDTH >= 128 ? ((pixel & 3) << 1) : WIDTH >= 64 ? (pixel & 3) : (pixel & (WIDTH / 16 - 1));
+}
 template <int WIDTH>
 __device__ __forceinline__ int wg_lds_index(int pixel, int ch) {
-    constexpr int MASK = WIDTH / 16 >= 4 ? 3 : WIDTH / 16 - 1;
-    return pixel * WIDTH + ((((ch >> 4) ^ (pixel & MASK)) << 4) | (ch & 15));
+    return pixel * WIDTH + ((((ch >> 4) ^ wg_swizzle<WIDTH>(pixel)) << 4) | (ch & 15));
 }
 
 // MFMA operand of a 32-channel tile for reduction pixels [p16 + 8*(lane/32), +8) from such an LDS tile.
@@ -437,12 +444,11 @@ __global__ __launch_bounds__(256, 2) void conv_igemm_kernel(ConvArgs a) {   // a
             offB[it] = (int64_t)j * a.ldb;
         }
     } else if (DIRECT_WG) {
-        // slot p of pixel row x holds the 8 channels starting at (((p >> 1) ^ (x & MASK)) << 4) | ((p & 1) << 3)
+        // slot p of pixel row x holds the 8 channels starting at (((p >> 1) ^ wg_swizzle(x)) << 4) | ((p & 1) << 3)
         // (wg_lds_index); a lane's pixels are a multiple of 4 apart, so its channels are the same in all of them
-        constexpr int MASKA = BM / 16 >= 4 ? 3 : BM / 16 - 1, MASKB = BN / 16 >= 4 ? 3 : BN / 16 - 1;
         const int pa = tid % RVA, pb = tid % RVB;
-        const int chA = ((((pa >> 1) ^ ((tid / RVA) & MASKA)) << 4) | ((pa & 1) << 3));
-        const int chB = ((((pb >> 1) ^ ((tid / RVB) & MASKB)) << 4) | ((pb & 1) << 3));
+        const int chA = ((((pa >> 1) ^ wg_swizzle<BM>(tid / RVA)) << 4) | ((pa & 1) << 3));
+        const int chB = ((((pb >> 1) ^ wg_swizzle<BN>(tid / RVB)) << 4) | ((pb & 1) << 3));
         rowA_ok = m0 + chA < a.M;
         const int j0 = n0 + chB;
         const int tap = j0 / a.C;
