@@ -509,6 +509,7 @@ static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, siz
     bool used_side = false;
     size_t fused_for = (size_t)-1;   // the layer whose masked gradient and column sums the dgrad after it left
     int fused_rows = 0;
+    size_t premasked_for = (size_t)-1;   // the layer whose gradient the max pool after it left masked by its ReLU
     for (size_t ii = op_hi; ii-- > op_lo;) {
         const Op& op = g.ops[ii];
         switch (op.kind) {
@@ -520,7 +521,7 @@ static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, siz
                 const int64_t M = (int64_t)n * q.Ho * q.Wo;
                 const bool padded = h->L.wpad[ii] >= 0;
                 launch_bias_relu_backward(dt, h->act(op.y), h->grad(op.y), op.bias ? G + op.b_off : nullptr, M, op.K,
-                                          op.relu, partial, fused_for == ii ? fused_rows : 0, st);
+                                          op.relu && premasked_for != ii, partial, fused_for == ii ? fused_rows : 0, st);
                 // The weight gradient needs only dy (final from here on) and the layer's input, and nothing
                 // before the update reads it: it runs on the second stream, beside the chain of input
                 // gradients, whose short kernels leave part of the chip idle.
@@ -582,7 +583,8 @@ static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, siz
                 }
                 launch_bn_backward(dt, h->act(op.x), h->act(op.y), h->grad(op.y), h->grad(op.x), dres, dres_acc,
                                    h->w() + op.w_off, h->at<float>(h->L.bn_save[ii]), G + op.w_off, G + op.b_off,
-                                   (int64_t)n * t.H * t.W, t.C, op.relu, partial, coef, fused_for == ii ? fused_rows : 0, st);
+                                   (int64_t)n * t.H * t.W, t.C, op.relu && premasked_for != ii, partial, coef,
+                                   fused_for == ii ? fused_rows : 0, st);
                 written[(size_t)sx] = 1;
                 break;
             }
@@ -591,9 +593,18 @@ static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, siz
                 const Tensor& ty = g.tensors[(size_t)op.y];
                 const int sx = storage_of(g, op.x);
                 if (sx != 0) {
-                    launch_maxpool_backward(dt, h->grad(op.y), h->at<uint8_t>(h->L.pool_arg[ii]), h->grad(op.x),
-                                            written[(size_t)sx] != 0, n, tx.H, tx.W, tx.C, op.R, op.stride, op.pad, ty.H,
-                                            ty.W, st);
+                    // a ReLU layer just before in the list whose output only this pool reads: its gradient can leave
+                    // the pool already masked
+                    const void* relu_act = nullptr;
+                    if (ii > op_lo && written[(size_t)sx] == 0 && h->readers[(size_t)sx] == 1) {
+                        const Op& prod = g.ops[ii - 1];
+                        if (prod.relu && storage_of(g, prod.y) == sx && (prod.kind == OP_BN || prod.kind == OP_CONV))
+                            relu_act = h->act(op.x);
+                    }
+                    if (launch_maxpool_backward(dt, h->grad(op.y), h->at<uint8_t>(h->L.pool_arg[ii]), h->grad(op.x),
+                                                written[(size_t)sx] != 0, n, tx.H, tx.W, tx.C, op.R, op.stride, op.pad, ty.H,
+                                                ty.W, relu_act, st))
+                        premasked_for = ii - 1;
                     written[(size_t)sx] = 1;
                 }
                 break;

@@ -175,10 +175,12 @@ __global__ __launch_bounds__(256) void maxpool_bwd_vec_kernel(const T* __restric
 // The same with the window positions that can reach an input pixel enumerated without branches: at most
 // NC = ceil(k / stride) per dimension.  All NC*NC loads are issued before the first use (a position outside
 // the output reads a clamped one and is ignored), instead of one load and one wait per tap.
-template <typename T, int NC>
+// MASK: the pooled tensor is the output of a ReLU; the gradient is stored already multiplied by (act > 0),
+// so that the producer's backward need not read its activation again.
+template <typename T, int NC, bool MASK>
 __global__ __launch_bounds__(256) void maxpool_bwd_win_kernel(const T* __restrict__ dy, const uint8_t* __restrict__ arg,
-                                                              T* dx, int accumulate, int N, int H, int W, int C, int k,
-                                                              int stride, int pad, int Ho, int Wo) {
+                                                              T* dx, const T* __restrict__ act, int accumulate, int N, int H,
+                                                              int W, int C, int k, int stride, int pad, int Ho, int Wo) {
     constexpr int VEC = Elem<T>::VEC;
     const int cv = C / VEC;
     const int64_t total = (int64_t)N * H * W * cv;
@@ -211,9 +213,10 @@ __global__ __launch_bounds__(256) void maxpool_bwd_win_kernel(const T* __restric
         }
     }
     const int64_t xo = (((int64_t)n * H + h) * W + w) * C + c0;
-    Vec16<T> old;
+    Vec16<T> old, av;
     old.u = make_uint4(0, 0, 0, 0);
     if (accumulate) old = load_vec(dx + xo);
+    if (MASK) av = load_vec(act + xo);
     float g[VEC];
     #pragma unroll
     for (int e = 0; e < VEC; ++e) g[e] = 0.f;
@@ -233,7 +236,7 @@ __global__ __launch_bounds__(256) void maxpool_bwd_win_kernel(const T* __restric
     }
     Vec16<T> out;
     #pragma unroll
-    for (int e = 0; e < VEC; ++e) out.e[e] = Elem<T>::from_f32(g[e]);
+    for (int e = 0; e < VEC; ++e) out.e[e] = Elem<T>::from_f32((!MASK || Elem<T>::to_f32(av.e[e]) > 0.f) ? g[e] : 0.f);
     store_vec(dx + xo, out);
 }
 
@@ -261,23 +264,32 @@ void launch_maxpool_forward(int dtype, const void* x, void* y, uint8_t* arg, int
                            W, C, k, stride, pad, Ho, Wo);
 }
 
-void launch_maxpool_backward(int dtype, const void* dy, const uint8_t* arg, void* dx, bool accumulate, int N, int H,
-                             int W, int C, int k, int stride, int pad, int Ho, int Wo, hipStream_t st) {
+bool launch_maxpool_backward(int dtype, const void* dy, const uint8_t* arg, void* dx, bool accumulate, int N, int H,
+                             int W, int C, int k, int stride, int pad, int Ho, int Wo, const void* relu_act, hipStream_t st) {
     const int grid = ew_grid((int64_t)N * H * W * C);
     const double esz = dtype == 1 ? 2.0 : 4.0;
-    ProfScope ps("maxpool_bwd", 0.0, esz * (double)N * H * W * C * (accumulate ? 2.0 : 1.0) + (esz + 1.0) * (double)N * Ho * Wo * C, st);
     const int vec = dtype == 1 ? 8 : 4;
+    const int nc = (k + stride - 1) / stride;
+    const int64_t lanes = C % vec == 0 ? (int64_t)N * H * W * (C / vec) : 0;
+    const bool win = C % vec == 0 && nc <= 2 && lanes < (int64_t)1 << 38;
+    const bool masked = win && relu_act != nullptr && !accumulate;
+    ProfScope ps("maxpool_bwd", 0.0, esz * (double)N * H * W * C * ((accumulate ? 2.0 : 1.0) + (masked ? 1.0 : 0.0)) + (esz + 1.0) * (double)N * Ho * Wo * C, st);
     if (C % vec == 0) {
         const int vgrid = ew_grid((int64_t)N * H * W * (C / vec));
-        const int nc = (k + stride - 1) / stride;
-        const int64_t lanes = (int64_t)N * H * W * (C / vec);
-        if (nc <= 2 && lanes < (int64_t)1 << 38) {
+        if (win) {
             const dim3 g1((unsigned)((lanes + 255) / 256));
-            if (dtype == 1 && nc == 1) hipLaunchKernelGGL((maxpool_bwd_win_kernel<bf16_t, 1>), g1, dim3(256), 0, st, (const bf16_t*)dy, arg, (bf16_t*)dx, accumulate ? 1 : 0, N, H, W, C, k, stride, pad, Ho, Wo);
-            else if (dtype == 1) hipLaunchKernelGGL((maxpool_bwd_win_kernel<bf16_t, 2>), g1, dim3(256), 0, st, (const bf16_t*)dy, arg, (bf16_t*)dx, accumulate ? 1 : 0, N, H, W, C, k, stride, pad, Ho, Wo);
-            else if (nc == 1) hipLaunchKernelGGL((maxpool_bwd_win_kernel<float, 1>), g1, dim3(256), 0, st, (const float*)dy, arg, (float*)dx, accumulate ? 1 : 0, N, H, W, C, k, stride, pad, Ho, Wo);
-            else hipLaunchKernelGGL((maxpool_bwd_win_kernel<float, 2>), g1, dim3(256), 0, st, (const float*)dy, arg, (float*)dx, accumulate ? 1 : 0, N, H, W, C, k, stride, pad, Ho, Wo);
-            return;
+#define EDL_POOL_BWD(TT, NCC, MM)                                                                                               \
+    hipLaunchKernelGGL((maxpool_bwd_win_kernel<TT, NCC, MM>), g1, dim3(256), 0, st, (const TT*)dy, arg, (TT*)dx, (const TT*)relu_act, \
+                       accumulate ? 1 : 0, N, H, W, C, k, stride, pad, Ho, Wo)
+            if (dtype == 1) {
+                if (nc == 1) { if (masked) EDL_POOL_BWD(bf16_t, 1, true); else EDL_POOL_BWD(bf16_t, 1, false); }
+                else { if (masked) EDL_POOL_BWD(bf16_t, 2, true); else EDL_POOL_BWD(bf16_t, 2, false); }
+            } else {
+                if (nc == 1) { if (masked) EDL_POOL_BWD(float, 1, true); else EDL_POOL_BWD(float, 1, false); }
+                else { if (masked) EDL_POOL_BWD(float, 2, true); else EDL_POOL_BWD(float, 2, false); }
+            }
+#undef EDL_POOL_BWD
+            return masked;
         }
         if (dtype == 1)
             hipLaunchKernelGGL(maxpool_bwd_vec_kernel<bf16_t>, dim3(vgrid), dim3(256), 0, st, (const bf16_t*)dy, arg,
@@ -285,7 +297,7 @@ void launch_maxpool_backward(int dtype, const void* dy, const uint8_t* arg, void
         else
             hipLaunchKernelGGL(maxpool_bwd_vec_kernel<float>, dim3(vgrid), dim3(256), 0, st, (const float*)dy, arg, (float*)dx,
                                accumulate ? 1 : 0, N, H, W, C, k, stride, pad, Ho, Wo);
-        return;
+        return false;
     }
     if (dtype == 1)
         hipLaunchKernelGGL(maxpool_bwd_kernel<bf16_t>, dim3(grid), dim3(256), 0, st, (const bf16_t*)dy, arg, (bf16_t*)dx,
@@ -293,6 +305,7 @@ void launch_maxpool_backward(int dtype, const void* dy, const uint8_t* arg, void
     else
         hipLaunchKernelGGL(maxpool_bwd_kernel<float>, dim3(grid), dim3(256), 0, st, (const float*)dy, arg, (float*)dx,
                            accumulate ? 1 : 0, N, H, W, C, k, stride, pad, Ho, Wo);
+    return false;
 }
 
 // ---------------------------------------------------------------------------

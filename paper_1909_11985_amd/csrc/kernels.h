@@ -115,8 +115,10 @@ void launch_bias_relu_backward(int dtype, const void* y, void* dy, float* dbias,
 // ---- pooling --------------------------------------------------------------
 void launch_maxpool_forward(int dtype, const void* x, void* y, uint8_t* arg, int N, int H, int W, int C, int k,
                             int stride, int pad, int Ho, int Wo, hipStream_t st);
-void launch_maxpool_backward(int dtype, const void* dy, const uint8_t* arg, void* dx, bool accumulate, int N, int H,
-                             int W, int C, int k, int stride, int pad, int Ho, int Wo, hipStream_t st);
+// relu_act: if the pooled tensor is the output of a ReLU layer with no other reader, that output; the gradient is
+// then stored multiplied by (relu_act > 0) where the kernel taken supports it.  Returns whether it was.
+bool launch_maxpool_backward(int dtype, const void* dy, const uint8_t* arg, void* dx, bool accumulate, int N, int H,
+                             int W, int C, int k, int stride, int pad, int Ho, int Wo, const void* relu_act, hipStream_t st);
 void launch_gavgpool_forward(int dtype, const void* x, void* y, int N, int HW, int C, hipStream_t st);
 void launch_gavgpool_backward(int dtype, const void* dy, void* dx, bool accumulate, int N, int HW, int C,
                               hipStream_t st);
