@@ -49,6 +49,7 @@ struct Layout {
     int64_t idx = 0, labels = 0, row_loss = 0, losses = 0, partial = 0, coef = 0, wgrad_scratch = 0;
     int64_t wide_sums = 0, wide_sums_floats = 0;   // partial column sums of launches with more row tiles than `partial` holds
     int64_t wgrad_scratch_bytes = 0;
+    int64_t wgrad_scratch2 = 0;          // for the few weight gradients that run on the main stream beside the second one
     // partial sums of forward / dgrad reductions that are cut; apart from the weight-gradient
     // scratch because weight gradients may run on the second stream meanwhile
     int64_t splitk_scratch = 0, splitk_scratch_bytes = 0;
@@ -172,6 +173,7 @@ void plan_layout(const edl_config& c, const Graph& g, Layout& L) {
         }
     }
     L.wgrad_scratch = take(std::max<int64_t>(L.wgrad_scratch_bytes, 16));
+    L.wgrad_scratch2 = take(std::max<int64_t>(L.wgrad_scratch_bytes, 16));
     L.wide_sums = take(std::max<int64_t>(4 * L.wide_sums_floats, 16));
     L.splitk_scratch = take(std::max<int64_t>(L.splitk_scratch_bytes, 16));
     L.dwpad = take(dwpad_bytes);
@@ -526,7 +528,14 @@ static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, siz
                 // before the update reads it: it runs on the second stream, beside the chain of input
                 // gradients, whose short kernels leave part of the chip idle.
                 hipStream_t ws = st;
-                if (overlap) {
+                // The first layers' weight gradients are the last of the pass: by then the main stream has nothing
+                // else to do, so they stay on it (with a scratch of their own) and run beside the second stream's backlog.
+                static const int tail_main = getenv("EDL_TUNE_WGRAD_TAIL_MAIN") ? atoi(getenv("EDL_TUNE_WGRAD_TAIL_MAIN")) : 1;
+                int conv_ordinal = 0;
+                for (size_t j = 0; j < ii; ++j) conv_ordinal += g.ops[j].kind == OP_CONV;
+                const bool on_main = overlap && conv_ordinal < tail_main;
+                float* const wscratch = h->at<float>(on_main ? h->L.wgrad_scratch2 : h->L.wgrad_scratch);
+                if (overlap && !on_main) {
                     hipEvent_t ev = h->ev_ready[h->ev_slot];
                     h->ev_slot = (h->ev_slot + 1) % kReadyEvents;
                     if (hipEventRecord(ev, st) == hipSuccess && hipStreamWaitEvent(h->side, ev, 0) == hipSuccess) {
@@ -535,7 +544,7 @@ static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, siz
                     }
                 }
                 launch_conv_wgrad(dt, q, h->act(op.x), h->grad(op.y), padded ? h->at<float>(h->L.dwpad) : G + op.w_off,
-                                  h->at<float>(h->L.wgrad_scratch), (size_t)h->L.wgrad_scratch_bytes, ws);
+                                  wscratch, (size_t)h->L.wgrad_scratch_bytes, ws);
                 if (padded)
                     launch_unpad_rows(h->at<float>(h->L.dwpad), G + op.w_off, (int64_t)op.K * op.R * op.S, g.tensors[0].C, h->L.cpad, ws);
                 const int sx = storage_of(g, op.x);
