@@ -618,6 +618,39 @@ def test_step_is_deterministic():
     assert np.array_equal(a["job"].params(), b["job"].params())
 
 
+_STREAM_SCRIPT = r"""
+import sys, hashlib
+sys.path.insert(0, sys.argv[1]); sys.path.insert(0, sys.argv[2])
+import numpy as np, torch, synth_inputs
+import paper_1909_11985_amd as E
+from paper_1909_11985_amd.binding import make_config
+N, B = 64, 32
+x, y = synth_inputs.dataset(1, N, 64, 64, 3, 1000)
+cfg = make_config("resnet50", dtype="bf16", N=N, B=B, p_max=4, max_shard=B, lr=0.002, H=64, W=64)
+job = E.Job(cfg, 0)
+job.bind_dataset(torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda())
+for p in (1, 2, 4, 1):
+    job.step(p)
+print(hashlib.sha256(job.params().tobytes() + job.momentum().tobytes() + job.running().tobytes()).hexdigest())
+"""
+
+
+def test_the_second_stream_does_not_change_the_result():
+    """Weight gradients run on a second stream beside the input-gradient chain (the first layer's on the main
+    one): the model after four steps is bit for bit the one of a run that keeps everything on one stream."""
+    import os
+    import subprocess
+    import sys
+    here = os.path.dirname(os.path.abspath(__file__))
+    digests = []
+    for env_extra in ({}, {"EDL_TUNE_WGRAD_STREAM": "0"}, {"EDL_TUNE_WGRAD_TAIL_MAIN": "0"}):
+        out = subprocess.run([sys.executable, "-c", _STREAM_SCRIPT, os.path.dirname(here), here], env=dict(os.environ, **env_extra),
+                             capture_output=True, text=True, timeout=300)
+        assert out.returncode == 0, out.stdout[-2000:] + out.stderr[-2000:]
+        digests.append(out.stdout.strip().splitlines()[-1])
+    assert digests[0] == digests[1] == digests[2], digests
+
+
 # ---------------------------------------------------------------- argument checking
 def test_step_rejects_bad_requests():
     torch = _torch()
