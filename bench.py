@@ -135,7 +135,12 @@ def main():
     ap.add_argument("--elastic", action="store_true",
                     help="the elastic schedule instead: ResNet-50 bf16, global batch 256 as p = 1, 2, 4, 8, 4 shards, "
                          "--steps mini-batches per phase (10 if not given), a snapshot and a joiner's restore at every adjustment")
+    ap.add_argument("--by-layer-shape", action="store_true",
+                    help="name every contraction in the kernel list by its layer shape (one line per distinct shape, "
+                         "none cut off) instead of by tile family; the roofline object then names the slowest shape")
     args = ap.parse_args()
+    if args.by_layer_shape:
+        os.environ["EDL_PROFILE_BY_SHAPE"] = "1"      # read by the library at its first contraction launch
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the p workers are shards of the batch on that GPU); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
@@ -363,7 +368,7 @@ def main():
         "config": {"workload": args.workload, "global_batch": B, "p": p, "shard": B // p, "image": [H, W, C],
                    "classes": classes, "parameters": job_P, "dataset_samples": N},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "step": step_summary,
-        "update": update, "snapshot": snapshot, "attainable": attainable, "kernels": kernels[:24],
+        "update": update, "snapshot": snapshot, "attainable": attainable, "kernels": kernels if args.by_layer_shape else kernels[:24],
     }
     print(json.dumps(out))
 

@@ -1600,7 +1600,7 @@ static WgradPlan plan_wgrad(const ConvGeom& g) {
     if (Nn <= 32) p.t = T128x32;
     else if (M <= 64 || Nn <= 64) p.t = (Nn <= 64 && M >= 128) ? T128x64 : T64x64;
     else if (t128 >= 128) p.t = T128x128;
-    else if (t64 >= 256) p.t = T64x64;
+    else if (t64 >= 256 && Kred < 4096) p.t = T64x64;   // long reductions are cut instead (below)
     else p.t = T128x128;
     switch (p.t) {
         case T128x128: p.bm = 128; p.bn = 128; break;
@@ -1611,6 +1611,14 @@ static WgradPlan plan_wgrad(const ConvGeom& g) {
     p.tiles = (int64_t)((M + p.bm - 1) / p.bm) * ((Nn + p.bn - 1) / p.bn);
     static const int target = env_int("EDL_TUNE_WGRAD_BLOCKS", 256);
     int64_t splits = (target + p.tiles - 1) / p.tiles;
+    // A long reduction (VGG-16's layers on large images at a shard of 32) is cut into two workgroups per CU
+    // (all that are resident at once), as long as each cut keeps long_ks elements: the partial results are
+    // small beside the operands there, and a second workgroup hides the operand latency that one per CU
+    // leaves exposed.  Measured on VGG-16: 5.28 -> 5.14 ms per step; three per CU (a second, ragged round
+    // of workgroups) is slower again.
+    static const int long_target = env_int("EDL_TUNE_WGRAD_LONG_BLOCKS", 512), long_ks = env_int("EDL_TUNE_WGRAD_LONG_KS", 3072);
+    const int64_t more = std::min<int64_t>(long_target / p.tiles, Kred / (long_ks > 0 ? long_ks : 1));
+    if (more > splits) splits = more;
     const int64_t max_splits = (Kred + 255) / 256;  // at least 4 reduction steps per split
     if (splits > max_splits) splits = max_splits;
     if (splits < 1) splits = 1;
