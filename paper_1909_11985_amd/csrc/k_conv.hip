@@ -1221,8 +1221,11 @@ static int env_int(const char* name, int dflt) {
 // short_fwd: a problem whose epilogue is most of the workgroup's time (a forward pass of one or two
 // reduction steps, an input-gradient pass whose epilogue adds, masks and sums); twice as many workgroups of
 // half the width measured faster there
-static TileCfg pick_tile(int M, int Nn, int* bm, int* bn, bool short_fwd = false) {
-    static const int min128 = env_int("EDL_TUNE_MIN128", 256);
+static TileCfg pick_tile(int M, int Nn, int Kred, int* bm, int* bn, bool short_fwd = false) {
+    // A long reduction takes the 128x128 tile from fewer tiles on (the reduction is cut to fill the chip):
+    // VGG-16's 14x14 layers, 196 tiles, measured 64 -> 48 us forward and 71 -> 47 us dgrad.
+    static const int min128_short = env_int("EDL_TUNE_MIN128", 256), min128_long = env_int("EDL_TUNE_MIN128_LONG", 160);
+    const int min128 = Kred >= 4096 ? std::min(min128_short, min128_long) : min128_short;
     TileCfg t;
     if (Nn <= 32) t = T128x32;
     else if (Nn <= 64) t = (M >= 128) ? T128x64 : T64x64;
@@ -1472,7 +1475,7 @@ size_t conv_splitk_scratch_bytes(int dtype, const ConvGeom& g) {
         const int Nn = mode == 0 ? g.K : g.C;
         const int Kred = mode == 0 ? g.R * g.S * g.C : g.R * g.S * g.K;
         int bm, bn, ks;
-        pick_tile(M, Nn, &bm, &bn, mode == 0 && Kred <= 128);
+        pick_tile(M, Nn, Kred, &bm, &bn, mode == 0 && Kred <= 128);
         const int splits = plan_splitk(dtype, M, Nn, Kred, bm, bn, &ks);
         if (splits > 1) need = std::max(need, (size_t)splits * M * Nn * sizeof(float));
     }
@@ -1493,7 +1496,7 @@ int launch_conv_fwd(int dtype, const ConvGeom& g, const void* x, const void* w, 
     a.ksplit = a.Kred;
     a.ldb = a.Kred;
     int bm, bn;
-    const TileCfg t = pick_tile(a.M, a.Nn, &bm, &bn, a.Kred <= 128);
+    const TileCfg t = pick_tile(a.M, a.Nn, a.Kred, &bm, &bn, a.Kred <= 128);
     int splits = 1, ks = a.Kred;
     if (conv_fast(dtype, CONV_FWD, a)) {
         splits = plan_splitk(dtype, a.M, a.Nn, a.Kred, bm, bn, &ks);
@@ -1551,7 +1554,7 @@ int launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dy, const void* 
             // -0.4% of the ResNet-50 step, 64x64 tiles +1.5%)
             static const int join_tile = env_int("EDL_TUNE_JOIN_TILE", 1);
             const bool heavy = join_tile != 0 && mask != nullptr && mask->act != nullptr && accumulate && g.stride == 1;
-            const TileCfg t = pick_tile(a.M, a.Nn, &bm, &bn, heavy);
+            const TileCfg t = pick_tile(a.M, a.Nn, a.Kred, &bm, &bn, heavy);
             int splits = 1, ks = a.ksplit;
             if (g.stride == 1 && conv_fast(dtype, CONV_DGRAD, a)) {
                 splits = plan_splitk(dtype, a.M, a.Nn, a.Kred, bm, bn, &ks);
