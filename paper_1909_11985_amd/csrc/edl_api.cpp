@@ -46,7 +46,7 @@ static_assert(sizeof(SnapshotHeader) == 104, "snapshot header layout");
 
 struct Layout {
     int64_t params = 0, momentum = 0, second = -1, running = 0, shadow = 0, grads = 0, grad_stride = 0;
-    int64_t idx = 0, labels = 0, row_loss = 0, losses = 0, partial = 0, coef = 0, wgrad_scratch = 0;
+    int64_t idx = 0, labels = 0, row_loss = 0, losses = 0, partial = 0, partial_held = 0, coef = 0, wgrad_scratch = 0;
     int64_t wide_sums = 0, wide_sums_floats = 0;   // partial column sums of launches with more row tiles than `partial` holds
     int64_t wgrad_scratch_bytes = 0;
     int64_t wgrad_scratch2 = 0;          // for the few weight gradients that run on the main stream beside the second one
@@ -128,6 +128,9 @@ void plan_layout(const edl_config& c, const Graph& g, Layout& L) {
     for (const Op& op : g.ops)
         if (op.kind == OP_CONV || op.kind == OP_BN) cmax = std::max(cmax, op.K);
     L.partial = take(4 * 2 * (int64_t)kRedRowBlocks * cmax);
+    // a second one for sums that wait while another batch norm runs (a block's last convolution, whose
+    // batch norm comes after the projection shortcut's)
+    L.partial_held = take(4 * 2 * (int64_t)kRedRowBlocks * cmax);
     L.coef = take(4 * 2 * (int64_t)cmax);
     const size_t nt = g.tensors.size();
     L.act.assign(nt, -1);
@@ -454,6 +457,9 @@ static void forward_shard(edl_handle* h, const int64_t* dev_idx, int n, float* d
     }
     if (op_hi > g.ops.size()) op_hi = g.ops.size();
     int stats_row_blocks = 0;   // > 0: the convolution just launched left the next batch norm's partial sums
+    // the same for a convolution whose batch norm is not the next op: its sums wait in a buffer of their own
+    float* const partial_held = h->at<float>(h->L.partial_held);
+    int held_rows = 0, held_tensor = -1;
     for (size_t i = op_lo; i < op_hi; ++i) {
         const Op& op = g.ops[i];
         switch (op.kind) {
@@ -462,19 +468,34 @@ static void forward_shard(edl_handle* h, const int64_t* dev_idx, int n, float* d
                 if (h->L.wpad[i] >= 0) wsrc = h->arena + h->L.wpad[i];
                 // the batch norm that follows (in this call) can take its sums from the convolution's epilogue
                 const bool bn_next = i + 1 < op_hi && g.ops[i + 1].kind == OP_BN && g.ops[i + 1].x == op.y;
-                stats_row_blocks = launch_conv_fwd(dt, geom_padded(g, op, n, h->L.cpad), h->act(op.x), wsrc,
-                                                   op.bias ? h->w() + op.b_off : nullptr, op.relu, g.tensors[(size_t)op.y].fp32,
-                                                   h->act(op.y), h->at<float>(h->L.splitk_scratch),
-                                                   (size_t)h->L.splitk_scratch_bytes, bn_next ? partial : nullptr,
-                                                   WideSums{h->at<float>(h->L.wide_sums), (size_t)h->L.wide_sums_floats}, st);
+                // ... or a later one of this call, if the held buffer is free
+                static const bool tune_held = getenv("EDL_TUNE_HELD_STATS") == nullptr || atoi(getenv("EDL_TUNE_HELD_STATS")) != 0;
+                bool bn_later = false;
+                if (!bn_next && tune_held && held_tensor < 0)
+                    for (size_t j = i + 2; j < op_hi && j <= i + 4 && !bn_later; ++j)
+                        bn_later = g.ops[j].kind == OP_BN && g.ops[j].x == op.y;
+                const int rows = launch_conv_fwd(dt, geom_padded(g, op, n, h->L.cpad), h->act(op.x), wsrc,
+                                                 op.bias ? h->w() + op.b_off : nullptr, op.relu, g.tensors[(size_t)op.y].fp32,
+                                                 h->act(op.y), h->at<float>(h->L.splitk_scratch),
+                                                 (size_t)h->L.splitk_scratch_bytes,
+                                                 bn_next ? partial : bn_later ? partial_held : nullptr,
+                                                 WideSums{h->at<float>(h->L.wide_sums), (size_t)h->L.wide_sums_floats}, st);
+                if (bn_later) {
+                    if (rows > 0) { held_rows = rows; held_tensor = op.y; }
+                    stats_row_blocks = 0;
+                } else {
+                    stats_row_blocks = rows;
+                }
                 break;
             }
             case OP_BN: {
                 const Tensor& t = g.tensors[(size_t)op.x];
+                const bool held = held_tensor == op.x && held_rows > 0;
                 launch_bn_forward(dt, h->act(op.x), op.res >= 0 ? h->act(op.res) : nullptr, h->act(op.y), h->w() + op.w_off,
                                   h->w() + op.b_off, h->at<float>(h->L.bn_save[i]),
                                   update_running ? h->running() + op.run_off : nullptr, (int64_t)n * t.H * t.W, t.C, op.relu,
-                                  partial, stats_row_blocks, st);
+                                  held ? partial_held : partial, held ? held_rows : stats_row_blocks, st);
+                if (held) { held_rows = 0; held_tensor = -1; }
                 stats_row_blocks = 0;
                 break;
             }

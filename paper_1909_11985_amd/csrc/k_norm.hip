@@ -303,7 +303,7 @@ static void bn_forward_t(const void* x, const void* res, void* y, const float* g
     const RedShape s = red_shape(M, C, VEC);
     const double tb = (double)sizeof(T) * (double)M * C;   // bytes of one [M][C] tensor
     if (stats_row_blocks <= 0) {   // else the producer of x left the partial sums
-        ProfScope ps("bn_stats", 0.0, tb, st);
+        ProfScope ps(prof_shape_label("bn_stats", M, C), 0.0, tb, st);
         hipLaunchKernelGGL((colreduce_kernel<T, VEC, 0>), s.grid, s.block, 0, st, (const T*)x, (const T*)nullptr, (T*)nullptr,
                            (const float*)nullptr, M, C, s.rows_per_block, 0, partial);
         stats_row_blocks = s.row_blocks;
@@ -313,7 +313,7 @@ static void bn_forward_t(const void* x, const void* res, void* y, const float* g
         hipLaunchKernelGGL(bn_stats_finalize_kernel, dim3((C + 3) / 4), dim3(256), 0, st, partial, stats_row_blocks, M, C,
                            save, running);
     }
-    ProfScope ps("bn_apply", 0.0, tb * (res ? 3.0 : 2.0), st);
+    ProfScope ps(prof_shape_label("bn_apply", M, C), 0.0, tb * (res ? 3.0 : 2.0), st);
     if (res)
         hipLaunchKernelGGL((bn_apply_kernel<T, VEC, true>), dim3(ew_grid(M * s.cvecs)), dim3(256), 0, st, (const T*)x,
                            (const T*)res, (T*)y, gamma, beta, save, M, C, s.cvecs, relu ? 1 : 0);
@@ -342,7 +342,7 @@ static void bn_backward_t(const void* x, const void* y, const void* dy, void* dx
     const double tb = (double)sizeof(T) * (double)M * C;
     const bool fused = sums_row_blocks > 0;
     if (sums_row_blocks <= 0) {   // else the dgrad that produced dy left the sums
-        ProfScope ps("bn_bwd_reduce", 0.0, tb * (relu ? 3.0 : 2.0), st);
+        ProfScope ps(prof_shape_label("bn_bwd_reduce", M, C), 0.0, tb * (relu ? 3.0 : 2.0), st);
         hipLaunchKernelGGL((colreduce_kernel<T, VEC, 1>), s.grid, s.block, 0, st, (const T*)x, (const T*)(relu ? y : x), (T*)dy, save,
                            M, C, s.rows_per_block, relu ? 1 : 0, partial);
         sums_row_blocks = s.row_blocks;
@@ -355,7 +355,7 @@ static void bn_backward_t(const void* x, const void* y, const void* dy, void* dx
     // the dgrad that left the sums also left dy masked: the activation is then not read again
     const bool mask = relu && !fused;
     const bool acc = dres && dres_acc;
-    ProfScope ps("bn_bwd_apply", 0.0, tb * ((mask ? 3.0 : 2.0) + 1.0 + (dres ? (acc ? 2.0 : 1.0) : 0.0)), st);
+    ProfScope ps(prof_shape_label("bn_bwd_apply", M, C), 0.0, tb * ((mask ? 3.0 : 2.0) + 1.0 + (dres ? (acc ? 2.0 : 1.0) : 0.0)), st);
     const dim3 grid(ew_grid(M * s.cvecs));
 #define EDL_BN_BWD_APPLY(MASK, ACC)                                                                                       \
     hipLaunchKernelGGL((bn_bwd_apply_kernel<T, VEC, MASK, ACC>), grid, dim3(256), 0, st, (const T*)x, (const T*)y, (const T*)dy, \

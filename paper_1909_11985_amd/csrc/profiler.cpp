@@ -1,6 +1,8 @@
 #include "profiler.h"
 
 #include <cstdio>
+#include <cstdlib>
+#include <deque>
 #include <map>
 #include <string>
 #include <vector>
@@ -31,6 +33,18 @@ hipEvent_t take_event() {
 
 void prof_enable(bool on) { g_on = on; }
 bool prof_enabled() { return g_on; }
+
+const char* prof_shape_label(const char* base, long long M, int C) {
+    static const bool by_shape = getenv("EDL_PROFILE_BY_SHAPE") != nullptr;
+    if (!by_shape || !g_on) return base;
+    static std::deque<std::string> names;   // a deque keeps the strings where they are
+    char buf[160];
+    snprintf(buf, sizeof(buf), "%s M=%lld C=%d", base, M, C);
+    for (const std::string& n : names)
+        if (n == buf) return n.c_str();
+    names.emplace_back(buf);
+    return names.back().c_str();
+}
 
 void prof_begin(const char* label, double flops, double bytes, hipStream_t st) {
     Rec r{label, flops, bytes, take_event(), take_event()};

@@ -16,6 +16,10 @@ void prof_end(hipStream_t st);
 // Returns the number of characters needed (excluding the NUL), or -1 on a HIP error.
 long prof_report(char* buf, size_t cap);
 
+// `base`, or with EDL_PROFILE_BY_SHAPE in the environment and profiling on "base M=.. C=.." (one report
+// line per distinct shape); the returned string lives until the process ends.
+const char* prof_shape_label(const char* base, long long M, int C);
+
 struct ProfScope {
     hipStream_t st;
     bool on;
