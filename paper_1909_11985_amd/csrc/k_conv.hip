@@ -1120,10 +1120,12 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restri
 // Finish of a forward / dgrad whose reduction was cut: sum the splits in order,
 // add the bias / apply ReLU (forward) or add the existing gradient (dgrad), and
 // store in the output type.  Four outputs per lane.
-template <typename T>
+template <typename T, bool MASKED>
 __global__ __launch_bounds__(256) void splitk_finish_kernel(const float* __restrict__ part, void* out, const float* __restrict__ bias,
                                                             int64_t M, int Nn, int splits, int relu, int out_fp32, int accumulate,
-                                                            int rows_per_block, float* __restrict__ stats) {
+                                                            int rows_per_block, float* __restrict__ stats,
+                                                            const T* __restrict__ mask_act, const T* __restrict__ xin,
+                                                            const float* __restrict__ mean_rstd) {
     // a workgroup owns 64 columns of rows_per_block rows: 16 lanes across (4 columns each), 16 rows at a time
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
     const int col = (blockIdx.x * 16 + tx) * 4;
@@ -1135,6 +1137,13 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(const float* __restr
     float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
     if (bias && active) bv = *reinterpret_cast<const float4*>(bias + col);
     float cs[4] = {0.f, 0.f, 0.f, 0.f}, cq[4] = {0.f, 0.f, 0.f, 0.f};
+    // MASKED (input gradient): the sum is stored where the activation is positive, zero elsewhere, and the
+    // column sums are those of the stored gradient and of gradient x normalised input (with xin)
+    float mu[4] = {0.f, 0.f, 0.f, 0.f}, rs[4] = {0.f, 0.f, 0.f, 0.f};
+    if (MASKED && xin != nullptr && active) {
+        #pragma unroll
+        for (int e = 0; e < 4; ++e) { mu[e] = mean_rstd[col + e]; rs[e] = mean_rstd[Nn + col + e]; }
+    }
     if (active) {
         for (int64_t r = r0 + ty; r < r1; r += 16) {
             const int64_t i = r * Nn + col;
@@ -1148,7 +1157,22 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(const float* __restr
             if (out_fp32 || sizeof(T) == 4) {
                 float4* d = reinterpret_cast<float4*>((float*)out + i);
                 if (accumulate) { const float4 o = *d; s.x += o.x; s.y += o.y; s.z += o.z; s.w += o.w; }
+                if (MASKED) {
+                    const float4 am = *reinterpret_cast<const float4*>((const float*)mask_act + i);
+                    s.x = am.x > 0.f ? s.x : 0.f; s.y = am.y > 0.f ? s.y : 0.f;
+                    s.z = am.z > 0.f ? s.z : 0.f; s.w = am.w > 0.f ? s.w : 0.f;
+                }
                 *d = s;
+                if (MASKED) {
+                    float4 xv = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (xin != nullptr) xv = *reinterpret_cast<const float4*>((const float*)xin + i);
+                    cs[0] += s.x; cs[1] += s.y; cs[2] += s.z; cs[3] += s.w;
+                    if (xin != nullptr) {
+                        cq[0] += s.x * ((xv.x - mu[0]) * rs[0]); cq[1] += s.y * ((xv.y - mu[1]) * rs[1]);
+                        cq[2] += s.z * ((xv.z - mu[2]) * rs[2]); cq[3] += s.w * ((xv.w - mu[3]) * rs[3]);
+                    }
+                    continue;
+                }
             } else {
                 uint2* d = reinterpret_cast<uint2*>((bf16_t*)out + i);
                 if (accumulate) {
@@ -1156,11 +1180,30 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(const float* __restr
                     s.x += __uint_as_float(o.x << 16); s.y += __uint_as_float(o.x & 0xffff0000u);
                     s.z += __uint_as_float(o.y << 16); s.w += __uint_as_float(o.y & 0xffff0000u);
                 }
+                if (MASKED) {   // activation > 0: a positive bf16
+                    const uint2 am = *reinterpret_cast<const uint2*>((const bf16_t*)mask_act + i);
+                    if (!(__uint_as_float(am.x << 16) > 0.f)) s.x = 0.f;
+                    if (!(__uint_as_float(am.x & 0xffff0000u) > 0.f)) s.y = 0.f;
+                    if (!(__uint_as_float(am.y << 16) > 0.f)) s.z = 0.f;
+                    if (!(__uint_as_float(am.y & 0xffff0000u) > 0.f)) s.w = 0.f;
+                }
                 const uint2 pk = make_uint2(pack2_bf16(s.x, s.y), pack2_bf16(s.z, s.w));
                 *d = pk;
                 // what a reader of the stored tensor sees
                 s.x = __uint_as_float(pk.x << 16); s.y = __uint_as_float(pk.x & 0xffff0000u);
                 s.z = __uint_as_float(pk.y << 16); s.w = __uint_as_float(pk.y & 0xffff0000u);
+                if (MASKED) {
+                    uint2 xw = make_uint2(0u, 0u);
+                    if (xin != nullptr) xw = *reinterpret_cast<const uint2*>((const bf16_t*)xin + i);
+                    const float x0 = __uint_as_float(xw.x << 16), x1 = __uint_as_float(xw.x & 0xffff0000u);
+                    const float x2 = __uint_as_float(xw.y << 16), x3 = __uint_as_float(xw.y & 0xffff0000u);
+                    cs[0] += s.x; cs[1] += s.y; cs[2] += s.z; cs[3] += s.w;
+                    if (xin != nullptr) {
+                        cq[0] += s.x * ((x0 - mu[0]) * rs[0]); cq[1] += s.y * ((x1 - mu[1]) * rs[1]);
+                        cq[2] += s.z * ((x2 - mu[2]) * rs[2]); cq[3] += s.w * ((x3 - mu[3]) * rs[3]);
+                    }
+                    continue;
+                }
             }
             cs[0] += s.x; cq[0] += s.x * s.x; cs[1] += s.y; cq[1] += s.y * s.y;
             cs[2] += s.z; cq[2] += s.z * s.z; cs[3] += s.w; cq[3] += s.w * s.w;
@@ -1454,7 +1497,7 @@ static int plan_splitk(int dtype, int M, int Nn, int Kred, int bm, int bn, int* 
 
 // Returns the number of row blocks whose column sums it left in stats (0 if stats is null).
 template <typename T>
-static int launch_finish(const ConvArgs& a, int splits, float* stats, hipStream_t st) {
+static int launch_finish(const ConvArgs& a, int splits, float* stats, hipStream_t st, const DgradMask* mask = nullptr) {
     const int col_blocks = (a.Nn + 63) / 64;
     // about 1024 workgroups, at least 16 rows each
     int64_t rb = (1024 + col_blocks - 1) / col_blocks;
@@ -1465,8 +1508,14 @@ static int launch_finish(const ConvArgs& a, int splits, float* stats, hipStream_
     const int rows_per_block = (int)(((int64_t)a.M + rb - 1) / rb);
     const int row_blocks = (int)(((int64_t)a.M + rows_per_block - 1) / rows_per_block);
     ProfScope ps("splitk_finish", 0.0, 4.0 * (double)a.M * a.Nn * splits + (a.out_fp32 ? 4.0 : (double)sizeof(T)) * (double)a.M * a.Nn, st);
-    hipLaunchKernelGGL(splitk_finish_kernel<T>, dim3(col_blocks, row_blocks), dim3(256), 0, st, a.partial, a.out, a.bias, (int64_t)a.M,
-                       a.Nn, splits, a.relu, a.out_fp32, a.accumulate, rows_per_block, stats);
+    if (mask != nullptr)
+        hipLaunchKernelGGL((splitk_finish_kernel<T, true>), dim3(col_blocks, row_blocks), dim3(256), 0, st, a.partial, a.out, a.bias,
+                           (int64_t)a.M, a.Nn, splits, a.relu, a.out_fp32, a.accumulate, rows_per_block, stats,
+                           (const T*)mask->act, (const T*)mask->xin, mask->mean_rstd);
+    else
+        hipLaunchKernelGGL((splitk_finish_kernel<T, false>), dim3(col_blocks, row_blocks), dim3(256), 0, st, a.partial, a.out, a.bias,
+                           (int64_t)a.M, a.Nn, splits, a.relu, a.out_fp32, a.accumulate, rows_per_block, stats,
+                           (const T*)nullptr, (const T*)nullptr, (const float*)nullptr);
     return stats ? row_blocks : 0;
 }
 
@@ -1580,8 +1629,13 @@ int launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dy, const void* 
             launch_mode<CONV_DGRAD>(dtype, t, dim3(row_tiles, (a.Nn + bn - 1) / bn, splits), a, st);
             if (fuse) fused_rows = finish_sums(mask->sums, mask->wide, row_tiles, a.Nn, st);
             if (splits > 1) {
-                if (dtype == 1) launch_finish<bf16_t>(a, splits, nullptr, st);
-                else launch_finish<float>(a, splits, nullptr, st);
+                // a cut reduction: the finishing kernel masks and sums instead of the epilogue
+                static const bool tune_cut = env_int("EDL_TUNE_FUSED_MASK_CUT", 1) != 0;
+                const bool cut_mask = tune_cut && tune_mask && mask != nullptr && mask->act != nullptr && mask->sums != nullptr &&
+                                      g.stride == 1 && a.Nn % 4 == 0;
+                const DgradMask* fm = cut_mask ? mask : nullptr;
+                float* fs = cut_mask ? mask->sums : nullptr;
+                fused_rows = dtype == 1 ? launch_finish<bf16_t>(a, splits, fs, st, fm) : launch_finish<float>(a, splits, fs, st, fm);
             }
         }
     }
