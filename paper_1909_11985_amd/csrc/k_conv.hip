@@ -1669,7 +1669,11 @@ static WgradPlan plan_wgrad(const ConvGeom& g) {
         default: p.bm = 64; p.bn = 64; break;
     }
     p.tiles = (int64_t)((M + p.bm - 1) / p.bm) * ((Nn + p.bn - 1) / p.bn);
-    static const int target = env_int("EDL_TUNE_WGRAD_BLOCKS", 256);
+    // The weight gradients run beside the input-gradient chain on a second stream: about one workgroup per
+    // two CUs leaves that chain the room it needs (ResNet-50 at a shard of 32: 256 -> 128 workgroups, alone on
+    // the chip 3% slower per step, beside the main stream 1.4% faster; ResNet-152 1.8%; below 96 the second
+    // stream becomes the longer one).
+    static const int target = env_int("EDL_TUNE_WGRAD_BLOCKS", 128);
     int64_t splits = (target + p.tiles - 1) / p.tiles;
     // A long reduction (VGG-16's layers on large images at a shard of 32) is cut into two workgroups per CU
     // (all that are resident at once), as long as each cut keeps long_ks elements: the partial results are
