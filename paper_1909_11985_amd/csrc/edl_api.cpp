@@ -29,6 +29,7 @@ namespace {
 constexpr int64_t kAlign = 256;
 constexpr int kIdxSlots = 4;
 constexpr int kReadyEvents = 64;   // ring of "dy is final" events for the second stream
+constexpr int kChunkEvents = 64;   // ring of "these weight gradients are final" events for the update stream
 
 int64_t align_up(int64_t v, int64_t a = kAlign) { return (v + a - 1) / a * a; }
 
@@ -219,6 +220,15 @@ struct edl_handle {
     hipEvent_t ev_ready[kReadyEvents];
     hipEvent_t ev_side_done = nullptr;
     int ev_slot = 0;
+    // The update of the parameters whose gradients are final starts during the last backward pass of a step,
+    // on a stream of its own: `early_p` > 0 asks the backward pass for it (the p of the step), `applied_from`
+    // is the first parameter already updated (P = none yet).
+    hipStream_t upd = nullptr;
+    hipEvent_t ev_chunk[kChunkEvents];
+    hipEvent_t ev_upd_done = nullptr;
+    int chunk_slot = 0;
+    int early_p = 0;
+    int64_t applied_from = 0;
 
     template <typename T> T* at(int64_t off) const { return reinterpret_cast<T*>(arena + off); }
     float* w() const { return at<float>(L.params); }
@@ -370,8 +380,12 @@ int32_t edl_init(edl_handle** out, const edl_config* cfg, uint64_t seed, void* d
             HIP_TRY(hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking));
             for (int e = 0; e < kReadyEvents; ++e) HIP_TRY(hipEventCreateWithFlags(&h->ev_ready[e], hipEventDisableTiming));
             HIP_TRY(hipEventCreateWithFlags(&h->ev_side_done, hipEventDisableTiming));
+            HIP_TRY(hipStreamCreateWithFlags(&h->upd, hipStreamNonBlocking));
+            for (int e = 0; e < kChunkEvents; ++e) HIP_TRY(hipEventCreateWithFlags(&h->ev_chunk[e], hipEventDisableTiming));
+            HIP_TRY(hipEventCreateWithFlags(&h->ev_upd_done, hipEventDisableTiming));
         }
     }
+    h->applied_from = h->g.P;
     std::vector<float> init((size_t)h->g.P);
     he_init(h->g, seed, init.data());
     HIP_TRY(hipMemcpyAsync(h->w(), init.data(), sizeof(float) * (size_t)h->g.P, hipMemcpyHostToDevice, h->st));
@@ -519,7 +533,11 @@ static void forward_shard(edl_handle* h, const int64_t* dev_idx, int n, float* d
     }
 }
 
-static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, size_t op_hi = (size_t)-1) {
+static int apply_range(edl_handle* h, int32_t p, int64_t lo, int64_t hi, hipStream_t st, int max_blocks = 0);
+
+// early_p > 0: this is the last backward pass of a step of early_p shards, so gradients that are final may be
+// applied while the pass goes on.
+static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, size_t op_hi = (size_t)-1, int early_p = 0) {
     const Graph& g = h->g;
     const int dt = h->cfg.dtype;
     hipStream_t st = h->st;
@@ -529,7 +547,7 @@ static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, siz
     if (op_hi > g.ops.size()) op_hi = g.ops.size();
     // per-kernel timing wants one kernel at a time
     const bool overlap = h->side != nullptr && !prof_enabled();
-    bool used_side = false;
+    bool used_side = false, used_upd = false;
     size_t fused_for = (size_t)-1;   // the layer whose masked gradient and column sums the dgrad after it left
     int fused_rows = 0;
     size_t premasked_for = (size_t)-1;   // the layer whose gradient the max pool after it left masked by its ReLU
@@ -568,6 +586,30 @@ static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, siz
                                   wscratch, (size_t)h->L.wgrad_scratch_bytes, ws);
                 if (padded)
                     launch_unpad_rows(h->at<float>(h->L.dwpad), G + op.w_off, (int64_t)op.K * op.R * op.S, g.tensors[0].C, h->L.cpad, ws);
+                // Parameters are laid out in layer order, so everything from this layer's weights on now has its
+                // final gradient: the second stream holds the weight gradients, and the event it waited for
+                // covers what the main stream has written (bias and batch-norm gradients of the later layers)
+                // and read (their batch-norm scales).  Nothing of the rest of the pass reads those parameters
+                // (input gradients use the transposed copies), so their update starts now, on a third stream, in
+                // pieces of at least chunk_min parameters; the first piece boundary is rounded up to 64 so that
+                // the vector accesses stay aligned, the few weights below it go with the next piece.
+                static const int64_t chunk_min = getenv("EDL_TUNE_EARLY_UPDATE") ? atoll(getenv("EDL_TUNE_EARLY_UPDATE")) : 16000000;
+                if (early_p > 0 && ws == h->side && ws != st && h->upd != nullptr && chunk_min > 0) {
+                    const int64_t lo = (op.w_off + 63) / 64 * 64;
+                    const int64_t own = (int64_t)op.K * op.R * op.S * g.tensors[(size_t)op.x].C;
+                    if (lo > 0 && lo < h->applied_from && own >= chunk_min) {
+                        hipEvent_t ev = h->ev_chunk[h->chunk_slot];
+                        h->chunk_slot = (h->chunk_slot + 1) % kChunkEvents;
+                        if (hipEventRecord(ev, h->side) == hipSuccess && hipStreamWaitEvent(h->upd, ev, 0) == hipSuccess) {
+                            // held to few workgroups: a full-width launch would take the CUs from the chain of
+                            // input gradients for as long as it runs
+                            static const int early_blocks = getenv("EDL_TUNE_EARLY_BLOCKS") ? atoi(getenv("EDL_TUNE_EARLY_BLOCKS")) : 256;
+                            apply_range(h, early_p, lo, h->applied_from, h->upd, early_blocks);
+                            h->applied_from = lo;
+                            used_upd = true;
+                        }
+                    }
+                }
                 const int sx = storage_of(g, op.x);
                 if (sx != 0) {
                     // If the layer just before in the list produced this convolution's input and ends in a ReLU, and
@@ -655,6 +697,10 @@ static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, siz
         (void)hipEventRecord(h->ev_side_done, h->side);
         (void)hipStreamWaitEvent(st, h->ev_side_done, 0);
     }
+    if (used_upd) {
+        (void)hipEventRecord(h->ev_upd_done, h->upd);
+        (void)hipStreamWaitEvent(st, h->ev_upd_done, 0);
+    }
 }
 
 static int check_p(const edl_handle* h, int32_t p) {
@@ -716,11 +762,14 @@ int32_t edl_gradients(edl_handle* h, int32_t p, const int64_t* idx, const int64_
     float* dev_losses = h->at<float>(h->L.losses);
     int64_t at = 0;
     bool first = true;       // the first worker that has samples keeps the running statistics
+    int last_k = -1;
+    for (int k = 0; k < p; ++k)
+        if (sizes[(size_t)k] > 0) last_k = k;
     for (int k = 0; k < p; ++k) {
         const int64_t nk = sizes[(size_t)k];
         if (nk > 0) {
             forward_shard(h, dev_idx + at, (int)nk, dev_losses + k, first);
-            backward_shard(h, (int)nk, h->grad_buf(k));
+            backward_shard(h, (int)nk, h->grad_buf(k), 0, (size_t)-1, k == last_k ? h->early_p : 0);
             first = false;
         }
         at += nk;
@@ -748,38 +797,52 @@ static void adam_corrections(double beta1, double beta2, int64_t t, float* c1, f
     *c2 = (float)(1.0 / (1.0 - std::pow(beta2, (double)t)));
 }
 
-static void apply_adam(edl_handle* h, int np, const GradPtrs& gp, const ShardShares* sh, uint16_t* shadow) {
-    float c1, c2;
-    adam_corrections(h->cfg.momentum, h->cfg.beta2, h->prog.step + 1, &c1, &c2);
-    launch_adam_update(np, gp, sh, h->w(), h->v(), h->s2(), shadow, h->g.P, h->cfg.lr, h->cfg.momentum, h->cfg.beta2,
-                       h->cfg.eps, h->cfg.wd, c1, c2, h->st);
+// The update of parameters [lo, hi) from the gradient buffers of the step's p shards (every buffer weighs in
+// with its shard's share of the mini-batch if the shards are unequal), on stream st.  lo is a multiple of 4.
+static int apply_range(edl_handle* h, int32_t p, int64_t lo, int64_t hi, hipStream_t st, int max_blocks) {
+    if (hi <= lo) return EDL_OK;
+    uint16_t* shadow = h->cfg.dtype == EDL_DTYPE_BF16 ? h->at<uint16_t>(h->L.shadow) + lo : nullptr;
+    const int64_t len = hi - lo;
+    GradPtrs gp = {};
+    ShardShares sh = {};
+    int np = 0;
+    if (h->shards_equal) {
+        for (int k = 0; k < p; ++k) gp.g[k] = h->grad_buf(k) + lo;
+        np = p;
+    } else {
+        for (int k = 0; k < p; ++k) {
+            if (h->shard_n[(size_t)k] == 0) continue;
+            gp.g[np] = h->grad_buf(k) + lo;
+            sh.share[np] = (float)((double)h->shard_n[(size_t)k] / (double)h->cfg.B);
+            ++np;
+        }
+    }
+    if (h->adam()) {
+        float c1, c2;
+        adam_corrections(h->cfg.momentum, h->cfg.beta2, h->prog.step + 1, &c1, &c2);
+        launch_adam_update(np, gp, h->shards_equal ? nullptr : &sh, h->w() + lo, h->v() + lo, h->s2() + lo, shadow, len, h->cfg.lr,
+                           h->cfg.momentum, h->cfg.beta2, h->cfg.eps, h->cfg.wd, c1, c2, st, max_blocks);
+    } else if (h->shards_equal) {
+        launch_average_update(np, gp, h->w() + lo, h->v() + lo, shadow, len, h->cfg.lr, h->cfg.momentum, h->cfg.wd, st, max_blocks);
+    } else {
+        launch_weighted_update(np, gp, sh, h->w() + lo, h->v() + lo, shadow, len, h->cfg.lr, h->cfg.momentum, h->cfg.wd, st);
+    }
+    return EDL_OK;
 }
 
 int32_t edl_apply(edl_handle* h, int32_t p) {
     if (!h) { set_error("null handle"); return EDL_EINVAL; }
-    uint16_t* shadow = h->cfg.dtype == EDL_DTYPE_BF16 ? h->at<uint16_t>(h->L.shadow) : nullptr;
     if (h->shards_equal) {
         const int rc = check_p(h, p);
         if (rc) return rc;
-        GradPtrs gp = {};
-        for (int k = 0; k < p; ++k) gp.g[k] = h->grad_buf(k);
-        if (h->adam()) apply_adam(h, p, gp, nullptr, shadow);
-        else launch_average_update(p, gp, h->w(), h->v(), shadow, h->g.P, h->cfg.lr, h->cfg.momentum, h->cfg.wd, h->st);
-    } else {
+    } else if ((size_t)p != h->shard_n.size()) {
         // shards of unequal size: each gradient buffer weighs in with its shard's share of the mini-batch
-        if ((size_t)p != h->shard_n.size()) { set_error("p=%d, but the gradients are of %zu shards", p, h->shard_n.size()); return EDL_EINVAL; }
-        GradPtrs gp = {};
-        ShardShares sh = {};
-        int np = 0;
-        for (int k = 0; k < p; ++k) {
-            if (h->shard_n[(size_t)k] == 0) continue;
-            gp.g[np] = h->grad_buf(k);
-            sh.share[np] = (float)((double)h->shard_n[(size_t)k] / (double)h->cfg.B);
-            ++np;
-        }
-        if (h->adam()) apply_adam(h, np, gp, &sh, shadow);
-        else launch_weighted_update(np, gp, sh, h->w(), h->v(), shadow, h->g.P, h->cfg.lr, h->cfg.momentum, h->cfg.wd, h->st);
+        set_error("p=%d, but the gradients are of %zu shards", p, h->shard_n.size());
+        return EDL_EINVAL;
     }
+    // what the backward pass has not already updated (all of it, unless this is the second half of edl_step)
+    apply_range(h, p, 0, h->applied_from, h->st);
+    h->applied_from = h->g.P;
     HIP_TRY(hipGetLastError());
     h->prog.step += 1;
     h->prog.step_in_epoch += 1;
@@ -791,8 +854,16 @@ int32_t edl_apply(edl_handle* h, int32_t p) {
 }
 
 int32_t edl_step(edl_handle* h, int32_t p, const int64_t* idx, const int64_t* off, float* out_loss) {
+    if (h) h->early_p = p;      // the last backward pass may start the update
     const int rc = edl_gradients(h, p, idx, off, out_loss);
-    if (rc) return rc;
+    if (h) h->early_p = 0;
+    if (rc) {
+        if (h && h->applied_from != h->g.P) {   // cannot happen after the arguments passed their checks
+            set_error("the step failed after part of the update was launched");
+            h->applied_from = h->g.P;
+        }
+        return rc;
+    }
     return edl_apply(h, p);
 }
 
@@ -1134,6 +1205,12 @@ int32_t edl_shutdown(edl_handle* h) {
         for (int e = 0; e < kReadyEvents; ++e) (void)hipEventDestroy(h->ev_ready[e]);
         (void)hipEventDestroy(h->ev_side_done);
         (void)hipStreamDestroy(h->side);
+    }
+    if (h->upd) {
+        (void)hipStreamSynchronize(h->upd);
+        for (int e = 0; e < kChunkEvents; ++e) (void)hipEventDestroy(h->ev_chunk[e]);
+        (void)hipEventDestroy(h->ev_upd_done);
+        (void)hipStreamDestroy(h->upd);
     }
     delete h;
     return EDL_OK;

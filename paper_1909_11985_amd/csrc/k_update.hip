@@ -32,8 +32,10 @@ __global__ __launch_bounds__(256) void average_update_kernel(GradPtrs gp, int p,
                                                              float wd) {
     const int np = NP > 0 ? NP : p;
     const float fp = (float)np;
-    const int64_t i0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * VPT;
-    if (i0 < nvec) {
+    // one pass for a launch that covers the vector (the usual one); a launch held to fewer workgroups, which
+    // runs in the background of other work, strides on
+    const int64_t step = (int64_t)gridDim.x * blockDim.x * VPT;
+    for (int64_t i0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * VPT; i0 < nvec; i0 += step) {
         float4 s[VPT], wi[VPT], vi[VPT];
         #pragma unroll
         for (int u = 0; u < VPT; ++u) {
@@ -98,12 +100,13 @@ static void launch_update_t(int grid, const GradPtrs& grads, int p, float* w, fl
 }
 
 void launch_average_update(int p, const GradPtrs& grads, float* w, float* v, uint16_t* w16, int64_t P, float lr,
-                           float momentum, float wd, hipStream_t st) {
+                           float momentum, float wd, hipStream_t st, int max_blocks) {
     const int64_t nvec = P / 4;
     // one workgroup per 256*VPT vectors, no grid-stride loop (measured ~20% faster than looping over a few thousand workgroups)
     static const int vpt = getenv("EDL_TUNE_UPD_VPT") ? atoi(getenv("EDL_TUNE_UPD_VPT")) : 1;
     const int64_t per_block = 256 * (vpt == 2 ? 2 : 1);
-    const int grid = (int)std::max<int64_t>(1, (nvec + per_block - 1) / per_block);
+    int grid = (int)std::max<int64_t>(1, (nvec + per_block - 1) / per_block);
+    if (max_blocks > 0 && grid > max_blocks) grid = max_blocks;
     // p gradient reads + w, v read and written (+ the bf16 copy)
     ProfScope ps("average_update", 0.0, (4.0 * p + 16.0 + (w16 ? 2.0 : 0.0)) * (double)P, st);
 #define EDL_UPD(NP)                                                                                   \
@@ -173,8 +176,8 @@ __global__ __launch_bounds__(256) void adam_update_kernel(GradPtrs gp, ShardShar
                                                           uint16_t* __restrict__ w16, int64_t nvec, int64_t P, AdamCoef a) {
     const int np = NP > 0 ? NP : p;
     const float inv_p = 1.0f / (float)np;
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < nvec) {
+    const int64_t step = (int64_t)gridDim.x * blockDim.x;   // see average_update_kernel
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += step) {
         float4 wi = reinterpret_cast<float4*>(w)[i];
         float4 mi = reinterpret_cast<float4*>(m)[i];
         float4 si = reinterpret_cast<float4*>(s)[i];
@@ -227,9 +230,11 @@ static void launch_adam_t(int grid, const GradPtrs& grads, const ShardShares& sh
 }
 
 void launch_adam_update(int p, const GradPtrs& grads, const ShardShares* shares, float* w, float* m, float* s, uint16_t* w16,
-                        int64_t P, float lr, float beta1, float beta2, float eps, float wd, float c1, float c2, hipStream_t st) {
+                        int64_t P, float lr, float beta1, float beta2, float eps, float wd, float c1, float c2, hipStream_t st,
+                        int max_blocks) {
     const int64_t nvec = P / 4;
-    const int grid = (int)std::max<int64_t>(1, (nvec + 255) / 256);
+    int grid = (int)std::max<int64_t>(1, (nvec + 255) / 256);
+    if (max_blocks > 0 && grid > max_blocks) grid = max_blocks;
     const AdamCoef a = {lr, beta1, beta2, eps, wd, c1, c2};
     // p gradient reads + w, m, s read and written (+ the bf16 copy)
     ProfScope ps("adam_update", 0.0, (4.0 * p + 24.0 + (w16 ? 2.0 : 0.0)) * (double)P, st);

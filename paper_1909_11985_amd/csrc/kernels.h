@@ -15,15 +15,17 @@ struct GradPtrs { const float* g[kMaxP]; };
 struct ShardShares { float share[kMaxP]; };   // a shard's part of the mini-batch
 
 // ---- aggregation + update, copies ----------------------------------------
+// max_blocks > 0 holds the launch to that many workgroups (a pass that runs in the background of other work).
 void launch_average_update(int p, const GradPtrs& grads, float* w, float* v, uint16_t* w16, int64_t P,
-                           float lr, float momentum, float wd, hipStream_t st);
+                           float lr, float momentum, float wd, hipStream_t st, int max_blocks = 0);
 // aggregate = sum_k shares[k] * grads[k] (shards of unequal size)
 void launch_weighted_update(int np, const GradPtrs& grads, const ShardShares& shares, float* w, float* v, uint16_t* w16,
                             int64_t P, float lr, float momentum, float wd, hipStream_t st);
 // Adam on the aggregated gradient.  shares == nullptr: the mean of the p gradients; otherwise sum_k shares->share[k]*G_k.
 // c1 = 1/(1-beta1^t), c2 = 1/(1-beta2^t).
 void launch_adam_update(int p, const GradPtrs& grads, const ShardShares* shares, float* w, float* m, float* s, uint16_t* w16,
-                        int64_t P, float lr, float beta1, float beta2, float eps, float wd, float c1, float c2, hipStream_t st);
+                        int64_t P, float lr, float beta1, float beta2, float eps, float wd, float c1, float c2, hipStream_t st,
+                        int max_blocks = 0);
 void launch_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
 void launch_fill_f32(float* dst, float value, int64_t n, hipStream_t st);
 // dst[c][r][s][k] = cast(src[k][r][s][c]) (weights for the input-gradient contraction) for every

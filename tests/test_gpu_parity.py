@@ -651,6 +651,50 @@ def test_the_second_stream_does_not_change_the_result():
     assert digests[0] == digests[1] == digests[2], digests
 
 
+_EARLY_SCRIPT = r"""
+import sys, hashlib
+sys.path.insert(0, sys.argv[1]); sys.path.insert(0, sys.argv[2])
+import numpy as np, torch, synth_inputs
+import paper_1909_11985_amd as E
+from paper_1909_11985_amd.binding import make_config
+N, B = 96, 24
+x, y = synth_inputs.dataset(1, N, 64, 64, 3, 1000)
+h = hashlib.sha256()
+for optimizer in ("momentum", "adam"):
+    cfg = make_config("resnet50", dtype="bf16", N=N, B=B, p_max=4, max_shard=B, lr=0.002, H=64, W=64, optimizer=optimizer)
+    job = E.Job(cfg, 0)
+    job.bind_dataset(torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda())
+    for p in (1, 2, 4):
+        job.step(p)
+    idx, _ = job.shard(B, 1, 0, 3)
+    job.step(3, idx, np.array([0, 10, 10, 24], dtype=np.int64))      # unequal shards, an empty one in the middle
+    job.step(2, idx, np.array([0, 24, 24], dtype=np.int64))          # the last shard is empty
+    h.update(job.params().tobytes() + job.momentum().tobytes() + job.running().tobytes())
+    if optimizer == "adam":
+        h.update(job.second_moment().tobytes())
+print(h.hexdigest())
+"""
+
+
+def test_the_update_started_during_the_backward_pass_does_not_change_the_result():
+    """The update of layers whose gradients are final starts during the last backward pass of a step, in pieces on
+    a third stream (by default only from layers of 16 M weights on; here from every layer, and with the
+    background launch held to 8 workgroups): momentum and Adam, equal and unequal shards, give bit for bit the
+    model of a run that updates everything after the pass."""
+    import os
+    import subprocess
+    import sys
+    here = os.path.dirname(os.path.abspath(__file__))
+    digests = []
+    for env_extra in ({"EDL_TUNE_EARLY_UPDATE": "0"}, {"EDL_TUNE_EARLY_UPDATE": "1"},
+                      {"EDL_TUNE_EARLY_UPDATE": "100000", "EDL_TUNE_EARLY_BLOCKS": "8"}):
+        out = subprocess.run([sys.executable, "-c", _EARLY_SCRIPT, os.path.dirname(here), here], env=dict(os.environ, **env_extra),
+                             capture_output=True, text=True, timeout=300)
+        assert out.returncode == 0, out.stdout[-2000:] + out.stderr[-2000:]
+        digests.append(out.stdout.strip().splitlines()[-1])
+    assert digests[0] == digests[1] == digests[2], digests
+
+
 # ---------------------------------------------------------------- argument checking
 def test_step_rejects_bad_requests():
     torch = _torch()
