@@ -204,6 +204,10 @@ int32_t edl_shard(const edl_handle* h, int64_t B, int32_t p, int64_t epoch, int6
  * out_loss (host, may be NULL) receives the mean loss over the mini-batch
  * (the mean of the workers' mean losses, weighted by n_k/B if unequal); asking
  * for it synchronises the stream, otherwise the call only queues work.
+ * Some of that work (weight gradients, the update of the largest layers) is
+ * queued on streams of the library's own; it is joined to the handle's stream
+ * before the call returns, so whatever the caller queues on that stream next
+ * sees the finished step.
  * EDL_EINVAL p<=0 or p>p_max; without idx/off: EDL_EINDIVISIBLE B%p, EDL_ENOMEM
  * B/p>max_shard; with them: EDL_ENOMEM a shard larger than max_shard, EDL_ERANGE
  * index outside [0,N) or offsets not monotone from 0 to B. */
