@@ -590,9 +590,11 @@ static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, siz
                 // final gradient: the second stream holds the weight gradients, and the event it waited for
                 // covers what the main stream has written (bias and batch-norm gradients of the later layers)
                 // and read (their batch-norm scales).  Nothing of the rest of the pass reads those parameters
-                // (input gradients use the transposed copies), so their update starts now, on a third stream, in
-                // pieces of at least chunk_min parameters; the first piece boundary is rounded up to 64 so that
-                // the vector accesses stay aligned, the few weights below it go with the next piece.
+                // (input gradients use the transposed copies), so their update starts now, on a third stream, if
+                // the layer is a large one (chunk_min weights or more: the update of a small piece gains less than
+                // its launch beside the input-gradient chain costs).  The piece starts at the layer's first weight
+                // rounded up to 64, so that the vector accesses stay aligned; the few weights below go with the
+                // next piece or with the rest of the update after the pass.
                 static const int64_t chunk_min = getenv("EDL_TUNE_EARLY_UPDATE") ? atoll(getenv("EDL_TUNE_EARLY_UPDATE")) : 16000000;
                 if (early_p > 0 && ws == h->side && ws != st && h->upd != nullptr && chunk_min > 0) {
                     const int64_t lo = (op.w_off + 63) / 64 * 64;
