@@ -22,10 +22,22 @@
  *   - every call returns 0 on success or a negative EDL_E* code;
  *     edl_last_error() gives a thread-local message for the last failure.
  *   - "dev" pointers are device memory owned by the caller; "host" pointers
- *     are ordinary host memory owned by the caller.  The library owns only
- *     the handle (freed by edl_shutdown) and allocates no device memory.
- *   - all device work is queued on the hipStream_t given to edl_init (NULL =
- *     the default stream).  Calls on one handle are not thread-safe.
+ *     are ordinary host memory owned by the caller.  The library allocates no
+ *     device memory.  A handle owns (until edl_shutdown) a few small pinned
+ *     host staging buffers (the mini-batch's indices, the workers' losses),
+ *     HIP events, and - unless the caller brings them, see
+ *     edl_set_side_streams - two non-blocking streams of default priority.
+ *   - device work is queued on the hipStream_t given to edl_init (NULL = the
+ *     default stream).  A training pass also uses the two side streams (weight
+ *     gradients; the update of layers whose gradients are final), ordered
+ *     against the job's stream by events and joined to it before the call
+ *     returns, so work queued on the job's stream afterwards sees the finished
+ *     call.  Calls on one handle are not thread-safe.
+ *   - launch heuristics and code-path switches live in one table of named
+ *     integer options (edl_set_option / edl_get_option), each preset from
+ *     the environment variable EDL_TUNE_<NAME> when the library is first used.
+ *     They choose between paths that compute the same thing; none is needed
+ *     for normal use.
  *   - tensors are channels-last: images [N][H][W][C], convolution weights
  *     [K][R][S][C]; parameters, momentum and gradients are float32 in one
  *     flat vector whose order is the model's layer order (see
@@ -179,6 +191,23 @@ int32_t edl_pipeline_destroy(edl_pipeline* pl);
 int32_t edl_init(edl_handle** out, const edl_config* cfg, uint64_t seed, void* dev_arena,
                  size_t arena_bytes, void* hip_stream);
 
+/* The two streams a training pass uses beside the job's own (see Conventions): the caller's, which must
+ * differ from each other and from the job's stream, be of default priority and outlive the handle's use of
+ * them; or NULL, NULL for none (everything then runs on the job's stream).  Replaces whatever the handle used
+ * before (streams the library created itself are destroyed).  Synchronises the job's stream and the old side
+ * streams.  Results do not depend on the choice, bit for bit. */
+int32_t edl_set_side_streams(edl_handle* h, void* wgrad_stream, void* update_stream);
+
+/* Named integer options of the library (process-wide; see Conventions).  EDL_EINVAL for an unknown name.  Names:
+ * force_tile (-1, or 0..3 = every forward / input-gradient launch on 128x128, 128x64, 128x32, 64x64 tiles),
+ * wgrad_stream (1: jobs created from now on make their own side streams; 0: they do not), wgrad_tail_main,
+ * early_update (least weights of a layer whose update starts during the backward pass; 0 = never),
+ * early_blocks, join_tile, fused_stats, held_stats, fused_mask, fused_mask_cut, fused_mask_join, persistent,
+ * min128, min128_long, bk64_kred, xcd, order, splitk_tiles, splitk_target, wgrad_blocks, wgrad_long_blocks,
+ * wgrad_long_ks, upd_vpt. */
+int32_t edl_set_option(const char* name, int64_t value);
+int32_t edl_get_option(const char* name, int64_t* out_value);
+
 /* The data set the shards index into: dev_x float32 [N][H][W][C], dev_y int32 [N]
  * (device memory, caller-owned, must stay alive). */
 int32_t edl_bind_dataset(edl_handle* h, const float* dev_x, const int32_t* dev_y, int64_t N);
@@ -218,7 +247,8 @@ int32_t edl_step(edl_handle* h, int32_t p, const int64_t* idx, const int64_t* of
 int32_t edl_gradients(edl_handle* h, int32_t p, const int64_t* idx, const int64_t* off, float* out_loss);
 
 /* Only the second half: aggregate the gradient buffers of the last edl_gradients (by the mean, or by the
- * shards' shares if they were unequal: p must then be that call's p) and update. */
+ * shards' shares if they were unequal) and update.  p must be that call's p.  The buffers are applied once:
+ * EDL_EINVAL without a preceding edl_gradients, or on a second call after one. */
 int32_t edl_apply(edl_handle* h, int32_t p);
 
 /* The scheduler's profile(min_p, max_p) operator (sections 3.2, 5): the job is
@@ -246,8 +276,13 @@ int32_t edl_profile_parallelism(edl_handle* h, int32_t min_p, int32_t max_p, int
 
 /* State image for a joining worker: header, w[P], v[P], with Adam s[P], then
  * running[R] (float32, little endian), written to device memory dev_dst of
- * capacity cap.  The header names the optimizer; edl_restore refuses (EDL_EINVAL)
- * an image of another model, job size or optimizer. */
+ * capacity cap.  The header carries the job's meta-data (section 4.2): model,
+ * dtype, seed, N, B, progress, optimizer and its coefficients (lr, momentum,
+ * wd; beta2, eps).  edl_restore refuses (EDL_EINVAL) an image of another model,
+ * job size, optimizer or dtype (the worker's buffers were laid out for its
+ * own), and ADOPTS the rest: seed, progress and the optimizer's coefficients
+ * replace what the worker was created with, so a joiner continues exactly as
+ * the job it joined.  Gradients pending from before the restore are void. */
 int32_t edl_snapshot(edl_handle* h, void* dev_dst, size_t cap, size_t* out_written);
 int32_t edl_restore(edl_handle* h, const void* dev_src, size_t len);
 
@@ -300,6 +335,11 @@ int32_t edl_debug_backward_op(edl_handle* h, int32_t op, int32_t n, int32_t k);
  * convolution's input-gradient pass can hand the masked gradient and its
  * column sums to the layer before it). */
 int32_t edl_debug_backward_range(edl_handle* h, int32_t op_lo, int32_t op_hi, int32_t n, int32_t k);
+/* The same when other readers of some tensors lie outside the range: the gradient buffers of the tensors in
+ * held[0..n_held) already hold those readers' contribution (written with edl_debug_set_tensor) and the range
+ * adds to it, as the readers inside a step find it at a residual join. */
+int32_t edl_debug_backward_range_from(edl_handle* h, int32_t op_lo, int32_t op_hi, int32_t n, int32_t k,
+                                      const int32_t* held, int32_t n_held);
 int32_t edl_debug_set_labels(edl_handle* h, const int32_t* labels, int32_t n);
 
 int32_t edl_shutdown(edl_handle* h);

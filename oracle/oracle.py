@@ -511,10 +511,20 @@ class Oracle:
         return self.w[off:off + n].reshape(shape)
 
     # -- forward + backward on one worker's samples ------------------------
-    def forward_backward(self, x, labels, update_running=False):
+    def forward_backward(self, x, labels, update_running=False, decisions=None):
         """x: [n,H,W,C] float64, labels: [n] ints.  Returns (mean loss over
-        the n samples, flat gradient of that mean loss w.r.t. all parameters)."""
+        the n samples, flat gradient of that mean loss w.r.t. all parameters).
+
+        The backward pass takes two kinds of discrete decision from the forward
+        activations: which outputs a ReLU let through (output > 0) and which
+        element of its window a max pool picked.  They are kept in
+        self.last_decisions {op index: boolean mask | int32 positions}.
+        `decisions` (test hook; same keys) replaces any of them by given ones,
+        so that a test can ask what the gradient would be had a neighbouring
+        computation decided differently; the forward values are not changed."""
         g = self.graph
+        decisions = decisions or {}
+        self.last_decisions = {}
         q = self._q
         act = {"x": q(np.ascontiguousarray(x, dtype=np.float64))}
         saved = {}
@@ -589,7 +599,9 @@ class Oracle:
             elif kind == "conv":
                 dy = grad.pop(op["y"])
                 if op["relu"]:
-                    dy = dy * (act[op["y"]] > 0)
+                    passed = decisions.get(i, act[op["y"]] > 0)
+                    self.last_decisions[i] = passed
+                    dy = dy * passed
                 xin = act[op["x"]]
                 w = saved[i]
                 dw, db = conv2d_backward_weight(xin, np.ascontiguousarray(dy), w.shape, op["stride"],
@@ -603,7 +615,9 @@ class Oracle:
             elif kind == "bn":
                 dy = grad.pop(op["y"])
                 if op["relu"]:
-                    dy = dy * (act[op["y"]] > 0)
+                    passed = decisions.get(i, act[op["y"]] > 0)
+                    self.last_decisions[i] = passed
+                    dy = dy * passed
                 if op["res"] is not None:
                     add(op["res"], dy)
                 xhat, var = saved[i]
@@ -615,7 +629,9 @@ class Oracle:
                 add(op["x"], dx)
             elif kind == "maxpool":
                 dy = grad.pop(op["y"])
-                add(op["x"], maxpool_backward(np.ascontiguousarray(dy), saved[i], act[op["x"]].shape))
+                picked = np.ascontiguousarray(decisions.get(i, saved[i]), dtype=np.int32)
+                self.last_decisions[i] = picked
+                add(op["x"], maxpool_backward(np.ascontiguousarray(dy), picked, act[op["x"]].shape))
             elif kind == "gavgpool":
                 dy = grad.pop(op["y"])
                 a = act[op["x"]]
@@ -665,6 +681,42 @@ class Oracle:
             self.epoch += 1
         return mean_loss
 
+    # -- approximate recovery (section 4.2, failure recovery) ---------------
+    @staticmethod
+    def survivor_cut(B, survivors):
+        """The mini-batch of B samples re-cut over `survivors` workers, as evenly
+        as the counts allow: the first B mod survivors workers take one sample
+        more (the paper only says that a worker's batch follows from the
+        parallelism; the aggregate batch stays B).  Returns off[survivors+1]."""
+        base, extra = divmod(B, survivors)
+        sizes = [base + (1 if k < extra else 0) for k in range(survivors)]
+        return np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+
+    def redo_with_survivors(self, p, lost_k, data_x, data_y):
+        """Worker lost_k of p fails during the current mini-batch (its gradient
+        never arrives, so the aggregation of that attempt cannot complete and
+        nothing of it is applied).  Approximate recovery: the p-1 survivors form
+        a new group and redo the CURRENT mini-batch - the same B samples at the
+        same cursor, re-cut over p-1 workers, every worker weighing in with its
+        share n_k/B - and the job moves on by one mini-batch.  Returns
+        (loss of the redone mini-batch, gradients of the discarded attempt's
+        surviving workers)."""
+        assert p >= 2 and 0 <= lost_k < p
+        idx, off = shard(self.seed, self.N, self.B, p, self.epoch, self.step_in_epoch)
+        before = (self.w.copy(), self.v.copy(), self.s.copy(), self.running.copy(), self.step_count)
+        discarded = []
+        for k in range(p):
+            if k == lost_k:
+                continue
+            sel = idx[off[k]:off[k + 1]]
+            _, G = self.forward_backward(np.asarray(data_x[sel], dtype=np.float64), np.asarray(data_y[sel]))
+            discarded.append(G)
+        # nothing of the failed attempt may have touched the job
+        assert all(np.array_equal(a, b) for a, b in zip(before[:4], (self.w, self.v, self.s, self.running)))
+        loss = self.step(p - 1, data_x, data_y, idx, self.survivor_cut(self.B, p - 1))
+        assert self.step_count == before[4] + 1
+        return loss, discarded
+
     # -- what a joining worker receives ------------------------------------
     def snapshot(self) -> bytes:
         """Header (job meta-data and progress), then parameters, the optimizer's
@@ -684,8 +736,13 @@ class Oracle:
         P, R = self.graph.P, self.graph.R
         f = struct.unpack_from("<IIIIQqqqqqfffIqq", blob, 0)
         assert f[0] == SNAPSHOT_MAGIC and f[14] == P and f[15] == R and f[13] == OPTIMIZER_IDS[self.optimizer]
-        self.seed, self.N, self.B = f[4], f[5], f[6]      # job meta-data travels with the model
+        # job meta-data travels with the model (section 4.2): seed, sizes, progress and the optimizer's
+        # coefficients of the job replace whatever this worker was created with
+        self.seed, self.N, self.B = f[4], f[5], f[6]
         self.step_count, self.epoch, self.step_in_epoch = f[7], f[8], f[9]
+        self.lr, self.momentum, self.wd = f[10], f[11], f[12]
+        if self.optimizer == "adam":
+            self.beta2, self.eps = struct.unpack_from("<ff", blob, 96)
         o = SNAPSHOT_HEADER_BYTES
         self.w = np.frombuffer(blob, np.float32, P, o).astype(np.float64)
         self.v = np.frombuffer(blob, np.float32, P, o + 4 * P).astype(np.float64)

@@ -8,4 +8,5 @@ from .binding import (  # noqa: F401
     EdlError, Config, Sizes, Job, Pipeline, MODELS, DTYPES,
     edl_query, edl_shard_host, edl_init_params_host, edl_tensor_table,
     edl_adam_update, edl_average_update, edl_copy, edl_mfma_rate, edl_profile, edl_profile_report, lib,
+    edl_set_option, edl_get_option, options,
 )

@@ -90,7 +90,11 @@ _SIGS = {
     "edl_debug_forward_range": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32],
     "edl_debug_backward_op": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32],
     "edl_debug_backward_range": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32],
+    "edl_debug_backward_range_from": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.c_int32],
     "edl_debug_set_labels": [C.c_void_p, C.POINTER(C.c_int32), C.c_int32],
+    "edl_set_side_streams": [C.c_void_p, C.c_void_p, C.c_void_p],
+    "edl_set_option": [C.c_char_p, C.c_int64],
+    "edl_get_option": [C.c_char_p, _i64p],
     "edl_shutdown": [C.c_void_p],
     "edl_average_update": [C.c_int32, C.POINTER(C.c_void_p), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
                            C.c_float, C.c_float, C.c_float, C.c_void_p],
@@ -207,6 +211,34 @@ def edl_copy(dst, src, nbytes, stream=0):
     _check(lib.edl_copy(dst.data_ptr(), src.data_ptr(), nbytes, stream))
 
 
+def edl_set_option(name, value):
+    _check(lib.edl_set_option(name.encode(), int(value)))
+
+
+def edl_get_option(name):
+    v = C.c_int64()
+    _check(lib.edl_get_option(name.encode(), C.byref(v)))
+    return v.value
+
+
+class options:
+    """with options(force_tile=2, ...): the named options hold inside the block and are put back after it."""
+
+    def __init__(self, **kw):
+        self.kw = kw
+
+    def __enter__(self):
+        self.old = {k: edl_get_option(k) for k in self.kw}
+        for k, v in self.kw.items():
+            edl_set_option(k, v)
+        return self
+
+    def __exit__(self, *exc):
+        for k, v in self.old.items():
+            edl_set_option(k, v)
+        return False
+
+
 def edl_profile(enable):
     _check(lib.edl_profile(1 if enable else 0))
 
@@ -280,7 +312,10 @@ class Job:
     """One elastic job on one GPU.  Allocates the arena with torch and hands
     raw pointers to the library."""
 
-    def __init__(self, cfg, seed, device="cuda:0", stream=None):
+    def __init__(self, cfg, seed, device="cuda:0", stream=None, side_streams="library"):
+        """side_streams: "library" (the handle makes its own two side streams, unless the option wgrad_stream
+        is 0), "torch" (two torch.cuda.Stream objects of default priority made here and handed over), or None
+        (everything on the job's stream)."""
         import torch
         self.torch = torch
         self.cfg = cfg
@@ -293,6 +328,12 @@ class Job:
         _check(lib.edl_init(C.byref(self._h), C.byref(cfg), seed, self.arena.data_ptr(), self.arena.numel(), sp))
         self.P, self.R = self.sizes.P, self.sizes.R
         self._data = None
+        self._side = None
+        if side_streams == "torch":
+            self._side = (torch.cuda.Stream(device=self.device), torch.cuda.Stream(device=self.device))
+            _check(lib.edl_set_side_streams(self._h, self._side[0].cuda_stream, self._side[1].cuda_stream))
+        elif side_streams is None:
+            _check(lib.edl_set_side_streams(self._h, None, None))
 
     def bind_dataset(self, x, y):
         """x: float32 [N,H,W,C] device tensor, y: int32 [N] device tensor."""
@@ -431,6 +472,10 @@ class Job:
 
     def debug_backward_range(self, op_lo, op_hi, n, k=0):
         _check(lib.edl_debug_backward_range(self._h, op_lo, op_hi, n, k))
+
+    def debug_backward_range_from(self, op_lo, op_hi, n, held, k=0):
+        arr = (C.c_int32 * len(held))(*held)
+        _check(lib.edl_debug_backward_range_from(self._h, op_lo, op_hi, n, k, arr, len(held)))
 
     def debug_set_labels(self, labels):
         labels = np.ascontiguousarray(labels, dtype=np.int32)

@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libedl.so")
-SOURCES = ["edl_api.cpp", "host_logic.cpp", "pipeline.cpp", "profiler.cpp", "k_update.hip", "k_norm.hip", "k_misc.hip", "k_conv.hip"]
+SOURCES = ["edl_api.cpp", "host_logic.cpp", "pipeline.cpp", "profiler.cpp", "tune.cpp", "k_update.hip", "k_norm.hip", "k_misc.hip", "k_conv.hip"]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Wall", "-Wno-unused-result",
          # packed-fp32 arithmetic is switched off for device code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

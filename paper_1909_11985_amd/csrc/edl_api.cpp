@@ -12,6 +12,7 @@
 #include "graph.h"
 #include "kernels.h"
 #include "profiler.h"
+#include "tune.h"
 
 using namespace edl;
 
@@ -207,7 +208,7 @@ struct edl_handle {
     double tv_bytes = 0;
     // pinned staging
     int64_t* idx_host[kIdxSlots] = {nullptr, nullptr, nullptr, nullptr};
-    hipEvent_t idx_event[kIdxSlots];
+    hipEvent_t idx_event[kIdxSlots] = {};
     int idx_slot = 0;
     float* loss_host = nullptr;
     std::vector<int> readers;            // per tensor storage: how many layers read it (as input or as residual)
@@ -215,16 +216,18 @@ struct edl_handle {
     // shard sizes of the last edl_gradients (what edl_apply weighs the gradient buffers by)
     std::vector<int64_t> shard_n;
     bool shards_equal = true;
-    // second stream for the weight gradients (null: everything on st)
+    bool grads_pending = false;          // edl_gradients has run and edl_apply has not consumed its buffers yet
+    // second stream for the weight gradients (null: everything on st); own_streams: created here, not the caller's
     hipStream_t side = nullptr;
-    hipEvent_t ev_ready[kReadyEvents];
+    bool own_streams = false;
+    hipEvent_t ev_ready[kReadyEvents] = {};
     hipEvent_t ev_side_done = nullptr;
     int ev_slot = 0;
     // The update of the parameters whose gradients are final starts during the last backward pass of a step,
     // on a stream of its own: `early_p` > 0 asks the backward pass for it (the p of the step), `applied_from`
     // is the first parameter already updated (P = none yet).
     hipStream_t upd = nullptr;
-    hipEvent_t ev_chunk[kChunkEvents];
+    hipEvent_t ev_chunk[kChunkEvents] = {};
     hipEvent_t ev_upd_done = nullptr;
     int chunk_slot = 0;
     int early_p = 0;
@@ -337,6 +340,50 @@ static void transpose_weights(edl_handle* h) {
         }
 }
 
+static int init_device_state(edl_handle* h);
+
+// events that order the side streams against the job's stream (created once, whoever owns the streams)
+static int create_side_events(edl_handle* h) {
+    for (int e = 0; e < kReadyEvents; ++e)
+        if (!h->ev_ready[e]) HIP_TRY(hipEventCreateWithFlags(&h->ev_ready[e], hipEventDisableTiming));
+    if (!h->ev_side_done) HIP_TRY(hipEventCreateWithFlags(&h->ev_side_done, hipEventDisableTiming));
+    for (int e = 0; e < kChunkEvents; ++e)
+        if (!h->ev_chunk[e]) HIP_TRY(hipEventCreateWithFlags(&h->ev_chunk[e], hipEventDisableTiming));
+    if (!h->ev_upd_done) HIP_TRY(hipEventCreateWithFlags(&h->ev_upd_done, hipEventDisableTiming));
+    return EDL_OK;
+}
+
+// waits for the side streams and lets go of them (destroys them only if the library made them)
+static void release_side_streams(edl_handle* h) {
+    if (h->side) (void)hipStreamSynchronize(h->side);
+    if (h->upd) (void)hipStreamSynchronize(h->upd);
+    if (h->own_streams) {
+        if (h->side) (void)hipStreamDestroy(h->side);
+        if (h->upd) (void)hipStreamDestroy(h->upd);
+    }
+    h->side = nullptr;
+    h->upd = nullptr;
+    h->own_streams = false;
+}
+
+// frees whatever of the handle's resources exist (also a half-built handle) and the handle
+static void destroy_handle(edl_handle* h) {
+    (void)hipStreamSynchronize(h->st);
+    release_side_streams(h);
+    for (int s = 0; s < kIdxSlots; ++s) {
+        if (h->idx_host[s]) (void)hipHostFree(h->idx_host[s]);
+        if (h->idx_event[s]) (void)hipEventDestroy(h->idx_event[s]);
+    }
+    if (h->loss_host) (void)hipHostFree(h->loss_host);
+    for (int e = 0; e < kReadyEvents; ++e)
+        if (h->ev_ready[e]) (void)hipEventDestroy(h->ev_ready[e]);
+    for (int e = 0; e < kChunkEvents; ++e)
+        if (h->ev_chunk[e]) (void)hipEventDestroy(h->ev_chunk[e]);
+    if (h->ev_side_done) (void)hipEventDestroy(h->ev_side_done);
+    if (h->ev_upd_done) (void)hipEventDestroy(h->ev_upd_done);
+    delete h;
+}
+
 int32_t edl_init(edl_handle** out, const edl_config* cfg, uint64_t seed, void* dev_arena, size_t arena_bytes,
                  void* hip_stream) {
     if (!out || !cfg || !dev_arena) { set_error("null argument"); return EDL_EINVAL; }
@@ -369,24 +416,36 @@ int32_t edl_init(edl_handle** out, const edl_config* cfg, uint64_t seed, void* d
         if (op.x >= 0) reads(op.x);
         if (op.kind == OP_BN && op.res >= 0) reads(op.res);
     }
+    h->applied_from = h->g.P;
+    rc = init_device_state(h);
+    if (rc) {                            // whatever was created so far goes again
+        destroy_handle(h);
+        return rc;
+    }
+    *out = h;
+    return EDL_OK;
+}
+
+// Pinned staging, events, the library's own side streams, and the initial model on the device.
+static int init_device_state(edl_handle* h) {
+    const edl_config* cfg = &h->cfg;
+    const uint64_t seed = h->seed;
     for (int s = 0; s < kIdxSlots; ++s) {
         HIP_TRY(hipHostMalloc((void**)&h->idx_host[s], sizeof(int64_t) * (size_t)cfg->B, hipHostMallocDefault));
         HIP_TRY(hipEventCreateWithFlags(&h->idx_event[s], hipEventDisableTiming));
     }
     HIP_TRY(hipHostMalloc((void**)&h->loss_host, sizeof(float) * kMaxP, hipHostMallocDefault));
-    {
-        const char* v = getenv("EDL_TUNE_WGRAD_STREAM");
-        if (!v || atoi(v) != 0) {
-            HIP_TRY(hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking));
-            for (int e = 0; e < kReadyEvents; ++e) HIP_TRY(hipEventCreateWithFlags(&h->ev_ready[e], hipEventDisableTiming));
-            HIP_TRY(hipEventCreateWithFlags(&h->ev_side_done, hipEventDisableTiming));
-            HIP_TRY(hipStreamCreateWithFlags(&h->upd, hipStreamNonBlocking));
-            for (int e = 0; e < kChunkEvents; ++e) HIP_TRY(hipEventCreateWithFlags(&h->ev_chunk[e], hipEventDisableTiming));
-            HIP_TRY(hipEventCreateWithFlags(&h->ev_upd_done, hipEventDisableTiming));
-        }
+    if (tune().wgrad_stream != 0) {
+        HIP_TRY(hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking));
+        h->own_streams = true;
+        HIP_TRY(hipStreamCreateWithFlags(&h->upd, hipStreamNonBlocking));
+        const int rc = create_side_events(h);
+        if (rc) return rc;
     }
-    h->applied_from = h->g.P;
     std::vector<float> init((size_t)h->g.P);
+    std::vector<TransposeEntry> tab, tabv;
+    // the copies below read these host arrays: whichever way this function is left, the stream is drained first
+    struct DrainOnExit { hipStream_t st; ~DrainOnExit() { (void)hipStreamSynchronize(st); } } drain{h->st};
     he_init(h->g, seed, init.data());
     HIP_TRY(hipMemcpyAsync(h->w(), init.data(), sizeof(float) * (size_t)h->g.P, hipMemcpyHostToDevice, h->st));
     launch_fill_f32(h->v(), 0.f, h->g.P, h->st);
@@ -399,7 +458,6 @@ int32_t edl_init(edl_handle** out, const edl_config* cfg, uint64_t seed, void* d
     {
         // bf16 layers of vector-friendly shape are transposed from the bf16 copy of the weights in 64x64
         // tiles; the others element by element from the float32 weights
-        std::vector<TransposeEntry> tab, tabv;
         const double esz = cfg->dtype == EDL_DTYPE_BF16 ? 2.0 : 4.0;
         for (size_t i = 0; i < h->g.ops.size(); ++i) {
             const Op& op = h->g.ops[i];
@@ -428,11 +486,38 @@ int32_t edl_init(edl_handle** out, const edl_config* cfg, uint64_t seed, void* d
         if (!tabv.empty())
             HIP_TRY(hipMemcpyAsync(h->at<TransposeEntry>(h->L.ttable) + h->g.ops.size(), tabv.data(),
                                    sizeof(TransposeEntry) * tabv.size(), hipMemcpyHostToDevice, h->st));
-        HIP_TRY(hipStreamSynchronize(h->st));   // init[] and tab[] leave scope
+        HIP_TRY(hipStreamSynchronize(h->st));
     }
     h->weights_dirty = true;
     HIP_TRY(hipGetLastError());
-    *out = h;
+    return EDL_OK;
+}
+
+int32_t edl_set_side_streams(edl_handle* h, void* wgrad_stream, void* update_stream) {
+    if (!h) { set_error("null handle"); return EDL_EINVAL; }
+    if ((wgrad_stream == nullptr) != (update_stream == nullptr)) { set_error("give both streams or neither"); return EDL_EINVAL; }
+    if (wgrad_stream != nullptr && (wgrad_stream == update_stream || wgrad_stream == (void*)h->st || update_stream == (void*)h->st)) {
+        set_error("the two side streams must differ from each other and from the job's stream");
+        return EDL_EINVAL;
+    }
+    HIP_TRY(hipStreamSynchronize(h->st));
+    release_side_streams(h);
+    if (wgrad_stream == nullptr) return EDL_OK;         // everything on the job's stream from now on
+    h->side = (hipStream_t)wgrad_stream;
+    h->upd = (hipStream_t)update_stream;
+    h->own_streams = false;
+    const int rc = create_side_events(h);
+    if (rc) { release_side_streams(h); return rc; }
+    return EDL_OK;
+}
+
+int32_t edl_set_option(const char* name, int64_t value) {
+    if (!tune_set(name, value)) { set_error("no option named '%s'", name ? name : "(null)"); return EDL_EINVAL; }
+    return EDL_OK;
+}
+
+int32_t edl_get_option(const char* name, int64_t* out_value) {
+    if (!tune_get(name, out_value)) { set_error("no option named '%s'", name ? name : "(null)"); return EDL_EINVAL; }
     return EDL_OK;
 }
 
@@ -483,7 +568,7 @@ static void forward_shard(edl_handle* h, const int64_t* dev_idx, int n, float* d
                 // the batch norm that follows (in this call) can take its sums from the convolution's epilogue
                 const bool bn_next = i + 1 < op_hi && g.ops[i + 1].kind == OP_BN && g.ops[i + 1].x == op.y;
                 // ... or a later one of this call, if the held buffer is free
-                static const bool tune_held = getenv("EDL_TUNE_HELD_STATS") == nullptr || atoi(getenv("EDL_TUNE_HELD_STATS")) != 0;
+                const bool tune_held = tune().held_stats != 0;
                 bool bn_later = false;
                 if (!bn_next && tune_held && held_tensor < 0)
                     for (size_t j = i + 2; j < op_hi && j <= i + 4 && !bn_later; ++j)
@@ -537,13 +622,17 @@ static int apply_range(edl_handle* h, int32_t p, int64_t lo, int64_t hi, hipStre
 
 // early_p > 0: this is the last backward pass of a step of early_p shards, so gradients that are final may be
 // applied while the pass goes on.
-static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, size_t op_hi = (size_t)-1, int early_p = 0) {
+// held (debugging hook only): tensors whose gradient buffers already hold a contribution the pass adds to.
+static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, size_t op_hi = (size_t)-1, int early_p = 0,
+                           const std::vector<int>* held = nullptr) {
     const Graph& g = h->g;
     const int dt = h->cfg.dtype;
     hipStream_t st = h->st;
     float* partial = h->at<float>(h->L.partial);
     float* coef = h->at<float>(h->L.coef);
     std::vector<char> written(g.tensors.size(), 0);
+    if (held)
+        for (int t : *held) written[(size_t)storage_of(g, t)] = 1;
     if (op_hi > g.ops.size()) op_hi = g.ops.size();
     // per-kernel timing wants one kernel at a time
     const bool overlap = h->side != nullptr && !prof_enabled();
@@ -569,7 +658,7 @@ static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, siz
                 hipStream_t ws = st;
                 // The first layers' weight gradients are the last of the pass: by then the main stream has nothing
                 // else to do, so they stay on it (with a scratch of their own) and run beside the second stream's backlog.
-                static const int tail_main = getenv("EDL_TUNE_WGRAD_TAIL_MAIN") ? atoi(getenv("EDL_TUNE_WGRAD_TAIL_MAIN")) : 1;
+                const int tail_main = (int)tune().wgrad_tail_main;
                 int conv_ordinal = 0;
                 for (size_t j = 0; j < ii; ++j) conv_ordinal += g.ops[j].kind == OP_CONV;
                 const bool on_main = overlap && conv_ordinal < tail_main;
@@ -595,7 +684,7 @@ static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, siz
                 // its launch beside the input-gradient chain costs).  The piece starts at the layer's first weight
                 // rounded up to 64, so that the vector accesses stay aligned; the few weights below go with the
                 // next piece or with the rest of the update after the pass.
-                static const int64_t chunk_min = getenv("EDL_TUNE_EARLY_UPDATE") ? atoll(getenv("EDL_TUNE_EARLY_UPDATE")) : 16000000;
+                const int64_t chunk_min = tune().early_update;
                 if (early_p > 0 && ws == h->side && ws != st && h->upd != nullptr && chunk_min > 0) {
                     const int64_t lo = (op.w_off + 63) / 64 * 64;
                     const int64_t own = (int64_t)op.K * op.R * op.S * g.tensors[(size_t)op.x].C;
@@ -605,7 +694,7 @@ static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, siz
                         if (hipEventRecord(ev, h->side) == hipSuccess && hipStreamWaitEvent(h->upd, ev, 0) == hipSuccess) {
                             // held to few workgroups: a full-width launch would take the CUs from the chain of
                             // input gradients for as long as it runs
-                            static const int early_blocks = getenv("EDL_TUNE_EARLY_BLOCKS") ? atoi(getenv("EDL_TUNE_EARLY_BLOCKS")) : 256;
+                            const int early_blocks = (int)tune().early_blocks;
                             apply_range(h, early_p, lo, h->applied_from, h->upd, early_blocks);
                             h->applied_from = lo;
                             used_upd = true;
@@ -621,7 +710,7 @@ static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, siz
                     // and that layer then skips its own reduction pass.
                     DgradMask mask = {};
                     const bool acc = written[(size_t)sx] != 0;
-                    static const bool fuse_joins = getenv("EDL_TUNE_FUSED_MASK_JOIN") ? atoi(getenv("EDL_TUNE_FUSED_MASK_JOIN")) != 0 : true;
+                    const bool fuse_joins = tune().fused_mask_join != 0;
                     const bool last_writer = h->first_reader[(size_t)sx] == ii &&
                                              (h->readers[(size_t)sx] == 1 ? !acc : (fuse_joins && acc));
                     if (ii > op_lo && last_writer) {
@@ -790,6 +879,7 @@ int32_t edl_gradients(edl_handle* h, int32_t p, const int64_t* idx, const int64_
         }
         *out_loss = (float)s;
     }
+    h->grads_pending = true;
     return EDL_OK;
 }
 
@@ -834,14 +924,14 @@ static int apply_range(edl_handle* h, int32_t p, int64_t lo, int64_t hi, hipStre
 
 int32_t edl_apply(edl_handle* h, int32_t p) {
     if (!h) { set_error("null handle"); return EDL_EINVAL; }
-    if (h->shards_equal) {
-        const int rc = check_p(h, p);
-        if (rc) return rc;
-    } else if ((size_t)p != h->shard_n.size()) {
-        // shards of unequal size: each gradient buffer weighs in with its shard's share of the mini-batch
-        set_error("p=%d, but the gradients are of %zu shards", p, h->shard_n.size());
+    // the gradient buffers are applied once: a second call, or one without gradients, would move the model by
+    // whatever the buffers happen to hold
+    if (!h->grads_pending) { set_error("no gradients pending: edl_apply follows one edl_gradients"); return EDL_EINVAL; }
+    if ((size_t)p != h->shard_n.size()) {
+        set_error("p=%d, but the pending gradients are of %zu shards", p, h->shard_n.size());
         return EDL_EINVAL;
     }
+    h->grads_pending = false;
     // what the backward pass has not already updated (all of it, unless this is the second half of edl_step)
     apply_range(h, p, 0, h->applied_from, h->st);
     h->applied_from = h->g.P;
@@ -964,6 +1054,12 @@ int32_t edl_restore(edl_handle* h, const void* dev_src, size_t len) {
     if (sh.P != P || sh.R != R || (int32_t)sh.model != h->cfg.model) { set_error("snapshot is of another model (P=%lld, R=%lld)", (long long)sh.P, (long long)sh.R); return EDL_EINVAL; }
     if (sh.N != h->cfg.N || sh.B != h->cfg.B) { set_error("snapshot is of a job with N=%lld B=%lld", (long long)sh.N, (long long)sh.B); return EDL_EINVAL; }
     if ((int32_t)sh.optimizer != h->cfg.optimizer) { set_error("snapshot is of a job with optimizer %u", sh.optimizer); return EDL_EINVAL; }
+    if ((int32_t)sh.dtype != h->cfg.dtype) { set_error("snapshot is of a job with dtype %u, this worker was created for %d", sh.dtype, h->cfg.dtype); return EDL_EINVAL; }
+    if (!std::isfinite(sh.lr) || !std::isfinite(sh.momentum) || !std::isfinite(sh.wd)) { set_error("snapshot header holds non-finite hyper-parameters"); return EDL_EINVAL; }
+    if (h->adam() && !(sh.momentum >= 0.f && sh.momentum < 1.f && sh.beta2 >= 0.f && sh.beta2 < 1.f && sh.eps >= 0.f)) {
+        set_error("snapshot header holds Adam coefficients outside their range");
+        return EDL_EINVAL;
+    }
     const char* src = (const char*)dev_src;
     launch_copy(h->w(), src + EDL_SNAPSHOT_HEADER_BYTES, 4 * (size_t)P, h->st);
     launch_copy(h->v(), src + EDL_SNAPSHOT_HEADER_BYTES + 4 * (size_t)P, 4 * (size_t)P, h->st);
@@ -971,7 +1067,12 @@ int32_t edl_restore(edl_handle* h, const void* dev_src, size_t len) {
     if (h->adam()) { launch_copy(h->s2(), src + at, 4 * (size_t)P, h->st); at += 4 * (size_t)P; }
     launch_copy(h->running(), src + at, 4 * (size_t)R, h->st);
     HIP_TRY(hipGetLastError());
-    h->seed = sh.seed;                      // job meta-data travels with the model
+    // job meta-data travels with the model (section 4.2): the joiner takes over the seed, the progress and the
+    // optimizer's coefficients, whatever it was created with
+    h->seed = sh.seed;
+    h->cfg.lr = sh.lr; h->cfg.momentum = sh.momentum; h->cfg.wd = sh.wd;
+    if (h->adam()) { h->cfg.beta2 = sh.beta2; h->cfg.eps = sh.eps; }
+    h->grads_pending = false;               // gradients of the model that was replaced are void
     h->prog.step = sh.step; h->prog.epoch = sh.epoch; h->prog.step_in_epoch = sh.step_in_epoch;
     h->perm_epoch = -1;
     h->weights_dirty = true;
@@ -1114,11 +1215,22 @@ int32_t edl_debug_backward_op(edl_handle* h, int32_t op, int32_t n, int32_t k) {
 }
 
 int32_t edl_debug_backward_range(edl_handle* h, int32_t op_lo, int32_t op_hi, int32_t n, int32_t k) {
+    return edl_debug_backward_range_from(h, op_lo, op_hi, n, k, nullptr, 0);
+}
+
+int32_t edl_debug_backward_range_from(edl_handle* h, int32_t op_lo, int32_t op_hi, int32_t n, int32_t k,
+                                      const int32_t* held, int32_t n_held) {
     int rc = debug_prepare(h, n);
     if (rc) return rc;
     if (op_lo < 0 || op_hi < op_lo || (size_t)op_hi > h->g.ops.size()) { set_error("layers [%d, %d) out of range", op_lo, op_hi); return EDL_ERANGE; }
     if (k < 0 || k >= h->cfg.p_max) { set_error("gradient buffer %d outside [0,p_max)", k); return EDL_EINVAL; }
-    backward_shard(h, n, h->grad_buf(k), (size_t)op_lo, (size_t)op_hi);
+    if (n_held < 0 || (n_held > 0 && !held)) { set_error("bad list of held tensors"); return EDL_EINVAL; }
+    std::vector<int> hv;
+    for (int32_t i = 0; i < n_held; ++i) {
+        if (held[i] <= 0 || (size_t)held[i] >= h->g.tensors.size()) { set_error("held tensor %d out of range", held[i]); return EDL_ERANGE; }
+        hv.push_back(held[i]);
+    }
+    backward_shard(h, n, h->grad_buf(k), (size_t)op_lo, (size_t)op_hi, 0, &hv);
     HIP_TRY(hipStreamSynchronize(h->st));
     HIP_TRY(hipGetLastError());
     return EDL_OK;
@@ -1196,25 +1308,7 @@ int32_t edl_set_second_moment(edl_handle* h, const float* host_src) {
 
 int32_t edl_shutdown(edl_handle* h) {
     if (!h) { set_error("null handle"); return EDL_EINVAL; }
-    (void)hipStreamSynchronize(h->st);
-    for (int s = 0; s < kIdxSlots; ++s) {
-        if (h->idx_host[s]) (void)hipHostFree(h->idx_host[s]);
-        (void)hipEventDestroy(h->idx_event[s]);
-    }
-    if (h->loss_host) (void)hipHostFree(h->loss_host);
-    if (h->side) {
-        (void)hipStreamSynchronize(h->side);
-        for (int e = 0; e < kReadyEvents; ++e) (void)hipEventDestroy(h->ev_ready[e]);
-        (void)hipEventDestroy(h->ev_side_done);
-        (void)hipStreamDestroy(h->side);
-    }
-    if (h->upd) {
-        (void)hipStreamSynchronize(h->upd);
-        for (int e = 0; e < kChunkEvents; ++e) (void)hipEventDestroy(h->ev_chunk[e]);
-        (void)hipEventDestroy(h->ev_upd_done);
-        (void)hipStreamDestroy(h->upd);
-    }
-    delete h;
+    destroy_handle(h);
     return EDL_OK;
 }
 

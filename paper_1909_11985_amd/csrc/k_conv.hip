@@ -45,6 +45,7 @@
 #include "dev_common.h"
 #include "kernels.h"
 #include "profiler.h"
+#include "tune.h"
 
 // 1: LDS fragment reads run one fragment group ahead of the MFMAs (tiles of more than one MFMA per group;
 // measured -6% on the 128x128 weight gradient, nothing on the others)
@@ -1256,18 +1257,13 @@ enum TileCfg { T128x128, T128x64, T128x32, T64x64 };
 // reduction elements per tile: eight 16-byte vectors per row for either type
 template <typename T> constexpr int kConvBK = 8 * Elem<T>::VEC;
 
-static int env_int(const char* name, int dflt) {
-    const char* v = getenv(name);
-    return v ? atoi(v) : dflt;
-}
-
 // short_fwd: a problem whose epilogue is most of the workgroup's time (a forward pass of one or two
 // reduction steps, an input-gradient pass whose epilogue adds, masks and sums); twice as many workgroups of
 // half the width measured faster there
 static TileCfg pick_tile(int M, int Nn, int Kred, int* bm, int* bn, bool short_fwd = false) {
     // A long reduction takes the 128x128 tile from fewer tiles on (the reduction is cut to fill the chip):
     // VGG-16's 14x14 layers, 196 tiles, measured 64 -> 48 us forward and 71 -> 47 us dgrad.
-    static const int min128_short = env_int("EDL_TUNE_MIN128", 256), min128_long = env_int("EDL_TUNE_MIN128_LONG", 160);
+    const int min128_short = (int)tune().min128, min128_long = (int)tune().min128_long;
     const int min128 = Kred >= 4096 ? std::min(min128_short, min128_long) : min128_short;
     TileCfg t;
     if (Nn <= 32) t = T128x32;
@@ -1277,7 +1273,7 @@ static TileCfg pick_tile(int M, int Nn, int Kred, int* bm, int* bn, bool short_f
         t = (tiles >= min128 && M >= 128) ? (short_fwd ? T128x64 : T128x128) : T64x64;
     }
     // measurement aid: one tile shape for every forward / dgrad problem it fits (0..3 = 128x128, 128x64, 128x32, 64x64)
-    static const int force = env_int("EDL_TUNE_FORCE_TILE", -1);
+    const int force = (int)tune().force_tile;
     if (force >= 0 && force <= 3) t = (TileCfg)force;
     switch (t) {
         case T128x128: *bm = 128; *bn = 128; break;
@@ -1326,7 +1322,7 @@ static void launch_cfg(TileCfg t, bool fast, dim3 tiles, const ConvArgs& a_in, h
             // Long reductions (VGG-16's 3x3 layers: 1,152 to 4,608 elements) run faster on full-length reduction
             // steps (half the barriers per MFMA: measured 159 -> 135 us forward, 174 -> 154 us dgrad on VGG-16);
             // short ones (ResNet-50's 1x1 layers) want the smaller LDS footprint and more workgroups per CU.
-            static const int full_steps_from = env_int("EDL_TUNE_BK64_KRED", 1024);
+            const int full_steps_from = (int)tune().bk64_kred;
             if (BK_BIG != BK && a.Kred >= full_steps_from)
                 hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 2, 2, BK, true, PF_BIG>), grid, dim3(256), 0, st, a);
             else
@@ -1384,7 +1380,7 @@ static void launch_mode(int dtype, TileCfg t, dim3 grid, const ConvArgs& a_in, h
     // Tile order: the reduction cuts are the slowest index, so a die's run of tiles
     // stays within few cuts; inside a cut the tiles that share the larger operand
     // (activations: the same row tile; weights: the same column tile) are neighbours.
-    static const int tune_xcd = env_int("EDL_TUNE_XCD", 1), tune_order = env_int("EDL_TUNE_ORDER", -1);
+    const int tune_xcd = (int)tune().xcd, tune_order = (int)tune().order;
     a.xcd_chunked = tune_xcd;
     if (tune_order >= 0) a.n_fastest = tune_order;
     else if (MODE == CONV_WGRAD) a.n_fastest = 1;
@@ -1483,7 +1479,7 @@ static int plan_splitk(int dtype, int M, int Nn, int Kred, int bm, int bn, int* 
     const int64_t tiles = (int64_t)((M + bm - 1) / bm) * ((Nn + bn - 1) / bn);
     const int nk = (Kred + BK - 1) / BK;
     int splits = 1;
-    static const int max_tiles = env_int("EDL_TUNE_SPLITK_TILES", 300), target = env_int("EDL_TUNE_SPLITK_TARGET", 320);
+    const int max_tiles = (int)tune().splitk_tiles, target = (int)tune().splitk_target;
     if (tiles < max_tiles && nk >= 8) {
         splits = (int)((target + tiles - 1) / tiles);
         if (splits > nk / 4) splits = nk / 4;
@@ -1556,7 +1552,7 @@ int launch_conv_fwd(int dtype, const ConvGeom& g, const void* x, const void* w, 
     }
     if (splits > 1) { a.ksplit = ks; a.partial = scratch; }
     const int row_tiles = (a.M + bm - 1) / bm;
-    static const bool tune_stats = env_int("EDL_TUNE_FUSED_STATS", 1) != 0;
+    const bool tune_stats = tune().fused_stats != 0;
     const bool want_stats = tune_stats && stats != nullptr && !out_fp32 && conv_fast(dtype, CONV_FWD, a) && conv_magic_ok(CONV_FWD, a);
     // whole reduction in one workgroup: the epilogue leaves the sums; cut reduction: the finishing kernel does
     float* const target = (want_stats && splits == 1) ? sums_target(stats, wide, row_tiles, a.Nn, &a.red_stride) : nullptr;
@@ -1604,7 +1600,7 @@ int launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dy, const void* 
             // an epilogue that adds to the gradient already there, masks and sums it reads three more tensors
             // than it writes: 128x64 tiles (twice the workgroups, half the vectors in flight per lane; measured
             // -0.4% of the ResNet-50 step, 64x64 tiles +1.5%)
-            static const int join_tile = env_int("EDL_TUNE_JOIN_TILE", 1);
+            const int join_tile = (int)tune().join_tile;
             const bool heavy = join_tile != 0 && mask != nullptr && mask->act != nullptr && accumulate && g.stride == 1;
             const TileCfg t = pick_tile(a.M, a.Nn, a.Kred, &bm, &bn, heavy);
             int splits = 1, ks = a.ksplit;
@@ -1616,7 +1612,7 @@ int launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dy, const void* 
             const int row_tiles = (a.M + bm - 1) / bm;
             // masked store and column sums in the epilogue: one launch that covers every pixel and leaves the
             // final gradient (it may add to what other readers of the tensor have left there)
-            static const bool tune_mask = env_int("EDL_TUNE_FUSED_MASK", 1) != 0;
+            const bool tune_mask = tune().fused_mask != 0;
             float* target = nullptr;
             if (tune_mask && mask != nullptr && mask->act != nullptr && g.stride == 1 && splits == 1 &&
                 conv_fast(dtype, CONV_DGRAD, a) && conv_magic_ok(CONV_DGRAD, a))
@@ -1630,7 +1626,7 @@ int launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dy, const void* 
             if (fuse) fused_rows = finish_sums(mask->sums, mask->wide, row_tiles, a.Nn, st);
             if (splits > 1) {
                 // a cut reduction: the finishing kernel masks and sums instead of the epilogue
-                static const bool tune_cut = env_int("EDL_TUNE_FUSED_MASK_CUT", 1) != 0;
+                const bool tune_cut = tune().fused_mask_cut != 0;
                 const bool cut_mask = tune_cut && tune_mask && mask != nullptr && mask->act != nullptr && mask->sums != nullptr &&
                                       g.stride == 1 && a.Nn % 4 == 0;
                 const DgradMask* fm = cut_mask ? mask : nullptr;
@@ -1673,14 +1669,14 @@ static WgradPlan plan_wgrad(const ConvGeom& g) {
     // two CUs leaves that chain the room it needs (ResNet-50 at a shard of 32: 256 -> 128 workgroups, alone on
     // the chip 3% slower per step, beside the main stream 1.4% faster; ResNet-152 1.8%; below 96 the second
     // stream becomes the longer one).
-    static const int target = env_int("EDL_TUNE_WGRAD_BLOCKS", 128);
+    const int target = (int)tune().wgrad_blocks;
     int64_t splits = (target + p.tiles - 1) / p.tiles;
     // A long reduction (VGG-16's layers on large images at a shard of 32) is cut into two workgroups per CU
     // (all that are resident at once), as long as each cut keeps long_ks elements: the partial results are
     // small beside the operands there, and a second workgroup hides the operand latency that one per CU
     // leaves exposed.  Measured on VGG-16: 5.28 -> 5.14 ms per step; three per CU (a second, ragged round
     // of workgroups) is slower again.
-    static const int long_target = env_int("EDL_TUNE_WGRAD_LONG_BLOCKS", 512), long_ks = env_int("EDL_TUNE_WGRAD_LONG_KS", 3072);
+    const int long_target = (int)tune().wgrad_long_blocks, long_ks = (int)tune().wgrad_long_ks;
     const int64_t more = std::min<int64_t>(long_target / p.tiles, Kred / (long_ks > 0 ? long_ks : 1));
     if (more > splits) splits = more;
     const int64_t max_splits = (Kred + 255) / 256;  // at least 4 reduction steps per split

@@ -8,6 +8,7 @@
 #include "dev_common.h"
 #include "kernels.h"
 #include "profiler.h"
+#include "tune.h"
 
 namespace edl {
 
@@ -103,7 +104,7 @@ void launch_average_update(int p, const GradPtrs& grads, float* w, float* v, uin
                            float momentum, float wd, hipStream_t st, int max_blocks) {
     const int64_t nvec = P / 4;
     // one workgroup per 256*VPT vectors, no grid-stride loop (measured ~20% faster than looping over a few thousand workgroups)
-    static const int vpt = getenv("EDL_TUNE_UPD_VPT") ? atoi(getenv("EDL_TUNE_UPD_VPT")) : 1;
+    const int vpt = (int)tune().upd_vpt;
     const int64_t per_block = 256 * (vpt == 2 ? 2 : 1);
     int grid = (int)std::max<int64_t>(1, (nvec + per_block - 1) / per_block);
     if (max_blocks > 0 && grid > max_blocks) grid = max_blocks;

@@ -175,3 +175,18 @@ def test_pipeline_save_load_and_errors(E):
     with pytest.raises(E.EdlError) as ei:
         a.next_batch(36, [0, 1])                              # 36 does not divide 240
     assert ei.value.code == -2
+
+
+def test_options_are_named_set_and_read_back(E):
+    """The table of launch heuristics and code-path switches: defaults, a change and its undoing, unknown names."""
+    assert E.edl_get_option("force_tile") == -1 and E.edl_get_option("wgrad_stream") == 1
+    assert E.edl_get_option("early_update") == 16000000
+    with E.options(force_tile=2, early_update=0):
+        assert E.edl_get_option("force_tile") == 2 and E.edl_get_option("early_update") == 0
+    assert E.edl_get_option("force_tile") == -1 and E.edl_get_option("early_update") == 16000000
+    for bad in ("no_such_option", ""):
+        with pytest.raises(E.EdlError) as ei:
+            E.edl_set_option(bad, 1)
+        assert ei.value.code == -1
+        with pytest.raises(E.EdlError):
+            E.edl_get_option(bad)
