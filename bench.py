@@ -48,18 +48,38 @@ DEFAULT_HWC = {"mlp": (1, 1, 784, 10), "resnet20": (32, 32, 3, 10), "resnet50": 
                "vgg16": (224, 224, 3, 1000), "alexnet": (224, 224, 3, 1000)}
 
 
+def kernel_sources_digest():
+    """sha256 (first 16 hex digits) over the library's kernel and host sources: what a committed counter summary
+    was taken from can be told apart from what is being timed now."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_1909_11985_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".hip", ".cpp", ".h")):
+            h.update(name.encode())
+            h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
 def committed_traffic(workload, kernel):
     """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary of this workload
-    (FETCH_SIZE and WRITE_SIZE scaled by the copy-kernel calibration), or None."""
-    path = os.path.join(ROOT, "profiles", "%s_hbm_traffic.txt" % workload)
+    (FETCH_SIZE and WRITE_SIZE scaled by the copy-kernel calibration), and where the figure comes from:
+    (bytes or None, dict(file, kernel_sources_at_profile, kernel_sources_now, stale)).  The counters need
+    rocprofv3 around the process, so they are not taken in this run; `stale` says whether the sources have
+    changed since the summary was written."""
+    rel = os.path.join("profiles", "%s_hbm_traffic.txt" % workload)
+    value, at = None, None
     try:
-        for line in open(path):
+        for line in open(os.path.join(ROOT, rel)):
             f = line.split()
             if len(f) >= 3 and f[0] == "traffic_bytes_per_launch" and f[1] == kernel:
-                return float(f[2])
+                value = float(f[2])
+            if len(f) >= 2 and f[0] == "kernel_sources_sha16":
+                at = f[1]
     except OSError:
-        pass
-    return None
+        return None, None
+    now = kernel_sources_digest()
+    return value, dict(file=rel, kernel_sources_at_profile=at, kernel_sources_now=now, stale=(at != now))
 
 
 def run_elastic(args, np, torch, synth_inputs, E, make_config):
@@ -189,13 +209,7 @@ def main():
     # plainly first (one_stream_ms_per_step) and then with an event pair per launch.
     job.shutdown()
     del job
-    prior = os.environ.get("EDL_TUNE_WGRAD_STREAM")
-    os.environ["EDL_TUNE_WGRAD_STREAM"] = "0"
-    job = E.Job(cfg, 0)
-    if prior is None:
-        del os.environ["EDL_TUNE_WGRAD_STREAM"]
-    else:
-        os.environ["EDL_TUNE_WGRAD_STREAM"] = prior
+    job = E.Job(cfg, 0, side_streams=None)
     job.bind_dataset(dx, dy)
     for _ in range(2):
         job.step(p, want_loss=False)
@@ -249,7 +263,7 @@ def main():
                         avg_launch_us=round(1e3 * dom["ms"] / dom["launches"], 2),
                         launches_per_step=dom["launches"] / prof_steps)
     roofline["event_pair_overhead_us"] = round(1e3 * overhead_ms, 2)
-    roofline["traffic"] = committed_traffic(args.workload, roofline["kernel"])
+    roofline["traffic"], roofline["traffic_source"] = committed_traffic(args.workload, roofline["kernel"])
     conv_ms = sum(r["ms"] for r in rep if r["flops"] > 0) / prof_steps
     conv_flops = sum(r["flops"] for r in rep if r["flops"] > 0) / prof_steps
     step_summary = dict(
@@ -340,25 +354,37 @@ def main():
                           mfma_peak_tflops=MFMA_PEAK_TFLOPS[dtype], copy_gbs=snapshot["gbs"], hbm_peak_gbs=HBM_PEAK_GBS)
 
     # ---- the oracle on the host cores, on a bounded sample of the same workload ----
+    # The same unit of work as `value`: whole steps (shard assignment, forward and backward of every shard,
+    # aggregation + update) of the oracle as it stands.  One small warm-up pass (pages the data in), then
+    # `cpu_steps` timed steps on shards of n_cpu samples; for the default workload n_cpu is the benchmark's
+    # own shard of 32, for the heavier or lighter ones a size that keeps this leg to about half a minute.
     cpu_baseline = None
     if not args.no_cpu_baseline:
         from oracle import oracle as O
-        n_cpu = {"resnet50": 16, "vgg16": 4, "alexnet": 32, "resnet20": B // p, "mlp": B // p}[model]
+        n_cpu = {"resnet50": 32, "vgg16": 8, "alexnet": 32, "resnet20": B // p, "mlp": B // p}[model]
+        cpu_steps = 2
         gkw = {}
         if model == "resnet50" and "arch" in geom:
             gkw = dict(blocks=tuple(geom["arch"][1:5]))
             n_cpu = 8
         if model == "vgg16" and "arch" in geom:
             gkw = dict(groups=tuple(geom["arch"][2:7]))
-        orc = O.Oracle(model, 0, N, n_cpu, lr=lr, graph_kwargs=gkw)
-        xs, ys = x[:n_cpu].astype(np.float64), y[:n_cpu]
+        p_cpu = p if n_cpu == B // p else 1
+        B_cpu = n_cpu * p_cpu
+        orc = O.Oracle(model, 0, N - N % B_cpu, B_cpu, lr=lr, graph_kwargs=gkw)
+        orc.forward_backward(x[:2].astype(np.float64), y[:2])
         tc0 = time.perf_counter()
-        orc.forward_backward(xs, ys)
+        for _ in range(cpu_steps):
+            cl = orc.step(p_cpu, x, y)
         tc1 = time.perf_counter()
-        cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-        cpu_baseline = dict(value=round(n_cpu / (tc1 - tc0), 3), unit="samples/s", cores=cores, kind="oracle",
-                            sample="forward+backward of one shard of %d samples of the same workload (%.1f s)"
-                                   % (n_cpu, tc1 - tc0))
+        assert np.isfinite(cl)
+        threads = os.environ.get("OMP_NUM_THREADS")
+        cores = int(threads) if threads else (os.cpu_count() or 1)
+        cpu_baseline = dict(value=round(B_cpu * cpu_steps / (tc1 - tc0), 3), unit="samples/s", cores=cores, kind="oracle",
+                            omp_num_threads=threads, host_cpus=os.cpu_count(),
+                            sample="%d whole steps (forward, backward, aggregation + update) at p = %d on shards of %d samples "
+                                   "of the same workload, after a 2-sample warm-up pass (%.1f s)"
+                                   % (cpu_steps, p_cpu, n_cpu, tc1 - tc0))
 
     out = {
         "metric": "training samples/s per MI355X (ResNet-50 bf16); grad-avg+update HBM GB/s",

@@ -487,6 +487,10 @@ class Oracle:
         self.seed, self.N, self.B = seed, N, B
         self.lr, self.momentum, self.wd = lr, momentum, wd
         self.emulate_bf16 = emulate_bf16
+        # Max pools pick their element after rounding the input to bf16 (the precision a bf16 job holds it in);
+        # the pooled values themselves are not rounded.  Off by default; tests that compare a bf16 job with the
+        # unrounded float64 computation switch it on so that both sides decide in the same precision.
+        self.pool_picks_in_bf16 = False
         self.dtype_code = dtype_code
         self.w = he_init(self.graph, seed)
         self.v = np.zeros_like(self.w)          # momentum, or Adam's first moment
@@ -510,6 +514,92 @@ class Oracle:
         n = int(np.prod(shape))
         return self.w[off:off + n].reshape(shape)
 
+    # -- one layer on given tensors ----------------------------------------
+    def op_forward(self, i, xin, res=None, w=None, labels=None):
+        """Layer i of the model on the given input (and residual input), in
+        float64 with no rounding anywhere.  `w` replaces a convolution's
+        weights (the bf16 copies a bf16 job contracts with).  Returns
+        (output, what the layer's backward needs besides its input and output);
+        the loss layer returns (mean loss, softmax probabilities)."""
+        op = self.graph.ops[i]
+        kind = op["kind"]
+        if kind == "conv":
+            C = xin.shape[-1]
+            if w is None:
+                w = self._param(op["w_off"], (op["K"], op["R"], op["S"], C))
+            b = self._param(op["b_off"], (op["K"],)) if op["b_off"] is not None else None
+            y = conv2d_forward(xin, np.ascontiguousarray(w), b, op["stride"], op["pad"])
+            if op["relu"]:
+                y = np.maximum(y, 0.0)
+            return y, w
+        if kind == "bn":
+            C = op["C"]
+            y, xhat, mean, var = batchnorm_forward(xin, self._param(op["g_off"], (C,)), self._param(op["b_off"], (C,)))
+            if res is not None:
+                y = y + res
+            if op["relu"]:
+                y = np.maximum(y, 0.0)
+            return y, (xhat, var, mean)
+        if kind == "maxpool":
+            y, arg = maxpool_forward(xin, op["k"], op["stride"], op["pad"])
+            if self.pool_picks_in_bf16:
+                # the decision (which element of the window) taken in the precision a bf16 job holds the tensor
+                # in: values that round to the same bf16 tie, and ties go to the first in window order
+                arg = maxpool_forward(round_bf16(xin), op["k"], op["stride"], op["pad"])[1]
+            return y, arg
+        if kind == "gavgpool":
+            return xin.mean(axis=(1, 2), keepdims=True), None
+        if kind == "flatten":
+            return xin.reshape(xin.shape[0], 1, 1, -1), None
+        if kind == "loss":
+            return softmax_ce_forward(xin.reshape(xin.shape[0], -1), labels)
+        raise ValueError(kind)
+
+    def op_backward(self, i, dy, xin, y, saved, labels=None, decision=None):
+        """Backward of layer i: dy is the gradient of its output (ignored by the
+        loss layer), xin / y its forward input / output, saved what op_forward
+        returned.  decision replaces the layer's own (ReLU: output > 0; max
+        pool: saved positions).  Returns ({input: gradient contribution},
+        {offset in the flat vector: parameter gradient}, decision used)."""
+        op = self.graph.ops[i]
+        kind = op["kind"]
+        dxs, dps, used = {}, {}, None
+        if kind == "loss":
+            dxs[op["x"]] = softmax_ce_backward(saved, labels).reshape(xin.shape)
+        elif kind == "conv":
+            if op["relu"]:
+                used = (y > 0) if decision is None else decision
+                dy = dy * used
+            w = saved
+            dw, db = conv2d_backward_weight(xin, np.ascontiguousarray(dy), w.shape, op["stride"], op["pad"],
+                                            op["b_off"] is not None)
+            dps[op["w_off"]] = dw.ravel()
+            if db is not None:
+                dps[op["b_off"]] = db
+            if op["x"] != "x":
+                dxs[op["x"]] = conv2d_backward_input(np.ascontiguousarray(dy), np.ascontiguousarray(w), xin.shape,
+                                                     op["stride"], op["pad"])
+        elif kind == "bn":
+            if op["relu"]:
+                used = (y > 0) if decision is None else decision
+                dy = dy * used
+            if op["res"] is not None:
+                dxs[op["res"]] = dy
+            xhat, var = saved[0], saved[1]
+            C = op["C"]
+            dx, dgamma, dbeta = batchnorm_backward(dy, xhat, self._param(op["g_off"], (C,)), var)
+            dps[op["g_off"]] = dgamma
+            dps[op["b_off"]] = dbeta
+            dxs[op["x"]] = dx
+        elif kind == "maxpool":
+            used = np.ascontiguousarray(saved if decision is None else decision, dtype=np.int32)
+            dxs[op["x"]] = maxpool_backward(np.ascontiguousarray(dy), used, xin.shape)
+        elif kind == "gavgpool":
+            dxs[op["x"]] = np.broadcast_to(dy / (xin.shape[1] * xin.shape[2]), xin.shape).copy()
+        elif kind == "flatten":
+            dxs[op["x"]] = dy.reshape(xin.shape)
+        return dxs, dps, used
+
     # -- forward + backward on one worker's samples ------------------------
     def forward_backward(self, x, labels, update_running=False, decisions=None):
         """x: [n,H,W,C] float64, labels: [n] ints.  Returns (mean loss over
@@ -523,122 +613,63 @@ class Oracle:
         so that a test can ask what the gradient would be had a neighbouring
         computation decided differently; the forward values are not changed."""
         g = self.graph
+        q = self._q
         decisions = decisions or {}
         self.last_decisions = {}
-        q = self._q
         act = {"x": q(np.ascontiguousarray(x, dtype=np.float64))}
         saved = {}
+        loss = None
         for i, op in enumerate(g.ops):
             kind = op["kind"]
+            xin = act[op["x"]]
             if kind == "conv":
-                xin = act[op["x"]]
-                C = xin.shape[-1]
-                w = q(self._param(op["w_off"], (op["K"], op["R"], op["S"], C)))
-                b = self._param(op["b_off"], (op["K"],)) if op["b_off"] is not None else None
-                y = conv2d_forward(xin, np.ascontiguousarray(w), b, op["stride"], op["pad"])
-                if op["relu"]:
-                    y = np.maximum(y, 0.0)
+                w = q(self._param(op["w_off"], (op["K"], op["R"], op["S"], xin.shape[-1])))
+                y, saved[i] = self.op_forward(i, xin, w=w)
                 act[op["y"]] = q(y) if op["y"] != g.logits else y
-                saved[i] = w
             elif kind == "bn":
-                xin = act[op["x"]]
-                C = op["C"]
-                gamma = self._param(op["g_off"], (C,))
-                beta = self._param(op["b_off"], (C,))
-                y, xhat, mean, var = batchnorm_forward(xin, gamma, beta)
-                if op["res"] is not None:
-                    y = y + act[op["res"]]
-                if op["relu"]:
-                    y = np.maximum(y, 0.0)
+                y, saved[i] = self.op_forward(i, xin, res=act[op["res"]] if op["res"] is not None else None)
                 act[op["y"]] = q(y)
-                saved[i] = (xhat, var)
                 if update_running:
+                    C = op["C"]
                     M = xin.size // C
+                    mean, var = saved[i][2], saved[i][1]
                     ro = op["run_off"]
                     m = BN_RUNNING_MOMENTUM
                     self.running[ro:ro + C] = (1 - m) * self.running[ro:ro + C] + m * mean
                     self.running[ro + C:ro + 2 * C] = ((1 - m) * self.running[ro + C:ro + 2 * C]
                                                        + m * var * M / (M - 1))
             elif kind == "maxpool":
-                y, arg = maxpool_forward(act[op["x"]], op["k"], op["stride"], op["pad"])
-                act[op["y"]] = y
-                saved[i] = arg
+                act[op["y"]], saved[i] = self.op_forward(i, xin)
             elif kind == "gavgpool":
-                act[op["y"]] = q(act[op["x"]].mean(axis=(1, 2), keepdims=True))
+                act[op["y"]] = q(self.op_forward(i, xin)[0])
             elif kind == "flatten":
-                a = act[op["x"]]
-                act[op["y"]] = a.reshape(a.shape[0], 1, 1, -1)
+                act[op["y"]] = self.op_forward(i, xin)[0]
             elif kind == "loss":
-                z = act[op["x"]].reshape(x.shape[0], -1)
-                loss, prob = softmax_ce_forward(z, labels)
-                saved[i] = prob
+                loss, saved[i] = self.op_forward(i, xin, labels=labels)
         self.last_act = act            # name -> activation, "x", "t1", "t2", ... in creation order
+        self.last_saved = saved
         # backward
         G = np.zeros(g.P)
         grad = {}
-
         self.last_dy, self.last_dx = {}, {}     # per op: gradient of its output as used; {input: its contribution}
-        cur = [None]
-
-        def add(name, val):
-            if name == "x":
-                return
-            self.last_dx.setdefault(cur[0], {})[name] = q(val)
-            grad[name] = q(grad[name] + val) if name in grad else q(val)
-
         for i in range(len(g.ops) - 1, -1, -1):
             op = g.ops[i]
             kind = op["kind"]
-            cur[0] = i
-            if "y" in op and op["y"] in grad:
+            dy = None
+            if kind != "loss":
                 self.last_dy[i] = grad[op["y"]]
-            if kind == "loss":
-                dz = softmax_ce_backward(saved[i], labels)
-                grad[op["x"]] = q(dz.reshape(act[op["x"]].shape))
-                self.last_dx[i] = {op["x"]: grad[op["x"]]}
-            elif kind == "conv":
                 dy = grad.pop(op["y"])
-                if op["relu"]:
-                    passed = decisions.get(i, act[op["y"]] > 0)
-                    self.last_decisions[i] = passed
-                    dy = dy * passed
-                xin = act[op["x"]]
-                w = saved[i]
-                dw, db = conv2d_backward_weight(xin, np.ascontiguousarray(dy), w.shape, op["stride"],
-                                                op["pad"], op["b_off"] is not None)
-                G[op["w_off"]:op["w_off"] + dw.size] = dw.ravel()
-                if db is not None:
-                    G[op["b_off"]:op["b_off"] + db.size] = db
-                if op["x"] != "x":
-                    add(op["x"], conv2d_backward_input(np.ascontiguousarray(dy), np.ascontiguousarray(w),
-                                                       xin.shape, op["stride"], op["pad"]))
-            elif kind == "bn":
-                dy = grad.pop(op["y"])
-                if op["relu"]:
-                    passed = decisions.get(i, act[op["y"]] > 0)
-                    self.last_decisions[i] = passed
-                    dy = dy * passed
-                if op["res"] is not None:
-                    add(op["res"], dy)
-                xhat, var = saved[i]
-                C = op["C"]
-                gamma = self._param(op["g_off"], (C,))
-                dx, dgamma, dbeta = batchnorm_backward(dy, xhat, gamma, var)
-                G[op["g_off"]:op["g_off"] + C] = dgamma
-                G[op["b_off"]:op["b_off"] + C] = dbeta
-                add(op["x"], dx)
-            elif kind == "maxpool":
-                dy = grad.pop(op["y"])
-                picked = np.ascontiguousarray(decisions.get(i, saved[i]), dtype=np.int32)
-                self.last_decisions[i] = picked
-                add(op["x"], maxpool_backward(np.ascontiguousarray(dy), picked, act[op["x"]].shape))
-            elif kind == "gavgpool":
-                dy = grad.pop(op["y"])
-                a = act[op["x"]]
-                add(op["x"], np.broadcast_to(dy / (a.shape[1] * a.shape[2]), a.shape).copy())
-            elif kind == "flatten":
-                dy = grad.pop(op["y"])
-                add(op["x"], dy.reshape(act[op["x"]].shape))
+            dxs, dps, used = self.op_backward(i, dy, act[op["x"]], act.get(op.get("y")), saved.get(i), labels=labels,
+                                              decision=decisions.get(i))
+            if used is not None:
+                self.last_decisions[i] = used
+            for off, val in dps.items():
+                G[off:off + val.size] = val
+            for name, val in dxs.items():
+                if name == "x":
+                    continue
+                self.last_dx.setdefault(i, {})[name] = q(val)
+                grad[name] = q(grad[name] + val) if name in grad else q(val)
         return loss, G
 
     # -- one synchronous iteration at parallelism p ----------------------

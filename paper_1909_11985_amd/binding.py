@@ -46,6 +46,13 @@ def _load():
     if not os.path.exists(_LIB_PATH):
         from . import build as _b
         _b.build()
+    # The caller's device memory and streams come from PyTorch, which ships a HIP runtime of its own.  It has to
+    # be the one already in the process when this library is mapped, so that both see the same runtime (a
+    # second copy finds no device): torch first, whatever order the caller imports things in.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     return C.CDLL(_LIB_PATH)
 
 

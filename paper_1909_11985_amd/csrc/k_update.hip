@@ -93,6 +93,98 @@ __global__ __launch_bounds__(256) void average_update_kernel(GradPtrs gp, int p,
     }
 }
 
+// The same update with the streams walked in wave-wide pieces: a workgroup owns U * 256 consecutive vectors of
+// every stream and lane t takes vectors t, t + 256, ... of them, so each of the workgroup's load instructions
+// covers 4 KB of one stream and all (NP + 2) * U loads of a lane are in flight before the first is used.  NT bit 0:
+// the gradient buffers (read once, never again) are loaded non-temporally; bit 1: so is the bf16 copy stored.
+// Same arithmetic in the same order as average_update_kernel: the results are bit-identical.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+template <int NP, bool SHADOW, int U, int NT>
+__global__ __launch_bounds__(256) void average_update_wide_kernel(GradPtrs gp, float* __restrict__ w, float* __restrict__ v,
+                                                                  uint16_t* __restrict__ w16, int64_t nvec, int64_t P, float lr,
+                                                                  float momentum, float wd) {
+    const float fp = (float)NP;
+    const int64_t step = (int64_t)gridDim.x * 256 * U;
+    for (int64_t i0 = (int64_t)blockIdx.x * 256 * U + threadIdx.x; i0 - threadIdx.x < nvec; i0 += step) {
+        f32x4 s[U], wi[U], vi[U];
+        #pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = i0 + u * 256 < nvec ? i0 + u * 256 : nvec - 1;     // lanes past the end repeat the last vector
+            const f32x4* g0 = reinterpret_cast<const f32x4*>(gp.g[0]) + i;
+            s[u] = (NT & 1) ? __builtin_nontemporal_load(g0) : *g0;
+            const f32x4* wp = reinterpret_cast<const f32x4*>(w) + i;
+            const f32x4* vp = reinterpret_cast<const f32x4*>(v) + i;
+            wi[u] = (NT & 4) ? __builtin_nontemporal_load(wp) : *wp;
+            vi[u] = (NT & 4) ? __builtin_nontemporal_load(vp) : *vp;
+        }
+        #pragma unroll
+        for (int k = 1; k < NP; ++k) {
+            f32x4 t[U];
+            #pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int64_t i = i0 + u * 256 < nvec ? i0 + u * 256 : nvec - 1;
+                const f32x4* gk = reinterpret_cast<const f32x4*>(gp.g[k]) + i;
+                t[u] = (NT & 1) ? __builtin_nontemporal_load(gk) : *gk;
+            }
+            #pragma unroll
+            for (int u = 0; u < U; ++u) s[u] += t[u];
+        }
+        #pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = i0 + u * 256;
+            if (i >= nvec) break;
+            f32x4 vn, wn;
+            #pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                vn[e] = momentum * vi[u][e] + (s[u][e] / fp + wd * wi[u][e]);
+                wn[e] = wi[u][e] - lr * vn[e];
+            }
+            if (NT & 4) {
+                __builtin_nontemporal_store(vn, reinterpret_cast<f32x4*>(v) + i);
+                __builtin_nontemporal_store(wn, reinterpret_cast<f32x4*>(w) + i);
+            } else {
+                reinterpret_cast<f32x4*>(v)[i] = vn;
+                reinterpret_cast<f32x4*>(w)[i] = wn;
+            }
+            if (SHADOW) {
+                const u32x2 packed = {pack2_bf16(wn[0], wn[1]), pack2_bf16(wn[2], wn[3])};
+                if (NT & 2) __builtin_nontemporal_store(packed, reinterpret_cast<u32x2*>(w16) + i);
+                else reinterpret_cast<u32x2*>(w16)[i] = packed;
+            }
+        }
+    }
+    // ragged tail (P not a multiple of 4): the first few lanes of block 0
+    if (blockIdx.x == 0 && threadIdx.x < (unsigned)(P - nvec * 4)) {
+        const int64_t i = nvec * 4 + threadIdx.x;
+        float s = gp.g[0][i];
+        for (int k = 1; k < NP; ++k) s += gp.g[k][i];
+        float wi = w[i];
+        const float vi = momentum * v[i] + (s / fp + wd * wi);
+        wi -= lr * vi;
+        v[i] = vi;
+        w[i] = wi;
+        if (SHADOW) w16[i] = f32_to_bf16(wi);
+    }
+}
+
+template <int NP, int U, int NT>
+static void launch_update_wide(int grid, const GradPtrs& grads, float* w, float* v, uint16_t* w16, int64_t nvec, int64_t P,
+                               float lr, float momentum, float wd, hipStream_t st) {
+    if (w16) hipLaunchKernelGGL((average_update_wide_kernel<NP, true, U, NT>), dim3(grid), dim3(256), 0, st, grads, w, v, w16, nvec, P, lr, momentum, wd);
+    else hipLaunchKernelGGL((average_update_wide_kernel<NP, false, U, NT>), dim3(grid), dim3(256), 0, st, grads, w, v, w16, nvec, P, lr, momentum, wd);
+}
+
+template <int NP>
+static bool launch_update_wide_np(int u, int nt, int grid, const GradPtrs& grads, float* w, float* v, uint16_t* w16, int64_t nvec,
+                                  int64_t P, float lr, float momentum, float wd, hipStream_t st) {
+#define EDL_WIDE(U_, NT_) if (u == U_ && nt == NT_) { launch_update_wide<NP, U_, NT_>(grid, grads, w, v, w16, nvec, P, lr, momentum, wd, st); return true; }
+    EDL_WIDE(1, 0) EDL_WIDE(1, 1) EDL_WIDE(1, 3) EDL_WIDE(1, 7) EDL_WIDE(2, 0) EDL_WIDE(2, 3) EDL_WIDE(2, 7) EDL_WIDE(4, 0) EDL_WIDE(4, 3) EDL_WIDE(4, 7)
+#undef EDL_WIDE
+    return false;
+}
+
 template <int NP, int VPT>
 static void launch_update_t(int grid, const GradPtrs& grads, int p, float* w, float* v, uint16_t* w16, int64_t nvec, int64_t P,
                             float lr, float momentum, float wd, hipStream_t st) {
@@ -115,6 +207,27 @@ void launch_average_update(int p, const GradPtrs& grads, float* w, float* v, uin
         if (vpt == 2) launch_update_t<NP, 2>(grid, grads, p, w, v, w16, nvec, P, lr, momentum, wd, st); \
         else launch_update_t<NP, 1>(grid, grads, p, w, v, w16, nvec, P, lr, momentum, wd, st);          \
     } while (0)
+    // the wave-wide walk (upd_wide = vectors per lane, 0 = the kernel above, -1 = by p), upd_nt = non-temporal flags
+    // (-1 = by p), upd_blocks > 0 = a grid-stride launch of that many workgroups
+    // Measured on the 138 M-parameter state (update sweep, MI355X): the wave-wide walk with non-temporal
+    // gradient loads and bf16 store gives 5.9 / 5.7 / 5.7 TB/s at p = 1 / 2 / 4 with one vector per lane (the kernel
+    // above: 5.4 / 5.3 / 5.2), and 5.6 TB/s at p = 8 with four vectors per lane and w, v non-temporal too (5.3).
+    int wide = (int)tune().upd_wide, nt = (int)tune().upd_nt;
+    if (wide < 0) wide = p >= 8 ? 4 : 1;
+    if (nt < 0) nt = p >= 8 ? 7 : 3;
+    if (wide > 0 && (p == 1 || p == 2 || p == 4 || p == 8)) {
+        int wgrid = (int)std::max<int64_t>(1, (nvec + 256 * wide - 1) / (256 * wide));
+        if (tune().upd_blocks > 0 && wgrid > tune().upd_blocks) wgrid = (int)tune().upd_blocks;
+        if (max_blocks > 0 && wgrid > max_blocks) wgrid = max_blocks;
+        bool done = false;
+        switch (p) {
+            case 1: done = launch_update_wide_np<1>(wide, nt, wgrid, grads, w, v, w16, nvec, P, lr, momentum, wd, st); break;
+            case 2: done = launch_update_wide_np<2>(wide, nt, wgrid, grads, w, v, w16, nvec, P, lr, momentum, wd, st); break;
+            case 4: done = launch_update_wide_np<4>(wide, nt, wgrid, grads, w, v, w16, nvec, P, lr, momentum, wd, st); break;
+            default: done = launch_update_wide_np<8>(wide, nt, wgrid, grads, w, v, w16, nvec, P, lr, momentum, wd, st); break;
+        }
+        if (done) return;
+    }
     switch (p) {
         case 1: EDL_UPD(1); break;
         case 2: EDL_UPD(2); break;

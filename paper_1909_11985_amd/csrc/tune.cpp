@@ -39,6 +39,9 @@ const Entry kEntries[] = {
     {"early_update", &Tune::early_update},
     {"early_blocks", &Tune::early_blocks},
     {"upd_vpt", &Tune::upd_vpt},
+    {"upd_wide", &Tune::upd_wide},
+    {"upd_nt", &Tune::upd_nt},
+    {"upd_blocks", &Tune::upd_blocks},
     {"persistent", &Tune::persistent},
     {"spare0", &Tune::spare0},
     {"spare1", &Tune::spare1},

@@ -5,8 +5,8 @@ import pytest
 
 import synth_inputs
 from oracle import oracle as O
-from parity_util import (TOL, conv_bn_pair_parity, forced_parity, layerwise_parity, relerr, relu_producer_pair_parity,
-                         run_parity)
+from parity_util import (TIGHT, TOL, conv_bn_pair_parity, forced_parity, layerwise_ok, layerwise_parity, relerr,
+                         relu_producer_pair_parity, run_parity, stepwise_parity)
 
 pytestmark = pytest.mark.gpu
 
@@ -141,16 +141,23 @@ def test_copy_is_exact(nbytes, shift):
 
 
 # ---------------------------------------------------------------- parity of the training pass
-# Three kinds of comparison, all through the C boundary (the reasons are in the design notes):
-#  * layerwise: every layer alone, at its in-network shape, on the oracle's inputs -> the stated
-#    tolerance (1e-4 float32, 2e-2 bf16) on outputs, input gradients and parameter gradients;
-#  * pinned: the whole backward chain in one go with the ReLU-sign / arg-max decisions taken from
-#    the oracle's activations -> the stated tolerance for float32; for bf16 the whole-vector error
-#    (rounding-boundary differences of ~6e-5 per layer are amplified by the chain);
-#  * free running: edl_step against oracle.step over several steps and p changes.  A ReLU whose
-#    input is within rounding of zero may take the other sign on the GPU, which changes a tensor's
-#    gradient by ~1/sqrt(elements) however exact the arithmetic is; tight agreement is therefore
-#    asserted where no such decision is near (shallow nets), a loose one elsewhere.
+# All comparisons go through the C boundary and carry two criteria per tensor, norm-wise and element-wise
+# (parity_util).  bf16 jobs are compared with the plain float64 oracle at the stated 2e-2 and, as a tight
+# regression bound, with the oracle that rounds where the HIP path stores bf16; float32 jobs with the plain
+# oracle at a bound tighter than the stated 1e-4.
+#  * layerwise: every layer alone, at its in-network shape, on the oracle's inputs;
+#  * pairs: layers that hand something to their neighbour inside a step (batch statistics out of the
+#    convolution's epilogue; masked gradient + column sums out of the input-gradient epilogue, also at
+#    residual joins), run together as a step runs them;
+#  * pinned chain: one worker's whole backward pass in one go with the ReLU-sign / arg-max decisions taken
+#    from the oracle's activations;
+#  * step by step along a real trajectory (the configurations' schedules, p changing): at every checked step
+#    the oracle starts from the job's own parameters and momentum; pinned-chain gradients on that step's real
+#    shards, free-running gradients given the decisions the HIP forward pass took (float32), free-running
+#    losses, the update formula on the job's own gradient buffers, running statistics, bit-exact shard sets.
+# A ReLU whose input is within rounding of zero may take the other sign on the GPU, which changes a tensor's
+# gradient by a whole term however exact the arithmetic is (tests/test_oracle_decisions.py shows it inside
+# the oracle): this is why gradients are compared given the decisions and never across several free steps.
 TINY = {
     "mlp": dict(H=1, W=1, C=24, classes=5, arch=(20, 12)),                 # odd sizes: scalar load paths
     "resnet20": dict(H=12, W=12, C=3, classes=6, arch=(8, 2, 1)),
@@ -165,13 +172,12 @@ DEEP = {
     "vgg19": ("vgg16", dict(H=64, W=64, arch=(64, 512, 2, 2, 4, 4, 4))),
     "alexnet": ("alexnet", dict(H=131, W=131, arch=(64, 512))),
 }
-# the bf16 chain amplifies last-place differences; see the comment above
-PINNED_WHOLE_TOL = {"f32": 1e-4, "bf16": 5e-2}
 
 
 def _assert_layerwise(r, dtype):
-    tol = TOL[dtype]
-    assert r["fwd"] < tol and r["dx"] < tol and r["dw"] < tol, r
+    ok, text = layerwise_ok(r, dtype)
+    print(text)
+    assert ok, text
 
 
 @pytest.mark.parametrize("model", list(TINY))
@@ -212,9 +218,8 @@ def test_convolution_hands_batch_statistics_to_its_batch_norm(model, dtype, n, k
     """Convolution + batch norm run as a pair, as inside a step: the batch norm's output against the
     oracle's, from the oracle's input of the convolution."""
     r = conv_bn_pair_parity(model, dtype, n, **kw)
-    print(r)
-    assert r["pairs"] > 0
-    assert r["fwd"] < TOL[dtype], r
+    assert r["plain"]["pairs"] > 0
+    _assert_layerwise(r, dtype)
 
 
 @pytest.mark.parametrize("model,dtype,n,kw", [
@@ -227,9 +232,23 @@ def test_input_gradient_pass_hands_masked_gradient_and_sums_to_its_producer(mode
     """ReLU-ending producer + convolution run backward as a pair, as inside a step: the producer's input gradient
     and parameter gradients against the oracle's, from the oracle's tensors."""
     r = relu_producer_pair_parity(model, dtype, n, **kw)
-    print(r)
-    assert r["pairs"] > 0
-    assert r["dx"] < TOL[dtype] and r["dw"] < TOL[dtype], r
+    assert r["plain"]["pairs"] > 0
+    if model.startswith("resnet"):
+        assert r["plain"]["join_pairs"] > 0
+    _assert_layerwise(r, dtype)
+
+
+def test_residual_join_epilogue_at_the_benchmark_shape():
+    """The 15 residual joins of ResNet-50 at 224x224 with the shard of 32: the first convolution of a block runs
+    its input-gradient pass on top of the shortcut's part already in the buffer (the oracle's), masks the total
+    by the previous block's ReLU and leaves that block's batch-norm sums.  Here on the tile a plain launch of
+    that shape would get (option join_tile = 0); the 128x64 tile the heuristics give this epilogue is what the
+    test of all 47 pairs at this shape runs."""
+    import paper_1909_11985_amd as E
+    with E.options(join_tile=0):
+        r = relu_producer_pair_parity("resnet50", "bf16", 32, only_joins=True)
+    assert r["plain"]["join_pairs"] == r["plain"]["pairs"] == 15
+    _assert_layerwise(r, "bf16")
 
 
 def test_layerwise_resnet50_bf16_at_the_benchmark_shape():
@@ -239,35 +258,20 @@ def test_layerwise_resnet50_bf16_at_the_benchmark_shape():
     _assert_layerwise(r, "bf16")
 
 
-_FORCED_TILE_SCRIPT = r"""
-import sys
-sys.path.insert(0, sys.argv[1]); sys.path.insert(0, sys.argv[2])
-from parity_util import TOL, layerwise_parity, forced_parity
-cases = [("resnet50", dict(H=64, W=64)), ("resnet50", dict(H=32, W=32, C=3, classes=10, arch=(8, 1, 1, 0, 0))),
-         ("vgg16", dict(H=64, W=64, arch=(64, 512))), ("resnet20", {})]
-for model, kw in cases:
-    for dtype, n in (("bf16", 9), ("f32", 5)):
-        r = layerwise_parity(model, dtype, n, verbose=False, **kw)
-        assert r["fwd"] < TOL[dtype] and r["dx"] < TOL[dtype] and r["dw"] < TOL[dtype], (model, dtype, r)
-r = forced_parity("resnet50", "bf16", 8, H=64, W=64)
-assert r["fwd"] < TOL["bf16"] and r["loss"] < TOL["bf16"] and r["grad_whole"] < 5e-2, r
-print("ok")
-"""
-
-
 @pytest.mark.parametrize("tile", [0, 1, 2, 3])
 def test_layerwise_under_every_tile_shape(tile):
     """The tile heuristics pick one shape per layer; here every forward / dgrad launch is forced onto 128x128,
-    128x64, 128x32 or 64x64 tiles in turn (the library reads the knob once, hence the child process), on shapes
-    with ragged rows and columns, so that each kernel variant meets each kind of layer."""
-    import os
-    import subprocess
-    import sys
-    here = os.path.dirname(os.path.abspath(__file__))
-    env = dict(os.environ, EDL_TUNE_FORCE_TILE=str(tile))
-    out = subprocess.run([sys.executable, "-c", _FORCED_TILE_SCRIPT, os.path.dirname(here), here], env=env,
-                         capture_output=True, text=True, timeout=600)
-    assert out.returncode == 0 and out.stdout.strip().endswith("ok"), out.stdout[-2000:] + out.stderr[-2000:]
+    128x64, 128x32 or 64x64 tiles in turn (option force_tile), on shapes with ragged rows and columns, so that
+    each kernel variant meets each kind of layer."""
+    import paper_1909_11985_amd as E
+    cases = [("resnet50", dict(H=64, W=64)), ("resnet50", TINY["resnet50"]), ("vgg16", dict(H=64, W=64, arch=(64, 512))),
+             ("resnet20", {})]
+    with E.options(force_tile=tile):
+        for model, kw in cases:
+            for dtype, n in (("bf16", 9), ("f32", 5)):
+                _assert_layerwise(layerwise_parity(model, dtype, n, verbose=False, **kw), dtype)
+        _assert_pinned(forced_parity("resnet50", "bf16", 8, H=64, W=64, verbose=False), "bf16")
+    assert E.edl_get_option("force_tile") == -1
 
 
 def test_layerwise_vgg16_bf16_at_full_size():
@@ -284,6 +288,22 @@ def test_layerwise_alexnet_bf16_at_full_size():
     _assert_layerwise(r, "bf16")
 
 
+def _assert_pinned(r, dtype, whole_bound=None):
+    """float32: every parameter tensor norm-wise below the tight bound and element-wise within the stated bar.
+    bf16: the whole gradient vector at the stated 2e-2 (whole_bound: a case's own, recorded bound), against the
+    plain float64 chain and against the rounding one (single tensors whose terms cancel - a batch-norm shift
+    behind another batch norm - carry no per-tensor statement in bf16: measured up to 1e-1 on the stem's shift
+    with either reference)."""
+    for mode, m in r.items():
+        assert m["loss"] < TOL[dtype], (mode, m)
+        if dtype == "f32":
+            assert m["fwd"] < TIGHT["f32"] and m["fwd_elem"] <= 1.0, (mode, m)
+            assert m["grad"] < TIGHT["f32"] and m["grad_elem"] <= 1.0, (mode, m)
+        else:
+            assert m["fwd"] < (TOL["bf16"] if mode == "plain" else TIGHT["bf16"]), (mode, m)
+            assert m["grad_whole"] < (whole_bound or TOL["bf16"]), (mode, m)
+
+
 @pytest.mark.parametrize("model,dtype,n,kw", [
     ("mlp", "f32", 12, TINY["mlp"]), ("resnet20", "f32", 12, TINY["resnet20"]),
     ("resnet50", "f32", 12, TINY["resnet50"]), ("vgg16", "f32", 12, TINY["vgg16"]),
@@ -292,71 +312,126 @@ def test_layerwise_alexnet_bf16_at_full_size():
     ("resnet50", "f32", 16, dict(H=64, W=64)), ("resnet50", "bf16", 16, dict(H=64, W=64)),
     ("vgg16", "bf16", 8, dict(H=64, W=64, arch=(64, 512))),
     ("alexnet", "f32", 12, TINY["alexnet"]), ("alexnet", "bf16", 8, DEEP["alexnet"][1]),
-    ("vgg16", "bf16", 8, DEEP["vgg19"][1]), ("resnet50", "bf16", 8, DEEP["resnet101"][1]),
+    ("vgg16", "bf16", 8, DEEP["vgg19"][1]), ("resnet50", "f32", 8, DEEP["resnet101"][1]),
 ])
 def test_pinned_backward_chain(model, dtype, n, kw):
-    r = forced_parity(model, dtype, n, **kw)
-    assert r["fwd"] < TOL[dtype] and r["loss"] < TOL[dtype], r
-    assert r["grad_whole"] < PINNED_WHOLE_TOL[dtype], r
+    _assert_pinned(forced_parity(model, dtype, n, **kw), dtype)
+
+
+def test_pinned_backward_chain_of_resnet101_in_bf16():
+    """The one chain that does not meet 2e-2 on the whole gradient vector in bf16: ResNet-101, 101 layers of bf16
+    gradient tensors behind one another.  Measured 2.08e-2 against the plain float64 chain and 2.29e-2 against
+    the rounding one at 128x128 images (2.09e-2 / 2.25e-2 at 64x64), so it is the chain's own rounding noise, not
+    the reference's; the same chain in float32 is inside 5e-5 per tensor (the case above), and every one of
+    its layers alone meets the bar in bf16 (test_layerwise_other_networks_of_the_evaluation).  Held to 3e-2."""
+    _assert_pinned(forced_parity("resnet50", "bf16", 8, H=128, W=128, arch=(64, 3, 4, 23, 3)), "bf16", whole_bound=3e-2)
+
+
+# ---------------------------------------------------------------- step by step along the configurations' trajectories
+def _assert_stepwise(r, dtype, steps, free=None):
+    """What every checked step of a trajectory carries (parity_util.stepwise_parity)."""
+    print({k: v for k, v in r.items() if k not in ("job", "case", "table", "losses")})
+    assert r["checked_steps"] == steps and r["checked_shards"] >= steps
+    assert r["update"] < 1e-6, r["update"]              # the oracle's update formula on the job's own gradient buffers
     if dtype == "f32":
-        assert r["grad"] < TOL["f32"], r
+        assert r["pinned"] < TOL["f32"] and r["pinned_elem"] <= 1.0, (r["pinned"], r["pinned_elem"])
+        assert r["loss"] < 1e-5 and r["running"] < TOL["f32"], (r["loss"], r["running"])
+        if free is not False:
+            # free-running gradients, given the decisions the HIP forward pass took
+            assert r["decisions"] > 0 and r["free"] < TOL["f32"] and r["free_elem"] <= 1.0, (r["free"], r["free_elem"])
+    else:
+        assert r["pinned_whole"] < TOL["bf16"], r["pinned_whole"]
+        assert r["loss"] < TOL["bf16"] and r["running"] < TOL["bf16"], (r["loss"], r["running"])
+    assert all(np.isfinite(l) for l in r["losses"])
 
 
 def test_config1_mlp_fp32():
-    """MLP 784-256-256-10, global batch 64 as p=4 shards of 16, 5 steps, free running."""
-    r = run_parity("mlp", "f32", N=1024, B=64, schedule=[4] * 5)
+    """MLP 784-256-256-10, global batch 64 as p=4 shards of 16, 5 steps: free running against the free-running
+    oracle (gradients, parameters after every step: norm-wise and element-wise), and step by step."""
+    r = run_parity("mlp", "f32", N=1024, B=64, schedule=[4] * 5, verbose=False)
     assert r["grad"] < TOL["f32"] and r["param"] < TOL["f32"] and r["loss"] < 1e-5, r
+    assert r["grad_elem"] <= 1.0 and r["param_elem"] <= 1.0, r
+    s = stepwise_parity("mlp", "f32", N=1024, B=64, schedule=[4] * 5, verbose=False)
+    _assert_stepwise(s, "f32", 5)
+    assert s["job"].progress() == (5, 0, 5)
+
+
+@pytest.mark.parametrize("model", ["mlp", "vgg16", "resnet20", "alexnet", "resnet50"])
+def test_step_by_step_tiny_fp32(model):
+    """Several steps with p changing every step (shards of 12, 24, 6, 8 samples), every step and shard checked."""
+    lr = 0.01 if model in ("vgg16", "alexnet") else 0.1
+    r = stepwise_parity(model, "f32", N=48, B=24, schedule=[2, 1, 4, 3], lr=lr, verbose=False, **TINY[model])
+    _assert_stepwise(r, "f32", 4)
+    assert r["checked_shards"] == 10
 
 
 @pytest.mark.parametrize("model", ["mlp", "vgg16", "resnet20", "alexnet"])
 def test_free_running_tiny_fp32(model):
-    """Several steps with p changing every step (shards of 12, 24, 6, 8 samples)."""
+    """The same schedule with both sides running freely from the same initial model.  Held to the stated bar where
+    no ReLU / arg-max decision differs between the two (these seeds; the step-by-step test above is the one that
+    does not depend on that).  The tiny ResNet-50 is not in this list: one of its ~760,000 decisions per step
+    falls within float32 rounding of zero at the third step, after which the two free trajectories are different
+    training runs (gradient error 0.23); given the decisions it agrees to 5e-6 (test_step_by_step_tiny_fp32)."""
     lr = 0.01 if model in ("vgg16", "alexnet") else 0.1
-    r = run_parity(model, "f32", N=48, B=24, schedule=[2, 1, 4, 3], lr=lr, **TINY[model])
+    r = run_parity(model, "f32", N=48, B=24, schedule=[2, 1, 4, 3], lr=lr, verbose=False, **TINY[model])
     assert r["grad"] < TOL["f32"] and r["param"] < TOL["f32"] and r["momentum"] < TOL["f32"], r
     assert r["running"] < TOL["f32"] and r["loss"] < 1e-5
 
 
 def test_config2_resnet20_fp32_p_changes():
-    """ResNet-20, global batch 128, p = 2 -> 4 -> 8 at steps 10 / 20, 30 steps (crosses an epoch).
-    The trajectory is chaotic in the sense of the comment above, so the tight check is on the
-    first step and the rest is held to the oracle's loss curve."""
-    first = run_parity("resnet20", "f32", N=2048, B=128, schedule=[2], verbose=False)
-    assert first["loss"] < 1e-5 and first["param_whole"] < TOL["f32"], first
-    r = run_parity("resnet20", "f32", N=2048, B=128, schedule=[2] * 10 + [4] * 10 + [8] * 10,
-                   check_every_step=False)
+    """ResNet-20, global batch 128, p = 2 -> 4 -> 8 at steps 10 / 20, 30 steps (crosses an epoch): every step
+    checked, on worker 0's shard and one more that moves round (52 shards of 64, 32 and 16 samples)."""
+    r = stepwise_parity("resnet20", "f32", N=2048, B=128, schedule=[2] * 10 + [4] * 10 + [8] * 10,
+                        shards_of=lambda t, p: (0, t % p), verbose=False)
+    _assert_stepwise(r, "f32", 30)
     assert r["job"].progress() == (30, 1, 14)
-    assert r["loss"] < 0.05, r                                   # every step's loss within 5% of the oracle's
-    assert r["grad_whole"] < 2.0                                 # finite and of the oracle's magnitude
+    assert r["checked_shards"] == 52
+    print("decisions that differed between the HIP forward pass and the oracle's: %d of %d" % (r["flips"], r["decisions"]))
 
 
-def test_free_running_resnet50_bf16():
-    """Full ResNet-50 layer table at 64x64, p = 1, 2, 1: losses follow the oracle's.  The first loss is a
-    forward pass on equal weights and is held to the bf16 bar.  Later ones see weights moved by
-    free-running bf16 gradients, which decorrelate from the oracle's with depth (rounding decides ReLU
-    signs; the pinned tests above take that away), so they are held to the loss curve only, at a
-    learning rate at which this net does not blow up on white-noise images."""
-    r = run_parity("resnet50", "bf16", N=64, B=32, schedule=[1, 2, 1], H=64, W=64, lr=0.002, check_every_step=False)
-    assert r["loss_steps"][0] < TOL["bf16"], r
-    assert r["loss"] < 0.1, r
+def test_config3_resnet50_bf16_shard_of_32_at_full_size():
+    """ResNet-50 at 224x224, bf16, one worker's shard of 32, 20 steps at lr 0.1 - the job bench.py times: the
+    first, a middle and the last step are checked on the real shard."""
+    r = stepwise_parity("resnet50", "bf16", N=1024, B=32, schedule=[1] * 20, check=(0, 10, 19), verbose=False)
+    _assert_stepwise(r, "bf16", 3)
+    assert r["job"].progress() == (20, 0, 20)
+
+
+def test_config4_vgg16_bf16_batch_32_at_full_size():
+    """VGG-16 at 224x224, bf16, batch 32, 3 steps at lr 0.01: the first and the last are checked (25088-long
+    reductions, the 102,760,448-weight layer, the early update of the large layers inside the step)."""
+    r = stepwise_parity("vgg16", "bf16", N=64, B=32, schedule=[1] * 3, lr=0.01, check=(0, 2), verbose=False)
+    _assert_stepwise(r, "bf16", 2)
+    assert r["job"].progress() == (3, 1, 1)
+
+
+def test_config5_elastic_schedule_resnet50_bf16_at_full_size():
+    """The elastic schedule at full size: ResNet-50 bf16, 224x224, aggregate batch 256, two mini-batches per phase
+    of p = 4 -> 8 -> 4 (shards of 64, 32, 64): the step before and after each change of p is checked on one shard
+    (worker 0's before a change, the last worker's after it); shard index sets bit-exact at every step."""
+    sched = [4, 4, 8, 8, 4, 4]
+    r = stepwise_parity("resnet50", "bf16", N=1024, B=256, schedule=sched, check=(1, 2, 3, 4), max_shard=64,
+                        shards_of=lambda t, p: (0,) if t in (1, 3) else (p - 1,), verbose=False)
+    _assert_stepwise(r, "bf16", 4)
+    assert r["job"].progress() == (6, 1, 2)
 
 
 def test_config5_elastic_schedule_resnet50_bf16():
-    """The elastic schedule: the aggregate batch stays fixed while p goes 1 -> 2 -> 4 -> 8 -> 4 (here on 64x64
-    images, batch 32, one mini-batch per phase).  The shard index sets are the oracle's bit for bit at every p
-    (asserted inside run_parity), the losses follow the oracle's, and at every adjustment a joiner that receives
-    the state image continues exactly as the job it joined."""
+    """The whole elastic schedule, p = 1 -> 2 -> 4 -> 8 -> 4 with the aggregate batch fixed at 256 (here on 64x64
+    images, two mini-batches per phase): the step before and after every change of p is checked on worker 0's
+    shard; the shard index sets are the oracle's bit for bit at every p; and at every adjustment a joiner that
+    receives the state image continues exactly as the job it joined."""
     torch = _torch()
     import paper_1909_11985_amd as E
-    schedule = [1, 2, 4, 8, 4]
-    r = run_parity("resnet50", "bf16", N=64, B=32, schedule=schedule, H=64, W=64, lr=0.002, check_every_step=False)
-    assert r["loss_steps"][0] < TOL["bf16"], r
-    assert r["loss"] < 0.1, r
-    assert r["job"].progress() == (5, 2, 1)
+    sched = [1, 1, 2, 2, 4, 4, 8, 8, 4, 4]
+    r = stepwise_parity("resnet50", "bf16", N=512, B=256, schedule=sched, H=64, W=64, lr=0.01, check=tuple(range(1, 9)),
+                        shards_of=lambda t, p: (0,), verbose=False)
+    _assert_stepwise(r, "bf16", 8)
     job = r["job"]
+    assert job.progress() == (10, 5, 0)
     joiner = E.Job(job.cfg, 123)
     joiner.bind_dataset(*job._data)
-    for p in schedule:
+    for p in (1, 2, 4, 8, 4):
         snap = job.snapshot()
         joiner.restore(snap)
         assert joiner.progress() == job.progress()
@@ -440,8 +515,7 @@ def test_profile_parallelism_scales_in_and_trains_like_the_same_steps():
 @pytest.mark.parametrize("model,dtype", [("mlp", "f32"), ("resnet20", "f32"), ("resnet50", "bf16")])
 def test_unequal_shards_weigh_in_with_their_share(model, dtype):
     """A caller's cut with unequal (and one empty) shard: gradients per shard, the weighted aggregate and the
-    update against the oracle's; then the current mini-batch redone by three survivors of four workers
-    (approximate recovery): 24 samples as 8 + 8 + 8, and 11 + 11 + 10 of a batch of 32 would be the same path."""
+    update against the oracle's, for three cuts in a row; then cuts that the call must refuse."""
     torch = _torch()
     import paper_1909_11985_amd as E
     from paper_1909_11985_amd.binding import make_config
@@ -511,6 +585,97 @@ def test_a_tail_batch_of_the_pipeline_trains():
         assert abs(loss - lo) < 1e-5 * max(abs(lo), 1.0)
     assert off.tolist() == [0, 6, 12, 12]
     assert relerr(job.params(), orc.w) < TOL["f32"]
+
+
+# ---------------------------------------------------------------- approximate recovery
+@pytest.mark.parametrize("model,dtype,B,p,lost", [("mlp", "f32", 32, 4, 2), ("resnet20", "f32", 32, 4, 0),
+                                                  ("resnet50", "bf16", 32, 4, 3), ("vgg16", "f32", 8, 8, 5)])
+def test_approximate_recovery_redoes_the_mini_batch_on_the_survivors(model, dtype, B, p, lost):
+    """Section 4.2, approximate recovery.  Gradients at p workers; worker `lost` fails, so that attempt is never
+    applied; the same mini-batch is re-cut over the p-1 survivors (32 samples as 11 + 11 + 10; 8 as
+    2 + 1 + 1 + 1 + 1 + 1 + 1) and applied with every worker's share: gradients, parameters, momentum and
+    progress against the oracle's redo_with_survivors, and the progress advances once."""
+    torch = _torch()
+    import paper_1909_11985_amd as E
+    from paper_1909_11985_amd.binding import make_config
+    from parity_util import oracle_kwargs, per_tensor_elementwise, per_tensor_relerr
+    N, seed = 2 * B, 1
+    kw = TINY[model]
+    lr = 0.01 if model == "vgg16" else 0.05
+    x, y = synth_inputs.dataset(1, N, kw["H"], kw["W"], kw["C"], kw["classes"])
+    cfg = make_config(model, dtype=dtype, N=N, B=B, p_max=p, max_shard=B, lr=lr, H=kw["H"], W=kw["W"], C_=kw["C"],
+                      classes=kw["classes"], arch=kw["arch"])
+    job = E.Job(cfg, seed)
+    job.bind_dataset(torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda())
+    orc = O.Oracle(model, seed, N, B, lr=F32(lr), momentum=F32(0.9), wd=F32(5e-4), emulate_bf16=(dtype == "bf16"),
+                   dtype_code=E.DTYPES[dtype], graph_kwargs=oracle_kwargs(model, kw["H"], kw["W"], kw["C"], kw["classes"], kw["arch"]))
+    table = E.edl_tensor_table(cfg)
+    tol = TOL[dtype]
+    job.step(2)                                                  # somewhere inside the epoch, momentum non-zero
+    orc.step(2, x, y)
+    w0, v0 = job.params(), job.momentum()
+    orc.w, orc.v = w0.astype(np.float64), v0.astype(np.float64)                           # the same model from here
+    # the attempt at p workers
+    idx, off = job.shard(B, p, *job.progress()[1:])
+    job.gradients(p, idx, off)
+    attempt = [job.grad(k).astype(np.float64) for k in range(p) if k != lost]
+    assert np.array_equal(job.params(), w0) and job.progress() == (1, 0, 1)               # nothing applied
+    # worker `lost` is gone: the survivors redo the same mini-batch
+    cut = O.Oracle.survivor_cut(B, p - 1)
+    assert B % (p - 1) != 0 and len(set(np.diff(cut).tolist())) == 2
+    loss = job.gradients(p - 1, idx, cut)
+    G = [job.grad(k).astype(np.float64) for k in range(p - 1)]
+    job.apply(p - 1)
+    lo, discarded = orc.redo_with_survivors(p, lost, x, y)
+    assert job.progress() == (2, orc.epoch, orc.step_in_epoch) == (2, 1, 0)
+    assert abs(loss - lo) < tol * max(abs(lo), 1.0)
+    # the weighted aggregate + update by itself: the oracle's formula on the library's own gradient buffers
+    shares = (np.diff(cut) / float(B)).tolist()
+    w1, v1 = O.sgd_momentum_update(w0.astype(np.float64), v0.astype(np.float64), G, F32(lr), F32(0.9), F32(5e-4), weights=shares)
+    assert relerr(job.params(), w1) < 1e-6 and relerr(job.momentum(), v1) < 1e-6
+    if dtype == "f32":      # free-running bf16 gradients of a deep net are compared elsewhere, given their decisions
+        for got, want in list(zip(attempt, discarded)) + list(zip(G, orc.last_grads)):
+            e, name, whole = per_tensor_relerr(table, got, want)
+            assert whole < tol and e < 10 * tol, (name, e, whole)
+        assert relerr(job.params(), orc.w) < tol and relerr(job.momentum(), orc.v) < tol
+
+
+def test_a_joiner_adopts_the_jobs_coefficients_and_a_foreign_image_is_refused():
+    """Section 4.2: the job's meta-data travels with the model.  A joiner created with another learning rate,
+    momentum and weight decay continues bit for bit as the job whose image it received; an image of a job of
+    another dtype is refused (the worker's buffers were laid out for its own)."""
+    torch = _torch()
+    import paper_1909_11985_amd as E
+    from paper_1909_11985_amd.binding import make_config
+    geom = _cfg_geom(TINY["resnet20"])
+    N, B = 48, 24
+    x, y = synth_inputs.dataset(1, N, TINY["resnet20"]["H"], TINY["resnet20"]["W"], 3, TINY["resnet20"]["classes"])
+    dx, dy = torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda()
+    job = E.Job(make_config("resnet20", N=N, B=B, p_max=4, max_shard=B, lr=0.05, momentum=0.8, wd=1e-3, **geom), 3)
+    joiner = E.Job(make_config("resnet20", N=N, B=B, p_max=4, max_shard=B, lr=0.5, momentum=0.0, wd=0.0, **geom), 99)
+    job.bind_dataset(dx, dy)
+    joiner.bind_dataset(dx, dy)
+    for p in (2, 4):
+        job.step(p)
+    joiner.gradients(1)                                            # pending gradients of the joiner's old model ...
+    snap = job.snapshot()
+    joiner.restore(snap)
+    with pytest.raises(E.EdlError):
+        joiner.apply(1)                                            # ... are void after the restore
+    assert joiner.progress() == job.progress() == (2, 1, 0)
+    for p in (1, 3, 2):
+        assert job.step(p) == joiner.step(p)
+    assert np.array_equal(job.params(), joiner.params()) and np.array_equal(job.momentum(), joiner.momentum())
+    assert np.array_equal(job.running(), joiner.running())
+    # the joiner's own image now names the job's coefficients
+    hdr = joiner.snapshot()[:104].cpu().numpy().tobytes()
+    import struct
+    lr, mom, wd = struct.unpack_from("<fff", hdr, 64)
+    assert (lr, mom, wd) == (F32(0.05), F32(0.8), F32(1e-3))
+    other = E.Job(make_config("resnet20", dtype="bf16", N=N, B=B, p_max=4, max_shard=B, **geom), 0)
+    with pytest.raises(E.EdlError) as ei:
+        other.restore(snap)
+    assert ei.value.code == -1
 
 
 # ---------------------------------------------------------------- Adam jobs
@@ -618,62 +783,43 @@ def test_step_is_deterministic():
     assert np.array_equal(a["job"].params(), b["job"].params())
 
 
-_STREAM_SCRIPT = r"""
-import sys, hashlib
-sys.path.insert(0, sys.argv[1]); sys.path.insert(0, sys.argv[2])
-import numpy as np, torch, synth_inputs
-import paper_1909_11985_amd as E
-from paper_1909_11985_amd.binding import make_config
-N, B = 64, 32
-x, y = synth_inputs.dataset(1, N, 64, 64, 3, 1000)
-cfg = make_config("resnet50", dtype="bf16", N=N, B=B, p_max=4, max_shard=B, lr=0.002, H=64, W=64)
-job = E.Job(cfg, 0)
-job.bind_dataset(torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda())
-for p in (1, 2, 4, 1):
-    job.step(p)
-print(hashlib.sha256(job.params().tobytes() + job.momentum().tobytes() + job.running().tobytes()).hexdigest())
-"""
+def _digest_after_steps(options, side_streams="library", optimizers=("momentum",), unequal=False):
+    """sha256 of the model state after a few ResNet-50 steps (64x64 images, bf16) under the given options."""
+    import hashlib
+    torch = _torch()
+    import paper_1909_11985_amd as E
+    from paper_1909_11985_amd.binding import make_config
+    N, B = 96, 24
+    x, y = synth_inputs.dataset(1, N, 64, 64, 3, 1000)
+    dx, dy = torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda()
+    h = hashlib.sha256()
+    with E.options(**options):
+        for optimizer in optimizers:
+            cfg = make_config("resnet50", dtype="bf16", N=N, B=B, p_max=4, max_shard=B, lr=0.002, H=64, W=64, optimizer=optimizer)
+            job = E.Job(cfg, 0, side_streams=side_streams)
+            job.bind_dataset(dx, dy)
+            for p in (1, 2, 4, 1):
+                job.step(p)
+            if unequal:
+                idx, _ = job.shard(B, 1, 1, 0)
+                job.step(3, idx, np.array([0, 10, 10, 24], dtype=np.int64))      # unequal shards, an empty one in the middle
+                job.step(2, idx, np.array([0, 24, 24], dtype=np.int64))          # the last shard is empty
+            h.update(job.params().tobytes() + job.momentum().tobytes() + job.running().tobytes())
+            if optimizer == "adam":
+                h.update(job.second_moment().tobytes())
+            job.shutdown()
+    return h.hexdigest()
 
 
 def test_the_second_stream_does_not_change_the_result():
     """Weight gradients run on a second stream beside the input-gradient chain (the first layer's on the main
-    one): the model after four steps is bit for bit the one of a run that keeps everything on one stream."""
-    import os
-    import subprocess
-    import sys
-    here = os.path.dirname(os.path.abspath(__file__))
-    digests = []
-    for env_extra in ({}, {"EDL_TUNE_WGRAD_STREAM": "0"}, {"EDL_TUNE_WGRAD_TAIL_MAIN": "0"}):
-        out = subprocess.run([sys.executable, "-c", _STREAM_SCRIPT, os.path.dirname(here), here], env=dict(os.environ, **env_extra),
-                             capture_output=True, text=True, timeout=300)
-        assert out.returncode == 0, out.stdout[-2000:] + out.stderr[-2000:]
-        digests.append(out.stdout.strip().splitlines()[-1])
-    assert digests[0] == digests[1] == digests[2], digests
-
-
-_EARLY_SCRIPT = r"""
-import sys, hashlib
-sys.path.insert(0, sys.argv[1]); sys.path.insert(0, sys.argv[2])
-import numpy as np, torch, synth_inputs
-import paper_1909_11985_amd as E
-from paper_1909_11985_amd.binding import make_config
-N, B = 96, 24
-x, y = synth_inputs.dataset(1, N, 64, 64, 3, 1000)
-h = hashlib.sha256()
-for optimizer in ("momentum", "adam"):
-    cfg = make_config("resnet50", dtype="bf16", N=N, B=B, p_max=4, max_shard=B, lr=0.002, H=64, W=64, optimizer=optimizer)
-    job = E.Job(cfg, 0)
-    job.bind_dataset(torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda())
-    for p in (1, 2, 4):
-        job.step(p)
-    idx, _ = job.shard(B, 1, 0, 3)
-    job.step(3, idx, np.array([0, 10, 10, 24], dtype=np.int64))      # unequal shards, an empty one in the middle
-    job.step(2, idx, np.array([0, 24, 24], dtype=np.int64))          # the last shard is empty
-    h.update(job.params().tobytes() + job.momentum().tobytes() + job.running().tobytes())
-    if optimizer == "adam":
-        h.update(job.second_moment().tobytes())
-print(h.hexdigest())
-"""
+    one): the model after four steps is bit for bit the one of a run that keeps everything on one stream - whether
+    the library makes the side streams, the caller brings torch's, or there are none."""
+    base = _digest_after_steps({})
+    assert _digest_after_steps({"wgrad_stream": 0}) == base               # jobs created without side streams
+    assert _digest_after_steps({"wgrad_tail_main": 0}) == base
+    assert _digest_after_steps({}, side_streams="torch") == base          # the caller's streams
+    assert _digest_after_steps({}, side_streams=None) == base             # none: edl_set_side_streams(NULL, NULL)
 
 
 def test_the_update_started_during_the_backward_pass_does_not_change_the_result():
@@ -681,18 +827,25 @@ def test_the_update_started_during_the_backward_pass_does_not_change_the_result(
     a third stream (by default only from layers of 16 M weights on; here from every layer, and with the
     background launch held to 8 workgroups): momentum and Adam, equal and unequal shards, give bit for bit the
     model of a run that updates everything after the pass."""
-    import os
-    import subprocess
-    import sys
-    here = os.path.dirname(os.path.abspath(__file__))
-    digests = []
-    for env_extra in ({"EDL_TUNE_EARLY_UPDATE": "0"}, {"EDL_TUNE_EARLY_UPDATE": "1"},
-                      {"EDL_TUNE_EARLY_UPDATE": "100000", "EDL_TUNE_EARLY_BLOCKS": "8"}):
-        out = subprocess.run([sys.executable, "-c", _EARLY_SCRIPT, os.path.dirname(here), here], env=dict(os.environ, **env_extra),
-                             capture_output=True, text=True, timeout=300)
-        assert out.returncode == 0, out.stdout[-2000:] + out.stderr[-2000:]
-        digests.append(out.stdout.strip().splitlines()[-1])
-    assert digests[0] == digests[1] == digests[2], digests
+    kw = dict(optimizers=("momentum", "adam"), unequal=True)
+    base = _digest_after_steps({"early_update": 0}, **kw)
+    assert _digest_after_steps({"early_update": 1}, **kw) == base
+    assert _digest_after_steps({"early_update": 100000, "early_blocks": 8}, **kw) == base
+    assert _digest_after_steps({"early_update": 1}, side_streams="torch", **kw) == base
+
+
+def test_side_streams_are_checked():
+    torch = _torch()
+    import ctypes as C
+    import paper_1909_11985_amd as E
+    from paper_1909_11985_amd.binding import make_config
+    job = E.Job(make_config("mlp", N=64, B=16, p_max=4, max_shard=16, C_=8, arch=(8, 8), classes=3), 0)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    for a, b in ((s1.cuda_stream, None), (s1.cuda_stream, s1.cuda_stream)):
+        assert E.lib.edl_set_side_streams(job._h, a, b) == -1
+    assert E.lib.edl_set_side_streams(job._h, s1.cuda_stream, s2.cuda_stream) == 0
+    assert E.lib.edl_set_side_streams(job._h, None, None) == 0
+    job.shutdown()
 
 
 # ---------------------------------------------------------------- argument checking
@@ -719,6 +872,18 @@ def test_step_rejects_bad_requests():
     assert job.progress() == (0, 0, 0)                             # failed calls leave the cursor alone
     job.step(2, idx, off)
     assert job.progress() == (1, 0, 1)
+    # the gradient buffers are applied once, by the p they were computed for
+    with pytest.raises(E.EdlError) as ei:
+        job.apply(2)                                               # the step above has consumed its gradients
+    assert ei.value.code == -1
+    w_before = job.params()
+    job.gradients(2)
+    with pytest.raises(E.EdlError):
+        job.apply(4)
+    job.apply(2)
+    with pytest.raises(E.EdlError):
+        job.apply(2)
+    assert job.progress() == (2, 0, 2) and not np.array_equal(job.params(), w_before)
 
 
 # ---------------------------------------------------------------- edge cases
@@ -726,7 +891,7 @@ def test_update_of_nothing_is_a_no_op():
     torch = _torch()
     import paper_1909_11985_amd as E
     w = torch.ones(64, device="cuda")
-    E.edl_average_update([w[:0]] if False else [w], w[:0] if False else w, torch.zeros(64, device="cuda"), None, 0.0, 0.0, 0.0)
+    E.edl_average_update([w], w, torch.zeros(64, device="cuda"), None, 0.0, 0.0, 0.0)
     torch.cuda.synchronize()
     assert float(w.sum()) == 64.0                                   # lr = 0: weights unchanged
     import ctypes as C
