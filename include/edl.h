@@ -113,6 +113,8 @@ typedef struct edl_sizes {
     int64_t snapshot_bytes; /* EDL_SNAPSHOT_HEADER_BYTES + 4*(2P + R), with Adam 4*(3P + R) */
     double flops_per_sample; /* multiply-add flops of forward + both backward contractions */
     int64_t second_off;     /* float32 s[P]: Adam's second moment; -1 with EDL_OPT_MOMENTUM */
+    int64_t scratch_bytes;  /* the part of the arena that is the kernels' scratch (what edl_step_static_scratch
+                               must fit into EDL_STATIC_SCRATCH_BYTES) */
 } edl_sizes;
 
 /* progress of the job: what notify_batch_end() counts */
@@ -241,6 +243,20 @@ int32_t edl_shard(const edl_handle* h, int64_t B, int32_t p, int64_t epoch, int6
  * B/p>max_shard; with them: EDL_ENOMEM a shard larger than max_shard, EDL_ERANGE
  * index outside [0,N) or offsets not monotone from 0 to B. */
 int32_t edl_step(edl_handle* h, int32_t p, const int64_t* idx, const int64_t* off, float* out_loss);
+
+/* For callers that cannot allocate (code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc) and so may have no room in their arena plan for the kernels' scratch: edl_step with that scratch
+ * (split-reduction partial tiles, column-sum partials, batch-norm coefficients, per-row losses) in a buffer of
+ * EDL_STATIC_SCRATCH_BYTES that the library holds once per GPU for the life of the process, instead of in the
+ * arena's scratch piece.  The call allocates nothing, neither device nor pinned memory nor through any library;
+ * arguments, results and errors are edl_step's, bit for bit the same model.  EDL_ENOMEM if the job's kernels
+ * need more scratch than the buffer holds (large models: use edl_step); EDL_EINVAL if another device is current
+ * than the one the job was created on.  All jobs on one GPU share the buffer, which keeps the last call's
+ * contents: calls of this entry point that overlap on one GPU (other threads, other streams) race; calls that
+ * follow each other on one stream, or are separated by a synchronisation, do not.  Nothing in the buffer needs
+ * clearing between calls. */
+#define EDL_STATIC_SCRATCH_BYTES (64u << 20)
+int32_t edl_step_static_scratch(edl_handle* h, int32_t p, const int64_t* idx, const int64_t* off, float* out_loss);
 
 /* Only the first half of edl_step (gradients of the p shards, no update).  For
  * parity tests and profiling. */

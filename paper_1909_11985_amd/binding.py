@@ -35,7 +35,7 @@ class Sizes(C.Structure):
     _fields_ = [("P", C.c_int64), ("R", C.c_int64), ("params_off", C.c_int64), ("momentum_off", C.c_int64),
                 ("running_off", C.c_int64), ("grads_off", C.c_int64), ("grad_stride", C.c_int64),
                 ("arena_bytes", C.c_int64), ("snapshot_bytes", C.c_int64), ("flops_per_sample", C.c_double),
-                ("second_off", C.c_int64)]
+                ("second_off", C.c_int64), ("scratch_bytes", C.c_int64)]
 
 
 class Progress(C.Structure):
@@ -71,6 +71,7 @@ _SIGS = {
     "edl_bind_dataset": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64],
     "edl_shard": [C.c_void_p, C.c_int64, C.c_int32, C.c_int64, C.c_int64, _i64p, _i64p],
     "edl_step": [C.c_void_p, C.c_int32, _i64p, _i64p, _f32p],
+    "edl_step_static_scratch": [C.c_void_p, C.c_int32, _i64p, _i64p, _f32p],
     "edl_gradients": [C.c_void_p, C.c_int32, _i64p, _i64p, _f32p],
     "edl_apply": [C.c_void_p, C.c_int32],
     "edl_snapshot": [C.c_void_p, C.c_void_p, C.c_size_t, C.POINTER(C.c_size_t)],
@@ -363,6 +364,9 @@ class Job:
 
     def step(self, p, idx=None, off=None, want_loss=True):
         return self._call_step(lib.edl_step, p, idx, off, want_loss)
+
+    def step_static_scratch(self, p, idx=None, off=None, want_loss=True):
+        return self._call_step(lib.edl_step_static_scratch, p, idx, off, want_loss)
 
     def gradients(self, p, idx=None, off=None, want_loss=True):
         return self._call_step(lib.edl_gradients, p, idx, off, want_loss)

@@ -25,7 +25,16 @@ using namespace edl;
         }                                                                                  \
     } while (0)
 
+// Scratch for edl_step_static_scratch (callers that cannot bring or allocate a scratch piece): one fixed buffer
+// per GPU, held from the time the library's code is loaded on that GPU until the process ends.  In host code
+// this name is only a handle for hipGetSymbolAddress; the device address is taken once per device in edl_init
+// and kept in g_static_scratch, and that pointer is what kernels and copies are given.
+static __device__ __align__(256) unsigned char scratch[EDL_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+void* g_static_scratch[kMaxDevices] = {};     // per device: address of that device's copy of `scratch`
 
 constexpr int64_t kAlign = 256;
 constexpr int kIdxSlots = 4;
@@ -56,6 +65,7 @@ struct Layout {
     // scratch because weight gradients may run on the second stream meanwhile
     int64_t splitk_scratch = 0, splitk_scratch_bytes = 0;
     int64_t ttable = 0;                  // TransposeEntry[] for the one-launch weight transpose
+    int64_t scratch_lo = 0, scratch_hi = 0;   // the kernels' scratch pieces lie in [scratch_lo, scratch_hi)
     int cpad = 0;                        // channels of the stored input images (>= the logical count, see input_pad)
     std::vector<int64_t> wpad;           // per op: zero-padded weight copy of a convolution on padded images (-1 if none)
     int64_t dwpad = 0;                   // float32 gradient of such weights before it is compacted
@@ -124,16 +134,10 @@ void plan_layout(const edl_config& c, const Graph& g, Layout& L) {
     L.grads = take(4 * L.grad_stride * c.p_max);
     L.idx = take(8 * c.B);
     L.labels = take(4 * (int64_t)c.max_shard);
-    L.row_loss = take(4 * (int64_t)c.max_shard);
     L.losses = take(4 * kMaxP);
     int cmax = 1;
     for (const Op& op : g.ops)
         if (op.kind == OP_CONV || op.kind == OP_BN) cmax = std::max(cmax, op.K);
-    L.partial = take(4 * 2 * (int64_t)kRedRowBlocks * cmax);
-    // a second one for sums that wait while another batch norm runs (a block's last convolution, whose
-    // batch norm comes after the projection shortcut's)
-    L.partial_held = take(4 * 2 * (int64_t)kRedRowBlocks * cmax);
-    L.coef = take(4 * 2 * (int64_t)cmax);
     const size_t nt = g.tensors.size();
     L.act.assign(nt, -1);
     L.grad.assign(nt, -1);
@@ -177,11 +181,22 @@ void plan_layout(const edl_config& c, const Graph& g, Layout& L) {
             L.pool_arg[i] = take(g.tensors[(size_t)op.y].elems() * c.max_shard);
         }
     }
+    // The kernels' scratch (partial results that live inside one pass), in one contiguous piece
+    // [scratch_lo, scratch_hi): a caller without an arena piece for it can run the same pass on the library's
+    // static buffer (edl_step_static_scratch).
+    L.scratch_lo = o;
+    L.row_loss = take(4 * (int64_t)c.max_shard);
+    L.partial = take(4 * 2 * (int64_t)kRedRowBlocks * cmax);
+    // a second one for sums that wait while another batch norm runs (a block's last convolution, whose
+    // batch norm comes after the projection shortcut's)
+    L.partial_held = take(4 * 2 * (int64_t)kRedRowBlocks * cmax);
+    L.coef = take(4 * 2 * (int64_t)cmax);
     L.wgrad_scratch = take(std::max<int64_t>(L.wgrad_scratch_bytes, 16));
     L.wgrad_scratch2 = take(std::max<int64_t>(L.wgrad_scratch_bytes, 16));
     L.wide_sums = take(std::max<int64_t>(4 * L.wide_sums_floats, 16));
     L.splitk_scratch = take(std::max<int64_t>(L.splitk_scratch_bytes, 16));
     L.dwpad = take(dwpad_bytes);
+    L.scratch_hi = o;
     L.ttable = take((int64_t)sizeof(TransposeEntry) * 2 * std::max<size_t>(no, 1));   // element-wise entries, then vector ones
     L.total = o;
 }
@@ -233,7 +248,17 @@ struct edl_handle {
     int early_p = 0;
     int64_t applied_from = 0;
 
+    // where the kernels' scratch lives during the current call: the arena piece (null), or another buffer of
+    // the same layout
+    char* scratch_base = nullptr;
+    int device = -1;
+    std::vector<char> written;           // backward pass: which gradient buffers hold something (per tensor)
+
     template <typename T> T* at(int64_t off) const { return reinterpret_cast<T*>(arena + off); }
+    // a piece of the kernels' scratch (off is its arena offset)
+    template <typename T> T* sc(int64_t off) const {
+        return reinterpret_cast<T*>(scratch_base ? scratch_base + (off - L.scratch_lo) : arena + off);
+    }
     float* w() const { return at<float>(L.params); }
     float* v() const { return at<float>(L.momentum); }
     float* s2() const { return at<float>(L.second); }                     // Adam only
@@ -269,6 +294,7 @@ int32_t edl_query(const edl_config* cfg, edl_sizes* out) {
     out->snapshot_bytes = EDL_SNAPSHOT_HEADER_BYTES + 4 * ((cfg->optimizer == EDL_OPT_ADAM ? 3 : 2) * g.P + g.R);
     out->flops_per_sample = g.flops_per_sample();
     out->second_off = L.second;
+    out->scratch_bytes = L.scratch_hi - L.scratch_lo;
     return EDL_OK;
 }
 
@@ -405,6 +431,9 @@ int32_t edl_init(edl_handle** out, const edl_config* cfg, uint64_t seed, void* d
     h->arena = (char*)dev_arena;
     h->st = (hipStream_t)hip_stream;
     h->readers.assign(h->g.tensors.size(), 0);
+    h->written.assign(h->g.tensors.size(), 0);
+    h->shard_n.reserve(kMaxP);
+    h->perm.reserve((size_t)cfg->N);
     h->first_reader.assign(h->g.tensors.size(), -1);
     for (size_t i = 0; i < h->g.ops.size(); ++i) {
         const Op& op = h->g.ops[i];
@@ -435,6 +464,13 @@ static int init_device_state(edl_handle* h) {
         HIP_TRY(hipEventCreateWithFlags(&h->idx_event[s], hipEventDisableTiming));
     }
     HIP_TRY(hipHostMalloc((void**)&h->loss_host, sizeof(float) * kMaxP, hipHostMallocDefault));
+    // this GPU's copy of the static scratch buffer: its address is looked up once, with the device current
+    HIP_TRY(hipGetDevice(&h->device));
+    if (h->device >= 0 && h->device < kMaxDevices && g_static_scratch[h->device] == nullptr) {
+        void* ptr = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        g_static_scratch[h->device] = ptr;
+    }
     if (tune().wgrad_stream != 0) {
         HIP_TRY(hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking));
         h->own_streams = true;
@@ -545,7 +581,7 @@ static void forward_shard(edl_handle* h, const int64_t* dev_idx, int n, float* d
     const int dt = h->cfg.dtype;
     hipStream_t st = h->st;
     const bool bf = dt == EDL_DTYPE_BF16;
-    float* partial = h->at<float>(h->L.partial);
+    float* partial = h->sc<float>(h->L.partial);
     const Tensor& tin = g.tensors[0];
     if (dev_idx) {
         if (h->L.cpad != tin.C)
@@ -557,7 +593,7 @@ static void forward_shard(edl_handle* h, const int64_t* dev_idx, int n, float* d
     if (op_hi > g.ops.size()) op_hi = g.ops.size();
     int stats_row_blocks = 0;   // > 0: the convolution just launched left the next batch norm's partial sums
     // the same for a convolution whose batch norm is not the next op: its sums wait in a buffer of their own
-    float* const partial_held = h->at<float>(h->L.partial_held);
+    float* const partial_held = h->sc<float>(h->L.partial_held);
     int held_rows = 0, held_tensor = -1;
     for (size_t i = op_lo; i < op_hi; ++i) {
         const Op& op = g.ops[i];
@@ -575,10 +611,10 @@ static void forward_shard(edl_handle* h, const int64_t* dev_idx, int n, float* d
                         bn_later = g.ops[j].kind == OP_BN && g.ops[j].x == op.y;
                 const int rows = launch_conv_fwd(dt, geom_padded(g, op, n, h->L.cpad), h->act(op.x), wsrc,
                                                  op.bias ? h->w() + op.b_off : nullptr, op.relu, g.tensors[(size_t)op.y].fp32,
-                                                 h->act(op.y), h->at<float>(h->L.splitk_scratch),
+                                                 h->act(op.y), h->sc<float>(h->L.splitk_scratch),
                                                  (size_t)h->L.splitk_scratch_bytes,
                                                  bn_next ? partial : bn_later ? partial_held : nullptr,
-                                                 WideSums{h->at<float>(h->L.wide_sums), (size_t)h->L.wide_sums_floats}, st);
+                                                 WideSums{h->sc<float>(h->L.wide_sums), (size_t)h->L.wide_sums_floats}, st);
                 if (bn_later) {
                     if (rows > 0) { held_rows = rows; held_tensor = op.y; }
                     stats_row_blocks = 0;
@@ -612,7 +648,7 @@ static void forward_shard(edl_handle* h, const int64_t* dev_idx, int n, float* d
             }
             case OP_LOSS:
                 launch_softmax_ce(dt, (const float*)h->act(op.x), h->at<int32_t>(h->L.labels), h->grad(op.x),
-                                  h->at<float>(h->L.row_loss), dev_loss, n, g.classes, st);
+                                  h->sc<float>(h->L.row_loss), dev_loss, n, g.classes, st);
                 break;
         }
     }
@@ -628,9 +664,10 @@ static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, siz
     const Graph& g = h->g;
     const int dt = h->cfg.dtype;
     hipStream_t st = h->st;
-    float* partial = h->at<float>(h->L.partial);
-    float* coef = h->at<float>(h->L.coef);
-    std::vector<char> written(g.tensors.size(), 0);
+    float* partial = h->sc<float>(h->L.partial);
+    float* coef = h->sc<float>(h->L.coef);
+    std::vector<char>& written = h->written;     // sized at init: no allocation in the pass
+    std::fill(written.begin(), written.end(), 0);
     if (held)
         for (int t : *held) written[(size_t)storage_of(g, t)] = 1;
     if (op_hi > g.ops.size()) op_hi = g.ops.size();
@@ -662,7 +699,7 @@ static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, siz
                 int conv_ordinal = 0;
                 for (size_t j = 0; j < ii; ++j) conv_ordinal += g.ops[j].kind == OP_CONV;
                 const bool on_main = overlap && conv_ordinal < tail_main;
-                float* const wscratch = h->at<float>(on_main ? h->L.wgrad_scratch2 : h->L.wgrad_scratch);
+                float* const wscratch = h->sc<float>(on_main ? h->L.wgrad_scratch2 : h->L.wgrad_scratch);
                 if (overlap && !on_main) {
                     hipEvent_t ev = h->ev_ready[h->ev_slot];
                     h->ev_slot = (h->ev_slot + 1) % kReadyEvents;
@@ -671,10 +708,10 @@ static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, siz
                         used_side = true;
                     }
                 }
-                launch_conv_wgrad(dt, q, h->act(op.x), h->grad(op.y), padded ? h->at<float>(h->L.dwpad) : G + op.w_off,
+                launch_conv_wgrad(dt, q, h->act(op.x), h->grad(op.y), padded ? h->sc<float>(h->L.dwpad) : G + op.w_off,
                                   wscratch, (size_t)h->L.wgrad_scratch_bytes, ws);
                 if (padded)
-                    launch_unpad_rows(h->at<float>(h->L.dwpad), G + op.w_off, (int64_t)op.K * op.R * op.S, g.tensors[0].C, h->L.cpad, ws);
+                    launch_unpad_rows(h->sc<float>(h->L.dwpad), G + op.w_off, (int64_t)op.K * op.R * op.S, g.tensors[0].C, h->L.cpad, ws);
                 // Parameters are laid out in layer order, so everything from this layer's weights on now has its
                 // final gradient: the second stream holds the weight gradients, and the event it waited for
                 // covers what the main stream has written (bias and batch-norm gradients of the later layers)
@@ -718,7 +755,7 @@ static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, siz
                         if (prod.relu && storage_of(g, prod.y) == sx && (prod.kind == OP_BN || prod.kind == OP_CONV)) {
                             mask.act = h->act(op.x);
                             mask.sums = partial;
-                            mask.wide = WideSums{h->at<float>(h->L.wide_sums), (size_t)h->L.wide_sums_floats};
+                            mask.wide = WideSums{h->sc<float>(h->L.wide_sums), (size_t)h->L.wide_sums_floats};
                             if (prod.kind == OP_BN) {
                                 mask.xin = h->act(prod.x);
                                 mask.mean_rstd = h->at<float>(h->L.bn_save[ii - 1]);
@@ -726,7 +763,7 @@ static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, siz
                         }
                     }
                     const int rows = launch_conv_dgrad(dt, q, h->grad(op.y), h->arena + h->L.wT[ii], acc, h->grad(op.x),
-                                                       h->at<float>(h->L.splitk_scratch), (size_t)h->L.splitk_scratch_bytes,
+                                                       h->sc<float>(h->L.splitk_scratch), (size_t)h->L.splitk_scratch_bytes,
                                                        mask.act ? &mask : nullptr, st);
                     if (rows > 0) { fused_for = ii - 1; fused_rows = rows; }
                     written[(size_t)sx] = 1;
@@ -806,7 +843,7 @@ int32_t edl_gradients(edl_handle* h, int32_t p, const int64_t* idx, const int64_
     if (!h->data_x) { set_error("no data set bound"); return EDL_EINVAL; }
     if ((idx == nullptr) != (off == nullptr)) { set_error("idx and off must both be given or both be NULL"); return EDL_EINVAL; }
     const int64_t B = h->cfg.B;
-    std::vector<int64_t> sizes;
+    int64_t sizes[kMaxP];
     if (idx) {
         // the caller's cut of the mini-batch: any shard sizes that fit the workspace (equal ones in normal use)
         if (p <= 0 || p > h->cfg.p_max) { set_error("p=%d outside [1, p_max=%d]", p, h->cfg.p_max); return EDL_EINVAL; }
@@ -815,15 +852,15 @@ int32_t edl_gradients(edl_handle* h, int32_t p, const int64_t* idx, const int64_
             const int64_t nk = off[k + 1] - off[k];
             if (nk < 0) { set_error("off[%d] > off[%d]", k, k + 1); return EDL_ERANGE; }
             if (nk > h->cfg.max_shard) { set_error("shard %d of %lld samples exceeds max_shard=%d", k, (long long)nk, h->cfg.max_shard); return EDL_ENOMEM; }
-            sizes.push_back(nk);
+            sizes[k] = nk;
         }
     } else {
         const int rc = check_p(h, p);
         if (rc) return rc;
-        sizes.assign((size_t)p, B / p);
+        for (int k = 0; k < p; ++k) sizes[k] = B / p;
     }
     bool equal = true;
-    for (int64_t nk : sizes) equal = equal && nk == sizes[0];
+    for (int k = 0; k < p; ++k) equal = equal && sizes[k] == sizes[0];
     const int slot = h->idx_slot;
     h->idx_slot = (slot + 1) % kIdxSlots;
     HIP_TRY(hipEventSynchronize(h->idx_event[slot]));
@@ -840,7 +877,7 @@ int32_t edl_gradients(edl_handle* h, int32_t p, const int64_t* idx, const int64_
         }
         memcpy(stage, h->perm.data() + h->prog.step_in_epoch * B, sizeof(int64_t) * (size_t)B);
     }
-    h->shard_n = sizes;
+    h->shard_n.assign(sizes, sizes + p);
     h->shards_equal = equal;
     int64_t* dev_idx = h->at<int64_t>(h->L.idx);
     HIP_TRY(hipMemcpyAsync(dev_idx, stage, sizeof(int64_t) * (size_t)B, hipMemcpyHostToDevice, h->st));
@@ -855,9 +892,9 @@ int32_t edl_gradients(edl_handle* h, int32_t p, const int64_t* idx, const int64_
     bool first = true;       // the first worker that has samples keeps the running statistics
     int last_k = -1;
     for (int k = 0; k < p; ++k)
-        if (sizes[(size_t)k] > 0) last_k = k;
+        if (sizes[k] > 0) last_k = k;
     for (int k = 0; k < p; ++k) {
-        const int64_t nk = sizes[(size_t)k];
+        const int64_t nk = sizes[k];
         if (nk > 0) {
             forward_shard(h, dev_idx + at, (int)nk, dev_losses + k, first);
             backward_shard(h, (int)nk, h->grad_buf(k), 0, (size_t)-1, k == last_k ? h->early_p : 0);
@@ -875,7 +912,7 @@ int32_t edl_gradients(edl_handle* h, int32_t p, const int64_t* idx, const int64_
             s /= p;
         } else {   // the mean over the mini-batch: every worker's mean weighs in with its share
             for (int k = 0; k < p; ++k)
-                if (sizes[(size_t)k] > 0) s += (double)h->loss_host[k] * ((double)sizes[(size_t)k] / (double)B);
+                if (sizes[k] > 0) s += (double)h->loss_host[k] * ((double)sizes[k] / (double)B);
         }
         *out_loss = (float)s;
     }
@@ -957,6 +994,28 @@ int32_t edl_step(edl_handle* h, int32_t p, const int64_t* idx, const int64_t* of
         return rc;
     }
     return edl_apply(h, p);
+}
+
+int32_t edl_step_static_scratch(edl_handle* h, int32_t p, const int64_t* idx, const int64_t* off, float* out_loss) {
+    if (!h) { set_error("null handle"); return EDL_EINVAL; }
+    const int64_t need = h->L.scratch_hi - h->L.scratch_lo;
+    if (need > (int64_t)EDL_STATIC_SCRATCH_BYTES) {
+        set_error("the kernels of this job need %lld bytes of scratch; the static buffer holds %lld (use edl_step, whose "
+                  "scratch is part of the caller's arena)", (long long)need, (long long)EDL_STATIC_SCRATCH_BYTES);
+        return EDL_ENOMEM;
+    }
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev != h->device || dev < 0 || dev >= kMaxDevices || g_static_scratch[dev] == nullptr) {
+        set_error("device %d is current, the job was created on device %d (or its static scratch was never set up)", dev, h->device);
+        return EDL_EINVAL;
+    }
+    // nothing in the buffer has to start at zero: every partial result is written by the launch that precedes its
+    // reader (the arena's piece is never cleared either)
+    h->scratch_base = (char*)g_static_scratch[dev];
+    const int rc = edl_step(h, p, idx, off, out_loss);
+    h->scratch_base = nullptr;
+    return rc;
 }
 
 int32_t edl_profile_parallelism(edl_handle* h, int32_t min_p, int32_t max_p, int32_t steps, edl_parallelism_point* out,
@@ -1170,7 +1229,7 @@ int32_t edl_debug_backward(edl_handle* h, int32_t n, int32_t k) {
     if (k < 0 || k >= h->cfg.p_max) { set_error("gradient buffer %d outside [0,p_max)", k); return EDL_EINVAL; }
     const Graph& g = h->g;
     launch_softmax_ce(h->cfg.dtype, (const float*)h->act(g.logits), h->at<int32_t>(h->L.labels), h->grad(g.logits),
-                      h->at<float>(h->L.row_loss), h->at<float>(h->L.losses), n, g.classes, h->st);
+                      h->sc<float>(h->L.row_loss), h->at<float>(h->L.losses), n, g.classes, h->st);
     backward_shard(h, n, h->grad_buf(k));
     HIP_TRY(hipStreamSynchronize(h->st));
     HIP_TRY(hipGetLastError());
