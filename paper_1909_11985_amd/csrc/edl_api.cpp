@@ -40,6 +40,7 @@ constexpr int64_t kAlign = 256;
 constexpr int kIdxSlots = 4;
 constexpr int kReadyEvents = 64;   // ring of "dy is final" events for the second stream
 constexpr int kChunkEvents = 64;   // ring of "these weight gradients are final" events for the update stream
+constexpr int kBranchEvents = 16;  // ring of event pairs around a shortcut branch on the second side stream
 
 int64_t align_up(int64_t v, int64_t a = kAlign) { return (v + a - 1) / a * a; }
 
@@ -58,6 +59,7 @@ static_assert(sizeof(SnapshotHeader) == 104, "snapshot header layout");
 struct Layout {
     int64_t params = 0, momentum = 0, second = -1, running = 0, shadow = 0, grads = 0, grad_stride = 0;
     int64_t idx = 0, labels = 0, row_loss = 0, losses = 0, partial = 0, partial_held = 0, coef = 0, wgrad_scratch = 0;
+    int64_t partial_side = 0, coef_side = 0, wide_sums_side = 0, splitk_side = 0;   // the branch stream's own scratch
     int64_t wide_sums = 0, wide_sums_floats = 0;   // partial column sums of launches with more row tiles than `partial` holds
     int64_t wgrad_scratch_bytes = 0;
     int64_t wgrad_scratch2 = 0;          // for the few weight gradients that run on the main stream beside the second one
@@ -191,10 +193,17 @@ void plan_layout(const edl_config& c, const Graph& g, Layout& L) {
     // batch norm comes after the projection shortcut's)
     L.partial_held = take(4 * 2 * (int64_t)kRedRowBlocks * cmax);
     L.coef = take(4 * 2 * (int64_t)cmax);
+    // the same pair for the projection shortcut's batch norm while it runs on the branch stream beside the main one
+    L.partial_side = take(4 * 2 * (int64_t)kRedRowBlocks * cmax);
+    L.coef_side = take(4 * 2 * (int64_t)cmax);
     L.wgrad_scratch = take(std::max<int64_t>(L.wgrad_scratch_bytes, 16));
     L.wgrad_scratch2 = take(std::max<int64_t>(L.wgrad_scratch_bytes, 16));
     L.wide_sums = take(std::max<int64_t>(4 * L.wide_sums_floats, 16));
     L.splitk_scratch = take(std::max<int64_t>(L.splitk_scratch_bytes, 16));
+    // the branch stream cuts reductions and keeps wide sums exactly as the main stream would (same results, bit
+    // for bit, whichever stream a layer runs on), in buffers of its own
+    L.wide_sums_side = take(std::max<int64_t>(4 * L.wide_sums_floats, 16));
+    L.splitk_side = take(std::max<int64_t>(L.splitk_scratch_bytes, 16));
     L.dwpad = take(dwpad_bytes);
     L.scratch_hi = o;
     L.ttable = take((int64_t)sizeof(TransposeEntry) * 2 * std::max<size_t>(no, 1));   // element-wise entries, then vector ones
@@ -253,6 +262,12 @@ struct edl_handle {
     char* scratch_base = nullptr;
     int device = -1;
     std::vector<char> written;           // backward pass: which gradient buffers hold something (per tensor)
+    std::vector<char> op_done;           // a pass: layers already launched out of list order (on the branch stream)
+    // The projection shortcut of a residual block (a convolution and its batch norm) depends only on the block's
+    // input (forward) / on the gradient the block's last batch norm leaves for it (backward), so it runs on the
+    // second side stream beside the main branch: ev_branch_go releases it, ev_branch_done joins it.
+    hipEvent_t ev_branch_go[kBranchEvents] = {}, ev_branch_done[kBranchEvents] = {};
+    int branch_slot = 0;
 
     template <typename T> T* at(int64_t off) const { return reinterpret_cast<T*>(arena + off); }
     // a piece of the kernels' scratch (off is its arena offset)
@@ -376,6 +391,10 @@ static int create_side_events(edl_handle* h) {
     for (int e = 0; e < kChunkEvents; ++e)
         if (!h->ev_chunk[e]) HIP_TRY(hipEventCreateWithFlags(&h->ev_chunk[e], hipEventDisableTiming));
     if (!h->ev_upd_done) HIP_TRY(hipEventCreateWithFlags(&h->ev_upd_done, hipEventDisableTiming));
+    for (int e = 0; e < kBranchEvents; ++e) {
+        if (!h->ev_branch_go[e]) HIP_TRY(hipEventCreateWithFlags(&h->ev_branch_go[e], hipEventDisableTiming));
+        if (!h->ev_branch_done[e]) HIP_TRY(hipEventCreateWithFlags(&h->ev_branch_done[e], hipEventDisableTiming));
+    }
     return EDL_OK;
 }
 
@@ -407,6 +426,10 @@ static void destroy_handle(edl_handle* h) {
         if (h->ev_chunk[e]) (void)hipEventDestroy(h->ev_chunk[e]);
     if (h->ev_side_done) (void)hipEventDestroy(h->ev_side_done);
     if (h->ev_upd_done) (void)hipEventDestroy(h->ev_upd_done);
+    for (int e = 0; e < kBranchEvents; ++e) {
+        if (h->ev_branch_go[e]) (void)hipEventDestroy(h->ev_branch_go[e]);
+        if (h->ev_branch_done[e]) (void)hipEventDestroy(h->ev_branch_done[e]);
+    }
     delete h;
 }
 
@@ -432,6 +455,7 @@ int32_t edl_init(edl_handle** out, const edl_config* cfg, uint64_t seed, void* d
     h->st = (hipStream_t)hip_stream;
     h->readers.assign(h->g.tensors.size(), 0);
     h->written.assign(h->g.tensors.size(), 0);
+    h->op_done.assign(h->g.ops.size(), 0);
     h->shard_n.reserve(kMaxP);
     h->perm.reserve((size_t)cfg->N);
     h->first_reader.assign(h->g.tensors.size(), -1);
@@ -595,12 +619,54 @@ static void forward_shard(edl_handle* h, const int64_t* dev_idx, int n, float* d
     // the same for a convolution whose batch norm is not the next op: its sums wait in a buffer of their own
     float* const partial_held = h->sc<float>(h->L.partial_held);
     int held_rows = 0, held_tensor = -1;
+    auto weights_of = [&](size_t i) {
+        const Op& o = g.ops[i];
+        const void* wsrc = bf ? (const void*)(h->at<uint16_t>(h->L.shadow) + o.w_off) : (const void*)(h->w() + o.w_off);
+        if (h->L.wpad[i] >= 0) wsrc = h->arena + h->L.wpad[i];
+        return wsrc;
+    };
+    // A residual block's projection shortcut (convolution + batch norm on the block's input) runs on the second
+    // side stream while the main branch runs here; the block's last batch norm, which adds the two, waits for it.
+    // Only when the whole list runs and nothing is being timed kernel by kernel.
+    const bool branch = op_lo == 0 && op_hi == g.ops.size() && h->upd != nullptr && !prof_enabled() && tune().branch_stream != 0;
+    std::vector<char>& done = h->op_done;
+    std::fill(done.begin(), done.end(), 0);
+    int join_tensor = -1;
+    hipEvent_t join_event = nullptr;
     for (size_t i = op_lo; i < op_hi; ++i) {
         const Op& op = g.ops[i];
+        if (done[i]) continue;
+        if (branch && op.kind == OP_CONV && join_tensor < 0) {
+            for (size_t j = i + 1; j + 2 < op_hi && j <= i + 8; ++j) {
+                const Op& pj = g.ops[j];
+                const Op& pb = g.ops[j + 1];
+                if (!(pj.kind == OP_CONV && pj.x == op.x && pb.kind == OP_BN && pb.x == pj.y && pb.res < 0)) continue;
+                bool joins = false;
+                for (size_t k = j + 2; k < op_hi && k <= j + 3; ++k) joins = joins || (g.ops[k].kind == OP_BN && g.ops[k].res == pb.y);
+                if (!joins) break;
+                hipEvent_t go = h->ev_branch_go[h->branch_slot], dn = h->ev_branch_done[h->branch_slot];
+                if (hipEventRecord(go, st) != hipSuccess || hipStreamWaitEvent(h->upd, go, 0) != hipSuccess) break;
+                h->branch_slot = (h->branch_slot + 1) % kBranchEvents;
+                float* const ps = h->sc<float>(h->L.partial_side);
+                // this stream's own split-reduction scratch and wide-sums buffer (the main stream's are in use)
+                const int rows = launch_conv_fwd(dt, geom_padded(g, pj, n, h->L.cpad), h->act(pj.x), weights_of(j),
+                                                 pj.bias ? h->w() + pj.b_off : nullptr, pj.relu, g.tensors[(size_t)pj.y].fp32,
+                                                 h->act(pj.y), h->sc<float>(h->L.splitk_side), (size_t)h->L.splitk_scratch_bytes, ps,
+                                                 WideSums{h->sc<float>(h->L.wide_sums_side), (size_t)h->L.wide_sums_floats}, h->upd);
+                const Tensor& t = g.tensors[(size_t)pb.x];
+                launch_bn_forward(dt, h->act(pb.x), nullptr, h->act(pb.y), h->w() + pb.w_off, h->w() + pb.b_off,
+                                  h->at<float>(h->L.bn_save[j + 1]), update_running ? h->running() + pb.run_off : nullptr,
+                                  (int64_t)n * t.H * t.W, t.C, pb.relu, ps, rows, h->upd);
+                (void)hipEventRecord(dn, h->upd);
+                done[j] = done[j + 1] = 1;
+                join_tensor = pb.y;
+                join_event = dn;
+                break;
+            }
+        }
         switch (op.kind) {
             case OP_CONV: {
-                const void* wsrc = bf ? (const void*)(h->at<uint16_t>(h->L.shadow) + op.w_off) : (const void*)(h->w() + op.w_off);
-                if (h->L.wpad[i] >= 0) wsrc = h->arena + h->L.wpad[i];
+                const void* wsrc = weights_of(i);
                 // the batch norm that follows (in this call) can take its sums from the convolution's epilogue
                 const bool bn_next = i + 1 < op_hi && g.ops[i + 1].kind == OP_BN && g.ops[i + 1].x == op.y;
                 // ... or a later one of this call, if the held buffer is free
@@ -626,6 +692,10 @@ static void forward_shard(edl_handle* h, const int64_t* dev_idx, int n, float* d
             case OP_BN: {
                 const Tensor& t = g.tensors[(size_t)op.x];
                 const bool held = held_tensor == op.x && held_rows > 0;
+                if (op.res >= 0 && op.res == join_tensor) {      // the shortcut's part comes from the other stream
+                    (void)hipStreamWaitEvent(st, join_event, 0);
+                    join_tensor = -1;
+                }
                 launch_bn_forward(dt, h->act(op.x), op.res >= 0 ? h->act(op.res) : nullptr, h->act(op.y), h->w() + op.w_off,
                                   h->w() + op.b_off, h->at<float>(h->L.bn_save[i]),
                                   update_running ? h->running() + op.run_off : nullptr, (int64_t)n * t.H * t.W, t.C, op.relu,
@@ -652,6 +722,7 @@ static void forward_shard(edl_handle* h, const int64_t* dev_idx, int n, float* d
                 break;
         }
     }
+    if (join_tensor >= 0) (void)hipStreamWaitEvent(st, join_event, 0);   // a branch nobody joined (cannot happen)
 }
 
 static int apply_range(edl_handle* h, int32_t p, int64_t lo, int64_t hi, hipStream_t st, int max_blocks = 0);
@@ -674,11 +745,23 @@ static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, siz
     // per-kernel timing wants one kernel at a time
     const bool overlap = h->side != nullptr && !prof_enabled();
     bool used_side = false, used_upd = false;
+    // the projection shortcut's backward on the second side stream (see forward_shard)
+    const bool branch = overlap && op_lo == 0 && op_hi == g.ops.size() && h->upd != nullptr && tune().branch_stream != 0;
+    std::vector<char>& done = h->op_done;
+    std::fill(done.begin(), done.end(), 0);
+    int join_storage = -1;               // gradient buffer the branch stream is still writing
+    hipEvent_t join_event = nullptr;
     size_t fused_for = (size_t)-1;   // the layer whose masked gradient and column sums the dgrad after it left
     int fused_rows = 0;
     size_t premasked_for = (size_t)-1;   // the layer whose gradient the max pool after it left masked by its ReLU
     for (size_t ii = op_hi; ii-- > op_lo;) {
         const Op& op = g.ops[ii];
+        if (done[ii]) continue;
+        if (join_storage >= 0 && op.x >= 0 && storage_of(g, op.x) == join_storage) {
+            // this layer adds to the gradient the branch stream has been writing
+            (void)hipStreamWaitEvent(st, join_event, 0);
+            join_storage = -1;
+        }
         switch (op.kind) {
             case OP_LOSS:
                 written[(size_t)storage_of(g, op.x)] = 1;
@@ -786,6 +869,54 @@ static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, siz
                                    (int64_t)n * t.H * t.W, t.C, op.relu && premasked_for != ii, partial, coef,
                                    fused_for == ii ? fused_rows : 0, st);
                 written[(size_t)sx] = 1;
+                // The gradient of the shortcut is final now.  If the shortcut is a projection (the convolution and
+                // batch norm listed just before), its backward - batch norm, weight gradient, input gradient into
+                // the block's input - needs nothing else of the main branch: it goes to the second side stream,
+                // with a reduction scratch of its own, while the main branch's chain continues here.  The block's
+                // first convolution, which adds to the same input gradient, waits for it.
+                if (branch && op.res >= 0 && ii >= op_lo + 2 && join_storage < 0) {
+                    const Op& pb = g.ops[ii - 1];
+                    const Op& pj = g.ops[ii - 2];
+                    const int pj_sx = pj.x >= 0 ? storage_of(g, pj.x) : 0;
+                    if (pb.kind == OP_BN && pb.y == op.res && pb.res < 0 && pj.kind == OP_CONV && pj.y == pb.x && pj_sx != 0 &&
+                        h->L.wpad[ii - 2] < 0) {
+                        hipEvent_t go = h->ev_branch_go[h->branch_slot], dn = h->ev_branch_done[h->branch_slot];
+                        hipEvent_t wg = h->ev_ready[h->ev_slot];
+                        if (hipEventRecord(go, st) == hipSuccess && hipStreamWaitEvent(h->upd, go, 0) == hipSuccess) {
+                            h->branch_slot = (h->branch_slot + 1) % kBranchEvents;
+                            h->ev_slot = (h->ev_slot + 1) % kReadyEvents;
+                            hipStream_t bs = h->upd;
+                            float* const ps = h->sc<float>(h->L.partial_side);
+                            const Tensor& tb = g.tensors[(size_t)pb.x];
+                            launch_bn_backward(dt, h->act(pb.x), h->act(pb.y), h->grad(pb.y), h->grad(pb.x), nullptr, false,
+                                               h->w() + pb.w_off, h->at<float>(h->L.bn_save[ii - 1]), G + pb.w_off, G + pb.b_off,
+                                               (int64_t)n * tb.H * tb.W, tb.C, pb.relu, ps, h->sc<float>(h->L.coef_side), 0, bs);
+                            written[(size_t)storage_of(g, pb.x)] = 1;
+                            const ConvGeom qj = geom_padded(g, pj, n, h->L.cpad);
+                            launch_bias_relu_backward(dt, h->act(pj.y), h->grad(pj.y), pj.bias ? G + pj.b_off : nullptr,
+                                                      (int64_t)n * qj.Ho * qj.Wo, pj.K, pj.relu, ps, 0, bs);
+                            // weight gradient: on the first side stream like every other, behind this stream's work
+                            hipStream_t ws = bs;
+                            if (hipEventRecord(wg, bs) == hipSuccess && hipStreamWaitEvent(h->side, wg, 0) == hipSuccess) {
+                                ws = h->side;
+                                used_side = true;
+                            }
+                            launch_conv_wgrad(dt, qj, h->act(pj.x), h->grad(pj.y), G + pj.w_off,
+                                              ws == h->side ? h->sc<float>(h->L.wgrad_scratch) : nullptr,
+                                              ws == h->side ? (size_t)h->L.wgrad_scratch_bytes : 0, ws);
+                            // input gradient, with this stream's own split-reduction scratch; nothing to hand over (the
+                            // block's first convolution is the last to add to this gradient)
+                            launch_conv_dgrad(dt, qj, h->grad(pj.y), h->arena + h->L.wT[ii - 2], written[(size_t)pj_sx] != 0,
+                                              h->grad(pj.x), h->sc<float>(h->L.splitk_side), (size_t)h->L.splitk_scratch_bytes, nullptr, bs);
+                            written[(size_t)pj_sx] = 1;
+                            (void)hipEventRecord(dn, bs);
+                            done[ii - 1] = done[ii - 2] = 1;
+                            join_storage = pj_sx;
+                            join_event = dn;
+                            used_upd = true;
+                        }
+                    }
+                }
                 break;
             }
             case OP_MAXPOOL: {

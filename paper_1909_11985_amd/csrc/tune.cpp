@@ -42,6 +42,7 @@ const Entry kEntries[] = {
     {"upd_wide", &Tune::upd_wide},
     {"upd_nt", &Tune::upd_nt},
     {"upd_blocks", &Tune::upd_blocks},
+    {"branch_stream", &Tune::branch_stream},
     {"persistent", &Tune::persistent},
     {"spare0", &Tune::spare0},
     {"spare1", &Tune::spare1},

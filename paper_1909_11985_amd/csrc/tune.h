@@ -37,6 +37,7 @@ struct Tune {
     int64_t upd_wide = -1;            // > 0: the update walks its streams in wave-wide pieces, this many vectors per lane (1, 2, 4); -1: chosen by p; 0: one vector per lane, plain loads
     int64_t upd_nt = -1;              // ... non-temporal accesses: bit 0 gradient loads, bit 1 bf16 store, bit 2 w and v; -1: chosen by p
     int64_t upd_blocks = 0;           // ... > 0: grid-stride launch of this many workgroups
+    int64_t branch_stream = 1;        // a residual block's projection shortcut runs on the second side stream beside the main branch
     int64_t persistent = 1;           // persistent tile loop for forward / dgrad launches with several rounds of workgroups
     int64_t spare0 = 0, spare1 = 0;   // free slots for experiments (EDL_TUNE_SPARE0 / 1)
 };

@@ -824,6 +824,8 @@ def test_the_second_stream_does_not_change_the_result():
     base = _digest_after_steps({})
     assert _digest_after_steps({"wgrad_stream": 0}) == base               # jobs created without side streams
     assert _digest_after_steps({"wgrad_tail_main": 0}) == base
+    assert _digest_after_steps({"branch_stream": 0}) == base              # projection shortcuts on the main stream
+    assert _digest_after_steps({"branch_stream": 0, "wgrad_stream": 0}) == base
     assert _digest_after_steps({}, side_streams="torch") == base          # the caller's streams
     assert _digest_after_steps({}, side_streams=None) == base             # none: edl_set_side_streams(NULL, NULL)
 
@@ -838,6 +840,7 @@ def test_the_update_started_during_the_backward_pass_does_not_change_the_result(
     assert _digest_after_steps({"early_update": 1}, **kw) == base
     assert _digest_after_steps({"early_update": 100000, "early_blocks": 8}, **kw) == base
     assert _digest_after_steps({"early_update": 1}, side_streams="torch", **kw) == base
+    assert _digest_after_steps({"early_update": 1, "branch_stream": 0}, **kw) == base
 
 
 def test_side_streams_are_checked():
