@@ -263,11 +263,16 @@ struct edl_handle {
     int device = -1;
     std::vector<char> written;           // backward pass: which gradient buffers hold something (per tensor)
     std::vector<char> op_done;           // a pass: layers already launched out of list order (on the branch stream)
+    // backward pass, per tensor: where the gradient "already there" is to be read from if not from the tensor's
+    // own gradient buffer (an identity shortcut's part is the masked gradient of the block's output itself)
+    std::vector<const void*> grad_alias;
     // The projection shortcut of a residual block (a convolution and its batch norm) depends only on the block's
     // input (forward) / on the gradient the block's last batch norm leaves for it (backward), so it runs on the
     // second side stream beside the main branch: ev_branch_go releases it, ev_branch_done joins it.
     hipEvent_t ev_branch_go[kBranchEvents] = {}, ev_branch_done[kBranchEvents] = {};
     int branch_slot = 0;
+    hipEvent_t ev_tr_go = nullptr, ev_tr_done = nullptr;   // around the weight transposes on the weight-gradient stream
+    bool transposes_pending = false;
 
     template <typename T> T* at(int64_t off) const { return reinterpret_cast<T*>(arena + off); }
     // a piece of the kernels' scratch (off is its arena offset)
@@ -367,12 +372,14 @@ static int refresh_weight_copies(edl_handle* h) {
     return EDL_OK;
 }
 
-static void transpose_weights(edl_handle* h) {
+// The transposed weight copies (read by the input-gradient passes only) on stream tst; the zero-padded copy of
+// the first convolution's weights (read by the forward pass) on the job's stream.
+static void transpose_weights(edl_handle* h, hipStream_t tst) {
     launch_weight_transpose_all(h->cfg.dtype, h->w(), h->arena, h->at<TransposeEntry>(h->L.ttable), h->t_entries,
-                                h->t_tiles, h->t_bytes, h->st);
+                                h->t_tiles, h->t_bytes, tst);
     if (h->tv_entries > 0)
         launch_weight_transpose_bf16(h->at<uint16_t>(h->L.shadow), h->arena, h->at<TransposeEntry>(h->L.ttable) + h->g.ops.size(),
-                                     h->tv_entries, h->tv_tiles, h->tv_bytes, h->st);
+                                     h->tv_entries, h->tv_tiles, h->tv_bytes, tst);
     for (size_t i = 0; i < h->g.ops.size(); ++i)
         if (h->L.wpad[i] >= 0) {
             const Op& op = h->g.ops[i];
@@ -391,6 +398,8 @@ static int create_side_events(edl_handle* h) {
     for (int e = 0; e < kChunkEvents; ++e)
         if (!h->ev_chunk[e]) HIP_TRY(hipEventCreateWithFlags(&h->ev_chunk[e], hipEventDisableTiming));
     if (!h->ev_upd_done) HIP_TRY(hipEventCreateWithFlags(&h->ev_upd_done, hipEventDisableTiming));
+    if (!h->ev_tr_go) HIP_TRY(hipEventCreateWithFlags(&h->ev_tr_go, hipEventDisableTiming));
+    if (!h->ev_tr_done) HIP_TRY(hipEventCreateWithFlags(&h->ev_tr_done, hipEventDisableTiming));
     for (int e = 0; e < kBranchEvents; ++e) {
         if (!h->ev_branch_go[e]) HIP_TRY(hipEventCreateWithFlags(&h->ev_branch_go[e], hipEventDisableTiming));
         if (!h->ev_branch_done[e]) HIP_TRY(hipEventCreateWithFlags(&h->ev_branch_done[e], hipEventDisableTiming));
@@ -426,6 +435,8 @@ static void destroy_handle(edl_handle* h) {
         if (h->ev_chunk[e]) (void)hipEventDestroy(h->ev_chunk[e]);
     if (h->ev_side_done) (void)hipEventDestroy(h->ev_side_done);
     if (h->ev_upd_done) (void)hipEventDestroy(h->ev_upd_done);
+    if (h->ev_tr_go) (void)hipEventDestroy(h->ev_tr_go);
+    if (h->ev_tr_done) (void)hipEventDestroy(h->ev_tr_done);
     for (int e = 0; e < kBranchEvents; ++e) {
         if (h->ev_branch_go[e]) (void)hipEventDestroy(h->ev_branch_go[e]);
         if (h->ev_branch_done[e]) (void)hipEventDestroy(h->ev_branch_done[e]);
@@ -456,6 +467,7 @@ int32_t edl_init(edl_handle** out, const edl_config* cfg, uint64_t seed, void* d
     h->readers.assign(h->g.tensors.size(), 0);
     h->written.assign(h->g.tensors.size(), 0);
     h->op_done.assign(h->g.ops.size(), 0);
+    h->grad_alias.assign(h->g.tensors.size(), nullptr);
     h->shard_n.reserve(kMaxP);
     h->perm.reserve((size_t)cfg->N);
     h->first_reader.assign(h->g.tensors.size(), -1);
@@ -737,8 +749,13 @@ static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, siz
     hipStream_t st = h->st;
     float* partial = h->sc<float>(h->L.partial);
     float* coef = h->sc<float>(h->L.coef);
+    if (h->transposes_pending) {          // the transposed weight copies were made on the weight-gradient stream
+        (void)hipStreamWaitEvent(st, h->ev_tr_done, 0);
+        h->transposes_pending = false;
+    }
     std::vector<char>& written = h->written;     // sized at init: no allocation in the pass
     std::fill(written.begin(), written.end(), 0);
+    std::fill(h->grad_alias.begin(), h->grad_alias.end(), nullptr);
     if (held)
         for (int t : *held) written[(size_t)storage_of(g, t)] = 1;
     if (op_hi > g.ops.size()) op_hi = g.ops.size();
@@ -847,7 +864,8 @@ static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, siz
                     }
                     const int rows = launch_conv_dgrad(dt, q, h->grad(op.y), h->arena + h->L.wT[ii], acc, h->grad(op.x),
                                                        h->sc<float>(h->L.splitk_scratch), (size_t)h->L.splitk_scratch_bytes,
-                                                       mask.act ? &mask : nullptr, st);
+                                                       mask.act ? &mask : nullptr, st, acc ? h->grad_alias[(size_t)sx] : nullptr);
+                    h->grad_alias[(size_t)sx] = nullptr;
                     if (rows > 0) { fused_for = ii - 1; fused_rows = rows; }
                     written[(size_t)sx] = 1;
                 }
@@ -863,8 +881,28 @@ static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, siz
                     dres = h->grad(op.res);
                     dres_acc = written[(size_t)sr] != 0;
                     written[(size_t)sr] = 1;
+                    // An identity shortcut whose gradient would be a plain copy of this layer's (already masked)
+                    // output gradient: nothing is copied; the one other reader of the tensor - a stride-1
+                    // convolution later in this pass, which adds its part - reads it from where it lies.
+                    const bool dy_is_dres = !dres_acc && (!op.relu || fused_for == ii || premasked_for == ii);
+                    const int fr = h->first_reader[(size_t)sr];
+                    if (dy_is_dres && tune().alias_shortcut != 0 && h->readers[(size_t)sr] == 2 && fr >= (int)op_lo && fr < (int)ii &&
+                        g.ops[(size_t)fr].kind == OP_CONV && g.ops[(size_t)fr].stride == 1 && storage_of(g, g.ops[(size_t)fr].x) == sr) {
+                        h->grad_alias[(size_t)sr] = h->grad(op.y);
+                        dres = nullptr;
+                    }
+                    // The same for a projection shortcut: the batch norm listed just before produced the tensor and is
+                    // its only other user, and its backward only reads the gradient.
+                    if (dy_is_dres && tune().alias_shortcut != 0 && h->readers[(size_t)sr] == 1 && ii >= op_lo + 1 &&
+                        g.ops[ii - 1].kind == OP_BN && g.ops[ii - 1].y == op.res && !g.ops[ii - 1].relu) {
+                        h->grad_alias[(size_t)sr] = h->grad(op.y);
+                        dres = nullptr;
+                    }
                 }
-                launch_bn_backward(dt, h->act(op.x), h->act(op.y), h->grad(op.y), h->grad(op.x), dres, dres_acc,
+                const size_t sy = (size_t)storage_of(g, op.y);
+                const void* const dy_src = h->grad_alias[sy] ? h->grad_alias[sy] : h->grad(op.y);
+                h->grad_alias[sy] = nullptr;
+                launch_bn_backward(dt, h->act(op.x), h->act(op.y), dy_src, h->grad(op.x), dres, dres_acc,
                                    h->w() + op.w_off, h->at<float>(h->L.bn_save[ii]), G + op.w_off, G + op.b_off,
                                    (int64_t)n * t.H * t.W, t.C, op.relu && premasked_for != ii, partial, coef,
                                    fused_for == ii ? fused_rows : 0, st);
@@ -888,7 +926,10 @@ static void backward_shard(edl_handle* h, int n, float* G, size_t op_lo = 0, siz
                             hipStream_t bs = h->upd;
                             float* const ps = h->sc<float>(h->L.partial_side);
                             const Tensor& tb = g.tensors[(size_t)pb.x];
-                            launch_bn_backward(dt, h->act(pb.x), h->act(pb.y), h->grad(pb.y), h->grad(pb.x), nullptr, false,
+                            const size_t spy = (size_t)storage_of(g, pb.y);
+                            const void* const pdy = h->grad_alias[spy] ? h->grad_alias[spy] : h->grad(pb.y);
+                            h->grad_alias[spy] = nullptr;
+                            launch_bn_backward(dt, h->act(pb.x), h->act(pb.y), pdy, h->grad(pb.x), nullptr, false,
                                                h->w() + pb.w_off, h->at<float>(h->L.bn_save[ii - 1]), G + pb.w_off, G + pb.b_off,
                                                (int64_t)n * tb.H * tb.W, tb.C, pb.relu, ps, h->sc<float>(h->L.coef_side), 0, bs);
                             written[(size_t)storage_of(g, pb.x)] = 1;
@@ -1017,7 +1058,17 @@ int32_t edl_gradients(edl_handle* h, int32_t p, const int64_t* idx, const int64_
         refresh_weight_copies(h);
         h->weights_dirty = false;
     }
-    transpose_weights(h);
+    // The transposed copies are first read by the backward pass: they are made on the weight-gradient stream, which
+    // is idle during the forward pass, and the first backward pass waits for them.
+    h->transposes_pending = false;
+    if (h->side != nullptr && !prof_enabled() && tune().transpose_stream != 0 &&
+        hipEventRecord(h->ev_tr_go, h->st) == hipSuccess && hipStreamWaitEvent(h->side, h->ev_tr_go, 0) == hipSuccess) {
+        transpose_weights(h, h->side);
+        h->transposes_pending = hipEventRecord(h->ev_tr_done, h->side) == hipSuccess;
+        if (!h->transposes_pending) (void)hipStreamSynchronize(h->side);
+    } else {
+        transpose_weights(h, h->st);
+    }
     float* dev_losses = h->at<float>(h->L.losses);
     int64_t at = 0;
     bool first = true;       // the first worker that has samples keeps the running statistics
@@ -1335,7 +1386,7 @@ static int debug_prepare(edl_handle* h, int32_t n) {
     if (!h) { set_error("null handle"); return EDL_EINVAL; }
     if (n <= 0 || n > h->cfg.max_shard || n > h->cfg.B) { set_error("n=%d outside [1, max_shard]", n); return EDL_EINVAL; }
     if (h->weights_dirty) { refresh_weight_copies(h); h->weights_dirty = false; }
-    transpose_weights(h);
+    transpose_weights(h, h->st);
     return EDL_OK;
 }
 

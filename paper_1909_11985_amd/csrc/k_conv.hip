@@ -87,6 +87,10 @@ struct ConvArgs {
     int ph, pw, Hc, Wc, r0, s0, nr, ns;
     int ldb;     // fwd/dgrad: elements between consecutive rows of B
     float* partial;  // fwd/dgrad with a cut reduction: float32 [split][M][Nn] partial sums, else null
+    // dgrad with accumulate: the gradient that is added to is read here (same shape and layout as the output;
+    // null: from the output buffer itself).  Lets the first reader of a residual join take the shortcut's part
+    // from where it already lies instead of from a copy.
+    const void* acc_src;
     // fwd, vector path, whole reduction: if not null, the column sums of the stored output and of its
     // squares over this tile's rows go to stats[c * kRedRowBlocks + row tile] and
     // stats[(Nn + c) * kRedRowBlocks + row tile] (the layout of the batch-norm reduction's partial sums)
@@ -883,7 +887,7 @@ __global__ __launch_bounds__(256, 2) void conv_igemm_kernel(ConvArgs a) {   // a
                     } else if (MODE == CONV_DGRAD) {
                         const int64_t o = out_row<MODE>(a, row) * a.Nn + col;
                         T* dst = (T*)a.out;
-                        if (a.accumulate) v += Elem<T>::to_f32(dst[o]);
+                        if (a.accumulate) v += Elem<T>::to_f32(a.acc_src ? ((const T*)a.acc_src)[o] : dst[o]);
                         dst[o] = Elem<T>::from_f32(v);
                     } else {
                         ((float*)a.out)[((int64_t)tile_z * a.M + row) * a.Nn + col] = v;
@@ -897,6 +901,7 @@ __global__ __launch_bounds__(256, 2) void conv_igemm_kernel(ConvArgs a) {   // a
     // lane and row, conflict-free), then leaves as 16-byte vectors along the output row
     float* const stage = reinterpret_cast<float*>(smem);
     unsigned char* const outp = (unsigned char*)a.out + (WG ? (int64_t)tile_z * a.M * a.Nn * 4 : 0);
+    const unsigned char* const accp = (MODE == CONV_DGRAD && a.acc_src != nullptr) ? (const unsigned char*)a.acc_src : outp;
     const bool to_partial = !WG && a.partial != nullptr;     // cut reduction: raw float32 sums, finished by another kernel
     const bool f32_out = (MODE == CONV_FWD) && a.out_fp32 && !OUT_F32;
     // Every lane stores the same OVEC columns in each of its rows (256 is a multiple of the
@@ -931,7 +936,7 @@ __global__ __launch_bounds__(256, 2) void conv_igemm_kernel(ConvArgs a) {   // a
                 const int v = tid + k * 256, rl = v / CV, cv = v - rl * CV;
                 const int row = m0 + pass * STAGE_ROWS + rl, col = n0 + cv * OVEC;
                 const bool inside = v < STAGE_ROWS * CV && row < a.M && col < a.Nn;
-                const unsigned char* src = inside ? outp + (out_row<MODE, true>(a, row) * a.Nn + col) * OSZ : outp;
+                const unsigned char* src = inside ? accp + (out_row<MODE, true>(a, row) * a.Nn + col) * OSZ : accp;
                 oldv[k] = *reinterpret_cast<const uint4*>(src);
             }
         }
@@ -1126,7 +1131,8 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(const float* __restr
                                                             int64_t M, int Nn, int splits, int relu, int out_fp32, int accumulate,
                                                             int rows_per_block, float* __restrict__ stats,
                                                             const T* __restrict__ mask_act, const T* __restrict__ xin,
-                                                            const float* __restrict__ mean_rstd) {
+                                                            const float* __restrict__ mean_rstd, const void* acc_src) {
+    if (acc_src == nullptr) acc_src = out;      // where the gradient that is added to is read (see ConvArgs)
     // a workgroup owns 64 columns of rows_per_block rows: 16 lanes across (4 columns each), 16 rows at a time
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
     const int col = (blockIdx.x * 16 + tx) * 4;
@@ -1157,7 +1163,10 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(const float* __restr
             if (relu) { s.x = fmaxf(s.x, 0.f); s.y = fmaxf(s.y, 0.f); s.z = fmaxf(s.z, 0.f); s.w = fmaxf(s.w, 0.f); }
             if (out_fp32 || sizeof(T) == 4) {
                 float4* d = reinterpret_cast<float4*>((float*)out + i);
-                if (accumulate) { const float4 o = *d; s.x += o.x; s.y += o.y; s.z += o.z; s.w += o.w; }
+                if (accumulate) {
+                    const float4 o = *reinterpret_cast<const float4*>((const float*)acc_src + i);
+                    s.x += o.x; s.y += o.y; s.z += o.z; s.w += o.w;
+                }
                 if (MASKED) {
                     const float4 am = *reinterpret_cast<const float4*>((const float*)mask_act + i);
                     s.x = am.x > 0.f ? s.x : 0.f; s.y = am.y > 0.f ? s.y : 0.f;
@@ -1177,7 +1186,7 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(const float* __restr
             } else {
                 uint2* d = reinterpret_cast<uint2*>((bf16_t*)out + i);
                 if (accumulate) {
-                    const uint2 o = *d;
+                    const uint2 o = *reinterpret_cast<const uint2*>((const bf16_t*)acc_src + i);
                     s.x += __uint_as_float(o.x << 16); s.y += __uint_as_float(o.x & 0xffff0000u);
                     s.z += __uint_as_float(o.y << 16); s.w += __uint_as_float(o.y & 0xffff0000u);
                 }
@@ -1507,11 +1516,11 @@ static int launch_finish(const ConvArgs& a, int splits, float* stats, hipStream_
     if (mask != nullptr)
         hipLaunchKernelGGL((splitk_finish_kernel<T, true>), dim3(col_blocks, row_blocks), dim3(256), 0, st, a.partial, a.out, a.bias,
                            (int64_t)a.M, a.Nn, splits, a.relu, a.out_fp32, a.accumulate, rows_per_block, stats,
-                           (const T*)mask->act, (const T*)mask->xin, mask->mean_rstd);
+                           (const T*)mask->act, (const T*)mask->xin, mask->mean_rstd, a.acc_src);
     else
         hipLaunchKernelGGL((splitk_finish_kernel<T, false>), dim3(col_blocks, row_blocks), dim3(256), 0, st, a.partial, a.out, a.bias,
                            (int64_t)a.M, a.Nn, splits, a.relu, a.out_fp32, a.accumulate, rows_per_block, stats,
-                           (const T*)nullptr, (const T*)nullptr, (const float*)nullptr);
+                           (const T*)nullptr, (const T*)nullptr, (const float*)nullptr, a.acc_src);
     return stats ? row_blocks : 0;
 }
 
@@ -1567,7 +1576,7 @@ int launch_conv_fwd(int dtype, const ConvGeom& g, const void* x, const void* w, 
 }
 
 int launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dy, const void* wT, bool accumulate, void* dx,
-                      float* scratch, size_t scratch_bytes, const DgradMask* mask, hipStream_t st) {
+                      float* scratch, size_t scratch_bytes, const DgradMask* mask, hipStream_t st, const void* acc_src) {
     int fused_rows = 0;
     const int VEC = dtype == 1 ? 8 : 4;
     ConvArgs a = base_args(g);
@@ -1575,6 +1584,7 @@ int launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dy, const void* 
     a.Nn = g.C;
     a.ldb = g.R * g.S * g.K;
     a.accumulate = accumulate;
+    a.acc_src = (accumulate && g.stride == 1) ? acc_src : nullptr;
     const double esz = dtype == 1 ? 2.0 : 4.0;
     const double bA = esz * (double)g.N * g.Ho * g.Wo * g.K, bB = esz * (double)a.Nn * a.ldb;
     // the vector gather of dy divides pixel coordinates by the stride with a shift

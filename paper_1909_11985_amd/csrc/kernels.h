@@ -88,8 +88,11 @@ struct DgradMask {
 // launch over all pixels, writing), dx is stored already masked and the sums are left in mask->sums; returns
 // the number of row tiles summed (what the producer's backward takes as its row-block count), else 0 and dx
 // is the plain gradient.
+// acc_src (stride 1 with accumulate only; may be null): the gradient that is added to is read from this tensor of
+// dx's shape instead of from dx itself (dx is then written, not read).
 int launch_conv_dgrad(int dtype, const ConvGeom& g, const void* dy, const void* wT, bool accumulate, void* dx,
-                      float* scratch, size_t scratch_bytes, const DgradMask* mask, hipStream_t st);
+                      float* scratch, size_t scratch_bytes, const DgradMask* mask, hipStream_t st,
+                      const void* acc_src = nullptr);
 // float32 scratch a forward / dgrad launch may use to cut a long reduction of a small problem
 size_t conv_splitk_scratch_bytes(int dtype, const ConvGeom& g);
 // dw = x^T * dy, float32 [K][R][S][C]; scratch holds split partial sums

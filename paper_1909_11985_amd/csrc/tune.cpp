@@ -43,6 +43,8 @@ const Entry kEntries[] = {
     {"upd_nt", &Tune::upd_nt},
     {"upd_blocks", &Tune::upd_blocks},
     {"branch_stream", &Tune::branch_stream},
+    {"transpose_stream", &Tune::transpose_stream},
+    {"alias_shortcut", &Tune::alias_shortcut},
     {"persistent", &Tune::persistent},
     {"spare0", &Tune::spare0},
     {"spare1", &Tune::spare1},

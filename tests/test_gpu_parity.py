@@ -826,6 +826,8 @@ def test_the_second_stream_does_not_change_the_result():
     assert _digest_after_steps({"wgrad_tail_main": 0}) == base
     assert _digest_after_steps({"branch_stream": 0}) == base              # projection shortcuts on the main stream
     assert _digest_after_steps({"branch_stream": 0, "wgrad_stream": 0}) == base
+    assert _digest_after_steps({"transpose_stream": 0}) == base           # weight transposes on the main stream
+    assert _digest_after_steps({"alias_shortcut": 0}) == base             # identity shortcuts' gradients copied
     assert _digest_after_steps({}, side_streams="torch") == base          # the caller's streams
     assert _digest_after_steps({}, side_streams=None) == base             # none: edl_set_side_streams(NULL, NULL)
 
