@@ -204,9 +204,12 @@ int32_t edl_set_side_streams(edl_handle* h, void* wgrad_stream, void* update_str
  * force_tile (-1, or 0..3 = every forward / input-gradient launch on 128x128, 128x64, 128x32, 64x64 tiles),
  * wgrad_stream (1: jobs created from now on make their own side streams; 0: they do not), wgrad_tail_main,
  * early_update (least weights of a layer whose update starts during the backward pass; 0 = never),
- * early_blocks, join_tile, fused_stats, held_stats, fused_mask, fused_mask_cut, fused_mask_join, persistent,
+ * early_blocks, join_tile, fused_stats, held_stats, fused_mask, fused_mask_cut, fused_mask_join,
  * min128, min128_long, bk64_kred, xcd, order, splitk_tiles, splitk_target, wgrad_blocks, wgrad_long_blocks,
- * wgrad_long_ks, upd_vpt. */
+ * wgrad_long_ks, upd_vpt, upd_wide, upd_nt, upd_blocks (shape and cache hints of the update kernel's memory
+ * walk), branch_stream (projection shortcuts on the second side stream), transpose_stream, alias_shortcut
+ * (a shortcut's gradient read from the block output's gradient instead of copied), bn_nt, bn_nt_bytes
+ * (non-temporal loads in the batch-norm passes for tensors of at least that many bytes), spare0, spare1. */
 int32_t edl_set_option(const char* name, int64_t value);
 int32_t edl_get_option(const char* name, int64_t* out_value);
 

@@ -12,6 +12,7 @@
 #include "dev_common.h"
 #include "kernels.h"
 #include "profiler.h"
+#include "tune.h"
 
 namespace edl {
 
@@ -49,6 +50,21 @@ template <typename T, int VEC>
 __device__ __forceinline__ void load_row(const T* base, int64_t r, int C, int c0, float (&out)[VEC]) {
     if (VEC > 1) {
         const Vec16<T> v = load_vec(base + r * C + c0);
+        #pragma unroll
+        for (int e = 0; e < VEC; ++e) out[e] = Elem<T>::to_f32(v.e[e]);
+    } else {
+        out[0] = Elem<T>::to_f32(base[r * C + c0]);
+    }
+}
+
+// the same through a non-temporal load: for a tensor this pass reads once and nothing reads again soon
+typedef unsigned int nt_u32x4 __attribute__((ext_vector_type(4)));
+template <typename T, int VEC>
+__device__ __forceinline__ void load_row_nt(const T* base, int64_t r, int C, int c0, float (&out)[VEC]) {
+    if (VEC > 1) {
+        Vec16<T> v;
+        const nt_u32x4 q = __builtin_nontemporal_load(reinterpret_cast<const nt_u32x4*>(base + r * C + c0));
+        v.u = make_uint4(q.x, q.y, q.z, q.w);
         #pragma unroll
         for (int e = 0; e < VEC; ++e) out[e] = Elem<T>::to_f32(v.e[e]);
     } else {
@@ -227,7 +243,7 @@ __global__ __launch_bounds__(256) void bias_finalize_kernel(const float* __restr
 
 // y = relu(gamma * (x - mean) * rstd + beta + res)
 // No load sits behind a run-time branch, so that all of a lane's loads are in flight together.
-template <typename T, int VEC, bool RES>
+template <typename T, int VEC, bool RES, bool NT>
 __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ x, const T* __restrict__ res,
                                                        T* __restrict__ y, const float* __restrict__ gamma,
                                                        const float* __restrict__ beta, const float* __restrict__ mean_rstd,
@@ -238,8 +254,8 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ x, 
         const int64_t r = i / cvecs;
         const int c0 = (int)(i - r * cvecs) * VEC;
         float xv[VEC], rv[VEC], out[VEC];
-        load_row<T, VEC>(x, r, C, c0, xv);
-        if (RES) load_row<T, VEC>(res, r, C, c0, rv);
+        if (NT) load_row_nt<T, VEC>(x, r, C, c0, xv); else load_row<T, VEC>(x, r, C, c0, xv);
+        if (RES) { if (NT) load_row_nt<T, VEC>(res, r, C, c0, rv); else load_row<T, VEC>(res, r, C, c0, rv); }
         #pragma unroll
         for (int e = 0; e < VEC; ++e) {
             const float sc = gamma[c0 + e] * mean_rstd[C + c0 + e];
@@ -255,7 +271,7 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ x, 
 // MASK: dy' = dy * (y > 0) is formed here (else dy arrives masked, or there is no ReLU, and y is not read);
 // ACC: dres already holds a gradient that dy' is added to.  Compile-time, so that no load sits behind a
 // run-time branch and none is issued that is not needed.
-template <typename T, int VEC, bool MASK, bool ACC>
+template <typename T, int VEC, bool MASK, bool ACC, bool NT>
 __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const T* __restrict__ x, const T* __restrict__ y,
                                                            const T* __restrict__ dy, T* __restrict__ dx, T* dres,
                                                            const float* __restrict__ gamma,
@@ -267,9 +283,9 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const T* __restrict__
         const int64_t r = i / cvecs;
         const int c0 = (int)(i - r * cvecs) * VEC;
         float xv[VEC], yv[VEC], g[VEC], old[VEC], out[VEC];
-        load_row<T, VEC>(x, r, C, c0, xv);
+        if (NT) load_row_nt<T, VEC>(x, r, C, c0, xv); else load_row<T, VEC>(x, r, C, c0, xv);
         load_row<T, VEC>(dy, r, C, c0, g);
-        if (MASK) load_row<T, VEC>(y, r, C, c0, yv);
+        if (MASK) { if (NT) load_row_nt<T, VEC>(y, r, C, c0, yv); else load_row<T, VEC>(y, r, C, c0, yv); }
         if (ACC) load_row<T, VEC>(dres, r, C, c0, old);
         #pragma unroll
         for (int e = 0; e < VEC; ++e) {
@@ -314,12 +330,13 @@ static void bn_forward_t(const void* x, const void* res, void* y, const float* g
                            save, running);
     }
     ProfScope ps(prof_shape_label("bn_apply", M, C), 0.0, tb * (res ? 3.0 : 2.0), st);
-    if (res)
-        hipLaunchKernelGGL((bn_apply_kernel<T, VEC, true>), dim3(ew_grid(M * s.cvecs)), dim3(256), 0, st, (const T*)x,
-                           (const T*)res, (T*)y, gamma, beta, save, M, C, s.cvecs, relu ? 1 : 0);
-    else
-        hipLaunchKernelGGL((bn_apply_kernel<T, VEC, false>), dim3(ew_grid(M * s.cvecs)), dim3(256), 0, st, (const T*)x,
-                           (const T*)nullptr, (T*)y, gamma, beta, save, M, C, s.cvecs, relu ? 1 : 0);
+    const bool nt = tune().bn_nt != 0 && tb >= (double)tune().bn_nt_bytes;
+#define EDL_BN_APPLY(RES, NT)                                                                                          \
+    hipLaunchKernelGGL((bn_apply_kernel<T, VEC, RES, NT>), dim3(ew_grid(M * s.cvecs)), dim3(256), 0, st, (const T*)x, \
+                       (const T*)res, (T*)y, gamma, beta, save, M, C, s.cvecs, relu ? 1 : 0)
+    if (res) { if (nt) EDL_BN_APPLY(true, true); else EDL_BN_APPLY(true, false); }
+    else { if (nt) EDL_BN_APPLY(false, true); else EDL_BN_APPLY(false, false); }
+#undef EDL_BN_APPLY
 }
 
 void launch_bn_forward(int dtype, const void* x, const void* res, void* y, const float* gamma, const float* beta,
@@ -357,9 +374,14 @@ static void bn_backward_t(const void* x, const void* y, const void* dy, void* dx
     const bool acc = dres && dres_acc;
     ProfScope ps(prof_shape_label("bn_bwd_apply", M, C), 0.0, tb * ((mask ? 3.0 : 2.0) + 1.0 + (dres ? (acc ? 2.0 : 1.0) : 0.0)), st);
     const dim3 grid(ew_grid(M * s.cvecs));
+    const bool nt = tune().bn_nt != 0 && tb >= (double)tune().bn_nt_bytes;
 #define EDL_BN_BWD_APPLY(MASK, ACC)                                                                                       \
-    hipLaunchKernelGGL((bn_bwd_apply_kernel<T, VEC, MASK, ACC>), grid, dim3(256), 0, st, (const T*)x, (const T*)y, (const T*)dy, \
-                       (T*)dx, (T*)dres, gamma, save, coef, M, C, s.cvecs)
+    do {                                                                                                                  \
+        if (nt) hipLaunchKernelGGL((bn_bwd_apply_kernel<T, VEC, MASK, ACC, true>), grid, dim3(256), 0, st, (const T*)x, (const T*)y, (const T*)dy, \
+                                   (T*)dx, (T*)dres, gamma, save, coef, M, C, s.cvecs);                                  \
+        else hipLaunchKernelGGL((bn_bwd_apply_kernel<T, VEC, MASK, ACC, false>), grid, dim3(256), 0, st, (const T*)x, (const T*)y, (const T*)dy, \
+                                (T*)dx, (T*)dres, gamma, save, coef, M, C, s.cvecs);                                     \
+    } while (0)
     if (mask) { if (acc) EDL_BN_BWD_APPLY(true, true); else EDL_BN_BWD_APPLY(true, false); }
     else { if (acc) EDL_BN_BWD_APPLY(false, true); else EDL_BN_BWD_APPLY(false, false); }
 #undef EDL_BN_BWD_APPLY

@@ -45,7 +45,8 @@ const Entry kEntries[] = {
     {"branch_stream", &Tune::branch_stream},
     {"transpose_stream", &Tune::transpose_stream},
     {"alias_shortcut", &Tune::alias_shortcut},
-    {"persistent", &Tune::persistent},
+    {"bn_nt", &Tune::bn_nt},
+    {"bn_nt_bytes", &Tune::bn_nt_bytes},
     {"spare0", &Tune::spare0},
     {"spare1", &Tune::spare1},
 };

@@ -40,7 +40,8 @@ struct Tune {
     int64_t branch_stream = 1;        // a residual block's projection shortcut runs on the second side stream beside the main branch
     int64_t transpose_stream = 0;     // 1: the transposed weight copies are made on the weight-gradient stream during the forward pass (measured: no gain, 4.499 vs 4.509 ms)
     int64_t alias_shortcut = 1;       // an identity shortcut's gradient is read from the block output's gradient instead of being copied
-    int64_t persistent = 1;           // persistent tile loop for forward / dgrad launches with several rounds of workgroups
+    int64_t bn_nt = 1;                // the batch-norm element-wise passes load what they read once (the convolution's output; the activation for the mask) non-temporally ...
+    int64_t bn_nt_bytes = 8000000;    // ... for tensors of at least this many bytes
     int64_t spare0 = 0, spare1 = 0;   // free slots for experiments (EDL_TUNE_SPARE0 / 1)
 };
 
