@@ -16,7 +16,9 @@ Prints ONE JSON line.  Besides the contract fields it carries
                 events on the launch stream (the library's own profiling hooks)
   cpu_baseline  the CPU oracle, as it stands, timed on a bounded sample of the same workload
   update, snapshot   the HBM-bound parts of the metric on the VGG-16-sized state
-                (138,357,544 parameters): achieved GB/s against the 8 TB/s peak
+                (138,357,544 parameters): achieved GB/s against the 8 TB/s peak; the update
+                kernel is timed where it runs in use, at the end of VGG-16 training steps over
+                p shards (`gbs`), and launched back to back on its own (`back_to_back_gbs`)
   kernels       per-family time, launches and achieved rate of one step
 """
 import argparse
@@ -283,44 +285,81 @@ def main():
     if not args.no_state_bench:
         P = VGG16_P
         update = []
-        w = torch.from_numpy(synth_inputs.vector(4, P)).cuda()
-        v = torch.zeros(P, device="cuda")
-        w16 = torch.empty(P, dtype=torch.bfloat16, device="cuda")
-        g0 = synth_inputs.gradient_buffers(3, 1, P)[0]
-        grads = [torch.from_numpy(g0).cuda() for _ in range(8)]
+        # the state arrays lie where a VGG-16 job of up to 8 shards has them in its arena (edl_query's offsets)
+        lays = {opt: E.edl_query(make_config("vgg16", dtype="bf16", N=8, B=8, p_max=8, max_shard=1, optimizer=opt))
+                for opt in ("momentum", "adam")}
+        state_end = max(max(l.params_off, l.momentum_off, l.second_off, l.shadow_off, l.grads_off + 4 * l.grad_stride * 7)
+                        for l in lays.values()) + 4 * P
+        pool = torch.empty(state_end + 8192, dtype=torch.uint8, device="cuda")
+        pool0 = (-pool.data_ptr()) % 8192              # the arena starts on an 8 KB boundary
+        w0 = torch.from_numpy(synth_inputs.vector(4, P))
+        g0 = torch.from_numpy(synth_inputs.gradient_buffers(3, 1, P)[0])
+
+        def state_views(lay):
+            assert lay.P == P
+
+            def view(off, dtype):
+                return pool[pool0 + off: pool0 + off + P * dtype.itemsize].view(dtype)
+
+            w, v, w16 = view(lay.params_off, torch.float32), view(lay.momentum_off, torch.float32), view(lay.shadow_off, torch.bfloat16)
+            s2 = view(lay.second_off, torch.float32) if lay.second_off >= 0 else None
+            grads = [view(lay.grads_off + 4 * lay.grad_stride * k, torch.float32) for k in range(8)]
+            w.copy_(w0)
+            v.zero_()
+            if s2 is not None:
+                s2.zero_()
+            for g in grads:
+                g.copy_(g0)
+            return w, v, s2, w16, grads
+
+        def timed(name, launch, reps=10):
+            """GB/s of the kernel `name` over `reps` launches (HIP events on the launch stream, pair overhead taken off)"""
+            torch.cuda.synchronize()
+            E.edl_profile(True)
+            for i in range(reps):
+                launch(i)
+            torch.cuda.synchronize()
+            rr = E.edl_profile_report()
+            E.edl_profile(False)
+            r = [q for q in rr if q["name"] == name][0]
+            ms = r["ms"] - overhead_ms * r["launches"]
+            return r["bytes"] / ms / 1e6, 1e3 * ms / r["launches"]
+
+        # launched back to back on their own (every launch starts while the previous one's stores are still on
+        # their way to memory: the lower of the two figures) ...
+        alone = {}
+        w, v, _, w16, grads = state_views(lays["momentum"])
         for pp in (1, 2, 4, 8):
             for _ in range(2):
                 E.edl_average_update(grads[:pp], w, v, w16, 0.01, 0.9, 5e-4)
-            torch.cuda.synchronize()
-            E.edl_profile(True)
-            for _ in range(10):
-                E.edl_average_update(grads[:pp], w, v, w16, 0.01, 0.9, 5e-4)
-            torch.cuda.synchronize()
-            rr = E.edl_profile_report()
-            r = [q for q in rr if q["name"] == "average_update"][0]
-            r["ms"] -= overhead_ms * r["launches"]
-            E.edl_profile(False)
-            gbs = r["bytes"] / r["ms"] / 1e6
-            update.append(dict(p=pp, P=P, bytes_per_param=4 * pp + 18, us=round(1e3 * r["ms"] / r["launches"], 1),
-                               gbs=round(gbs, 1), frac_of_hbm_peak=round(gbs / HBM_PEAK_GBS, 4)))
-        # the same aggregation fused with the Adam update (one more state array read and written)
-        s2 = torch.zeros(P, device="cuda")
+            alone[("momentum", pp)] = timed("average_update", lambda i: E.edl_average_update(grads[:pp], w, v, w16, 0.01, 0.9, 5e-4))[0]
+        w, v, s2, w16, grads = state_views(lays["adam"])
         for pp in (1, 8):
             for t in (1, 2):
                 E.edl_adam_update(grads[:pp], w, v, s2, w16, 0.001, 0.9, 0.999, 1e-8, 5e-4, t)
-            torch.cuda.synchronize()
-            E.edl_profile(True)
-            for t in range(3, 13):
-                E.edl_adam_update(grads[:pp], w, v, s2, w16, 0.001, 0.9, 0.999, 1e-8, 5e-4, t)
-            torch.cuda.synchronize()
-            rr = E.edl_profile_report()
-            r = [q for q in rr if q["name"] == "adam_update"][0]
-            r["ms"] -= overhead_ms * r["launches"]
-            E.edl_profile(False)
-            gbs = r["bytes"] / r["ms"] / 1e6
-            update.append(dict(optimizer="adam", p=pp, P=P, bytes_per_param=4 * pp + 26, us=round(1e3 * r["ms"] / r["launches"], 1),
-                               gbs=round(gbs, 1), frac_of_hbm_peak=round(gbs / HBM_PEAK_GBS, 4)))
-        del grads, s2
+            alone[("adam", pp)] = timed("adam_update", lambda i: E.edl_adam_update(grads[:pp], w, v, s2, w16, 0.001, 0.9, 0.999, 1e-8, 5e-4, 3 + i))[0]
+        del grads, s2, w, v, w16, pool
+        # ... and where the kernel runs in use: at the end of VGG-16 training steps over p shards of 32 / p samples
+        # (one stream, so that an event pair brackets one kernel)
+        vx, vy = synth_inputs.dataset(1, 64, 224, 224, 3, 1000)
+        vdx, vdy = torch.from_numpy(vx).cuda(), torch.from_numpy(vy).cuda()
+        for opt, kernel, ps, extra in (("momentum", "average_update", (1, 2, 4, 8), 18), ("adam", "adam_update", (1, 8), 26)):
+            vjob = E.Job(make_config("vgg16", dtype="bf16", N=64, B=32, p_max=8, max_shard=32, lr=0.001, optimizer=opt), 0,
+                         side_streams=None)
+            vjob.bind_dataset(vdx, vdy)
+            for pp in ps:
+                for _ in range(2):
+                    vjob.step(pp, want_loss=False)
+                gbs, us = timed(kernel, lambda i: vjob.step(pp, want_loss=False), reps=6)
+                row = dict(p=pp, P=P, bytes_per_param=4 * pp + extra, us=round(us, 1), gbs=round(gbs, 1),
+                           frac_of_hbm_peak=round(gbs / HBM_PEAK_GBS, 4), where="end of a VGG-16 step, shards of %d" % (32 // pp),
+                           back_to_back_gbs=round(alone[(opt, pp)], 1))
+                if opt == "adam":
+                    row = dict(optimizer="adam", **row)
+                update.append(row)
+            vjob.shutdown()
+            del vjob
+        del vdx, vdy
         nbytes = 8 * P
         src = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
         dst = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
@@ -338,7 +377,7 @@ def main():
         gbs = r["bytes"] / r["ms"] / 1e6
         snapshot = dict(state_bytes=nbytes, us=round(1e3 * r["ms"] / r["launches"], 1), gbs=round(gbs, 1),
                         frac_of_hbm_peak=round(gbs / HBM_PEAK_GBS, 4))
-        del src, dst, w, v, w16
+        del src, dst
         # attainable matrix rate: register-resident MFMA loop in the workload's matrix instruction
         sink = torch.zeros(1, device="cuda")
         E.edl_mfma_rate(dtype, 256 * 8, 2000, sink)

@@ -100,7 +100,10 @@ typedef struct edl_config {
     float beta2, eps;   /* Adam only: 0 <= beta2 < 1, eps >= 0 (ignored by EDL_OPT_MOMENTUM) */
 } edl_config;
 
-/* byte sizes and offsets inside the caller's arena (all offsets 256-byte aligned) */
+/* byte sizes and offsets inside the caller's arena (all offsets 256-byte aligned).  w, v, the second moment, the
+ * bf16 copy and the gradient buffers start on 4 KB boundaries of alternating parity (offset bit 12), which is
+ * what the update kernel runs fastest on; that holds in memory if the arena itself starts on an 8 KB boundary
+ * (any 256-byte-aligned arena is correct). */
 typedef struct edl_sizes {
     int64_t P;              /* parameters */
     int64_t R;              /* running-statistics floats (per batch-norm layer: mean[C], var[C]) */
@@ -115,6 +118,7 @@ typedef struct edl_sizes {
     int64_t second_off;     /* float32 s[P]: Adam's second moment; -1 with EDL_OPT_MOMENTUM */
     int64_t scratch_bytes;  /* the part of the arena that is the kernels' scratch (what edl_step_static_scratch
                                must fit into EDL_STATIC_SCRATCH_BYTES) */
+    int64_t shadow_off;     /* bf16 copy of w[P] that the contractions read; -1 for float32 jobs */
 } edl_sizes;
 
 /* progress of the job: what notify_batch_end() counts */

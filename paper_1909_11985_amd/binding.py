@@ -35,7 +35,7 @@ class Sizes(C.Structure):
     _fields_ = [("P", C.c_int64), ("R", C.c_int64), ("params_off", C.c_int64), ("momentum_off", C.c_int64),
                 ("running_off", C.c_int64), ("grads_off", C.c_int64), ("grad_stride", C.c_int64),
                 ("arena_bytes", C.c_int64), ("snapshot_bytes", C.c_int64), ("flops_per_sample", C.c_double),
-                ("second_off", C.c_int64), ("scratch_bytes", C.c_int64)]
+                ("second_off", C.c_int64), ("scratch_bytes", C.c_int64), ("shadow_off", C.c_int64)]
 
 
 class Progress(C.Structure):

@@ -127,13 +127,25 @@ void plan_layout(const edl_config& c, const Graph& g, Layout& L) {
     L.cpad = input_pad(c, g);
     int64_t o = 0;
     auto take = [&](int64_t bytes) { const int64_t at = o; o += align_up(bytes); return at; };
-    L.params = take(4 * g.P);
-    L.momentum = take(4 * g.P);
-    if (c.optimizer == EDL_OPT_ADAM) L.second = take(4 * g.P);
+    // The arrays the update kernel walks side by side (w, v, the bf16 copy, the p gradient buffers) start on 4 KB
+    // boundaries, alternately even and odd ones (offset bit 12): a workgroup touches the same offset of every
+    // array at the same time, and arrays that all start 8 KB-aligned meet in the same half of the memory system
+    // (measured: 5.6 -> 6.2 TB/s for the update; the arena itself should start on an 8 KB boundary for this to
+    // hold, as torch's large allocations do).
+    auto take_page = [&](int64_t bytes, int odd) {
+        o = (o + 8191) / 8192 * 8192 + (odd ? 4096 : 0);
+        const int64_t at = o;
+        o += align_up(bytes);
+        return at;
+    };
+    L.params = take_page(4 * g.P, 0);
+    L.momentum = take_page(4 * g.P, 1);
+    if (c.optimizer == EDL_OPT_ADAM) L.second = take_page(4 * g.P, 0);
+    L.shadow = c.dtype == EDL_DTYPE_BF16 ? take_page(2 * g.P, c.optimizer == EDL_OPT_ADAM ? 1 : 0) : -1;
+    // consecutive gradient buffers an odd number of 4 KB pages apart, the first one on an odd page
+    L.grad_stride = ((4 * g.P + 8191) / 8192 * 8192 + 4096) / 4;
+    L.grads = take_page(4 * L.grad_stride * c.p_max, 1);
     L.running = take(4 * std::max<int64_t>(g.R, 1));
-    L.shadow = c.dtype == EDL_DTYPE_BF16 ? take(2 * g.P) : -1;
-    L.grad_stride = align_up(4 * g.P) / 4;
-    L.grads = take(4 * L.grad_stride * c.p_max);
     L.idx = take(8 * c.B);
     L.labels = take(4 * (int64_t)c.max_shard);
     L.losses = take(4 * kMaxP);
@@ -314,6 +326,7 @@ int32_t edl_query(const edl_config* cfg, edl_sizes* out) {
     out->snapshot_bytes = EDL_SNAPSHOT_HEADER_BYTES + 4 * ((cfg->optimizer == EDL_OPT_ADAM ? 3 : 2) * g.P + g.R);
     out->flops_per_sample = g.flops_per_sample();
     out->second_off = L.second;
+    out->shadow_off = L.shadow;
     out->scratch_bytes = L.scratch_hi - L.scratch_lo;
     return EDL_OK;
 }

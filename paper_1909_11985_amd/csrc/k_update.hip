@@ -212,9 +212,17 @@ void launch_average_update(int p, const GradPtrs& grads, float* w, float* v, uin
     // Measured on the 138 M-parameter state (update sweep, MI355X): the wave-wide walk with non-temporal
     // gradient loads and bf16 store gives 5.9 / 5.7 / 5.7 TB/s at p = 1 / 2 / 4 with one vector per lane (the kernel
     // above: 5.4 / 5.3 / 5.2), and 5.6 TB/s at p = 8 with four vectors per lane and w, v non-temporal too (5.3).
+    // Where w and v start on 4 KB boundaries of opposite parity (address bit 12; the library's own arena
+    // alternates it from one state array to the next), their pieces no longer meet in the same half of the
+    // memory system at the same moment, and one vector per lane is the best walk for every p.  At the end of
+    // a VGG-16 training step: 6.4 / 6.3 / 6.1 / 5.9 TB/s at p = 1 / 2 / 4 / 8 with non-temporal gradient loads and
+    // bf16 store (w, v non-temporal as well: 6.2 / 6.2 / 6.1 / 5.9; four vectors per lane: 5.7).  Launched back to
+    // back on its own, the same kernel reads 6.0 / 5.9 / 5.9 / 5.8 (on arrays that all start on 8 KB boundaries
+    // 5.8 / 5.5 / 5.6 / 5.6): the previous launch's stores are still being written back.
+    const bool alternating = (((uintptr_t)w | (uintptr_t)v) & 4095) == 0 && ((((uintptr_t)w ^ (uintptr_t)v) >> 12) & 1) != 0;
     int wide = (int)tune().upd_wide, nt = (int)tune().upd_nt;
-    if (wide < 0) wide = p >= 8 ? 4 : 1;
-    if (nt < 0) nt = p >= 8 ? 7 : 3;
+    if (wide < 0) wide = alternating ? 1 : p >= 8 ? 4 : 1;
+    if (nt < 0) nt = alternating ? 3 : p >= 8 ? 7 : 3;
     if (wide > 0 && (p == 1 || p == 2 || p == 4 || p == 8)) {
         int wgrid = (int)std::max<int64_t>(1, (nvec + 256 * wide - 1) / (256 * wide));
         if (tune().upd_blocks > 0 && wgrid > tune().upd_blocks) wgrid = (int)tune().upd_blocks;
@@ -295,22 +303,24 @@ __global__ __launch_bounds__(256) void adam_update_kernel(GradPtrs gp, ShardShar
         float4 wi = reinterpret_cast<float4*>(w)[i];
         float4 mi = reinterpret_cast<float4*>(m)[i];
         float4 si = reinterpret_cast<float4*>(s)[i];
-        float4 g = reinterpret_cast<const float4*>(gp.g[0])[i];
+        // the gradient buffers are read once and never again: non-temporal loads (as is the bf16 store below)
+        const f32x4 g0 = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(gp.g[0]) + i);
+        float4 g = make_float4(g0[0], g0[1], g0[2], g0[3]);
         if (WEIGHTED) { g.x *= sh.share[0]; g.y *= sh.share[0]; g.z *= sh.share[0]; g.w *= sh.share[0]; }
         if (NP > 0) {
-            float4 t[NP > 1 ? NP - 1 : 1];
+            f32x4 t[NP > 1 ? NP - 1 : 1];
             #pragma unroll
-            for (int k = 1; k < NP; ++k) t[k - 1] = reinterpret_cast<const float4*>(gp.g[k])[i];
+            for (int k = 1; k < NP; ++k) t[k - 1] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(gp.g[k]) + i);
             #pragma unroll
             for (int k = 1; k < NP; ++k) {
                 const float c = WEIGHTED ? sh.share[k] : 1.0f;
-                g.x += c * t[k - 1].x; g.y += c * t[k - 1].y; g.z += c * t[k - 1].z; g.w += c * t[k - 1].w;
+                g.x += c * t[k - 1][0]; g.y += c * t[k - 1][1]; g.z += c * t[k - 1][2]; g.w += c * t[k - 1][3];
             }
         } else {
             for (int k = 1; k < np; ++k) {
-                const float4 t = reinterpret_cast<const float4*>(gp.g[k])[i];
+                const f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(gp.g[k]) + i);
                 const float c = WEIGHTED ? sh.share[k] : 1.0f;
-                g.x += c * t.x; g.y += c * t.y; g.z += c * t.z; g.w += c * t.w;
+                g.x += c * t[0]; g.y += c * t[1]; g.z += c * t[2]; g.w += c * t[3];
             }
         }
         if (!WEIGHTED) { g.x *= inv_p; g.y *= inv_p; g.z *= inv_p; g.w *= inv_p; }
@@ -321,7 +331,10 @@ __global__ __launch_bounds__(256) void adam_update_kernel(GradPtrs gp, ShardShar
         reinterpret_cast<float4*>(m)[i] = mi;
         reinterpret_cast<float4*>(s)[i] = si;
         reinterpret_cast<float4*>(w)[i] = wi;
-        if (SHADOW) reinterpret_cast<uint2*>(w16)[i] = make_uint2(pack2_bf16(wi.x, wi.y), pack2_bf16(wi.z, wi.w));
+        if (SHADOW) {
+            const u32x2 packed = {pack2_bf16(wi.x, wi.y), pack2_bf16(wi.z, wi.w)};
+            __builtin_nontemporal_store(packed, reinterpret_cast<u32x2*>(w16) + i);
+        }
     }
     // ragged tail (P not a multiple of 4): the first few lanes of block 0
     if (blockIdx.x == 0 && threadIdx.x < (unsigned)(P - nvec * 4)) {

@@ -34,8 +34,8 @@ struct Tune {
     int64_t early_update = 16000000;  // layers of at least this many weights start their update during the backward pass (0: none)
     int64_t early_blocks = 256;       // workgroups of such a background update
     int64_t upd_vpt = 1;              // 16-byte vectors per lane of the update kernel (1 or 2)
-    int64_t upd_wide = -1;            // > 0: the update walks its streams in wave-wide pieces, this many vectors per lane (1, 2, 4); -1: chosen by p; 0: one vector per lane, plain loads
-    int64_t upd_nt = -1;              // ... non-temporal accesses: bit 0 gradient loads, bit 1 bf16 store, bit 2 w and v; -1: chosen by p
+    int64_t upd_wide = -1;            // > 0: the update walks its streams in wave-wide pieces, this many vectors per lane (1, 2, 4); -1: chosen by the launcher (array placement, p); 0: one vector per lane, plain loads
+    int64_t upd_nt = -1;              // ... non-temporal accesses: bit 0 gradient loads, bit 1 bf16 store, bit 2 w and v; -1: chosen by the launcher
     int64_t upd_blocks = 0;           // ... > 0: grid-stride launch of this many workgroups
     int64_t branch_stream = 1;        // a residual block's projection shortcut runs on the second side stream beside the main branch
     int64_t transpose_stream = 0;     // 1: the transposed weight copies are made on the weight-gradient stream during the forward pass (measured: no gain, 4.499 vs 4.509 ms)

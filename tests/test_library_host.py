@@ -74,8 +74,23 @@ def test_adam_configuration_sizes_and_checks(E):
     from paper_1909_11985_amd.binding import make_config
     a = E.edl_query(make_config("resnet20", N=64, B=32, p_max=2))
     b = E.edl_query(make_config("resnet20", N=64, B=32, p_max=2, optimizer="adam"))
-    assert a.second_off == -1 and b.second_off == b.momentum_off + (b.running_off - b.momentum_off) // 2
-    assert b.second_off % 256 == 0 and b.running_off - b.second_off >= 4 * b.P
+    assert a.second_off == -1 and b.second_off >= 0 and a.shadow_off == -1
+    for s in (a, b, E.edl_query(make_config("resnet20", dtype="bf16", N=64, B=32, p_max=2, optimizer="adam"))):
+        # the state arrays: disjoint, inside the arena, on 4 KB boundaries of alternating parity
+        arrays = [(s.params_off, 4 * s.P), (s.momentum_off, 4 * s.P)]
+        if s.second_off >= 0:
+            arrays.append((s.second_off, 4 * s.P))
+        if s.shadow_off >= 0:
+            arrays.append((s.shadow_off, 2 * s.P))
+        arrays += [(s.grads_off + 4 * s.grad_stride * k, 4 * s.P) for k in range(2)]
+        arrays.append((s.running_off, 4 * s.R))
+        spans = sorted(arrays)
+        assert all(lo % 256 == 0 for lo, _ in spans) and spans[-1][0] + spans[-1][1] <= s.arena_bytes
+        assert all(spans[i][0] + spans[i][1] <= spans[i + 1][0] for i in range(len(spans) - 1))
+        pages = [lo for lo, _ in arrays[:-1]]
+        assert all(lo % 4096 == 0 for lo in pages)
+        assert (s.params_off >> 12) % 2 != (s.momentum_off >> 12) % 2             # w and v never on the same parity
+        assert 4 * s.grad_stride % 8192 == 4096                                    # neighbouring gradient buffers neither
     assert b.snapshot_bytes == a.snapshot_bytes + 4 * a.P and b.arena_bytes >= a.arena_bytes + 4 * a.P
     for kw in [dict(momentum=1.0), dict(beta2=1.0), dict(beta2=-0.5), dict(eps=-1e-8), dict(optimizer=7)]:
         base = dict(model="mlp", N=64, B=32, p_max=2, optimizer="adam")
