@@ -154,6 +154,9 @@ def main():
     ap.add_argument("--p", type=int, default=0, help="override the parallelism (shards of the global batch)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-state-bench", action="store_true", help="skip the VGG-16-sized update / snapshot timing")
+    ap.add_argument("--no-in-step-update", action="store_true",
+                    help="time the update kernel back to back only, not inside VGG-16 training steps (the counter "
+                         "passes of the profiler use this: those steps add some 30,000 dispatches)")
     ap.add_argument("--elastic", action="store_true",
                     help="the elastic schedule instead: ResNet-50 bf16, global batch 256 as p = 1, 2, 4, 8, 4 shards, "
                          "--steps mini-batches per phase (10 if not given), a snapshot and a joiner's restore at every adjustment")
@@ -343,7 +346,16 @@ def main():
         # (one stream, so that an event pair brackets one kernel)
         vx, vy = synth_inputs.dataset(1, 64, 224, 224, 3, 1000)
         vdx, vdy = torch.from_numpy(vx).cuda(), torch.from_numpy(vy).cuda()
-        for opt, kernel, ps, extra in (("momentum", "average_update", (1, 2, 4, 8), 18), ("adam", "adam_update", (1, 8), 26)):
+        legs = (("momentum", "average_update", (1, 2, 4, 8), 18), ("adam", "adam_update", (1, 8), 26))
+        if args.no_in_step_update:
+            for opt, kernel, ps, extra in legs:
+                for pp in ps:
+                    gbs = alone[(opt, pp)]
+                    row = dict(p=pp, P=P, bytes_per_param=4 * pp + extra, us=round((4 * pp + extra) * P / gbs / 1e3, 1),
+                               gbs=round(gbs, 1), frac_of_hbm_peak=round(gbs / HBM_PEAK_GBS, 4), where="back to back, on its own")
+                    update.append(dict(optimizer="adam", **row) if opt == "adam" else row)
+            legs = ()
+        for opt, kernel, ps, extra in legs:
             vjob = E.Job(make_config("vgg16", dtype="bf16", N=64, B=32, p_max=8, max_shard=32, lr=0.001, optimizer=opt), 0,
                          side_streams=None)
             vjob.bind_dataset(vdx, vdy)
