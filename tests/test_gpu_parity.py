@@ -180,6 +180,12 @@ def _assert_layerwise(r, dtype):
     assert ok, text
 
 
+def test_smoke_entry_point_runs():
+    """The driver's smoke() call: one small invocation of the path checked against the oracle."""
+    import __graft_entry__
+    __graft_entry__.smoke()
+
+
 @pytest.mark.parametrize("model", list(TINY))
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_layerwise_tiny_nets(model, dtype):
