@@ -371,7 +371,10 @@ int32_t edl_shutdown(edl_handle* h);
  * model): dev_grads is a HOST array of p device pointers to float32[P];
  * dev_w, dev_v float32[P]; dev_w16 (may be NULL) receives the bf16 copy of the
  * updated weights, rounded to nearest even.  P need not be a multiple of
- * anything; pointers must be 16-byte aligned. */
+ * anything; pointers must be 16-byte aligned.  Any placement gives the same
+ * bits; the kernel is fastest when the arrays start on 4 KB boundaries and
+ * consecutive ones (dev_w / dev_v above all) differ in address bit 12, which
+ * is how edl_query lays the same arrays out in a job's arena. */
 int32_t edl_average_update(int32_t p, const float* const* dev_grads, float* dev_w, float* dev_v,
                            uint16_t* dev_w16, int64_t P, float lr, float momentum, float wd,
                            void* hip_stream);
