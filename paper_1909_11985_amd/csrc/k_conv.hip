@@ -1259,6 +1259,12 @@ enum TileCfg { T128x128, T128x64, T128x32, T64x64 };
 #ifndef EDL_PF_BIG_HALF
 #define EDL_PF_BIG_HALF EDL_PF_BIG
 #endif
+#ifndef EDL_PF_WG_BIG
+#define EDL_PF_WG_BIG EDL_PF_BIG
+#endif
+#ifndef EDL_PF_WG_DEEP
+#define EDL_PF_WG_DEEP 2
+#endif
 #ifndef EDL_PF_WG_SMALL
 #define EDL_PF_WG_SMALL 2
 #endif
@@ -1319,9 +1325,16 @@ static void launch_cfg(TileCfg t, bool fast, dim3 tiles, const ConvArgs& a_in, h
     // two register sets of loads in flight; the 128-wide tiles gain nothing from a second set but do from
     // half-length reduction steps (half the LDS per workgroup, so more workgroups per CU).
     constexpr int PF_BIG = EDL_PF_BIG, PF_SMALL = MODE == CONV_WGRAD ? EDL_PF_WG_SMALL : EDL_PF_SMALL;
-    constexpr int PF_HALF = MODE == CONV_WGRAD ? EDL_PF_BIG : EDL_PF_BIG_HALF;   // 128-wide tiles on half-length steps
+    constexpr int PF_HALF = MODE == CONV_WGRAD ? EDL_PF_WG_BIG : EDL_PF_BIG_HALF;   // 128-wide tiles on half-length steps
     constexpr int BK_SMALL = MODE == CONV_WGRAD ? BK : EDL_BK_SMALL_MULT * BK / EDL_BK_SMALL_DIV;
     constexpr int BK_BIG = MODE == CONV_WGRAD ? BK : BK / EDL_BK_BIG_DIV;
+    // A weight gradient of at most one workgroup per CU has nobody to take turns with: one more tile in flight
+    // hides the operand latency its single wave per SIMD leaves exposed (bf16; ResNet-50 at a shard of 32: 128x128 tiles
+    // 22.2 -> 20.1 us, 128x64 24.4 -> 18.4 us).  Launches of more workgroups than CUs (VGG-16's long reductions, cut
+    // into two workgroups per CU) keep the two-stage form: with a third stage only one workgroup fits a CU's LDS
+    // (73.7 -> 113 us).
+    constexpr int PF_DEEP = MODE == CONV_WGRAD ? EDL_PF_WG_DEEP : PF_BIG;
+    const bool deep = MODE == CONV_WGRAD && total <= (double)tune().wgrad_deep_max;
     if (!fast) {   // element-wise kernel: one tile shape only
         hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 1, 1, BK, false, 1>), grid, dim3(256), 0, st, a);
         return;
@@ -1332,13 +1345,27 @@ static void launch_cfg(TileCfg t, bool fast, dim3 tiles, const ConvArgs& a_in, h
             // steps (half the barriers per MFMA: measured 159 -> 135 us forward, 174 -> 154 us dgrad on VGG-16);
             // short ones (ResNet-50's 1x1 layers) want the smaller LDS footprint and more workgroups per CU.
             const int full_steps_from = (int)tune().bk64_kred;
+            if constexpr (MODE == CONV_WGRAD && sizeof(T) == 2) {
+                if (deep) {
+                    hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 2, 2, BK, true, PF_DEEP>), grid, dim3(256), 0, st, a);
+                    break;
+                }
+            }
             if (BK_BIG != BK && a.Kred >= full_steps_from)
                 hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 2, 2, BK, true, PF_BIG>), grid, dim3(256), 0, st, a);
             else
                 hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 2, 2, BK_BIG, true, PF_HALF>), grid, dim3(256), 0, st, a);
             break;
         }
-        case T128x64: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 2, 1, BK_BIG, true, PF_HALF>), grid, dim3(256), 0, st, a); break;
+        case T128x64:
+            if constexpr (MODE == CONV_WGRAD && sizeof(T) == 2) {
+                if (deep) {
+                    hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 2, 1, BK, true, PF_DEEP>), grid, dim3(256), 0, st, a);
+                    break;
+                }
+            }
+            hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 2, 1, BK_BIG, true, PF_HALF>), grid, dim3(256), 0, st, a);
+            break;
         case T128x32: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 4, 1, 1, 1, BK, true, PF_BIG>), grid, dim3(256), 0, st, a); break;
         default: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 1, 1, BK_SMALL, true, PF_SMALL>), grid, dim3(256), 0, st, a); break;
     }

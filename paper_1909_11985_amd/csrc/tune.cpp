@@ -34,6 +34,7 @@ const Entry kEntries[] = {
     {"wgrad_blocks", &Tune::wgrad_blocks},
     {"wgrad_long_blocks", &Tune::wgrad_long_blocks},
     {"wgrad_long_ks", &Tune::wgrad_long_ks},
+    {"wgrad_deep_max", &Tune::wgrad_deep_max},
     {"wgrad_stream", &Tune::wgrad_stream},
     {"wgrad_tail_main", &Tune::wgrad_tail_main},
     {"early_update", &Tune::early_update},

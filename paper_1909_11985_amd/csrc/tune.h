@@ -29,6 +29,7 @@ struct Tune {
     int64_t wgrad_blocks = 128;       // workgroups a weight gradient is cut towards
     int64_t wgrad_long_blocks = 512;  // ... for long reductions
     int64_t wgrad_long_ks = 3072;     // least reduction elements per cut of a long reduction
+    int64_t wgrad_deep_max = 256;     // weight gradients of at most this many workgroups keep one more tile in flight (0: none do)
     int64_t wgrad_stream = 1;         // weight gradients on a second stream (read when a job is created)
     int64_t wgrad_tail_main = 1;      // the first this-many convolutions keep their weight gradient on the main stream
     int64_t early_update = 16000000;  // layers of at least this many weights start their update during the backward pass (0: none)

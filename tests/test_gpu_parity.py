@@ -834,6 +834,7 @@ def test_the_second_stream_does_not_change_the_result():
     assert _digest_after_steps({"branch_stream": 0, "wgrad_stream": 0}) == base
     assert _digest_after_steps({"transpose_stream": 1}) == base           # weight transposes on the weight-gradient stream
     assert _digest_after_steps({"alias_shortcut": 0}) == base             # identity shortcuts' gradients copied
+    assert _digest_after_steps({"wgrad_deep_max": 0}) == base             # weight gradients without the extra tile in flight
     # batch-norm passes with non-temporal loads on every tensor (by default only from 8 MB on: none at this size)
     assert _digest_after_steps({"bn_nt_bytes": 0}) == base
     assert _digest_after_steps({}, side_streams="torch") == base          # the caller's streams
