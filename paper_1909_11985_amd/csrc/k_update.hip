@@ -219,7 +219,10 @@ void launch_average_update(int p, const GradPtrs& grads, float* w, float* v, uin
     // bf16 store (w, v non-temporal as well: 6.2 / 6.2 / 6.1 / 5.9; four vectors per lane: 5.7).  Launched back to
     // back on its own, the same kernel reads 6.0 / 5.9 / 5.9 / 5.8 (on arrays that all start on 8 KB boundaries
     // 5.8 / 5.5 / 5.6 / 5.6): the previous launch's stores are still being written back.
-    const bool alternating = (((uintptr_t)w | (uintptr_t)v) & 4095) == 0 && ((((uintptr_t)w ^ (uintptr_t)v) >> 12) & 1) != 0;
+    // (a piece of the arrays that starts at the same offset of both keeps that relation: same position inside the
+    // page, pages of opposite parity)
+    const uintptr_t wv = (uintptr_t)w ^ (uintptr_t)v;
+    const bool alternating = (wv & 4095) == 0 && ((wv >> 12) & 1) != 0;
     int wide = (int)tune().upd_wide, nt = (int)tune().upd_nt;
     if (wide < 0) wide = alternating ? 1 : p >= 8 ? 4 : 1;
     if (nt < 0) nt = alternating ? 3 : p >= 8 ? 7 : 3;
