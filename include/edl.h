@@ -210,6 +210,7 @@ int32_t edl_set_side_streams(edl_handle* h, void* wgrad_stream, void* update_str
  * early_update (least weights of a layer whose update starts during the backward pass; 0 = never),
  * early_blocks, join_tile, fused_stats, held_stats, fused_mask, fused_mask_cut, fused_mask_join,
  * min128, min128_long, bk64_kred, xcd, order, splitk_tiles, splitk_target, wgrad_blocks, wgrad_long_blocks,
+ * small_tail_from, small_tail_to (64x64 launches of that many workgroups run with two LDS stages, all resident at once),
  * wgrad_long_ks, wgrad_deep_max (weight gradients of at most this many workgroups keep a third tile in flight), upd_vpt, upd_wide, upd_nt, upd_blocks (shape and cache hints of the update kernel's memory
  * walk), branch_stream (projection shortcuts on the second side stream), transpose_stream, alias_shortcut
  * (a shortcut's gradient read from the block output's gradient instead of copied), bn_nt, bn_nt_bytes

@@ -1259,6 +1259,9 @@ enum TileCfg { T128x128, T128x64, T128x32, T64x64 };
 #ifndef EDL_PF_BIG_HALF
 #define EDL_PF_BIG_HALF EDL_PF_BIG
 #endif
+#ifndef EDL_PF_SMALL_TAIL
+#define EDL_PF_SMALL_TAIL 1
+#endif
 #ifndef EDL_PF_WG_BIG
 #define EDL_PF_WG_BIG EDL_PF_BIG
 #endif
@@ -1367,7 +1370,21 @@ static void launch_cfg(TileCfg t, bool fast, dim3 tiles, const ConvArgs& a_in, h
             hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 2, 1, BK_BIG, true, PF_HALF>), grid, dim3(256), 0, st, a);
             break;
         case T128x32: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 4, 1, 1, 1, BK, true, PF_BIG>), grid, dim3(256), 0, st, a); break;
-        default: hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 1, 1, BK_SMALL, true, PF_SMALL>), grid, dim3(256), 0, st, a); break;
+        default:
+            if constexpr (MODE != CONV_WGRAD && sizeof(T) == 2) {
+                // Three stages of a 64x64 tile are 48 KB of LDS: three workgroups per CU, 768 on the chip.  A launch
+                // of a few more (784 and 800 are common: 25,088 pixels x 128 channels, 1,568 x 2,048) ran a second
+                // round for its last 16 or 32 workgroups and took almost twice one round.  Such launches run the
+                // two-stage form (32 KB, five per CU), so that all of their workgroups are resident at once:
+                // 22.1 -> 18.2 us and 25.9 -> 22.2 us for the 3x3 layers at 28x28, 0.490 -> 0.422 ms per ResNet-50
+                // step over all launches of that size.
+                if (total > (double)tune().small_tail_from && total <= (double)tune().small_tail_to) {
+                    hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 1, 1, BK_SMALL, true, EDL_PF_SMALL_TAIL>), grid, dim3(256), 0, st, a);
+                    break;
+                }
+            }
+            hipLaunchKernelGGL((conv_igemm_kernel<T, MODE, 2, 2, 1, 1, BK_SMALL, true, PF_SMALL>), grid, dim3(256), 0, st, a);
+            break;
     }
 }
 

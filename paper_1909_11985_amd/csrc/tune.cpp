@@ -31,6 +31,8 @@ const Entry kEntries[] = {
     {"fused_mask_cut", &Tune::fused_mask_cut},
     {"fused_mask_join", &Tune::fused_mask_join},
     {"join_tile", &Tune::join_tile},
+    {"small_tail_from", &Tune::small_tail_from},
+    {"small_tail_to", &Tune::small_tail_to},
     {"wgrad_blocks", &Tune::wgrad_blocks},
     {"wgrad_long_blocks", &Tune::wgrad_long_blocks},
     {"wgrad_long_ks", &Tune::wgrad_long_ks},

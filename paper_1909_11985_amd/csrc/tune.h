@@ -26,6 +26,8 @@ struct Tune {
     int64_t fused_mask_cut = 1;       // ... out of the finishing kernel where the dgrad's reduction is cut
     int64_t fused_mask_join = 1;      // ... at a residual join (the epilogue adds to the shortcut's part first)
     int64_t join_tile = 1;            // 128x64 tiles for the join epilogue
+    int64_t small_tail_from = 768;    // 64x64 forward / dgrad launches of more workgroups than this (three per CU) ...
+    int64_t small_tail_to = 1280;     // ... and at most this many (five per CU) run the two-stage form, all workgroups resident at once
     int64_t wgrad_blocks = 128;       // workgroups a weight gradient is cut towards
     int64_t wgrad_long_blocks = 512;  // ... for long reductions
     int64_t wgrad_long_ks = 3072;     // least reduction elements per cut of a long reduction

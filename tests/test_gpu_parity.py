@@ -835,6 +835,9 @@ def test_the_second_stream_does_not_change_the_result():
     assert _digest_after_steps({"transpose_stream": 1}) == base           # weight transposes on the weight-gradient stream
     assert _digest_after_steps({"alias_shortcut": 0}) == base             # identity shortcuts' gradients copied
     assert _digest_after_steps({"wgrad_deep_max": 0}) == base             # weight gradients without the extra tile in flight
+    # 64x64 launches of every size on the two-stage form, and none of them
+    assert _digest_after_steps({"small_tail_from": 0, "small_tail_to": 1 << 30}) == base
+    assert _digest_after_steps({"small_tail_to": 0}) == base
     # batch-norm passes with non-temporal loads on every tensor (by default only from 8 MB on: none at this size)
     assert _digest_after_steps({"bn_nt_bytes": 0}) == base
     assert _digest_after_steps({}, side_streams="torch") == base          # the caller's streams
